@@ -1,0 +1,166 @@
+"""ctypes front end of the C oracle (oracle/bsp_oracle.c).  Test infrastructure only.
+
+Every function takes and returns numpy arrays on the host.  Low-precision tensors travel as
+float32 arrays whose values are exactly representable in the low-precision type; dtype codes
+F32 / BF16 / F16 say what a result is rounded to.  Citations of the paper are in the C file.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+F32, BF16, F16 = 0, 1, 2
+ALPHA_SQNORM, ALPHA_NORM = 0, 1
+SCOPE_BLOCK, SCOPE_MATRIX = 0, 1
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build.build(force=False)
+        _lib = C.CDLL(path)
+        _lib.orc_round.restype = C.c_double
+        _lib.orc_round.argtypes = [C.c_double, C.c_int]
+        _lib.orc_compression_rate.restype = C.c_double
+        _lib.orc_compression_rate.argtypes = [C.c_int64, C.c_int64, C.c_int32, C.c_int64]
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _f32(a):
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    return a
+
+
+def round_to(v, dtype):
+    """Round python floats / arrays (as doubles) to dtype, RNE; returns float64 array."""
+    v = np.asarray(v, dtype=np.float64)
+    out = np.empty_like(v)
+    L = lib()
+    flat_in, flat_out = v.ravel(), out.ravel()
+    for i in range(flat_in.size):
+        flat_out[i] = L.orc_round(float(flat_in[i]), dtype)
+    return out
+
+
+def sumsq(W, R):
+    W = _f32(W)
+    M, N = W.shape
+    assert M % R == 0
+    s = np.empty((M // R, N), dtype=np.float32)
+    lib().orc_sumsq(_p(W), C.c_int64(M), C.c_int64(N), C.c_int32(R), _p(s))
+    return s
+
+
+def sumsq_exact(W, R):
+    W = _f32(W)
+    M, N = W.shape
+    assert M % R == 0
+    s = np.empty((M // R, N), dtype=np.float64)
+    lib().orc_sumsq_exact(_p(W), C.c_int64(M), C.c_int64(N), C.c_int32(R), _p(s))
+    return s
+
+
+def norm_alpha(s, eps, mode):
+    s = _f32(s)
+    norm = np.empty_like(s)
+    alpha = np.empty_like(s)
+    lib().orc_norm_alpha(_p(s), C.c_int64(s.size), C.c_float(eps), C.c_int32(mode), _p(norm), _p(alpha))
+    return norm, alpha
+
+
+def penalty_grad(W, R, alpha, lam, mode, gdt=F32, G0=None):
+    """Returns (G, penalty).  G0 given => accumulate into a copy of it."""
+    W = _f32(W)
+    M, N = W.shape
+    alpha = _f32(alpha)
+    assert alpha.shape == (M // R, N)
+    G = np.zeros_like(W) if G0 is None else _f32(G0).copy()
+    pen = C.c_double(0.0)
+    lib().orc_penalty_grad(_p(W), C.c_int64(M), C.c_int64(N), C.c_int32(R), _p(alpha), C.c_float(lam),
+                           C.c_int32(mode), C.c_int32(0 if G0 is None else 1), C.c_int32(gdt), _p(G),
+                           C.byref(pen))
+    return G, pen.value
+
+
+def mask_threshold(s, t):
+    s = _f32(s)
+    keep = np.empty(s.shape, dtype=np.uint8)
+    lib().orc_mask_threshold(_p(s), C.c_int64(s.size), C.c_float(t), _p(keep))
+    return keep
+
+
+def mask_rank(s, n_keep, scope):
+    s = _f32(s)
+    B, N = s.shape
+    keep = np.empty((B, N), dtype=np.uint8)
+    t_used = np.empty(B if scope == SCOPE_BLOCK else 1, dtype=np.float32)
+    lib().orc_mask_rank(_p(s), C.c_int64(B), C.c_int64(N), C.c_int64(n_keep), C.c_int32(scope), _p(keep),
+                        _p(t_used))
+    return keep, t_used
+
+
+def pack_count(keep, k_align):
+    keep = np.ascontiguousarray(keep, dtype=np.uint8)
+    B, N = keep.shape
+    cnt = np.empty(B, dtype=np.int32)
+    ptr = np.empty(B + 1, dtype=np.int32)
+    lib().orc_pack_count(_p(keep), C.c_int64(B), C.c_int64(N), C.c_int32(k_align), _p(cnt), _p(ptr))
+    return cnt, ptr
+
+
+def pack(W, R, keep, k_align, vdt=F32):
+    """Returns dict(blk_cnt, blk_ptr, col_idx, vals) in the canonical compact layout."""
+    W = _f32(W)
+    M, N = W.shape
+    keep = np.ascontiguousarray(keep, dtype=np.uint8)
+    assert keep.shape == (M // R, N)
+    cnt, ptr = pack_count(keep, k_align)
+    total = int(ptr[-1])
+    col_idx = np.empty(total, dtype=np.int32)
+    vals = np.empty(R * total, dtype=np.float32)
+    lib().orc_pack(_p(W), C.c_int64(M), C.c_int64(N), C.c_int32(R), _p(keep), C.c_int32(k_align), _p(cnt),
+                   _p(ptr), C.c_int32(vdt), _p(col_idx), _p(vals))
+    return dict(blk_cnt=cnt, blk_ptr=ptr, col_idx=col_idx, vals=vals, R=R, M=M, N=N, k_align=k_align)
+
+
+def linear_dense(X, W, keep, bias, R, ydt=F32):
+    """Brute force: dense product with pruned entries zeroed.  Returns (Y rounded, Y double)."""
+    X, W = _f32(X), _f32(W)
+    T, N = X.shape
+    M = W.shape[0]
+    keep = np.ascontiguousarray(keep, dtype=np.uint8)
+    bias = None if bias is None else _f32(bias)
+    Y = np.empty((T, M), dtype=np.float32)
+    Yd = np.empty((T, M), dtype=np.float64)
+    lib().orc_linear_dense(_p(X), _p(W), _p(keep), _p(bias), C.c_int64(T), C.c_int64(M), C.c_int64(N),
+                           C.c_int32(R), C.c_int32(ydt), _p(Y), _p(Yd))
+    return Y, Yd
+
+
+def linear_packed(X, packed, bias, ydt=F32, t0=0, t1=None, n_threads=1):
+    """The layer through the compact storage, rows t0..t1-1 of X.  Returns (Y, Yd) of full
+    shape [T, M]; rows outside [t0, t1) are left as NaN."""
+    X = _f32(X)
+    T, N = X.shape
+    M, R = packed["M"], packed["R"]
+    assert N == packed["N"]
+    t1 = T if t1 is None else t1
+    bias = None if bias is None else _f32(bias)
+    Y = np.full((T, M), np.nan, dtype=np.float32)
+    Yd = np.full((T, M), np.nan, dtype=np.float64)
+    lib().orc_linear_packed(_p(X), C.c_int64(t0), C.c_int64(t1), C.c_int64(M), C.c_int64(N), C.c_int32(R),
+                            _p(packed["blk_cnt"]), _p(packed["blk_ptr"]), _p(packed["col_idx"]),
+                            _p(packed["vals"]), _p(bias), C.c_int32(ydt), _p(Y), _p(Yd), C.c_int32(n_threads))
+    return Y, Yd
+
+
+def compression_rate(M, N, R, kept_cols_total):
+    return lib().orc_compression_rate(M, N, R, kept_cols_total)

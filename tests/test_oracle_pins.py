@@ -1,0 +1,428 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix: closed forms,
+brute force on tiny inputs, textbook special cases, library routines and invariants.
+None of these tests touches the GPU library."""
+import itertools
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import bsp_workloads as wl
+from oracle import bsp_oracle as orc
+
+RNG = np.random.default_rng(1234)
+
+
+def rand(shape, std=1.0):
+    return (RNG.standard_normal(shape) * std).astype(np.float32)
+
+
+# --------------------------------------------------------------------------- rounding
+@pytest.mark.parametrize("code,tdt", [(orc.BF16, torch.bfloat16), (orc.F16, torch.float16)])
+def test_round_matches_library_conversion(code, tdt):
+    # float32 -> low precision through torch is a single RNE rounding of an exactly known value
+    x = np.concatenate([rand(4000), rand(2000, 1e-3), rand(2000, 300.0),
+                        np.array([0.0, -0.0, 1.0, 65504.0, 65520.0, 1e-8, 6e-8, 3e38], dtype=np.float32)])
+    want = torch.from_numpy(x).to(tdt).to(torch.float64).numpy()
+    got = orc.round_to(x.astype(np.float64), code)
+    assert np.array_equal(want, got)
+
+
+def test_round_ties_to_even():
+    # bf16 has 8 significand bits: spacing 2^-7 in [1,2)
+    assert orc.round_to(1.0 + 2.0 ** -8, orc.BF16) == 1.0              # tie -> even (down)
+    assert orc.round_to(1.0 + 3 * 2.0 ** -8, orc.BF16) == 1.0 + 2.0 ** -6  # tie -> even (up)
+    assert orc.round_to(1.0 + 2.0 ** -8 + 2.0 ** -40, orc.BF16) == 1.0 + 2.0 ** -7  # above tie
+    # fp16: 11 bits, spacing 2^-10 in [1,2)
+    assert orc.round_to(1.0 + 2.0 ** -11, orc.F16) == 1.0
+    assert orc.round_to(1.0 + 3 * 2.0 ** -11, orc.F16) == 1.0 + 2.0 ** -9
+    # a double that would round wrongly if it went through float first (double rounding)
+    v = 1.0 + 2.0 ** -8 + 2.0 ** -30
+    assert orc.round_to(v, orc.BF16) == 1.0 + 2.0 ** -7
+
+
+# --------------------------------------------------------------------------- sums of squares
+def test_sumsq_closed_forms():
+    for R in (1, 2, 3, 8, 16, 32, 64):
+        M, N = 4 * R, 7
+        assert np.array_equal(orc.sumsq(np.ones((M, N), np.float32), R), np.full((4, N), R, np.float32))
+    # one-hot: a single non-zero lands in exactly its own group, value w^2
+    W = np.zeros((12, 5), np.float32)
+    W[7, 3] = 1.5
+    s = orc.sumsq(W, 4)
+    want = np.zeros((3, 5), np.float32)
+    want[1, 3] = 2.25
+    assert np.array_equal(s, want)
+    # R = 1: norm is |w|
+    W = rand((6, 9))
+    assert np.array_equal(orc.sumsq(W, 1), W * W)
+
+
+def test_sumsq_power_of_two_scaling_is_exact():
+    W = rand((32, 11), 0.02)
+    assert np.array_equal(orc.sumsq(W * np.float32(8.0), 16), orc.sumsq(W, 16) * np.float32(64.0))
+
+
+def test_sumsq_group_geometry_and_error_bound():
+    # rows of a group are R consecutive rows of W at a fixed column; check against an independent
+    # float64 evaluation with numpy reshapes on a non-square matrix
+    M, N, R = 48, 20, 16
+    W = rand((M, N), 0.02)
+    want = (W.astype(np.float64).reshape(M // R, R, N) ** 2).sum(axis=1)
+    exact = orc.sumsq_exact(W, R)
+    assert np.allclose(exact, want, rtol=1e-14, atol=0)
+    s = orc.sumsq(W, R).astype(np.float64)
+    assert np.all(np.abs(s - exact) <= R * 2.0 ** -24 * exact)
+
+
+def test_sumsq_canonical_order_is_ascending_fma_chain():
+    # values chosen so that the fused chain, an unfused chain and a reversed chain all differ
+    col = np.array([1.0 + 2.0 ** -12, 2.0 ** -13, 3.0, 1.0 - 2.0 ** -13], np.float32)
+    W = col.reshape(4, 1)
+    acc = 0.0  # exact rational arithmetic of "round(w*w + acc)" with float32 rounding, rows ascending
+    from fractions import Fraction
+    acc = Fraction(0)
+    for w in col:
+        acc = Fraction(float(np.float32(float(Fraction(float(w)) ** 2 + acc))))
+    assert float(orc.sumsq(W, 4)[0, 0]) == float(acc)
+
+
+# --------------------------------------------------------------------------- norm, reweighting
+def test_norm_alpha_closed_forms():
+    eps = 1e-6
+    for R in (4, 16):
+        s = np.full((2, 3), R, np.float32)
+        norm, a_sq = orc.norm_alpha(s, eps, orc.ALPHA_SQNORM)
+        _, a_n = orc.norm_alpha(s, eps, orc.ALPHA_NORM)
+        assert np.allclose(norm, math.sqrt(R), rtol=1e-7)
+        assert np.allclose(a_sq, 1.0 / (R + eps), rtol=1e-6)
+        assert np.allclose(a_n, 1.0 / (math.sqrt(R) + eps), rtol=1e-6)   # Sec. 3.2, gamma update rule
+    z = np.zeros((1, 1), np.float32)
+    assert orc.norm_alpha(z, eps, orc.ALPHA_SQNORM)[1][0, 0] == np.float32(1.0) / np.float32(eps)
+    assert orc.norm_alpha(z, eps, orc.ALPHA_NORM)[1][0, 0] == np.float32(1.0) / np.float32(eps)
+
+
+def test_norm_alpha_against_float64():
+    s = np.abs(rand((5, 40), 0.01)) + np.float32(1e-4)
+    eps = 1e-6
+    norm, a_sq = orc.norm_alpha(s, eps, orc.ALPHA_SQNORM)
+    _, a_n = orc.norm_alpha(s, eps, orc.ALPHA_NORM)
+    s64 = s.astype(np.float64)
+    assert np.allclose(norm, np.sqrt(s64), rtol=2e-7)
+    assert np.allclose(a_sq, 1 / (s64 + eps), rtol=3e-7)
+    assert np.allclose(a_n, 1 / (np.sqrt(s64) + eps), rtol=3e-7)
+
+
+# --------------------------------------------------------------------------- penalty, gradient
+@pytest.mark.parametrize("mode", [orc.ALPHA_SQNORM, orc.ALPHA_NORM])
+def test_penalty_gradient_is_derivative_of_penalty(mode):
+    M, N, R, lam = 8, 5, 4, 0.37
+    W = rand((M, N), 0.5)
+    s = orc.sumsq(W, R)
+    _, alpha = orc.norm_alpha(s, 1e-6, mode)
+    G, pen = orc.penalty_grad(W, R, alpha, lam, mode)
+    # central differences of the penalty value (alpha held fixed) at a few coordinates
+    for (m, j) in [(0, 0), (3, 4), (5, 2), (7, 1)]:
+        h = 1e-3
+        Wp, Wm = W.copy(), W.copy()
+        Wp[m, j] += h
+        Wm[m, j] -= h
+        pp = orc.penalty_grad(Wp, R, alpha, lam, mode)[1]
+        pm = orc.penalty_grad(Wm, R, alpha, lam, mode)[1]
+        fd = (pp - pm) / (float(Wp[m, j]) - float(Wm[m, j]))
+        assert abs(fd - G[m, j]) <= 2e-4 * abs(fd) + 1e-7, (m, j, fd, G[m, j])
+
+
+def test_penalty_value_closed_form_is_eq3():
+    # all-ones weights: every group has norm sqrt(R); Eq. 3's term is lambda * sum_g gamma_g ||W_g||
+    M, N, R, lam, eps = 8, 6, 4, 0.25, 1e-6
+    W = np.ones((M, N), np.float32)
+    _, gamma = orc.norm_alpha(orc.sumsq(W, R), eps, orc.ALPHA_NORM)
+    G, pen = orc.penalty_grad(W, R, gamma, lam, orc.ALPHA_NORM)
+    n_groups = (M // R) * N
+    assert pen == pytest.approx(lam * n_groups * (1 / (2 + eps)) * 2.0, rel=1e-6)
+    # gradient of gamma*||w|| wrt each of the R equal entries: gamma * w/||w|| = gamma / 2
+    assert np.allclose(G, lam * (1 / (2 + eps)) / 2.0, rtol=1e-6)
+    # squared form: alpha * w, penalty (lambda/2) * alpha * ||w||^2
+    _, alpha = orc.norm_alpha(orc.sumsq(W, R), eps, orc.ALPHA_SQNORM)
+    G, pen = orc.penalty_grad(W, R, alpha, lam, orc.ALPHA_SQNORM)
+    assert np.allclose(G, lam / (4 + eps), rtol=1e-6)
+    assert pen == pytest.approx(0.5 * lam * n_groups * 4 / (4 + eps), rel=1e-6)
+
+
+def test_penalty_grad_zero_group_and_accumulate():
+    W = rand((8, 4), 0.3)
+    W[0:4, 2] = 0.0
+    for mode in (orc.ALPHA_SQNORM, orc.ALPHA_NORM):
+        _, alpha = orc.norm_alpha(orc.sumsq(W, 4), 1e-6, mode)
+        G, _ = orc.penalty_grad(W, 4, alpha, 0.1, mode)
+        assert np.all(G[0:4, 2] == 0.0) and np.all(np.isfinite(G))
+        G0 = rand((8, 4))
+        G1, _ = orc.penalty_grad(W, 4, alpha, 0.1, mode, G0=G0)
+        assert np.allclose(G1, G0.astype(np.float64) + G, rtol=0, atol=5e-7)
+    # gradient rounded to bf16 is the fp32 gradient rounded once
+    _, alpha = orc.norm_alpha(orc.sumsq(W, 4), 1e-6, orc.ALPHA_SQNORM)
+    G32, _ = orc.penalty_grad(W, 4, alpha, 0.1, orc.ALPHA_SQNORM)
+    Gb, _ = orc.penalty_grad(W, 4, alpha, 0.1, orc.ALPHA_SQNORM, gdt=orc.BF16)
+    assert np.array_equal(Gb, torch.from_numpy(G32).bfloat16().float().numpy())
+
+
+# --------------------------------------------------------------------------- masks
+def test_threshold_tie_is_pruned():
+    # Alg. 1 zeroes a group whose norm is <= t_b
+    s = np.array([[0.25, 0.2500001, 0.2499999, 0.0]], np.float32)
+    keep = orc.mask_threshold(s, 0.5)
+    assert keep.tolist() == [[0, 1, 0, 0]]
+    assert orc.mask_threshold(s, -1.0).tolist() == [[1, 1, 1, 1]]
+    assert orc.mask_threshold(s, 0.0).tolist() == [[1, 1, 1, 0]]
+
+
+def test_threshold_compare_is_exact_in_the_squared_domain():
+    # t*t is not representable in fp32: a float-rounded t^2 would flip this decision
+    t = np.float32(0.1)
+    t2 = float(t) * float(t)
+    below = np.nextafter(np.float32(t2), np.float32(0))
+    above = np.nextafter(below, np.float32(1))
+    s = np.array([[below, above]], np.float32)
+    want = [[int(float(below) > t2), int(float(above) > t2)]]
+    assert orc.mask_threshold(s, float(t)).tolist() == want
+    assert want == [[0, 1]]
+
+
+def test_r1_is_elementwise_magnitude_pruning_and_b1_is_column_pruning():
+    W = rand((16, 12))
+    t = 0.7
+    keep = orc.mask_threshold(orc.sumsq(W, 1), t)
+    assert np.array_equal(keep, (np.abs(W.astype(np.float64)) > np.float32(t).astype(np.float64)).astype(np.uint8))
+    keep = orc.mask_threshold(orc.sumsq(W, 16), 4.0)
+    col_norm = np.linalg.norm(W.astype(np.float64), axis=0)
+    assert np.array_equal(keep[0], (col_norm > 4.0).astype(np.uint8))
+    assert 0 < keep.sum() < 12
+
+
+def test_threshold_monotone():
+    s = orc.sumsq(rand((32, 50), 0.02), 16)
+    prev = None
+    for t in (0.0, 0.05, 0.07, 0.08, 0.1, 1.0):
+        keep = orc.mask_threshold(s, t)
+        if prev is not None:
+            assert np.all(keep <= prev)
+        prev = keep
+    assert prev.sum() == 0
+
+
+@pytest.mark.parametrize("scope", [orc.SCOPE_BLOCK, orc.SCOPE_MATRIX])
+def test_rank_mask_vs_brute_force(scope):
+    B, N = 5, 9
+    s = np.abs(rand((B, N)))
+    s[1, 3] = s[1, 4]            # a tie inside one row
+    s[2, :] = 0.5                # a row of equal values
+    s[0, 0] = s[4, 8]            # a tie across rows
+    n_scope = N if scope == orc.SCOPE_BLOCK else B * N
+    for n_keep in [0, 1, 2, n_scope // 2, n_scope - 1, n_scope, n_scope + 3]:
+        keep, t_used = orc.mask_rank(s, n_keep, scope)
+        rows = [s[b] for b in range(B)] if scope == orc.SCOPE_BLOCK else [s.ravel()]
+        got = [keep[b] for b in range(B)] if scope == orc.SCOPE_BLOCK else [keep.ravel()]
+        for i, (v, k) in enumerate(zip(rows, got)):
+            P = len(v) - n_keep
+            if P <= 0:
+                assert k.all() and t_used[i] == -np.inf
+                continue
+            thr = sorted(v.tolist())[P - 1]          # P-th smallest, plain python
+            want = [int(x > thr) for x in v.tolist()]
+            assert k.tolist() == want
+            assert t_used[i] == np.float32(thr)
+            assert k.sum() <= n_keep
+            if k.any() and not k.all():
+                assert v[k == 1].min() > v[k == 0].max()
+
+
+def test_rank_mask_exact_count_when_distinct():
+    s = np.abs(rand((8, 64))) + np.float32(1e-3)
+    assert len(np.unique(s)) == s.size
+    for n_keep in (0, 1, 17, 200, 512):
+        assert orc.mask_rank(s, n_keep, orc.SCOPE_MATRIX)[0].sum() == n_keep
+    for n_keep in (0, 1, 21, 64):
+        keep, _ = orc.mask_rank(s, n_keep, orc.SCOPE_BLOCK)
+        assert np.all(keep.sum(axis=1) == n_keep)
+
+
+# --------------------------------------------------------------------------- packing
+def unpack(p, vdt_values=True):
+    """Independent inverse of the compact layout, written from its definition."""
+    M, N, R = p["M"], p["N"], p["R"]
+    Wd = np.zeros((M, N), np.float32)
+    for b in range(M // R):
+        base, kb = int(p["blk_ptr"][b]), int(p["blk_cnt"][b])
+        kp = int(p["blk_ptr"][b + 1]) - base
+        panel = p["vals"][R * base:R * (base + kp)].reshape(R, kp) if kp else np.zeros((R, 0), np.float32)
+        for c in range(kb):
+            Wd[b * R:(b + 1) * R, p["col_idx"][base + c]] = panel[:, c]
+    return Wd
+
+
+@pytest.mark.parametrize("k_align", [1, 16, 32])
+@pytest.mark.parametrize("R", [1, 3, 8, 16])
+def test_pack_round_trip_and_layout(R, k_align):
+    M, N = 6 * R, 75
+    W = rand((M, N), 0.02)
+    keep = wl.bernoulli_keep_mask(7 + R, M // R, N, 0.4)
+    keep[1, :] = 0                      # an empty block
+    keep[2, :] = 1                      # a full block
+    p = orc.pack(W, R, keep, k_align)
+    assert np.array_equal(unpack(p), W * np.repeat(keep, R, axis=0))
+    assert np.array_equal(p["blk_cnt"], keep.sum(axis=1))
+    kp = -(-p["blk_cnt"] // k_align) * k_align
+    assert p["blk_ptr"][0] == 0 and np.array_equal(np.diff(p["blk_ptr"]), kp)
+    assert p["col_idx"].size == p["blk_ptr"][-1] and p["vals"].size == R * p["blk_ptr"][-1]
+    for b in range(M // R):
+        base, kb = p["blk_ptr"][b], p["blk_cnt"][b]
+        idx = p["col_idx"][base:base + kp[b]]
+        assert np.array_equal(idx[:kb], np.flatnonzero(keep[b]))       # ascending kept columns
+        assert np.all(idx[kb:] == (idx[kb - 1] if kb else 0))          # pads repeat the last one
+        panel = p["vals"][R * base:R * (base + kp[b])].reshape(R, kp[b])
+        assert np.all(panel[:, kb:] == 0) and not np.signbit(panel[:, kb:]).any()
+
+
+def test_pack_rounds_values_to_bf16():
+    W = rand((16, 20), 0.02)
+    keep = wl.bernoulli_keep_mask(3, 1, 20, 0.5)
+    p32, pb = orc.pack(W, 16, keep, 1, orc.F32), orc.pack(W, 16, keep, 1, orc.BF16)
+    assert np.array_equal(pb["vals"], torch.from_numpy(p32["vals"]).bfloat16().float().numpy())
+    assert np.array_equal(pb["col_idx"], p32["col_idx"])
+
+
+def test_compression_rate_and_storage_accounting():
+    # Sec. 4.4: 1.428x <=> 30 % sparsity; 2.0x <=> 50 %; 5x <=> 80 %
+    assert orc.compression_rate(768, 768, 16, int(48 * 768 * 0.7)) == pytest.approx(1 / 0.7, rel=1e-3)
+    assert round(orc.compression_rate(100, 100, 10, 70 * 10), 3) == 1.429
+    assert orc.compression_rate(768, 768, 16, 48 * 384) == 2.0
+    assert orc.compression_rate(1000, 10, 10, 200) == 5.0
+    # Sec. 4.4 worked example: 8x8 matrix, 4 row-blocks... read as 4x4 blocks => groups of 4 weights,
+    # 16 groups, half kept: values 32 + one index/flag per group 16 = 48 words; COO 3 words per non-zero = 96
+    W = rand((8, 8)) + np.float32(3.0)
+    keep = wl.random_keep_mask(1, 2, 8, 4)
+    p = orc.pack(W, 4, keep, 1)
+    nnz = int(np.count_nonzero(unpack(p)))
+    assert nnz == 32 and p["vals"].size == 32
+    n_groups = keep.size
+    assert p["vals"].size + n_groups == 48
+    assert 3 * nnz == 96
+
+
+# --------------------------------------------------------------------------- the layer
+def brute_force_layer(X, W, keep, bias, R):
+    """Triple python loop in exact rational arithmetic, then to float."""
+    from fractions import Fraction
+    T, N = X.shape
+    M = W.shape[0]
+    Y = np.zeros((T, M), np.float64)
+    for t in range(T):
+        for m in range(M):
+            acc = Fraction(float(bias[m])) if bias is not None else Fraction(0)
+            for j in range(N):
+                if keep[m // R, j]:
+                    acc += Fraction(float(X[t, j])) * Fraction(float(W[m, j]))
+            Y[t, m] = float(acc)
+    return Y
+
+
+@pytest.mark.parametrize("R", [1, 2, 4, 8])
+def test_linear_vs_exact_brute_force(R):
+    T, M, N = 3, 8, 10
+    X, W, bias = rand((T, N)), rand((M, N), 0.02), rand((M,), 0.02)
+    keep = wl.bernoulli_keep_mask(R, M // R, N, 0.5)
+    want = brute_force_layer(X, W, keep, bias, R)
+    _, Yd = orc.linear_dense(X, W, keep, bias, R)
+    assert np.allclose(Yd, want, rtol=0, atol=1e-15)
+    p = orc.pack(W, R, keep, 1)
+    Yp, Ypd = orc.linear_packed(X, p, bias)
+    assert np.array_equal(Ypd, Yd)                       # bit for bit in double
+    assert np.array_equal(Yp, Yd.astype(np.float32))
+    # orientation: W is [out, in], Y = X W^T
+    assert Yd.shape == (T, M)
+
+
+@pytest.mark.parametrize("k_align", [1, 16, 32])
+def test_linear_dense_equals_packed_bitwise_with_padding(k_align):
+    T, M, N, R = 5, 32, 70, 16
+    X, W, bias = rand((T, N)), rand((M, N), 0.02), rand((M,), 0.02)
+    keep = wl.bernoulli_keep_mask(11, M // R, N, 0.3)
+    _, Yd = orc.linear_dense(X, W, keep, bias, R)
+    _, Ypd = orc.linear_packed(X, orc.pack(W, R, keep, k_align), bias)
+    assert np.array_equal(Yd, Ypd)
+
+
+def test_linear_keep_all_is_dense_gemm_and_keep_none_is_bias():
+    T, M, N, R = 7, 32, 24, 16
+    X, W, bias = rand((T, N)), rand((M, N), 0.02), rand((M,), 0.02)
+    ones, zeros = np.ones((M // R, N), np.uint8), np.zeros((M // R, N), np.uint8)
+    want = (torch.from_numpy(X).double() @ torch.from_numpy(W).double().T + torch.from_numpy(bias).double()).numpy()
+    for k_align in (1, 16):
+        Y, Yd = orc.linear_packed(X, orc.pack(W, R, ones, k_align), bias)
+        assert np.allclose(Yd, want, rtol=1e-13, atol=1e-15)
+        Y0, _ = orc.linear_packed(X, orc.pack(W, R, zeros, k_align), bias)
+        assert np.array_equal(Y0, np.broadcast_to(bias, (T, M)))
+    Y0, _ = orc.linear_packed(X, orc.pack(W, R, zeros, 1), None)
+    assert np.all(Y0 == 0)
+
+
+def test_linear_against_library_matmul_with_zeroed_weights():
+    T, M, N, R = 9, 48, 40, 8
+    X, W, bias = rand((T, N)), rand((M, N), 0.02), rand((M,), 0.02)
+    keep = wl.bernoulli_keep_mask(5, M // R, N, 0.35)
+    Wz = W.astype(np.float64) * np.repeat(keep, R, axis=0)
+    want = (torch.from_numpy(X).double() @ torch.from_numpy(Wz).T + torch.from_numpy(bias).double()).numpy()
+    _, Yd = orc.linear_packed(X, orc.pack(W, R, keep, 16), bias)
+    assert np.allclose(Yd, want, rtol=1e-12, atol=1e-15)
+
+
+def test_linear_additivity_permutation_and_block_locality():
+    T, M, N, R = 4, 24, 30, 8
+    X, W, bias = rand((T, N)), rand((M, N), 0.02), rand((M,), 0.02)
+    m1 = wl.bernoulli_keep_mask(1, M // R, N, 0.3)
+    m2 = wl.bernoulli_keep_mask(2, M // R, N, 0.3) & (1 - m1)
+    y = lambda m, XX=X, WW=W: orc.linear_packed(XX, orc.pack(WW, R, m, 1), bias)[1]
+    assert np.allclose(y(m1) + y(m2) - bias, y(m1 | m2), rtol=0, atol=1e-12)
+    perm = RNG.permutation(N)
+    assert np.allclose(y(m1[:, perm], X[:, perm], W[:, perm]), y(m1), rtol=0, atol=1e-13)
+    W2, mk2 = W.copy(), m1.copy()
+    W2[8:16] += 1.0
+    mk2[1] = 1 - mk2[1]
+    d = y(mk2, X, W2) != y(m1)
+    assert d[:, 8:16].any() and not d[:, :8].any() and not d[:, 16:].any()
+
+
+def test_linear_output_rounding_and_row_range():
+    T, M, N, R = 6, 16, 33, 16
+    X = wl.to_dtype_values(rand((T, N)), "bf16")
+    W = wl.to_dtype_values(rand((M, N), 0.02), "bf16")
+    bias = wl.to_dtype_values(rand((M,), 0.02), "bf16")
+    p = orc.pack(W, R, wl.bernoulli_keep_mask(9, 1, N, 0.5), 16, orc.BF16)
+    Y, Yd = orc.linear_packed(X, p, bias, ydt=orc.BF16)
+    assert np.array_equal(Y.astype(np.float64), orc.round_to(Yd, orc.BF16))
+    Ys, _ = orc.linear_packed(X, p, bias, ydt=orc.BF16, t0=2, t1=4)
+    assert np.array_equal(Ys[2:4], Y[2:4]) and np.isnan(Ys[:2]).all() and np.isnan(Ys[4:]).all()
+    Ymt, _ = orc.linear_packed(X, p, bias, ydt=orc.BF16, n_threads=4)
+    assert np.array_equal(Ymt, Y)
+
+
+# --------------------------------------------------------------------------- end to end
+def test_chain_on_base_attention_projection():
+    """norms -> percentile mask -> pack -> layer equals the dense layer with the mask's zeros."""
+    c = wl.config1(tokens=8)
+    X, W, bias, R = c["X"], c["W"], c["bias"], c["R"]
+    s = orc.sumsq(W, R)
+    keep, _ = orc.mask_rank(s, 384, orc.SCOPE_BLOCK)
+    assert np.all(keep.sum(axis=1) == 384)
+    p = orc.pack(W, R, keep, 32)
+    assert orc.compression_rate(768, 768, R, int(p["blk_cnt"].sum())) == 2.0
+    Y, Yd = orc.linear_packed(X, p, bias)
+    _, Yd_dense = orc.linear_dense(X, W, keep, bias, R)
+    assert np.array_equal(Yd, Yd_dense)
+    Wz = W.astype(np.float64) * np.repeat(keep, R, axis=0)
+    want = (torch.from_numpy(X).double() @ torch.from_numpy(Wz).T + torch.from_numpy(bias).double()).numpy()
+    assert np.allclose(Yd, want, rtol=1e-12, atol=1e-14)
+    # the given random mask of the workload keeps exactly half of every block
+    assert np.all(c["keep"].sum(axis=1) == 384)
