@@ -1,0 +1,214 @@
+"""Benchmark of the block-structured-pruning path on one MI355X.
+
+Workload: the BERT-large / RoBERTa-large linear set (QKV 3072x1024, attention out 1024x1024,
+FFN up 4096x1024, FFN down 1024x4096), bf16, 8192 tokens, row-blocks of R=16 rows, 5x
+compression chosen by a matrix-scope percentile of the group norms of N(0, 0.02) weights.
+
+One step = one pass of the whole path over the four matrices: group norms + reweighting
+factors, regulariser gradient, percentile mask, pack (count + pack), and the pruned layer.
+All inputs are resident in HBM before the timed region.  `value` is the useful FLOP rate of
+the layers (2 * T * R * kept columns, pads excluded) over the whole step time; `linear_only`
+gives the same rate over the layer kernels alone, timed with events on the launch stream.
+
+    python bench.py --gpus 1 --steps K --warmup W
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import bsp_workloads as wl  # noqa: E402
+import paper_2009_08065_amd as bsp  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
+
+
+class Matrix:
+    """Device-resident tensors and preallocated outputs of one layer of the set."""
+
+    def __init__(self, d, k_align=32):
+        self.name, self.M, self.N, self.R, self.T = d["name"], d["M"], d["N"], d["R"], d["T"]
+        self.n_keep, self.k_align = d["n_keep"], k_align
+        dev = "cuda"
+        self.W = torch.from_numpy(d["W"]).to(torch.bfloat16).to(dev)
+        self.X = torch.from_numpy(d["X"]).to(torch.bfloat16).to(dev)
+        self.bias = torch.from_numpy(d["bias"]).to(torch.bfloat16).to(dev)
+        B = self.M // self.R
+        self.B = B
+        f32 = dict(dtype=torch.float32, device=dev)
+        self.sumsq, self.alpha = torch.empty((B, self.N), **f32), torch.empty((B, self.N), **f32)
+        self.grad = torch.empty_like(self.W)
+        self.keep = torch.empty((B, self.N), dtype=torch.uint8, device=dev)
+        self.ws = torch.empty(bsp.lib().bsp_prune_mask_workspace_bytes(B, self.N, bsp.SCOPE_MATRIX),
+                              dtype=torch.uint8, device=dev)
+        self.blk_cnt = torch.empty(B, dtype=torch.int32, device=dev)
+        self.blk_ptr = torch.empty(B + 1, dtype=torch.int32, device=dev)
+        # at most n_keep groups survive a percentile, each block pads by < k_align columns
+        self.capacity = self.n_keep + B * (k_align - 1)
+        self.col_idx = torch.empty(self.capacity, dtype=torch.int32, device=dev)
+        self.vals = torch.empty(self.R * self.capacity, dtype=torch.bfloat16, device=dev)
+        self.Y = torch.empty((self.T, self.M), dtype=torch.bfloat16, device=dev)
+        self.packed = bsp.Packed(self.M, self.N, self.R, k_align, self.blk_cnt, self.blk_ptr, self.col_idx,
+                                 self.vals, self.capacity)
+        self.kept_cols = None
+
+    def prune_and_pack(self, lam=1e-4, eps=1e-6):
+        bsp.bsp_group_norms(self.W, self.R, eps=eps, mode=bsp.ALPHA_SQNORM, sumsq=self.sumsq, alpha=self.alpha,
+                            want=())
+        bsp.bsp_penalty_grad(self.W, self.R, self.alpha, lam, mode=bsp.ALPHA_SQNORM, grad=self.grad)
+        bsp.bsp_prune_mask(self.sumsq, n_keep=self.n_keep, scope=bsp.SCOPE_MATRIX, keep=self.keep, ws=self.ws)
+        bsp.bsp_pack_count(self.keep, self.k_align, blk_cnt=self.blk_cnt, blk_ptr=self.blk_ptr)
+        L = bsp.lib()
+        st = L.bsp_pack(self.W.data_ptr(), bsp.BF16, self.M, self.N, self.R, self.keep.data_ptr(), self.k_align,
+                        self.blk_cnt.data_ptr(), self.blk_ptr.data_ptr(), self.capacity, self.col_idx.data_ptr(),
+                        self.vals.data_ptr(), bsp.BF16, torch.cuda.current_stream().cuda_stream)
+        if st != 0:
+            raise bsp.BspError(st, "bsp_pack")
+
+    def linear(self):
+        bsp.bsp_linear(self.X, self.packed, self.bias, Y=self.Y)
+
+    # algorithmic work of one layer call
+    def useful_flops(self):
+        return 2.0 * self.T * self.R * self.kept_cols
+
+    def dense_flops(self):
+        return 2.0 * self.T * self.M * self.N
+
+    def linear_bytes(self):
+        padded = int(self.blk_ptr[-1].item())
+        return 2.0 * self.T * self.N + 2.0 * self.T * self.M + 2.0 * self.R * padded + 4.0 * padded + 2.0 * self.M
+
+
+def cpu_baseline(mats, target_seconds=12.0):
+    """The CPU oracle's layer on a bounded sample of the same workload (tokens 0..n-1 of the
+    FFN up-projection), on the host cores of this machine."""
+    from oracle import bsp_oracle as orc
+    m = next(x for x in mats if x.name == "ffn_up")
+    cores = min(len(os.sched_getaffinity(0)), 16)
+    W = m.W.float().cpu().numpy()
+    X = m.X.float().cpu().numpy()
+    bias = m.bias.float().cpu().numpy()
+    keep = m.keep.cpu().numpy()
+    p = orc.pack(W, m.R, keep, m.k_align, orc.BF16)
+    kept = int(p["blk_cnt"].sum())
+
+    def run(n_tok):
+        t = time.perf_counter()
+        orc.linear_packed(X, p, bias, ydt=orc.BF16, t0=0, t1=n_tok, n_threads=cores)
+        return time.perf_counter() - t
+
+    probe_tok = 32
+    dt = run(probe_tok)
+    n_tok = int(min(m.T, max(probe_tok, probe_tok * target_seconds / max(dt, 1e-6))))
+    dt = run(n_tok)
+    flops = 2.0 * n_tok * m.R * kept
+    return {"value": flops / dt / 1e12, "unit": "useful TFLOP/s", "cores": cores, "kind": "oracle",
+            "sample": f"oracle layer (fp64 accumulate) on tokens 0..{n_tok - 1} of ffn_up 4096x1024, 5x, R=16; {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--R", type=int, default=16)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the path has no multi-GPU part; run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+
+    mats = [Matrix(d) for d in wl.config4(R=args.R)]
+    for m in mats:   # once, to learn the kept counts (needed only for the FLOP accounting)
+        m.prune_and_pack()
+        m.linear()
+    torch.cuda.synchronize()
+    for m in mats:
+        m.kept_cols = int(m.blk_cnt.sum().item())
+
+    def step(events=None):
+        for i, m in enumerate(mats):
+            m.prune_and_pack()
+            if events is not None:
+                events[i][0].record()
+            m.linear()
+            if events is not None:
+                events[i][1].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [[[torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)] for _ in mats]
+           for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step(evs[s])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    ms_per_step = wall * 1e3 / args.steps
+    lin_ms = np.array([[e[0].elapsed_time(e[1]) for e in ev] for ev in evs])       # [steps, matrices]
+    lin_avg = lin_ms.mean(axis=0)
+    useful = sum(m.useful_flops() for m in mats)
+    dense = sum(m.dense_flops() for m in mats)
+    lin_bytes = [m.linear_bytes() for m in mats]
+    lin_total_ms = float(lin_avg.sum())
+
+    per_matrix = {}
+    for m, ms, by in zip(mats, lin_avg, lin_bytes):
+        per_matrix[m.name] = {
+            "shape": [m.M, m.N], "kept_cols": m.kept_cols,
+            "rate": round(bsp.bsp_compression_rate(m.M, m.N, m.R, m.kept_cols), 4),
+            "us": round(float(ms) * 1e3, 2),
+            "useful_tflops": round(m.useful_flops() / (ms * 1e-3) / 1e12, 2),
+            "dense_equiv_tflops": round(m.dense_flops() / (ms * 1e-3) / 1e12, 2),
+            "hbm_gbs": round(by / (ms * 1e-3) / 1e9, 1),
+            "frac_mfma_peak": round(m.useful_flops() / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+            "frac_hbm_peak": round(by / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        }
+
+    achieved_gbs = sum(lin_bytes) / (lin_total_ms * 1e-3) / 1e9
+    achieved_tflops = useful / (lin_total_ms * 1e-3) / 1e12
+    out = {
+        "metric": "block-sparse linear useful TFLOP/s at BERT-large",
+        "value": round(useful / (ms_per_step * 1e-3) / 1e12, 3),
+        "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "BERT-large linear set (configs[3]): QKV 3072x1024, out 1024x1024, up 4096x1024, "
+                               "down 1024x4096; 8192 tokens; 5x compression; matrix-scope percentile mask",
+                   "block_rows": args.R, "k_align": 32, "tokens": 8192,
+                   "step": "group_norms + penalty_grad + prune_mask + pack_count + pack + linear, 4 matrices"},
+        "linear_only": {"ms": round(lin_total_ms, 4), "useful_tflops": round(achieved_tflops, 2),
+                        "dense_equiv_tflops": round(dense / (lin_total_ms * 1e-3) / 1e12, 2),
+                        "frac_mfma_peak": round(achieved_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
+                        "per_matrix": per_matrix},
+        "roofline": {"kernel": "bsp_linear (4 launches per step, one per matrix)", "bound": "hbm",
+                     "achieved": round(achieved_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved_gbs / HBM_PEAK_GBS, 4), "traffic": None},
+        "roofline_mfma": {"bound": "mfma", "achieved": round(achieved_tflops, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
+                          "unit": "TFLOP/s", "frac": round(achieved_tflops / MFMA_BF16_PEAK_TFLOPS, 4)},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(mats)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,142 @@
+/*
+ * bsp.h -- C ABI of the block-structured-pruning library for AMD CDNA4 (gfx950).
+ *
+ * The operations are those of "Efficient Transformer-based Large Scale Language
+ * Representations using Hardware-friendly Block Structured Pruning" (arXiv 2009.08065):
+ * group l2 norms and reweighting factors (Sec. 3.2, Eq. 3), the prune decision of
+ * Alg. 1 by threshold or percentile (Sec. 3.1), the compact storage in which only the
+ * kept columns of a block are indexed (Sec. 3.1), and the pruned linear layer the
+ * storage exists for (Sec. 3.1, Sec. 4.4).
+ *
+ * Conventions
+ *   W      weight, row-major [M, N] = [out_features, in_features];  Y = X W^T + bias.
+ *   R      rows per row-block ("block column size" d_n of Eq. 3);  B = M / R row-blocks.
+ *   group  g = (b, j): the R weights W[bR .. bR+R-1, j].
+ *   Every data pointer is a DEVICE pointer owned by the caller unless marked "host".
+ *   The library allocates nothing and keeps no state between calls; scratch memory is
+ *   passed in by the caller (see the *_workspace_bytes queries).
+ *   Every call validates its arguments on the host, then enqueues its kernels on
+ *   `stream` (a hipStream_t passed as void*; NULL = the default stream) and returns
+ *   without waiting.  Return value: a bsp_status; nothing is launched unless it is BSP_OK.
+ *   Inputs are assumed finite.
+ */
+#ifndef BSP_H
+#define BSP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    BSP_OK = 0,
+    BSP_ERR_NULL = 1,     /* a required pointer is NULL */
+    BSP_ERR_SHAPE = 2,    /* a dimension is <= 0, M % R != 0, R outside [1, 64], sizes overflow int32 where one is used */
+    BSP_ERR_DTYPE = 3,    /* dtype / enum value not supported by this call */
+    BSP_ERR_CAPACITY = 4, /* an output or workspace buffer is too small */
+    BSP_ERR_FORMAT = 5,   /* compact storage is malformed (bsp_packed_validate only) */
+    BSP_ERR_HIP = 6       /* a HIP call failed; see bsp_last_hip_error() */
+} bsp_status;
+
+typedef enum { BSP_F32 = 0, BSP_BF16 = 1, BSP_F16 = 2 } bsp_dtype;
+
+/* Reweighting factor of a group with sum of squares s (Sec. 3.2, update rule under Eq. 3):
+ * BSP_ALPHA_NORM   1 / (sqrt(s) + eps)   the form printed in the paper
+ * BSP_ALPHA_SQNORM 1 / (s + eps)         squared-norm form (its gradient alpha*W equals the
+ *                                        paper's gamma * W / ||W|| at the moment of a refresh) */
+typedef enum { BSP_ALPHA_SQNORM = 0, BSP_ALPHA_NORM = 1 } bsp_alpha_mode;
+
+/* What a percentile ranks over: each row of the [B, N] group array on its own (one
+ * row-block), or all B*N groups together (one matrix, or several matrices with equal R
+ * whose group arrays lie end to end). */
+typedef enum { BSP_SCOPE_BLOCK = 0, BSP_SCOPE_MATRIX = 1 } bsp_scope;
+
+/* ---- group norms and reweighting factors (Sec. 3.2, Eq. 3; Alg. 1 norm step) ---------
+ * For every group: sumsq = sum_r W[bR+r, j]^2 accumulated in fp32 with one fused
+ * multiply-add per row, rows ascending; norm = sqrt(sumsq); alpha per `mode`, each step
+ * one IEEE fp32 operation.
+ * W: [M, N] of dtype wdt.  sumsq, norm, alpha: [B, N] fp32, each may be NULL (not written). */
+int bsp_group_norms(const void *W, int wdt, int64_t M, int64_t N, int32_t R, float eps, int mode,
+                    float *sumsq, float *norm, float *alpha, void *stream);
+
+/* ---- gradient of the regulariser with fixed reweighting factors (Eq. 3; Alg. 2 loop) --
+ * coef_g = lambda * alpha_g                     (BSP_ALPHA_SQNORM)
+ *        = lambda * alpha_g / sqrt(sumsq_g)     (BSP_ALPHA_NORM; 0 for an all-zero group)
+ * grad[m, j] = coef_g * W[m, j], or fma(coef_g, W[m, j], grad[m, j]) when accumulate != 0,
+ * rounded to wdt.  sumsq_g is recomputed from W as in bsp_group_norms.
+ * grad: [M, N] of dtype wdt.  penalty: optional device double receiving the value of the
+ * regulariser, lambda * sum_g alpha_g ||W_g|| (NORM) or (lambda/2) * sum_g alpha_g ||W_g||^2
+ * (SQNORM); it is summed in a fixed order, so repeated calls give identical bits.
+ * ws: scratch of at least bsp_penalty_grad_workspace_bytes(M, N, R) bytes; only needed
+ * (may be NULL) when penalty != NULL. */
+int bsp_penalty_grad(const void *W, int wdt, int64_t M, int64_t N, int32_t R, const float *alpha,
+                     float lambda, int mode, int accumulate, void *grad, double *penalty, void *ws,
+                     size_t ws_bytes, void *stream);
+size_t bsp_penalty_grad_workspace_bytes(int64_t M, int64_t N, int32_t R);
+
+/* ---- prune decision (Alg. 1: a group with norm <= t_b is removed; Sec. 3.1 percentile) -
+ * sumsq: [B, N] fp32 as written by bsp_group_norms.  keep: [B, N] uint8, 1 = kept.
+ * n_keep < 0  threshold form: keep = (sumsq > t*t), compared exactly; t < 0 keeps all.
+ * n_keep >= 0 percentile form: in every scope of n groups, P = n - n_keep groups are to be
+ *             pruned; the threshold is the P-th smallest sumsq of the scope (none when
+ *             P <= 0) and keep = (sumsq > threshold): ties at the cut are pruned, so at
+ *             most n_keep groups survive.  `t` is ignored.
+ * t_used: optional, one fp32 per scope (B for BSP_SCOPE_BLOCK, 1 for BSP_SCOPE_MATRIX):
+ *         the threshold applied, in the squared domain (-inf when nothing was pruned).
+ *         Written by the percentile form only.
+ * ws: scratch of at least bsp_prune_mask_workspace_bytes(B, N, scope) bytes (percentile
+ *     form only).  B*N must be below 2^31. */
+int bsp_prune_mask(const float *sumsq, int64_t B, int64_t N, float t, int64_t n_keep, int scope,
+                   uint8_t *keep, float *t_used, void *ws, size_t ws_bytes, void *stream);
+size_t bsp_prune_mask_workspace_bytes(int64_t B, int64_t N, int scope);
+
+/* ---- compact storage (Sec. 3.1: only the kept columns of a block are indexed) ----------
+ * Layout.  For block b: cols_b = ascending j with keep[b, j] != 0; k_b = |cols_b| =
+ * blk_cnt[b]; kp_b = k_b rounded up to a multiple of k_align (0 stays 0);
+ * blk_ptr[0] = 0, blk_ptr[b+1] = blk_ptr[b] + kp_b.
+ *   col_idx[blk_ptr[b] + c]               = cols_b[c]          c < k_b
+ *                                         = cols_b[k_b - 1]    k_b <= c < kp_b   (pad)
+ *   vals[R*blk_ptr[b] + r*kp_b + c]       = W[bR + r, cols_b[c]] converted to vdt (RNE)
+ *                                         = +0                 pad
+ * Two phases because the size depends on the mask: bsp_pack_count fills blk_cnt [B] and
+ * blk_ptr [B+1]; the caller reads blk_ptr[B], allocates col_idx (that many int32) and vals
+ * (R times that many elements of vdt), and calls bsp_pack with capacity_cols = the number
+ * of columns the two buffers can hold.  A block whose range would exceed capacity_cols is
+ * left unwritten (nothing is written out of bounds).  k_align in {1, 8, 16, 32, 64}. */
+int bsp_pack_count(const uint8_t *keep, int64_t B, int64_t N, int32_t k_align, int32_t *blk_cnt,
+                   int32_t *blk_ptr, void *stream);
+int bsp_pack(const void *W, int wdt, int64_t M, int64_t N, int32_t R, const uint8_t *keep,
+             int32_t k_align, const int32_t *blk_cnt, const int32_t *blk_ptr, int64_t capacity_cols,
+             int32_t *col_idx, void *vals, int vdt, void *stream);
+
+/* Debug check of a compact storage: blk_ptr starts at 0 and grows by kp_b, indices in
+ * [0, N), strictly ascending over the first k_b slots, pads as specified.  Synchronises
+ * the stream.  Returns BSP_OK or BSP_ERR_FORMAT.  flag: device int32 scratch (1 element). */
+int bsp_packed_validate(int64_t M, int64_t N, int32_t R, int32_t k_align, const int32_t *blk_cnt,
+                        const int32_t *blk_ptr, const int32_t *col_idx, int64_t capacity_cols,
+                        int32_t *flag, void *stream);
+
+/* ---- the pruned linear layer (Sec. 3.1; Sec. 4.4) ---------------------------------------
+ *   Y[t, bR + r] = bias[bR + r] + sum_{c < kp_b} X[t, col_idx[blk_ptr[b] + c]] * vals[b, r, c]
+ * X: [T, N], Y: [T, M], row-major contiguous, dtype xdt; vals and bias have dtype xdt too;
+ * bias may be NULL.  Products are accumulated in fp32 (matrix cores for bf16 / fp16), the
+ * bias is added in fp32, and the sum is rounded once to xdt (RNE).  The order of the
+ * additions is unspecified.  The storage must be well formed (bsp_packed_validate).
+ * X and vals must be 16-byte aligned. */
+int bsp_linear(const void *X, int xdt, int64_t T, int64_t M, int64_t N, int32_t R, int32_t k_align,
+               const int32_t *blk_cnt, const int32_t *blk_ptr, const int32_t *col_idx, const void *vals,
+               const void *bias, void *Y, void *stream);
+
+/* ---- helpers (host only) -------------------------------------------------------------- */
+/* dense parameters / kept parameters = M*N / (R * kept_cols_total) (Sec. 4.4: 1.428x <=> 30 % sparsity) */
+double bsp_compression_rate(int64_t M, int64_t N, int32_t R, int64_t kept_cols_total);
+const char *bsp_status_string(int status);
+int bsp_last_hip_error(void); /* hipError_t of the last failing HIP call on this thread, 0 if none */
+const char *bsp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BSP_H */

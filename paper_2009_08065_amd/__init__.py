@@ -1,0 +1,10 @@
+"""Block-structured-pruned linear layers on AMD MI355X (gfx950).
+
+Thin Python binding over the C-ABI library libbsp.so (include/bsp.h).  Every operation runs
+in the library's HIP kernels; this package only marshals torch tensors into pointers.
+"""
+from .bsp import (  # noqa: F401
+    ALPHA_NORM, ALPHA_SQNORM, BF16, F16, F32, SCOPE_BLOCK, SCOPE_MATRIX, BspError, Packed,
+    bsp_compression_rate, bsp_group_norms, bsp_linear, bsp_pack, bsp_pack_count, bsp_packed_validate,
+    bsp_penalty_grad, bsp_prune_mask, lib, library_path,
+)

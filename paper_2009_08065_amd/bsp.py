@@ -1,0 +1,220 @@
+"""ctypes binding of include/bsp.h.  Same names as the C entry points; argument marshalling
+only.  Tensors must live on the GPU, be contiguous and have the dtype the C call expects; the
+kernels are enqueued on torch's current stream.  There is no CPU fallback: if libbsp.so cannot
+be loaded the import of `lib()` raises."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+F32, BF16, F16 = 0, 1, 2
+ALPHA_SQNORM, ALPHA_NORM = 0, 1
+SCOPE_BLOCK, SCOPE_MATRIX = 0, 1
+
+_DT = {torch.float32: F32, torch.bfloat16: BF16, torch.float16: F16}
+_TORCH = {F32: torch.float32, BF16: torch.bfloat16, F16: torch.float16}
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+
+class BspError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib().bsp_status_string(status).decode()
+        if status == 6:
+            msg += f" [hipError {lib().bsp_last_hip_error()}]"
+        super().__init__(f"{where}: {msg} (status {status})")
+
+
+def library_path() -> str:
+    return os.path.join(_HERE, "libbsp.so")
+
+
+def lib():
+    """Load libbsp.so (building it in-tree with hipcc first if it is not there)."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = library_path()
+    if not os.path.exists(path):
+        from . import build as _build
+        _build.build(force=True)
+    L = C.CDLL(path)
+    i64, i32, f32, vp, sz = C.c_int64, C.c_int32, C.c_float, C.c_void_p, C.c_size_t
+    L.bsp_group_norms.argtypes = [vp, C.c_int, i64, i64, i32, f32, C.c_int, vp, vp, vp, vp]
+    L.bsp_penalty_grad.argtypes = [vp, C.c_int, i64, i64, i32, vp, f32, C.c_int, C.c_int, vp, vp, vp, sz, vp]
+    L.bsp_penalty_grad_workspace_bytes.argtypes = [i64, i64, i32]
+    L.bsp_penalty_grad_workspace_bytes.restype = sz
+    L.bsp_prune_mask.argtypes = [vp, i64, i64, f32, i64, C.c_int, vp, vp, vp, sz, vp]
+    L.bsp_prune_mask_workspace_bytes.argtypes = [i64, i64, C.c_int]
+    L.bsp_prune_mask_workspace_bytes.restype = sz
+    L.bsp_pack_count.argtypes = [vp, i64, i64, i32, vp, vp, vp]
+    L.bsp_pack.argtypes = [vp, C.c_int, i64, i64, i32, vp, i32, vp, vp, i64, vp, vp, C.c_int, vp]
+    L.bsp_packed_validate.argtypes = [i64, i64, i32, i32, vp, vp, vp, i64, vp, vp]
+    L.bsp_linear.argtypes = [vp, C.c_int, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp, vp, vp]
+    L.bsp_compression_rate.argtypes = [i64, i64, i32, i64]
+    L.bsp_compression_rate.restype = C.c_double
+    L.bsp_status_string.argtypes = [C.c_int]
+    L.bsp_status_string.restype = C.c_char_p
+    L.bsp_last_hip_error.restype = C.c_int
+    L.bsp_version.restype = C.c_char_p
+    for name in ("bsp_group_norms", "bsp_penalty_grad", "bsp_prune_mask", "bsp_pack_count", "bsp_pack",
+                 "bsp_packed_validate", "bsp_linear"):
+        getattr(L, name).restype = C.c_int
+    _LIB = L
+    return L
+
+
+def _ptr(t: Optional[torch.Tensor], dtype=None):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("tensor must be a contiguous GPU tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"expected dtype {dtype}, got {t.dtype}")
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(st: int, where: str):
+    if st != 0:
+        raise BspError(st, where)
+
+
+def bsp_group_norms(W, R, eps=1e-6, mode=ALPHA_SQNORM, sumsq=None, norm=None, alpha=None, want=("sumsq", "norm", "alpha")):
+    """Returns (sumsq, norm, alpha) [B, N] fp32; entries not in `want` (and not passed) are None."""
+    M, N = W.shape
+    B = M // max(R, 1)
+    mk = lambda: torch.empty((B, N), dtype=torch.float32, device=W.device)
+    if sumsq is None and "sumsq" in want:
+        sumsq = mk()
+    if norm is None and "norm" in want:
+        norm = mk()
+    if alpha is None and "alpha" in want:
+        alpha = mk()
+    st = lib().bsp_group_norms(_ptr(W), _DT[W.dtype], M, N, R, eps, mode, _ptr(sumsq, torch.float32),
+                               _ptr(norm, torch.float32), _ptr(alpha, torch.float32), _stream())
+    _check(st, "bsp_group_norms")
+    return sumsq, norm, alpha
+
+
+def bsp_penalty_grad(W, R, alpha, lam, mode=ALPHA_SQNORM, grad=None, accumulate=False, want_penalty=False, ws=None):
+    """Returns (grad, penalty) with penalty a 1-element fp64 GPU tensor or None."""
+    M, N = W.shape
+    if grad is None:
+        grad = torch.empty_like(W)
+        accumulate = False
+    if grad.dtype != W.dtype or grad.shape != W.shape:
+        raise ValueError("grad must have the shape and dtype of W")
+    penalty = None
+    ws_bytes = 0
+    if want_penalty:
+        penalty = torch.empty(1, dtype=torch.float64, device=W.device)
+        need = lib().bsp_penalty_grad_workspace_bytes(M, N, R)
+        if ws is None:
+            ws = torch.empty(max(need, 8), dtype=torch.uint8, device=W.device)
+        ws_bytes = ws.numel() * ws.element_size()
+    st = lib().bsp_penalty_grad(_ptr(W), _DT[W.dtype], M, N, R, _ptr(alpha, torch.float32), lam, mode,
+                                int(bool(accumulate)), _ptr(grad), _ptr(penalty), _ptr(ws), ws_bytes, _stream())
+    _check(st, "bsp_penalty_grad")
+    return grad, penalty
+
+
+def bsp_prune_mask(sumsq, t=0.0, n_keep=-1, scope=SCOPE_BLOCK, keep=None, t_used=None, ws=None, want_t_used=False):
+    """Returns (keep uint8 [B, N], t_used or None)."""
+    B, N = sumsq.shape
+    if keep is None:
+        keep = torch.empty((B, N), dtype=torch.uint8, device=sumsq.device)
+    if t_used is None and want_t_used and n_keep >= 0:
+        t_used = torch.empty(B if scope == SCOPE_BLOCK else 1, dtype=torch.float32, device=sumsq.device)
+    ws_bytes = 0
+    if n_keep >= 0:
+        need = lib().bsp_prune_mask_workspace_bytes(B, N, scope)
+        if ws is None and need:
+            ws = torch.empty(need, dtype=torch.uint8, device=sumsq.device)
+        ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    st = lib().bsp_prune_mask(_ptr(sumsq, torch.float32), B, N, t, n_keep, scope, _ptr(keep, torch.uint8),
+                              _ptr(t_used, torch.float32), _ptr(ws), ws_bytes, _stream())
+    _check(st, "bsp_prune_mask")
+    return keep, t_used
+
+
+def bsp_pack_count(keep, k_align=32, blk_cnt=None, blk_ptr=None):
+    B, N = keep.shape
+    if blk_cnt is None:
+        blk_cnt = torch.empty(B, dtype=torch.int32, device=keep.device)
+    if blk_ptr is None:
+        blk_ptr = torch.empty(B + 1, dtype=torch.int32, device=keep.device)
+    st = lib().bsp_pack_count(_ptr(keep, torch.uint8), B, N, k_align, _ptr(blk_cnt, torch.int32),
+                              _ptr(blk_ptr, torch.int32), _stream())
+    _check(st, "bsp_pack_count")
+    return blk_cnt, blk_ptr
+
+
+@dataclass
+class Packed:
+    """The compact storage of one pruned weight (device tensors, canonical layout of bsp.h)."""
+    M: int
+    N: int
+    R: int
+    k_align: int
+    blk_cnt: torch.Tensor
+    blk_ptr: torch.Tensor
+    col_idx: torch.Tensor
+    vals: torch.Tensor
+    total_cols: int
+
+
+def bsp_pack(W, R, keep, k_align=32, vdt=None, blk_cnt=None, blk_ptr=None, total_cols=None):
+    """Two-phase pack.  Reads blk_ptr[B] back to the host once to size the buffers (unless
+    total_cols is given)."""
+    M, N = W.shape
+    if blk_cnt is None or blk_ptr is None:
+        blk_cnt, blk_ptr = bsp_pack_count(keep, k_align)
+    if total_cols is None:
+        total_cols = int(blk_ptr[-1].item())
+    vdtype = W.dtype if vdt is None else _TORCH[vdt]
+    col_idx = torch.empty(max(total_cols, 1), dtype=torch.int32, device=W.device)
+    vals = torch.empty(max(R * total_cols, 1), dtype=vdtype, device=W.device)
+    st = lib().bsp_pack(_ptr(W), _DT[W.dtype], M, N, R, _ptr(keep, torch.uint8), k_align, _ptr(blk_cnt, torch.int32),
+                        _ptr(blk_ptr, torch.int32), total_cols, _ptr(col_idx), _ptr(vals), _DT[vdtype], _stream())
+    _check(st, "bsp_pack")
+    return Packed(M, N, R, k_align, blk_cnt, blk_ptr, col_idx[:total_cols], vals[:R * total_cols], total_cols)
+
+
+def bsp_packed_validate(p: Packed) -> bool:
+    flag = torch.zeros(1, dtype=torch.int32, device=p.blk_ptr.device)
+    st = lib().bsp_packed_validate(p.M, p.N, p.R, p.k_align, _ptr(p.blk_cnt), _ptr(p.blk_ptr),
+                                   _ptr(p.col_idx) if p.total_cols else None, p.total_cols, _ptr(flag), _stream())
+    if st == 5:
+        return False
+    _check(st, "bsp_packed_validate")
+    return True
+
+
+def bsp_linear(X, p: Packed, bias=None, Y=None):
+    T, N = X.shape
+    if N != p.N:
+        raise ValueError("X has the wrong number of columns")
+    if p.vals.dtype != X.dtype or (bias is not None and bias.dtype != X.dtype):
+        raise ValueError("X, vals and bias must share one dtype")
+    if Y is None:
+        Y = torch.empty((T, p.M), dtype=X.dtype, device=X.device)
+    has = p.total_cols > 0
+    st = lib().bsp_linear(_ptr(X), _DT[X.dtype], T, p.M, N, p.R, p.k_align, _ptr(p.blk_cnt), _ptr(p.blk_ptr),
+                          _ptr(p.col_idx) if has else None, _ptr(p.vals) if has else None, _ptr(bias), _ptr(Y),
+                          _stream())
+    _check(st, "bsp_linear")
+    return Y
+
+
+def bsp_compression_rate(M, N, R, kept_cols_total) -> float:
+    return lib().bsp_compression_rate(M, N, R, kept_cols_total)

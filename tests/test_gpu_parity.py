@@ -1,0 +1,299 @@
+"""GPU vs CPU oracle, element by element, through the C ABI (paper_2009_08065_amd.bsp).
+
+Bars: bit-exact for sums of squares, norms, reweighting factors, gradients, masks and the
+compact storage; for Y, |y - y_oracle| <= tol * (|y_oracle| + rms(y_oracle)) with tol = 2e-2
+for bf16 / fp16 and 1e-5 for fp32."""
+import numpy as np
+import pytest
+import torch
+
+import bsp_workloads as wl
+import paper_2009_08065_amd as bsp
+from oracle import bsp_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+TDT = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}
+CODE = {"f32": orc.F32, "bf16": orc.BF16, "f16": orc.F16}
+TOL = {"f32": 1e-5, "bf16": 2e-2, "f16": 2e-2}
+
+
+def dev(a, dtype="f32"):
+    """numpy float32 (values representable in dtype) -> GPU tensor of that dtype."""
+    if a is None:
+        return None
+    return torch.from_numpy(np.ascontiguousarray(a)).to(TDT[dtype]).cuda()
+
+
+def host(t):
+    return t.detach().float().cpu().numpy() if t.is_floating_point() else t.detach().cpu().numpy()
+
+
+def bits_equal(gpu_f32, ref_f32):
+    a = np.ascontiguousarray(gpu_f32, dtype=np.float32).view(np.uint32)
+    b = np.ascontiguousarray(ref_f32, dtype=np.float32).view(np.uint32)
+    return np.array_equal(a, b)
+
+
+def assert_y_close(y_gpu, y_ref, dtype, rows=None):
+    y_ref = y_ref.astype(np.float64)
+    y_gpu = y_gpu.astype(np.float64)
+    if rows is not None:
+        y_ref, y_gpu = y_ref[rows], y_gpu[rows]
+    rms = np.sqrt(np.mean(y_ref ** 2))
+    err = np.abs(y_gpu - y_ref)
+    bound = TOL[dtype] * (np.abs(y_ref) + rms)
+    worst = np.max(err / bound) if err.size else 0.0
+    assert np.all(err <= bound), f"worst err/bound = {worst:.3f}"
+
+
+def pack_equal(p_gpu, p_ref):
+    assert np.array_equal(host(p_gpu.blk_cnt), p_ref["blk_cnt"])
+    assert np.array_equal(host(p_gpu.blk_ptr), p_ref["blk_ptr"])
+    assert p_gpu.total_cols == int(p_ref["blk_ptr"][-1])
+    assert np.array_equal(host(p_gpu.col_idx), p_ref["col_idx"])
+    assert bits_equal(host(p_gpu.vals), p_ref["vals"])
+
+
+# ------------------------------------------------------------------------------ norms
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+@pytest.mark.parametrize("R,M,N", [(16, 96, 1024), (8, 64, 777), (32, 64, 520), (1, 5, 64), (3, 27, 130), (64, 128, 72)])
+def test_group_norms_bit_exact(dtype, R, M, N):
+    W = wl.normal(R * 100 + N, (M, N), 0.02, dtype)
+    W[0:R, 3] = 0.0                                    # an all-zero group
+    for mode in (orc.ALPHA_SQNORM, orc.ALPHA_NORM):
+        s, nrm, alpha = bsp.bsp_group_norms(dev(W, dtype), R, eps=1e-6, mode=mode)
+        s_ref = orc.sumsq(W, R)
+        n_ref, a_ref = orc.norm_alpha(s_ref, 1e-6, mode)
+        assert bits_equal(host(s), s_ref)
+        assert bits_equal(host(nrm), n_ref)
+        assert bits_equal(host(alpha), a_ref)
+
+
+def test_group_norms_wide_value_range_and_partial_outputs():
+    rng = np.random.default_rng(5)
+    W = (rng.standard_normal((64, 256)) * np.exp(rng.uniform(-20, 20, (64, 256)))).astype(np.float32)
+    s_ref = orc.sumsq(W, 16)
+    s, nrm, alpha = bsp.bsp_group_norms(dev(W), 16, want=("sumsq",))
+    assert nrm is None and alpha is None and bits_equal(host(s), s_ref)
+    _, nrm, _ = bsp.bsp_group_norms(dev(W), 16, want=("norm",))
+    assert bits_equal(host(nrm), orc.norm_alpha(s_ref, 1e-6, 0)[0])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("R,M,N", [(16, 64, 512), (8, 32, 264), (32, 64, 100), (5, 20, 77)])
+@pytest.mark.parametrize("mode", [orc.ALPHA_SQNORM, orc.ALPHA_NORM])
+def test_penalty_grad(dtype, R, M, N, mode):
+    W = wl.normal(R + N, (M, N), 0.02, dtype)
+    W[0:R, 1] = 0.0
+    lam = 1e-4
+    _, alpha = orc.norm_alpha(orc.sumsq(W, R), 1e-6, mode)
+    G_ref, pen_ref = orc.penalty_grad(W, R, alpha, lam, mode, gdt=CODE[dtype])
+    Wd, ad = dev(W, dtype), dev(alpha)
+    G, pen = bsp.bsp_penalty_grad(Wd, R, ad, lam, mode=mode, want_penalty=True)
+    assert bits_equal(host(G), G_ref)
+    assert abs(pen.item() - pen_ref) <= 1e-11 * abs(pen_ref)
+    G2, pen2 = bsp.bsp_penalty_grad(Wd, R, ad, lam, mode=mode, want_penalty=True)
+    assert pen2.item() == pen.item()                   # fixed summation order
+    G3, _ = bsp.bsp_penalty_grad(Wd, R, ad, lam, mode=mode)
+    assert bits_equal(host(G3), G_ref)
+    G0 = wl.normal(99, (M, N), 0.01, dtype)
+    Gacc_ref, _ = orc.penalty_grad(W, R, alpha, lam, mode, gdt=CODE[dtype], G0=G0)
+    Gacc, _ = bsp.bsp_penalty_grad(Wd, R, ad, lam, mode=mode, grad=dev(G0, dtype), accumulate=True)
+    assert bits_equal(host(Gacc), Gacc_ref)
+
+
+# ------------------------------------------------------------------------------ masks
+def test_mask_threshold_bit_exact_with_ties():
+    W = wl.normal(3, (64, 333), 0.02)
+    s = orc.sumsq(W, 16)
+    t = np.float32(np.sqrt(np.median(s)))
+    s[1, 5] = np.float32(float(t) * float(t))           # as close to the tie as fp32 allows
+    for tt in (-1.0, 0.0, float(t), 0.05, 10.0):
+        keep, _ = bsp.bsp_prune_mask(dev(s), t=tt)
+        assert np.array_equal(host(keep), orc.mask_threshold(s, tt))
+    sq = np.array([[0.25, 0.2500001, 0.2499999, 0.0]], np.float32)   # Alg. 1: norm == t is pruned
+    assert host(bsp.bsp_prune_mask(dev(sq), t=0.5)[0]).tolist() == [[0, 1, 0, 0]]
+
+
+@pytest.mark.parametrize("scope", [orc.SCOPE_BLOCK, orc.SCOPE_MATRIX])
+@pytest.mark.parametrize("B,N", [(48, 768), (7, 1000), (3, 65), (1, 1), (64, 4096)])
+def test_mask_rank_bit_exact(scope, B, N):
+    W = wl.normal(B + N, (B * 16, N), 0.02)
+    s = orc.sumsq(W, 16)
+    if N > 8:
+        s[0, 1] = s[0, 2] = s[0, 3]                    # ties
+        s[B - 1, :] = s[B - 1, 0]                      # a constant row
+    if B > 2:
+        s[1, 0] = 0.0
+    n = N if scope == orc.SCOPE_BLOCK else B * N
+    sd = dev(s)
+    for n_keep in sorted({0, 1, n // 5, n // 3, n // 2, n - 1, n, n + 5}):
+        keep, t_used = bsp.bsp_prune_mask(sd, n_keep=n_keep, scope=scope, want_t_used=True)
+        k_ref, t_ref = orc.mask_rank(s, n_keep, scope)
+        assert np.array_equal(host(keep), k_ref), n_keep
+        assert bits_equal(host(t_used), t_ref), n_keep
+
+
+def test_mask_rank_wide_range_and_negative_values():
+    rng = np.random.default_rng(11)
+    s = (rng.standard_normal((16, 500)) * np.exp(rng.uniform(-30, 30, (16, 500)))).astype(np.float32)
+    for scope in (orc.SCOPE_BLOCK, orc.SCOPE_MATRIX):
+        n = 500 if scope == orc.SCOPE_BLOCK else 8000
+        for n_keep in (n // 7, n // 2, n - 3):
+            keep, t_used = bsp.bsp_prune_mask(dev(s), n_keep=n_keep, scope=scope, want_t_used=True)
+            k_ref, t_ref = orc.mask_rank(s, n_keep, scope)
+            assert np.array_equal(host(keep), k_ref) and bits_equal(host(t_used), t_ref)
+
+
+# ------------------------------------------------------------------------------ packing
+@pytest.mark.parametrize("k_align", [1, 8, 16, 32, 64])
+@pytest.mark.parametrize("R,N,wdt,vdt", [(16, 768, "f32", "f32"), (8, 300, "f32", "bf16"), (32, 1030, "bf16", "bf16"),
+                                         (3, 75, "f16", "f16"), (1, 40, "f32", "f16"), (64, 129, "bf16", "f32")])
+def test_pack_bit_exact(R, N, wdt, vdt, k_align):
+    M = 6 * R
+    W = wl.normal(R + N, (M, N), 0.02, wdt)
+    keep = wl.bernoulli_keep_mask(R * 7 + k_align, M // R, N, 0.3)
+    keep[1, :] = 0
+    keep[2, :] = 1
+    keep[3, :] = 0
+    keep[3, N - 1] = 1
+    p = bsp.bsp_pack(dev(W, wdt), R, torch.from_numpy(keep).cuda(), k_align,
+                     vdt=CODE[vdt])
+    pack_equal(p, orc.pack(W, R, keep, k_align, CODE[vdt]))
+    assert bsp.bsp_packed_validate(p)
+    if p.total_cols:
+        bad = bsp.Packed(p.M, p.N, p.R, p.k_align, p.blk_cnt, p.blk_ptr, p.col_idx.clone(), p.vals, p.total_cols)
+        bad.col_idx[0] = N
+        assert not bsp.bsp_packed_validate(bad)
+
+
+def test_pack_all_empty_and_capacity_guard():
+    W = wl.normal(1, (32, 64), 0.02)
+    keep0 = torch.zeros((2, 64), dtype=torch.uint8, device="cuda")
+    p = bsp.bsp_pack(dev(W), 16, keep0, 32)
+    assert p.total_cols == 0 and host(p.blk_ptr).tolist() == [0, 0, 0] and bsp.bsp_packed_validate(p)
+    Y = bsp.bsp_linear(dev(wl.normal(2, (5, 64), 1.0)), p, dev(wl.normal(3, (32,), 0.02)))
+    assert bits_equal(host(Y), np.broadcast_to(wl.normal(3, (32,), 0.02), (5, 32)))
+    # capacity smaller than needed: blocks beyond it stay unwritten, nothing out of bounds
+    keep = torch.from_numpy(wl.random_keep_mask(4, 2, 64, 20)).cuda()
+    cnt, ptr = bsp.bsp_pack_count(keep, 32)
+    assert host(ptr).tolist() == [0, 32, 64]
+    col = torch.full((64,), -7, dtype=torch.int32, device="cuda")
+    vals = torch.full((16 * 64,), 5.0, device="cuda")
+    st = bsp.lib().bsp_pack(dev(W).data_ptr(), 0, 32, 64, 16, keep.data_ptr(), 32, cnt.data_ptr(), ptr.data_ptr(), 32,
+                            col.data_ptr(), vals.data_ptr(), 0, None)
+    torch.cuda.synchronize()
+    assert st == 0 and (host(col)[32:] == -7).all() and (host(col)[:20] >= 0).all() and (host(vals)[16 * 32:] == 5).all()
+
+
+# ------------------------------------------------------------------------------ the layer
+def run_layer(X, W, bias, R, keep, k_align, dtype, T_rows=None):
+    code = CODE[dtype]
+    p_ref = orc.pack(W, R, keep, k_align, code)
+    Xd, bd = dev(X, dtype), dev(bias, dtype)
+    p = bsp.bsp_pack(dev(W, dtype), R, torch.from_numpy(np.ascontiguousarray(keep)).cuda(), k_align)
+    pack_equal(p, p_ref)
+    Y = host(bsp.bsp_linear(Xd, p, bd))
+    if T_rows is None:
+        Y_ref, _ = orc.linear_packed(X, p_ref, bias, ydt=code, n_threads=8)
+        assert_y_close(Y, Y_ref, dtype)
+    else:
+        for (t0, t1) in T_rows:
+            Y_ref, _ = orc.linear_packed(X, p_ref, bias, ydt=code, t0=t0, t1=t1, n_threads=8)
+            assert_y_close(Y, Y_ref, dtype, rows=slice(t0, t1))
+    return Y, p
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+@pytest.mark.parametrize("k_align", [1, 16, 32])
+@pytest.mark.parametrize("R,T,M,N,p_keep", [(16, 100, 64, 200, 0.5), (8, 70, 40, 333, 0.2), (32, 130, 96, 256, 0.33),
+                                            (1, 9, 7, 50, 0.5), (3, 65, 12, 100, 0.7), (64, 17, 128, 96, 0.4)])
+def test_linear_small_shapes(dtype, k_align, R, T, M, N, p_keep):
+    d = wl.layer(R * 1000 + T, T, M, N, dtype)
+    keep = wl.bernoulli_keep_mask(T + N, M // R, N, p_keep)
+    keep[0, :] = 0                                      # a row-block with nothing kept: bias only
+    if M // R > 1:
+        keep[1, :] = 1                                  # a dense row-block
+    run_layer(d["X"], d["W"], d["bias"], R, keep, k_align, dtype)
+    run_layer(d["X"], d["W"], None, R, keep, k_align, dtype)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_linear_keep_all_is_dense_gemm_keep_none_is_bias(dtype):
+    d = wl.layer(77, 96, 64, 160, dtype)
+    ones = np.ones((4, 160), np.uint8)
+    Y, _ = run_layer(d["X"], d["W"], d["bias"], 16, ones, 32, dtype)
+    want = d["X"].astype(np.float64) @ d["W"].astype(np.float64).T + d["bias"]
+    assert_y_close(Y, want, dtype)
+    Y0, _ = run_layer(d["X"], d["W"], d["bias"], 16, np.zeros((4, 160), np.uint8), 32, dtype)
+    assert bits_equal(Y0, np.broadcast_to(d["bias"], (96, 64)))
+
+
+def test_config1_fp32_attention_projection():
+    c = wl.config1()
+    run_layer(c["X"], c["W"], c["bias"], c["R"], c["keep"], 32, "f32")
+
+
+def test_config2_bf16_ffn_up_full_chain():
+    c = wl.config2()
+    W, R = c["W"], c["R"]
+    Wd = dev(W, "bf16")
+    s, _, _ = bsp.bsp_group_norms(Wd, R)
+    s_ref = orc.sumsq(W, R)
+    assert bits_equal(host(s), s_ref)
+    keep, _ = bsp.bsp_prune_mask(s, n_keep=c["n_keep"], scope=bsp.SCOPE_BLOCK)
+    k_ref, _ = orc.mask_rank(s_ref, c["n_keep"], orc.SCOPE_BLOCK)
+    assert np.array_equal(host(keep), k_ref)
+    assert (k_ref.sum(axis=1) == 256).all()
+    run_layer(c["X"], W, c["bias"], R, k_ref, 32, "bf16", T_rows=[(0, 64), (1000, 1100), (4090, 4096)])
+
+
+def chain_matrix(d, k_align=32, rows=((0, 48), (5000, 5040), (8180, 8192))):
+    W, R = d["W"], d["R"]
+    Wd = dev(W, "bf16")
+    s, _, _ = bsp.bsp_group_norms(Wd, R)
+    s_ref = orc.sumsq(W, R)
+    assert bits_equal(host(s), s_ref)
+    keep, t_used = bsp.bsp_prune_mask(s, n_keep=d["n_keep"], scope=bsp.SCOPE_MATRIX, want_t_used=True)
+    k_ref, t_ref = orc.mask_rank(s_ref, d["n_keep"], orc.SCOPE_MATRIX)
+    assert np.array_equal(host(keep), k_ref) and bits_equal(host(t_used), t_ref)
+    T = d["X"].shape[0]
+    rows = [(min(a, T - 1), min(b, T)) for a, b in rows]
+    run_layer(d["X"], W, d["bias"], R, k_ref, k_align, "bf16", T_rows=rows)
+
+
+def test_config3_bert_base_layer_set():
+    for d in wl.config3():
+        chain_matrix(d)
+
+
+@pytest.mark.parametrize("R", [8, 16, 32])
+def test_config4_bert_large_layer_set(R):
+    for d in wl.config4(R=R):
+        chain_matrix(d)
+
+
+def test_skewed_weights_ragged_blocks():
+    R, M, N, T = 16, 512, 1024, 300
+    W = wl.skewed_weight(21, M, N, R, "bf16", sigma=1.5)
+    X = wl.normal(22, (T, N), 1.0, "bf16")
+    bias = wl.normal(23, (M,), 0.02, "bf16")
+    s_ref = orc.sumsq(W, R)
+    k_ref, _ = orc.mask_rank(s_ref, (M // R) * N // 5, orc.SCOPE_MATRIX)
+    cnt = k_ref.sum(axis=1)
+    assert cnt.max() > 4 * max(cnt.min(), 1)            # the kept count per block really is skewed
+    keep, _ = bsp.bsp_prune_mask(dev(s_ref), n_keep=(M // R) * N // 5, scope=bsp.SCOPE_MATRIX)
+    assert np.array_equal(host(keep), k_ref)
+    run_layer(X, W, bias, R, k_ref, 32, "bf16")
+
+
+def test_determinism_run_to_run():
+    d = wl.config4(tokens=512, shapes=[("attn_out", 1024, 1024)])[0]
+    s_ref = orc.sumsq(d["W"], 16)
+    k_ref, _ = orc.mask_rank(s_ref, d["n_keep"], orc.SCOPE_MATRIX)
+    p = bsp.bsp_pack(dev(d["W"], "bf16"), 16, torch.from_numpy(k_ref).cuda(), 32)
+    Xd, bd = dev(d["X"], "bf16"), dev(d["bias"], "bf16")
+    y1 = bsp.bsp_linear(Xd, p, bd).clone()
+    y2 = bsp.bsp_linear(Xd, p, bd)
+    assert torch.equal(y1, y2)
