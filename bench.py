@@ -35,7 +35,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
 class Matrix:
     """Device-resident tensors and preallocated outputs of one layer of the set."""
 
-    def __init__(self, d, k_align=32):
+    def __init__(self, d, k_align=32, path="planned"):
         self.name, self.M, self.N, self.R, self.T = d["name"], d["M"], d["N"], d["R"], d["T"]
         self.n_keep, self.k_align = d["n_keep"], k_align
         dev = "cuda"
@@ -60,6 +60,11 @@ class Matrix:
         self.packed = bsp.Packed(self.M, self.N, self.R, k_align, self.blk_cnt, self.blk_ptr, self.col_idx,
                                  self.vals, self.capacity)
         self.kept_cols = None
+        self.use_plan = path == "planned" and bsp.bsp_linear_plan_supported(torch.bfloat16, self.N, k_align)
+        self.plan = None
+        if self.use_plan:
+            self.plan = torch.empty(bsp.lib().bsp_linear_plan_bytes(self.R, self.capacity), dtype=torch.uint8,
+                                    device=dev)
 
     def prune_and_pack(self, lam=1e-4, eps=1e-6):
         bsp.bsp_group_norms(self.W, self.R, eps=eps, mode=bsp.ALPHA_SQNORM, sumsq=self.sumsq, alpha=self.alpha,
@@ -73,9 +78,14 @@ class Matrix:
                         self.vals.data_ptr(), bsp.BF16, torch.cuda.current_stream().cuda_stream)
         if st != 0:
             raise bsp.BspError(st, "bsp_pack")
+        if self.use_plan:
+            bsp.bsp_linear_plan(self.packed, plan=self.plan)
 
     def linear(self):
-        bsp.bsp_linear(self.X, self.packed, self.bias, Y=self.Y)
+        if self.use_plan:
+            bsp.bsp_linear_planned(self.X, self.packed, self.plan, self.bias, Y=self.Y)
+        else:
+            bsp.bsp_linear(self.X, self.packed, self.bias, Y=self.Y)
 
     # algorithmic work of one layer call
     def useful_flops(self):
@@ -89,31 +99,23 @@ class Matrix:
         return 2.0 * self.T * self.N + 2.0 * self.T * self.M + 2.0 * self.R * padded + 4.0 * padded + 2.0 * self.M
 
 
-def cpu_baseline(mats, target_seconds=12.0):
-    """The CPU oracle's layer on a bounded sample of the same workload (tokens 0..n-1 of the
-    FFN up-projection), on the host cores of this machine."""
+def cpu_baseline(mats):
+    """The CPU oracle's layer on the same workload (all four matrices, all tokens: about a
+    second per matrix on this machine's host cores), timed as it stands."""
     from oracle import bsp_oracle as orc
-    m = next(x for x in mats if x.name == "ffn_up")
     cores = min(len(os.sched_getaffinity(0)), 16)
-    W = m.W.float().cpu().numpy()
-    X = m.X.float().cpu().numpy()
-    bias = m.bias.float().cpu().numpy()
-    keep = m.keep.cpu().numpy()
-    p = orc.pack(W, m.R, keep, m.k_align, orc.BF16)
-    kept = int(p["blk_cnt"].sum())
-
-    def run(n_tok):
+    flops, secs = 0.0, 0.0
+    for m in mats:
+        W = m.W.float().cpu().numpy()
+        X = m.X.float().cpu().numpy()
+        bias = m.bias.float().cpu().numpy()
+        p = orc.pack(W, m.R, m.keep.cpu().numpy(), m.k_align, orc.BF16)
         t = time.perf_counter()
-        orc.linear_packed(X, p, bias, ydt=orc.BF16, t0=0, t1=n_tok, n_threads=cores)
-        return time.perf_counter() - t
-
-    probe_tok = 32
-    dt = run(probe_tok)
-    n_tok = int(min(m.T, max(probe_tok, probe_tok * target_seconds / max(dt, 1e-6))))
-    dt = run(n_tok)
-    flops = 2.0 * n_tok * m.R * kept
-    return {"value": flops / dt / 1e12, "unit": "useful TFLOP/s", "cores": cores, "kind": "oracle",
-            "sample": f"oracle layer (fp64 accumulate) on tokens 0..{n_tok - 1} of ffn_up 4096x1024, 5x, R=16; {dt:.1f} s"}
+        orc.linear_packed(X, p, bias, ydt=orc.BF16, n_threads=cores)
+        secs += time.perf_counter() - t
+        flops += 2.0 * m.T * m.R * int(p["blk_cnt"].sum())
+    return {"value": round(flops / secs / 1e12, 5), "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+            "sample": f"oracle layer (fp64 accumulate, OpenMP over row-blocks) on the full set, all 8192 tokens; {secs:.1f} s"}
 
 
 def main():
@@ -123,6 +125,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--R", type=int, default=16)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--path", choices=["planned", "canonical"], default="planned",
+                    help="layer operands: the derived plan buffer (default) or the compact storage itself")
+    ap.add_argument("--waves", type=int, default=0, help="experiment: wavefronts per workgroup of the tiled kernel")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: the path has no multi-GPU part; run with --gpus 1", file=sys.stderr)
@@ -132,7 +137,9 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
 
-    mats = [Matrix(d) for d in wl.config4(R=args.R)]
+    if args.waves:
+        bsp.lib().bsp_debug_set_tiled_waves(args.waves)
+    mats = [Matrix(d, path=args.path) for d in wl.config4(R=args.R)]
     for m in mats:   # once, to learn the kept counts (needed only for the FLOP accounting)
         m.prune_and_pack()
         m.linear()
@@ -194,7 +201,9 @@ def main():
         "config": {"workload": "BERT-large linear set (configs[3]): QKV 3072x1024, out 1024x1024, up 4096x1024, "
                                "down 1024x4096; 8192 tokens; 5x compression; matrix-scope percentile mask",
                    "block_rows": args.R, "k_align": 32, "tokens": 8192,
-                   "step": "group_norms + penalty_grad + prune_mask + pack_count + pack + linear, 4 matrices"},
+                   "layer_path": args.path,
+                   "step": "group_norms + penalty_grad + prune_mask + pack_count + pack + linear_plan + linear, "
+                           "4 matrices"},
         "linear_only": {"ms": round(lin_total_ms, 4), "useful_tflops": round(achieved_tflops, 2),
                         "dense_equiv_tflops": round(dense / (lin_total_ms * 1e-3) / 1e12, 2),
                         "frac_mfma_peak": round(achieved_tflops / MFMA_BF16_PEAK_TFLOPS, 4),

@@ -57,6 +57,12 @@ def lib():
     L.bsp_pack.argtypes = [vp, C.c_int, i64, i64, i32, vp, i32, vp, vp, i64, vp, vp, C.c_int, vp]
     L.bsp_packed_validate.argtypes = [i64, i64, i32, i32, vp, vp, vp, i64, vp, vp]
     L.bsp_linear.argtypes = [vp, C.c_int, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp, vp, vp]
+    L.bsp_linear_plan_supported.argtypes = [C.c_int, i64, i32]
+    L.bsp_linear_plan_supported.restype = C.c_int
+    L.bsp_linear_plan_bytes.argtypes = [i32, i64]
+    L.bsp_linear_plan_bytes.restype = sz
+    L.bsp_linear_plan.argtypes = [C.c_int, i64, i64, i32, i32, vp, vp, vp, vp, i64, vp, sz, vp]
+    L.bsp_linear_planned.argtypes = [vp, C.c_int, i64, i64, i64, i32, i32, vp, vp, i64, vp, vp, vp]
     L.bsp_compression_rate.argtypes = [i64, i64, i32, i64]
     L.bsp_compression_rate.restype = C.c_double
     L.bsp_status_string.argtypes = [C.c_int]
@@ -64,7 +70,7 @@ def lib():
     L.bsp_last_hip_error.restype = C.c_int
     L.bsp_version.restype = C.c_char_p
     for name in ("bsp_group_norms", "bsp_penalty_grad", "bsp_prune_mask", "bsp_pack_count", "bsp_pack",
-                 "bsp_packed_validate", "bsp_linear"):
+                 "bsp_packed_validate", "bsp_linear", "bsp_linear_plan", "bsp_linear_planned"):
         getattr(L, name).restype = C.c_int
     _LIB = L
     return L
@@ -213,6 +219,37 @@ def bsp_linear(X, p: Packed, bias=None, Y=None):
                           _ptr(p.col_idx) if has else None, _ptr(p.vals) if has else None, _ptr(bias), _ptr(Y),
                           _stream())
     _check(st, "bsp_linear")
+    return Y
+
+
+def bsp_linear_plan_supported(dtype, N, k_align) -> bool:
+    return bool(lib().bsp_linear_plan_supported(_DT[dtype], N, k_align))
+
+
+def bsp_linear_plan(p: Packed, plan=None):
+    """Build the derived operand buffer of a compact storage.  Returns a uint8 GPU tensor."""
+    need = lib().bsp_linear_plan_bytes(p.R, max(p.total_cols, 1))
+    if plan is None:
+        plan = torch.empty(max(need, 16), dtype=torch.uint8, device=p.blk_ptr.device)
+    has = p.total_cols > 0
+    st = lib().bsp_linear_plan(_DT[p.vals.dtype], p.M, p.N, p.R, p.k_align, _ptr(p.blk_cnt), _ptr(p.blk_ptr),
+                               _ptr(p.col_idx) if has else None, _ptr(p.vals) if has else None, p.total_cols,
+                               _ptr(plan), plan.numel(), _stream())
+    _check(st, "bsp_linear_plan")
+    return plan
+
+
+def bsp_linear_planned(X, p: Packed, plan, bias=None, Y=None):
+    T, N = X.shape
+    if N != p.N:
+        raise ValueError("X has the wrong number of columns")
+    if bias is not None and bias.dtype != X.dtype:
+        raise ValueError("X and bias must share one dtype")
+    if Y is None:
+        Y = torch.empty((T, p.M), dtype=X.dtype, device=X.device)
+    st = lib().bsp_linear_planned(_ptr(X), _DT[X.dtype], T, p.M, N, p.R, p.k_align, _ptr(p.blk_ptr), _ptr(plan),
+                                  p.total_cols, _ptr(bias), _ptr(Y), _stream())
+    _check(st, "bsp_linear_planned")
     return Y
 
 

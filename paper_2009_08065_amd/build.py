@@ -8,7 +8,8 @@ CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libbsp.so")
 OBJ_DIR = os.path.join(HERE, "_build")
-SOURCES = ["bsp_api.hip", "bsp_norms.hip", "bsp_mask.hip", "bsp_pack.hip", "bsp_linear.hip"]
+SOURCES = ["bsp_api.hip", "bsp_norms.hip", "bsp_mask.hip", "bsp_pack.hip", "bsp_linear.hip", "bsp_linear_tiled.hip",
+           "bsp_plan.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off", "-fno-fast-math",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -28,7 +29,7 @@ def _compile(src):
 
 
 def build(force: bool = True) -> str:
-    srcs = [os.path.join(CSRC, s) for s in SOURCES] + [os.path.join(CSRC, "bsp_common.h"),
+    srcs = [os.path.join(CSRC, s) for s in SOURCES] + [os.path.join(CSRC, "bsp_common.h"), os.path.join(CSRC, "bsp_linear_internal.h"),
                                                        os.path.join(INCLUDE, "bsp.h")]
     if not force and os.path.exists(LIB) and all(os.path.getmtime(LIB) >= os.path.getmtime(s) for s in srcs):
         return LIB

@@ -2,6 +2,7 @@
 //   Y[t, bR + r] = bias[bR + r] + sum_c X[t, col_idx[b, c]] * vals[b, r, c]
 // i.e. per row-block a gather of the kept columns of X followed by a small dense product.
 #include "bsp_common.h"
+#include "bsp_linear_internal.h"
 
 namespace bsp {
 namespace {
@@ -170,6 +171,18 @@ extern "C" int bsp_linear(const void *X, int xdt, int64_t T, int64_t M, int64_t 
     hipStream_t s = (hipStream_t)stream;
     dim3 grid((unsigned)tok_tiles, (unsigned)B, 1);
     const bool mfma_ok = xdt != BSP_F32 && k_align % 32 == 0 && col_idx && vals && aligned(col_idx, 16);
+    if (mfma_ok && aligned(Y, 16) && tiled_supported(xdt, N, k_align)) {
+        TiledArgs a{};
+        a.xdt = xdt;
+        a.X = (const uint16_t *)X;
+        a.T = T; a.M = M; a.N = N; a.B = B; a.R = R;
+        a.blk_ptr = blk_ptr;
+        a.col_idx = col_idx;
+        a.vals = (const uint16_t *)vals;
+        a.bias = bias;
+        a.Y = Y;
+        return launch_linear_tiled(a, false, s);
+    }
     if (mfma_ok) {
         if (xdt == BSP_BF16)
             linear_mfma_direct_kernel<BSP_BF16><<<grid, kThreads, 0, s>>>((const uint16_t *)X, T, M, N, R, blk_ptr,

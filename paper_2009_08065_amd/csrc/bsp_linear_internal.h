@@ -1,0 +1,39 @@
+// Internal interface between the layer's entry points and its tiled matrix-core kernel.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace bsp {
+
+struct TiledArgs {
+    int xdt;
+    const uint16_t *X;
+    int64_t T, M, N, B;
+    int32_t R;
+    int32_t npad;             // filled by the launcher: N rounded up to 256 columns
+    const int32_t *blk_ptr;
+    const int32_t *col_idx;   // canonical source
+    const uint16_t *vals;     // canonical source
+    const void *wfrag;        // planned source: [step][fragment][lane] 16-byte panel fragments
+    const uint32_t *xoff;     // planned source: [step][lane] two 16-bit LDS byte offsets
+    const void *bias;
+    void *Y;
+};
+
+// True when the tiled kernel can take this layer (16-bit floats, kp_b % 32 == 0, X tile fits in LDS).
+bool tiled_supported(int xdt, int64_t N, int32_t k_align);
+int launch_linear_tiled(const TiledArgs &args, bool plan, hipStream_t s);
+void set_tiled_waves(int waves);
+// Steps the planned kernel may read past the last step of the storage (values unused).
+int plan_slack_steps();
+
+// Placement of X column c inside a 16-token sub-tile held in LDS, shared by the copy-in of the
+// tiled kernel and by the plan builder: byte offset of token quad p (tokens 4p .. 4p+3).
+__host__ __device__ inline uint32_t lds_col_offset(uint32_t c, uint32_t p) {
+    const uint32_t row = (c & ~31u) | ((c >> 2) & 7u) | ((c & 3u) << 3);
+    return row * 32u + ((p ^ ((c >> 5) & 3u)) << 3);
+}
+// LDS bank group (8 banks of 4 bytes = one 32-byte row) that column c lands in.
+__host__ __device__ inline uint32_t lds_bank_group(uint32_t c) { return (c >> 2) & 7u; }
+
+}  // namespace bsp

@@ -1,0 +1,525 @@
+// Tiled matrix-core kernels of the block-structure-pruned linear layer (Sec. 3.1, Sec. 4.4)
+// for bf16 / fp16 on gfx950.
+//
+// A workgroup owns a tile of 16*NSUB tokens and a strip of row-blocks.  It copies its X tile
+// from HBM into LDS once, with full-row coalesced loads, transposed to [column][16 tokens] so
+// that the 16 tokens of one X column are 32 contiguous bytes.  Every wavefront then takes a
+// contiguous run of the strip's row-blocks holding an equal share of the strip's kept columns
+// (uneven kept counts balance).  It walks its kept columns 32 at a time ("step"): the value
+// panel fragment (16 rows x 32 kept columns) comes straight from global memory / L2 and is
+// reused for all NSUB token sub-tiles; the matching X fragment (32 kept columns x 16 tokens)
+// is gathered out of LDS by two transposing reads (ds_read_b64_tr_b16), in which every lane
+// supplies the address of its own column, so the per-row-block gather costs no extra
+// instructions.  One v_mfma_f32_16x16x32 per (32 kept columns, 16 tokens, 16 rows).
+//
+// LDS placement of column c of a sub-tile (swizzled so that the transposing 8-byte stores of
+// the copy-in are bank-conflict free): see lds_col_offset().
+//
+// Two kernels, one per source of the per-step operands:
+//   canonical  the compact storage itself (col_idx / vals);
+//   planned    a derived buffer built by bsp_linear_plan, where the kept columns of a row-block
+//              are re-ordered so that the 8 columns one half-wavefront reads in one LDS
+//              instruction fall into 8 different bank groups, and where the panel fragment
+//              and the two LDS offsets of every lane are stored ready to load.  Its inner loop
+//              is written to keep vector-ALU work per step minimal (on CDNA a 64-lane VALU
+//              instruction occupies the SIMD for 4 cycles, a 16x16x32 MFMA for 16): operand
+//              addresses advance by constants, operands of the next kRing steps are in flight,
+//              and the LDS reads of step s+1 are issued before the MFMAs of step s.
+#include "bsp_common.h"
+#include "bsp_linear_internal.h"
+
+namespace bsp {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+
+constexpr int kMaxStripBlocks = 1024;  // row-blocks per strip (their blk_ptr slice is cached in LDS)
+constexpr int kRing = 4;               // steps of operands in flight per wavefront
+
+// Distance in LDS between the 16-token sub-tiles of a workgroup's X tile: a constant, so that
+// sub-tile offsets fold into the immediate field of the LDS instructions.
+template <int NSUB>
+constexpr uint32_t sub_stride() { return NSUB == 4 ? 32768u : 65536u; }
+
+template <int DT>
+__device__ __forceinline__ f32x4 mfma16(uint4 a, uint4 b, f32x4 c) {
+    if constexpr (DT == BSP_BF16)
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c,
+                                                       0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0,
+                                                      0, 0);
+}
+
+__device__ __forceinline__ uint2 tr_read(const uint8_t *lds_base, uint32_t off) {
+    s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(lds_base + off));
+    return __builtin_bit_cast(uint2, v);
+}
+
+// Two fp32 -> two 16-bit floats (round-to-nearest-even, hardware conversion), packed.
+template <int DT>
+__device__ __forceinline__ uint32_t cvt_pk(float a, float b) {
+    if constexpr (DT == BSP_BF16)
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{a, b}, bf16x2));
+    else
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{a, b}, f16x2));
+}
+
+extern __shared__ __attribute__((aligned(16))) uint8_t smem_x[];
+
+// Copy the workgroup's X tile into LDS, transposed.  Unit of work = 4 columns x 4 tokens per
+// lane (four 8-byte loads, a 4x4 transpose of 16-bit values in registers, four 8-byte LDS
+// stores); all the loads of a batch are issued before the first store so their latencies overlap.
+template <int NSUB>
+__device__ __forceinline__ void stage_x_tile(const uint16_t *__restrict__ X, int64_t T, int64_t N, int32_t npad,
+                                             int64_t t0) {
+    constexpr int kBatch = 4;
+    const int cquads = npad >> 2;
+    const int units = cquads * (4 * NSUB);
+    for (int u0 = threadIdx.x; u0 < units; u0 += blockDim.x * kBatch) {
+        uint2 a[kBatch][4];
+#pragma unroll
+        for (int k = 0; k < kBatch; ++k) {
+            const int u = u0 + k * blockDim.x;
+            const int cq = u % cquads, tq = u / cquads;
+            const int c = cq << 2;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int64_t t = t0 + 4 * tq + i;
+                a[k][i] = (u < units && t < T && c < N) ? *reinterpret_cast<const uint2 *>(X + t * N + c)
+                                                        : make_uint2(0u, 0u);
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < kBatch; ++k) {
+            const int u = u0 + k * blockDim.x;
+            if (u >= units) break;
+            const int cq = u % cquads, tq = u / cquads;
+            const int c = cq << 2;
+            const uint32_t sub = (uint32_t)(tq >> 2), pq = (uint32_t)(tq & 3);
+            uint8_t *dst = smem_x + sub * sub_stride<NSUB>() + lds_col_offset((uint32_t)c, pq);
+            uint2 w;  // columns c+1 .. c+3 lie 8, 16, 24 LDS rows further on
+            w.x = (a[k][0].x & 0xffffu) | (a[k][1].x << 16);
+            w.y = (a[k][2].x & 0xffffu) | (a[k][3].x << 16);
+            *reinterpret_cast<uint2 *>(dst) = w;
+            w.x = (a[k][0].x >> 16) | (a[k][1].x & 0xffff0000u);
+            w.y = (a[k][2].x >> 16) | (a[k][3].x & 0xffff0000u);
+            *reinterpret_cast<uint2 *>(dst + 8 * 32) = w;
+            w.x = (a[k][0].y & 0xffffu) | (a[k][1].y << 16);
+            w.y = (a[k][2].y & 0xffffu) | (a[k][3].y << 16);
+            *reinterpret_cast<uint2 *>(dst + 16 * 32) = w;
+            w.x = (a[k][0].y >> 16) | (a[k][1].y & 0xffff0000u);
+            w.y = (a[k][2].y >> 16) | (a[k][3].y & 0xffff0000u);
+            *reinterpret_cast<uint2 *>(dst + 24 * 32) = w;
+        }
+    }
+}
+
+// This wavefront's share of the strip: a contiguous run [b_lo, b_hi) of row-blocks holding about
+// 1 / nwaves of the strip's padded kept columns (lower bounds on the cached blk_ptr slice).
+__device__ __forceinline__ void wave_share(const int *s_ptr, int nrb, int wave, int nwaves, int &b_lo, int &b_hi) {
+    auto first_block_at = [&](int64_t target_cols) {
+        int lo = 0, hi = nrb;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (s_ptr[mid] < target_cols) lo = mid + 1; else hi = mid;
+        }
+        return lo;
+    };
+    const int64_t c_begin = s_ptr[0], c_total = (int64_t)s_ptr[nrb] - s_ptr[0];
+    b_lo = wave == 0 ? 0 : first_block_at(c_begin + c_total * wave / nwaves);
+    b_hi = wave == nwaves - 1 ? nrb : first_block_at(c_begin + c_total * (wave + 1) / nwaves);
+    b_lo = __builtin_amdgcn_readfirstlane(b_lo);
+    b_hi = __builtin_amdgcn_readfirstlane(b_hi);
+}
+
+// Per-lane output state of a wavefront: where its accumulators go and the bias of the
+// current row-block.  acc[f][u][v] = Y[t0 + 16u + l16, bR + 16f + 4G + v] before the bias.
+template <int DT, int NFRAG, int NSUB>
+struct Epilogue {
+    uint16_t *yrow[NSUB];  // Y + token row of sub-tile u + 4G
+    uint32_t tok_ok;       // bit u: the lane's token of sub-tile u is inside T
+    const void *bias;
+    int64_t M;
+    int32_t R, G;
+    bool vec4;             // 4 consecutive outputs can go out as one 8-byte store
+    float bv[NFRAG][4];
+    // Finished row-blocks wait here, converted and packed, until the 64 output features of a
+    // 128-byte line of Y are complete (4 row-blocks of 16 rows): their stores then go out back
+    // to back and the line is whole when it leaves the L2.
+    static constexpr int kPend = 4 / NFRAG;
+    uint2 pend[kPend][NFRAG][NSUB];
+    int pend_first;        // first occupied slot, -1 when empty
+
+    __device__ __forceinline__ void init(void *Y, const void *bias_, int64_t T, int64_t M_, int32_t R_, int64_t t0,
+                                         int l16, int G_) {
+        bias = bias_; M = M_; R = R_; G = G_;
+        pend_first = -1;
+        vec4 = (R & 3) == 0 && (M & 3) == 0 && (reinterpret_cast<uintptr_t>(bias) & 7) == 0;
+        tok_ok = 0;
+#pragma unroll
+        for (int u = 0; u < NSUB; ++u) {
+            const int64_t t = t0 + 16 * u + l16;
+            if (t < T) tok_ok |= 1u << u;
+            yrow[u] = (uint16_t *)Y + (t < T ? t : 0) * M + 4 * G;
+        }
+#pragma unroll
+        for (int f = 0; f < NFRAG; ++f)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) bv[f][v] = 0.0f;
+    }
+    // Issued when a row-block starts and used when it ends; unconditional loads on clamped rows,
+    // so nothing waits on them before the use.
+    __device__ __forceinline__ void load_bias(int64_t b) {
+        if (!bias) return;
+#pragma unroll
+        for (int f = 0; f < NFRAG; ++f) {
+            const int r0 = f * 16 + 4 * G;
+            if (vec4) {
+                const int rr = r0 < R ? r0 : 0;
+                const uint2 w = *reinterpret_cast<const uint2 *>((const uint16_t *)bias + b * R + rr);
+                const uint32_t h[4] = {w.x & 0xffffu, w.x >> 16, w.y & 0xffffu, w.y >> 16};
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    if constexpr (DT == BSP_BF16) bv[f][v] = __uint_as_float(h[v] << 16);
+                    else bv[f][v] = (float)__builtin_bit_cast(_Float16, (uint16_t)h[v]);
+                }
+            } else {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int rr = r0 + v < R ? r0 + v : R - 1;
+                    bv[f][v] = elem<DT>::load(bias, b * R + rr);
+                }
+            }
+        }
+    }
+    // `last`: no further row-block of this wavefront follows.
+    __device__ __forceinline__ void write_block(int64_t b, const f32x4 (&acc)[NFRAG][NSUB], bool last) {
+        if (!vec4) {
+#pragma unroll
+            for (int f = 0; f < NFRAG; ++f) {
+                const int r0 = f * 16 + 4 * G;
+                const int64_t mcol = b * R + f * 16;  // + 4G is already in yrow
+#pragma unroll
+                for (int u = 0; u < NSUB; ++u) {
+                    if (!((tok_ok >> u) & 1u)) continue;
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        if (r0 + v < R) elem<DT>::store(yrow[u], mcol + v, acc[f][u][v] + bv[f][v]);
+                }
+            }
+            return;
+        }
+        const int slot = (int)(b % kPend);
+#pragma unroll
+        for (int s = 0; s < kPend; ++s) {
+            if (s != slot) continue;  // uniform
+#pragma unroll
+            for (int f = 0; f < NFRAG; ++f)
+#pragma unroll
+                for (int u = 0; u < NSUB; ++u) {
+                    pend[s][f][u].x = cvt_pk<DT>(acc[f][u][0] + bv[f][0], acc[f][u][1] + bv[f][1]);
+                    pend[s][f][u].y = cvt_pk<DT>(acc[f][u][2] + bv[f][2], acc[f][u][3] + bv[f][3]);
+                }
+        }
+        if (pend_first < 0) pend_first = slot;
+        if (slot != kPend - 1 && !last) return;
+        const int64_t b0 = b - slot;
+#pragma unroll
+        for (int s = 0; s < kPend; ++s) {
+            if (s < pend_first || s > slot) continue;  // uniform
+#pragma unroll
+            for (int f = 0; f < NFRAG; ++f) {
+                if (f * 16 + 4 * G >= R) continue;
+                const int64_t mcol = (b0 + s) * R + f * 16;
+#pragma unroll
+                for (int u = 0; u < NSUB; ++u)
+                    if ((tok_ok >> u) & 1u) *reinterpret_cast<uint2 *>(yrow[u] + mcol) = pend[s][f][u];
+            }
+        }
+        pend_first = -1;
+    }
+};
+
+template <int NFRAG, int NSUB>
+__device__ __forceinline__ void clear_acc(f32x4 (&acc)[NFRAG][NSUB]) {
+#pragma unroll
+    for (int f = 0; f < NFRAG; ++f)
+#pragma unroll
+        for (int u = 0; u < NSUB; ++u) acc[f][u] = f32x4{0.f, 0.f, 0.f, 0.f};
+}
+
+// ---------------------------------------------------------------------------------------------
+// canonical operands
+// ---------------------------------------------------------------------------------------------
+template <int NFRAG>
+struct StepOps {       // one lane's operands of one step, as loaded (nothing is derived from the
+    uint4 a[NFRAG];    // loaded words at fetch time: a use would stall the stream on the load)
+    uint32_t c1, c2;   // the lane's two columns
+};
+
+template <int DT, int NFRAG, int NSUB>
+__global__ __launch_bounds__(1024) void linear_tiled_canonical_kernel(
+    const uint16_t *__restrict__ X, int64_t T, int64_t M, int64_t N, int32_t R, int32_t npad,
+    const int32_t *__restrict__ blk_ptr, const int32_t *__restrict__ col_idx, const uint16_t *__restrict__ vals,
+    const void *__restrict__ bias, void *__restrict__ Y, int32_t ntiles, int32_t rb_per_strip, int32_t B) {
+    __shared__ int s_ptr[kMaxStripBlocks + 1];
+    const int tile = blockIdx.x % ntiles, strip = blockIdx.x / ntiles;
+    const int64_t t0 = (int64_t)tile * (16 * NSUB);
+    const int rb0 = strip * rb_per_strip;
+    const int nrb = min(rb_per_strip, B - rb0);
+    for (int i = threadIdx.x; i <= nrb; i += blockDim.x) s_ptr[i] = blk_ptr[rb0 + i];
+    stage_x_tile<NSUB>(X, T, N, npad, t0);
+    __syncthreads();
+
+    const int lane = threadIdx.x & 63;
+    const int l16 = lane & 15, G = lane >> 4, q = (lane >> 2) & 3, p = lane & 3;
+    int b_lo, b_hi;
+    wave_share(s_ptr, nrb, __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)), blockDim.x >> 6, b_lo, b_hi);
+    if (b_lo >= b_hi) return;
+    const int gs_lo = s_ptr[b_lo] >> 5, gs_hi = s_ptr[b_hi] >> 5;
+
+    // cursor of the operand stream (which row-block the next fetched step belongs to)
+    int f_blk = b_lo, f_base = s_ptr[b_lo], f_end = s_ptr[b_lo + 1];
+    auto fetch = [&](int gs, StepOps<NFRAG> &o) {
+        while ((gs << 5) >= f_end && f_blk + 1 < nrb) {
+            ++f_blk;
+            f_base = f_end;
+            f_end = s_ptr[f_blk + 1];
+        }
+        const int kp = f_end - f_base, cpos = (gs << 5) - f_base;
+#pragma unroll
+        for (int f = 0; f < NFRAG; ++f) {
+            const int r = f * 16 + l16;
+            o.a[f] = (r < R) ? *reinterpret_cast<const uint4 *>(vals + (int64_t)R * f_base + (int64_t)r * kp + cpos + 8 * G)
+                             : make_uint4(0u, 0u, 0u, 0u);
+        }
+        o.c1 = (uint32_t)col_idx[f_base + cpos + 8 * G + q];
+        o.c2 = (uint32_t)col_idx[f_base + cpos + 8 * G + 4 + q];
+    };
+
+    Epilogue<DT, NFRAG, NSUB> ep;
+    ep.init(Y, bias, T, M, R, t0, l16, G);
+    f32x4 acc[NFRAG][NSUB];
+    clear_acc(acc);
+    ep.load_bias(rb0 + b_lo);
+    int blk = b_lo;
+    int blk_end = s_ptr[blk + 1] >> 5;  // first step index past the current row-block
+    int gs = gs_lo;
+    // finished (possibly empty) row-blocks are written as soon as the stream has passed them
+    auto pass_boundaries = [&]() {
+        while (blk < b_hi && blk_end <= gs) {
+            ep.write_block(rb0 + blk, acc, blk + 1 >= b_hi);
+            clear_acc(acc);
+            ++blk;
+            blk_end = blk < b_hi ? (s_ptr[blk + 1] >> 5) : -1;
+            if (blk < b_hi) ep.load_bias(rb0 + blk);
+        }
+    };
+    pass_boundaries();
+
+    StepOps<NFRAG> ring[kRing];
+#pragma unroll
+    for (int j = 0; j < kRing; ++j)
+        if (gs + j < gs_hi) fetch(gs + j, ring[j]);
+    while (gs < gs_hi) {
+#pragma unroll
+        for (int j = 0; j < kRing; ++j) {
+            if (gs < gs_hi) {
+                const StepOps<NFRAG> cur = ring[j];
+                if (gs + kRing < gs_hi) fetch(gs + kRing, ring[j]);
+                const uint32_t o1 = lds_col_offset(cur.c1, (uint32_t)p), o2 = lds_col_offset(cur.c2, (uint32_t)p);
+                uint4 xb[NSUB];
+#pragma unroll
+                for (int u = 0; u < NSUB; ++u) {
+                    const uint2 lo = tr_read(smem_x + u * sub_stride<NSUB>(), o1);
+                    const uint2 hi = tr_read(smem_x + u * sub_stride<NSUB>(), o2);
+                    xb[u] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+                }
+#pragma unroll
+                for (int u = 0; u < NSUB; ++u)
+#pragma unroll
+                    for (int f = 0; f < NFRAG; ++f) acc[f][u] = mfma16<DT>(cur.a[f], xb[u], acc[f][u]);
+                ++gs;
+                pass_boundaries();
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// planned operands
+// ---------------------------------------------------------------------------------------------
+template <int DT, int NFRAG, int NSUB>
+__global__ __launch_bounds__(1024) void linear_tiled_planned_kernel(
+    const uint16_t *__restrict__ X, int64_t T, int64_t M, int64_t N, int32_t R, int32_t npad,
+    const int32_t *__restrict__ blk_ptr, const uint4 *__restrict__ wfrag, const uint32_t *__restrict__ xoff,
+    const void *__restrict__ bias, void *__restrict__ Y, int32_t ntiles, int32_t rb_per_strip, int32_t B) {
+    __shared__ int s_ptr[kMaxStripBlocks + 1];
+    const int tile = blockIdx.x % ntiles, strip = blockIdx.x / ntiles;
+    const int64_t t0 = (int64_t)tile * (16 * NSUB);
+    const int rb0 = strip * rb_per_strip;
+    const int nrb = min(rb_per_strip, B - rb0);
+    for (int i = threadIdx.x; i <= nrb; i += blockDim.x) s_ptr[i] = blk_ptr[rb0 + i];
+    stage_x_tile<NSUB>(X, T, N, npad, t0);
+    __syncthreads();
+
+    const int lane = threadIdx.x & 63;
+    const int l16 = lane & 15, G = lane >> 4;
+    int b_lo, b_hi;
+    wave_share(s_ptr, nrb, __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)), blockDim.x >> 6, b_lo, b_hi);
+    if (b_lo >= b_hi) return;
+    const int gs_lo = s_ptr[b_lo] >> 5, gs_hi = s_ptr[b_hi] >> 5;
+
+    Epilogue<DT, NFRAG, NSUB> ep;
+    ep.init(Y, bias, T, M, R, t0, l16, G);
+    f32x4 acc[NFRAG][NSUB];
+    clear_acc(acc);
+    ep.load_bias(rb0 + b_lo);
+    int blk = b_lo;
+    int blk_end = s_ptr[blk + 1] >> 5;
+    int gs = gs_lo;
+    auto pass_boundaries = [&]() {
+        while (blk < b_hi && blk_end <= gs) {
+            ep.write_block(rb0 + blk, acc, blk + 1 >= b_hi);
+            clear_acc(acc);
+            ++blk;
+            blk_end = blk < b_hi ? (s_ptr[blk + 1] >> 5) : -1;
+            if (blk < b_hi) ep.load_bias(rb0 + blk);
+        }
+    };
+    pass_boundaries();
+    if (gs >= gs_hi) return;
+
+    // Per-lane operand pointers, advanced by a constant per group of kRing steps.  The stream is
+    // read up to kRing steps past the wavefront's last step: those loads stay inside the plan
+    // buffer (its size includes that slack) and their values are never used.
+    const uint4 *wp = wfrag + (int64_t)gs * (NFRAG * 64) + lane;
+    const uint32_t *xp = xoff + (int64_t)gs * 64 + lane;
+    uint4 ra[kRing][NFRAG];
+    uint32_t rx[kRing];
+#pragma unroll
+    for (int j = 0; j < kRing; ++j) {
+#pragma unroll
+        for (int f = 0; f < NFRAG; ++f) ra[j][f] = wp[(j * NFRAG + f) * 64];
+        rx[j] = xp[j * 64];
+    }
+    // X fragments of the current step (even / odd ping-pong, resolved by the unrolling)
+    uint4 xb[2][NSUB];
+    auto issue_reads = [&](uint32_t w, uint4 (&dst)[NSUB]) {
+        const uint32_t o1 = w & 0xffffu, o2 = w >> 16;
+#pragma unroll
+        for (int u = 0; u < NSUB; ++u) {
+            const uint2 lo = tr_read(smem_x + u * sub_stride<NSUB>(), o1);
+            const uint2 hi = tr_read(smem_x + u * sub_stride<NSUB>(), o2);
+            dst[u] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+        }
+    };
+    issue_reads(rx[0], xb[0]);
+
+    static_assert(kRing % 2 == 0, "the X fragment ping-pong needs an even ring");
+    for (;;) {
+#pragma unroll
+        for (int j = 0; j < kRing; ++j) {
+            // LDS reads of the next step go out before this step's MFMAs
+            issue_reads(rx[(j + 1) % kRing], xb[(j + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);  // the scheduler would otherwise sink the reads below the MFMAs
+#pragma unroll
+            for (int u = 0; u < NSUB; ++u)
+#pragma unroll
+                for (int f = 0; f < NFRAG; ++f) acc[f][u] = mfma16<DT>(ra[j][f], xb[j & 1][u], acc[f][u]);
+            __builtin_amdgcn_sched_barrier(0);
+            // refill this ring slot with step gs + kRing
+#pragma unroll
+            for (int f = 0; f < NFRAG; ++f) ra[j][f] = wp[((kRing + j) * NFRAG + f) * 64];
+            rx[j] = xp[(kRing + j) * 64];  // its old value went into the previous sub-iteration's reads
+            ++gs;
+            if (gs >= blk_end || gs >= gs_hi) {  // uniform; also ends the walk on a malformed blk_ptr
+                pass_boundaries();
+                if (gs >= gs_hi) return;
+            }
+        }
+        wp += kRing * NFRAG * 64;
+        xp += kRing * 64;
+    }
+}
+
+template <int DT, int NFRAG, int NSUB, bool PLAN>
+int launch(const TiledArgs &a, int waves, hipStream_t s) {
+    const size_t lds = (size_t)(NSUB - 1) * sub_stride<NSUB>() + (size_t)a.npad * 32;
+    const void *kern = PLAN ? (const void *)linear_tiled_planned_kernel<DT, NFRAG, NSUB>
+                            : (const void *)linear_tiled_canonical_kernel<DT, NFRAG, NSUB>;
+    static thread_local size_t configured = 0;  // per instantiation and thread: raise the dynamic LDS limit once
+    if (lds > configured) {
+        hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) {
+            set_last_hip_error((int)e);
+            return BSP_ERR_HIP;
+        }
+        configured = lds;
+    }
+    const int64_t ntiles = (a.T + 16 * NSUB - 1) / (16 * NSUB);
+    // enough strips to give every compute unit a workgroup, but never fewer than 4 row-blocks per strip
+    int64_t nstrips = (256 + ntiles - 1) / ntiles;
+    const int64_t max_strips = (a.B + 3) / 4;
+    if (nstrips > max_strips) nstrips = max_strips;
+    if (nstrips < 1) nstrips = 1;
+    int64_t rb_per_strip = (a.B + nstrips - 1) / nstrips;
+    if (rb_per_strip > kMaxStripBlocks) rb_per_strip = kMaxStripBlocks;
+    nstrips = (a.B + rb_per_strip - 1) / rb_per_strip;
+    if (ntiles * nstrips >= ((int64_t)1 << 31)) return BSP_ERR_SHAPE;
+    const dim3 grid((unsigned)(ntiles * nstrips)), block((unsigned)(waves * 64));
+    if constexpr (PLAN)
+        linear_tiled_planned_kernel<DT, NFRAG, NSUB><<<grid, block, lds, s>>>(
+            a.X, a.T, a.M, a.N, a.R, a.npad, a.blk_ptr, (const uint4 *)a.wfrag, a.xoff, a.bias, a.Y, (int32_t)ntiles,
+            (int32_t)rb_per_strip, (int32_t)a.B);
+    else
+        linear_tiled_canonical_kernel<DT, NFRAG, NSUB><<<grid, block, lds, s>>>(
+            a.X, a.T, a.M, a.N, a.R, a.npad, a.blk_ptr, a.col_idx, a.vals, a.bias, a.Y, (int32_t)ntiles,
+            (int32_t)rb_per_strip, (int32_t)a.B);
+    return check_launch();
+}
+
+template <int DT, int NFRAG, bool PLAN>
+int launch_nsub(const TiledArgs &a, int waves, hipStream_t s) {
+    if (a.npad <= 1024) return launch<DT, NFRAG, 4, PLAN>(a, waves, s);
+    return launch<DT, NFRAG, 2, PLAN>(a, waves, s);
+}
+
+template <int DT, bool PLAN>
+int launch_nfrag(const TiledArgs &a, int waves, hipStream_t s) {
+    if (a.R <= 16) return launch_nsub<DT, 1, PLAN>(a, waves, s);
+    if (a.R <= 32) return launch_nsub<DT, 2, PLAN>(a, waves, s);
+    return launch_nsub<DT, 4, PLAN>(a, waves, s);
+}
+
+}  // namespace
+
+static int g_tiled_waves = 16;
+void set_tiled_waves(int w) { g_tiled_waves = (w == 4 || w == 8 || w == 16) ? w : 16; }
+
+int plan_slack_steps() { return kRing; }
+
+bool tiled_supported(int xdt, int64_t N, int32_t k_align) {
+    if (xdt != BSP_BF16 && xdt != BSP_F16) return false;
+    if (k_align % 32 != 0 || N < 32 || N % 8 != 0) return false;
+    const int64_t npad = (N + 255) / 256 * 256;
+    return npad <= 2048;  // LDS byte offsets inside a sub-tile are 16-bit
+}
+
+int launch_linear_tiled(const TiledArgs &args, bool plan, hipStream_t s) {
+    TiledArgs a = args;
+    a.npad = (int32_t)((a.N + 255) / 256 * 256);
+    if (a.xdt == BSP_BF16)
+        return plan ? launch_nfrag<BSP_BF16, true>(a, g_tiled_waves, s) : launch_nfrag<BSP_BF16, false>(a, g_tiled_waves, s);
+    return plan ? launch_nfrag<BSP_F16, true>(a, g_tiled_waves, s) : launch_nfrag<BSP_F16, false>(a, g_tiled_waves, s);
+}
+
+}  // namespace bsp

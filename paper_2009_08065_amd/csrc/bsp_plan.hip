@@ -1,0 +1,197 @@
+// Derived operand buffer ("plan") for the tiled layer kernel, built from the compact storage.
+//
+// The contraction order inside a row-block is free, so the kept columns are re-ordered for
+// the LDS gather: the tiled kernel fetches an X fragment with two transposing reads, and in
+// each of them a half-wavefront touches 8 columns (8 rows of 32 bytes = all 64 LDS banks when
+// the rows fall into 8 different bank groups).  The kept columns of a row-block are dealt into
+// sets of 8, one column per bank group where the counts allow; columns of over-full groups and
+// zero-weight pads fill the gaps.  Per 32-column step the plan stores, ready to load per lane,
+// the value-panel fragments (16 rows x 32 columns, 16 bytes per lane) and the two 16-bit LDS
+// byte offsets of the lane's transposing reads.  Integer work only; deterministic.
+#include "bsp_common.h"
+#include "bsp_linear_internal.h"
+
+namespace bsp {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kMaxKp = 2048 + 32;
+
+__device__ __forceinline__ int slot_index(int set, int group) {
+    // sets 4s .. 4s+3 of step s are what {first, second} read x {lower, upper} half-wavefront touch
+    return 32 * (set >> 2) + ((set >> 1) & 1) * 16 + (set & 1) * 4 + (group >> 2) * 8 + (group & 3);
+}
+
+__global__ __launch_bounds__(kThreads) void plan_kernel(int32_t R, int32_t nfrag, const int32_t *__restrict__ blk_cnt,
+                                                        const int32_t *__restrict__ blk_ptr,
+                                                        const int32_t *__restrict__ col_idx,
+                                                        const uint16_t *__restrict__ vals, int64_t capacity_cols,
+                                                        int32_t slack_steps, uint4 *__restrict__ wfrag,
+                                                        uint32_t *__restrict__ xoff) {
+    __shared__ int32_t slotcol[kMaxKp], slotsrc[kMaxKp], ovfcol[kMaxKp], ovfsrc[kMaxKp];
+    __shared__ int s_filled[8], s_hp[9], s_novf;
+    const int64_t b = blockIdx.x;
+    const int base = blk_ptr[b];
+    const int kp = blk_ptr[b + 1] - base;
+    const int kb = blk_cnt[b];
+    if (b == gridDim.x - 1) {
+        // the layer kernel reads a few steps past the end of the storage: give those steps the
+        // LDS offset 0 (their values are never used, but the addresses must be valid)
+        const int64_t total_steps = (int64_t)blk_ptr[b + 1] >> 5;
+        if (total_steps >= 0 && (total_steps << 5) <= capacity_cols)
+            for (int i = threadIdx.x; i < slack_steps * 64; i += kThreads) xoff[total_steps * 64 + i] = 0u;
+    }
+    if (kp <= 0 || kp > kMaxKp || (kp & 31) || kb > kp || kb < 0 || (int64_t)base + kp > capacity_cols) return;
+    const int S = kp >> 3;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+
+    if (wave == 0) {
+        int cnt[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        int novf = 0;
+        const uint64_t lt = (1ull << lane) - 1ull;
+        for (int i0 = 0; i0 < kb; i0 += 64) {
+            const int i = i0 + lane;
+            const bool valid = i < kb;
+            const int col = valid ? col_idx[base + i] : 0;
+            const int g = (int)lds_bank_group((uint32_t)col);
+            int rank = 0;
+#pragma unroll
+            for (int gg = 0; gg < 8; ++gg) {
+                const uint64_t m = __ballot(valid && g == gg);
+                if (g == gg) rank = cnt[gg] + __popcll(m & lt);
+                cnt[gg] += __popcll(m);
+            }
+            const bool over = valid && rank >= S;
+            const uint64_t mo = __ballot(over);
+            if (valid && !over) {
+                const int slot = slot_index(rank, g);
+                slotcol[slot] = col;
+                slotsrc[slot] = i;
+            } else if (over) {
+                const int oi = novf + __popcll(mo & lt);
+                ovfcol[oi] = col;
+                ovfsrc[oi] = i;
+            }
+            novf += __popcll(mo);
+        }
+        if (lane == 0) {
+            int run = 0;
+            for (int g = 0; g < 8; ++g) {
+                const int f = cnt[g] < S ? cnt[g] : S;
+                s_filled[g] = f;
+                s_hp[g] = run;
+                run += S - f;
+            }
+            s_hp[8] = run;
+            s_novf = novf;
+        }
+    }
+    __syncthreads();
+    // gaps: group g lacks a column in sets filled[g] .. S-1; gap e takes overflow column e, else a zero pad
+    const int H = s_hp[8], novf = s_novf;
+    for (int e = threadIdx.x; e < H; e += kThreads) {
+        int g = 0;
+#pragma unroll
+        for (int gg = 1; gg < 8; ++gg)
+            if (s_hp[gg] <= e) g = gg;
+        const int set = s_filled[g] + (e - s_hp[g]);
+        const int slot = slot_index(set, g);
+        if (e < novf) {
+            slotcol[slot] = ovfcol[e];
+            slotsrc[slot] = ovfsrc[e];
+        } else {
+            slotcol[slot] = g << 2;  // any column of bank group g; its weight is zero
+            slotsrc[slot] = -1;
+        }
+    }
+    __syncthreads();
+    // per-lane operands of every step
+    const int l16 = lane & 15, G = lane >> 4, q = (lane >> 2) & 3, p = lane & 3;
+    const int nsteps = kp >> 5;
+    const int64_t gs0 = base >> 5;
+    for (int s = wave; s < nsteps; s += kThreads / 64) {
+        const int s1 = 32 * s + 8 * G + q;
+        const uint32_t o1 = lds_col_offset((uint32_t)slotcol[s1], (uint32_t)p);
+        const uint32_t o2 = lds_col_offset((uint32_t)slotcol[s1 + 4], (uint32_t)p);
+        xoff[(gs0 + s) * 64 + lane] = o1 | (o2 << 16);
+        for (int f = 0; f < nfrag; ++f) {
+            const int r = f * 16 + l16;
+            uint32_t w[4] = {0u, 0u, 0u, 0u};
+            if (r < R) {
+                const uint16_t *row = vals + (int64_t)R * base + (int64_t)r * kp;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const int src = slotsrc[32 * s + 8 * G + i];
+                    const uint32_t v = src >= 0 ? (uint32_t)row[src] : 0u;
+                    w[i >> 1] |= v << (16 * (i & 1));
+                }
+            }
+            wfrag[((gs0 + s) * nfrag + f) * 64 + lane] = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+    }
+}
+
+inline int nfrag_of(int32_t R) { return R <= 16 ? 1 : (R <= 32 ? 2 : 4); }
+// Steps the plan buffer holds: those of capacity_cols columns plus the read-ahead slack.
+inline size_t plan_steps(int64_t capacity_cols) { return (size_t)((capacity_cols + 31) / 32) + (size_t)plan_slack_steps(); }
+
+}  // namespace
+}  // namespace bsp
+
+using namespace bsp;
+
+extern "C" int bsp_linear_plan_supported(int xdt, int64_t N, int32_t k_align) {
+    return tiled_supported(xdt, N, k_align) ? 1 : 0;
+}
+
+extern "C" size_t bsp_linear_plan_bytes(int32_t R, int64_t capacity_cols) {
+    if (R < 1 || R > 64 || capacity_cols <= 0) return 0;
+    return plan_steps(capacity_cols) * ((size_t)nfrag_of(R) * 1024 + 256);
+}
+
+extern "C" int bsp_linear_plan(int vdt, int64_t M, int64_t N, int32_t R, int32_t k_align, const int32_t *blk_cnt,
+                               const int32_t *blk_ptr, const int32_t *col_idx, const void *vals,
+                               int64_t capacity_cols, void *plan, size_t plan_bytes, void *stream) {
+    if (!blk_cnt || !blk_ptr) return BSP_ERR_NULL;
+    if (M <= 0 || N <= 0 || R < 1 || R > 64 || M % R != 0) return BSP_ERR_SHAPE;
+    if (!tiled_supported(vdt, N, k_align)) return BSP_ERR_SHAPE;
+    if (capacity_cols < 0) return BSP_ERR_CAPACITY;
+    if (capacity_cols == 0) return BSP_OK;
+    if (!col_idx || !vals || !plan) return BSP_ERR_NULL;
+    if (plan_bytes < bsp_linear_plan_bytes(R, capacity_cols) || !aligned(plan, 16)) return BSP_ERR_CAPACITY;
+    const int64_t B = M / R;
+    const size_t steps = plan_steps(capacity_cols);
+    const int nf = nfrag_of(R);
+    uint4 *wfrag = (uint4 *)plan;
+    uint32_t *xoff = (uint32_t *)((uint8_t *)plan + steps * (size_t)nf * 1024);
+    plan_kernel<<<(unsigned)B, kThreads, 0, (hipStream_t)stream>>>(R, nf, blk_cnt, blk_ptr, col_idx,
+                                                                            (const uint16_t *)vals, capacity_cols,
+                                                               plan_slack_steps(), wfrag, xoff);
+    return check_launch();
+}
+
+extern "C" int bsp_linear_planned(const void *X, int xdt, int64_t T, int64_t M, int64_t N, int32_t R, int32_t k_align,
+                                  const int32_t *blk_ptr, const void *plan, int64_t capacity_cols, const void *bias,
+                                  void *Y, void *stream) {
+    if (!X || !blk_ptr || !Y) return BSP_ERR_NULL;
+    if (T < 0 || M <= 0 || N <= 0 || R < 1 || R > 64 || M % R != 0) return BSP_ERR_SHAPE;
+    if (!tiled_supported(xdt, N, k_align)) return BSP_ERR_SHAPE;
+    if (capacity_cols < 0) return BSP_ERR_CAPACITY;
+    if (capacity_cols > 0 && !plan) return BSP_ERR_NULL;
+    if (!aligned(X, 16) || !aligned(Y, 16) || !aligned(plan, 16)) return BSP_ERR_SHAPE;
+    if (T == 0) return BSP_OK;
+    const size_t steps = plan_steps(capacity_cols);
+    TiledArgs a{};
+    a.xdt = xdt;
+    a.X = (const uint16_t *)X;
+    a.T = T; a.M = M; a.N = N; a.B = M / R; a.R = R;
+    a.blk_ptr = blk_ptr;
+    a.wfrag = plan;
+    a.xoff = (const uint32_t *)((const uint8_t *)plan + steps * (size_t)nfrag_of(R) * 1024);
+    a.bias = bias;
+    a.Y = Y;
+    return launch_linear_tiled(a, true, (hipStream_t)stream);
+}
+
+// Experiment hook (not part of the documented ABI): wavefronts per workgroup of the tiled kernel.
+extern "C" void bsp_debug_set_tiled_waves(int waves) { set_tiled_waves(waves); }

@@ -194,7 +194,17 @@ def run_layer(X, W, bias, R, keep, k_align, dtype, T_rows=None):
     Xd, bd = dev(X, dtype), dev(bias, dtype)
     p = bsp.bsp_pack(dev(W, dtype), R, torch.from_numpy(np.ascontiguousarray(keep)).cuda(), k_align)
     pack_equal(p, p_ref)
+    check = lambda y: _check_y(y, X, p_ref, bias, code, dtype, T_rows)
     Y = host(bsp.bsp_linear(Xd, p, bd))
+    if k_align % 32 == 0 and bsp.bsp_linear_plan_supported(TDT[dtype], X.shape[1], k_align):
+        # the planned path computes the same sums from a re-ordered copy of the storage
+        Yp = host(bsp.bsp_linear_planned(Xd, p, bsp.bsp_linear_plan(p), bd))
+        check(Yp)
+    check(Y)
+    return Y, p
+
+
+def _check_y(Y, X, p_ref, bias, code, dtype, T_rows):
     if T_rows is None:
         Y_ref, _ = orc.linear_packed(X, p_ref, bias, ydt=code, n_threads=8)
         assert_y_close(Y, Y_ref, dtype)
@@ -202,7 +212,6 @@ def run_layer(X, W, bias, R, keep, k_align, dtype, T_rows=None):
         for (t0, t1) in T_rows:
             Y_ref, _ = orc.linear_packed(X, p_ref, bias, ydt=code, t0=t0, t1=t1, n_threads=8)
             assert_y_close(Y, Y_ref, dtype, rows=slice(t0, t1))
-    return Y, p
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
