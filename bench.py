@@ -63,7 +63,7 @@ class Matrix:
         self.use_plan = path == "planned" and bsp.bsp_linear_plan_supported(torch.bfloat16, self.N, k_align)
         self.plan = None
         if self.use_plan:
-            self.plan = torch.empty(bsp.lib().bsp_linear_plan_bytes(self.R, self.capacity), dtype=torch.uint8,
+            self.plan = torch.empty(bsp.lib().bsp_linear_plan_bytes(self.M, self.R, self.capacity), dtype=torch.uint8,
                                     device=dev)
 
     def prune_and_pack(self, lam=1e-4, eps=1e-6):

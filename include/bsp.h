@@ -134,22 +134,22 @@ int bsp_linear(const void *X, int xdt, int64_t T, int64_t M, int64_t N, int32_t 
  * row-block is free, so it is chosen for the hardware) ---------------------------------------
  * bsp_linear_plan builds, from a compact storage with k_align = 32 or 64 and 16-bit values, a
  * buffer in which the kept columns of each row-block are re-ordered for conflict-free LDS
- * gathers and every lane's matrix-core operands lie ready to load.  bsp_linear_planned
- * computes exactly what bsp_linear computes (same sums, different order of the additions)
- * from that buffer; it needs blk_ptr but neither col_idx nor vals.
+ * gathers, the row-blocks are laid out in the order the kernel's wavefronts visit them, and
+ * every lane's matrix-core operands lie ready to load.  bsp_linear_planned computes exactly
+ * what bsp_linear computes (same sums, different order of the additions) from that buffer
+ * alone; it needs neither blk_ptr, col_idx nor vals.
  * bsp_linear_plan_supported: 1 when (xdt, N, k_align) can be planned (bf16 / fp16,
- * 32 <= N <= 2048, N % 8 == 0, k_align % 32 == 0), else 0; the other two calls return
+ * 32 <= N <= 4096, N % 8 == 0, k_align % 32 == 0), else 0; the other calls return
  * BSP_ERR_SHAPE for an unsupported layer and the caller stays with bsp_linear.
- * plan: device buffer of at least bsp_linear_plan_bytes(R, capacity_cols) bytes, 16-byte
+ * plan: device buffer of at least bsp_linear_plan_bytes(M, R, capacity_cols) bytes, 16-byte
  * aligned, where capacity_cols >= blk_ptr[B] is the same value in all three calls. */
 int bsp_linear_plan_supported(int xdt, int64_t N, int32_t k_align);
-size_t bsp_linear_plan_bytes(int32_t R, int64_t capacity_cols);
+size_t bsp_linear_plan_bytes(int64_t M, int32_t R, int64_t capacity_cols);
 int bsp_linear_plan(int vdt, int64_t M, int64_t N, int32_t R, int32_t k_align, const int32_t *blk_cnt,
                     const int32_t *blk_ptr, const int32_t *col_idx, const void *vals, int64_t capacity_cols,
                     void *plan, size_t plan_bytes, void *stream);
 int bsp_linear_planned(const void *X, int xdt, int64_t T, int64_t M, int64_t N, int32_t R, int32_t k_align,
-                       const int32_t *blk_ptr, const void *plan, int64_t capacity_cols, const void *bias, void *Y,
-                       void *stream);
+                       const void *plan, int64_t capacity_cols, const void *bias, void *Y, void *stream);
 
 /* ---- helpers (host only) -------------------------------------------------------------- */
 /* dense parameters / kept parameters = M*N / (R * kept_cols_total) (Sec. 4.4: 1.428x <=> 30 % sparsity) */

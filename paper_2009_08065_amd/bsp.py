@@ -59,10 +59,10 @@ def lib():
     L.bsp_linear.argtypes = [vp, C.c_int, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp, vp, vp]
     L.bsp_linear_plan_supported.argtypes = [C.c_int, i64, i32]
     L.bsp_linear_plan_supported.restype = C.c_int
-    L.bsp_linear_plan_bytes.argtypes = [i32, i64]
+    L.bsp_linear_plan_bytes.argtypes = [i64, i32, i64]
     L.bsp_linear_plan_bytes.restype = sz
     L.bsp_linear_plan.argtypes = [C.c_int, i64, i64, i32, i32, vp, vp, vp, vp, i64, vp, sz, vp]
-    L.bsp_linear_planned.argtypes = [vp, C.c_int, i64, i64, i64, i32, i32, vp, vp, i64, vp, vp, vp]
+    L.bsp_linear_planned.argtypes = [vp, C.c_int, i64, i64, i64, i32, i32, vp, i64, vp, vp, vp]
     L.bsp_compression_rate.argtypes = [i64, i64, i32, i64]
     L.bsp_compression_rate.restype = C.c_double
     L.bsp_status_string.argtypes = [C.c_int]
@@ -228,7 +228,7 @@ def bsp_linear_plan_supported(dtype, N, k_align) -> bool:
 
 def bsp_linear_plan(p: Packed, plan=None):
     """Build the derived operand buffer of a compact storage.  Returns a uint8 GPU tensor."""
-    need = lib().bsp_linear_plan_bytes(p.R, max(p.total_cols, 1))
+    need = lib().bsp_linear_plan_bytes(p.M, p.R, p.total_cols)
     if plan is None:
         plan = torch.empty(max(need, 16), dtype=torch.uint8, device=p.blk_ptr.device)
     has = p.total_cols > 0
@@ -247,7 +247,7 @@ def bsp_linear_planned(X, p: Packed, plan, bias=None, Y=None):
         raise ValueError("X and bias must share one dtype")
     if Y is None:
         Y = torch.empty((T, p.M), dtype=X.dtype, device=X.device)
-    st = lib().bsp_linear_planned(_ptr(X), _DT[X.dtype], T, p.M, N, p.R, p.k_align, _ptr(p.blk_ptr), _ptr(plan),
+    st = lib().bsp_linear_planned(_ptr(X), _DT[X.dtype], T, p.M, N, p.R, p.k_align, _ptr(plan),
                                   p.total_cols, _ptr(bias), _ptr(Y), _stream())
     _check(st, "bsp_linear_planned")
     return Y

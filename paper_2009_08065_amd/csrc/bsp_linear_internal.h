@@ -5,6 +5,8 @@
 
 namespace bsp {
 
+constexpr int kPlanWaves = 8;  // wavefronts per workgroup of the planned kernel = streams of a plan
+
 struct TiledArgs {
     int xdt;
     const uint16_t *X;
@@ -14,6 +16,7 @@ struct TiledArgs {
     const int32_t *blk_ptr;
     const int32_t *col_idx;   // canonical source
     const uint16_t *vals;     // canonical source
+    const int32_t *wptr;      // planned source: [kPlanWaves][NG + 1] first step of block kPlanWaves * g + w in wavefront w's stream
     const void *wfrag;        // planned source: [step][fragment][lane] 16-byte panel fragments
     const uint32_t *xoff;     // planned source: [step][lane] two 16-bit LDS byte offsets
     const void *bias;

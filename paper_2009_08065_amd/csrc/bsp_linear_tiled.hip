@@ -41,7 +41,10 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
 constexpr int kMaxStripBlocks = 1024;  // row-blocks per strip (their blk_ptr slice is cached in LDS)
-constexpr int kRing = 4;               // steps of operands in flight per wavefront
+constexpr int kRing = 4;               // steps of operands in flight per wavefront, canonical kernel
+constexpr int kPlanRing = 16;          // the same for the planned kernel: 8 wavefronts x 16 steps x 1.25 KiB
+                                       // in flight per compute unit cover the L2 latency of the operand stream
+constexpr int kMaxStripGroups = 128;   // groups of kPlanWaves row-blocks per strip of the planned kernel
 
 // Distance in LDS between the 16-token sub-tiles of a workgroup's X tile: a constant, so that
 // sub-tile offsets fold into the immediate field of the LDS instructions.
@@ -151,17 +154,10 @@ struct Epilogue {
     int32_t R, G;
     bool vec4;             // 4 consecutive outputs can go out as one 8-byte store
     float bv[NFRAG][4];
-    // Finished row-blocks wait here, converted and packed, until the 64 output features of a
-    // 128-byte line of Y are complete (4 row-blocks of 16 rows): their stores then go out back
-    // to back and the line is whole when it leaves the L2.
-    static constexpr int kPend = 4 / NFRAG;
-    uint2 pend[kPend][NFRAG][NSUB];
-    int pend_first;        // first occupied slot, -1 when empty
 
     __device__ __forceinline__ void init(void *Y, const void *bias_, int64_t T, int64_t M_, int32_t R_, int64_t t0,
                                          int l16, int G_) {
         bias = bias_; M = M_; R = R_; G = G_;
-        pend_first = -1;
         vec4 = (R & 3) == 0 && (M & 3) == 0 && (reinterpret_cast<uintptr_t>(bias) & 7) == 0;
         tok_ok = 0;
 #pragma unroll
@@ -200,51 +196,27 @@ struct Epilogue {
             }
         }
     }
-    // `last`: no further row-block of this wavefront follows.
-    __device__ __forceinline__ void write_block(int64_t b, const f32x4 (&acc)[NFRAG][NSUB], bool last) {
-        if (!vec4) {
+    __device__ __forceinline__ void write_block(int64_t b, const f32x4 (&acc)[NFRAG][NSUB]) {
 #pragma unroll
-            for (int f = 0; f < NFRAG; ++f) {
-                const int r0 = f * 16 + 4 * G;
-                const int64_t mcol = b * R + f * 16;  // + 4G is already in yrow
+        for (int f = 0; f < NFRAG; ++f) {
+            const int r0 = f * 16 + 4 * G;
+            if (r0 >= R) continue;
+            const int64_t mcol = b * R + f * 16;  // + 4G is already in yrow
 #pragma unroll
-                for (int u = 0; u < NSUB; ++u) {
-                    if (!((tok_ok >> u) & 1u)) continue;
+            for (int u = 0; u < NSUB; ++u) {
+                if (!((tok_ok >> u) & 1u)) continue;
+                if (vec4) {
+                    uint2 o;
+                    o.x = cvt_pk<DT>(acc[f][u][0] + bv[f][0], acc[f][u][1] + bv[f][1]);
+                    o.y = cvt_pk<DT>(acc[f][u][2] + bv[f][2], acc[f][u][3] + bv[f][3]);
+                    *reinterpret_cast<uint2 *>(yrow[u] + mcol) = o;
+                } else {
 #pragma unroll
                     for (int v = 0; v < 4; ++v)
                         if (r0 + v < R) elem<DT>::store(yrow[u], mcol + v, acc[f][u][v] + bv[f][v]);
                 }
             }
-            return;
         }
-        const int slot = (int)(b % kPend);
-#pragma unroll
-        for (int s = 0; s < kPend; ++s) {
-            if (s != slot) continue;  // uniform
-#pragma unroll
-            for (int f = 0; f < NFRAG; ++f)
-#pragma unroll
-                for (int u = 0; u < NSUB; ++u) {
-                    pend[s][f][u].x = cvt_pk<DT>(acc[f][u][0] + bv[f][0], acc[f][u][1] + bv[f][1]);
-                    pend[s][f][u].y = cvt_pk<DT>(acc[f][u][2] + bv[f][2], acc[f][u][3] + bv[f][3]);
-                }
-        }
-        if (pend_first < 0) pend_first = slot;
-        if (slot != kPend - 1 && !last) return;
-        const int64_t b0 = b - slot;
-#pragma unroll
-        for (int s = 0; s < kPend; ++s) {
-            if (s < pend_first || s > slot) continue;  // uniform
-#pragma unroll
-            for (int f = 0; f < NFRAG; ++f) {
-                if (f * 16 + 4 * G >= R) continue;
-                const int64_t mcol = (b0 + s) * R + f * 16;
-#pragma unroll
-                for (int u = 0; u < NSUB; ++u)
-                    if ((tok_ok >> u) & 1u) *reinterpret_cast<uint2 *>(yrow[u] + mcol) = pend[s][f][u];
-            }
-        }
-        pend_first = -1;
     }
 };
 
@@ -316,7 +288,7 @@ __global__ __launch_bounds__(1024) void linear_tiled_canonical_kernel(
     // finished (possibly empty) row-blocks are written as soon as the stream has passed them
     auto pass_boundaries = [&]() {
         while (blk < b_hi && blk_end <= gs) {
-            ep.write_block(rb0 + blk, acc, blk + 1 >= b_hi);
+            ep.write_block(rb0 + blk, acc);
             clear_acc(acc);
             ++blk;
             blk_end = blk < b_hi ? (s_ptr[blk + 1] >> 5) : -1;
@@ -357,64 +329,45 @@ __global__ __launch_bounds__(1024) void linear_tiled_canonical_kernel(
 // ---------------------------------------------------------------------------------------------
 // planned operands
 // ---------------------------------------------------------------------------------------------
+// Row-blocks are dealt to the kPlanWaves wavefronts of a workgroup round-robin (wavefront w owns
+// blocks w, w + kPlanWaves, ...; a "group" g is kPlanWaves consecutive blocks).  The wavefronts advance nearly in
+// lockstep, so at any time they work on neighbouring row-blocks, and the 32-byte pieces that
+// four neighbouring row-blocks contribute to one 128-byte line of Y reach the L2 close together
+// and leave it as a whole line.  The plan stores the steps in exactly that order: all steps of
+// wavefront w, group after group, are contiguous, so a wavefront streams its operands with
+// constant address increments; wptr[w][g] is the step index where block 16g + w starts.
 template <int DT, int NFRAG, int NSUB>
-__global__ __launch_bounds__(1024) void linear_tiled_planned_kernel(
+__global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
     const uint16_t *__restrict__ X, int64_t T, int64_t M, int64_t N, int32_t R, int32_t npad,
-    const int32_t *__restrict__ blk_ptr, const uint4 *__restrict__ wfrag, const uint32_t *__restrict__ xoff,
-    const void *__restrict__ bias, void *__restrict__ Y, int32_t ntiles, int32_t rb_per_strip, int32_t B) {
-    __shared__ int s_ptr[kMaxStripBlocks + 1];
+    const int32_t *__restrict__ wptr, const uint32_t *__restrict__ wfrag, const uint32_t *__restrict__ xoff,
+    const void *__restrict__ bias, void *__restrict__ Y, int32_t ntiles, int32_t groups_per_strip, int32_t NG,
+    int32_t B) {
+    constexpr int RING = kPlanRing / NFRAG;  // the same bytes in flight for every fragment count
+    __shared__ int s_w[kPlanWaves][kMaxStripGroups + 1];
     const int tile = blockIdx.x % ntiles, strip = blockIdx.x / ntiles;
     const int64_t t0 = (int64_t)tile * (16 * NSUB);
-    const int rb0 = strip * rb_per_strip;
-    const int nrb = min(rb_per_strip, B - rb0);
-    for (int i = threadIdx.x; i <= nrb; i += blockDim.x) s_ptr[i] = blk_ptr[rb0 + i];
+    const int g0 = strip * groups_per_strip;
+    const int ng = min(groups_per_strip, NG - g0);
+    for (int i = threadIdx.x; i < kPlanWaves * (ng + 1); i += blockDim.x) {
+        const int w = i / (ng + 1), k = i % (ng + 1);
+        s_w[w][k] = wptr[w * (NG + 1) + g0 + k];
+    }
     stage_x_tile<NSUB>(X, T, N, npad, t0);
     __syncthreads();
 
     const int lane = threadIdx.x & 63;
     const int l16 = lane & 15, G = lane >> 4;
-    int b_lo, b_hi;
-    wave_share(s_ptr, nrb, __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)), blockDim.x >> 6, b_lo, b_hi);
-    if (b_lo >= b_hi) return;
-    const int gs_lo = s_ptr[b_lo] >> 5, gs_hi = s_ptr[b_hi] >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int *my = s_w[wave];
 
     Epilogue<DT, NFRAG, NSUB> ep;
     ep.init(Y, bias, T, M, R, t0, l16, G);
     f32x4 acc[NFRAG][NSUB];
-    clear_acc(acc);
-    ep.load_bias(rb0 + b_lo);
-    int blk = b_lo;
-    int blk_end = s_ptr[blk + 1] >> 5;
-    int gs = gs_lo;
-    auto pass_boundaries = [&]() {
-        while (blk < b_hi && blk_end <= gs) {
-            ep.write_block(rb0 + blk, acc, blk + 1 >= b_hi);
-            clear_acc(acc);
-            ++blk;
-            blk_end = blk < b_hi ? (s_ptr[blk + 1] >> 5) : -1;
-            if (blk < b_hi) ep.load_bias(rb0 + blk);
-        }
-    };
-    pass_boundaries();
-    if (gs >= gs_hi) return;
-
-    // Per-lane operand pointers, advanced by a constant per group of kRing steps.  The stream is
-    // read up to kRing steps past the wavefront's last step: those loads stay inside the plan
-    // buffer (its size includes that slack) and their values are never used.
-    const uint4 *wp = wfrag + (int64_t)gs * (NFRAG * 64) + lane;
-    const uint32_t *xp = xoff + (int64_t)gs * 64 + lane;
-    uint4 ra[kRing][NFRAG];
-    uint32_t rx[kRing];
-#pragma unroll
-    for (int j = 0; j < kRing; ++j) {
-#pragma unroll
-        for (int f = 0; f < NFRAG; ++f) ra[j][f] = wp[(j * NFRAG + f) * 64];
-        rx[j] = xp[j * 64];
-    }
-    // X fragments of the current step (even / odd ping-pong, resolved by the unrolling)
-    uint4 xb[2][NSUB];
+    uint4 ra[RING][NFRAG];
+    uint32_t rx[RING];
+    uint4 xb[2][NSUB];  // X fragments of the current step (even / odd ping-pong, resolved by the unrolling)
     auto issue_reads = [&](uint32_t w, uint4 (&dst)[NSUB]) {
-        const uint32_t o1 = w & 0xffffu, o2 = w >> 16;
+        const uint32_t o1 = (w & 0xffffu) << 3, o2 = (w >> 13) & 0x7fff8u;  // packed in units of 8 bytes
 #pragma unroll
         for (int u = 0; u < NSUB; ++u) {
             const uint2 lo = tr_read(smem_x + u * sub_stride<NSUB>(), o1);
@@ -422,75 +375,139 @@ __global__ __launch_bounds__(1024) void linear_tiled_planned_kernel(
             dst[u] = make_uint4(lo.x, lo.y, hi.x, hi.y);
         }
     };
-    issue_reads(rx[0], xb[0]);
+    static_assert(RING % 2 == 0, "the X fragment ping-pong needs an even ring");
 
-    static_assert(kRing % 2 == 0, "the X fragment ping-pong needs an even ring");
-    for (;;) {
-#pragma unroll
-        for (int j = 0; j < kRing; ++j) {
-            // LDS reads of the next step go out before this step's MFMAs
-            issue_reads(rx[(j + 1) % kRing], xb[(j + 1) & 1]);
-            __builtin_amdgcn_sched_barrier(0);  // the scheduler would otherwise sink the reads below the MFMAs
-#pragma unroll
-            for (int u = 0; u < NSUB; ++u)
-#pragma unroll
-                for (int f = 0; f < NFRAG; ++f) acc[f][u] = mfma16<DT>(ra[j][f], xb[j & 1][u], acc[f][u]);
-            __builtin_amdgcn_sched_barrier(0);
-            // refill this ring slot with step gs + kRing
-#pragma unroll
-            for (int f = 0; f < NFRAG; ++f) ra[j][f] = wp[((kRing + j) * NFRAG + f) * 64];
-            rx[j] = xp[(kRing + j) * 64];  // its old value went into the previous sub-iteration's reads
-            ++gs;
-            if (gs >= blk_end || gs >= gs_hi) {  // uniform; also ends the walk on a malformed blk_ptr
-                pass_boundaries();
-                if (gs >= gs_hi) return;
+    // Workgroups that share an L2 (blockIdx.x mod 8 picks the XCD) walk the strip's groups from
+    // different starting points, so that they do not all pull the same plan lines at the same time:
+    // groups [rot, ng) first, then [0, rot).
+    const int rot = ng > 1 ? ((tile >> 3) + strip) % ng : 0;
+    for (int seg = 0; seg < 2; ++seg) {
+        const int ga = seg == 0 ? rot : 0, gb = seg == 0 ? ng : rot;
+        if (ga >= gb) continue;
+        const int gs_hi = __builtin_amdgcn_readfirstlane(my[gb]);
+        int gs = __builtin_amdgcn_readfirstlane(my[ga]);
+        int grp = ga;                      // current group; its block is 16 (g0 + grp) + wave
+        int64_t blk = (int64_t)kPlanWaves * (g0 + ga) + wave;
+        int blk_end = __builtin_amdgcn_readfirstlane(my[ga + 1]);  // first step index past the current block
+        clear_acc(acc);
+        if (blk < B) ep.load_bias(blk);
+        // finished (possibly empty) row-blocks are written as soon as the stream has passed them
+        auto pass_boundaries = [&]() {
+            while (grp < gb && blk_end <= gs) {
+                if (blk < B) ep.write_block(blk, acc);
+                clear_acc(acc);
+                ++grp;
+                blk += kPlanWaves;
+                blk_end = grp < gb ? __builtin_amdgcn_readfirstlane(my[grp + 1]) : -1;
+                if (grp < gb && blk < B) ep.load_bias(blk);
             }
+        };
+        pass_boundaries();
+        if (gs >= gs_hi) continue;
+
+        // Per-lane operand pointers, advanced by a constant per RING steps.  The stream is read up
+        // to RING steps past the segment's last step: those loads stay inside the plan buffer (its
+        // size includes that slack) and their values are never used.
+        // A fragment is stored as 4 planes of 64 dwords (dword k of every lane's 16 bytes together): a
+        // 4-byte-per-lane load moves 256 contiguous bytes, the access width the vector memory
+        // pipeline sustains best on this hardware (about 1.6x the bytes per clock of 16-byte loads).
+        const uint32_t *wp = wfrag + (int64_t)gs * (NFRAG * 256) + lane;
+        const uint32_t *xp = xoff + (int64_t)gs * 64 + lane;
+        auto load_frag = [&](const uint32_t *q) { return make_uint4(q[0], q[64], q[128], q[192]); };
+#pragma unroll
+        for (int j = 0; j < RING; ++j) {
+#pragma unroll
+            for (int f = 0; f < NFRAG; ++f) ra[j][f] = load_frag(wp + (j * NFRAG + f) * 256);
+            rx[j] = xp[j * 64];
         }
-        wp += kRing * NFRAG * 64;
-        xp += kRing * 64;
+        issue_reads(rx[0], xb[0]);
+        bool done = false;
+        while (!done) {
+#pragma unroll
+            for (int j = 0; j < RING; ++j) {
+                // the LDS reads of the next step go out before this step's MFMAs (the scheduler
+                // would otherwise sink them below the MFMAs)
+                issue_reads(rx[(j + 1) % RING], xb[(j + 1) & 1]);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int u = 0; u < NSUB; ++u)
+#pragma unroll
+                    for (int f = 0; f < NFRAG; ++f) acc[f][u] = mfma16<DT>(ra[j][f], xb[j & 1][u], acc[f][u]);
+                __builtin_amdgcn_sched_barrier(0);
+                // refill this ring slot with step gs + RING
+#pragma unroll
+                for (int f = 0; f < NFRAG; ++f) ra[j][f] = load_frag(wp + ((RING + j) * NFRAG + f) * 256);
+                rx[j] = xp[(RING + j) * 64];  // its old value went into the previous sub-iteration's reads
+                ++gs;
+                if (gs >= blk_end || gs >= gs_hi) {  // uniform; also ends the walk on a malformed plan
+                    pass_boundaries();
+                    if (gs >= gs_hi) {
+                        done = true;
+                        break;
+                    }
+                }
+            }
+            wp += RING * NFRAG * 256;
+            xp += RING * 64;
+        }
     }
+}
+
+template <typename K>
+int raise_lds_limit(K kern, size_t lds, size_t &configured) {
+    if (lds <= configured) return BSP_OK;
+    hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) {
+        set_last_hip_error((int)e);
+        return BSP_ERR_HIP;
+    }
+    configured = lds;
+    return BSP_OK;
 }
 
 template <int DT, int NFRAG, int NSUB, bool PLAN>
 int launch(const TiledArgs &a, int waves, hipStream_t s) {
     const size_t lds = (size_t)(NSUB - 1) * sub_stride<NSUB>() + (size_t)a.npad * 32;
-    const void *kern = PLAN ? (const void *)linear_tiled_planned_kernel<DT, NFRAG, NSUB>
-                            : (const void *)linear_tiled_canonical_kernel<DT, NFRAG, NSUB>;
-    static thread_local size_t configured = 0;  // per instantiation and thread: raise the dynamic LDS limit once
-    if (lds > configured) {
-        hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) {
-            set_last_hip_error((int)e);
-            return BSP_ERR_HIP;
-        }
-        configured = lds;
-    }
+    static thread_local size_t configured = 0;  // per instantiation and thread
     const int64_t ntiles = (a.T + 16 * NSUB - 1) / (16 * NSUB);
-    // enough strips to give every compute unit a workgroup, but never fewer than 4 row-blocks per strip
-    int64_t nstrips = (256 + ntiles - 1) / ntiles;
-    const int64_t max_strips = (a.B + 3) / 4;
-    if (nstrips > max_strips) nstrips = max_strips;
+    int64_t nstrips = (256 + ntiles - 1) / ntiles;  // enough strips to give every compute unit a workgroup
     if (nstrips < 1) nstrips = 1;
-    int64_t rb_per_strip = (a.B + nstrips - 1) / nstrips;
-    if (rb_per_strip > kMaxStripBlocks) rb_per_strip = kMaxStripBlocks;
-    nstrips = (a.B + rb_per_strip - 1) / rb_per_strip;
-    if (ntiles * nstrips >= ((int64_t)1 << 31)) return BSP_ERR_SHAPE;
-    const dim3 grid((unsigned)(ntiles * nstrips)), block((unsigned)(waves * 64));
-    if constexpr (PLAN)
-        linear_tiled_planned_kernel<DT, NFRAG, NSUB><<<grid, block, lds, s>>>(
-            a.X, a.T, a.M, a.N, a.R, a.npad, a.blk_ptr, (const uint4 *)a.wfrag, a.xoff, a.bias, a.Y, (int32_t)ntiles,
-            (int32_t)rb_per_strip, (int32_t)a.B);
-    else
-        linear_tiled_canonical_kernel<DT, NFRAG, NSUB><<<grid, block, lds, s>>>(
+    if constexpr (PLAN) {
+        auto kern = linear_tiled_planned_kernel<DT, NFRAG, NSUB>;
+        int st = raise_lds_limit(kern, lds, configured);
+        if (st != BSP_OK) return st;
+        const int64_t NG = (a.B + kPlanWaves - 1) / kPlanWaves;
+        if (nstrips > NG) nstrips = NG;
+        int64_t gps = (NG + nstrips - 1) / nstrips;
+        if (gps > kMaxStripGroups) gps = kMaxStripGroups;
+        nstrips = (NG + gps - 1) / gps;
+        if (ntiles * nstrips >= ((int64_t)1 << 31)) return BSP_ERR_SHAPE;
+        kern<<<dim3((unsigned)(ntiles * nstrips)), dim3(kPlanWaves * 64), lds, s>>>(
+            a.X, a.T, a.M, a.N, a.R, a.npad, a.wptr, (const uint32_t *)a.wfrag, a.xoff, a.bias, a.Y, (int32_t)ntiles,
+            (int32_t)gps, (int32_t)NG, (int32_t)a.B);
+    } else {
+        auto kern = linear_tiled_canonical_kernel<DT, NFRAG, NSUB>;
+        int st = raise_lds_limit(kern, lds, configured);
+        if (st != BSP_OK) return st;
+        const int64_t max_strips = (a.B + 3) / 4;  // never fewer than 4 row-blocks per strip
+        if (nstrips > max_strips) nstrips = max_strips;
+        int64_t rb_per_strip = (a.B + nstrips - 1) / nstrips;
+        if (rb_per_strip > kMaxStripBlocks) rb_per_strip = kMaxStripBlocks;
+        nstrips = (a.B + rb_per_strip - 1) / rb_per_strip;
+        if (ntiles * nstrips >= ((int64_t)1 << 31)) return BSP_ERR_SHAPE;
+        kern<<<dim3((unsigned)(ntiles * nstrips)), dim3((unsigned)(waves * 64)), lds, s>>>(
             a.X, a.T, a.M, a.N, a.R, a.npad, a.blk_ptr, a.col_idx, a.vals, a.bias, a.Y, (int32_t)ntiles,
             (int32_t)rb_per_strip, (int32_t)a.B);
+    }
     return check_launch();
 }
 
 template <int DT, int NFRAG, bool PLAN>
 int launch_nsub(const TiledArgs &a, int waves, hipStream_t s) {
+    // the X tile must fit the 160 KiB of LDS: 64 tokens up to 1024 columns, 32 up to 2048, 16 up to 4096
     if (a.npad <= 1024) return launch<DT, NFRAG, 4, PLAN>(a, waves, s);
-    return launch<DT, NFRAG, 2, PLAN>(a, waves, s);
+    if (a.npad <= 2048) return launch<DT, NFRAG, 2, PLAN>(a, waves, s);
+    return launch<DT, NFRAG, 1, PLAN>(a, waves, s);
 }
 
 template <int DT, bool PLAN>
@@ -505,13 +522,13 @@ int launch_nfrag(const TiledArgs &a, int waves, hipStream_t s) {
 static int g_tiled_waves = 16;
 void set_tiled_waves(int w) { g_tiled_waves = (w == 4 || w == 8 || w == 16) ? w : 16; }
 
-int plan_slack_steps() { return kRing; }
+int plan_slack_steps() { return kPlanRing; }
 
 bool tiled_supported(int xdt, int64_t N, int32_t k_align) {
     if (xdt != BSP_BF16 && xdt != BSP_F16) return false;
     if (k_align % 32 != 0 || N < 32 || N % 8 != 0) return false;
     const int64_t npad = (N + 255) / 256 * 256;
-    return npad <= 2048;  // LDS byte offsets inside a sub-tile are 16-bit
+    return npad <= 4096;  // a 16-token sub-tile of 4096 columns fills 128 KiB of LDS
 }
 
 int launch_linear_tiled(const TiledArgs &args, bool plan, hipStream_t s) {

@@ -7,7 +7,16 @@
 // sets of 8, one column per bank group where the counts allow; columns of over-full groups and
 // zero-weight pads fill the gaps.  Per 32-column step the plan stores, ready to load per lane,
 // the value-panel fragments (16 rows x 32 columns, 16 bytes per lane) and the two 16-bit LDS
-// byte offsets of the lane's transposing reads.  Integer work only; deterministic.
+// byte offsets of the lane's transposing reads.
+//
+// Order of the steps: the layer kernel deals row-blocks to its 16 wavefronts round-robin, so the
+// plan keeps the steps of wavefront w (blocks w, w+16, w+32, ...) contiguous, stream after
+// stream; wptr[w][g] is the step index where block 16g + w starts, wptr[w][NG] where stream w ends.
+//
+// Buffer layout (bytes): wptr int32 [streams][NG+1], padded to 256 | fragments [steps][nfrag][4][64] dwords
+// (dword k of every lane's 16-byte fragment lies in plane k, so that 4-byte-per-lane loads are contiguous)
+// | offsets uint32 [steps][64], with steps = capacity_cols / 32 + read-ahead slack.
+// Integer work only; deterministic.
 #include "bsp_common.h"
 #include "bsp_linear_internal.h"
 
@@ -15,32 +24,71 @@ namespace bsp {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kMaxKp = 2048 + 32;
+constexpr int kMaxKp = 4096 + 32;
 
 __device__ __forceinline__ int slot_index(int set, int group) {
     // sets 4s .. 4s+3 of step s are what {first, second} read x {lower, upper} half-wavefront touch
     return 32 * (set >> 2) + ((set >> 1) & 1) * 16 + (set & 1) * 4 + (group >> 2) * 8 + (group & 3);
 }
 
-__global__ __launch_bounds__(kThreads) void plan_kernel(int32_t R, int32_t nfrag, const int32_t *__restrict__ blk_cnt,
-                                                        const int32_t *__restrict__ blk_ptr,
-                                                        const int32_t *__restrict__ col_idx,
-                                                        const uint16_t *__restrict__ vals, int64_t capacity_cols,
-                                                        int32_t slack_steps, uint4 *__restrict__ wfrag,
-                                                        uint32_t *__restrict__ xoff) {
-    __shared__ int32_t slotcol[kMaxKp], slotsrc[kMaxKp], ovfcol[kMaxKp], ovfsrc[kMaxKp];
+// One workgroup of 16 wavefronts: wavefront w scans the step counts of its blocks.
+__global__ __launch_bounds__(kPlanWaves * 64) void plan_scan_kernel(const int32_t *__restrict__ blk_ptr, int32_t B,
+                                                                    int32_t NG, int64_t capacity_cols,
+                                                                    int32_t slack_steps, int32_t *__restrict__ wptr,
+                                                                    uint32_t *__restrict__ xoff) {
+    __shared__ int totals[kPlanWaves];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    int32_t *mine = wptr + (int64_t)w * (NG + 1);
+    int carry = 0;
+    for (int gbase = 0; gbase < NG; gbase += 64) {
+        const int g = gbase + lane;
+        const int64_t b = (int64_t)kPlanWaves * g + w;
+        int st = 0;
+        if (g < NG && b < B) {
+            const int kp = blk_ptr[b + 1] - blk_ptr[b];
+            st = kp > 0 ? kp >> 5 : 0;
+        }
+        int incl = st;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int up = __shfl_up(incl, o, 64);
+            if (lane >= o) incl += up;
+        }
+        if (g < NG) mine[g] = carry + incl - st;
+        carry += __shfl(incl, 63, 64);
+    }
+    if (lane == 0) {
+        mine[NG] = carry;
+        totals[w] = carry;
+    }
+    __syncthreads();
+    int wbase = 0;
+    for (int k = 0; k < w; ++k) wbase += totals[k];
+    __syncthreads();  // the stores above are visible to the whole workgroup now
+    for (int g = lane; g <= NG; g += 64) mine[g] += wbase;
+    // the layer kernel reads a few steps past the end of the last stream: give those steps the
+    // LDS offset 0 (their values are never used, but the addresses must be valid)
+    if (w == kPlanWaves - 1) {
+        const int64_t total = (int64_t)wbase + carry;
+        if ((total << 5) <= capacity_cols)
+            for (int i = lane; i < slack_steps * 64; i += 64) xoff[total * 64 + i] = 0u;
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void plan_fill_kernel(int32_t R, int32_t nfrag, int32_t NG,
+                                                             const int32_t *__restrict__ blk_cnt,
+                                                             const int32_t *__restrict__ blk_ptr,
+                                                             const int32_t *__restrict__ col_idx,
+                                                             const uint16_t *__restrict__ vals, int64_t capacity_cols,
+                                                             const int32_t *__restrict__ wptr,
+                                                             uint32_t *__restrict__ wfrag, uint32_t *__restrict__ xoff) {
+    // columns and canonical positions are below 4096 + 32: 16 bits each; 0xffff marks a pad
+    __shared__ uint16_t slotcol[kMaxKp], slotsrc[kMaxKp], ovfcol[kMaxKp], ovfsrc[kMaxKp];
     __shared__ int s_filled[8], s_hp[9], s_novf;
     const int64_t b = blockIdx.x;
     const int base = blk_ptr[b];
     const int kp = blk_ptr[b + 1] - base;
     const int kb = blk_cnt[b];
-    if (b == gridDim.x - 1) {
-        // the layer kernel reads a few steps past the end of the storage: give those steps the
-        // LDS offset 0 (their values are never used, but the addresses must be valid)
-        const int64_t total_steps = (int64_t)blk_ptr[b + 1] >> 5;
-        if (total_steps >= 0 && (total_steps << 5) <= capacity_cols)
-            for (int i = threadIdx.x; i < slack_steps * 64; i += kThreads) xoff[total_steps * 64 + i] = 0u;
-    }
     if (kp <= 0 || kp > kMaxKp || (kp & 31) || kb > kp || kb < 0 || (int64_t)base + kp > capacity_cols) return;
     const int S = kp >> 3;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -65,12 +113,12 @@ __global__ __launch_bounds__(kThreads) void plan_kernel(int32_t R, int32_t nfrag
             const uint64_t mo = __ballot(over);
             if (valid && !over) {
                 const int slot = slot_index(rank, g);
-                slotcol[slot] = col;
-                slotsrc[slot] = i;
+                slotcol[slot] = (uint16_t)col;
+                slotsrc[slot] = (uint16_t)i;
             } else if (over) {
                 const int oi = novf + __popcll(mo & lt);
-                ovfcol[oi] = col;
-                ovfsrc[oi] = i;
+                ovfcol[oi] = (uint16_t)col;
+                ovfsrc[oi] = (uint16_t)i;
             }
             novf += __popcll(mo);
         }
@@ -100,20 +148,21 @@ __global__ __launch_bounds__(kThreads) void plan_kernel(int32_t R, int32_t nfrag
             slotcol[slot] = ovfcol[e];
             slotsrc[slot] = ovfsrc[e];
         } else {
-            slotcol[slot] = g << 2;  // any column of bank group g; its weight is zero
-            slotsrc[slot] = -1;
+            slotcol[slot] = (uint16_t)(g << 2);  // any column of bank group g; its weight is zero
+            slotsrc[slot] = 0xffffu;
         }
     }
     __syncthreads();
     // per-lane operands of every step
     const int l16 = lane & 15, G = lane >> 4, q = (lane >> 2) & 3, p = lane & 3;
     const int nsteps = kp >> 5;
-    const int64_t gs0 = base >> 5;
+    const int64_t gs0 = wptr[(b % kPlanWaves) * (NG + 1) + b / kPlanWaves];
+    if (gs0 < 0 || ((gs0 + nsteps) << 5) > capacity_cols) return;
     for (int s = wave; s < nsteps; s += kThreads / 64) {
         const int s1 = 32 * s + 8 * G + q;
         const uint32_t o1 = lds_col_offset((uint32_t)slotcol[s1], (uint32_t)p);
         const uint32_t o2 = lds_col_offset((uint32_t)slotcol[s1 + 4], (uint32_t)p);
-        xoff[(gs0 + s) * 64 + lane] = o1 | (o2 << 16);
+        xoff[(gs0 + s) * 64 + lane] = (o1 >> 3) | ((o2 >> 3) << 16);  // offsets are multiples of 8 bytes
         for (int f = 0; f < nfrag; ++f) {
             const int r = f * 16 + l16;
             uint32_t w[4] = {0u, 0u, 0u, 0u};
@@ -121,19 +170,34 @@ __global__ __launch_bounds__(kThreads) void plan_kernel(int32_t R, int32_t nfrag
                 const uint16_t *row = vals + (int64_t)R * base + (int64_t)r * kp;
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
-                    const int src = slotsrc[32 * s + 8 * G + i];
-                    const uint32_t v = src >= 0 ? (uint32_t)row[src] : 0u;
+                    const uint32_t src = slotsrc[32 * s + 8 * G + i];
+                    const uint32_t v = src != 0xffffu ? (uint32_t)row[src] : 0u;
                     w[i >> 1] |= v << (16 * (i & 1));
                 }
             }
-            wfrag[((gs0 + s) * nfrag + f) * 64 + lane] = make_uint4(w[0], w[1], w[2], w[3]);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) wfrag[(((gs0 + s) * nfrag + f) * 4 + k) * 64 + lane] = w[k];
         }
     }
 }
 
 inline int nfrag_of(int32_t R) { return R <= 16 ? 1 : (R <= 32 ? 2 : 4); }
-// Steps the plan buffer holds: those of capacity_cols columns plus the read-ahead slack.
-inline size_t plan_steps(int64_t capacity_cols) { return (size_t)((capacity_cols + 31) / 32) + (size_t)plan_slack_steps(); }
+
+struct PlanLayout {
+    int64_t NG;
+    size_t steps, wptr_bytes, wfrag_bytes, xoff_bytes;
+    size_t total() const { return wptr_bytes + wfrag_bytes + xoff_bytes; }
+};
+inline PlanLayout plan_layout(int64_t M, int32_t R, int64_t capacity_cols) {
+    PlanLayout L;
+    const int64_t B = M / R;
+    L.NG = (B + kPlanWaves - 1) / kPlanWaves;
+    L.steps = (size_t)((capacity_cols + 31) / 32) + (size_t)plan_slack_steps();
+    L.wptr_bytes = ((size_t)kPlanWaves * (size_t)(L.NG + 1) * sizeof(int32_t) + 255) / 256 * 256;
+    L.wfrag_bytes = L.steps * (size_t)nfrag_of(R) * 1024;
+    L.xoff_bytes = L.steps * 256;
+    return L;
+}
 
 }  // namespace
 }  // namespace bsp
@@ -144,54 +208,55 @@ extern "C" int bsp_linear_plan_supported(int xdt, int64_t N, int32_t k_align) {
     return tiled_supported(xdt, N, k_align) ? 1 : 0;
 }
 
-extern "C" size_t bsp_linear_plan_bytes(int32_t R, int64_t capacity_cols) {
-    if (R < 1 || R > 64 || capacity_cols <= 0) return 0;
-    return plan_steps(capacity_cols) * ((size_t)nfrag_of(R) * 1024 + 256);
+extern "C" size_t bsp_linear_plan_bytes(int64_t M, int32_t R, int64_t capacity_cols) {
+    if (R < 1 || R > 64 || M <= 0 || M % R != 0 || capacity_cols < 0) return 0;
+    return plan_layout(M, R, capacity_cols).total();
 }
 
 extern "C" int bsp_linear_plan(int vdt, int64_t M, int64_t N, int32_t R, int32_t k_align, const int32_t *blk_cnt,
                                const int32_t *blk_ptr, const int32_t *col_idx, const void *vals,
                                int64_t capacity_cols, void *plan, size_t plan_bytes, void *stream) {
-    if (!blk_cnt || !blk_ptr) return BSP_ERR_NULL;
-    if (M <= 0 || N <= 0 || R < 1 || R > 64 || M % R != 0) return BSP_ERR_SHAPE;
+    if (!blk_cnt || !blk_ptr || !plan) return BSP_ERR_NULL;
+    if (M <= 0 || N <= 0 || R < 1 || R > 64 || M % R != 0 || M / R > 65535) return BSP_ERR_SHAPE;
     if (!tiled_supported(vdt, N, k_align)) return BSP_ERR_SHAPE;
     if (capacity_cols < 0) return BSP_ERR_CAPACITY;
-    if (capacity_cols == 0) return BSP_OK;
-    if (!col_idx || !vals || !plan) return BSP_ERR_NULL;
-    if (plan_bytes < bsp_linear_plan_bytes(R, capacity_cols) || !aligned(plan, 16)) return BSP_ERR_CAPACITY;
+    if (capacity_cols > 0 && (!col_idx || !vals)) return BSP_ERR_NULL;
+    const PlanLayout L = plan_layout(M, R, capacity_cols);
+    if (plan_bytes < L.total() || !aligned(plan, 16)) return BSP_ERR_CAPACITY;
     const int64_t B = M / R;
-    const size_t steps = plan_steps(capacity_cols);
     const int nf = nfrag_of(R);
-    uint4 *wfrag = (uint4 *)plan;
-    uint32_t *xoff = (uint32_t *)((uint8_t *)plan + steps * (size_t)nf * 1024);
-    plan_kernel<<<(unsigned)B, kThreads, 0, (hipStream_t)stream>>>(R, nf, blk_cnt, blk_ptr, col_idx,
-                                                                            (const uint16_t *)vals, capacity_cols,
-                                                               plan_slack_steps(), wfrag, xoff);
+    int32_t *wptr = (int32_t *)plan;
+    uint32_t *wfrag = (uint32_t *)((uint8_t *)plan + L.wptr_bytes);
+    uint32_t *xoff = (uint32_t *)((uint8_t *)plan + L.wptr_bytes + L.wfrag_bytes);
+    hipStream_t s = (hipStream_t)stream;
+    plan_scan_kernel<<<1, kPlanWaves * 64, 0, s>>>(blk_ptr, (int32_t)B, (int32_t)L.NG, capacity_cols,
+                                                   plan_slack_steps(), wptr, xoff);
+    if (capacity_cols > 0)
+        plan_fill_kernel<<<(unsigned)B, kThreads, 0, s>>>(R, nf, (int32_t)L.NG, blk_cnt, blk_ptr, col_idx,
+                                                          (const uint16_t *)vals, capacity_cols, wptr, wfrag, xoff);
     return check_launch();
 }
 
 extern "C" int bsp_linear_planned(const void *X, int xdt, int64_t T, int64_t M, int64_t N, int32_t R, int32_t k_align,
-                                  const int32_t *blk_ptr, const void *plan, int64_t capacity_cols, const void *bias,
-                                  void *Y, void *stream) {
-    if (!X || !blk_ptr || !Y) return BSP_ERR_NULL;
-    if (T < 0 || M <= 0 || N <= 0 || R < 1 || R > 64 || M % R != 0) return BSP_ERR_SHAPE;
+                                  const void *plan, int64_t capacity_cols, const void *bias, void *Y, void *stream) {
+    if (!X || !plan || !Y) return BSP_ERR_NULL;
+    if (T < 0 || M <= 0 || N <= 0 || R < 1 || R > 64 || M % R != 0 || M / R > 65535) return BSP_ERR_SHAPE;
     if (!tiled_supported(xdt, N, k_align)) return BSP_ERR_SHAPE;
     if (capacity_cols < 0) return BSP_ERR_CAPACITY;
-    if (capacity_cols > 0 && !plan) return BSP_ERR_NULL;
     if (!aligned(X, 16) || !aligned(Y, 16) || !aligned(plan, 16)) return BSP_ERR_SHAPE;
     if (T == 0) return BSP_OK;
-    const size_t steps = plan_steps(capacity_cols);
+    const PlanLayout L = plan_layout(M, R, capacity_cols);
     TiledArgs a{};
     a.xdt = xdt;
     a.X = (const uint16_t *)X;
     a.T = T; a.M = M; a.N = N; a.B = M / R; a.R = R;
-    a.blk_ptr = blk_ptr;
-    a.wfrag = plan;
-    a.xoff = (const uint32_t *)((const uint8_t *)plan + steps * (size_t)nfrag_of(R) * 1024);
+    a.wptr = (const int32_t *)plan;
+    a.wfrag = (const uint8_t *)plan + L.wptr_bytes;
+    a.xoff = (const uint32_t *)((const uint8_t *)plan + L.wptr_bytes + L.wfrag_bytes);
     a.bias = bias;
     a.Y = Y;
     return launch_linear_tiled(a, true, (hipStream_t)stream);
 }
 
-// Experiment hook (not part of the documented ABI): wavefronts per workgroup of the tiled kernel.
+// Experiment hook (not part of the documented ABI): wavefronts per workgroup of the canonical tiled kernel.
 extern "C" void bsp_debug_set_tiled_waves(int waves) { set_tiled_waves(waves); }
