@@ -81,6 +81,14 @@ class Matrix:
         if self.use_plan:
             bsp.bsp_linear_plan(self.packed, plan=self.plan)
 
+    def capture(self):
+        """Record the two halves of this matrix's step into HIP graphs (after a warm-up run)."""
+        self.g_prep, self.g_lin = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
+        with torch.cuda.graph(self.g_prep):
+            self.prune_and_pack()
+        with torch.cuda.graph(self.g_lin):
+            self.linear()
+
     def linear(self):
         if self.use_plan:
             bsp.bsp_linear_planned(self.X, self.packed, self.plan, self.bias, Y=self.Y)
@@ -128,6 +136,8 @@ def main():
     ap.add_argument("--path", choices=["planned", "canonical"], default="planned",
                     help="layer operands: the derived plan buffer (default) or the compact storage itself")
     ap.add_argument("--waves", type=int, default=0, help="experiment: wavefronts per workgroup of the tiled kernel")
+    ap.add_argument("--no-graphs", action="store_true",
+                    help="launch every kernel from Python instead of replaying two HIP graphs per matrix")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: the path has no multi-GPU part; run with --gpus 1", file=sys.stderr)
@@ -147,12 +157,23 @@ def main():
     for m in mats:
         m.kept_cols = int(m.blk_cnt.sum().item())
 
+    use_graphs = not args.no_graphs
+    if use_graphs:   # the step is launch-bound from Python (about 40 short kernels): replay it from HIP graphs
+        for m in mats:
+            m.capture()
+
     def step(events=None):
         for i, m in enumerate(mats):
-            m.prune_and_pack()
+            if use_graphs:
+                m.g_prep.replay()
+            else:
+                m.prune_and_pack()
             if events is not None:
                 events[i][0].record()
-            m.linear()
+            if use_graphs:
+                m.g_lin.replay()
+            else:
+                m.linear()
             if events is not None:
                 events[i][1].record()
 
@@ -201,7 +222,7 @@ def main():
         "config": {"workload": "BERT-large linear set (configs[3]): QKV 3072x1024, out 1024x1024, up 4096x1024, "
                                "down 1024x4096; 8192 tokens; 5x compression; matrix-scope percentile mask",
                    "block_rows": args.R, "k_align": 32, "tokens": 8192,
-                   "layer_path": args.path,
+                   "layer_path": args.path, "launch": "hip graphs (2 per matrix)" if use_graphs else "eager",
                    "step": "group_norms + penalty_grad + prune_mask + pack_count + pack + linear_plan + linear, "
                            "4 matrices"},
         "linear_only": {"ms": round(lin_total_ms, 4), "useful_tflops": round(achieved_tflops, 2),

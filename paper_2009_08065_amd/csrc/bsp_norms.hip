@@ -63,6 +63,34 @@ struct vec_io<BSP_F16, 8> {
         *reinterpret_cast<h8 *>((_Float16 *)p + i) = q;
     }
 };
+// 4-byte vector of 2 bf16 / 2 fp16: a wavefront load covers 256 contiguous bytes, the width the
+// vector memory pipeline sustains best, and a row-block offers 4x more lanes than with 16-byte vectors.
+template <>
+struct vec_io<BSP_BF16, 2> {
+    static __device__ __forceinline__ void load(const void *p, int64_t i, float (&v)[2]) {
+        const uint32_t w = *reinterpret_cast<const uint32_t *>((const uint16_t *)p + i);
+        v[0] = __uint_as_float(w << 16);
+        v[1] = __uint_as_float(w & 0xffff0000u);
+    }
+    static __device__ __forceinline__ void store(void *p, int64_t i, const float (&v)[2]) {
+        *reinterpret_cast<uint32_t *>((uint16_t *)p + i) = (uint32_t)float_to_bf16(v[0]) | ((uint32_t)float_to_bf16(v[1]) << 16);
+    }
+};
+template <>
+struct vec_io<BSP_F16, 2> {
+    typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+    static __device__ __forceinline__ void load(const void *p, int64_t i, float (&v)[2]) {
+        const h2 q = *reinterpret_cast<const h2 *>((const _Float16 *)p + i);
+        v[0] = (float)q[0];
+        v[1] = (float)q[1];
+    }
+    static __device__ __forceinline__ void store(void *p, int64_t i, const float (&v)[2]) {
+        h2 q;
+        q[0] = (_Float16)v[0];
+        q[1] = (_Float16)v[1];
+        *reinterpret_cast<h2 *>((_Float16 *)p + i) = q;
+    }
+};
 // Scalar fallback for unaligned or ragged rows.
 template <int DT>
 struct vec_io<DT, 1> {
@@ -78,6 +106,8 @@ template <int VEC>
 __device__ __forceinline__ void store_f32(float *p, int64_t i, const float (&v)[VEC]) {
     if constexpr (VEC == 1) {
         p[i] = v[0];
+    } else if constexpr (VEC == 2) {
+        *reinterpret_cast<float2 *>(p + i) = make_float2(v[0], v[1]);
     } else {
 #pragma unroll
         for (int k = 0; k < VEC; k += 4)
@@ -88,6 +118,10 @@ template <int VEC>
 __device__ __forceinline__ void load_f32(const float *p, int64_t i, float (&v)[VEC]) {
     if constexpr (VEC == 1) {
         v[0] = p[i];
+    } else if constexpr (VEC == 2) {
+        const float2 q = *reinterpret_cast<const float2 *>(p + i);
+        v[0] = q.x;
+        v[1] = q.y;
     } else {
 #pragma unroll
         for (int k = 0; k < VEC; k += 4) {
@@ -234,6 +268,29 @@ __global__ __launch_bounds__(kThreads) void penalty_grad_kernel(const void *__re
     }
 }
 
+// Squared-norm form without the penalty value: coef depends on alpha only, so the gradient is a
+// plain element-wise product; one lane per 16-byte vector of W, rows of W along grid.y.
+template <int DT, int VEC>
+__global__ __launch_bounds__(kThreads) void penalty_grad_sq_kernel(const void *__restrict__ W, int64_t N, int32_t R,
+                                                                   const float *__restrict__ alpha, float lambda,
+                                                                   int accumulate, void *__restrict__ G) {
+    const int64_t j = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * VEC;
+    if (j >= N) return;
+    const int64_t m = blockIdx.y;
+    float a[VEC], w[VEC], g[VEC];
+    load_f32<VEC>(alpha, (m / R) * N + j, a);
+    vec_io<DT, VEC>::load(W, m * N + j, w);
+    if (accumulate) {
+        vec_io<DT, VEC>::load(G, m * N + j, g);
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) g[v] = __builtin_fmaf(lambda * a[v], w[v], g[v]);
+    } else {
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) g[v] = (lambda * a[v]) * w[v];
+    }
+    vec_io<DT, VEC>::store(G, m * N + j, g);
+}
+
 // One workgroup sums the per-workgroup partials in index order.
 __global__ __launch_bounds__(kThreads) void penalty_finish_kernel(const double *__restrict__ partial, int64_t n,
                                                                   double *__restrict__ out) {
@@ -252,7 +309,7 @@ __global__ __launch_bounds__(kThreads) void penalty_finish_kernel(const double *
 }
 
 template <int DT>
-constexpr int native_vec() { return DT == BSP_F32 ? 4 : 8; }
+constexpr int native_vec() { return DT == BSP_F32 ? 1 : 2; }  // 4 bytes per lane
 
 inline int check_matrix(const void *W, int wdt, int64_t M, int64_t N, int32_t R) {
     if (!W) return BSP_ERR_NULL;
@@ -336,6 +393,22 @@ extern "C" int bsp_penalty_grad(const void *W, int wdt, int64_t M, int64_t N, in
     }
     hipStream_t s = (hipStream_t)stream;
     double *partial = (double *)ws;
+    if (mode == BSP_ALPHA_SQNORM && !penalty && M <= 65535) {
+        BSP_DISPATCH_DTYPE(wdt, DT, {
+            constexpr int V16 = DT == BSP_F32 ? 4 : 8;  // 16 bytes per lane: every lane is independent here
+            const bool vec_ok = (N % V16 == 0) && aligned(W, 16) && aligned(grad, 16) && aligned(alpha, 16);
+            if (vec_ok) {
+                const int64_t nv = N / V16;
+                const unsigned bs = nv >= 256 ? 256 : (unsigned)((nv + 63) / 64 * 64);
+                penalty_grad_sq_kernel<DT, V16><<<dim3((unsigned)((nv + bs - 1) / bs), (unsigned)M), bs, 0, s>>>(
+                    W, N, R, alpha, lambda, accumulate, grad);
+            } else {
+                penalty_grad_sq_kernel<DT, 1><<<dim3((unsigned)((N + 255) / 256), (unsigned)M), 256, 0, s>>>(
+                    W, N, R, alpha, lambda, accumulate, grad);
+            }
+        });
+        return check_launch();
+    }
     BSP_DISPATCH_DTYPE(wdt, DT, {
         constexpr int V = native_vec<DT>();
         const bool vec_ok = (N % V == 0) && aligned(W, 16) && aligned(grad, 16) && aligned(alpha, 16);

@@ -66,15 +66,25 @@ __global__ __launch_bounds__(kThreads) void pack_scan_kernel(const int32_t *__re
     if (threadIdx.x == 0) blk_ptr[B] = carry;
 }
 
-// One workgroup per row-block.
+// One workgroup per row-block.  The keep row is cut into chunks of 64 columns, one wavefront
+// ballot each: pass 1 counts the kept columns of every chunk, wavefront 0 scans the counts, pass 2
+// writes each kept column index at (chunk offset + lane prefix) and copies its R values from W
+// straight into the panel.  Reads of a W row touch consecutive columns, panel writes are
+// contiguous in c.
+constexpr int kMaxChunks = 1024;  // 64-column chunks handled with LDS-resident counts (N <= 65536)
+
+constexpr int kPackThreads = 1024;  // 16 wavefronts: one 64-column chunk each for N = 1024, so the chunks'
+                                    // load -> ballot -> gather chains run side by side
+constexpr int kPackWaves = kPackThreads / kWave;
+
 template <int WDT, int VDT>
-__global__ __launch_bounds__(kThreads) void pack_kernel(const void *__restrict__ W, int64_t N, int32_t R,
+__global__ __launch_bounds__(kPackThreads) void pack_kernel(const void *__restrict__ W, int64_t N, int32_t R,
                                                         const uint8_t *__restrict__ keep,
                                                         const int32_t *__restrict__ blk_cnt,
                                                         const int32_t *__restrict__ blk_ptr, int64_t capacity_cols,
                                                         int32_t *__restrict__ col_idx, void *__restrict__ vals) {
-    __shared__ int wcnt[kWaves];
-    __shared__ int running;
+    __shared__ int chunk_off[kMaxChunks + 1];
+    __shared__ int s_last;
     const int64_t b = blockIdx.x;
     const int64_t base = blk_ptr[b];
     const int kp = blk_ptr[b + 1] - blk_ptr[b];
@@ -83,43 +93,58 @@ __global__ __launch_bounds__(kThreads) void pack_kernel(const void *__restrict__
     const uint8_t *krow = keep + b * N;
     int32_t *idx = col_idx + base;
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-    if (threadIdx.x == 0) running = 0;
-    __syncthreads();
-    // ascending compaction of the kept column indices
-    for (int64_t j0 = 0; j0 < N; j0 += kThreads) {
-        const int64_t j = j0 + threadIdx.x;
-        const bool k = j < N && krow[j] != 0;
-        const uint64_t m = __ballot(k);
-        const int before = __popcll(m & ((1ull << lane) - 1ull));
-        if (lane == 0) wcnt[wave] = __popcll(m);
-        __syncthreads();
-        int off = running;
-        for (int w = 0; w < wave; ++w) off += wcnt[w];
-        const int pos = off + before;
-        if (k && pos < kb) idx[pos] = (int32_t)j;
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            int t = running;
-            for (int w = 0; w < kWaves; ++w) t += wcnt[w];
-            running = t;
-        }
-        __syncthreads();
-    }
-    // the list just written by this workgroup is read back below
-    __threadfence_block();
-    __syncthreads();
-    const int32_t last = idx[kb - 1];
-    for (int c = kb + threadIdx.x; c < kp; c += kThreads) idx[c] = last;
-    // value panel: row r of the panel is contiguous in c
+    const int nchunks = (int)((N + kWave - 1) / kWave);
+    const uint64_t lt = (1ull << lane) - 1ull;
     const int64_t vbase = (int64_t)R * base;
-    for (int c = threadIdx.x; c < kp; c += kThreads) {
-        const bool real = c < kb;
-        const int64_t wcol = b * R * N + (real ? idx[c] : 0);
-#pragma unroll 8
-        for (int r = 0; r < R; ++r) {
-            const float v = real ? elem<WDT>::load(W, wcol + (int64_t)r * N) : 0.0f;
-            elem<VDT>::store(vals, vbase + (int64_t)r * kp + c, v);
+    const int64_t wbase = b * R * N;
+
+    for (int c0 = 0; c0 < nchunks; c0 += kMaxChunks) {  // one round unless N > 65536
+        const int nc = min(kMaxChunks, nchunks - c0);
+        const int carry = c0 == 0 ? 0 : chunk_off[kMaxChunks];
+        __syncthreads();
+        for (int c = wave; c < nc; c += kPackWaves) {
+            const int64_t j = (int64_t)(c0 + c) * kWave + lane;
+            const uint64_t m = __ballot(j < N && krow[j] != 0);
+            if (lane == 0) chunk_off[c] = __popcll(m);
         }
+        __syncthreads();
+        if (wave == 0) {  // exclusive scan of the chunk counts
+            int run = carry;
+            for (int cb = 0; cb < nc; cb += kWave) {
+                const int c = cb + lane;
+                const int v = c < nc ? chunk_off[c] : 0;
+                int incl = v;
+#pragma unroll
+                for (int o = 1; o < kWave; o <<= 1) {
+                    const int up = __shfl_up(incl, o, kWave);
+                    if (lane >= o) incl += up;
+                }
+                if (c < nc) chunk_off[c] = run + incl - v;
+                run += __shfl(incl, kWave - 1, kWave);
+            }
+            if (lane == 0) chunk_off[kMaxChunks] = run;
+        }
+        __syncthreads();
+        for (int c = wave; c < nc; c += kPackWaves) {
+            const int64_t j = (int64_t)(c0 + c) * kWave + lane;
+            const bool k = j < N && krow[j] != 0;
+            const uint64_t m = __ballot(k);
+            const int pos = chunk_off[c] + __popcll(m & lt);
+            if (k && pos < kb) {
+                idx[pos] = (int32_t)j;
+                if (pos == kb - 1) s_last = (int32_t)j;
+#pragma unroll 8
+                for (int r = 0; r < R; ++r)
+                    elem<VDT>::store(vals, vbase + (int64_t)r * kp + pos, elem<WDT>::load(W, wbase + (int64_t)r * N + j));
+            }
+        }
+    }
+    __syncthreads();
+    // pads: repeat the last kept column, zero values
+    const int32_t last = s_last;
+    for (int c = kb + threadIdx.x; c < kp; c += kPackThreads) {
+        idx[c] = last;
+        for (int r = 0; r < R; ++r) elem<VDT>::store(vals, vbase + (int64_t)r * kp + c, 0.0f);
     }
 }
 
@@ -183,7 +208,7 @@ extern "C" int bsp_pack(const void *W, int wdt, int64_t M, int64_t N, int32_t R,
     hipStream_t s = (hipStream_t)stream;
     BSP_DISPATCH_DTYPE(wdt, WDT, {
         BSP_DISPATCH_DTYPE(vdt, VDT, {
-            pack_kernel<WDT, VDT><<<(unsigned)B, kThreads, 0, s>>>(W, N, R, keep, blk_cnt, blk_ptr, capacity_cols,
+            pack_kernel<WDT, VDT><<<(unsigned)B, kPackThreads, 0, s>>>(W, N, R, keep, blk_cnt, blk_ptr, capacity_cols,
                                                                    col_idx, vals);
         });
     });

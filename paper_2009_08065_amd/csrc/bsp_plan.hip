@@ -92,6 +92,10 @@ __global__ __launch_bounds__(kThreads) void plan_fill_kernel(int32_t R, int32_t 
     if (kp <= 0 || kp > kMaxKp || (kp & 31) || kb > kp || kb < 0 || (int64_t)base + kp > capacity_cols) return;
     const int S = kp >> 3;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    // the block's kept columns, fetched once with coalesced loads
+    __shared__ uint16_t cols[kMaxKp];
+    for (int i = threadIdx.x; i < kb; i += kThreads) cols[i] = (uint16_t)col_idx[base + i];
+    __syncthreads();
 
     if (wave == 0) {
         int cnt[8] = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -100,7 +104,7 @@ __global__ __launch_bounds__(kThreads) void plan_fill_kernel(int32_t R, int32_t 
         for (int i0 = 0; i0 < kb; i0 += 64) {
             const int i = i0 + lane;
             const bool valid = i < kb;
-            const int col = valid ? col_idx[base + i] : 0;
+            const int col = valid ? cols[i] : 0;
             const int g = (int)lds_bank_group((uint32_t)col);
             int rank = 0;
 #pragma unroll

@@ -1,0 +1,63 @@
+"""The whole path replayed from a HIP graph gives, on every replay, the bits of the eager run."""
+import numpy as np
+import pytest
+import torch
+
+import bsp_workloads as wl
+import paper_2009_08065_amd as bsp
+
+pytestmark = pytest.mark.gpu
+
+
+def test_graph_replays_match_eager():
+    T, M, N, R = 200, 512, 1024, 16
+    d = wl.layer(31, T, M, N, "bf16")
+    W = torch.from_numpy(d["W"]).bfloat16().cuda()
+    bias = torch.from_numpy(d["bias"]).bfloat16().cuda()
+    Xs = [torch.from_numpy(wl.normal(100 + i, (T, N), 1.0, "bf16")).bfloat16().cuda() for i in range(3)]
+    n_keep = (M // R) * N // 5
+    B = M // R
+    cap = n_keep + B * 31
+    dev = "cuda"
+    X = Xs[0].clone()
+    sumsq = torch.empty((B, N), dtype=torch.float32, device=dev)
+    alpha = torch.empty_like(sumsq)
+    grad = torch.empty_like(W)
+    keep = torch.empty((B, N), dtype=torch.uint8, device=dev)
+    ws = torch.empty(bsp.lib().bsp_prune_mask_workspace_bytes(B, N, bsp.SCOPE_MATRIX), dtype=torch.uint8, device=dev)
+    cnt = torch.empty(B, dtype=torch.int32, device=dev)
+    ptr = torch.empty(B + 1, dtype=torch.int32, device=dev)
+    col = torch.empty(cap, dtype=torch.int32, device=dev)
+    vals = torch.empty(R * cap, dtype=torch.bfloat16, device=dev)
+    plan = torch.empty(bsp.lib().bsp_linear_plan_bytes(M, R, cap), dtype=torch.uint8, device=dev)
+    Y = torch.empty((T, M), dtype=torch.bfloat16, device=dev)
+    p = bsp.Packed(M, N, R, 32, cnt, ptr, col, vals, cap)
+
+    def path():
+        bsp.bsp_group_norms(W, R, sumsq=sumsq, alpha=alpha, want=())
+        bsp.bsp_penalty_grad(W, R, alpha, 1e-4, grad=grad)
+        bsp.bsp_prune_mask(sumsq, n_keep=n_keep, scope=bsp.SCOPE_MATRIX, keep=keep, ws=ws)
+        bsp.bsp_pack_count(keep, 32, blk_cnt=cnt, blk_ptr=ptr)
+        st = bsp.lib().bsp_pack(W.data_ptr(), bsp.BF16, M, N, R, keep.data_ptr(), 32, cnt.data_ptr(), ptr.data_ptr(),
+                                cap, col.data_ptr(), vals.data_ptr(), bsp.BF16,
+                                torch.cuda.current_stream().cuda_stream)
+        assert st == 0
+        bsp.bsp_linear_plan(p, plan=plan)
+        bsp.bsp_linear_planned(X, p, plan, bias, Y=Y)
+
+    want = []
+    for Xi in Xs:                       # eager reference (also the warm-up before capture)
+        X.copy_(Xi)
+        path()
+        torch.cuda.synchronize()
+        want.append((Y.clone(), keep.clone(), grad.clone()))
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        path()
+    for rep in range(2):
+        for Xi, (y_ref, k_ref, g_ref) in zip(Xs, want):
+            X.copy_(Xi)
+            Y.zero_(); keep.zero_(); grad.zero_(); col.zero_(); plan.zero_()   # eager work between replays
+            g.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(Y, y_ref) and torch.equal(keep, k_ref) and torch.equal(grad, g_ref)
