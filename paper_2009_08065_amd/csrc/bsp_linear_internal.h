@@ -16,9 +16,10 @@ struct TiledArgs {
     const int32_t *blk_ptr;
     const int32_t *col_idx;   // canonical source
     const uint16_t *vals;     // canonical source
-    const int32_t *wptr;      // planned source: [kPlanWaves][NG + 1] first step of block kPlanWaves * g + w in wavefront w's stream
+    const int32_t *wptr;      // planned source: [kPlanWaves][chunks * NG + 1] first step of (chunk q, block kPlanWaves * g + w) at [w][q * NG + g]
     const void *wfrag;        // planned source: [step][fragment][lane] 16-byte panel fragments
     const uint32_t *xoff;     // planned source: [step][lane] two 16-bit LDS byte offsets
+    int64_t plan_steps;       // planned source: steps the fragment / offset regions hold (slack included)
     const void *bias;
     void *Y;
 };
@@ -27,6 +28,18 @@ struct TiledArgs {
 bool tiled_supported(int xdt, int64_t N, int32_t k_align);
 int launch_linear_tiled(const TiledArgs &args, bool plan, hipStream_t s);
 void set_tiled_waves(int waves);
+// Column chunks of a plan: layers with more than 1024 (padded) input columns are cut into chunks of
+// 1024 columns, the width of X that fits in LDS next to 64 tokens; narrower layers are one chunk.
+constexpr int kPlanMaxChunks = 4;
+struct PlanChunks {
+    int32_t n;      // number of chunks
+    int32_t shift;  // column >> shift = chunk
+};
+inline PlanChunks plan_chunks(int64_t N) {
+    const int64_t npad = (N + 255) / 256 * 256;
+    if (npad <= 1024) return PlanChunks{1, 30};
+    return PlanChunks{(int32_t)((npad + 1023) / 1024), 10};
+}
 // Steps the planned kernel may read past the last step of the storage (values unused).
 int plan_slack_steps();
 

@@ -44,6 +44,7 @@ constexpr int kMaxStripBlocks = 1024;  // row-blocks per strip (their blk_ptr sl
 constexpr int kRing = 4;               // steps of operands in flight per wavefront, canonical kernel
 constexpr int kPlanRing = 16;          // the same for the planned kernel: 8 wavefronts x 16 steps x 1.25 KiB
                                        // in flight per compute unit cover the L2 latency of the operand stream
+constexpr int kChunkedAcc = 4;         // 16-row accumulator fragments per wavefront carried across column chunks
 constexpr int kMaxStripGroups = 128;   // groups of kPlanWaves row-blocks per strip of the planned kernel
 
 // Distance in LDS between the 16-token sub-tiles of a workgroup's X tile: a constant, so that
@@ -80,11 +81,12 @@ extern __shared__ __attribute__((aligned(16))) uint8_t smem_x[];
 // Copy the workgroup's X tile into LDS, transposed.  Unit of work = 4 columns x 4 tokens per
 // lane (four 8-byte loads, a 4x4 transpose of 16-bit values in registers, four 8-byte LDS
 // stores); all the loads of a batch are issued before the first store so their latencies overlap.
+// The tile holds columns [col0, col0 + width) of X (width a multiple of 4), at LDS columns 0 .. width-1.
 template <int NSUB>
-__device__ __forceinline__ void stage_x_tile(const uint16_t *__restrict__ X, int64_t T, int64_t N, int32_t npad,
-                                             int64_t t0) {
+__device__ __forceinline__ void stage_x_chunk(const uint16_t *__restrict__ X, int64_t T, int64_t N, int32_t col0,
+                                              int32_t width, int64_t t0) {
     constexpr int kBatch = 4;
-    const int cquads = npad >> 2;
+    const int cquads = width >> 2;
     const int units = cquads * (4 * NSUB);
     for (int u0 = threadIdx.x; u0 < units; u0 += blockDim.x * kBatch) {
         uint2 a[kBatch][4];
@@ -96,8 +98,9 @@ __device__ __forceinline__ void stage_x_tile(const uint16_t *__restrict__ X, int
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int64_t t = t0 + 4 * tq + i;
-                a[k][i] = (u < units && t < T && c < N) ? *reinterpret_cast<const uint2 *>(X + t * N + c)
-                                                        : make_uint2(0u, 0u);
+                a[k][i] = (u < units && t < T && col0 + c < N)
+                              ? *reinterpret_cast<const uint2 *>(X + t * N + col0 + c)
+                              : make_uint2(0u, 0u);
             }
         }
 #pragma unroll
@@ -123,6 +126,12 @@ __device__ __forceinline__ void stage_x_tile(const uint16_t *__restrict__ X, int
             *reinterpret_cast<uint2 *>(dst + 24 * 32) = w;
         }
     }
+}
+
+template <int NSUB>
+__device__ __forceinline__ void stage_x_tile(const uint16_t *__restrict__ X, int64_t T, int64_t N, int32_t npad,
+                                             int64_t t0) {
+    stage_x_chunk<NSUB>(X, T, N, 0, npad, t0);
 }
 
 // This wavefront's share of the strip: a contiguous run [b_lo, b_hi) of row-blocks holding about
@@ -453,6 +462,140 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
     }
 }
 
+// Layers wider than one LDS tile (more than 1024 input columns): the workgroup keeps the 64-token
+// tile, walks the input columns chunk by chunk (1024 columns of X in LDS at a time) and carries the
+// accumulators of all its row-blocks across the chunks, so the operand stream is read once per
+// 64 tokens whatever the layer width.  The plan stores wavefront w's steps chunk-major (all its
+// row-blocks' steps of chunk 0, then chunk 1, ...; entry q * NG + g of its pointer row), so inside a
+// chunk the steps of the strip's groups are contiguous.  A wavefront owns up to MAXG row-blocks (one
+// per group of the strip); which accumulator set a step feeds is a wavefront-uniform branch.
+template <int DT, int NFRAG>
+__global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_chunked_kernel(
+    const uint16_t *__restrict__ X, int64_t T, int64_t M, int64_t N, int32_t R, int32_t npad,
+    const int32_t *__restrict__ wptr, const uint32_t *__restrict__ wfrag, const uint32_t *__restrict__ xoff,
+    const void *__restrict__ bias, void *__restrict__ Y, int32_t ntiles, int32_t groups_per_strip, int32_t NG,
+    int32_t B, int32_t nchunks, int32_t max_step) {
+    constexpr int NSUB = 4;
+    constexpr int MAXG = kChunkedAcc / NFRAG;
+    constexpr int RING = kPlanRing / NFRAG;
+    static_assert(RING % 2 == 0, "the X fragment ping-pong needs an even ring");
+    const int tile = blockIdx.x % ntiles, strip = blockIdx.x / ntiles;
+    const int64_t t0 = (int64_t)tile * (16 * NSUB);
+    const int g0 = strip * groups_per_strip;
+    const int ng = min(min(groups_per_strip, MAXG), NG - g0);
+    const int lane = threadIdx.x & 63;
+    const int l16 = lane & 15, G = lane >> 4;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int32_t *my = wptr + (int64_t)wave * ((int64_t)nchunks * NG + 1);
+
+    f32x4 acc[MAXG][NFRAG][NSUB];
+#pragma unroll
+    for (int gi = 0; gi < MAXG; ++gi) clear_acc(acc[gi]);
+    uint4 ra[RING][NFRAG];
+    uint32_t rx[RING];
+    uint4 xb[2][NSUB];
+    auto issue_reads = [&](uint32_t w, uint4 (&dst)[NSUB]) {
+        const uint32_t o1 = (w & 0xffffu) << 3, o2 = (w >> 13) & 0x7fff8u;  // packed in units of 8 bytes
+#pragma unroll
+        for (int u = 0; u < NSUB; ++u) {
+            const uint2 lo = tr_read(smem_x + u * sub_stride<NSUB>(), o1);
+            const uint2 hi = tr_read(smem_x + u * sub_stride<NSUB>(), o2);
+            dst[u] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+        }
+    };
+    auto load_frag = [&](const uint32_t *q) { return make_uint4(q[0], q[64], q[128], q[192]); };
+
+    for (int q = 0; q < nchunks; ++q) {
+        // the wavefront's step range of this chunk and where each of its row-blocks ends
+        const int32_t *ent = my + (int64_t)q * NG + g0;
+        int gs = __builtin_amdgcn_readfirstlane(ent[0]);
+        int ends[MAXG];
+#pragma unroll
+        for (int gi = 0; gi < MAXG; ++gi) ends[gi] = __builtin_amdgcn_readfirstlane(ent[min(gi + 1, ng)]);
+        int gs_hi = ends[MAXG - 1];
+        // a malformed plan must not drive the operand pointers out of the buffer
+        gs = max(gs, 0);
+        gs_hi = min(gs_hi, max_step);
+        const bool work = gs < gs_hi;
+        const uint32_t *wp = wfrag + (int64_t)gs * (NFRAG * 256) + lane;
+        const uint32_t *xp = xoff + (int64_t)gs * 64 + lane;
+        if (work) {  // operands of the first RING steps travel while the chunk of X is copied in
+#pragma unroll
+            for (int j = 0; j < RING; ++j) {
+#pragma unroll
+                for (int f = 0; f < NFRAG; ++f) ra[j][f] = load_frag(wp + (j * NFRAG + f) * 256);
+                rx[j] = xp[j * 64];
+            }
+        }
+        __syncthreads();  // every wavefront is done with the previous chunk of X
+        stage_x_chunk<NSUB>(X, T, N, q << 10, min(1024, npad - (q << 10)), t0);
+        __syncthreads();
+        if (!work) continue;  // no barrier below this line inside the chunk
+
+        int grp = 0;
+        auto end_of = [&](int g) {
+            int e = ends[0];
+#pragma unroll
+            for (int gi = 1; gi < MAXG; ++gi) e = g == gi ? ends[gi] : e;
+            return e;
+        };
+        int blk_end = ends[0];
+        while (blk_end <= gs && grp < MAXG - 1) blk_end = end_of(++grp);
+        issue_reads(rx[0], xb[0]);
+        bool done = false;
+        while (!done) {
+#pragma unroll
+            for (int j = 0; j < RING; ++j) {
+                issue_reads(rx[(j + 1) % RING], xb[(j + 1) & 1]);
+                __builtin_amdgcn_sched_barrier(0);
+                auto fma_into = [&](f32x4 (&a)[NFRAG][NSUB]) {
+#pragma unroll
+                    for (int u = 0; u < NSUB; ++u)
+#pragma unroll
+                        for (int f = 0; f < NFRAG; ++f) a[f][u] = mfma16<DT>(ra[j][f], xb[j & 1][u], a[f][u]);
+                };
+                if constexpr (MAXG == 1) {
+                    fma_into(acc[0]);
+                } else if constexpr (MAXG == 2) {
+                    if (grp == 0) fma_into(acc[0]); else fma_into(acc[1]);
+                } else {
+                    static_assert(MAXG == 4, "accumulator sets per wavefront");
+                    if (grp < 2) {
+                        if (grp == 0) fma_into(acc[0]); else fma_into(acc[1]);
+                    } else {
+                        if (grp == 2) fma_into(acc[2]); else fma_into(acc[3]);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int f = 0; f < NFRAG; ++f) ra[j][f] = load_frag(wp + ((RING + j) * NFRAG + f) * 256);
+                rx[j] = xp[(RING + j) * 64];
+                ++gs;
+                if (gs >= blk_end) {  // uniform
+                    if (gs >= gs_hi) {
+                        done = true;
+                        break;
+                    }
+                    while (blk_end <= gs && grp < MAXG - 1) blk_end = end_of(++grp);
+                }
+            }
+            wp += RING * NFRAG * 256;
+            xp += RING * 64;
+        }
+    }
+
+    Epilogue<DT, NFRAG, NSUB> ep;
+    ep.init(Y, bias, T, M, R, t0, l16, G);
+#pragma unroll
+    for (int gi = 0; gi < MAXG; ++gi) {
+        const int64_t blk = (int64_t)kPlanWaves * (g0 + gi) + wave;
+        if (gi < ng && blk < B) {
+            ep.load_bias(blk);
+            ep.write_block(blk, acc[gi]);
+        }
+    }
+}
+
 template <typename K>
 int raise_lds_limit(K kern, size_t lds, size_t &configured) {
     if (lds <= configured) return BSP_OK;
@@ -502,8 +645,34 @@ int launch(const TiledArgs &a, int waves, hipStream_t s) {
     return check_launch();
 }
 
+template <int DT, int NFRAG>
+int launch_chunked(const TiledArgs &a, hipStream_t s) {
+    constexpr int MAXG = kChunkedAcc / NFRAG;
+    const size_t lds = 4 * (size_t)sub_stride<4>();
+    static thread_local size_t configured = 0;
+    auto kern = linear_tiled_chunked_kernel<DT, NFRAG>;
+    int st = raise_lds_limit(kern, lds, configured);
+    if (st != BSP_OK) return st;
+    const int64_t ntiles = (a.T + 63) / 64;
+    const int64_t NG = (a.B + kPlanWaves - 1) / kPlanWaves;
+    // as many row-blocks per wavefront as the accumulators allow, unless that leaves compute units idle
+    int64_t gps = NG * ntiles / 256;
+    gps = gps < 1 ? 1 : (gps > MAXG ? MAXG : gps);
+    const int64_t nstrips = (NG + gps - 1) / gps;
+    if (ntiles * nstrips >= ((int64_t)1 << 31)) return BSP_ERR_SHAPE;
+    const PlanChunks ch = plan_chunks(a.N);
+    const int64_t max_step = a.plan_steps - plan_slack_steps();
+    if (max_step < 0 || max_step > INT32_MAX) return BSP_ERR_CAPACITY;
+    kern<<<dim3((unsigned)(ntiles * nstrips)), dim3(kPlanWaves * 64), lds, s>>>(
+        a.X, a.T, a.M, a.N, a.R, a.npad, a.wptr, (const uint32_t *)a.wfrag, a.xoff, a.bias, a.Y, (int32_t)ntiles,
+        (int32_t)gps, (int32_t)NG, (int32_t)a.B, ch.n, (int32_t)max_step);
+    return check_launch();
+}
+
 template <int DT, int NFRAG, bool PLAN>
 int launch_nsub(const TiledArgs &a, int waves, hipStream_t s) {
+    if constexpr (PLAN)
+        if (a.npad > 1024) return launch_chunked<DT, NFRAG>(a, s);
     // the X tile must fit the 160 KiB of LDS: 64 tokens up to 1024 columns, 32 up to 2048, 16 up to 4096
     if (a.npad <= 1024) return launch<DT, NFRAG, 4, PLAN>(a, waves, s);
     if (a.npad <= 2048) return launch<DT, NFRAG, 2, PLAN>(a, waves, s);

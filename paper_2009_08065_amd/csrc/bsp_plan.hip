@@ -25,162 +25,203 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kMaxKp = 4096 + 32;
+constexpr int kMaxChunk = 1024 + 32;  // kept columns of one row-block inside one column chunk, padded
 
 __device__ __forceinline__ int slot_index(int set, int group) {
     // sets 4s .. 4s+3 of step s are what {first, second} read x {lower, upper} half-wavefront touch
     return 32 * (set >> 2) + ((set >> 1) & 1) * 16 + (set & 1) * 4 + (group >> 2) * 8 + (group & 3);
 }
 
-// One workgroup of 16 wavefronts: wavefront w scans the step counts of its blocks.
-__global__ __launch_bounds__(kPlanWaves * 64) void plan_scan_kernel(const int32_t *__restrict__ blk_ptr, int32_t B,
-                                                                    int32_t NG, int64_t capacity_cols,
+// Steps of every (row-block, column chunk): ceil(kept columns of the block inside the chunk / 32).
+// One workgroup per row-block; the result goes to steps_bq[b * kPlanMaxChunks + q].
+__global__ __launch_bounds__(kThreads) void plan_count_kernel(const int32_t *__restrict__ blk_cnt,
+                                                              const int32_t *__restrict__ blk_ptr,
+                                                              const int32_t *__restrict__ col_idx,
+                                                              int64_t capacity_cols, int32_t chunk_shift,
+                                                              int32_t nchunks, int32_t *__restrict__ steps_bq) {
+    __shared__ int cnt[kPlanMaxChunks];
+    const int64_t b = blockIdx.x;
+    const int base = blk_ptr[b];
+    const int kp = blk_ptr[b + 1] - base;
+    const int kb = blk_cnt[b];
+    if (threadIdx.x < kPlanMaxChunks) cnt[threadIdx.x] = 0;
+    __syncthreads();
+    const bool ok = kp > 0 && kp <= kMaxKp && kb >= 0 && kb <= kp && base >= 0 && (int64_t)base + kp <= capacity_cols;
+    if (ok)
+        for (int i = threadIdx.x; i < kb; i += kThreads) {
+            const int q = col_idx[base + i] >> chunk_shift;
+            if (q >= 0 && q < nchunks) atomicAdd(&cnt[q], 1);
+        }
+    __syncthreads();
+    if (threadIdx.x < kPlanMaxChunks) steps_bq[b * kPlanMaxChunks + threadIdx.x] = (cnt[threadIdx.x] + 31) >> 5;
+}
+
+// One workgroup of kPlanWaves wavefronts: wavefront w scans the step counts of its blocks in
+// stream order (chunk-major: all its blocks' steps of chunk 0, then chunk 1, ...).
+__global__ __launch_bounds__(kPlanWaves * 64) void plan_scan_kernel(const int32_t *__restrict__ steps_bq, int32_t B,
+                                                                    int32_t NG, int32_t nchunks, int64_t cap_steps,
                                                                     int32_t slack_steps, int32_t *__restrict__ wptr,
                                                                     uint32_t *__restrict__ xoff) {
     __shared__ int totals[kPlanWaves];
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    int32_t *mine = wptr + (int64_t)w * (NG + 1);
+    const int E = nchunks * NG;  // entries of a stream: (chunk q, group g) at q * NG + g
+    int32_t *mine = wptr + (int64_t)w * (E + 1);
     int carry = 0;
-    for (int gbase = 0; gbase < NG; gbase += 64) {
-        const int g = gbase + lane;
+    for (int ebase = 0; ebase < E; ebase += 64) {
+        const int e = ebase + lane;
+        const int q = e / NG, g = e % NG;
         const int64_t b = (int64_t)kPlanWaves * g + w;
-        int st = 0;
-        if (g < NG && b < B) {
-            const int kp = blk_ptr[b + 1] - blk_ptr[b];
-            st = kp > 0 ? kp >> 5 : 0;
-        }
+        const int st = (e < E && b < B) ? steps_bq[b * kPlanMaxChunks + q] : 0;
         int incl = st;
 #pragma unroll
         for (int o = 1; o < 64; o <<= 1) {
             const int up = __shfl_up(incl, o, 64);
             if (lane >= o) incl += up;
         }
-        if (g < NG) mine[g] = carry + incl - st;
+        if (e < E) mine[e] = carry + incl - st;
         carry += __shfl(incl, 63, 64);
     }
     if (lane == 0) {
-        mine[NG] = carry;
+        mine[E] = carry;
         totals[w] = carry;
     }
     __syncthreads();
     int wbase = 0;
     for (int k = 0; k < w; ++k) wbase += totals[k];
     __syncthreads();  // the stores above are visible to the whole workgroup now
-    for (int g = lane; g <= NG; g += 64) mine[g] += wbase;
+    for (int e = lane; e <= E; e += 64) mine[e] += wbase;
     // the layer kernel reads a few steps past the end of the last stream: give those steps the
     // LDS offset 0 (their values are never used, but the addresses must be valid)
     if (w == kPlanWaves - 1) {
         const int64_t total = (int64_t)wbase + carry;
-        if ((total << 5) <= capacity_cols)
+        if (total + slack_steps <= cap_steps)
             for (int i = lane; i < slack_steps * 64; i += 64) xoff[total * 64 + i] = 0u;
     }
 }
 
-__global__ __launch_bounds__(kThreads) void plan_fill_kernel(int32_t R, int32_t nfrag, int32_t NG,
-                                                             const int32_t *__restrict__ blk_cnt,
+// One workgroup per row-block: order the kept columns of every chunk and write the steps.
+__global__ __launch_bounds__(kThreads) void plan_fill_kernel(int32_t R, int32_t nfrag, int32_t NG, int32_t chunk_shift,
+                                                             int32_t nchunks, const int32_t *__restrict__ blk_cnt,
                                                              const int32_t *__restrict__ blk_ptr,
                                                              const int32_t *__restrict__ col_idx,
                                                              const uint16_t *__restrict__ vals, int64_t capacity_cols,
-                                                             const int32_t *__restrict__ wptr,
+                                                             int64_t cap_steps, const int32_t *__restrict__ wptr,
                                                              uint32_t *__restrict__ wfrag, uint32_t *__restrict__ xoff) {
     // columns and canonical positions are below 4096 + 32: 16 bits each; 0xffff marks a pad
-    __shared__ uint16_t slotcol[kMaxKp], slotsrc[kMaxKp], ovfcol[kMaxKp], ovfsrc[kMaxKp];
-    __shared__ int s_filled[8], s_hp[9], s_novf;
+    __shared__ uint16_t cols[kMaxKp];
+    __shared__ uint16_t slotcol[kMaxChunk], slotsrc[kMaxChunk], ovfcol[kMaxChunk], ovfsrc[kMaxChunk];
+    __shared__ int s_filled[8], s_hp[9], s_novf, s_cnt[kPlanMaxChunks];
     const int64_t b = blockIdx.x;
     const int base = blk_ptr[b];
     const int kp = blk_ptr[b + 1] - base;
     const int kb = blk_cnt[b];
-    if (kp <= 0 || kp > kMaxKp || (kp & 31) || kb > kp || kb < 0 || (int64_t)base + kp > capacity_cols) return;
-    const int S = kp >> 3;
+    if (kp <= 0 || kp > kMaxKp || kb > kp || kb < 0 || base < 0 || (int64_t)base + kp > capacity_cols) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    // the block's kept columns, fetched once with coalesced loads
-    __shared__ uint16_t cols[kMaxKp];
-    for (int i = threadIdx.x; i < kb; i += kThreads) cols[i] = (uint16_t)col_idx[base + i];
+    const int l16 = lane & 15, G = lane >> 4, qd = (lane >> 2) & 3, p = lane & 3;
+    // the block's kept columns, fetched once with coalesced loads, and their count per chunk
+    if (threadIdx.x < kPlanMaxChunks) s_cnt[threadIdx.x] = 0;
+    __syncthreads();
+    for (int i = threadIdx.x; i < kb; i += kThreads) {
+        const int c = col_idx[base + i];
+        cols[i] = (uint16_t)c;
+        const int q = c >> chunk_shift;
+        if (q >= 0 && q < nchunks) atomicAdd(&s_cnt[q], 1);
+    }
     __syncthreads();
 
-    if (wave == 0) {
-        int cnt[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-        int novf = 0;
-        const uint64_t lt = (1ull << lane) - 1ull;
-        for (int i0 = 0; i0 < kb; i0 += 64) {
-            const int i = i0 + lane;
-            const bool valid = i < kb;
-            const int col = valid ? cols[i] : 0;
-            const int g = (int)lds_bank_group((uint32_t)col);
-            int rank = 0;
+    int lo = 0;  // canonical position of the chunk's first kept column (columns ascend, so chunks are runs)
+    for (int q = 0; q < nchunks; lo += s_cnt[q], ++q) {
+        const int cq = s_cnt[q];
+        if (cq <= 0) continue;  // uniform
+        if (cq > 1024) return;  // malformed storage (duplicate columns): nothing more is written
+        const int nsteps = (cq + 31) >> 5;
+        const int S = nsteps * 4;  // sets of 8 columns
+        const int col0 = q << chunk_shift;
+        __syncthreads();  // the previous chunk's slot arrays are no longer read
+        if (wave == 0) {
+            int cnt[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+            int novf = 0;
+            const uint64_t lt = (1ull << lane) - 1ull;
+            for (int i0 = 0; i0 < cq; i0 += 64) {
+                const int i = i0 + lane;
+                const bool valid = i < cq;
+                const int col = valid ? (int)cols[lo + i] - col0 : 0;  // column inside the chunk
+                const int g = (int)lds_bank_group((uint32_t)col);
+                int rank = 0;
 #pragma unroll
-            for (int gg = 0; gg < 8; ++gg) {
-                const uint64_t m = __ballot(valid && g == gg);
-                if (g == gg) rank = cnt[gg] + __popcll(m & lt);
-                cnt[gg] += __popcll(m);
-            }
-            const bool over = valid && rank >= S;
-            const uint64_t mo = __ballot(over);
-            if (valid && !over) {
-                const int slot = slot_index(rank, g);
-                slotcol[slot] = (uint16_t)col;
-                slotsrc[slot] = (uint16_t)i;
-            } else if (over) {
-                const int oi = novf + __popcll(mo & lt);
-                ovfcol[oi] = (uint16_t)col;
-                ovfsrc[oi] = (uint16_t)i;
-            }
-            novf += __popcll(mo);
-        }
-        if (lane == 0) {
-            int run = 0;
-            for (int g = 0; g < 8; ++g) {
-                const int f = cnt[g] < S ? cnt[g] : S;
-                s_filled[g] = f;
-                s_hp[g] = run;
-                run += S - f;
-            }
-            s_hp[8] = run;
-            s_novf = novf;
-        }
-    }
-    __syncthreads();
-    // gaps: group g lacks a column in sets filled[g] .. S-1; gap e takes overflow column e, else a zero pad
-    const int H = s_hp[8], novf = s_novf;
-    for (int e = threadIdx.x; e < H; e += kThreads) {
-        int g = 0;
-#pragma unroll
-        for (int gg = 1; gg < 8; ++gg)
-            if (s_hp[gg] <= e) g = gg;
-        const int set = s_filled[g] + (e - s_hp[g]);
-        const int slot = slot_index(set, g);
-        if (e < novf) {
-            slotcol[slot] = ovfcol[e];
-            slotsrc[slot] = ovfsrc[e];
-        } else {
-            slotcol[slot] = (uint16_t)(g << 2);  // any column of bank group g; its weight is zero
-            slotsrc[slot] = 0xffffu;
-        }
-    }
-    __syncthreads();
-    // per-lane operands of every step
-    const int l16 = lane & 15, G = lane >> 4, q = (lane >> 2) & 3, p = lane & 3;
-    const int nsteps = kp >> 5;
-    const int64_t gs0 = wptr[(b % kPlanWaves) * (NG + 1) + b / kPlanWaves];
-    if (gs0 < 0 || ((gs0 + nsteps) << 5) > capacity_cols) return;
-    for (int s = wave; s < nsteps; s += kThreads / 64) {
-        const int s1 = 32 * s + 8 * G + q;
-        const uint32_t o1 = lds_col_offset((uint32_t)slotcol[s1], (uint32_t)p);
-        const uint32_t o2 = lds_col_offset((uint32_t)slotcol[s1 + 4], (uint32_t)p);
-        xoff[(gs0 + s) * 64 + lane] = (o1 >> 3) | ((o2 >> 3) << 16);  // offsets are multiples of 8 bytes
-        for (int f = 0; f < nfrag; ++f) {
-            const int r = f * 16 + l16;
-            uint32_t w[4] = {0u, 0u, 0u, 0u};
-            if (r < R) {
-                const uint16_t *row = vals + (int64_t)R * base + (int64_t)r * kp;
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const uint32_t src = slotsrc[32 * s + 8 * G + i];
-                    const uint32_t v = src != 0xffffu ? (uint32_t)row[src] : 0u;
-                    w[i >> 1] |= v << (16 * (i & 1));
+                for (int gg = 0; gg < 8; ++gg) {
+                    const uint64_t m = __ballot(valid && g == gg);
+                    if (g == gg) rank = cnt[gg] + __popcll(m & lt);
+                    cnt[gg] += __popcll(m);
                 }
+                const bool over = valid && rank >= S;
+                const uint64_t mo = __ballot(over);
+                if (valid && !over) {
+                    const int slot = slot_index(rank, g);
+                    slotcol[slot] = (uint16_t)col;
+                    slotsrc[slot] = (uint16_t)(lo + i);
+                } else if (over) {
+                    const int oi = novf + __popcll(mo & lt);
+                    ovfcol[oi] = (uint16_t)col;
+                    ovfsrc[oi] = (uint16_t)(lo + i);
+                }
+                novf += __popcll(mo);
             }
+            if (lane == 0) {
+                int run = 0;
+                for (int g = 0; g < 8; ++g) {
+                    const int f = cnt[g] < S ? cnt[g] : S;
+                    s_filled[g] = f;
+                    s_hp[g] = run;
+                    run += S - f;
+                }
+                s_hp[8] = run;
+                s_novf = novf;
+            }
+        }
+        __syncthreads();
+        // gaps: group g lacks a column in sets filled[g] .. S-1; gap e takes overflow column e, else a zero pad
+        const int H = s_hp[8], novf = s_novf;
+        for (int e = threadIdx.x; e < H; e += kThreads) {
+            int g = 0;
 #pragma unroll
-            for (int k = 0; k < 4; ++k) wfrag[(((gs0 + s) * nfrag + f) * 4 + k) * 64 + lane] = w[k];
+            for (int gg = 1; gg < 8; ++gg)
+                if (s_hp[gg] <= e) g = gg;
+            const int set = s_filled[g] + (e - s_hp[g]);
+            const int slot = slot_index(set, g);
+            if (e < novf) {
+                slotcol[slot] = ovfcol[e];
+                slotsrc[slot] = ovfsrc[e];
+            } else {
+                slotcol[slot] = (uint16_t)(g << 2);  // any column of bank group g; its weight is zero
+                slotsrc[slot] = 0xffffu;
+            }
+        }
+        __syncthreads();
+        // per-lane operands of the chunk's steps
+        const int E = nchunks * NG;
+        const int64_t gs0 = wptr[(b % kPlanWaves) * (E + 1) + q * NG + b / kPlanWaves];
+        if (gs0 < 0 || gs0 + nsteps > cap_steps) return;
+        for (int s = wave; s < nsteps; s += kThreads / 64) {
+            const int s1 = 32 * s + 8 * G + qd;
+            const uint32_t o1 = lds_col_offset((uint32_t)slotcol[s1], (uint32_t)p);
+            const uint32_t o2 = lds_col_offset((uint32_t)slotcol[s1 + 4], (uint32_t)p);
+            xoff[(gs0 + s) * 64 + lane] = (o1 >> 3) | ((o2 >> 3) << 16);  // offsets are multiples of 8 bytes
+            for (int f = 0; f < nfrag; ++f) {
+                const int r = f * 16 + l16;
+                uint32_t w[4] = {0u, 0u, 0u, 0u};
+                if (r < R) {
+                    const uint16_t *row = vals + (int64_t)R * base + (int64_t)r * kp;
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        const uint32_t src = slotsrc[32 * s + 8 * G + i];
+                        const uint32_t v = src != 0xffffu ? (uint32_t)row[src] : 0u;
+                        w[i >> 1] |= v << (16 * (i & 1));
+                    }
+                }
+#pragma unroll
+                for (int k = 0; k < 4; ++k) wfrag[(((gs0 + s) * nfrag + f) * 4 + k) * 64 + lane] = w[k];
+            }
         }
     }
 }
@@ -192,12 +233,14 @@ struct PlanLayout {
     size_t steps, wptr_bytes, wfrag_bytes, xoff_bytes;
     size_t total() const { return wptr_bytes + wfrag_bytes + xoff_bytes; }
 };
+// Sized for the worst case of kPlanMaxChunks column chunks, so that the size does not depend on N:
+// every (row-block, chunk) pads its columns to a multiple of 32 on its own.
 inline PlanLayout plan_layout(int64_t M, int32_t R, int64_t capacity_cols) {
     PlanLayout L;
     const int64_t B = M / R;
     L.NG = (B + kPlanWaves - 1) / kPlanWaves;
-    L.steps = (size_t)((capacity_cols + 31) / 32) + (size_t)plan_slack_steps();
-    L.wptr_bytes = ((size_t)kPlanWaves * (size_t)(L.NG + 1) * sizeof(int32_t) + 255) / 256 * 256;
+    L.steps = (size_t)((capacity_cols + 31) / 32) + (size_t)B * (kPlanMaxChunks - 1) + (size_t)plan_slack_steps();
+    L.wptr_bytes = ((size_t)kPlanWaves * (size_t)(kPlanMaxChunks * L.NG + 1) * sizeof(int32_t) + 255) / 256 * 256;
     L.wfrag_bytes = L.steps * (size_t)nfrag_of(R) * 1024;
     L.xoff_bytes = L.steps * 256;
     return L;
@@ -233,11 +276,19 @@ extern "C" int bsp_linear_plan(int vdt, int64_t M, int64_t N, int32_t R, int32_t
     uint32_t *wfrag = (uint32_t *)((uint8_t *)plan + L.wptr_bytes);
     uint32_t *xoff = (uint32_t *)((uint8_t *)plan + L.wptr_bytes + L.wfrag_bytes);
     hipStream_t s = (hipStream_t)stream;
-    plan_scan_kernel<<<1, kPlanWaves * 64, 0, s>>>(blk_ptr, (int32_t)B, (int32_t)L.NG, capacity_cols,
+    const PlanChunks ch = plan_chunks(N);
+    // step counts per (row-block, chunk) are parked at the start of the offsets region: the scan has
+    // consumed them before the fill kernel overwrites that region
+    int32_t *steps_bq = (int32_t *)xoff;
+    if ((size_t)B * kPlanMaxChunks * sizeof(int32_t) > L.xoff_bytes) return BSP_ERR_CAPACITY;
+    plan_count_kernel<<<(unsigned)B, kThreads, 0, s>>>(blk_cnt, blk_ptr, col_idx, capacity_cols, ch.shift, ch.n,
+                                                       steps_bq);
+    plan_scan_kernel<<<1, kPlanWaves * 64, 0, s>>>(steps_bq, (int32_t)B, (int32_t)L.NG, ch.n, (int64_t)L.steps,
                                                    plan_slack_steps(), wptr, xoff);
     if (capacity_cols > 0)
-        plan_fill_kernel<<<(unsigned)B, kThreads, 0, s>>>(R, nf, (int32_t)L.NG, blk_cnt, blk_ptr, col_idx,
-                                                          (const uint16_t *)vals, capacity_cols, wptr, wfrag, xoff);
+        plan_fill_kernel<<<(unsigned)B, kThreads, 0, s>>>(R, nf, (int32_t)L.NG, ch.shift, ch.n, blk_cnt, blk_ptr,
+                                                          col_idx, (const uint16_t *)vals, capacity_cols,
+                                                          (int64_t)L.steps, wptr, wfrag, xoff);
     return check_launch();
 }
 
@@ -257,6 +308,7 @@ extern "C" int bsp_linear_planned(const void *X, int xdt, int64_t T, int64_t M, 
     a.wptr = (const int32_t *)plan;
     a.wfrag = (const uint8_t *)plan + L.wptr_bytes;
     a.xoff = (const uint32_t *)((const uint8_t *)plan + L.wptr_bytes + L.wfrag_bytes);
+    a.plan_steps = (int64_t)L.steps;
     a.bias = bias;
     a.Y = Y;
     return launch_linear_tiled(a, true, (hipStream_t)stream);

@@ -228,6 +228,38 @@ def test_linear_small_shapes(dtype, k_align, R, T, M, N, p_keep):
     run_layer(d["X"], d["W"], None, R, keep, k_align, dtype)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("R,T,M,N,p_keep", [(16, 150, 272, 2304, 0.2), (16, 64, 48, 1032, 0.5), (32, 70, 160, 4096, 0.1),
+                                            (64, 33, 192, 3000, 0.3), (8, 129, 136, 1280, 0.25)])
+def test_linear_wide_layers_in_column_chunks(dtype, R, T, M, N, p_keep):
+    # more than 1024 input columns: the planned path walks X in chunks of 1024 columns (the last one
+    # ragged) and carries several row-blocks per wavefront across the chunks
+    d = wl.layer(R * 7 + N, T, M, N, dtype)
+    B = M // R
+    keep = wl.bernoulli_keep_mask(T + N + 1, B, N, p_keep)
+    keep[0, :] = 0                                      # nothing kept
+    keep[1, :] = 1                                      # dense
+    keep[2, :1024] = 0                                  # first chunk empty
+    if B > 3:
+        keep[3, 1024:] = 0                              # only the first chunk
+    if B > 4:
+        keep[4, :] = 0
+        keep[4, 1023:1025] = 1                          # one column on each side of a chunk border
+    run_layer(d["X"], d["W"], d["bias"], R, keep, 32, dtype)
+    run_layer(d["X"], d["W"], None, R, keep, 64, dtype)
+
+
+def test_linear_wide_layer_many_tokens_ragged_strips():
+    # enough token tiles that every wavefront carries 4 row-blocks across the chunks; 133 row-blocks
+    # leave the last strip with one group and that group with 5 of its 8 row-blocks
+    R, T, M, N = 16, 4100, 2128, 2304
+    d = wl.layer(991, T, M, N, "bf16")
+    keep = wl.bernoulli_keep_mask(992, M // R, N, 0.2)
+    keep[5, :] = 0
+    keep[130, 1024:2048] = 0
+    run_layer(d["X"], d["W"], d["bias"], R, keep, 32, "bf16", T_rows=[(0, 70), (2040, 2060), (4090, 4100)])
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_linear_keep_all_is_dense_gemm_keep_none_is_bias(dtype):
     d = wl.layer(77, 96, 64, 160, dtype)
