@@ -125,110 +125,165 @@ __global__ __launch_bounds__(kThreads) void mask_rank_block_kernel(const float *
 }
 
 // ------------------------------------------------------------------ percentile, matrix scope
-constexpr int kBits0 = 11, kBits2 = 10;  // digits: 11, 11, 10 bits
-constexpr int kBins = 2048;  // per-pass stride in the global histogram
-constexpr int kStage = kBins + kBins / 32;  // LDS copy of one histogram, padded
+// Three digits of 11 / 11 / 10 bits, one launch per digit plus the launch that writes the mask.
+// Workgroups never talk to each other inside a launch: each one histograms its slice of the array in
+// LDS and stores the histogram (2048 fine counters plus 64 coarse sums of 32 counters each) to its own
+// slot of the workspace with plain stores.  The next launch starts, in every workgroup, by locating
+// the digit that holds the wanted rank: it adds up the coarse sums of all slots, picks the coarse bin,
+// adds up that bin's 32 fine counters, picks the fine bin.  That costs each workgroup two short
+// dependent reads instead of a chip-wide atomic histogram and a last-workgroup election, needs no
+// zeroed memory, and is deterministic (integer sums).
+constexpr int kSelThreads = 1024;
+constexpr int kBins = 2048;     // fine counters per digit (the 10-bit digit uses the lower half)
+constexpr int kCoarse = 64;     // coarse sums per digit
+constexpr int kSlot = kBins + kCoarse;
+constexpr int kMaxSlots = 256;  // workgroups of a histogram launch
+constexpr int kStateWords = 16; // state[k] = {key bits fixed after k digits, rank wanted inside them}, k = 1..3
 
 __device__ __forceinline__ int pass_shift(int pass) { return pass == 0 ? 21 : (pass == 1 ? 10 : 0); }
-__device__ __forceinline__ int pass_bits(int pass) { return pass == 2 ? kBits2 : kBits0; }
-
-// Workspace of the matrix-scope select: three global histograms, then the state words.
-constexpr int kStatePrefix = 3 * kBins;      // key bits fixed so far
-constexpr int kStateWant = 3 * kBins + 1;    // rank still wanted inside the current prefix
-constexpr int kStateDone = 3 * kBins + 2;    // [3] workgroups that have flushed their histogram, per pass
-constexpr int kWsWords = 3 * kBins + 8;
-
-__global__ __launch_bounds__(kThreads) void mask_rank_init_kernel(uint32_t *ws, uint32_t P) {
-    const int i = blockIdx.x * kThreads + threadIdx.x;
-    if (i < kWsWords) ws[i] = i == kStateWant ? P : 0u;
+__device__ __forceinline__ int pass_bits(int pass) { return pass == 2 ? 10 : 11; }
+__device__ __forceinline__ const uint32_t *slots_of(const uint32_t *ws, int pass, int G) {
+    return ws + kStateWords + (size_t)(pass & 1) * G * kSlot;  // digits alternate between two slot arrays
 }
 
-// One digit of the select.  Every workgroup histograms its share in LDS and adds the non-empty
-// bins to the pass's global histogram; the workgroup that finishes last (a ticket counter tells)
-// locates the bin holding the wanted rank and publishes the longer prefix for the next launch.
-__global__ __launch_bounds__(kThreads) void mask_rank_hist_kernel(const float *__restrict__ s, int64_t n, int pass,
-                                                                  uint32_t *__restrict__ ws) {
-    __shared__ uint32_t hist[kStage];
-    __shared__ int s_last;
-    const uint32_t prefix = ws[kStatePrefix];
-    for (int i = threadIdx.x; i < kBins; i += kThreads) hist[i] = 0;
-    __syncthreads();
-    const int shift = pass_shift(pass);
-    const uint32_t dmask = (1u << pass_bits(pass)) - 1u;
-    const int hi = shift + pass_bits(pass);  // bits above the digit must match the prefix
-    const int64_t stride = (int64_t)gridDim.x * kThreads * 4;
-    const bool vec = (reinterpret_cast<uintptr_t>(s) & 15) == 0;
-    for (int64_t i = ((int64_t)blockIdx.x * kThreads + threadIdx.x) * 4; i < n; i += stride) {
-        float v[4];
-        int cnt = 4;
-        if (vec && i + 3 < n) {
-            float4 q = *reinterpret_cast<const float4 *>(s + i);
-            v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
-        } else {
-            cnt = (int)((n - i) < 4 ? (n - i) : 4);
-            for (int e = 0; e < cnt; ++e) v[e] = s[i + e];
-        }
-        for (int e = 0; e < 4; ++e) {
-            const uint32_t key = to_key(e < cnt ? v[e] : 0.0f);
-            const bool in = e < cnt && (pass == 0 || (key >> hi) == (prefix >> hi));
-            const uint32_t digit = (key >> shift) & dmask;
-            if (pass == 0) {
-                // The leading digit (sign, exponent, top mantissa bits) takes only a handful of values:
-                // lanes with equal digits elect one lane that adds their count, instead of up to 64
-                // serialized LDS atomics on one address.
-                uint64_t todo = __ballot(in);
-                while (todo) {
-                    const int leader = __ffsll((long long)todo) - 1;
-                    const uint32_t dl = (uint32_t)__builtin_amdgcn_readlane((int)digit, leader);  // leader is uniform
-                    const uint64_t same = __ballot(in && digit == dl);
-                    if ((int)(threadIdx.x & (kWave - 1)) == leader) atomicAdd(&hist[dl], (uint32_t)__popcll(same));
-                    todo &= ~same;
-                }
-            } else if (in) {
-                atomicAdd(&hist[digit], 1u);
-            }
-        }
+// Every workgroup of the launch after digit d's histogram: find digit d of the wanted element.
+// Returns (in all threads) the key bits fixed so far and the rank wanted among the keys that share them.
+__device__ __forceinline__ void resolve_digit(const uint32_t *__restrict__ ws, int d, int G, uint32_t P,
+                                              uint32_t &prefix, uint32_t &want) {
+    __shared__ uint32_t sh_coarse[kCoarse], sh_fine[32], sh_out[2];
+    const uint32_t *slots = slots_of(ws, d, G);
+    uint32_t prev_prefix = 0, prev_want = P;
+    if (d > 0) {  // written by workgroup 0 of the previous launch
+        prev_prefix = ws[2 * d];
+        prev_want = ws[2 * d + 1];
     }
+    if (threadIdx.x < kCoarse) sh_coarse[threadIdx.x] = 0;
+    if (threadIdx.x < 32) sh_fine[threadIdx.x] = 0;
     __syncthreads();
-    uint32_t *g = ws + pass * kBins;
-    // Device-scope atomics are performed at the memory side, coherent across the chip's L2s.  The
-    // additions return their old value and the ticket is taken only after every lane has its
-    // returns, so the workgroup that draws the last ticket knows that all additions have landed;
-    // no fence is used (a release fence would write back the whole L2 on this multi-L2 part).
-    uint32_t seen = 0;
-    for (int i = threadIdx.x; i < kBins; i += kThreads) {
-        const uint32_t c = hist[i];
-        if (c) seen |= atomicAdd(&g[i], c);
+    {
+        const int c = threadIdx.x & (kCoarse - 1);
+        uint32_t sum = 0;
+        for (int g = threadIdx.x / kCoarse; g < G; g += kSelThreads / kCoarse) sum += slots[(size_t)g * kSlot + kBins + c];
+        if (sum) atomicAdd(&sh_coarse[c], sum);
     }
-    __shared__ uint32_t s_sink[kThreads / kWave];
-    if ((threadIdx.x & (kWave - 1)) == 0) s_sink[threadIdx.x / kWave] = seen;  // needs the returns
-    __syncthreads();
-    if (threadIdx.x == 0) s_last = atomicAdd(&ws[kStateDone + pass], 1u) == gridDim.x - 1;
-    __syncthreads();
-    if (!s_last) return;
-    const int nb = 1 << pass_bits(pass);
-    for (int i = threadIdx.x; i < nb; i += kThreads)
-        hist[i + (i >> 5)] = __hip_atomic_load(&g[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // read at the memory side
     __syncthreads();
     if (threadIdx.x < kWave) {
         uint32_t bin, rank;
-        locate_rank<true>(hist, nb, __hip_atomic_load(&ws[kStateWant], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT), bin, rank);
+        locate_rank<false>(sh_coarse, kCoarse, prev_want, bin, rank);
         if (threadIdx.x == 0) {
-            __hip_atomic_store(&ws[kStatePrefix], prefix | (bin << shift), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(&ws[kStateWant], rank, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            sh_out[0] = bin;
+            sh_out[1] = rank;
         }
+    }
+    __syncthreads();
+    const uint32_t cb = sh_out[0], want_c = sh_out[1];
+    {
+        const int f = threadIdx.x & 31;
+        uint32_t sum = 0;
+        for (int g = threadIdx.x / 32; g < G; g += kSelThreads / 32) sum += slots[(size_t)g * kSlot + cb * 32 + f];
+        if (sum) atomicAdd(&sh_fine[f], sum);
+    }
+    __syncthreads();
+    if (threadIdx.x < kWave) {
+        const int lane = threadIdx.x;
+        const uint32_t mine = lane < 32 ? sh_fine[lane] : 0u;
+        uint32_t incl = mine;
+#pragma unroll
+        for (int o = 1; o < kWave; o <<= 1) {
+            const uint32_t up = __shfl_up(incl, o, kWave);
+            if (lane >= o) incl += up;
+        }
+        const uint64_t reach = __ballot(lane < 32 && incl >= want_c);
+        const int fb = reach ? (__ffsll((long long)reach) - 1) : 31;
+        const uint32_t before = __shfl(incl - mine, fb, kWave);
+        if (lane == 0) {
+            sh_out[0] = prev_prefix | ((cb * 32 + (uint32_t)fb) << pass_shift(d));
+            sh_out[1] = want_c - before;
+        }
+    }
+    __syncthreads();
+    prefix = sh_out[0];
+    want = sh_out[1];
+    __syncthreads();  // sh_out may be reused by a later call
+}
+
+// Histogram of digit PASS over the keys that share the digits found so far.
+template <int PASS>
+__global__ __launch_bounds__(kSelThreads) void mask_rank_hist_kernel(const float *__restrict__ s, int64_t n,
+                                                                     int64_t per_wg, uint32_t P,
+                                                                     uint32_t *__restrict__ ws) {
+    // The leading digit (sign, exponent, two mantissa bits) takes only a handful of values, so its LDS
+    // counters are kept in 4 copies picked by the lane: fewer lanes collide on one address.
+    constexpr int COPIES = PASS == 0 ? 4 : 1;
+    __shared__ uint32_t hist[kBins * COPIES];
+    const int G = gridDim.x;
+    uint32_t prefix = 0, want = P;
+    if constexpr (PASS > 0) {
+        resolve_digit(ws, PASS - 1, G, P, prefix, want);
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            ws[2 * PASS] = prefix;
+            ws[2 * PASS + 1] = want;
+        }
+    }
+    for (int i = threadIdx.x; i < kBins * COPIES; i += kSelThreads) hist[i] = 0;
+    __syncthreads();
+    constexpr int shift = PASS == 0 ? 21 : (PASS == 1 ? 10 : 0);
+    constexpr int bits = PASS == 2 ? 10 : 11;
+    constexpr int hi = shift + bits;  // bits above the digit must match the prefix
+    const int64_t lo = (int64_t)blockIdx.x * per_wg;  // per_wg is a multiple of 4
+    const int64_t end = lo + per_wg < n ? lo + per_wg : n;
+    const bool vec = (reinterpret_cast<uintptr_t>(s) & 15) == 0;
+    const uint32_t copy = COPIES > 1 ? (threadIdx.x & (COPIES - 1)) : 0;
+    for (int64_t i = lo + (int64_t)threadIdx.x * 4; i < end; i += kSelThreads * 4) {
+        float v[4];
+        int cnt = 4;
+        if (vec && i + 3 < end) {
+            const float4 q = *reinterpret_cast<const float4 *>(s + i);
+            v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+        } else {
+            cnt = (int)((end - i) < 4 ? (end - i) : 4);
+            for (int e = 0; e < cnt; ++e) v[e] = s[i + e];
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const uint32_t key = to_key(e < cnt ? v[e] : 0.0f);
+            bool in = e < cnt;
+            if constexpr (PASS > 0) in = in && (key >> hi) == (prefix >> hi);
+            const uint32_t digit = (key >> shift) & ((1u << bits) - 1u);
+            if (in) atomicAdd(&hist[digit * COPIES + copy], 1u);
+        }
+    }
+    __syncthreads();
+    uint32_t *slot = ws + kStateWords + (size_t)(PASS & 1) * G * kSlot + (size_t)blockIdx.x * kSlot;
+#pragma unroll
+    for (int k = 0; k < kBins / kSelThreads; ++k) {
+        const int bin = k * kSelThreads + threadIdx.x;
+        uint32_t c = 0;
+#pragma unroll
+        for (int j = 0; j < COPIES; ++j) c += hist[bin * COPIES + j];
+        slot[bin] = c;
+        uint32_t sum = c;  // coarse sum: the 32 lanes of a half-wavefront hold one coarse bin
+#pragma unroll
+        for (int o = 1; o < 32; o <<= 1) sum += __shfl_xor(sum, o, kWave);
+        if ((threadIdx.x & 31) == 0) slot[kBins + (bin >> 5)] = sum;
     }
 }
 
-__global__ __launch_bounds__(kThreads) void mask_rank_apply_kernel(const float *__restrict__ s, int64_t n, int64_t P,
-                                                                   const uint32_t *__restrict__ ws,
-                                                                   uint8_t *__restrict__ keep,
-                                                                   float *__restrict__ t_used) {
-    const float thr = P > 0 ? from_key(ws[kStatePrefix]) : -INFINITY;
+__global__ __launch_bounds__(kSelThreads) void mask_rank_apply_kernel(const float *__restrict__ s, int64_t n,
+                                                                      uint32_t P, int G,
+                                                                      const uint32_t *__restrict__ ws,
+                                                                      uint8_t *__restrict__ keep,
+                                                                      float *__restrict__ t_used) {
+    float thr = -INFINITY;
+    if (P > 0) {
+        uint32_t prefix, want;
+        resolve_digit(ws, 2, G, P, prefix, want);
+        thr = from_key(prefix);
+    }
     if (t_used && blockIdx.x == 0 && threadIdx.x == 0) *t_used = thr;
-    const int64_t stride = (int64_t)gridDim.x * kThreads * 4;
+    const int64_t stride = (int64_t)gridDim.x * kSelThreads * 4;
     const bool vec = ((reinterpret_cast<uintptr_t>(s) | reinterpret_cast<uintptr_t>(keep)) & 15) == 0;
-    for (int64_t i = ((int64_t)blockIdx.x * kThreads + threadIdx.x) * 4; i < n; i += stride) {
+    for (int64_t i = ((int64_t)blockIdx.x * kSelThreads + threadIdx.x) * 4; i < n; i += stride) {
         if (vec && i + 3 < n) {
             float4 q = *reinterpret_cast<const float4 *>(s + i);
             uchar4 k;
@@ -238,6 +293,12 @@ __global__ __launch_bounds__(kThreads) void mask_rank_apply_kernel(const float *
             for (int e = 0; e < 4 && i + e < n; ++e) keep[i + e] = s[i + e] > thr;
         }
     }
+}
+
+// Workgroups of the histogram launches: about 8192 elements each, at most kMaxSlots.
+inline int select_slots(int64_t n) {
+    int64_t g = (n + 8191) / 8192;
+    return (int)(g < 1 ? 1 : (g > kMaxSlots ? kMaxSlots : g));
 }
 
 inline unsigned grid_for_elems(int64_t n, int per_thread, unsigned cap) {
@@ -253,8 +314,8 @@ inline unsigned grid_for_elems(int64_t n, int per_thread, unsigned cap) {
 using namespace bsp;
 
 extern "C" size_t bsp_prune_mask_workspace_bytes(int64_t B, int64_t N, int scope) {
-    (void)B; (void)N;
-    return scope == BSP_SCOPE_MATRIX ? kWsWords * sizeof(uint32_t) : 0;
+    if (scope != BSP_SCOPE_MATRIX || B <= 0 || N <= 0) return 0;
+    return ((size_t)kStateWords + 2 * (size_t)select_slots(B * N) * kSlot) * sizeof(uint32_t);
 }
 
 extern "C" int bsp_prune_mask(const float *sumsq, int64_t B, int64_t N, float t, int64_t n_keep, int scope,
@@ -272,16 +333,20 @@ extern "C" int bsp_prune_mask(const float *sumsq, int64_t B, int64_t N, float t,
         mask_rank_block_kernel<<<(unsigned)B, kThreads, 0, s>>>(sumsq, N, n_keep, keep, t_used);
         return check_launch();
     }
-    const int64_t P = n - n_keep;
-    uint32_t *ghist = (uint32_t *)ws;
+    const int64_t P = n - n_keep > 0 ? n - n_keep : 0;
+    uint32_t *w = (uint32_t *)ws;
+    const int G = select_slots(n);
     if (P > 0) {
         if (!ws) return BSP_ERR_NULL;
         if (ws_bytes < bsp_prune_mask_workspace_bytes(B, N, scope) || !aligned(ws, 4)) return BSP_ERR_CAPACITY;
-        mask_rank_init_kernel<<<(kWsWords + kThreads - 1) / kThreads, kThreads, 0, s>>>(ghist, (uint32_t)P);
-        // few, large workgroups: every one of them ends with atomics on the same hot bins
-        const unsigned g = grid_for_elems(n, 8, 1024);
-        for (int pass = 0; pass < 3; ++pass) mask_rank_hist_kernel<<<g, kThreads, 0, s>>>(sumsq, n, pass, ghist);
+        int64_t per_wg = (n + G - 1) / G;
+        per_wg = (per_wg + 3) / 4 * 4;
+        mask_rank_hist_kernel<0><<<G, kSelThreads, 0, s>>>(sumsq, n, per_wg, (uint32_t)P, w);
+        mask_rank_hist_kernel<1><<<G, kSelThreads, 0, s>>>(sumsq, n, per_wg, (uint32_t)P, w);
+        mask_rank_hist_kernel<2><<<G, kSelThreads, 0, s>>>(sumsq, n, per_wg, (uint32_t)P, w);
     }
-    mask_rank_apply_kernel<<<grid_for_elems(n, 8, 4096), kThreads, 0, s>>>(sumsq, n, P, ghist, keep, t_used);
+    int64_t ga = (n + (int64_t)kSelThreads * 8 - 1) / ((int64_t)kSelThreads * 8);
+    ga = ga < 1 ? 1 : (ga > 1024 ? 1024 : ga);
+    mask_rank_apply_kernel<<<(unsigned)ga, kSelThreads, 0, s>>>(sumsq, n, (uint32_t)P, G, w, keep, t_used);
     return check_launch();
 }

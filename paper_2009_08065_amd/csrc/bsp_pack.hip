@@ -24,7 +24,18 @@ __global__ __launch_bounds__(kThreads) void pack_count_kernel(const uint8_t *__r
     __shared__ int wsum[kWaves];
     const uint8_t *row = keep + (int64_t)blockIdx.x * N;
     int cnt = 0;
-    for (int64_t j = threadIdx.x; j < N; j += kThreads) cnt += row[j] != 0;
+    if (((reinterpret_cast<uintptr_t>(row) | (uintptr_t)N) & 15) == 0) {  // 16 flags per load
+        for (int64_t j = (int64_t)threadIdx.x * 16; j < N; j += kThreads * 16) {
+            const uint4 q = *reinterpret_cast<const uint4 *>(row + j);
+            const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+            for (int k = 0; k < 4; ++k)  // a flag is any non-zero byte: fold each byte onto its low bit
+                cnt += __popc(((w[k] | (w[k] >> 1) | (w[k] >> 2) | (w[k] >> 3) | (w[k] >> 4) | (w[k] >> 5) | (w[k] >> 6) |
+                                (w[k] >> 7)) & 0x01010101u));
+        }
+    } else {
+        for (int64_t j = threadIdx.x; j < N; j += kThreads) cnt += row[j] != 0;
+    }
 #pragma unroll
     for (int o = kWave / 2; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o, kWave);
     if ((threadIdx.x & (kWave - 1)) == 0) wsum[threadIdx.x / kWave] = cnt;
@@ -66,7 +77,8 @@ __global__ __launch_bounds__(kThreads) void pack_scan_kernel(const int32_t *__re
     if (threadIdx.x == 0) blk_ptr[B] = carry;
 }
 
-// One workgroup per row-block.  The keep row is cut into chunks of 64 columns, one wavefront
+// One or more workgroups per row-block (gridDim.y of them share a block when there are few blocks: each
+// takes an equal run of 64-column chunks).  The keep row is cut into chunks of 64 columns, one wavefront
 // ballot each: pass 1 counts the kept columns of every chunk, wavefront 0 scans the counts, pass 2
 // writes each kept column index at (chunk offset + lane prefix) and copies its R values from W
 // straight into the panel.  Reads of a W row touch consecutive columns, panel writes are
@@ -85,6 +97,7 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(const void *__restri
                                                         int32_t *__restrict__ col_idx, void *__restrict__ vals) {
     __shared__ int chunk_off[kMaxChunks + 1];
     __shared__ int s_last;
+    if (threadIdx.x == 0) s_last = -1;
     const int64_t b = blockIdx.x;
     const int64_t base = blk_ptr[b];
     const int kp = blk_ptr[b + 1] - blk_ptr[b];
@@ -125,7 +138,10 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(const void *__restri
             if (lane == 0) chunk_off[kMaxChunks] = run;
         }
         __syncthreads();
-        for (int c = wave; c < nc; c += kPackWaves) {
+        // this workgroup's run of chunks
+        const int per = (nchunks + (int)gridDim.y - 1) / (int)gridDim.y;
+        const int mine_lo = max((int)blockIdx.y * per - c0, 0), mine_hi = min(((int)blockIdx.y + 1) * per - c0, nc);
+        for (int c = mine_lo + wave; c < mine_hi; c += kPackWaves) {
             const int64_t j = (int64_t)(c0 + c) * kWave + lane;
             const bool k = j < N && krow[j] != 0;
             const uint64_t m = __ballot(k);
@@ -140,8 +156,9 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(const void *__restri
         }
     }
     __syncthreads();
-    // pads: repeat the last kept column, zero values
+    // pads: repeat the last kept column, zero values (written by the workgroup that placed that column)
     const int32_t last = s_last;
+    if (last < 0) return;
     for (int c = kb + threadIdx.x; c < kp; c += kPackThreads) {
         idx[c] = last;
         for (int r = 0; r < R; ++r) elem<VDT>::store(vals, vbase + (int64_t)r * kp + c, 0.0f);
@@ -206,10 +223,14 @@ extern "C" int bsp_pack(const void *W, int wdt, int64_t M, int64_t N, int32_t R,
     if (!col_idx || !vals) return BSP_ERR_NULL;
     const int64_t B = M / R;
     hipStream_t s = (hipStream_t)stream;
+    // few row-blocks: several workgroups per block, each with at least 1024 columns (a chunk per wavefront)
+    int64_t split64 = (N + 1023) / 1024;
+    if (split64 > 512 / B) split64 = 512 / B;
+    const unsigned split = (unsigned)(split64 < 1 ? 1 : split64);
     BSP_DISPATCH_DTYPE(wdt, WDT, {
         BSP_DISPATCH_DTYPE(vdt, VDT, {
-            pack_kernel<WDT, VDT><<<(unsigned)B, kPackThreads, 0, s>>>(W, N, R, keep, blk_cnt, blk_ptr, capacity_cols,
-                                                                   col_idx, vals);
+            pack_kernel<WDT, VDT><<<dim3((unsigned)B, split), kPackThreads, 0, s>>>(W, N, R, keep, blk_cnt, blk_ptr,
+                                                                                capacity_cols, col_idx, vals);
         });
     });
     return check_launch();

@@ -99,7 +99,7 @@ __global__ __launch_bounds__(kPlanWaves * 64) void plan_scan_kernel(const int32_
     }
 }
 
-// One workgroup per row-block: order the kept columns of every chunk and write the steps.
+// One workgroup per (row-block, column chunk): order the chunk's kept columns and write its steps.
 __global__ __launch_bounds__(kThreads) void plan_fill_kernel(int32_t R, int32_t nfrag, int32_t NG, int32_t chunk_shift,
                                                              int32_t nchunks, const int32_t *__restrict__ blk_cnt,
                                                              const int32_t *__restrict__ blk_ptr,
@@ -129,15 +129,16 @@ __global__ __launch_bounds__(kThreads) void plan_fill_kernel(int32_t R, int32_t 
     }
     __syncthreads();
 
-    int lo = 0;  // canonical position of the chunk's first kept column (columns ascend, so chunks are runs)
-    for (int q = 0; q < nchunks; lo += s_cnt[q], ++q) {
+    {
+        const int q = blockIdx.y;
+        int lo = 0;  // canonical position of the chunk's first kept column (columns ascend, so chunks are runs)
+        for (int k = 0; k < q; ++k) lo += s_cnt[k];
         const int cq = s_cnt[q];
-        if (cq <= 0) continue;  // uniform
-        if (cq > 1024) return;  // malformed storage (duplicate columns): nothing more is written
+        if (cq <= 0) return;    // uniform
+        if (cq > 1024) return;  // malformed storage (duplicate columns): nothing is written
         const int nsteps = (cq + 31) >> 5;
         const int S = nsteps * 4;  // sets of 8 columns
         const int col0 = q << chunk_shift;
-        __syncthreads();  // the previous chunk's slot arrays are no longer read
         if (wave == 0) {
             int cnt[8] = {0, 0, 0, 0, 0, 0, 0, 0};
             int novf = 0;
@@ -286,7 +287,7 @@ extern "C" int bsp_linear_plan(int vdt, int64_t M, int64_t N, int32_t R, int32_t
     plan_scan_kernel<<<1, kPlanWaves * 64, 0, s>>>(steps_bq, (int32_t)B, (int32_t)L.NG, ch.n, (int64_t)L.steps,
                                                    plan_slack_steps(), wptr, xoff);
     if (capacity_cols > 0)
-        plan_fill_kernel<<<(unsigned)B, kThreads, 0, s>>>(R, nf, (int32_t)L.NG, ch.shift, ch.n, blk_cnt, blk_ptr,
+        plan_fill_kernel<<<dim3((unsigned)B, (unsigned)ch.n), kThreads, 0, s>>>(R, nf, (int32_t)L.NG, ch.shift, ch.n, blk_cnt, blk_ptr,
                                                           col_idx, (const uint16_t *)vals, capacity_cols,
                                                           (int64_t)L.steps, wptr, wfrag, xoff);
     return check_launch();

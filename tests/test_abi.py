@@ -64,5 +64,6 @@ def test_host_side_argument_checks():
     assert L.bsp_linear(one, 5, 4, 16, 8, 16, 32, one, one, one, one, None, one, None) == DTYPE
     assert L.bsp_packed_validate(16, 8, 16, 16, None, one, one, 0, one, None) == NULL
     assert L.bsp_penalty_grad_workspace_bytes(32, 300, 16) == 2 * 2 * 8
-    assert L.bsp_prune_mask_workspace_bytes(4, 100, 1) >= 3 * 2048 * 4
+    assert L.bsp_prune_mask_workspace_bytes(4, 100, 1) >= 2 * (2048 + 64) * 4   # two histogram slots at least
+    assert L.bsp_prune_mask_workspace_bytes(256, 4096, 1) > L.bsp_prune_mask_workspace_bytes(4, 100, 1)
     assert L.bsp_prune_mask_workspace_bytes(4, 100, 0) == 0
