@@ -137,6 +137,9 @@ def main():
     ap.add_argument("--launch", choices=["overlap", "serial", "eager"], default="overlap",
                     help="overlap: one HIP graph, a branch per matrix; serial: one HIP graph, matrices in turn; "
                          "eager: every kernel launched from Python")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one 256 MiB device-to-device copy (a kernel of known traffic, to scale the "
+                         "profiler's memory counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: the path has no multi-GPU part; run with --gpus 1", file=sys.stderr)
@@ -148,6 +151,12 @@ def main():
 
     if args.waves:
         bsp.lib().bsp_debug_set_tiled_waves(args.waves)
+    if args.copy_probe:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     mats = [Matrix(d, path=args.path) for d in wl.config4(R=args.R)]
     for m in mats:   # once, to learn the kept counts (needed only for the FLOP accounting)
         m.prune_and_pack()

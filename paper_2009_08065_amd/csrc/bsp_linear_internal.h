@@ -16,7 +16,7 @@ struct TiledArgs {
     const int32_t *blk_ptr;
     const int32_t *col_idx;   // canonical source
     const uint16_t *vals;     // canonical source
-    const int32_t *wptr;      // planned source: [kPlanWaves][chunks * NG + 1] first step of (chunk q, block kPlanWaves * g + w) at [w][q * NG + g]
+    const int32_t *wptr;      // planned source: [kPlanWaves][chunks * NG * nacc + 1] first step of (chunk q, block (g * kPlanWaves + w) * nacc + i) at [w][(q * NG + g) * nacc + i]
     const void *wfrag;        // planned source: [step][fragment][lane] 16-byte panel fragments
     const uint32_t *xoff;     // planned source: [step][lane] two 16-bit LDS byte offsets
     int64_t plan_steps;       // planned source: steps the fragment / offset regions hold (slack included)
@@ -39,6 +39,14 @@ inline PlanChunks plan_chunks(int64_t N) {
     const int64_t npad = (N + 255) / 256 * 256;
     if (npad <= 1024) return PlanChunks{1, 30};
     return PlanChunks{(int32_t)((npad + 1023) / 1024), 10};
+}
+// A wavefront of the planned kernels holds the accumulators of nacc consecutive row-blocks (a "quad"),
+// so that it writes 64 or 128 contiguous bytes per token row: 4 sixteen-row fragments' worth in the
+// column-chunked kernel (its output is written once, at the end), 2 in the kernel for layers of up to
+// 1024 columns (which stores inside its operand loop, where registers are scarcer).
+constexpr int plan_nacc(int nfrag, bool chunked) {
+    const int frags = chunked ? 4 : 2;
+    return frags / nfrag > 0 ? frags / nfrag : 1;
 }
 // Steps the planned kernel may read past the last step of the storage (values unused).
 int plan_slack_steps();

@@ -42,10 +42,8 @@ typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
 constexpr int kMaxStripBlocks = 1024;  // row-blocks per strip (their blk_ptr slice is cached in LDS)
 constexpr int kRing = 4;               // steps of operands in flight per wavefront, canonical kernel
-constexpr int kPlanRing = 16;          // the same for the planned kernel: 8 wavefronts x 16 steps x 1.25 KiB
-                                       // in flight per compute unit cover the L2 latency of the operand stream
-constexpr int kChunkedAcc = 4;         // 16-row accumulator fragments per wavefront carried across column chunks
-constexpr int kMaxStripGroups = 128;   // groups of kPlanWaves row-blocks per strip of the planned kernel
+constexpr int kPlanRing = 16;          // the same for the column-chunked planned kernel: 8 wavefronts x 16 steps x
+                                       // 1.25 KiB in flight per compute unit cover the L2 latency of the operand stream
 
 // Distance in LDS between the 16-token sub-tiles of a workgroup's X tile: a constant, so that
 // sub-tile offsets fold into the immediate field of the LDS instructions.
@@ -338,40 +336,203 @@ __global__ __launch_bounds__(1024) void linear_tiled_canonical_kernel(
 // ---------------------------------------------------------------------------------------------
 // planned operands
 // ---------------------------------------------------------------------------------------------
-// Row-blocks are dealt to the kPlanWaves wavefronts of a workgroup round-robin (wavefront w owns
-// blocks w, w + kPlanWaves, ...; a "group" g is kPlanWaves consecutive blocks).  The wavefronts advance nearly in
-// lockstep, so at any time they work on neighbouring row-blocks, and the 32-byte pieces that
-// four neighbouring row-blocks contribute to one 128-byte line of Y reach the L2 close together
-// and leave it as a whole line.  The plan stores the steps in exactly that order: all steps of
-// wavefront w, group after group, are contiguous, so a wavefront streams its operands with
-// constant address increments; wptr[w][g] is the step index where block 16g + w starts.
-template <int DT, int NFRAG, int NSUB>
+// A wavefront owns NACC = 4 / NFRAG consecutive row-blocks at a time (a "quad": 64 consecutive output
+// columns whatever R is) and keeps all their accumulators, so that it can write whole 128-byte lines
+// of Y: group g of a layer = kPlanWaves quads = blocks [g * 8 * NACC, (g + 1) * 8 * NACC), quad w of
+// the group belongs to wavefront w.  The plan stores the steps in exactly the order a wavefront walks
+// them (its quad of group 0 block by block, then group 1, ...; chunk-major for layers cut into column
+// chunks), so a wavefront streams its operands with constant address increments.
+// wptr[w][(q * NG + g) * NACC + i] = first step of block (g * 8 + w) * NACC + i inside chunk q.
+
+constexpr int kOutPitch = 144;  // bytes per token row of a wavefront's output staging (128 + pad)
+
+// Output of one quad.  The accumulators hold, per lane, 4 consecutive output columns of one token
+// (the MFMA result layout); written as they are, a store instruction would touch 16 token rows with
+// 32 bytes each.  They go through a small per-wavefront LDS buffer instead, so that 8 lanes write one
+// whole 128-byte line of a token row.
+template <int DT, int NFRAG, int NSUB, int NACC>
+struct QuadEpilogue {
+    uint16_t *Y;
+    const void *bias;
+    int64_t T, M, t0;
+    int32_t R, B, l16, G, lane;
+    bool fast;       // R == 16 * NFRAG: a quad is NACC * R contiguous output columns, a multiple of 64 bytes
+    uint8_t *stage;  // this wavefront's LDS staging, 16 rows of kOutPitch bytes
+    uint2 bv[NACC][NFRAG];  // bias of the lane's 4 output columns per (block, fragment), as stored (16-bit floats)
+
+    __device__ __forceinline__ void init(void *Y_, const void *bias_, int64_t T_, int64_t M_, int32_t R_, int32_t B_,
+                                         int64_t t0_, int lane_, uint8_t *stage_, bool fast_) {
+        Y = (uint16_t *)Y_; bias = bias_; T = T_; M = M_; R = R_; B = B_; t0 = t0_;
+        lane = lane_; l16 = lane_ & 15; G = lane_ >> 4; stage = stage_; fast = fast_;
+#pragma unroll
+        for (int k = 0; k < NACC; ++k)
+#pragma unroll
+            for (int f = 0; f < NFRAG; ++f) bv[k][f] = make_uint2(0u, 0u);  // +0 in both formats
+    }
+    // Bias of the quad whose first row-block is b0; issued early, used by convert().  Unconditional loads
+    // on clamped addresses, so nothing waits on them before the use.
+    __device__ __forceinline__ void load_bias(int64_t b0) {
+        if (!bias) return;
+#pragma unroll
+        for (int k = 0; k < NACC; ++k) {
+            const int64_t b = b0 + k < B ? b0 + k : B - 1;
+#pragma unroll
+            for (int f = 0; f < NFRAG; ++f) {
+                const int r0 = f * 16 + 4 * G;
+                if (fast) {
+                    bv[k][f] = *reinterpret_cast<const uint2 *>((const uint16_t *)bias + b * R + r0);
+                } else {
+                    uint32_t h[4];
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int rr = r0 + v < R ? r0 + v : R - 1;
+                        h[v] = ((const uint16_t *)bias)[b * R + rr];
+                    }
+                    bv[k][f] = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
+                }
+            }
+        }
+    }
+    __device__ __forceinline__ static float widen(uint32_t h) {
+        if constexpr (DT == BSP_BF16) return __uint_as_float(h << 16);
+        else return (float)__builtin_bit_cast(_Float16, (uint16_t)h);
+    }
+    // Bias added, rounded to the output type: the form in which a finished quad waits for its store.
+    typedef uint2 Packed[NACC][NFRAG][NSUB];
+    __device__ __forceinline__ void convert(const f32x4 (&acc)[NACC][NFRAG][NSUB], Packed &out) const {
+#pragma unroll
+        for (int k = 0; k < NACC; ++k)
+#pragma unroll
+            for (int f = 0; f < NFRAG; ++f)
+#pragma unroll
+                for (int u = 0; u < NSUB; ++u) {
+                    const float b0 = widen(bv[k][f].x & 0xffffu), b1 = widen(bv[k][f].x >> 16);
+                    const float b2 = widen(bv[k][f].y & 0xffffu), b3 = widen(bv[k][f].y >> 16);
+                    out[k][f][u].x = cvt_pk<DT>(acc[k][f][u][0] + b0, acc[k][f][u][1] + b1);
+                    out[k][f][u].y = cvt_pk<DT>(acc[k][f][u][2] + b2, acc[k][f][u][3] + b3);
+                }
+    }
+    // Store the quad whose first row-block is b0.  out[k][f][u] = 4 consecutive output columns
+    // (16 f + 4 G ..) of block b0 + k for token 16 u + l16 of the tile.
+    __device__ __forceinline__ void flush(int64_t b0, const Packed &out) {
+        if (b0 >= B) return;  // uniform
+        if (fast) {
+            // a token row of the quad is ROWB = 64 or 128 contiguous bytes: LPR lanes x 16 bytes write one row
+            constexpr int ROWB = NACC * NFRAG * 32, LPR = ROWB / 16, RPI = 64 / LPR;  // rows per store instruction
+            const int row = lane / LPR, piece = lane % LPR;
+            // the 16-byte piece covers 8 output columns, all inside one row-block
+            const bool blk_ok = b0 + (piece * 8) / (16 * NFRAG) < B;
+            uint16_t *dst = Y + b0 * R + piece * 8;
+#pragma unroll
+            for (int u = 0; u < NSUB; ++u) {
+#pragma unroll
+                for (int k = 0; k < NACC; ++k)
+#pragma unroll
+                    for (int f = 0; f < NFRAG; ++f)
+                        *reinterpret_cast<uint2 *>(stage + l16 * kOutPitch + (k * NFRAG + f) * 32 + 8 * G) = out[k][f][u];
+                // same wavefront writes and reads: LDS operations of a wavefront complete in order
+#pragma unroll
+                for (int i = 0; i < 16 / RPI; ++i) {
+                    const uint4 o = *reinterpret_cast<const uint4 *>(stage + (row + RPI * i) * kOutPitch + piece * 16);
+                    const int64_t t = t0 + 16 * u + RPI * i + row;
+                    if (t < T && blk_ok) *reinterpret_cast<uint4 *>(dst + t * M) = o;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < NACC; ++k) {
+                if (b0 + k >= B) continue;
+#pragma unroll
+                for (int f = 0; f < NFRAG; ++f) {
+                    const int r0 = f * 16 + 4 * G;
+#pragma unroll
+                    for (int u = 0; u < NSUB; ++u) {
+                        const int64_t t = t0 + 16 * u + l16;
+                        if (t >= T) continue;
+                        const uint32_t h[4] = {out[k][f][u].x & 0xffffu, out[k][f][u].x >> 16, out[k][f][u].y & 0xffffu,
+                                               out[k][f][u].y >> 16};
+#pragma unroll
+                        for (int v = 0; v < 4; ++v)
+                            if (r0 + v < R) Y[t * M + (b0 + k) * R + r0 + v] = (uint16_t)h[v];
+                    }
+                }
+            }
+        }
+    }
+};
+
+// The MFMAs of one step go to the accumulators of the row-block the step belongs to; `which` is
+// uniform over the wavefront, so this is a scalar branch.
+template <int DT, int NFRAG, int NSUB, int NACC>
+__device__ __forceinline__ void step_mfma(f32x4 (&acc)[NACC][NFRAG][NSUB], int which, const uint4 (&a)[NFRAG],
+                                          const uint4 (&xb)[NSUB]) {
+    auto into = [&](f32x4 (&c)[NFRAG][NSUB]) {
+#pragma unroll
+        for (int u = 0; u < NSUB; ++u)
+#pragma unroll
+            for (int f = 0; f < NFRAG; ++f) c[f][u] = mfma16<DT>(a[f], xb[u], c[f][u]);
+    };
+    if constexpr (NACC == 1) {
+        into(acc[0]);
+    } else if constexpr (NACC == 2) {
+        if (which == 0) into(acc[0]); else into(acc[1]);
+    } else {
+        static_assert(NACC == 4, "accumulator sets per wavefront");
+        if (which < 2) {
+            if (which == 0) into(acc[0]); else into(acc[1]);
+        } else {
+            if (which == 2) into(acc[2]); else into(acc[3]);
+        }
+    }
+}
+
+template <int NACC, int NFRAG, int NSUB>
+__device__ __forceinline__ void clear_quad(f32x4 (&acc)[NACC][NFRAG][NSUB]) {
+#pragma unroll
+    for (int k = 0; k < NACC; ++k) clear_acc(acc[k]);
+}
+
+// Layers of up to 1024 input columns: the whole 64-token X tile stays in LDS while the workgroup
+// walks the groups of its strip.
+//
+// Output path.  The MFMA result layout gives a lane 4 consecutive output columns of one token, so a
+// store straight from the accumulators touches 16 token rows with 32 bytes each.  Instead a finished
+// 16-row fragment is rounded (bias added) and parked in a per-wavefront LDS buffer of 64 token rows x
+// 64 bytes; every second fragment (two row-blocks for R = 16, one for R = 32, half a one for R = 64)
+// the buffer holds 32 consecutive output columns of all 64 tokens and is written with 16-byte lanes,
+// 64 contiguous bytes per token row.  The LDS operations of a wavefront complete in order, so the
+// buffer needs no barrier.
+constexpr uint32_t kXTileBytes = 4 * 32768;  // 64 tokens x 1024 columns
+constexpr uint32_t kOutStageBytes = 4096;    // per wavefront: 64 token rows x 64 bytes
+
+template <int DT, int NFRAG>
 __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
     const uint16_t *__restrict__ X, int64_t T, int64_t M, int64_t N, int32_t R, int32_t npad,
     const int32_t *__restrict__ wptr, const uint32_t *__restrict__ wfrag, const uint32_t *__restrict__ xoff,
     const void *__restrict__ bias, void *__restrict__ Y, int32_t ntiles, int32_t groups_per_strip, int32_t NG,
-    int32_t B) {
-    constexpr int RING = kPlanRing / NFRAG;  // the same bytes in flight for every fragment count
-    __shared__ int s_w[kPlanWaves][kMaxStripGroups + 1];
+    int32_t B, int32_t max_step, int32_t fast_store) {
+    constexpr int NSUB = 4;
+    constexpr int NACC = plan_nacc(NFRAG, false);  // row-blocks of a wavefront's run: their fragments pair up
+    constexpr int RING = kPlanRing / NFRAG;        // the same bytes in flight for every fragment count
+    static_assert(RING % 2 == 0, "the X fragment ping-pong needs an even ring");
     const int tile = blockIdx.x % ntiles, strip = blockIdx.x / ntiles;
     const int64_t t0 = (int64_t)tile * (16 * NSUB);
     const int g0 = strip * groups_per_strip;
     const int ng = min(groups_per_strip, NG - g0);
-    for (int i = threadIdx.x; i < kPlanWaves * (ng + 1); i += blockDim.x) {
-        const int w = i / (ng + 1), k = i % (ng + 1);
-        s_w[w][k] = wptr[w * (NG + 1) + g0 + k];
-    }
     stage_x_tile<NSUB>(X, T, N, npad, t0);
     __syncthreads();
 
     const int lane = threadIdx.x & 63;
     const int l16 = lane & 15, G = lane >> 4;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int *my = s_w[wave];
+    // this wavefront's row of step pointers, from the strip's first entry on (uniform: scalar loads)
+    const int32_t *my = wptr + (int64_t)wave * ((int64_t)NG * NACC + 1) + (int64_t)g0 * NACC;
+    uint8_t *stg = smem_x + kXTileBytes + wave * kOutStageBytes;
+    const bool fast = fast_store != 0;
+    uint16_t *Yh = (uint16_t *)Y;
 
-    Epilogue<DT, NFRAG, NSUB> ep;
-    ep.init(Y, bias, T, M, R, t0, l16, G);
     f32x4 acc[NFRAG][NSUB];
+    uint2 bvp[NFRAG];  // bias of the lane's 4 columns per fragment of the current block, as stored
     uint4 ra[RING][NFRAG];
     uint32_t rx[RING];
     uint4 xb[2][NSUB];  // X fragments of the current step (even / odd ping-pong, resolved by the unrolling)
@@ -384,35 +545,99 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
             dst[u] = make_uint4(lo.x, lo.y, hi.x, hi.y);
         }
     };
-    static_assert(RING % 2 == 0, "the X fragment ping-pong needs an even ring");
+    auto load_frag = [&](const uint32_t *q) { return make_uint4(q[0], q[64], q[128], q[192]); };
+    auto block_of = [&](int e) { return ((int64_t)(g0 + e / NACC) * kPlanWaves + wave) * NACC + e % NACC; };
+    auto widen = [](uint32_t h) {
+        if constexpr (DT == BSP_BF16) return __uint_as_float(h << 16);
+        else return (float)__builtin_bit_cast(_Float16, (uint16_t)h);
+    };
+    // Issued when a row-block starts, used when it ends: nothing waits on it in between.
+    auto load_bias = [&](int64_t b) {
+#pragma unroll
+        for (int f = 0; f < NFRAG; ++f) bvp[f] = make_uint2(0u, 0u);  // +0 in both formats
+        if (bias && fast && b < B) {
+#pragma unroll
+            for (int f = 0; f < NFRAG; ++f)
+                bvp[f] = *reinterpret_cast<const uint2 *>((const uint16_t *)bias + b * R + f * 16 + 4 * G);
+        }
+    };
+    // Output of the finished row-block b (the accumulators hold it).
+    auto finish_block = [&](int64_t b) __attribute__((always_inline)) {
+        if (b >= B) return;  // uniform
+        if (fast) {
+#pragma unroll
+            for (int f = 0; f < NFRAG; ++f) {
+                const int slot = NFRAG == 1 ? (int)(b & 1) : (f & 1);  // half of the 64-byte staging row
+                const float b0 = widen(bvp[f].x & 0xffffu), b1 = widen(bvp[f].x >> 16);
+                const float b2 = widen(bvp[f].y & 0xffffu), b3 = widen(bvp[f].y >> 16);
+#pragma unroll
+                for (int u = 0; u < NSUB; ++u) {
+                    uint2 o;
+                    o.x = cvt_pk<DT>(acc[f][u][0] + b0, acc[f][u][1] + b1);
+                    o.y = cvt_pk<DT>(acc[f][u][2] + b2, acc[f][u][3] + b3);
+                    *reinterpret_cast<uint2 *>(stg + (16 * u + l16) * 64 + slot * 32 + 8 * G) = o;
+                }
+                // The staging rows are complete after an odd fragment; a lone last row-block of an
+                // odd-sized layer (R = 16) leaves with its own half only.
+                const bool lone = NFRAG == 1 && slot == 0 && b + 1 >= B;
+                if (slot == 1 || lone) {
+                    const int piece = lane & 3;  // 16-byte piece of the 64-byte row
+                    const int64_t col0 = b * R + f * 16 - (slot == 1 ? 16 : 0);
+                    if (!lone || piece < 2) {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const int row = 16 * i + (lane >> 2);
+                            const uint4 o = *reinterpret_cast<const uint4 *>(stg + row * 64 + piece * 16);
+                            if (t0 + row < T) *reinterpret_cast<uint4 *>(Yh + (t0 + row) * M + col0 + piece * 8) = o;
+                        }
+                    }
+                }
+            }
+        } else {
+#pragma unroll
+            for (int f = 0; f < NFRAG; ++f)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int r = f * 16 + 4 * G + v;
+                    if (r >= R) continue;
+                    const float bb = bias ? elem<DT>::load(bias, b * R + r) : 0.0f;
+#pragma unroll
+                    for (int u = 0; u < NSUB; ++u) {
+                        const int64_t t = t0 + 16 * u + l16;
+                        if (t < T) elem<DT>::store(Y, t * M + b * R + r, acc[f][u][v] + bb);
+                    }
+                }
+        }
+    };
 
     // Workgroups that share an L2 (blockIdx.x mod 8 picks the XCD) walk the strip's groups from
     // different starting points, so that they do not all pull the same plan lines at the same time:
     // groups [rot, ng) first, then [0, rot).
     const int rot = ng > 1 ? ((tile >> 3) + strip) % ng : 0;
     for (int seg = 0; seg < 2; ++seg) {
-        const int ga = seg == 0 ? rot : 0, gb = seg == 0 ? ng : rot;
-        if (ga >= gb) continue;
-        const int gs_hi = __builtin_amdgcn_readfirstlane(my[gb]);
-        int gs = __builtin_amdgcn_readfirstlane(my[ga]);
-        int grp = ga;                      // current group; its block is 16 (g0 + grp) + wave
-        int64_t blk = (int64_t)kPlanWaves * (g0 + ga) + wave;
-        int blk_end = __builtin_amdgcn_readfirstlane(my[ga + 1]);  // first step index past the current block
+        const int ea = (seg == 0 ? rot : 0) * NACC, eb = (seg == 0 ? ng : rot) * NACC;
+        if (ea >= eb) continue;
+        // (the clamps keep a malformed plan from driving the operand pointers out of the buffer)
+        const int gs_hi = min(my[eb], max_step);
+        int gs = max(my[ea], 0);
+        int e = ea;                             // current entry, row-block block_of(e)
+        int blk_end = min(my[ea + 1], gs_hi);   // first step past the current block
+        int nxt_end = my[min(ea + 2, eb)];      // the same for the block after it, fetched one block ahead
         clear_acc(acc);
-        if (blk < B) ep.load_bias(blk);
-        // finished (possibly empty) row-blocks are written as soon as the stream has passed them
-        auto pass_boundaries = [&]() {
-            while (grp < gb && blk_end <= gs) {
-                if (blk < B) ep.write_block(blk, acc);
+        load_bias(block_of(e));
+        // finished (possibly empty) row-blocks leave as soon as the stream has passed them
+        auto pass_boundaries = [&]() __attribute__((always_inline)) {
+            while (e < eb && blk_end <= gs) {
+                finish_block(block_of(e));
                 clear_acc(acc);
-                ++grp;
-                blk += kPlanWaves;
-                blk_end = grp < gb ? __builtin_amdgcn_readfirstlane(my[grp + 1]) : -1;
-                if (grp < gb && blk < B) ep.load_bias(blk);
+                ++e;
+                blk_end = e < eb ? min(nxt_end, gs_hi) : 0x7fffffff;
+                nxt_end = my[min(e + 2, eb)];
+                if (e < eb) load_bias(block_of(e));
             }
         };
         pass_boundaries();
-        if (gs >= gs_hi) continue;
+        if (gs >= gs_hi) continue;  // then e == eb: every block of the segment has been written
 
         // Per-lane operand pointers, advanced by a constant per RING steps.  The stream is read up
         // to RING steps past the segment's last step: those loads stay inside the plan buffer (its
@@ -422,7 +647,6 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
         // pipeline sustains best on this hardware (about 1.6x the bytes per clock of 16-byte loads).
         const uint32_t *wp = wfrag + (int64_t)gs * (NFRAG * 256) + lane;
         const uint32_t *xp = xoff + (int64_t)gs * 64 + lane;
-        auto load_frag = [&](const uint32_t *q) { return make_uint4(q[0], q[64], q[128], q[192]); };
 #pragma unroll
         for (int j = 0; j < RING; ++j) {
 #pragma unroll
@@ -448,9 +672,9 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
                 for (int f = 0; f < NFRAG; ++f) ra[j][f] = load_frag(wp + ((RING + j) * NFRAG + f) * 256);
                 rx[j] = xp[(RING + j) * 64];  // its old value went into the previous sub-iteration's reads
                 ++gs;
-                if (gs >= blk_end || gs >= gs_hi) {  // uniform; also ends the walk on a malformed plan
+                if (gs >= blk_end) {  // uniform
                     pass_boundaries();
-                    if (gs >= gs_hi) {
+                    if (e >= eb) {
                         done = true;
                         break;
                     }
@@ -464,33 +688,27 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
 
 // Layers wider than one LDS tile (more than 1024 input columns): the workgroup keeps the 64-token
 // tile, walks the input columns chunk by chunk (1024 columns of X in LDS at a time) and carries the
-// accumulators of all its row-blocks across the chunks, so the operand stream is read once per
-// 64 tokens whatever the layer width.  The plan stores wavefront w's steps chunk-major (all its
-// row-blocks' steps of chunk 0, then chunk 1, ...; entry q * NG + g of its pointer row), so inside a
-// chunk the steps of the strip's groups are contiguous.  A wavefront owns up to MAXG row-blocks (one
-// per group of the strip); which accumulator set a step feeds is a wavefront-uniform branch.
+// accumulators of its quads across the chunks, so the operand stream is read once per 64 tokens
+// whatever the layer width.  One group (a quad per wavefront) per workgroup.
 template <int DT, int NFRAG>
 __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_chunked_kernel(
     const uint16_t *__restrict__ X, int64_t T, int64_t M, int64_t N, int32_t R, int32_t npad,
     const int32_t *__restrict__ wptr, const uint32_t *__restrict__ wfrag, const uint32_t *__restrict__ xoff,
-    const void *__restrict__ bias, void *__restrict__ Y, int32_t ntiles, int32_t groups_per_strip, int32_t NG,
-    int32_t B, int32_t nchunks, int32_t max_step) {
+    const void *__restrict__ bias, void *__restrict__ Y, int32_t ntiles, int32_t NG, int32_t B, int32_t nchunks,
+    int32_t max_step, int32_t fast_store) {
     constexpr int NSUB = 4;
-    constexpr int MAXG = kChunkedAcc / NFRAG;
+    constexpr int NACC = plan_nacc(NFRAG, true);
     constexpr int RING = kPlanRing / NFRAG;
     static_assert(RING % 2 == 0, "the X fragment ping-pong needs an even ring");
-    const int tile = blockIdx.x % ntiles, strip = blockIdx.x / ntiles;
+    __shared__ __attribute__((aligned(16))) uint8_t s_out[kPlanWaves][16 * kOutPitch];
+    const int tile = blockIdx.x % ntiles, g = blockIdx.x / ntiles;
     const int64_t t0 = (int64_t)tile * (16 * NSUB);
-    const int g0 = strip * groups_per_strip;
-    const int ng = min(min(groups_per_strip, MAXG), NG - g0);
     const int lane = threadIdx.x & 63;
-    const int l16 = lane & 15, G = lane >> 4;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int32_t *my = wptr + (int64_t)wave * ((int64_t)nchunks * NG + 1);
+    const int32_t *my = wptr + (int64_t)wave * ((int64_t)nchunks * NG * NACC + 1);
 
-    f32x4 acc[MAXG][NFRAG][NSUB];
-#pragma unroll
-    for (int gi = 0; gi < MAXG; ++gi) clear_acc(acc[gi]);
+    f32x4 acc[NACC][NFRAG][NSUB];
+    clear_quad(acc);
     uint4 ra[RING][NFRAG];
     uint32_t rx[RING];
     uint4 xb[2][NSUB];
@@ -507,12 +725,12 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_chunked_kernel(
 
     for (int q = 0; q < nchunks; ++q) {
         // the wavefront's step range of this chunk and where each of its row-blocks ends
-        const int32_t *ent = my + (int64_t)q * NG + g0;
+        const int32_t *ent = my + ((int64_t)q * NG + g) * NACC;
         int gs = __builtin_amdgcn_readfirstlane(ent[0]);
-        int ends[MAXG];
+        int ends[NACC];
 #pragma unroll
-        for (int gi = 0; gi < MAXG; ++gi) ends[gi] = __builtin_amdgcn_readfirstlane(ent[min(gi + 1, ng)]);
-        int gs_hi = ends[MAXG - 1];
+        for (int k = 0; k < NACC; ++k) ends[k] = __builtin_amdgcn_readfirstlane(ent[k + 1]);
+        int gs_hi = ends[NACC - 1];
         // a malformed plan must not drive the operand pointers out of the buffer
         gs = max(gs, 0);
         gs_hi = min(gs_hi, max_step);
@@ -532,15 +750,15 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_chunked_kernel(
         __syncthreads();
         if (!work) continue;  // no barrier below this line inside the chunk
 
-        int grp = 0;
-        auto end_of = [&](int g) {
-            int e = ends[0];
+        int cur = 0;
+        auto end_of = [&](int k) {
+            int v = ends[0];
 #pragma unroll
-            for (int gi = 1; gi < MAXG; ++gi) e = g == gi ? ends[gi] : e;
-            return e;
+            for (int i = 1; i < NACC; ++i) v = k == i ? ends[i] : v;
+            return v;
         };
         int blk_end = ends[0];
-        while (blk_end <= gs && grp < MAXG - 1) blk_end = end_of(++grp);
+        while (blk_end <= gs && cur < NACC - 1) blk_end = end_of(++cur);
         issue_reads(rx[0], xb[0]);
         bool done = false;
         while (!done) {
@@ -548,24 +766,7 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_chunked_kernel(
             for (int j = 0; j < RING; ++j) {
                 issue_reads(rx[(j + 1) % RING], xb[(j + 1) & 1]);
                 __builtin_amdgcn_sched_barrier(0);
-                auto fma_into = [&](f32x4 (&a)[NFRAG][NSUB]) {
-#pragma unroll
-                    for (int u = 0; u < NSUB; ++u)
-#pragma unroll
-                        for (int f = 0; f < NFRAG; ++f) a[f][u] = mfma16<DT>(ra[j][f], xb[j & 1][u], a[f][u]);
-                };
-                if constexpr (MAXG == 1) {
-                    fma_into(acc[0]);
-                } else if constexpr (MAXG == 2) {
-                    if (grp == 0) fma_into(acc[0]); else fma_into(acc[1]);
-                } else {
-                    static_assert(MAXG == 4, "accumulator sets per wavefront");
-                    if (grp < 2) {
-                        if (grp == 0) fma_into(acc[0]); else fma_into(acc[1]);
-                    } else {
-                        if (grp == 2) fma_into(acc[2]); else fma_into(acc[3]);
-                    }
-                }
+                step_mfma<DT, NFRAG, NSUB, NACC>(acc, cur, ra[j], xb[j & 1]);
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int f = 0; f < NFRAG; ++f) ra[j][f] = load_frag(wp + ((RING + j) * NFRAG + f) * 256);
@@ -576,7 +777,7 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_chunked_kernel(
                         done = true;
                         break;
                     }
-                    while (blk_end <= gs && grp < MAXG - 1) blk_end = end_of(++grp);
+                    while (blk_end <= gs && cur < NACC - 1) blk_end = end_of(++cur);
                 }
             }
             wp += RING * NFRAG * 256;
@@ -584,15 +785,15 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_chunked_kernel(
         }
     }
 
-    Epilogue<DT, NFRAG, NSUB> ep;
-    ep.init(Y, bias, T, M, R, t0, l16, G);
-#pragma unroll
-    for (int gi = 0; gi < MAXG; ++gi) {
-        const int64_t blk = (int64_t)kPlanWaves * (g0 + gi) + wave;
-        if (gi < ng && blk < B) {
-            ep.load_bias(blk);
-            ep.write_block(blk, acc[gi]);
-        }
+    typedef QuadEpilogue<DT, NFRAG, NSUB, NACC> Ep;
+    Ep ep;
+    ep.init(Y, bias, T, M, R, B, t0, lane, s_out[wave], fast_store != 0);
+    const int64_t b0 = ((int64_t)g * kPlanWaves + wave) * NACC;
+    if (b0 < B) {
+        typename Ep::Packed out;
+        ep.load_bias(b0);
+        ep.convert(acc, out);
+        ep.flush(b0, out);
     }
 }
 
@@ -608,75 +809,73 @@ int raise_lds_limit(K kern, size_t lds, size_t &configured) {
     return BSP_OK;
 }
 
-template <int DT, int NFRAG, int NSUB, bool PLAN>
-int launch(const TiledArgs &a, int waves, hipStream_t s) {
+template <int DT, int NFRAG, int NSUB>
+int launch_canonical(const TiledArgs &a, int waves, hipStream_t s) {
     const size_t lds = (size_t)(NSUB - 1) * sub_stride<NSUB>() + (size_t)a.npad * 32;
     static thread_local size_t configured = 0;  // per instantiation and thread
     const int64_t ntiles = (a.T + 16 * NSUB - 1) / (16 * NSUB);
     int64_t nstrips = (256 + ntiles - 1) / ntiles;  // enough strips to give every compute unit a workgroup
     if (nstrips < 1) nstrips = 1;
-    if constexpr (PLAN) {
-        auto kern = linear_tiled_planned_kernel<DT, NFRAG, NSUB>;
-        int st = raise_lds_limit(kern, lds, configured);
-        if (st != BSP_OK) return st;
-        const int64_t NG = (a.B + kPlanWaves - 1) / kPlanWaves;
-        if (nstrips > NG) nstrips = NG;
-        int64_t gps = (NG + nstrips - 1) / nstrips;
-        if (gps > kMaxStripGroups) gps = kMaxStripGroups;
-        nstrips = (NG + gps - 1) / gps;
-        if (ntiles * nstrips >= ((int64_t)1 << 31)) return BSP_ERR_SHAPE;
-        kern<<<dim3((unsigned)(ntiles * nstrips)), dim3(kPlanWaves * 64), lds, s>>>(
-            a.X, a.T, a.M, a.N, a.R, a.npad, a.wptr, (const uint32_t *)a.wfrag, a.xoff, a.bias, a.Y, (int32_t)ntiles,
-            (int32_t)gps, (int32_t)NG, (int32_t)a.B);
-    } else {
-        auto kern = linear_tiled_canonical_kernel<DT, NFRAG, NSUB>;
-        int st = raise_lds_limit(kern, lds, configured);
-        if (st != BSP_OK) return st;
-        const int64_t max_strips = (a.B + 3) / 4;  // never fewer than 4 row-blocks per strip
-        if (nstrips > max_strips) nstrips = max_strips;
-        int64_t rb_per_strip = (a.B + nstrips - 1) / nstrips;
-        if (rb_per_strip > kMaxStripBlocks) rb_per_strip = kMaxStripBlocks;
-        nstrips = (a.B + rb_per_strip - 1) / rb_per_strip;
-        if (ntiles * nstrips >= ((int64_t)1 << 31)) return BSP_ERR_SHAPE;
-        kern<<<dim3((unsigned)(ntiles * nstrips)), dim3((unsigned)(waves * 64)), lds, s>>>(
-            a.X, a.T, a.M, a.N, a.R, a.npad, a.blk_ptr, a.col_idx, a.vals, a.bias, a.Y, (int32_t)ntiles,
-            (int32_t)rb_per_strip, (int32_t)a.B);
-    }
+    auto kern = linear_tiled_canonical_kernel<DT, NFRAG, NSUB>;
+    int st = raise_lds_limit(kern, lds, configured);
+    if (st != BSP_OK) return st;
+    const int64_t max_strips = (a.B + 3) / 4;  // never fewer than 4 row-blocks per strip
+    if (nstrips > max_strips) nstrips = max_strips;
+    int64_t rb_per_strip = (a.B + nstrips - 1) / nstrips;
+    if (rb_per_strip > kMaxStripBlocks) rb_per_strip = kMaxStripBlocks;
+    nstrips = (a.B + rb_per_strip - 1) / rb_per_strip;
+    if (ntiles * nstrips >= ((int64_t)1 << 31)) return BSP_ERR_SHAPE;
+    kern<<<dim3((unsigned)(ntiles * nstrips)), dim3((unsigned)(waves * 64)), lds, s>>>(
+        a.X, a.T, a.M, a.N, a.R, a.npad, a.blk_ptr, a.col_idx, a.vals, a.bias, a.Y, (int32_t)ntiles,
+        (int32_t)rb_per_strip, (int32_t)a.B);
     return check_launch();
 }
 
 template <int DT, int NFRAG>
-int launch_chunked(const TiledArgs &a, hipStream_t s) {
-    constexpr int MAXG = kChunkedAcc / NFRAG;
-    const size_t lds = 4 * (size_t)sub_stride<4>();
-    static thread_local size_t configured = 0;
-    auto kern = linear_tiled_chunked_kernel<DT, NFRAG>;
-    int st = raise_lds_limit(kern, lds, configured);
-    if (st != BSP_OK) return st;
+int launch_planned(const TiledArgs &a, hipStream_t s) {
+    const int NACC = plan_nacc(NFRAG, a.npad > 1024);
+    const size_t lds = 4 * (size_t)sub_stride<4>();  // 64 tokens x 1024 columns
     const int64_t ntiles = (a.T + 63) / 64;
-    const int64_t NG = (a.B + kPlanWaves - 1) / kPlanWaves;
-    // as many row-blocks per wavefront as the accumulators allow, unless that leaves compute units idle
-    int64_t gps = NG * ntiles / 256;
-    gps = gps < 1 ? 1 : (gps > MAXG ? MAXG : gps);
-    const int64_t nstrips = (NG + gps - 1) / gps;
-    if (ntiles * nstrips >= ((int64_t)1 << 31)) return BSP_ERR_SHAPE;
-    const PlanChunks ch = plan_chunks(a.N);
+    const int64_t NG = (a.B + kPlanWaves * NACC - 1) / (kPlanWaves * NACC);
+    const int32_t fast = a.R == 16 * NFRAG ? 1 : 0;
     const int64_t max_step = a.plan_steps - plan_slack_steps();
     if (max_step < 0 || max_step > INT32_MAX) return BSP_ERR_CAPACITY;
-    kern<<<dim3((unsigned)(ntiles * nstrips)), dim3(kPlanWaves * 64), lds, s>>>(
+    if (a.npad > 1024) {
+        static thread_local size_t configured = 0;
+        auto kern = linear_tiled_chunked_kernel<DT, NFRAG>;
+        int st = raise_lds_limit(kern, lds, configured);
+        if (st != BSP_OK) return st;
+        if (ntiles * NG >= ((int64_t)1 << 31)) return BSP_ERR_SHAPE;
+        const PlanChunks ch = plan_chunks(a.N);
+        kern<<<dim3((unsigned)(ntiles * NG)), dim3(kPlanWaves * 64), lds, s>>>(
+            a.X, a.T, a.M, a.N, a.R, a.npad, a.wptr, (const uint32_t *)a.wfrag, a.xoff, a.bias, a.Y, (int32_t)ntiles,
+            (int32_t)NG, (int32_t)a.B, ch.n, (int32_t)max_step, fast);
+        return check_launch();
+    }
+    static thread_local size_t configured = 0;
+    auto kern = linear_tiled_planned_kernel<DT, NFRAG>;
+    const size_t lds_planned = kXTileBytes + (size_t)kPlanWaves * kOutStageBytes;  // all 160 KiB of a compute unit
+    int st = raise_lds_limit(kern, lds_planned, configured);
+    if (st != BSP_OK) return st;
+    int64_t nstrips = (256 + ntiles - 1) / ntiles;  // enough strips to give every compute unit a workgroup
+    if (nstrips > NG) nstrips = NG;
+    if (nstrips < 1) nstrips = 1;
+    int64_t gps = (NG + nstrips - 1) / nstrips;
+    nstrips = (NG + gps - 1) / gps;
+    if (ntiles * nstrips >= ((int64_t)1 << 31)) return BSP_ERR_SHAPE;
+    kern<<<dim3((unsigned)(ntiles * nstrips)), dim3(kPlanWaves * 64), lds_planned, s>>>(
         a.X, a.T, a.M, a.N, a.R, a.npad, a.wptr, (const uint32_t *)a.wfrag, a.xoff, a.bias, a.Y, (int32_t)ntiles,
-        (int32_t)gps, (int32_t)NG, (int32_t)a.B, ch.n, (int32_t)max_step);
+        (int32_t)gps, (int32_t)NG, (int32_t)a.B, (int32_t)max_step, fast);
     return check_launch();
 }
 
 template <int DT, int NFRAG, bool PLAN>
 int launch_nsub(const TiledArgs &a, int waves, hipStream_t s) {
-    if constexpr (PLAN)
-        if (a.npad > 1024) return launch_chunked<DT, NFRAG>(a, s);
+    if constexpr (PLAN) return launch_planned<DT, NFRAG>(a, s);
     // the X tile must fit the 160 KiB of LDS: 64 tokens up to 1024 columns, 32 up to 2048, 16 up to 4096
-    if (a.npad <= 1024) return launch<DT, NFRAG, 4, PLAN>(a, waves, s);
-    if (a.npad <= 2048) return launch<DT, NFRAG, 2, PLAN>(a, waves, s);
-    return launch<DT, NFRAG, 1, PLAN>(a, waves, s);
+    if (a.npad <= 1024) return launch_canonical<DT, NFRAG, 4>(a, waves, s);
+    if (a.npad <= 2048) return launch_canonical<DT, NFRAG, 2>(a, waves, s);
+    return launch_canonical<DT, NFRAG, 1>(a, waves, s);
 }
 
 template <int DT, bool PLAN>

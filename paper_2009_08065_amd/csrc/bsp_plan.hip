@@ -9,13 +9,17 @@
 // the value-panel fragments (16 rows x 32 columns, 16 bytes per lane) and the two 16-bit LDS
 // byte offsets of the lane's transposing reads.
 //
-// Order of the steps: the layer kernel deals row-blocks to its 16 wavefronts round-robin, so the
-// plan keeps the steps of wavefront w (blocks w, w+16, w+32, ...) contiguous, stream after
-// stream; wptr[w][g] is the step index where block 16g + w starts, wptr[w][NG] where stream w ends.
+// Order of the steps: a wavefront of the layer kernel owns "quads" of nacc = 4 / nfrag consecutive
+// row-blocks (quad w of every group of kPlanWaves quads), so the plan keeps the steps of wavefront w
+// contiguous, stream after stream, in the order it walks them: chunk by chunk (layers of more than
+// 1024 input columns are cut into chunks of 1024), group by group, block by block.
+// wptr[w][(q * NG + g) * nacc + i] is the step where block (g * kPlanWaves + w) * nacc + i starts in
+// chunk q; the last entry of a row is where stream w ends.
 //
-// Buffer layout (bytes): wptr int32 [streams][NG+1], padded to 256 | fragments [steps][nfrag][4][64] dwords
-// (dword k of every lane's 16-byte fragment lies in plane k, so that 4-byte-per-lane loads are contiguous)
-// | offsets uint32 [steps][64], with steps = capacity_cols / 32 + read-ahead slack.
+// Buffer layout (bytes): wptr int32 [kPlanWaves][4 * NG * nacc + 1], padded to 256 | fragments
+// [steps][nfrag][4][64] dwords (dword k of every lane's 16-byte fragment lies in plane k, so that
+// 4-byte-per-lane loads are contiguous) | offsets uint32 [steps][64], with steps = capacity_cols / 32
+// + 3 per row-block (every chunk pads its columns to a multiple of 32 on its own) + read-ahead slack.
 // Integer work only; deterministic.
 #include "bsp_common.h"
 #include "bsp_linear_internal.h"
@@ -59,18 +63,20 @@ __global__ __launch_bounds__(kThreads) void plan_count_kernel(const int32_t *__r
 // One workgroup of kPlanWaves wavefronts: wavefront w scans the step counts of its blocks in
 // stream order (chunk-major: all its blocks' steps of chunk 0, then chunk 1, ...).
 __global__ __launch_bounds__(kPlanWaves * 64) void plan_scan_kernel(const int32_t *__restrict__ steps_bq, int32_t B,
-                                                                    int32_t NG, int32_t nchunks, int64_t cap_steps,
+                                                                    int32_t NG, int32_t nacc, int32_t nchunks,
+                                                                    int64_t cap_steps,
                                                                     int32_t slack_steps, int32_t *__restrict__ wptr,
                                                                     uint32_t *__restrict__ xoff) {
     __shared__ int totals[kPlanWaves];
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const int E = nchunks * NG;  // entries of a stream: (chunk q, group g) at q * NG + g
+    const int per_chunk = NG * nacc;
+    const int E = nchunks * per_chunk;  // entries of a stream: (chunk q, group g, block i of the quad)
     int32_t *mine = wptr + (int64_t)w * (E + 1);
     int carry = 0;
     for (int ebase = 0; ebase < E; ebase += 64) {
         const int e = ebase + lane;
-        const int q = e / NG, g = e % NG;
-        const int64_t b = (int64_t)kPlanWaves * g + w;
+        const int q = e / per_chunk, gi = e % per_chunk;
+        const int64_t b = ((int64_t)(gi / nacc) * kPlanWaves + w) * nacc + gi % nacc;
         const int st = (e < E && b < B) ? steps_bq[b * kPlanMaxChunks + q] : 0;
         int incl = st;
 #pragma unroll
@@ -100,7 +106,8 @@ __global__ __launch_bounds__(kPlanWaves * 64) void plan_scan_kernel(const int32_
 }
 
 // One workgroup per (row-block, column chunk): order the chunk's kept columns and write its steps.
-__global__ __launch_bounds__(kThreads) void plan_fill_kernel(int32_t R, int32_t nfrag, int32_t NG, int32_t chunk_shift,
+__global__ __launch_bounds__(kThreads) void plan_fill_kernel(int32_t R, int32_t nfrag, int32_t NG, int32_t nacc,
+                                                             int32_t chunk_shift,
                                                              int32_t nchunks, const int32_t *__restrict__ blk_cnt,
                                                              const int32_t *__restrict__ blk_ptr,
                                                              const int32_t *__restrict__ col_idx,
@@ -200,8 +207,9 @@ __global__ __launch_bounds__(kThreads) void plan_fill_kernel(int32_t R, int32_t 
         }
         __syncthreads();
         // per-lane operands of the chunk's steps
-        const int E = nchunks * NG;
-        const int64_t gs0 = wptr[(b % kPlanWaves) * (E + 1) + q * NG + b / kPlanWaves];
+        const int E = nchunks * NG * nacc;
+        const int64_t quad = b / nacc;  // quad `quad % kPlanWaves` of group `quad / kPlanWaves`
+        const int64_t gs0 = wptr[(quad % kPlanWaves) * (E + 1) + ((int64_t)q * NG + quad / kPlanWaves) * nacc + b % nacc];
         if (gs0 < 0 || gs0 + nsteps > cap_steps) return;
         for (int s = wave; s < nsteps; s += kThreads / 64) {
             const int s1 = 32 * s + 8 * G + qd;
@@ -236,12 +244,17 @@ struct PlanLayout {
 };
 // Sized for the worst case of kPlanMaxChunks column chunks, so that the size does not depend on N:
 // every (row-block, chunk) pads its columns to a multiple of 32 on its own.
-inline PlanLayout plan_layout(int64_t M, int32_t R, int64_t capacity_cols) {
+// The buffer is sized for the finest grouping (nacc = 1) and the most chunks, so that its size does not
+// depend on N; NG is the number of groups for the grouping the layer's width selects.
+inline PlanLayout plan_layout(int64_t M, int64_t N, int32_t R, int64_t capacity_cols) {
     PlanLayout L;
     const int64_t B = M / R;
-    L.NG = (B + kPlanWaves - 1) / kPlanWaves;
+    const int64_t per_group = (int64_t)kPlanWaves * plan_nacc(nfrag_of(R), plan_chunks(N).n > 1);
+    L.NG = (B + per_group - 1) / per_group;
     L.steps = (size_t)((capacity_cols + 31) / 32) + (size_t)B * (kPlanMaxChunks - 1) + (size_t)plan_slack_steps();
-    L.wptr_bytes = ((size_t)kPlanWaves * (size_t)(kPlanMaxChunks * L.NG + 1) * sizeof(int32_t) + 255) / 256 * 256;
+    // entries per stream <= chunks * (blocks rounded up to whole groups) / kPlanWaves, groups of at most 32 blocks
+    L.wptr_bytes = ((size_t)kPlanWaves * (size_t)(kPlanMaxChunks * ((B + 31) / 32 * 4) + 1) * sizeof(int32_t) + 255) /
+                   256 * 256;
     L.wfrag_bytes = L.steps * (size_t)nfrag_of(R) * 1024;
     L.xoff_bytes = L.steps * 256;
     return L;
@@ -258,7 +271,7 @@ extern "C" int bsp_linear_plan_supported(int xdt, int64_t N, int32_t k_align) {
 
 extern "C" size_t bsp_linear_plan_bytes(int64_t M, int32_t R, int64_t capacity_cols) {
     if (R < 1 || R > 64 || M <= 0 || M % R != 0 || capacity_cols < 0) return 0;
-    return plan_layout(M, R, capacity_cols).total();
+    return plan_layout(M, 1, R, capacity_cols).total();
 }
 
 extern "C" int bsp_linear_plan(int vdt, int64_t M, int64_t N, int32_t R, int32_t k_align, const int32_t *blk_cnt,
@@ -269,7 +282,7 @@ extern "C" int bsp_linear_plan(int vdt, int64_t M, int64_t N, int32_t R, int32_t
     if (!tiled_supported(vdt, N, k_align)) return BSP_ERR_SHAPE;
     if (capacity_cols < 0) return BSP_ERR_CAPACITY;
     if (capacity_cols > 0 && (!col_idx || !vals)) return BSP_ERR_NULL;
-    const PlanLayout L = plan_layout(M, R, capacity_cols);
+    const PlanLayout L = plan_layout(M, N, R, capacity_cols);
     if (plan_bytes < L.total() || !aligned(plan, 16)) return BSP_ERR_CAPACITY;
     const int64_t B = M / R;
     const int nf = nfrag_of(R);
@@ -284,10 +297,11 @@ extern "C" int bsp_linear_plan(int vdt, int64_t M, int64_t N, int32_t R, int32_t
     if ((size_t)B * kPlanMaxChunks * sizeof(int32_t) > L.xoff_bytes) return BSP_ERR_CAPACITY;
     plan_count_kernel<<<(unsigned)B, kThreads, 0, s>>>(blk_cnt, blk_ptr, col_idx, capacity_cols, ch.shift, ch.n,
                                                        steps_bq);
-    plan_scan_kernel<<<1, kPlanWaves * 64, 0, s>>>(steps_bq, (int32_t)B, (int32_t)L.NG, ch.n, (int64_t)L.steps,
+    const int32_t nacc = plan_nacc(nf, ch.n > 1);
+    plan_scan_kernel<<<1, kPlanWaves * 64, 0, s>>>(steps_bq, (int32_t)B, (int32_t)L.NG, nacc, ch.n, (int64_t)L.steps,
                                                    plan_slack_steps(), wptr, xoff);
     if (capacity_cols > 0)
-        plan_fill_kernel<<<dim3((unsigned)B, (unsigned)ch.n), kThreads, 0, s>>>(R, nf, (int32_t)L.NG, ch.shift, ch.n, blk_cnt, blk_ptr,
+        plan_fill_kernel<<<dim3((unsigned)B, (unsigned)ch.n), kThreads, 0, s>>>(R, nf, (int32_t)L.NG, nacc, ch.shift, ch.n, blk_cnt, blk_ptr,
                                                           col_idx, (const uint16_t *)vals, capacity_cols,
                                                           (int64_t)L.steps, wptr, wfrag, xoff);
     return check_launch();
@@ -301,7 +315,7 @@ extern "C" int bsp_linear_planned(const void *X, int xdt, int64_t T, int64_t M, 
     if (capacity_cols < 0) return BSP_ERR_CAPACITY;
     if (!aligned(X, 16) || !aligned(Y, 16) || !aligned(plan, 16)) return BSP_ERR_SHAPE;
     if (T == 0) return BSP_OK;
-    const PlanLayout L = plan_layout(M, R, capacity_cols);
+    const PlanLayout L = plan_layout(M, N, R, capacity_cols);
     TiledArgs a{};
     a.xdt = xdt;
     a.X = (const uint16_t *)X;
