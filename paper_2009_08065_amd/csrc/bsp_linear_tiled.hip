@@ -505,12 +505,15 @@ __device__ __forceinline__ void clear_quad(f32x4 (&acc)[NACC][NFRAG][NSUB]) {
 constexpr uint32_t kXTileBytes = 4 * 32768;  // 64 tokens x 1024 columns
 constexpr uint32_t kOutStageBytes = 4096;    // per wavefront: 64 token rows x 64 bytes
 
-template <int DT, int NFRAG>
+// FAST: R == 16 * NFRAG (every fragment is full and the staged store applies); otherwise outputs are
+// stored one by one.  A template parameter, because the output code is inlined at every slot of the
+// unrolled operand ring and the kernel has to stay small enough for the instruction cache.
+template <int DT, int NFRAG, bool FAST>
 __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
     const uint16_t *__restrict__ X, int64_t T, int64_t M, int64_t N, int32_t R, int32_t npad,
     const int32_t *__restrict__ wptr, const uint32_t *__restrict__ wfrag, const uint32_t *__restrict__ xoff,
     const void *__restrict__ bias, void *__restrict__ Y, int32_t ntiles, int32_t groups_per_strip, int32_t NG,
-    int32_t B, int32_t max_step, int32_t fast_store) {
+    int32_t B, int32_t max_step) {
     constexpr int NSUB = 4;
     constexpr int NACC = plan_nacc(NFRAG, false);  // row-blocks of a wavefront's run: their fragments pair up
     constexpr int RING = kPlanRing / NFRAG;        // the same bytes in flight for every fragment count
@@ -528,7 +531,6 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
     // this wavefront's row of step pointers, from the strip's first entry on (uniform: scalar loads)
     const int32_t *my = wptr + (int64_t)wave * ((int64_t)NG * NACC + 1) + (int64_t)g0 * NACC;
     uint8_t *stg = smem_x + kXTileBytes + wave * kOutStageBytes;
-    const bool fast = fast_store != 0;
     uint16_t *Yh = (uint16_t *)Y;
 
     f32x4 acc[NFRAG][NSUB];
@@ -555,7 +557,7 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
     auto load_bias = [&](int64_t b) {
 #pragma unroll
         for (int f = 0; f < NFRAG; ++f) bvp[f] = make_uint2(0u, 0u);  // +0 in both formats
-        if (bias && fast && b < B) {
+        if (FAST && bias && b < B) {
 #pragma unroll
             for (int f = 0; f < NFRAG; ++f)
                 bvp[f] = *reinterpret_cast<const uint2 *>((const uint16_t *)bias + b * R + f * 16 + 4 * G);
@@ -564,7 +566,7 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
     // Output of the finished row-block b (the accumulators hold it).
     auto finish_block = [&](int64_t b) __attribute__((always_inline)) {
         if (b >= B) return;  // uniform
-        if (fast) {
+        if constexpr (FAST) {
 #pragma unroll
             for (int f = 0; f < NFRAG; ++f) {
                 const int slot = NFRAG == 1 ? (int)(b & 1) : (f & 1);  // half of the 64-byte staging row
@@ -831,6 +833,9 @@ int launch_canonical(const TiledArgs &a, int waves, hipStream_t s) {
     return check_launch();
 }
 
+template <int DT, int NFRAG, bool FAST>
+int launch_planned_1024(const TiledArgs &a, int64_t ntiles, int64_t NG, int64_t max_step, hipStream_t s);
+
 template <int DT, int NFRAG>
 int launch_planned(const TiledArgs &a, hipStream_t s) {
     const int NACC = plan_nacc(NFRAG, a.npad > 1024);
@@ -852,8 +857,14 @@ int launch_planned(const TiledArgs &a, hipStream_t s) {
             (int32_t)NG, (int32_t)a.B, ch.n, (int32_t)max_step, fast);
         return check_launch();
     }
+    if (fast) return launch_planned_1024<DT, NFRAG, true>(a, ntiles, NG, max_step, s);
+    return launch_planned_1024<DT, NFRAG, false>(a, ntiles, NG, max_step, s);
+}
+
+template <int DT, int NFRAG, bool FAST>
+int launch_planned_1024(const TiledArgs &a, int64_t ntiles, int64_t NG, int64_t max_step, hipStream_t s) {
     static thread_local size_t configured = 0;
-    auto kern = linear_tiled_planned_kernel<DT, NFRAG>;
+    auto kern = linear_tiled_planned_kernel<DT, NFRAG, FAST>;
     const size_t lds_planned = kXTileBytes + (size_t)kPlanWaves * kOutStageBytes;  // all 160 KiB of a compute unit
     int st = raise_lds_limit(kern, lds_planned, configured);
     if (st != BSP_OK) return st;
@@ -865,7 +876,7 @@ int launch_planned(const TiledArgs &a, hipStream_t s) {
     if (ntiles * nstrips >= ((int64_t)1 << 31)) return BSP_ERR_SHAPE;
     kern<<<dim3((unsigned)(ntiles * nstrips)), dim3(kPlanWaves * 64), lds_planned, s>>>(
         a.X, a.T, a.M, a.N, a.R, a.npad, a.wptr, (const uint32_t *)a.wfrag, a.xoff, a.bias, a.Y, (int32_t)ntiles,
-        (int32_t)gps, (int32_t)NG, (int32_t)a.B, (int32_t)max_step, fast);
+        (int32_t)gps, (int32_t)NG, (int32_t)a.B, (int32_t)max_step);
     return check_launch();
 }
 
