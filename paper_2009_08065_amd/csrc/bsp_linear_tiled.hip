@@ -42,8 +42,9 @@ typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
 constexpr int kMaxStripBlocks = 1024;  // row-blocks per strip (their blk_ptr slice is cached in LDS)
 constexpr int kRing = 4;               // steps of operands in flight per wavefront, canonical kernel
-constexpr int kPlanRing = 16;          // the same for the column-chunked planned kernel: 8 wavefronts x 16 steps x
-                                       // 1.25 KiB in flight per compute unit cover the L2 latency of the operand stream
+constexpr int kPlanRing = 8;           // the same for the planned kernels, divided by the fragments per step.  Deeper
+                                       // rings were measured slower (4 to 8 steps are equal, 16 is 10 % slower):
+                                       // latency is covered, and more requests in flight only queue up
 
 // Distance in LDS between the 16-token sub-tiles of a workgroup's X tile: a constant, so that
 // sub-tile offsets fold into the immediate field of the LDS instructions.
@@ -534,7 +535,7 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
     uint16_t *Yh = (uint16_t *)Y;
 
     f32x4 acc[NFRAG][NSUB];
-    uint2 bvp[NFRAG];  // bias of the lane's 4 columns per fragment of the current block, as stored
+    uint32_t bs[NFRAG][8];  // bias of the current block as stored, 16 values per fragment (uniform)
     uint4 ra[RING][NFRAG];
     uint32_t rx[RING];
     uint4 xb[2][NSUB];  // X fragments of the current step (even / odd ping-pong, resolved by the unrolling)
@@ -553,14 +554,21 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
         if constexpr (DT == BSP_BF16) return __uint_as_float(h << 16);
         else return (float)__builtin_bit_cast(_Float16, (uint16_t)h);
     };
-    // Issued when a row-block starts, used when it ends: nothing waits on it in between.
+    // Issued when a row-block starts, used when it ends.  The address is uniform, so these are scalar
+    // loads: a vector load here would put a "wait for (nearly) all vector loads" in front of the use,
+    // because vector loads complete in order, and drain the operand ring at every row-block.
+    const uint32_t *bias32 = (const uint32_t *)bias;
+    const uint32_t gm[4] = {G == 0 ? ~0u : 0u, G == 1 ? ~0u : 0u, G == 2 ? ~0u : 0u, G == 3 ? ~0u : 0u};
     auto load_bias = [&](int64_t b) {
 #pragma unroll
-        for (int f = 0; f < NFRAG; ++f) bvp[f] = make_uint2(0u, 0u);  // +0 in both formats
+        for (int f = 0; f < NFRAG; ++f)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) bs[f][i] = 0u;  // +0 in both formats
         if (FAST && bias && b < B) {
 #pragma unroll
             for (int f = 0; f < NFRAG; ++f)
-                bvp[f] = *reinterpret_cast<const uint2 *>((const uint16_t *)bias + b * R + f * 16 + 4 * G);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) bs[f][i] = bias32[(b * R + f * 16) / 2 + i];
         }
     };
     // Output of the finished row-block b (the accumulators hold it).
@@ -570,8 +578,12 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
 #pragma unroll
             for (int f = 0; f < NFRAG; ++f) {
                 const int slot = NFRAG == 1 ? (int)(b & 1) : (f & 1);  // half of the 64-byte staging row
-                const float b0 = widen(bvp[f].x & 0xffffu), b1 = widen(bvp[f].x >> 16);
-                const float b2 = widen(bvp[f].y & 0xffffu), b3 = widen(bvp[f].y >> 16);
+                // the lane's 4 columns 4 G .. 4 G + 3 are words 2 G and 2 G + 1 of the fragment's 8
+                // (picked with lane masks: and / or of uniform words, no indexing)
+                const uint32_t w0 = (bs[f][0] & gm[0]) | (bs[f][2] & gm[1]) | (bs[f][4] & gm[2]) | (bs[f][6] & gm[3]);
+                const uint32_t w1 = (bs[f][1] & gm[0]) | (bs[f][3] & gm[1]) | (bs[f][5] & gm[2]) | (bs[f][7] & gm[3]);
+                const float b0 = widen(w0 & 0xffffu), b1 = widen(w0 >> 16);
+                const float b2 = widen(w1 & 0xffffu), b3 = widen(w1 >> 16);
 #pragma unroll
                 for (int u = 0; u < NSUB; ++u) {
                     uint2 o;
@@ -842,7 +854,8 @@ int launch_planned(const TiledArgs &a, hipStream_t s) {
     const size_t lds = 4 * (size_t)sub_stride<4>();  // 64 tokens x 1024 columns
     const int64_t ntiles = (a.T + 63) / 64;
     const int64_t NG = (a.B + kPlanWaves * NACC - 1) / (kPlanWaves * NACC);
-    const int32_t fast = a.R == 16 * NFRAG ? 1 : 0;
+    // the staged store path: full fragments, and a bias that can be read in 4-byte words
+    const int32_t fast = (a.R == 16 * NFRAG && (reinterpret_cast<uintptr_t>(a.bias) & 3) == 0) ? 1 : 0;
     const int64_t max_step = a.plan_steps - plan_slack_steps();
     if (max_step < 0 || max_step > INT32_MAX) return BSP_ERR_CAPACITY;
     if (a.npad > 1024) {

@@ -249,6 +249,38 @@ def test_linear_wide_layers_in_column_chunks(dtype, R, T, M, N, p_keep):
     run_layer(d["X"], d["W"], None, R, keep, 64, dtype)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("R,T,M,N", [(16, 100, 80, 200), (16, 4100, 2128, 512), (32, 200, 224, 1024), (64, 130, 320, 640)])
+def test_linear_planned_output_staging(dtype, R, T, M, N):
+    # layers of up to 1024 columns on the planned path: an odd number of row-blocks (the last one leaves
+    # alone), several strips and groups, one and two fragments per staged row, ragged token tiles
+    d = wl.layer(R + T + M, T, M, N, dtype)
+    keep = wl.bernoulli_keep_mask(R + T + M + 1, M // R, N, 0.25)
+    keep[1, :] = 0
+    keep[M // R - 1, :] = 0                              # the lone last block with nothing kept
+    rows = None if T < 1000 else [(0, 70), (2040, 2060), (4090, 4100)]
+    run_layer(d["X"], d["W"], d["bias"], R, keep, 32, dtype, T_rows=rows)
+    keep[M // R - 1, ::3] = 1
+    run_layer(d["X"], d["W"], None, R, keep, 32, dtype, T_rows=rows)
+
+
+def test_linear_planned_bias_at_odd_address():
+    # a bias that starts on a 2-byte boundary cannot be read in 4-byte words: the element-wise output path
+    R, T, M, N = 16, 90, 96, 256
+    d = wl.layer(5150, T, M, N, "bf16")
+    keep = wl.bernoulli_keep_mask(5151, M // R, N, 0.3)
+    p_ref = orc.pack(d["W"], R, keep, 32, CODE["bf16"])
+    p = bsp.bsp_pack(dev(d["W"], "bf16"), R, torch.from_numpy(keep).cuda(), 32)
+    holder = torch.zeros(M + 1, dtype=torch.bfloat16, device="cuda")
+    holder[1:] = dev(d["bias"], "bf16")
+    bias_odd = holder[1:]
+    assert bias_odd.data_ptr() % 4 == 2
+    Xd = dev(d["X"], "bf16")
+    Y_ref, _ = orc.linear_packed(d["X"], p_ref, d["bias"], ydt=CODE["bf16"], n_threads=8)
+    assert_y_close(host(bsp.bsp_linear_planned(Xd, p, bsp.bsp_linear_plan(p), bias_odd)), Y_ref, "bf16")
+    assert_y_close(host(bsp.bsp_linear(Xd, p, bias_odd)), Y_ref, "bf16")
+
+
 def test_linear_wide_layer_many_tokens_ragged_strips():
     # enough token tiles that every wavefront carries 4 row-blocks across the chunks; 133 row-blocks
     # leave the last strip with one group and that group with 5 of its 8 row-blocks
