@@ -502,7 +502,7 @@ __device__ __forceinline__ void clear_quad(f32x4 (&acc)[NACC][NFRAG][NSUB]) {
 // 64 bytes; every second fragment (two row-blocks for R = 16, one for R = 32, half a one for R = 64)
 // the buffer holds 32 consecutive output columns of all 64 tokens and is written with 16-byte lanes,
 // 64 contiguous bytes per token row.  The LDS operations of a wavefront complete in order, so the
-// buffer needs no barrier.
+// buffer needs no barrier.  (In the read, row = 16 i + lane / 4, so row / 4 % 4 is the lane's G.)
 constexpr uint32_t kXTileBytes = 4 * 32768;  // 64 tokens x 1024 columns
 constexpr uint32_t kOutStageBytes = 4096;    // per wavefront: 64 token rows x 64 bytes
 
@@ -532,6 +532,10 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
     // this wavefront's row of step pointers, from the strip's first entry on (uniform: scalar loads)
     const int32_t *my = wptr + (int64_t)wave * ((int64_t)NG * NACC + 1) + (int64_t)g0 * NACC;
     uint8_t *stg = smem_x + kXTileBytes + wave * kOutStageBytes;
+    // 16-byte pieces of a staging row are stored at piece ^ (row / 4 % 4): with a pitch of 64 bytes both the
+    // 8-byte writes (16 token rows per half-wavefront) and the 16-byte reads (4 rows per 16 lanes) then
+    // spread over all LDS banks; unswizzled, the writes are a 4-way bank conflict
+    const int swz = (l16 >> 2) & 3;
     uint16_t *Yh = (uint16_t *)Y;
 
     f32x4 acc[NFRAG][NSUB];
@@ -589,7 +593,7 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
                     uint2 o;
                     o.x = cvt_pk<DT>(acc[f][u][0] + b0, acc[f][u][1] + b1);
                     o.y = cvt_pk<DT>(acc[f][u][2] + b2, acc[f][u][3] + b3);
-                    *reinterpret_cast<uint2 *>(stg + (16 * u + l16) * 64 + slot * 32 + 8 * G) = o;
+                    *reinterpret_cast<uint2 *>(stg + (16 * u + l16) * 64 + (((slot * 2 + (G >> 1)) ^ swz) << 4) + (G & 1) * 8) = o;
                 }
                 // The staging rows are complete after an odd fragment; a lone last row-block of an
                 // odd-sized layer (R = 16) leaves with its own half only.
@@ -601,7 +605,7 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
 #pragma unroll
                         for (int i = 0; i < 4; ++i) {
                             const int row = 16 * i + (lane >> 2);
-                            const uint4 o = *reinterpret_cast<const uint4 *>(stg + row * 64 + piece * 16);
+                            const uint4 o = *reinterpret_cast<const uint4 *>(stg + row * 64 + ((piece ^ G) << 4));
                             if (t0 + row < T) *reinterpret_cast<uint4 *>(Yh + (t0 + row) * M + col0 + piece * 8) = o;
                         }
                     }
