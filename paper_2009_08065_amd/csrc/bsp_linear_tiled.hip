@@ -543,7 +543,9 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
     uint4 ra[RING][NFRAG];
     uint32_t rx[RING];
     uint4 xb[2][NSUB];  // X fragments of the current step (even / odd ping-pong, resolved by the unrolling)
+    const uint32_t pmask = (uint32_t)(lane & 3) * 0x10001u;
     auto issue_reads = [&](uint32_t w, uint4 (&dst)[NSUB]) {
+        w ^= pmask;  // the stored word is the one of token quad 0
         const uint32_t o1 = (w & 0xffffu) << 3, o2 = (w >> 13) & 0x7fff8u;  // packed in units of 8 bytes
 #pragma unroll
         for (int u = 0; u < NSUB; ++u) {
@@ -664,12 +666,12 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
         // 4-byte-per-lane load moves 256 contiguous bytes, the access width the vector memory
         // pipeline sustains best on this hardware (about 1.6x the bytes per clock of 16-byte loads).
         const uint32_t *wp = wfrag + (int64_t)gs * (NFRAG * 256) + lane;
-        const uint32_t *xp = xoff + (int64_t)gs * 64 + lane;
+        const uint32_t *xp = xoff + (int64_t)gs * 16 + (lane >> 2);
 #pragma unroll
         for (int j = 0; j < RING; ++j) {
 #pragma unroll
             for (int f = 0; f < NFRAG; ++f) ra[j][f] = load_frag(wp + (j * NFRAG + f) * 256);
-            rx[j] = xp[j * 64];
+            rx[j] = xp[j * 16];
         }
         issue_reads(rx[0], xb[0]);
         bool done = false;
@@ -688,7 +690,7 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
                 // refill this ring slot with step gs + RING
 #pragma unroll
                 for (int f = 0; f < NFRAG; ++f) ra[j][f] = load_frag(wp + ((RING + j) * NFRAG + f) * 256);
-                rx[j] = xp[(RING + j) * 64];  // its old value went into the previous sub-iteration's reads
+                rx[j] = xp[(RING + j) * 16];  // its old value went into the previous sub-iteration's reads
                 ++gs;
                 if (gs >= blk_end) {  // uniform
                     pass_boundaries();
@@ -699,7 +701,7 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
                 }
             }
             wp += RING * NFRAG * 256;
-            xp += RING * 64;
+            xp += RING * 16;
         }
     }
 }
@@ -730,7 +732,9 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_chunked_kernel(
     uint4 ra[RING][NFRAG];
     uint32_t rx[RING];
     uint4 xb[2][NSUB];
+    const uint32_t pmask = (uint32_t)(lane & 3) * 0x10001u;
     auto issue_reads = [&](uint32_t w, uint4 (&dst)[NSUB]) {
+        w ^= pmask;  // the stored word is the one of token quad 0
         const uint32_t o1 = (w & 0xffffu) << 3, o2 = (w >> 13) & 0x7fff8u;  // packed in units of 8 bytes
 #pragma unroll
         for (int u = 0; u < NSUB; ++u) {
@@ -754,13 +758,13 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_chunked_kernel(
         gs_hi = min(gs_hi, max_step);
         const bool work = gs < gs_hi;
         const uint32_t *wp = wfrag + (int64_t)gs * (NFRAG * 256) + lane;
-        const uint32_t *xp = xoff + (int64_t)gs * 64 + lane;
+        const uint32_t *xp = xoff + (int64_t)gs * 16 + (lane >> 2);
         if (work) {  // operands of the first RING steps travel while the chunk of X is copied in
 #pragma unroll
             for (int j = 0; j < RING; ++j) {
 #pragma unroll
                 for (int f = 0; f < NFRAG; ++f) ra[j][f] = load_frag(wp + (j * NFRAG + f) * 256);
-                rx[j] = xp[j * 64];
+                rx[j] = xp[j * 16];
             }
         }
         __syncthreads();  // every wavefront is done with the previous chunk of X
@@ -788,7 +792,7 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_chunked_kernel(
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int f = 0; f < NFRAG; ++f) ra[j][f] = load_frag(wp + ((RING + j) * NFRAG + f) * 256);
-                rx[j] = xp[(RING + j) * 64];
+                rx[j] = xp[(RING + j) * 16];
                 ++gs;
                 if (gs >= blk_end) {  // uniform
                     if (gs >= gs_hi) {
@@ -799,7 +803,7 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_chunked_kernel(
                 }
             }
             wp += RING * NFRAG * 256;
-            xp += RING * 64;
+            xp += RING * 16;
         }
     }
 

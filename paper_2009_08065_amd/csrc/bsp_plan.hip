@@ -18,7 +18,8 @@
 //
 // Buffer layout (bytes): wptr int32 [kPlanWaves][4 * NG * nacc + 1], padded to 256 | fragments
 // [steps][nfrag][4][64] dwords (dword k of every lane's 16-byte fragment lies in plane k, so that
-// 4-byte-per-lane loads are contiguous) | offsets uint32 [steps][64], with steps = capacity_cols / 32
+// 4-byte-per-lane loads are contiguous) | offsets uint32 [steps][16] (one word per 4 lanes: the lanes
+// of a column differ by their token quad only), with steps = capacity_cols / 32
 // + 3 per row-block (every chunk pads its columns to a multiple of 32 on its own) + read-ahead slack.
 // Integer work only; deterministic.
 #include "bsp_common.h"
@@ -101,7 +102,7 @@ __global__ __launch_bounds__(kPlanWaves * 64) void plan_scan_kernel(const int32_
     if (w == kPlanWaves - 1) {
         const int64_t total = (int64_t)wbase + carry;
         if (total + slack_steps <= cap_steps)
-            for (int i = lane; i < slack_steps * 64; i += 64) xoff[total * 64 + i] = 0u;
+            for (int i = lane; i < slack_steps * 16; i += 64) xoff[total * 16 + i] = 0u;
     }
 }
 
@@ -215,7 +216,9 @@ __global__ __launch_bounds__(kThreads) void plan_fill_kernel(int32_t R, int32_t 
             const int s1 = 32 * s + 8 * G + qd;
             const uint32_t o1 = lds_col_offset((uint32_t)slotcol[s1], (uint32_t)p);
             const uint32_t o2 = lds_col_offset((uint32_t)slotcol[s1 + 4], (uint32_t)p);
-            xoff[(gs0 + s) * 64 + lane] = (o1 >> 3) | ((o2 >> 3) << 16);  // offsets are multiples of 8 bytes
+            // offsets are multiples of 8 bytes; the 4 lanes of a column (token quads p = 0 .. 3) differ by
+            // p in both halves (the swizzle is an exclusive-or on those bits), so p = 0 stands for all four
+            if (p == 0) xoff[(gs0 + s) * 16 + (lane >> 2)] = (o1 >> 3) | ((o2 >> 3) << 16);
             for (int f = 0; f < nfrag; ++f) {
                 const int r = f * 16 + l16;
                 uint32_t w[4] = {0u, 0u, 0u, 0u};
@@ -256,7 +259,7 @@ inline PlanLayout plan_layout(int64_t M, int64_t N, int32_t R, int64_t capacity_
     L.wptr_bytes = ((size_t)kPlanWaves * (size_t)(kPlanMaxChunks * ((B + 31) / 32 * 4) + 1) * sizeof(int32_t) + 255) /
                    256 * 256;
     L.wfrag_bytes = L.steps * (size_t)nfrag_of(R) * 1024;
-    L.xoff_bytes = L.steps * 256;
+    L.xoff_bytes = L.steps * 64;
     return L;
 }
 
