@@ -124,6 +124,111 @@ def cpu_baseline(mats):
             "sample": f"oracle layer (fp64 accumulate, OpenMP over row-blocks) on the full set, all 8192 tokens; {secs:.1f} s"}
 
 
+def prune_path_c5(layers=24, reps=5):
+    """HBM rate of the pruning pipeline on the 24-layer BERT-large weight set (fp32, 302 M parameters, R = 16):
+    group norms + reweighting factors, regulariser gradient, one global percentile over all 18.9 M groups (5x),
+    pack with fp32 and with bf16 value panels.  Matrices that are adjacent in the buffer and share their
+    width are stacked along the rows into one launch (row-blocks are independent), which leaves two launches
+    per layer.  Every stage is recorded into a HIP graph and replayed `reps` times between two events."""
+    c = wl.config5(layers)
+    R, eps, lam = c["R"], c["eps"], c["lam"]
+    Wbuf = torch.from_numpy(c["W"]).cuda()
+    runs = []                                   # (offset, rows, N) of every stacked launch
+    for off, m, n in c["desc"]:
+        if runs and runs[-1][2] == n and runs[-1][0] + runs[-1][1] * n == off:
+            runs[-1] = (runs[-1][0], runs[-1][1] + m, n)
+        else:
+            runs.append((off, m, n))
+    params = Wbuf.numel()
+    groups = params // R
+    dev = Wbuf.device
+    sumsq = torch.empty(groups, dtype=torch.float32, device=dev)
+    alpha = torch.empty(groups, dtype=torch.float32, device=dev)
+    grad = torch.empty_like(Wbuf)
+    keep = torch.empty(groups, dtype=torch.uint8, device=dev)
+    n_keep = groups * c["rate"][1] // c["rate"][0]
+    Bm, Nm = groups // 1024, 1024               # the global scope: all groups as one [B, N] array
+    ws = torch.empty(bsp.lib().bsp_prune_mask_workspace_bytes(Bm, Nm, bsp.SCOPE_MATRIX), dtype=torch.uint8, device=dev)
+    views = []
+    for off, rows, n in runs:
+        g0, ng = off // R, rows // R * n
+        views.append(dict(W=Wbuf[off:off + rows * n].view(rows, n), G=grad[off:off + rows * n].view(rows, n),
+                          s=sumsq[g0:g0 + ng].view(rows // R, n), a=alpha[g0:g0 + ng].view(rows // R, n),
+                          k=keep[g0:g0 + ng].view(rows // R, n),
+                          cnt=torch.empty(rows // R, dtype=torch.int32, device=dev),
+                          ptr=torch.empty(rows // R + 1, dtype=torch.int32, device=dev)))
+
+    def norms():
+        for v in views:
+            bsp.bsp_group_norms(v["W"], R, eps=eps, mode=bsp.ALPHA_SQNORM, sumsq=v["s"], alpha=v["a"], want=())
+
+    def gradient():
+        for v in views:
+            bsp.bsp_penalty_grad(v["W"], R, v["a"], lam, mode=bsp.ALPHA_SQNORM, grad=v["G"])
+
+    def mask():
+        bsp.bsp_prune_mask(sumsq.view(Bm, Nm), n_keep=n_keep, scope=bsp.SCOPE_MATRIX, keep=keep.view(Bm, Nm), ws=ws)
+
+    def count():
+        for v in views:
+            bsp.bsp_pack_count(v["k"], 32, blk_cnt=v["cnt"], blk_ptr=v["ptr"])
+
+    def pack(vdt):
+        L = bsp.lib()
+        for v in views:
+            rows, n = v["W"].shape
+            st = L.bsp_pack(v["W"].data_ptr(), bsp.F32, rows, n, R, v["k"].data_ptr(), 32, v["cnt"].data_ptr(),
+                            v["ptr"].data_ptr(), v["cap"], v["col"].data_ptr(), v["vals"][vdt].data_ptr(), vdt,
+                            torch.cuda.current_stream().cuda_stream)
+            if st != 0:
+                raise bsp.BspError(st, "bsp_pack")
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            fn()
+        g.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e3   # us
+
+    t = {}
+    t["group_norms"] = timed(norms)
+    t["penalty_grad"] = timed(gradient)
+    t["prune_mask"] = timed(mask)
+    t["pack_count"] = timed(count)
+    kept = 0
+    for v in views:                                 # capacities, read back once
+        v["cap"] = int(v["ptr"][-1].item())
+        kept += int(v["cnt"].sum().item())
+        v["col"] = torch.empty(max(v["cap"], 1), dtype=torch.int32, device=dev)
+        v["vals"] = {bsp.F32: torch.empty(max(R * v["cap"], 1), dtype=torch.float32, device=dev),
+                     bsp.BF16: torch.empty(max(R * v["cap"], 1), dtype=torch.bfloat16, device=dev)}
+    t["pack_fp32"] = timed(lambda: pack(bsp.F32))
+    t["pack_bf16"] = timed(lambda: pack(bsp.BF16))
+    padded = sum(v["cap"] for v in views)
+    # algorithmic bytes: W fp32 read once per stage that needs it, group arrays fp32, the mask 1 byte per group
+    by = {"group_norms": 4.0 * params + 8.0 * groups,
+          "penalty_grad": 8.0 * params + 4.0 * groups,
+          "prune_mask": (4.0 * 4 + 1.0) * groups,
+          "pack_count": 1.0 * groups,
+          "pack_fp32": 4.0 * params + 1.0 * groups + (4.0 * R + 4.0) * padded,
+          "pack_bf16": 4.0 * params + 1.0 * groups + (2.0 * R + 4.0) * padded}
+    stages = {k: {"us": round(t[k], 1), "gbs": round(by[k] / (t[k] * 1e-6) / 1e9, 1),
+                  "frac_hbm_peak": round(by[k] / (t[k] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)} for k in t}
+    return {"workload": "config 5: %d-layer BERT-large weight set, fp32, %d parameters, R = 16, global 5x percentile"
+                        % (layers, params),
+            "launches_per_stage": len(views), "groups": groups, "kept_groups": kept,
+            "rate": round(params / (R * max(kept, 1)), 4), "stages": stages}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -140,6 +245,8 @@ def main():
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one 256 MiB device-to-device copy (a kernel of known traffic, to scale the "
                          "profiler's memory counters)")
+    ap.add_argument("--no-c5", action="store_true",
+                    help="skip the bandwidth measurement of the pruning pipeline on the 302 M parameter weight set")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: the path has no multi-GPU part; run with --gpus 1", file=sys.stderr)
@@ -303,6 +410,10 @@ def main():
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(mats)
+    if not args.no_c5:
+        del mats
+        torch.cuda.empty_cache()
+        out["prune_path_c5"] = prune_path_c5()
     print(json.dumps(out))
 
 

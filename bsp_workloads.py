@@ -122,9 +122,12 @@ def config4(tokens=8192, R=16, shapes=None):
 
 
 def config5_shapes(layers=24):
-    """(M, N) of every matrix of a BERT-large weight set: per layer Q, K, V, O, up, down."""
-    per_layer = [(1024, 1024)] * 4 + [(4096, 1024), (1024, 4096)]
-    return per_layer * layers
+    """(M, N) of every matrix of a BERT-large weight set (per layer Q, K, V, O, up, down), in buffer order:
+    the matrices of width 1024 of all layers first, then the down-projections (width 4096), as a flat
+    parameter buffer that groups tensors of one shape would hold them."""
+    narrow = ([(1024, 1024)] * 4 + [(4096, 1024)]) * layers
+    wide = [(1024, 4096)] * layers
+    return narrow + wide
 
 
 def config5(layers=24):

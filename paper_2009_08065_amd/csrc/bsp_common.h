@@ -48,6 +48,7 @@ struct elem<BSP_F32> {
     using type = float;
     static __device__ __forceinline__ float load(const void *p, int64_t i) { return ((const float *)p)[i]; }
     static __device__ __forceinline__ void store(void *p, int64_t i, float v) { ((float *)p)[i] = v; }
+    static __device__ __forceinline__ uint32_t bits(float v) { return __float_as_uint(v); }
 };
 template <>
 struct elem<BSP_BF16> {
@@ -58,6 +59,8 @@ struct elem<BSP_BF16> {
     static __device__ __forceinline__ void store(void *p, int64_t i, float v) {
         ((uint16_t *)p)[i] = float_to_bf16(v);
     }
+    // the stored 16 bits of v (round-to-nearest-even), for packing two values into one word
+    static __device__ __forceinline__ uint32_t bits(float v) { return float_to_bf16(v); }
 };
 template <>
 struct elem<BSP_F16> {
@@ -67,6 +70,9 @@ struct elem<BSP_F16> {
     }
     static __device__ __forceinline__ void store(void *p, int64_t i, float v) {
         ((_Float16 *)p)[i] = (_Float16)v;  // v_cvt_f16_f32, round-to-nearest-even
+    }
+    static __device__ __forceinline__ uint32_t bits(float v) {
+        return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)v);
     }
 };
 

@@ -269,14 +269,16 @@ __global__ __launch_bounds__(kThreads) void penalty_grad_kernel(const void *__re
 }
 
 // Squared-norm form without the penalty value: coef depends on alpha only, so the gradient is a
-// plain element-wise product; one lane per 16-byte vector of W, rows of W along grid.y.
+// plain element-wise product; one lane per 16-byte vector of W, rows of W along grid.y (and grid.z
+// beyond 65535 rows).
 template <int DT, int VEC>
-__global__ __launch_bounds__(kThreads) void penalty_grad_sq_kernel(const void *__restrict__ W, int64_t N, int32_t R,
+__global__ __launch_bounds__(kThreads) void penalty_grad_sq_kernel(const void *__restrict__ W, int64_t M, int64_t N, int32_t R,
                                                                    const float *__restrict__ alpha, float lambda,
                                                                    int accumulate, void *__restrict__ G) {
     const int64_t j = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * VEC;
     if (j >= N) return;
-    const int64_t m = blockIdx.y;
+    const int64_t m = (int64_t)blockIdx.z * 65535 + blockIdx.y;
+    if (m >= M) return;
     float a[VEC], w[VEC], g[VEC];
     load_f32<VEC>(alpha, (m / R) * N + j, a);
     vec_io<DT, VEC>::load(W, m * N + j, w);
@@ -339,6 +341,7 @@ extern "C" int bsp_group_norms(const void *W, int wdt, int64_t M, int64_t N, int
     hipStream_t s = (hipStream_t)stream;
     BSP_DISPATCH_DTYPE(wdt, DT, {
         constexpr int V = native_vec<DT>();
+        // (4-byte lanes: 16-byte lanes were measured slower here, on small and on large matrices alike)
         const bool vec_ok = (N % V == 0) && aligned(W, 16) && (!sumsq || aligned(sumsq, 16)) &&
                             (!norm || aligned(norm, 16)) && (!alpha || aligned(alpha, 16));
         if (vec_ok)
@@ -393,18 +396,19 @@ extern "C" int bsp_penalty_grad(const void *W, int wdt, int64_t M, int64_t N, in
     }
     hipStream_t s = (hipStream_t)stream;
     double *partial = (double *)ws;
-    if (mode == BSP_ALPHA_SQNORM && !penalty && M <= 65535) {
+    if (mode == BSP_ALPHA_SQNORM && !penalty) {
+        const unsigned gy = (unsigned)(M < 65535 ? M : 65535), gz = (unsigned)((M + 65534) / 65535);
         BSP_DISPATCH_DTYPE(wdt, DT, {
             constexpr int V16 = DT == BSP_F32 ? 4 : 8;  // 16 bytes per lane: every lane is independent here
             const bool vec_ok = (N % V16 == 0) && aligned(W, 16) && aligned(grad, 16) && aligned(alpha, 16);
             if (vec_ok) {
                 const int64_t nv = N / V16;
                 const unsigned bs = nv >= 256 ? 256 : (unsigned)((nv + 63) / 64 * 64);
-                penalty_grad_sq_kernel<DT, V16><<<dim3((unsigned)((nv + bs - 1) / bs), (unsigned)M), bs, 0, s>>>(
-                    W, N, R, alpha, lambda, accumulate, grad);
+                penalty_grad_sq_kernel<DT, V16><<<dim3((unsigned)((nv + bs - 1) / bs), gy, gz), bs, 0, s>>>(
+                    W, M, N, R, alpha, lambda, accumulate, grad);
             } else {
-                penalty_grad_sq_kernel<DT, 1><<<dim3((unsigned)((N + 255) / 256), (unsigned)M), 256, 0, s>>>(
-                    W, N, R, alpha, lambda, accumulate, grad);
+                penalty_grad_sq_kernel<DT, 1><<<dim3((unsigned)((N + 255) / 256), gy, gz), 256, 0, s>>>(
+                    W, M, N, R, alpha, lambda, accumulate, grad);
             }
         });
         return check_launch();

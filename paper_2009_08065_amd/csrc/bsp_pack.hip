@@ -18,14 +18,16 @@ constexpr int kWaves = kThreads / kWave;
 
 __device__ __forceinline__ int round_up(int k, int a) { return ((k + a - 1) / a) * a; }
 
-// One workgroup per row of keep[B, N].
-__global__ __launch_bounds__(kThreads) void pack_count_kernel(const uint8_t *__restrict__ keep, int64_t N,
+// One wavefront per row of keep[B, N] (kWaves rows per workgroup).
+__global__ __launch_bounds__(kThreads) void pack_count_kernel(const uint8_t *__restrict__ keep, int64_t B, int64_t N,
                                                               int32_t *__restrict__ blk_cnt) {
-    __shared__ int wsum[kWaves];
-    const uint8_t *row = keep + (int64_t)blockIdx.x * N;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t b = (int64_t)blockIdx.x * kWaves + threadIdx.x / kWave;
+    if (b >= B) return;  // whole wavefronts leave
+    const uint8_t *row = keep + b * N;
     int cnt = 0;
     if (((reinterpret_cast<uintptr_t>(row) | (uintptr_t)N) & 15) == 0) {  // 16 flags per load
-        for (int64_t j = (int64_t)threadIdx.x * 16; j < N; j += kThreads * 16) {
+        for (int64_t j = (int64_t)lane * 16; j < N; j += kWave * 16) {
             const uint4 q = *reinterpret_cast<const uint4 *>(row + j);
             const uint32_t w[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
@@ -34,49 +36,132 @@ __global__ __launch_bounds__(kThreads) void pack_count_kernel(const uint8_t *__r
                                 (w[k] >> 7)) & 0x01010101u));
         }
     } else {
-        for (int64_t j = threadIdx.x; j < N; j += kThreads) cnt += row[j] != 0;
+        for (int64_t j = lane; j < N; j += kWave) cnt += row[j] != 0;
     }
 #pragma unroll
     for (int o = kWave / 2; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o, kWave);
-    if ((threadIdx.x & (kWave - 1)) == 0) wsum[threadIdx.x / kWave] = cnt;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        int t = 0;
-        for (int w = 0; w < kWaves; ++w) t += wsum[w];
-        blk_cnt[blockIdx.x] = t;
-    }
+    if (lane == 0) blk_cnt[b] = cnt;
 }
 
-// Single workgroup: blk_ptr = exclusive scan of the padded counts, blk_ptr[B] = total.
-__global__ __launch_bounds__(kThreads) void pack_scan_kernel(const int32_t *__restrict__ blk_cnt, int64_t B,
-                                                             int32_t k_align, int32_t *__restrict__ blk_ptr) {
-    __shared__ int wsum[kWaves];
-    __shared__ int carry;
-    if (threadIdx.x == 0) carry = 0;
-    __syncthreads();
+// Single workgroup: blk_ptr = exclusive scan of the padded counts, blk_ptr[B] = total.  Every thread owns a
+// run of consecutive row-blocks (sums it, the workgroup scans the run sums, the thread writes its run).
+constexpr int kScanThreads = 1024;
+__global__ __launch_bounds__(kScanThreads) void pack_scan_kernel(const int32_t *__restrict__ blk_cnt, int64_t B,
+                                                                 int32_t k_align, int32_t *__restrict__ blk_ptr) {
+    __shared__ int wsum[kScanThreads / kWave];
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-    for (int64_t base = 0; base < B; base += kThreads) {
-        const int64_t b = base + threadIdx.x;
-        const int kp = b < B ? round_up(blk_cnt[b], k_align) : 0;
-        int incl = kp;
+    const int64_t per = (B + kScanThreads - 1) / kScanThreads;
+    const int64_t lo = (int64_t)threadIdx.x * per, hi = lo + per < B ? lo + per : B;
+    int mine = 0;
+    for (int64_t b = lo; b < hi; ++b) mine += round_up(blk_cnt[b], k_align);
+    int incl = mine;
 #pragma unroll
-        for (int o = 1; o < kWave; o <<= 1) {
-            int up = __shfl_up(incl, o, kWave);
-            if (lane >= o) incl += up;
-        }
-        if (lane == kWave - 1) wsum[wave] = incl;
-        __syncthreads();
-        int woff = 0;
-        for (int w = 0; w < wave; ++w) woff += wsum[w];
-        const int c = carry;
-        if (b < B) blk_ptr[b] = c + woff + incl - kp;
-        __syncthreads();
-        if (threadIdx.x == kThreads - 1) carry = c + woff + incl;
-        __syncthreads();
+    for (int o = 1; o < kWave; o <<= 1) {
+        const int up = __shfl_up(incl, o, kWave);
+        if (lane >= o) incl += up;
     }
-    if (threadIdx.x == 0) blk_ptr[B] = carry;
+    if (lane == kWave - 1) wsum[wave] = incl;
+    __syncthreads();
+    int run = incl - mine;
+    for (int w = 0; w < wave; ++w) run += wsum[w];
+    for (int64_t b = lo; b < hi; ++b) {
+        blk_ptr[b] = run;
+        run += round_up(blk_cnt[b], k_align);
+    }
+    if (threadIdx.x == kScanThreads - 1) blk_ptr[B] = run;  // the last thread's run ends at B (or is empty)
 }
 
+// Compaction in two stages.  Every workgroup first builds the ascending list of the row-block's kept columns
+// in LDS (the keep row cut into chunks of 64 columns, one wavefront ballot each: count, scan, place).  Then it
+// works by *output position*: consecutive lanes take consecutive positions of the panel, so panel rows are
+// written contiguously (16-bit values two per lane, packed) and no lane idles on a pruned column.  gridDim.y
+// workgroups share a row-block when there are few row-blocks: each repeats the cheap first stage and takes a
+// run of positions.
+constexpr int kPackThreads = 1024;  // 16 wavefronts
+constexpr int kPackWaves = kPackThreads / kWave;
+constexpr int kPackMaxCols = 16384;  // widest layer for this kernel: the kept-column list is 16-bit in LDS
+
+template <int WDT, int VDT>
+__global__ __launch_bounds__(kPackThreads) void pack_positions_kernel(const void *__restrict__ W, int64_t N, int32_t R,
+                                                                      const uint8_t *__restrict__ keep,
+                                                                      const int32_t *__restrict__ blk_cnt,
+                                                                      const int32_t *__restrict__ blk_ptr,
+                                                                      int64_t capacity_cols, int32_t *__restrict__ col_idx,
+                                                                      void *__restrict__ vals) {
+    __shared__ int chunk_off[kPackMaxCols / kWave + 1];
+    __shared__ uint16_t s_cols[kPackMaxCols];
+    const int64_t b = blockIdx.x;
+    const int64_t base = blk_ptr[b];
+    const int kp = blk_ptr[b + 1] - blk_ptr[b];
+    const int kb = blk_cnt[b];
+    if (kp <= 0 || kb <= 0 || kb > kp || kb > N || base < 0 || base + kp > capacity_cols) return;  // uniform per workgroup
+    const uint8_t *krow = keep + b * N;
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const int nchunks = (int)((N + kWave - 1) / kWave);
+    const uint64_t lt = (1ull << lane) - 1ull;
+    for (int c = wave; c < nchunks; c += kPackWaves) {
+        const int64_t j = (int64_t)c * kWave + lane;
+        const uint64_t m = __ballot(j < N && krow[j] != 0);
+        if (lane == 0) chunk_off[c] = __popcll(m);
+    }
+    __syncthreads();
+    if (wave == 0) {  // exclusive scan of the chunk counts
+        int run = 0;
+        for (int cb = 0; cb < nchunks; cb += kWave) {
+            const int c = cb + lane;
+            const int v = c < nchunks ? chunk_off[c] : 0;
+            int incl = v;
+#pragma unroll
+            for (int o = 1; o < kWave; o <<= 1) {
+                const int up = __shfl_up(incl, o, kWave);
+                if (lane >= o) incl += up;
+            }
+            if (c < nchunks) chunk_off[c] = run + incl - v;
+            run += __shfl(incl, kWave - 1, kWave);
+        }
+    }
+    __syncthreads();
+    for (int c = wave; c < nchunks; c += kPackWaves) {
+        const int64_t j = (int64_t)c * kWave + lane;
+        const bool k = j < N && krow[j] != 0;
+        const uint64_t m = __ballot(k);
+        const int pos = chunk_off[c] + __popcll(m & lt);
+        if (k && pos < kb) s_cols[pos] = (uint16_t)j;
+    }
+    __syncthreads();
+    // this workgroup's run of positions, whole 64-position pieces
+    const int pieces = (kp + kWave - 1) / kWave;
+    const int per = (pieces + (int)gridDim.y - 1) / (int)gridDim.y;
+    const int p_lo = min((int)blockIdx.y * per, pieces) * kWave, p_hi = min(((int)blockIdx.y + 1) * per * kWave, kp);
+    if (p_lo >= p_hi) return;
+    const int last = s_cols[kb - 1];
+    for (int pos = p_lo + threadIdx.x; pos < p_hi; pos += kPackThreads) col_idx[base + pos] = pos < kb ? (int)s_cols[pos] : last;
+    // values: a unit is (row r, 64-position piece); wavefronts take units in turn.  Pads are +0.
+    const int npc = (p_hi - p_lo + kWave - 1) / kWave;
+    const int64_t vbase = (int64_t)R * base, wbase = b * R * N;
+    constexpr bool kPairs = VDT != BSP_F32;  // 16-bit values: a lane packs two neighbours into one 4-byte store
+    const bool pairs = kPairs && (kp & 1) == 0 && (vbase & 1) == 0 && (reinterpret_cast<uintptr_t>(vals) & 3) == 0;
+    if (pairs) {
+        const int npc2 = (p_hi - p_lo + 2 * kWave - 1) / (2 * kWave);
+        for (int u = wave; u < R * npc2; u += kPackWaves) {
+            const int r = u / npc2, pos = p_lo + (u % npc2) * (2 * kWave) + 2 * lane;
+            if (pos >= p_hi) continue;
+            const float v0 = pos < kb ? elem<WDT>::load(W, wbase + (int64_t)r * N + s_cols[pos]) : 0.0f;
+            const float v1 = pos + 1 < kb ? elem<WDT>::load(W, wbase + (int64_t)r * N + s_cols[pos + 1]) : 0.0f;
+            const uint32_t lo = elem<VDT>::bits(v0), hi = elem<VDT>::bits(v1);
+            *reinterpret_cast<uint32_t *>((uint16_t *)vals + vbase + (int64_t)r * kp + pos) = lo | (hi << 16);
+        }
+    } else {
+        for (int u = wave; u < R * npc; u += kPackWaves) {
+            const int r = u / npc, pos = p_lo + (u % npc) * kWave + lane;
+            if (pos >= p_hi) continue;
+            const float v = pos < kb ? elem<WDT>::load(W, wbase + (int64_t)r * N + s_cols[pos]) : 0.0f;
+            elem<VDT>::store(vals, vbase + (int64_t)r * kp + pos, v);
+        }
+    }
+}
+
+// The same for layers wider than kPackMaxCols: compaction and copy chunk by chunk, one lane per column.
 // One or more workgroups per row-block (gridDim.y of them share a block when there are few blocks: each
 // takes an equal run of 64-column chunks).  The keep row is cut into chunks of 64 columns, one wavefront
 // ballot each: pass 1 counts the kept columns of every chunk, wavefront 0 scans the counts, pass 2
@@ -85,9 +170,6 @@ __global__ __launch_bounds__(kThreads) void pack_scan_kernel(const int32_t *__re
 // contiguous in c.
 constexpr int kMaxChunks = 1024;  // 64-column chunks handled with LDS-resident counts (N <= 65536)
 
-constexpr int kPackThreads = 1024;  // 16 wavefronts: one 64-column chunk each for N = 1024, so the chunks'
-                                    // load -> ballot -> gather chains run side by side
-constexpr int kPackWaves = kPackThreads / kWave;
 
 template <int WDT, int VDT>
 __global__ __launch_bounds__(kPackThreads) void pack_kernel(const void *__restrict__ W, int64_t N, int32_t R,
@@ -207,8 +289,8 @@ extern "C" int bsp_pack_count(const uint8_t *keep, int64_t B, int64_t N, int32_t
     if (B <= 0 || N <= 0 || N >= ((int64_t)1 << 31) - 64 || B >= ((int64_t)1 << 31) || !valid_align(k_align)) return BSP_ERR_SHAPE;
     if ((B * (N + 63)) >= ((int64_t)1 << 31)) return BSP_ERR_SHAPE;  // blk_ptr is int32
     hipStream_t s = (hipStream_t)stream;
-    pack_count_kernel<<<(unsigned)B, kThreads, 0, s>>>(keep, N, blk_cnt);
-    pack_scan_kernel<<<1, kThreads, 0, s>>>(blk_cnt, B, k_align, blk_ptr);
+    pack_count_kernel<<<(unsigned)((B + kWaves - 1) / kWaves), kThreads, 0, s>>>(keep, B, N, blk_cnt);
+    pack_scan_kernel<<<1, kScanThreads, 0, s>>>(blk_cnt, B, k_align, blk_ptr);
     return check_launch();
 }
 
@@ -229,8 +311,12 @@ extern "C" int bsp_pack(const void *W, int wdt, int64_t M, int64_t N, int32_t R,
     const unsigned split = (unsigned)(split64 < 1 ? 1 : split64);
     BSP_DISPATCH_DTYPE(wdt, WDT, {
         BSP_DISPATCH_DTYPE(vdt, VDT, {
-            pack_kernel<WDT, VDT><<<dim3((unsigned)B, split), kPackThreads, 0, s>>>(W, N, R, keep, blk_cnt, blk_ptr,
-                                                                                capacity_cols, col_idx, vals);
+            if (N <= kPackMaxCols)
+                pack_positions_kernel<WDT, VDT><<<dim3((unsigned)B, split), kPackThreads, 0, s>>>(
+                    W, N, R, keep, blk_cnt, blk_ptr, capacity_cols, col_idx, vals);
+            else
+                pack_kernel<WDT, VDT><<<dim3((unsigned)B, split), kPackThreads, 0, s>>>(W, N, R, keep, blk_cnt, blk_ptr,
+                                                                                    capacity_cols, col_idx, vals);
         });
     });
     return check_launch();
