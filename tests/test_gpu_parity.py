@@ -347,6 +347,73 @@ def test_config4_bert_large_layer_set(R):
         chain_matrix(d)
 
 
+def test_config5_full_weight_set_sampled():
+    # 24-layer BERT-large weight set, fp32, 302 M parameters: norms, factors, gradient, one global 5x percentile
+    # over all 18.9 M groups, pack.  Full size on the GPU; the oracle checks sampled row-blocks element by
+    # element and the global threshold by its own sort.
+    c = wl.config5()
+    R, eps, lam = c["R"], c["eps"], c["lam"]
+    Wh = c["W"]
+    Wd = torch.from_numpy(Wh).cuda()
+    runs = []                                            # matrices of one width, adjacent in the buffer, stacked
+    for off, m, n in c["desc"]:
+        if runs and runs[-1][2] == n and runs[-1][0] + runs[-1][1] * n == off:
+            runs[-1] = (runs[-1][0], runs[-1][1] + m, n)
+        else:
+            runs.append((off, m, n))
+    assert len(runs) == 2 and sum(r * n for _, r, n in runs) == Wh.size == 301989888
+    groups = Wh.size // R
+    sumsq = torch.empty(groups, dtype=torch.float32, device="cuda")
+    alpha = torch.empty(groups, dtype=torch.float32, device="cuda")
+    grad = torch.empty_like(Wd)
+    keep = torch.empty(groups, dtype=torch.uint8, device="cuda")
+    rng = np.random.default_rng(5)
+    views = []
+    for off, rows, n in runs:
+        g0, ng = off // R, rows // R * n
+        v = dict(off=off, rows=rows, n=n, g0=g0, W=Wd[off:off + rows * n].view(rows, n),
+                 G=grad[off:off + rows * n].view(rows, n), s=sumsq[g0:g0 + ng].view(rows // R, n),
+                 a=alpha[g0:g0 + ng].view(rows // R, n), k=keep[g0:g0 + ng].view(rows // R, n))
+        bsp.bsp_group_norms(v["W"], R, eps=eps, mode=bsp.ALPHA_SQNORM, sumsq=v["s"], alpha=v["a"], want=())
+        bsp.bsp_penalty_grad(v["W"], R, v["a"], lam, mode=bsp.ALPHA_SQNORM, grad=v["G"])
+        v["blocks"] = sorted(set([0, rows // R - 1] + rng.integers(0, rows // R, 6).tolist()))
+        views.append(v)
+    n_keep = groups // 5
+    _, t_used = bsp.bsp_prune_mask(sumsq.view(groups // 1024, 1024), n_keep=n_keep, scope=bsp.SCOPE_MATRIX,
+                                   keep=keep.view(groups // 1024, 1024), want_t_used=True)
+    s_host = host(sumsq)
+    # sampled row-blocks: sums, factors, gradient
+    for v in views:
+        Wm = Wh[v["off"]:v["off"] + v["rows"] * v["n"]].reshape(v["rows"], v["n"])
+        for b in v["blocks"]:
+            Wb = Wm[b * R:(b + 1) * R]
+            s_ref = orc.sumsq(Wb, R)
+            _, a_ref = orc.norm_alpha(s_ref, eps, orc.ALPHA_SQNORM)
+            g_ref, _ = orc.penalty_grad(Wb, R, a_ref, lam, orc.ALPHA_SQNORM)
+            assert bits_equal(host(v["s"][b:b + 1]), s_ref) and bits_equal(host(v["a"][b:b + 1]), a_ref)
+            assert bits_equal(host(v["G"][b * R:(b + 1) * R]), g_ref)
+    # the global threshold and mask
+    k_ref, t_ref = orc.mask_rank(s_host.reshape(1, -1), n_keep, orc.SCOPE_MATRIX)
+    assert bits_equal(host(t_used), t_ref)
+    k_host = host(keep)
+    assert np.array_equal(k_host, k_ref.reshape(-1))
+    assert 0 <= n_keep - int(k_host.sum()) < 64           # fewer than n_keep only by ties at the cut
+    # pack (bf16 panels): counts everywhere, sampled row-blocks element by element
+    for v in views:
+        p = bsp.bsp_pack(v["W"], R, v["k"], 32, vdt=bsp.BF16)
+        assert bsp.bsp_packed_validate(p)
+        kv = k_host[v["g0"]:v["g0"] + v["rows"] // R * v["n"]].reshape(v["rows"] // R, v["n"])
+        cnt_ref, ptr_ref = orc.pack_count(kv, 32)
+        assert np.array_equal(host(p.blk_cnt), cnt_ref) and np.array_equal(host(p.blk_ptr), ptr_ref)
+        Wm = Wh[v["off"]:v["off"] + v["rows"] * v["n"]].reshape(v["rows"], v["n"])
+        col, ptr = host(p.col_idx), ptr_ref
+        for b in v["blocks"]:
+            ref = orc.pack(Wm[b * R:(b + 1) * R], R, kv[b:b + 1], 32, orc.BF16)
+            lo, hi = int(ptr[b]), int(ptr[b + 1])
+            assert np.array_equal(col[lo:hi], ref["col_idx"])
+            assert bits_equal(host(p.vals[R * lo:R * hi]), ref["vals"])
+
+
 def test_skewed_weights_ragged_blocks():
     R, M, N, T = 16, 512, 1024, 300
     W = wl.skewed_weight(21, M, N, R, "bf16", sigma=1.5)
