@@ -229,6 +229,45 @@ def prune_path_c5(layers=24, reps=5):
             "rate": round(params / (R * max(kept, 1)), 4), "stages": stages}
 
 
+def linear_grid(T=8192, R=16, reps=3):
+    """The layer alone over (matrix, compression rate): BERT-base and BERT-large shapes at 1.5x, 2x, 3x and 5x.
+    Per entry: microseconds per call (10 calls in a HIP graph, `reps` replays between two events), useful
+    TFLOP/s, and that rate as a fraction of the lower of the two roofs (MFMA peak, HBM peak x arithmetic
+    intensity)."""
+    shapes = [("base_qkv", 2304, 768), ("base_out", 768, 768), ("base_up", 3072, 768), ("base_down", 768, 3072),
+              ("large_qkv", 3072, 1024), ("large_out", 1024, 1024), ("large_up", 4096, 1024), ("large_down", 1024, 4096)]
+    out = {}
+    for si, (name, M, N) in enumerate(shapes):
+        for num, den in ((3, 2), (2, 1), (3, 1), (5, 1)):
+            d = wl.layer(900 + si, T, M, N, "bf16")
+            d.update(name=name, M=M, N=N, R=R, T=T, n_keep=(M // R) * N * den // num)
+            m = Matrix(d)
+            m.prune_and_pack()
+            m.linear()
+            torch.cuda.synchronize()
+            m.kept_cols = int(m.blk_cnt.sum().item())
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                for _ in range(10):
+                    m.linear()
+            g.replay()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                g.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            sec = e0.elapsed_time(e1) * 1e-3 / (10 * reps)
+            tf = m.useful_flops() / sec / 1e12
+            roof = min(MFMA_BF16_PEAK_TFLOPS, HBM_PEAK_GBS * 1e-3 * m.useful_flops() / m.linear_bytes())
+            out["%s@%.1fx" % (name, num / den)] = {"us": round(sec * 1e6, 1), "useful_tflops": round(tf, 1),
+                                                  "frac_mfma_peak": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
+                                                  "frac_of_lower_roof": round(tf / roof, 4)}
+            del m, g
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -245,6 +284,8 @@ def main():
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one 256 MiB device-to-device copy (a kernel of known traffic, to scale the "
                          "profiler's memory counters)")
+    ap.add_argument("--no-grid", action="store_true",
+                    help="skip the layer-only table over BERT-base / BERT-large shapes and compression rates")
     ap.add_argument("--no-c5", action="store_true",
                     help="skip the bandwidth measurement of the pruning pipeline on the 302 M parameter weight set")
     args = ap.parse_args()
@@ -410,6 +451,8 @@ def main():
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(mats)
+    if not args.no_grid:
+        out["linear_grid"] = linear_grid()
     if not args.no_c5:
         del mats
         torch.cuda.empty_cache()
