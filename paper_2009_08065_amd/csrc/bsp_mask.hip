@@ -234,16 +234,7 @@ __global__ __launch_bounds__(kSelThreads) void mask_rank_hist_kernel(const float
     const int64_t end = lo + per_wg < n ? lo + per_wg : n;
     const bool vec = (reinterpret_cast<uintptr_t>(s) & 15) == 0;
     const uint32_t copy = COPIES > 1 ? (threadIdx.x & (COPIES - 1)) : 0;
-    for (int64_t i = lo + (int64_t)threadIdx.x * 4; i < end; i += kSelThreads * 4) {
-        float v[4];
-        int cnt = 4;
-        if (vec && i + 3 < end) {
-            const float4 q = *reinterpret_cast<const float4 *>(s + i);
-            v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
-        } else {
-            cnt = (int)((end - i) < 4 ? (end - i) : 4);
-            for (int e = 0; e < cnt; ++e) v[e] = s[i + e];
-        }
+    auto count4 = [&](const float (&v)[4], int cnt) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const uint32_t key = to_key(e < cnt ? v[e] : 0.0f);
@@ -252,6 +243,34 @@ __global__ __launch_bounds__(kSelThreads) void mask_rank_hist_kernel(const float
             const uint32_t digit = (key >> shift) & ((1u << bits) - 1u);
             if (in) atomicAdd(&hist[digit * COPIES + copy], 1u);
         }
+    };
+    // Batches of kBatch 16-byte loads per thread are issued before any of them is used: one load per
+    // round trip leaves the kernel waiting on memory latency at large sizes.
+    constexpr int kBatch = 4;
+    int64_t i = lo + (int64_t)threadIdx.x * 4;
+    if (vec) {
+        for (; i + (int64_t)(kBatch - 1) * kSelThreads * 4 + 3 < end; i += (int64_t)kBatch * kSelThreads * 4) {
+            float4 q[kBatch];
+#pragma unroll
+            for (int k = 0; k < kBatch; ++k) q[k] = *reinterpret_cast<const float4 *>(s + i + (int64_t)k * kSelThreads * 4);
+#pragma unroll
+            for (int k = 0; k < kBatch; ++k) {
+                const float v[4] = {q[k].x, q[k].y, q[k].z, q[k].w};
+                count4(v, 4);
+            }
+        }
+    }
+    for (; i < end; i += kSelThreads * 4) {
+        float v[4] = {0.f, 0.f, 0.f, 0.f};
+        int cnt = 4;
+        if (vec && i + 3 < end) {
+            const float4 q = *reinterpret_cast<const float4 *>(s + i);
+            v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+        } else {
+            cnt = (int)((end - i) < 4 ? (end - i) : 4);
+            for (int e = 0; e < cnt; ++e) v[e] = s[i + e];
+        }
+        count4(v, cnt);
     }
     __syncthreads();
     uint32_t *slot = ws + kStateWords + (size_t)(PASS & 1) * G * kSlot + (size_t)blockIdx.x * kSlot;
@@ -281,16 +300,22 @@ __global__ __launch_bounds__(kSelThreads) void mask_rank_apply_kernel(const floa
         thr = from_key(prefix);
     }
     if (t_used && blockIdx.x == 0 && threadIdx.x == 0) *t_used = thr;
-    const int64_t stride = (int64_t)gridDim.x * kSelThreads * 4;
     const bool vec = ((reinterpret_cast<uintptr_t>(s) | reinterpret_cast<uintptr_t>(keep)) & 15) == 0;
-    for (int64_t i = ((int64_t)blockIdx.x * kSelThreads + threadIdx.x) * 4; i < n; i += stride) {
-        if (vec && i + 3 < n) {
-            float4 q = *reinterpret_cast<const float4 *>(s + i);
-            uchar4 k;
-            k.x = q.x > thr; k.y = q.y > thr; k.z = q.z > thr; k.w = q.w > thr;
-            *reinterpret_cast<uchar4 *>(keep + i) = k;
+    // 16 consecutive groups per thread and round: four 16-byte loads in flight, one 16-byte store
+    const int64_t stride = (int64_t)gridDim.x * kSelThreads * 16;
+    for (int64_t i = ((int64_t)blockIdx.x * kSelThreads + threadIdx.x) * 16; i < n; i += stride) {
+        if (vec && i + 15 < n) {
+            float4 q[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) q[k] = *reinterpret_cast<const float4 *>(s + i + 4 * k);
+            uint32_t w[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                w[k] = (uint32_t)(q[k].x > thr) | ((uint32_t)(q[k].y > thr) << 8) | ((uint32_t)(q[k].z > thr) << 16) |
+                       ((uint32_t)(q[k].w > thr) << 24);
+            *reinterpret_cast<uint4 *>(keep + i) = make_uint4(w[0], w[1], w[2], w[3]);
         } else {
-            for (int e = 0; e < 4 && i + e < n; ++e) keep[i + e] = s[i + e] > thr;
+            for (int e = 0; e < 16 && i + e < n; ++e) keep[i + e] = s[i + e] > thr;
         }
     }
 }
@@ -345,7 +370,7 @@ extern "C" int bsp_prune_mask(const float *sumsq, int64_t B, int64_t N, float t,
         mask_rank_hist_kernel<1><<<G, kSelThreads, 0, s>>>(sumsq, n, per_wg, (uint32_t)P, w);
         mask_rank_hist_kernel<2><<<G, kSelThreads, 0, s>>>(sumsq, n, per_wg, (uint32_t)P, w);
     }
-    int64_t ga = (n + (int64_t)kSelThreads * 8 - 1) / ((int64_t)kSelThreads * 8);
+    int64_t ga = (n + (int64_t)kSelThreads * 16 - 1) / ((int64_t)kSelThreads * 16);
     ga = ga < 1 ? 1 : (ga > 1024 ? 1024 : ga);
     mask_rank_apply_kernel<<<(unsigned)ga, kSelThreads, 0, s>>>(sumsq, n, (uint32_t)P, G, w, keep, t_used);
     return check_launch();
