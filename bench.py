@@ -72,10 +72,12 @@ class Matrix:
             self.plan = torch.empty(bsp.lib().bsp_linear_plan_bytes(self.M, self.R, self.capacity), dtype=torch.uint8,
                                     device=dev)
 
-    def prune_and_pack(self, lam=1e-4, eps=1e-6):
+    def penalty_grad(self, lam=1e-4):
+        bsp.bsp_penalty_grad(self.W, self.R, self.alpha, lam, mode=bsp.ALPHA_SQNORM, grad=self.grad)
+
+    def prune_and_pack(self, eps=1e-6):
         bsp.bsp_group_norms(self.W, self.R, eps=eps, mode=bsp.ALPHA_SQNORM, sumsq=self.sumsq, alpha=self.alpha,
                             want=())
-        bsp.bsp_penalty_grad(self.W, self.R, self.alpha, lam, mode=bsp.ALPHA_SQNORM, grad=self.grad)
         bsp.bsp_prune_mask(self.sumsq, n_keep=self.n_keep, scope=bsp.SCOPE_MATRIX, keep=self.keep, ws=self.ws)
         bsp.bsp_pack_count(self.keep, self.k_align, blk_cnt=self.blk_cnt, blk_ptr=self.blk_ptr)
         L = bsp.lib()
@@ -86,6 +88,13 @@ class Matrix:
             raise bsp.BspError(st, "bsp_pack")
         if self.use_plan:
             bsp.bsp_linear_plan(self.packed, plan=self.plan)
+
+    def whole_step(self):
+        """Norms, mask, pack, plan, layer; the regulariser's gradient last: it needs only the factors and
+        nothing in the step waits for it, so it is kept out of the chain that leads to the layer."""
+        self.prune_and_pack()
+        self.linear()
+        self.penalty_grad()
 
     def linear(self):
         if self.use_plan:
@@ -318,24 +327,21 @@ def main():
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g):
             for m in mats:
-                m.prune_and_pack()
-                m.linear()
+                m.whole_step()
         graphs = [g]
     elif args.launch == "overlap":
         # one graph per matrix, each replayed on a default-priority stream of its own
         for m in mats:
             g = torch.cuda.CUDAGraph()
             with torch.cuda.graph(g):
-                m.prune_and_pack()
-                m.linear()
+                m.whole_step()
             graphs.append(g)
         pool = [torch.cuda.Stream() for _ in range(8)]   # default priority
 
     def step():
         if args.launch == "eager":
             for m in mats:
-                m.prune_and_pack()
-                m.linear()
+                m.whole_step()
         elif args.launch == "serial":
             graphs[0].replay()
         else:

@@ -63,7 +63,11 @@ __global__ __launch_bounds__(kThreads) void plan_count_kernel(const int32_t *__r
 
 // One workgroup of kPlanWaves wavefronts: wavefront w scans the step counts of its blocks in
 // stream order (chunk-major: all its blocks' steps of chunk 0, then chunk 1, ...).
-__global__ __launch_bounds__(kPlanWaves * 64) void plan_scan_kernel(const int32_t *__restrict__ steps_bq, int32_t B,
+// steps_bq == nullptr (layers of one chunk): the count is ceil(blk_cnt / 32), taken from the storage itself.
+__global__ __launch_bounds__(kPlanWaves * 64) void plan_scan_kernel(const int32_t *__restrict__ steps_bq,
+                                                                    const int32_t *__restrict__ blk_cnt,
+                                                                    const int32_t *__restrict__ blk_ptr,
+                                                                    int64_t capacity_cols, int32_t B,
                                                                     int32_t NG, int32_t nacc, int32_t nchunks,
                                                                     int64_t cap_steps,
                                                                     int32_t slack_steps, int32_t *__restrict__ wptr,
@@ -78,7 +82,17 @@ __global__ __launch_bounds__(kPlanWaves * 64) void plan_scan_kernel(const int32_
         const int e = ebase + lane;
         const int q = e / per_chunk, gi = e % per_chunk;
         const int64_t b = ((int64_t)(gi / nacc) * kPlanWaves + w) * nacc + gi % nacc;
-        const int st = (e < E && b < B) ? steps_bq[b * kPlanMaxChunks + q] : 0;
+        int st = 0;
+        if (e < E && b < B) {
+            if (steps_bq) {
+                st = steps_bq[b * kPlanMaxChunks + q];
+            } else {  // the same validity test as the count and fill kernels make
+                const int base = blk_ptr[b], kp = blk_ptr[b + 1] - base, kb = blk_cnt[b];
+                const bool ok = kp > 0 && kp <= kMaxKp && kb >= 0 && kb <= kp && base >= 0 &&
+                                (int64_t)base + kp <= capacity_cols;
+                st = ok ? (kb + 31) >> 5 : 0;
+            }
+        }
         int incl = st;
 #pragma unroll
         for (int o = 1; o < 64; o <<= 1) {
@@ -298,10 +312,12 @@ extern "C" int bsp_linear_plan(int vdt, int64_t M, int64_t N, int32_t R, int32_t
     // consumed them before the fill kernel overwrites that region
     int32_t *steps_bq = (int32_t *)xoff;
     if ((size_t)B * kPlanMaxChunks * sizeof(int32_t) > L.xoff_bytes) return BSP_ERR_CAPACITY;
-    plan_count_kernel<<<(unsigned)B, kThreads, 0, s>>>(blk_cnt, blk_ptr, col_idx, capacity_cols, ch.shift, ch.n,
-                                                       steps_bq);
+    if (ch.n > 1)  // a layer of one chunk needs no count: its steps per row-block follow from blk_cnt
+        plan_count_kernel<<<(unsigned)B, kThreads, 0, s>>>(blk_cnt, blk_ptr, col_idx, capacity_cols, ch.shift, ch.n,
+                                                           steps_bq);
     const int32_t nacc = plan_nacc(nf, ch.n > 1);
-    plan_scan_kernel<<<1, kPlanWaves * 64, 0, s>>>(steps_bq, (int32_t)B, (int32_t)L.NG, nacc, ch.n, (int64_t)L.steps,
+    plan_scan_kernel<<<1, kPlanWaves * 64, 0, s>>>(ch.n > 1 ? steps_bq : nullptr, blk_cnt, blk_ptr, capacity_cols,
+                                                   (int32_t)B, (int32_t)L.NG, nacc, ch.n, (int64_t)L.steps,
                                                    plan_slack_steps(), wptr, xoff);
     if (capacity_cols > 0)
         plan_fill_kernel<<<dim3((unsigned)B, (unsigned)ch.n), kThreads, 0, s>>>(R, nf, (int32_t)L.NG, nacc, ch.shift, ch.n, blk_cnt, blk_ptr,
