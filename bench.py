@@ -36,6 +36,10 @@ import paper_2009_08065_amd as bsp  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
+# HBM bytes per launch of linear_tiled_planned_kernel on this workload (average of its three launches), from the
+# FETCH_SIZE / WRITE_SIZE counter runs summarised in profiles/linear_kernels_bert_large_r16_hbm_traffic.md
+# (27.8 MB read + 44.8 MB written; the algorithmic figure is 62.8 MB).  Void once that kernel changes.
+PLANNED_KERNEL_HBM_BYTES_PER_LAUNCH = 72.5e6
 
 
 class Matrix:
@@ -451,7 +455,9 @@ def main():
         "roofline": {"kernel": dom_name, "launches_per_step": dom["launches"],
                      "avg_launch_us": round(dom["ms"] * 1e3 / len(dom["launches"]), 2), "bound": "hbm",
                      "achieved": round(achieved_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved_gbs / HBM_PEAK_GBS, 4), "traffic": None},
+                     "frac": round(achieved_gbs / HBM_PEAK_GBS, 4),
+                     "traffic": PLANNED_KERNEL_HBM_BYTES_PER_LAUNCH if dom_name == "linear_tiled_planned_kernel"
+                     and args.R == 16 else None},
         "roofline_mfma": {"bound": "mfma", "achieved": round(achieved_tflops, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
                           "unit": "TFLOP/s", "frac": round(achieved_tflops / MFMA_BF16_PEAK_TFLOPS, 4)},
     }
