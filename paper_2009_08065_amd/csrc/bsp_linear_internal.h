@@ -40,11 +40,12 @@ inline PlanChunks plan_chunks(int64_t N) {
     if (npad <= 1024) return PlanChunks{1, 30};
     return PlanChunks{(int32_t)((npad + 1023) / 1024), 10};
 }
-// A wavefront of the planned kernels holds the accumulators of nacc consecutive row-blocks (a "quad"),
-// so that it writes 64 or 128 contiguous bytes per token row: 4 sixteen-row fragments' worth in the
-// column-chunked kernel (its output is written once, at the end), 2 in the kernel for layers of up to
-// 1024 columns (which stores inside its operand loop, where registers are scarcer).
-constexpr int plan_nacc(int nfrag, bool chunked) {
+// A wavefront of the planned kernels works on runs of nacc consecutive row-blocks, so that it can write 64
+// or 128 contiguous bytes per token row: 4 sixteen-row fragments' worth in the column-chunked kernel (which
+// holds all their accumulators and writes once, at the end), 2 in the kernel for layers of up to 1024 columns
+// (64 bytes per row are enough there).  R = 8 fills half a fragment, so 4 of its row-blocks make 64 bytes.
+constexpr int plan_nacc(int nfrag, bool chunked, int R) {
+    if (R == 8) return 4;
     const int frags = chunked ? 4 : 2;
     return frags / nfrag > 0 ? frags / nfrag : 1;
 }

@@ -357,7 +357,7 @@ struct QuadEpilogue {
     const void *bias;
     int64_t T, M, t0;
     int32_t R, B, l16, G, lane;
-    bool fast;       // R == 16 * NFRAG: a quad is NACC * R contiguous output columns, a multiple of 64 bytes
+    bool fast;       // R == 16 * NFRAG or R == 8: a quad is NACC * R contiguous output columns, a multiple of 64 bytes
     uint8_t *stage;  // this wavefront's LDS staging, 16 rows of kOutPitch bytes
     uint2 bv[NACC][NFRAG];  // bias of the lane's 4 output columns per (block, fragment), as stored (16-bit floats)
 
@@ -381,7 +381,8 @@ struct QuadEpilogue {
             for (int f = 0; f < NFRAG; ++f) {
                 const int r0 = f * 16 + 4 * G;
                 if (fast) {
-                    bv[k][f] = *reinterpret_cast<const uint2 *>((const uint16_t *)bias + b * R + r0);
+                    // (R = 8: the lanes of the unused upper half of the fragment read the lower half's bias)
+                    bv[k][f] = *reinterpret_cast<const uint2 *>((const uint16_t *)bias + b * R + (r0 < R ? r0 : r0 - 8));
                 } else {
                     uint32_t h[4];
 #pragma unroll
@@ -418,24 +419,27 @@ struct QuadEpilogue {
     __device__ __forceinline__ void flush(int64_t b0, const Packed &out) {
         if (b0 >= B) return;  // uniform
         if (fast) {
-            // a token row of the quad is ROWB = 64 or 128 contiguous bytes: LPR lanes x 16 bytes write one row
-            constexpr int ROWB = NACC * NFRAG * 32, LPR = ROWB / 16, RPI = 64 / LPR;  // rows per store instruction
-            const int row = lane / LPR, piece = lane % LPR;
+            // a token row of the quad is 64 or 128 contiguous bytes (32 per fragment, 16 when R = 8 leaves the
+            // upper half of the fragment unused): lpr lanes x 16 bytes write one row
+            const int bpf = NFRAG == 1 ? 2 * R : 32;
+            const int lpr = NACC * NFRAG * bpf / 16, rpi = 64 / lpr;  // lanes per row, rows per store instruction
+            const int row = lane / lpr, piece = lane % lpr;
             // the 16-byte piece covers 8 output columns, all inside one row-block
-            const bool blk_ok = b0 + (piece * 8) / (16 * NFRAG) < B;
+            const bool blk_ok = b0 + (piece * 8) / R < B;
             uint16_t *dst = Y + b0 * R + piece * 8;
 #pragma unroll
             for (int u = 0; u < NSUB; ++u) {
+                if (8 * G < bpf) {
 #pragma unroll
-                for (int k = 0; k < NACC; ++k)
+                    for (int k = 0; k < NACC; ++k)
 #pragma unroll
-                    for (int f = 0; f < NFRAG; ++f)
-                        *reinterpret_cast<uint2 *>(stage + l16 * kOutPitch + (k * NFRAG + f) * 32 + 8 * G) = out[k][f][u];
+                        for (int f = 0; f < NFRAG; ++f)
+                            *reinterpret_cast<uint2 *>(stage + l16 * kOutPitch + (k * NFRAG + f) * bpf + 8 * G) = out[k][f][u];
+                }
                 // same wavefront writes and reads: LDS operations of a wavefront complete in order
-#pragma unroll
-                for (int i = 0; i < 16 / RPI; ++i) {
-                    const uint4 o = *reinterpret_cast<const uint4 *>(stage + (row + RPI * i) * kOutPitch + piece * 16);
-                    const int64_t t = t0 + 16 * u + RPI * i + row;
+                for (int i = 0; i < 16 / rpi; ++i) {
+                    const uint4 o = *reinterpret_cast<const uint4 *>(stage + (row + rpi * i) * kOutPitch + piece * 16);
+                    const int64_t t = t0 + 16 * u + rpi * i + row;
                     if (t < T && blk_ok) *reinterpret_cast<uint4 *>(dst + t * M) = o;
                 }
             }
@@ -506,17 +510,24 @@ __device__ __forceinline__ void clear_quad(f32x4 (&acc)[NACC][NFRAG][NSUB]) {
 constexpr uint32_t kXTileBytes = 4 * 32768;  // 64 tokens x 1024 columns
 constexpr uint32_t kOutStageBytes = 4096;    // per wavefront: 64 token rows x 64 bytes
 
-// FAST: R == 16 * NFRAG (every fragment is full and the staged store applies); otherwise outputs are
-// stored one by one.  A template parameter, because the output code is inlined at every slot of the
-// unrolled operand ring and the kernel has to stay small enough for the instruction cache.
-template <int DT, int NFRAG, bool FAST>
+// OUT: how the output leaves.  kOutStaged: R == 16 * NFRAG, full fragments of 32 bytes per token row through the
+// staging buffer; kOutStaged8: R == 8 (NFRAG = 1), half fragments of 16 bytes, runs of 4 row-blocks;
+// kOutElements: any other R (or a bias that cannot be read in words), outputs stored one by one, and
+// kOutElements8 the same for R == 8, whose plan deals the row-blocks in runs of 4.  A template parameter,
+// because the output code is inlined at every slot of the unrolled operand ring: it has to be small, and its
+// constants known.
+enum { kOutElements = 0, kOutStaged = 1, kOutStaged8 = 2, kOutElements8 = 3 };
+template <int DT, int NFRAG, int OUT>
 __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
     const uint16_t *__restrict__ X, int64_t T, int64_t M, int64_t N, int32_t R, int32_t npad,
     const int32_t *__restrict__ wptr, const uint32_t *__restrict__ wfrag, const uint32_t *__restrict__ xoff,
     const void *__restrict__ bias, void *__restrict__ Y, int32_t ntiles, int32_t groups_per_strip, int32_t NG,
     int32_t B, int32_t max_step) {
     constexpr int NSUB = 4;
-    constexpr int NACC = plan_nacc(NFRAG, false);  // row-blocks of a wavefront's run: their fragments pair up
+    constexpr bool FAST = OUT == kOutStaged || OUT == kOutStaged8;
+    // row-blocks of a wavefront's run: together 64 bytes per token row
+    constexpr int NACC = plan_nacc(NFRAG, false, (OUT == kOutStaged8 || OUT == kOutElements8) ? 8 : 16 * NFRAG);
+    constexpr int nacc_shift = NACC == 4 ? 2 : (NACC == 2 ? 1 : 0);
     constexpr int RING = kPlanRing / NFRAG;        // the same bytes in flight for every fragment count
     static_assert(RING % 2 == 0, "the X fragment ping-pong needs an even ring");
     const int tile = blockIdx.x % ntiles, strip = blockIdx.x / ntiles;
@@ -555,7 +566,9 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
         }
     };
     auto load_frag = [&](const uint32_t *q) { return make_uint4(q[0], q[64], q[128], q[192]); };
-    auto block_of = [&](int e) { return ((int64_t)(g0 + e / NACC) * kPlanWaves + wave) * NACC + e % NACC; };
+    auto block_of = [&](int e) {
+        return ((((int64_t)(g0 + (e >> nacc_shift)) * kPlanWaves + wave)) << nacc_shift) + (e & (NACC - 1));
+    };
     auto widen = [](uint32_t h) {
         if constexpr (DT == BSP_BF16) return __uint_as_float(h << 16);
         else return (float)__builtin_bit_cast(_Float16, (uint16_t)h);
@@ -574,7 +587,8 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
 #pragma unroll
             for (int f = 0; f < NFRAG; ++f)
 #pragma unroll
-                for (int i = 0; i < 8; ++i) bs[f][i] = bias32[(b * R + f * 16) / 2 + i];
+                for (int i = 0; i < 8; ++i)
+                    if (OUT != kOutStaged8 || i < 4) bs[f][i] = bias32[(b * R + f * 16) / 2 + i];
         }
     };
     // Output of the finished row-block b (the accumulators hold it).
@@ -583,27 +597,34 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
         if constexpr (FAST) {
 #pragma unroll
             for (int f = 0; f < NFRAG; ++f) {
-                const int slot = NFRAG == 1 ? (int)(b & 1) : (f & 1);  // half of the 64-byte staging row
+                // A fragment of this block fills bpf bytes of a token row (32; 16 when R = 8 leaves the upper half
+                // of the fragment unused); `slot` is its place in the 64-byte staging row.
+                constexpr int bpf = OUT == kOutStaged8 ? 16 : 32;
+                constexpr int last_slot = 64 / bpf - 1;
+                const int slot = NFRAG == 1 ? (int)(b & last_slot) : (f & 1);
                 // the lane's 4 columns 4 G .. 4 G + 3 are words 2 G and 2 G + 1 of the fragment's 8
                 // (picked with lane masks: and / or of uniform words, no indexing)
                 const uint32_t w0 = (bs[f][0] & gm[0]) | (bs[f][2] & gm[1]) | (bs[f][4] & gm[2]) | (bs[f][6] & gm[3]);
                 const uint32_t w1 = (bs[f][1] & gm[0]) | (bs[f][3] & gm[1]) | (bs[f][5] & gm[2]) | (bs[f][7] & gm[3]);
                 const float b0 = widen(w0 & 0xffffu), b1 = widen(w0 >> 16);
                 const float b2 = widen(w1 & 0xffffu), b3 = widen(w1 >> 16);
+                const int byte = slot * bpf + 8 * G;  // of the row; its 16-byte piece is swizzled
+                if (8 * G < bpf) {
 #pragma unroll
-                for (int u = 0; u < NSUB; ++u) {
-                    uint2 o;
-                    o.x = cvt_pk<DT>(acc[f][u][0] + b0, acc[f][u][1] + b1);
-                    o.y = cvt_pk<DT>(acc[f][u][2] + b2, acc[f][u][3] + b3);
-                    *reinterpret_cast<uint2 *>(stg + (16 * u + l16) * 64 + (((slot * 2 + (G >> 1)) ^ swz) << 4) + (G & 1) * 8) = o;
+                    for (int u = 0; u < NSUB; ++u) {
+                        uint2 o;
+                        o.x = cvt_pk<DT>(acc[f][u][0] + b0, acc[f][u][1] + b1);
+                        o.y = cvt_pk<DT>(acc[f][u][2] + b2, acc[f][u][3] + b3);
+                        *reinterpret_cast<uint2 *>(stg + (16 * u + l16) * 64 + (((byte >> 4) ^ swz) << 4) + (byte & 8)) = o;
+                    }
                 }
-                // The staging rows are complete after an odd fragment; a lone last row-block of an
-                // odd-sized layer (R = 16) leaves with its own half only.
-                const bool lone = NFRAG == 1 && slot == 0 && b + 1 >= B;
-                if (slot == 1 || lone) {
+                // The staging rows are complete after the last slot; the last row-block of a layer whose
+                // block count is not a multiple of the run leaves with the slots filled so far.
+                const bool lone = NFRAG == 1 && slot != last_slot && b + 1 >= B;
+                if (slot == last_slot || lone) {
                     const int piece = lane & 3;  // 16-byte piece of the 64-byte row
-                    const int64_t col0 = b * R + f * 16 - (slot == 1 ? 16 : 0);
-                    if (!lone || piece < 2) {
+                    const int64_t col0 = b * R + f * 16 - slot * (bpf >> 1);
+                    if (piece * 16 < (slot + 1) * bpf) {
 #pragma unroll
                         for (int i = 0; i < 4; ++i) {
                             const int row = 16 * i + (lane >> 2);
@@ -635,7 +656,7 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
     // groups [rot, ng) first, then [0, rot).
     const int rot = ng > 1 ? ((tile >> 3) + strip) % ng : 0;
     for (int seg = 0; seg < 2; ++seg) {
-        const int ea = (seg == 0 ? rot : 0) * NACC, eb = (seg == 0 ? ng : rot) * NACC;
+        const int ea = (seg == 0 ? rot : 0) << nacc_shift, eb = (seg == 0 ? ng : rot) << nacc_shift;
         if (ea >= eb) continue;
         // (the clamps keep a malformed plan from driving the operand pointers out of the buffer)
         const int gs_hi = min(my[eb], max_step);
@@ -717,7 +738,7 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_chunked_kernel(
     const void *__restrict__ bias, void *__restrict__ Y, int32_t ntiles, int32_t NG, int32_t B, int32_t nchunks,
     int32_t max_step, int32_t fast_store) {
     constexpr int NSUB = 4;
-    constexpr int NACC = plan_nacc(NFRAG, true);
+    constexpr int NACC = plan_nacc(NFRAG, true, 16 * NFRAG);  // 4 / NFRAG; R = 8 (NFRAG = 1) has 4 too
     constexpr int RING = kPlanRing / NFRAG;
     static_assert(RING % 2 == 0, "the X fragment ping-pong needs an even ring");
     __shared__ __attribute__((aligned(16))) uint8_t s_out[kPlanWaves][16 * kOutPitch];
@@ -853,17 +874,17 @@ int launch_canonical(const TiledArgs &a, int waves, hipStream_t s) {
     return check_launch();
 }
 
-template <int DT, int NFRAG, bool FAST>
+template <int DT, int NFRAG, int OUT>
 int launch_planned_1024(const TiledArgs &a, int64_t ntiles, int64_t NG, int64_t max_step, hipStream_t s);
 
 template <int DT, int NFRAG>
 int launch_planned(const TiledArgs &a, hipStream_t s) {
-    const int NACC = plan_nacc(NFRAG, a.npad > 1024);
+    const int NACC = plan_nacc(NFRAG, a.npad > 1024, a.R);
     const size_t lds = 4 * (size_t)sub_stride<4>();  // 64 tokens x 1024 columns
     const int64_t ntiles = (a.T + 63) / 64;
     const int64_t NG = (a.B + kPlanWaves * NACC - 1) / (kPlanWaves * NACC);
     // the staged store path: full fragments, and a bias that can be read in 4-byte words
-    const int32_t fast = (a.R == 16 * NFRAG && (reinterpret_cast<uintptr_t>(a.bias) & 3) == 0) ? 1 : 0;
+    const int32_t fast = ((a.R == 16 * NFRAG || a.R == 8) && (reinterpret_cast<uintptr_t>(a.bias) & 3) == 0) ? 1 : 0;
     const int64_t max_step = a.plan_steps - plan_slack_steps();
     if (max_step < 0 || max_step > INT32_MAX) return BSP_ERR_CAPACITY;
     if (a.npad > 1024) {
@@ -878,14 +899,18 @@ int launch_planned(const TiledArgs &a, hipStream_t s) {
             (int32_t)NG, (int32_t)a.B, ch.n, (int32_t)max_step, fast);
         return check_launch();
     }
-    if (fast) return launch_planned_1024<DT, NFRAG, true>(a, ntiles, NG, max_step, s);
-    return launch_planned_1024<DT, NFRAG, false>(a, ntiles, NG, max_step, s);
+    if constexpr (NFRAG == 1) {
+        if (a.R == 8 && fast) return launch_planned_1024<DT, NFRAG, kOutStaged8>(a, ntiles, NG, max_step, s);
+        if (a.R == 8) return launch_planned_1024<DT, NFRAG, kOutElements8>(a, ntiles, NG, max_step, s);
+    }
+    if (fast) return launch_planned_1024<DT, NFRAG, kOutStaged>(a, ntiles, NG, max_step, s);
+    return launch_planned_1024<DT, NFRAG, kOutElements>(a, ntiles, NG, max_step, s);
 }
 
-template <int DT, int NFRAG, bool FAST>
+template <int DT, int NFRAG, int OUT>
 int launch_planned_1024(const TiledArgs &a, int64_t ntiles, int64_t NG, int64_t max_step, hipStream_t s) {
     static thread_local size_t configured = 0;
-    auto kern = linear_tiled_planned_kernel<DT, NFRAG, FAST>;
+    auto kern = linear_tiled_planned_kernel<DT, NFRAG, OUT>;
     const size_t lds_planned = kXTileBytes + (size_t)kPlanWaves * kOutStageBytes;  // all 160 KiB of a compute unit
     int st = raise_lds_limit(kern, lds_planned, configured);
     if (st != BSP_OK) return st;

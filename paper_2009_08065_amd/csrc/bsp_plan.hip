@@ -266,7 +266,7 @@ struct PlanLayout {
 inline PlanLayout plan_layout(int64_t M, int64_t N, int32_t R, int64_t capacity_cols) {
     PlanLayout L;
     const int64_t B = M / R;
-    const int64_t per_group = (int64_t)kPlanWaves * plan_nacc(nfrag_of(R), plan_chunks(N).n > 1);
+    const int64_t per_group = (int64_t)kPlanWaves * plan_nacc(nfrag_of(R), plan_chunks(N).n > 1, R);
     L.NG = (B + per_group - 1) / per_group;
     L.steps = (size_t)((capacity_cols + 31) / 32) + (size_t)B * (kPlanMaxChunks - 1) + (size_t)plan_slack_steps();
     // entries per stream <= chunks * (blocks rounded up to whole groups) / kPlanWaves, groups of at most 32 blocks
@@ -315,7 +315,7 @@ extern "C" int bsp_linear_plan(int vdt, int64_t M, int64_t N, int32_t R, int32_t
     if (ch.n > 1)  // a layer of one chunk needs no count: its steps per row-block follow from blk_cnt
         plan_count_kernel<<<(unsigned)B, kThreads, 0, s>>>(blk_cnt, blk_ptr, col_idx, capacity_cols, ch.shift, ch.n,
                                                            steps_bq);
-    const int32_t nacc = plan_nacc(nf, ch.n > 1);
+    const int32_t nacc = plan_nacc(nf, ch.n > 1, R);
     plan_scan_kernel<<<1, kPlanWaves * 64, 0, s>>>(ch.n > 1 ? steps_bq : nullptr, blk_cnt, blk_ptr, capacity_cols,
                                                    (int32_t)B, (int32_t)L.NG, nacc, ch.n, (int64_t)L.steps,
                                                    plan_slack_steps(), wptr, xoff);

@@ -250,7 +250,8 @@ def test_linear_wide_layers_in_column_chunks(dtype, R, T, M, N, p_keep):
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f16"])
-@pytest.mark.parametrize("R,T,M,N", [(16, 100, 80, 200), (16, 4100, 2128, 512), (32, 200, 224, 1024), (64, 130, 320, 640)])
+@pytest.mark.parametrize("R,T,M,N", [(16, 100, 80, 200), (16, 4100, 2128, 512), (32, 200, 224, 1024), (64, 130, 320, 640),
+                                     (8, 130, 88, 512), (8, 300, 1048, 1024)])
 def test_linear_planned_output_staging(dtype, R, T, M, N):
     # layers of up to 1024 columns on the planned path: an odd number of row-blocks (the last one leaves
     # alone), several strips and groups, one and two fragments per staged row, ragged token tiles
@@ -264,9 +265,10 @@ def test_linear_planned_output_staging(dtype, R, T, M, N):
     run_layer(d["X"], d["W"], None, R, keep, 32, dtype, T_rows=rows)
 
 
-def test_linear_planned_bias_at_odd_address():
+@pytest.mark.parametrize("R", [16, 8])
+def test_linear_planned_bias_at_odd_address(R):
     # a bias that starts on a 2-byte boundary cannot be read in 4-byte words: the element-wise output path
-    R, T, M, N = 16, 90, 96, 256
+    T, M, N = 90, 96, 256
     d = wl.layer(5150, T, M, N, "bf16")
     keep = wl.bernoulli_keep_mask(5151, M // R, N, 0.3)
     p_ref = orc.pack(d["W"], R, keep, 32, CODE["bf16"])
