@@ -246,7 +246,8 @@ def linear_grid(T=8192, R=16, reps=3):
     """The layer alone over (matrix, compression rate): BERT-base and BERT-large shapes at 1.5x, 2x, 3x and 5x.
     Per entry: microseconds per call (10 calls in a HIP graph, `reps` replays between two events), useful
     TFLOP/s, and that rate as a fraction of the lower of the two roofs (MFMA peak, HBM peak x arithmetic
-    intensity)."""
+    intensity).  Warm timing: the same layer is launched back to back, so X (12 to 67 MB) can stay in the
+    256 MB Infinity Cache between launches."""
     shapes = [("base_qkv", 2304, 768), ("base_out", 768, 768), ("base_up", 3072, 768), ("base_down", 768, 3072),
               ("large_qkv", 3072, 1024), ("large_out", 1024, 1024), ("large_up", 4096, 1024), ("large_down", 1024, 4096)]
     out = {}
@@ -448,7 +449,9 @@ def main():
                               "eager": "every kernel launched from Python"}[args.launch],
                    "step": "group_norms + penalty_grad + prune_mask + pack_count + pack + linear_plan + linear, "
                            "4 matrices"},
-        "linear_only": {"ms": round(lin_total_ms, 4), "useful_tflops": round(achieved_tflops, 2),
+        "linear_only": {"cache_state": "cold: the four layers run in turn, so about 250 MB of other X / Y traffic "
+                                       "(the size of the Infinity Cache) passes between two launches of one layer",
+                        "ms": round(lin_total_ms, 4), "useful_tflops": round(achieved_tflops, 2),
                         "dense_equiv_tflops": round(dense / (lin_total_ms * 1e-3) / 1e12, 2),
                         "frac_mfma_peak": round(achieved_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
                         "per_matrix": per_matrix},

@@ -534,8 +534,15 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
     const int64_t t0 = (int64_t)tile * (16 * NSUB);
     const int g0 = strip * groups_per_strip;
     const int ng = min(groups_per_strip, NG - g0);
-    stage_x_tile<NSUB>(X, T, N, npad, t0);
-    __syncthreads();
+    // The X tile is copied in by the first use (below): a wavefront first requests the operands of its
+    // first RING steps, so that they travel while the tile is copied.  Every wavefront passes the barrier once.
+    bool staged = false;
+    auto stage_once = [&]() {
+        if (staged) return;
+        stage_x_tile<NSUB>(X, T, N, npad, t0);
+        __syncthreads();
+        staged = true;
+    };
 
     const int lane = threadIdx.x & 63;
     const int l16 = lane & 15, G = lane >> 4;
@@ -694,6 +701,7 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
             for (int f = 0; f < NFRAG; ++f) ra[j][f] = load_frag(wp + (j * NFRAG + f) * 256);
             rx[j] = xp[j * 16];
         }
+        stage_once();
         issue_reads(rx[0], xb[0]);
         bool done = false;
         while (!done) {
@@ -725,6 +733,7 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
             xp += RING * 16;
         }
     }
+    stage_once();  // a wavefront without steps still takes part in the copy and its barrier
 }
 
 // Layers wider than one LDS tile (more than 1024 input columns): the workgroup keeps the 64-token
