@@ -309,6 +309,20 @@ void orc_linear_packed(const float *X, int64_t t0, int64_t t1, int64_t M, int64_
     }
 }
 
+/* ------------------------------------------------------------------------------------ */
+/* Alg. 1's effect on the stored weights ("the group is set to zero") and the retraining  */
+/* step of Alg. 2 (W = W * Mask after every update): every weight of a pruned group       */
+/* becomes +0, every weight of a kept group is left as it is (bit for bit).  The mask is  */
+/* the group mask keep[B, N] (Alg. 2 builds an element mask from W != 0 after pruning:    */
+/* the same thing except for a kept weight that happens to be exactly 0).                 */
+/* ------------------------------------------------------------------------------------ */
+void orc_mask_weights(float *W, int64_t M, int64_t N, int32_t R, const uint8_t *keep)
+{
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t j = 0; j < N; ++j)
+            if (!keep[(m / R) * N + j]) W[m * N + j] = 0.0f;
+}
+
 /* Compression rate as the paper counts it (Sec. 4.4: 1.428x <=> 30 % sparsity):          */
 /* dense parameters over kept parameters.                                                 */
 double orc_compression_rate(int64_t M, int64_t N, int32_t R, int64_t kept_cols_total)

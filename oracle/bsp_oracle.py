@@ -162,5 +162,15 @@ def linear_packed(X, packed, bias, ydt=F32, t0=0, t1=None, n_threads=1):
     return Y, Yd
 
 
+def mask_weights(W, R, keep):
+    """Returns a copy of W with every pruned group set to +0 (Alg. 1; the W = W * Mask step of Alg. 2)."""
+    W = _f32(W).copy()
+    M, N = W.shape
+    keep = np.ascontiguousarray(keep, dtype=np.uint8)
+    assert keep.shape == (M // R, N)
+    lib().orc_mask_weights(_p(W), C.c_int64(M), C.c_int64(N), C.c_int32(R), _p(keep))
+    return W
+
+
 def compression_rate(M, N, R, kept_cols_total):
     return lib().orc_compression_rate(M, N, R, kept_cols_total)

@@ -426,3 +426,39 @@ def test_chain_on_base_attention_projection():
     assert np.allclose(Yd, want, rtol=1e-12, atol=1e-14)
     # the given random mask of the workload keeps exactly half of every block
     assert np.all(c["keep"].sum(axis=1) == 384)
+
+
+# ---------------------------------------------------------------------------------- masked weights
+def test_mask_weights_definition_and_invariants():
+    # Alg. 1 sets a pruned group to zero; Alg. 2 re-applies W = W * Mask after every retraining update.
+    rng = np.random.default_rng(12)
+    R, B, N = 4, 5, 37
+    W = rng.standard_normal((B * R, N)).astype(np.float32)
+    W[3, 5] = -0.0                                       # a kept negative zero must stay as it is
+    W[7, 9] = np.float32("nan")                          # and so must any bit pattern of a kept weight
+    keep = (rng.random((B, N)) < 0.4).astype(np.uint8)
+    keep[0, 5] = 1
+    keep[1, 9] = 1
+    keep[2, :] = 0
+    keep[3, :] = 1
+    Wm = orc.mask_weights(W, R, keep)
+    big = np.repeat(keep, R, axis=0).astype(bool)        # the element mask of Alg. 2
+    assert np.array_equal(Wm.view(np.uint32)[big], W.view(np.uint32)[big])          # kept: untouched, bit for bit
+    assert np.all(Wm.view(np.uint32)[~big] == 0)                                    # pruned: +0 exactly
+    assert np.array_equal(orc.mask_weights(Wm, R, keep).view(np.uint32), Wm.view(np.uint32))   # idempotent
+    fin = np.isfinite(W)
+    assert np.array_equal((W * big)[fin & big], Wm[fin & big])                      # W * Mask where that is defined
+    # what survives is exactly what the group norms see and what the compact storage holds
+    s = orc.sumsq(np.nan_to_num(Wm), R)
+    assert np.all(s[keep == 0] == 0.0)
+    W2 = np.nan_to_num(W)
+    p1, p2 = orc.pack(W2, R, keep, 8), orc.pack(orc.mask_weights(W2, R, keep), R, keep, 8)
+    assert np.array_equal(p1["col_idx"], p2["col_idx"]) and np.array_equal(p1["vals"].view(np.uint32), p2["vals"].view(np.uint32))
+    # the element mask Alg. 2 would build from the pruned matrix reproduces the group mask on generic weights
+    Wg = rng.standard_normal((B * R, N)).astype(np.float32)
+    assert np.array_equal(orc.mask_weights(Wg, R, keep) != 0, big)
+    # and the masked layer equals the dense layer on the masked weights
+    X = rng.standard_normal((6, N)).astype(np.float32)
+    Yd, _ = orc.linear_dense(X, orc.mask_weights(Wg, R, keep), np.ones_like(keep), None, R, ydt=orc.F32)
+    Yp, _ = orc.linear_packed(X, orc.pack(Wg, R, keep, 1), None, ydt=orc.F32)
+    assert np.allclose(Yd, Yp, rtol=0, atol=1e-5)
