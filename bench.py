@@ -140,7 +140,7 @@ def cpu_baseline(mats):
 def prune_path_c5(layers=24, reps=5):
     """HBM rate of the pruning pipeline on the 24-layer BERT-large weight set (fp32, 302 M parameters, R = 16):
     group norms + reweighting factors, regulariser gradient, one global percentile over all 18.9 M groups (5x),
-    pack with fp32 and with bf16 value panels.  Matrices that are adjacent in the buffer and share their
+    pack with fp32 and with bf16 value panels, and the zeroing of the pruned groups in W.  Matrices that are adjacent in the buffer and share their
     width are stacked along the rows into one launch (row-blocks are independent), which leaves two launches
     per layer.  Every stage is recorded into a HIP graph and replayed `reps` times between two events."""
     c = wl.config5(layers)
@@ -226,6 +226,12 @@ def prune_path_c5(layers=24, reps=5):
                      bsp.BF16: torch.empty(max(R * v["cap"], 1), dtype=torch.bfloat16, device=dev)}
     t["pack_fp32"] = timed(lambda: pack(bsp.F32))
     t["pack_bf16"] = timed(lambda: pack(bsp.BF16))
+
+    def mask_weights():                              # last: it overwrites the pruned groups of W (idempotent)
+        for v in views:
+            bsp.bsp_mask_weights(v["W"], R, v["k"])
+
+    t["mask_weights"] = timed(mask_weights)
     padded = sum(v["cap"] for v in views)
     # algorithmic bytes: W fp32 read once per stage that needs it, group arrays fp32, the mask 1 byte per group
     by = {"group_norms": 4.0 * params + 8.0 * groups,
@@ -233,7 +239,8 @@ def prune_path_c5(layers=24, reps=5):
           "prune_mask": (4.0 * 4 + 1.0) * groups,
           "pack_count": 1.0 * groups,
           "pack_fp32": 4.0 * params + 1.0 * groups + (4.0 * R + 4.0) * padded,
-          "pack_bf16": 4.0 * params + 1.0 * groups + (2.0 * R + 4.0) * padded}
+          "pack_bf16": 4.0 * params + 1.0 * groups + (2.0 * R + 4.0) * padded,
+          "mask_weights": 8.0 * params + 1.0 * groups}   # W read and written back, the mask read
     stages = {k: {"us": round(t[k], 1), "gbs": round(by[k] / (t[k] * 1e-6) / 1e9, 1),
                   "frac_hbm_peak": round(by[k] / (t[k] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)} for k in t}
     return {"workload": "config 5: %d-layer BERT-large weight set, fp32, %d parameters, R = 16, global 5x percentile"

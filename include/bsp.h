@@ -92,6 +92,12 @@ int bsp_prune_mask(const float *sumsq, int64_t B, int64_t N, float t, int64_t n_
                    uint8_t *keep, float *t_used, void *ws, size_t ws_bytes, void *stream);
 size_t bsp_prune_mask_workspace_bytes(int64_t B, int64_t N, int scope);
 
+/* ---- masked weights (Alg. 1: a pruned group is set to zero; Alg. 2: W = W * Mask after every
+ * retraining update) ---------------------------------------------------------------------
+ * In place: every weight of a group with keep[b, j] == 0 becomes +0; the weights of kept
+ * groups keep their bits.  W: [M, N] row-major of dtype wdt; keep: [M / R, N] uint8. */
+int bsp_mask_weights(void *W, int wdt, int64_t M, int64_t N, int32_t R, const uint8_t *keep, void *stream);
+
 /* ---- compact storage (Sec. 3.1: only the kept columns of a block are indexed) ----------
  * Layout.  For block b: cols_b = ascending j with keep[b, j] != 0; k_b = |cols_b| =
  * blk_cnt[b]; kp_b = k_b rounded up to a multiple of k_align (0 stays 0);

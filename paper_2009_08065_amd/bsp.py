@@ -53,6 +53,7 @@ def lib():
     L.bsp_prune_mask.argtypes = [vp, i64, i64, f32, i64, C.c_int, vp, vp, vp, sz, vp]
     L.bsp_prune_mask_workspace_bytes.argtypes = [i64, i64, C.c_int]
     L.bsp_prune_mask_workspace_bytes.restype = sz
+    L.bsp_mask_weights.argtypes = [vp, C.c_int, i64, i64, i32, vp, vp]
     L.bsp_pack_count.argtypes = [vp, i64, i64, i32, vp, vp, vp]
     L.bsp_pack.argtypes = [vp, C.c_int, i64, i64, i32, vp, i32, vp, vp, i64, vp, vp, C.c_int, vp]
     L.bsp_packed_validate.argtypes = [i64, i64, i32, i32, vp, vp, vp, i64, vp, vp]
@@ -70,7 +71,7 @@ def lib():
     L.bsp_last_hip_error.restype = C.c_int
     L.bsp_version.restype = C.c_char_p
     for name in ("bsp_group_norms", "bsp_penalty_grad", "bsp_prune_mask", "bsp_pack_count", "bsp_pack",
-                 "bsp_packed_validate", "bsp_linear", "bsp_linear_plan", "bsp_linear_planned"):
+                 "bsp_packed_validate", "bsp_linear", "bsp_linear_plan", "bsp_linear_planned", "bsp_mask_weights"):
         getattr(L, name).restype = C.c_int
     _LIB = L
     return L
@@ -151,6 +152,14 @@ def bsp_prune_mask(sumsq, t=0.0, n_keep=-1, scope=SCOPE_BLOCK, keep=None, t_used
                               _ptr(t_used, torch.float32), _ptr(ws), ws_bytes, _stream())
     _check(st, "bsp_prune_mask")
     return keep, t_used
+
+
+def bsp_mask_weights(W, R, keep):
+    """In place: zero every pruned group of W (Alg. 1; the W = W * Mask step of Alg. 2).  Returns W."""
+    M, N = W.shape
+    st = lib().bsp_mask_weights(_ptr(W), _DT[W.dtype], M, N, R, _ptr(keep, torch.uint8), _stream())
+    _check(st, "bsp_mask_weights")
+    return W
 
 
 def bsp_pack_count(keep, k_align=32, blk_cnt=None, blk_ptr=None):

@@ -320,6 +320,63 @@ __global__ __launch_bounds__(kSelThreads) void mask_rank_apply_kernel(const floa
     }
 }
 
+// ------------------------------------------------------------------ masked weights
+// A stream over W in 16-byte lanes (4 fp32 or 8 sixteen-bit columns of one row): a vector whose columns are
+// all kept is skipped, one whose columns are all pruned is overwritten with zeros without being read, a mixed
+// one is read, masked and written back.  (Storing only the pruned elements, as sub-line masked stores, was
+// measured three times slower: partial lines are read-modify-write at the memory anyway.)
+template <int DT>
+__global__ __launch_bounds__(kThreads) void mask_weights_vec_kernel(void *__restrict__ W, int64_t M, int64_t N,
+                                                                    int32_t R, const uint8_t *__restrict__ keep) {
+    using E = typename elem<DT>::type;
+    constexpr int V = 16 / (int)sizeof(E);
+    const int64_t j = ((int64_t)blockIdx.x * kThreads + threadIdx.x) * V;
+    const int64_t m = (int64_t)blockIdx.z * 65535 + blockIdx.y;
+    if (j >= N || m >= M) return;
+    const uint8_t *k = keep + (m / R) * N + j;
+    uint32_t f[V / 4];
+#pragma unroll
+    for (int i = 0; i < V / 4; ++i) f[i] = reinterpret_cast<const uint32_t *>(k)[i];
+    uint32_t any_kept = 0, any_pruned = 0;
+#pragma unroll
+    for (int i = 0; i < V / 4; ++i) {
+        // fold every flag byte onto its low bit
+        uint32_t nz = (f[i] | (f[i] >> 1) | (f[i] >> 2) | (f[i] >> 3) | (f[i] >> 4) | (f[i] >> 5) | (f[i] >> 6) | (f[i] >> 7)) & 0x01010101u;
+        f[i] = nz;
+        any_kept |= nz;
+        any_pruned |= nz ^ 0x01010101u;
+    }
+    if (!any_pruned) return;
+    uint4 *p = reinterpret_cast<uint4 *>((E *)W + m * N + j);
+    if (!any_kept) {
+        *p = make_uint4(0u, 0u, 0u, 0u);
+        return;
+    }
+    uint4 w = *p;
+    uint32_t *wd = reinterpret_cast<uint32_t *>(&w);
+    if constexpr (V == 4) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            if (!((f[0] >> (8 * c)) & 1u)) wd[c] = 0u;
+    } else {
+#pragma unroll
+        for (int c = 0; c < 8; ++c)
+            if (!((f[c >> 2] >> (8 * (c & 3))) & 1u)) wd[c >> 1] &= (c & 1) ? 0x0000ffffu : 0xffff0000u;
+    }
+    *p = w;
+}
+
+// Any shape and alignment: one lane per element.
+template <int DT>
+__global__ __launch_bounds__(kThreads) void mask_weights_kernel(void *__restrict__ W, int64_t M, int64_t N, int32_t R,
+                                                                const uint8_t *__restrict__ keep) {
+    using E = typename elem<DT>::type;
+    const int64_t j = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const int64_t m = (int64_t)blockIdx.z * 65535 + blockIdx.y;
+    if (j >= N || m >= M) return;
+    if (keep[(m / R) * N + j] == 0) ((E *)W)[m * N + j] = E(0);
+}
+
 // Workgroups of the histogram launches: about 8192 elements each, at most kMaxSlots.
 inline int select_slots(int64_t n) {
     int64_t g = (n + 8191) / 8192;
@@ -373,5 +430,24 @@ extern "C" int bsp_prune_mask(const float *sumsq, int64_t B, int64_t N, float t,
     int64_t ga = (n + (int64_t)kSelThreads * 16 - 1) / ((int64_t)kSelThreads * 16);
     ga = ga < 1 ? 1 : (ga > 1024 ? 1024 : ga);
     mask_rank_apply_kernel<<<(unsigned)ga, kSelThreads, 0, s>>>(sumsq, n, (uint32_t)P, G, w, keep, t_used);
+    return check_launch();
+}
+
+extern "C" int bsp_mask_weights(void *W, int wdt, int64_t M, int64_t N, int32_t R, const uint8_t *keep, void *stream) {
+    if (!W || !keep) return BSP_ERR_NULL;
+    if (!valid_dtype(wdt)) return BSP_ERR_DTYPE;
+    if (M <= 0 || N <= 0 || R < 1 || R > 64 || M % R != 0) return BSP_ERR_SHAPE;
+    hipStream_t s = (hipStream_t)stream;
+    const unsigned gy = (unsigned)(M < 65535 ? M : 65535), gz = (unsigned)((M + 65534) / 65535);
+    const int V = wdt == BSP_F32 ? 4 : 8;
+    const bool vec = N % V == 0 && aligned(W, 16) && aligned(keep, 4);
+    BSP_DISPATCH_DTYPE(wdt, DT, {
+        if (vec)
+            mask_weights_vec_kernel<DT><<<dim3((unsigned)((N / V + kThreads - 1) / kThreads), gy, gz), kThreads, 0, s>>>(
+                W, M, N, R, keep);
+        else
+            mask_weights_kernel<DT><<<dim3((unsigned)((N + kThreads - 1) / kThreads), gy, gz), kThreads, 0, s>>>(W, M, N,
+                                                                                                              R, keep);
+    });
     return check_launch();
 }

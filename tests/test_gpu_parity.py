@@ -187,6 +187,27 @@ def test_pack_all_empty_and_capacity_guard():
     assert st == 0 and (host(col)[32:] == -7).all() and (host(col)[:20] >= 0).all() and (host(vals)[16 * 32:] == 5).all()
 
 
+# ------------------------------------------------------------------------------ masked weights
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+@pytest.mark.parametrize("R,M,N", [(16, 96, 1024), (8, 64, 777), (3, 27, 130), (64, 128, 73), (1, 5, 1)])
+def test_mask_weights_bit_exact(dtype, R, M, N):
+    W = wl.normal(R * 10 + N, (M, N), 0.02, dtype)
+    W[0, 0] = -0.0
+    keep = wl.bernoulli_keep_mask(R + M + N, M // R, N, 0.3)
+    keep[0, :] = 0
+    if M // R > 1:
+        keep[1, :] = 1
+    Wd = dev(W, dtype)
+    out = bsp.bsp_mask_weights(Wd, R, torch.from_numpy(keep).cuda())
+    assert out.data_ptr() == Wd.data_ptr()
+    assert bits_equal(host(Wd), orc.mask_weights(W, R, keep))
+    # a view that starts on an odd element: the two-element stores must not be used
+    holder = dev(np.concatenate([np.zeros(1, np.float32), W.reshape(-1)]), dtype)
+    Wo = holder[1:].view(M, N)
+    bsp.bsp_mask_weights(Wo, R, torch.from_numpy(keep).cuda())
+    assert bits_equal(host(Wo), orc.mask_weights(W, R, keep)) and float(holder[0]) == 0.0
+
+
 # ------------------------------------------------------------------------------ the layer
 def run_layer(X, W, bias, R, keep, k_align, dtype, T_rows=None):
     code = CODE[dtype]
