@@ -133,11 +133,20 @@ def cpu_baseline(mats):
         orc.linear_packed(X, p, bias, ydt=orc.BF16, n_threads=cores)
         secs += time.perf_counter() - t
         flops += 2.0 * m.T * m.R * int(p["blk_cnt"].sum())
+    # one thread, on the first 256 tokens of the first matrix
+    m = mats[0]
+    p = orc.pack(m.W.float().cpu().numpy(), m.R, m.keep.cpu().numpy(), m.k_align, orc.BF16)
+    X1 = m.X[:256].float().cpu().numpy()
+    t = time.perf_counter()
+    orc.linear_packed(X1, p, m.bias.float().cpu().numpy(), ydt=orc.BF16, n_threads=1)
+    one = 2.0 * 256 * m.R * int(p["blk_cnt"].sum()) / (time.perf_counter() - t) / 1e12
     return {"value": round(flops / secs / 1e12, 5), "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
-            "sample": f"oracle layer (fp64 accumulate, OpenMP over row-blocks) on the full set, all 8192 tokens; {secs:.1f} s"}
+            "single_thread_tflops": round(one, 5),
+            "sample": f"oracle layer (fp64 accumulate, OpenMP over row-blocks) on the full set, all 8192 tokens; {secs:.1f} s "
+                      f"on {cores} threads; single thread: 256 tokens of the QKV matrix"}
 
 
-def prune_path_c5(layers=24, reps=5):
+def prune_path_c5(layers=24, reps=5, with_cpu=True):
     """HBM rate of the pruning pipeline on the 24-layer BERT-large weight set (fp32, 302 M parameters, R = 16):
     group norms + reweighting factors, regulariser gradient, one global percentile over all 18.9 M groups (5x),
     pack with fp32 and with bf16 value panels, and the zeroing of the pruned groups in W.  Matrices that are adjacent in the buffer and share their
@@ -243,8 +252,34 @@ def prune_path_c5(layers=24, reps=5):
           "mask_weights": 8.0 * params + 1.0 * groups}   # W read and written back, the mask read
     stages = {k: {"us": round(t[k], 1), "gbs": round(by[k] / (t[k] * 1e-6) / 1e9, 1),
                   "frac_hbm_peak": round(by[k] / (t[k] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)} for k in t}
+    cpu = None
+    if with_cpu:
+        from oracle import bsp_oracle as orc
+        off, rows, n = runs[0]
+        rows1 = min(rows, 8192)                    # one layer's matrices of width 1024: 8.4 M parameters, 524 288 groups
+        W1 = c["W"][off:off + rows1 * n].reshape(rows1, n)
+        tt = time.perf_counter()
+        s1 = orc.sumsq(W1, R)
+        _, a1 = orc.norm_alpha(s1, eps, orc.ALPHA_SQNORM)
+        t_norm = time.perf_counter() - tt
+        tt = time.perf_counter()
+        orc.penalty_grad(W1, R, a1, lam, orc.ALPHA_SQNORM)
+        t_grad = time.perf_counter() - tt
+        tt = time.perf_counter()
+        k1, _ = orc.mask_rank(s1.reshape(1, -1), s1.size // 5, orc.SCOPE_MATRIX)
+        t_mask = time.perf_counter() - tt
+        tt = time.perf_counter()
+        orc.pack(W1, R, k1.reshape(s1.shape), 32, orc.F32)
+        t_pack = time.perf_counter() - tt
+        p1, g1 = W1.size, s1.size
+        cpu = {"kind": "oracle", "cores": 1, "sample": "the first layer's matrices of width 1024 (%d parameters)" % p1,
+               "group_norms_gbs": round((4.0 * p1 + 8.0 * g1) / t_norm / 1e9, 2),
+               "penalty_grad_gbs": round((8.0 * p1 + 4.0 * g1) / t_grad / 1e9, 2),
+               "prune_mask_gbs": round(17.0 * g1 / t_mask / 1e9, 3),
+               "pack_fp32_gbs": round((4.0 * p1 + g1 + 68.0 * (g1 // 5)) / t_pack / 1e9, 2)}
     return {"workload": "config 5: %d-layer BERT-large weight set, fp32, %d parameters, R = 16, global 5x percentile"
                         % (layers, params),
+            "cpu_baseline": cpu,
             "launches_per_stage": len(views), "groups": groups, "kept_groups": kept,
             "rate": round(params / (R * max(kept, 1)), 4), "stages": stages}
 
@@ -478,7 +513,7 @@ def main():
     if not args.no_c5:
         del mats
         torch.cuda.empty_cache()
-        out["prune_path_c5"] = prune_path_c5()
+        out["prune_path_c5"] = prune_path_c5(with_cpu=not args.no_cpu_baseline)
     print(json.dumps(out))
 
 
