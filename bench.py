@@ -188,6 +188,11 @@ def prune_path_c5(layers=24, reps=5, with_cpu=True):
         for v in views:
             bsp.bsp_penalty_grad(v["W"], R, v["a"], lam, mode=bsp.ALPHA_SQNORM, grad=v["G"])
 
+    def norms_gradient():
+        for v in views:
+            bsp.bsp_group_norms_grad(v["W"], R, lam, eps=eps, mode=bsp.ALPHA_SQNORM, sumsq=v["s"], alpha=v["a"],
+                                     grad=v["G"], want=())
+
     def mask():
         bsp.bsp_prune_mask(sumsq.view(Bm, Nm), n_keep=n_keep, scope=bsp.SCOPE_MATRIX, keep=keep.view(Bm, Nm), ws=ws)
 
@@ -224,6 +229,7 @@ def prune_path_c5(layers=24, reps=5, with_cpu=True):
     t = {}
     t["group_norms"] = timed(norms)
     t["penalty_grad"] = timed(gradient)
+    t["group_norms_grad"] = timed(norms_gradient)
     t["prune_mask"] = timed(mask)
     t["pack_count"] = timed(count)
     kept = 0
@@ -245,6 +251,7 @@ def prune_path_c5(layers=24, reps=5, with_cpu=True):
     # algorithmic bytes: W fp32 read once per stage that needs it, group arrays fp32, the mask 1 byte per group
     by = {"group_norms": 4.0 * params + 8.0 * groups,
           "penalty_grad": 8.0 * params + 4.0 * groups,
+          "group_norms_grad": 8.0 * params + 8.0 * groups,   # both of the above with W read once
           "prune_mask": (4.0 * 4 + 1.0) * groups,
           "pack_count": 1.0 * groups,
           "pack_fp32": 4.0 * params + 1.0 * groups + (4.0 * R + 4.0) * padded,

@@ -92,6 +92,14 @@ int bsp_prune_mask(const float *sumsq, int64_t B, int64_t N, float t, int64_t n_
                    uint8_t *keep, float *t_used, void *ws, size_t ws_bytes, void *stream);
 size_t bsp_prune_mask_workspace_bytes(int64_t B, int64_t N, int scope);
 
+/* ---- refresh and gradient in one pass (Alg. 2 at a milestone: "update gamma", then the
+ * regulariser term of the next step's gradient with the new factors) --------------------
+ * Exactly bsp_group_norms followed by bsp_penalty_grad with the alpha just computed, bit for
+ * bit, but W is read once.  sumsq, norm, alpha may be NULL; grad must not. */
+int bsp_group_norms_grad(const void *W, int wdt, int64_t M, int64_t N, int32_t R, float eps, int mode,
+                         float lambda, int accumulate, float *sumsq, float *norm, float *alpha, void *grad,
+                         void *stream);
+
 /* ---- masked weights (Alg. 1: a pruned group is set to zero; Alg. 2: W = W * Mask after every
  * retraining update) ---------------------------------------------------------------------
  * In place: every weight of a group with keep[b, j] == 0 becomes +0; the weights of kept

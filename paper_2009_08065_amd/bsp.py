@@ -54,6 +54,7 @@ def lib():
     L.bsp_prune_mask_workspace_bytes.argtypes = [i64, i64, C.c_int]
     L.bsp_prune_mask_workspace_bytes.restype = sz
     L.bsp_mask_weights.argtypes = [vp, C.c_int, i64, i64, i32, vp, vp]
+    L.bsp_group_norms_grad.argtypes = [vp, C.c_int, i64, i64, i32, f32, C.c_int, f32, C.c_int, vp, vp, vp, vp, vp]
     L.bsp_pack_count.argtypes = [vp, i64, i64, i32, vp, vp, vp]
     L.bsp_pack.argtypes = [vp, C.c_int, i64, i64, i32, vp, i32, vp, vp, i64, vp, vp, C.c_int, vp]
     L.bsp_packed_validate.argtypes = [i64, i64, i32, i32, vp, vp, vp, i64, vp, vp]
@@ -71,7 +72,8 @@ def lib():
     L.bsp_last_hip_error.restype = C.c_int
     L.bsp_version.restype = C.c_char_p
     for name in ("bsp_group_norms", "bsp_penalty_grad", "bsp_prune_mask", "bsp_pack_count", "bsp_pack",
-                 "bsp_packed_validate", "bsp_linear", "bsp_linear_plan", "bsp_linear_planned", "bsp_mask_weights"):
+                 "bsp_packed_validate", "bsp_linear", "bsp_linear_plan", "bsp_linear_planned", "bsp_mask_weights",
+                 "bsp_group_norms_grad"):
         getattr(L, name).restype = C.c_int
     _LIB = L
     return L
@@ -111,6 +113,30 @@ def bsp_group_norms(W, R, eps=1e-6, mode=ALPHA_SQNORM, sumsq=None, norm=None, al
                                _ptr(norm, torch.float32), _ptr(alpha, torch.float32), _stream())
     _check(st, "bsp_group_norms")
     return sumsq, norm, alpha
+
+
+def bsp_group_norms_grad(W, R, lam, eps=1e-6, mode=ALPHA_SQNORM, sumsq=None, norm=None, alpha=None, grad=None,
+                         accumulate=False, want=("sumsq", "alpha")):
+    """bsp_group_norms and bsp_penalty_grad in one pass over W.  Returns (sumsq, norm, alpha, grad)."""
+    M, N = W.shape
+    B = M // max(R, 1)
+    mk = lambda: torch.empty((B, N), dtype=torch.float32, device=W.device)
+    if sumsq is None and "sumsq" in want:
+        sumsq = mk()
+    if norm is None and "norm" in want:
+        norm = mk()
+    if alpha is None and "alpha" in want:
+        alpha = mk()
+    if grad is None:
+        grad = torch.empty_like(W)
+        accumulate = False
+    if grad.dtype != W.dtype or grad.shape != W.shape:
+        raise ValueError("grad must have the shape and dtype of W")
+    st = lib().bsp_group_norms_grad(_ptr(W), _DT[W.dtype], M, N, R, eps, mode, lam, int(bool(accumulate)),
+                                    _ptr(sumsq, torch.float32), _ptr(norm, torch.float32), _ptr(alpha, torch.float32),
+                                    _ptr(grad), _stream())
+    _check(st, "bsp_group_norms_grad")
+    return sumsq, norm, alpha, grad
 
 
 def bsp_penalty_grad(W, R, alpha, lam, mode=ALPHA_SQNORM, grad=None, accumulate=False, want_penalty=False, ws=None):

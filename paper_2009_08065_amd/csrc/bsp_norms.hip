@@ -171,6 +171,82 @@ __global__ __launch_bounds__(kThreads) void group_norms_kernel(const void *__res
     }
 }
 
+// Refresh and gradient in one pass over W (Alg. 2 at a milestone: the factors are recomputed and the next
+// step's regulariser gradient uses them).  The same arithmetic as group_norms_kernel followed by the gradient
+// kernels, operation for operation, so the results are bit-identical to the two separate calls; the R = RT
+// rows of the lane's groups stay in registers between the norm pass and the scaling pass (RT == 0: any R,
+// the second pass re-reads the rows).
+template <int DT, int VEC, int RT>
+__global__ __launch_bounds__(kThreads) void norms_grad_kernel(const void *__restrict__ W, int64_t N, int32_t R, float eps,
+                                                              int mode, float lambda, int accumulate,
+                                                              float *__restrict__ sumsq, float *__restrict__ norm,
+                                                              float *__restrict__ alpha, void *__restrict__ G) {
+    const int64_t jv = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const int64_t j = jv * VEC;
+    if (j >= N) return;
+    const int64_t b = blockIdx.y;
+    const int64_t base = b * R * N + j;
+    constexpr int RC = RT > 0 ? RT : 1;
+    float cache[RC][VEC];
+    float acc[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) acc[v] = 0.0f;
+    auto row_step = [&](int32_t r) {
+        float w[VEC];
+        vec_io<DT, VEC>::load(W, base + (int64_t)r * N, w);
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+            if constexpr (RT > 0) cache[r][v] = w[v];
+            acc[v] = __builtin_fmaf(w[v], w[v], acc[v]);
+        }
+    };
+    if constexpr (RT > 0) {
+#pragma unroll
+        for (int32_t r = 0; r < RT; ++r) row_step(r);
+    } else {
+#pragma unroll 4
+        for (int32_t r = 0; r < R; ++r) row_step(r);
+    }
+    float root[VEC], a[VEC], coef[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) {
+        root[v] = __builtin_sqrtf(acc[v]);
+        a[v] = alpha_of(acc[v], root[v], eps, mode);
+        coef[v] = lambda * a[v];
+        if (mode == BSP_ALPHA_NORM) coef[v] = (acc[v] > 0.0f) ? coef[v] / __builtin_sqrtf(acc[v]) : 0.0f;
+    }
+    const int64_t o = b * N + j;
+    if (sumsq) store_f32<VEC>(sumsq, o, acc);
+    if (norm) store_f32<VEC>(norm, o, root);
+    if (alpha) store_f32<VEC>(alpha, o, a);
+    auto out_step = [&](int32_t r) {
+        const int64_t off = base + (int64_t)r * N;
+        float w[VEC], g[VEC];
+        if constexpr (RT > 0) {
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) w[v] = cache[r][v];
+        } else {
+            vec_io<DT, VEC>::load(W, off, w);
+        }
+        if (accumulate) {
+            vec_io<DT, VEC>::load(G, off, g);
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) g[v] = __builtin_fmaf(coef[v], w[v], g[v]);
+        } else {
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) g[v] = coef[v] * w[v];
+        }
+        vec_io<DT, VEC>::store(G, off, g);
+    };
+    if constexpr (RT > 0) {
+#pragma unroll
+        for (int32_t r = 0; r < RT; ++r) out_step(r);
+    } else {
+#pragma unroll 4
+        for (int32_t r = 0; r < R; ++r) out_step(r);
+    }
+}
+
 // Gradient of the regulariser.  RT > 0: the R = RT rows of the lane's groups stay in
 // registers between the norm pass and the scaling pass, so W is read from HBM once.
 // RT == 0: any R; the second pass re-reads the rows (cache hits in the common case).
@@ -426,4 +502,31 @@ extern "C" int bsp_penalty_grad(const void *W, int wdt, int64_t M, int64_t N, in
             st = launch_penalty<DT, V, 0>(W, N, R, B, alpha, lambda, mode, accumulate, grad, penalty, partial, s);
     });
     return st;
+}
+
+#define BSP_NG_LAUNCH(VV, RT) \
+    norms_grad_kernel<DT, VV, RT><<<grid, kThreads, 0, s>>>(W, N, R, eps, mode, lambda, accumulate, sumsq, norm, alpha, grad)
+extern "C" int bsp_group_norms_grad(const void *W, int wdt, int64_t M, int64_t N, int32_t R, float eps, int mode,
+                                    float lambda, int accumulate, float *sumsq, float *norm, float *alpha, void *grad,
+                                    void *stream) {
+    int st = check_matrix(W, wdt, M, N, R);
+    if (st != BSP_OK) return st;
+    if (!grad) return BSP_ERR_NULL;
+    if (mode != BSP_ALPHA_SQNORM && mode != BSP_ALPHA_NORM) return BSP_ERR_DTYPE;
+    const int64_t B = M / R;
+    if (B > 65535) return BSP_ERR_SHAPE;
+    hipStream_t s = (hipStream_t)stream;
+    BSP_DISPATCH_DTYPE(wdt, DT, {
+        constexpr int V = native_vec<DT>();
+        const bool vec_ok = (N % V == 0) && aligned(W, 16) && aligned(grad, 16) && (!sumsq || aligned(sumsq, 16)) &&
+                            (!norm || aligned(norm, 16)) && (!alpha || aligned(alpha, 16));
+        const dim3 grid = vec_ok ? grid_for(N, V, B) : grid_for(N, 1, B);
+        if (!vec_ok) BSP_NG_LAUNCH(1, 0);
+        else if (R == 8) BSP_NG_LAUNCH(V, 8);
+        else if (R == 16) BSP_NG_LAUNCH(V, 16);
+        else if (R == 32) BSP_NG_LAUNCH(V, 32);
+        else BSP_NG_LAUNCH(V, 0);
+    });
+#undef BSP_NG_LAUNCH
+    return check_launch();
 }

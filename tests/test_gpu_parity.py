@@ -103,6 +103,33 @@ def test_penalty_grad(dtype, R, M, N, mode):
     assert bits_equal(host(Gacc), Gacc_ref)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+@pytest.mark.parametrize("R,M,N", [(16, 64, 512), (8, 32, 264), (32, 64, 1024), (5, 20, 77), (64, 128, 520)])
+@pytest.mark.parametrize("mode", [orc.ALPHA_SQNORM, orc.ALPHA_NORM])
+def test_group_norms_grad_one_pass(dtype, R, M, N, mode):
+    """The fused refresh + gradient is the chain sumsq -> factors -> Eq. 3 gradient, bit for bit."""
+    W = wl.normal(7 * R + N, (M, N), 0.02, dtype)
+    W[0:R, 1] = 0.0
+    lam = 1e-4
+    s_ref = orc.sumsq(W, R)
+    n_ref, a_ref = orc.norm_alpha(s_ref, 1e-6, mode)
+    G_ref, _ = orc.penalty_grad(W, R, a_ref, lam, mode, gdt=CODE[dtype])
+    Wd = dev(W, dtype)
+    s, nrm, alpha, G = bsp.bsp_group_norms_grad(Wd, R, lam, eps=1e-6, mode=mode, want=("sumsq", "norm", "alpha"))
+    assert bits_equal(host(s), s_ref) and bits_equal(host(nrm), n_ref) and bits_equal(host(alpha), a_ref)
+    assert bits_equal(host(G), G_ref)
+    s2, nrm2, alpha2, G2 = bsp.bsp_group_norms_grad(Wd, R, lam, eps=1e-6, mode=mode, want=())
+    assert s2 is None and nrm2 is None and alpha2 is None and bits_equal(host(G2), G_ref)
+    G0 = wl.normal(98, (M, N), 0.01, dtype)
+    Gacc_ref, _ = orc.penalty_grad(W, R, a_ref, lam, mode, gdt=CODE[dtype], G0=G0)
+    _, _, _, Gacc = bsp.bsp_group_norms_grad(Wd, R, lam, eps=1e-6, mode=mode, grad=dev(G0, dtype), accumulate=True)
+    assert bits_equal(host(Gacc), Gacc_ref)
+    # the two separate calls give the same bits
+    _, _, alpha_d = bsp.bsp_group_norms(Wd, R, eps=1e-6, mode=mode)
+    G_sep, _ = bsp.bsp_penalty_grad(Wd, R, alpha_d, lam, mode=mode)
+    assert torch.equal(G_sep.view(torch.uint8), G.view(torch.uint8))
+
+
 # ------------------------------------------------------------------------------ masks
 def test_mask_threshold_bit_exact_with_ties():
     W = wl.normal(3, (64, 333), 0.02)
