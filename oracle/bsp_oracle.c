@@ -323,6 +323,66 @@ void orc_mask_weights(float *W, int64_t M, int64_t N, int32_t R, const uint8_t *
             if (!keep[(m / R) * N + j]) W[m * N + j] = 0.0f;
 }
 
+/* ------------------------------------------------------------------------------------ */
+/* One weight update of Alg. 2: "update W to minimise the loss using Adam", where the     */
+/* loss is the mixed loss during reweighted training (gradient of the prediction loss G   */
+/* plus the gradient of the regulariser with the factors alpha held fixed, Eq. 3) and the */
+/* prediction loss alone during retraining, followed there by W = W * Mask.               */
+/* Adam as published (Kingma & Ba, Algorithm 1), all in fp32, every operation rounded     */
+/* once, in this order, per element (w, g, m, v):                                         */
+/*   g  <- fmaf(coef, w, g)              only when alpha != NULL (coef as orc_penalty_grad)*/
+/*   m  <- beta1*m + (1 - beta1)*g                                                        */
+/*   v  <- beta2*v + ((1 - beta2)*g)*g                                                    */
+/*   w  <- w - (lr * (m / c1)) / (sqrtf(v / c2) + eps),   c_i = 1 - beta_i^t              */
+/*   w  <- +0                             only when keep != NULL and the group is pruned   */
+/* c1, c2 are formed in double (pow) and rounded to fp32; 1 - beta_i is an fp32           */
+/* subtraction.  The moments of a pruned weight keep evolving: Alg. 2 masks W only.       */
+/* ------------------------------------------------------------------------------------ */
+void orc_adam_step(float *W, const float *G, float *m, float *v, int64_t M, int64_t N, int32_t R,
+                   const float *alpha, float lambda, int32_t mode, const uint8_t *keep, float lr,
+                   float beta1, float beta2, float eps, int64_t t)
+{
+    float c1 = (float)(1.0 - pow((double)beta1, (double)t));
+    float c2 = (float)(1.0 - pow((double)beta2, (double)t));
+    float omb1 = 1.0f - beta1, omb2 = 1.0f - beta2;
+    int64_t B = M / R;
+    for (int64_t b = 0; b < B; ++b)
+        for (int64_t j = 0; j < N; ++j) {
+            float coef = 0.0f;
+            if (alpha) {
+                float s = 0.0f;
+                for (int32_t r = 0; r < R; ++r) {
+                    float w = W[(b * R + r) * N + j];
+                    s = fmaf(w, w, s);
+                }
+                coef = lambda * alpha[b * N + j];
+                if (mode == ORC_ALPHA_NORM) coef = (s > 0.0f) ? coef / sqrtf(s) : 0.0f;
+            }
+            for (int32_t r = 0; r < R; ++r) {
+                int64_t i = (b * R + r) * N + j;
+                float w = W[i], g = G[i];
+                if (alpha) g = fmaf(coef, w, g);
+                float t1 = beta1 * m[i];
+                float t2 = omb1 * g;
+                float mn = t1 + t2;
+                float t3 = beta2 * v[i];
+                float t4 = omb2 * g;
+                t4 = t4 * g;
+                float vn = t3 + t4;
+                float mh = mn / c1;
+                float vh = vn / c2;
+                float num = lr * mh;
+                float den = sqrtf(vh) + eps;
+                float q = num / den;
+                float wn = w - q;
+                if (keep && !keep[b * N + j]) wn = 0.0f;
+                W[i] = wn;
+                m[i] = mn;
+                v[i] = vn;
+            }
+        }
+}
+
 /* Compression rate as the paper counts it (Sec. 4.4: 1.428x <=> 30 % sparsity):          */
 /* dense parameters over kept parameters.                                                 */
 double orc_compression_rate(int64_t M, int64_t N, int32_t R, int64_t kept_cols_total)

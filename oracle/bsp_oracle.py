@@ -172,5 +172,26 @@ def mask_weights(W, R, keep):
     return W
 
 
+def adam_step(W, G, m, v, R, lr, beta1=0.9, beta2=0.999, eps=1e-8, t=1, alpha=None, lam=0.0, mode=ALPHA_SQNORM,
+              keep=None):
+    """One Adam update of Alg. 2 (fp32): optional regulariser gradient (Eq. 3, factors alpha fixed) added to G,
+    moments, weight update, optional W = W * Mask.  Returns new copies (W, m, v)."""
+    W, m, v = _f32(W).copy(), _f32(m).copy(), _f32(v).copy()
+    G = _f32(G)
+    M, N = W.shape
+    assert G.shape == W.shape and m.shape == W.shape and v.shape == W.shape
+    if alpha is not None:
+        alpha = _f32(alpha)
+        assert alpha.shape == (M // R, N)
+    if keep is not None:
+        keep = np.ascontiguousarray(keep, dtype=np.uint8)
+        assert keep.shape == (M // R, N)
+    lib().orc_adam_step(_p(W), _p(G), _p(m), _p(v), C.c_int64(M), C.c_int64(N), C.c_int32(R),
+                        _p(alpha) if alpha is not None else None, C.c_float(lam), C.c_int32(mode),
+                        _p(keep) if keep is not None else None, C.c_float(lr), C.c_float(beta1), C.c_float(beta2),
+                        C.c_float(eps), C.c_int64(t))
+    return W, m, v
+
+
 def compression_rate(M, N, R, kept_cols_total):
     return lib().orc_compression_rate(M, N, R, kept_cols_total)

@@ -462,3 +462,104 @@ def test_mask_weights_definition_and_invariants():
     Yd, _ = orc.linear_dense(X, orc.mask_weights(Wg, R, keep), np.ones_like(keep), None, R, ydt=orc.F32)
     Yp, _ = orc.linear_packed(X, orc.pack(Wg, R, keep, 1), None, ydt=orc.F32)
     assert np.allclose(Yd, Yp, rtol=0, atol=1e-5)
+
+
+# ---------------------------------------------------------------------------------- the Adam update of Alg. 2
+def _adam_f64(w, g, m, v, lr, b1, b2, eps, t):
+    """Kingma & Ba, Algorithm 1, in double on the fp32 inputs and fp32 hyper-parameters."""
+    b1, b2, lr, eps = (float(np.float32(x)) for x in (b1, b2, lr, eps))
+    w, g, m, v = (np.asarray(a, np.float64) for a in (w, g, m, v))
+    m = b1 * m + (1.0 - b1) * g
+    v = b2 * v + (1.0 - b2) * g * g
+    w = w - lr * (m / (1.0 - b1 ** t)) / (np.sqrt(v / (1.0 - b2 ** t)) + eps)
+    return w, m, v
+
+
+def test_adam_step_against_the_published_update_in_double():
+    rng = np.random.default_rng(21)
+    R, B, N = 4, 6, 29
+    W = (rng.standard_normal((B * R, N)) * 0.05).astype(np.float32)
+    lr, b1, b2, eps = 3e-5, 0.9, 0.999, 1e-8
+    m = np.zeros_like(W)
+    v = np.zeros_like(W)
+    Wd, md, vd = W.astype(np.float64), m.astype(np.float64), v.astype(np.float64)
+    for t in range(1, 8):                                # several steps, the state carried by both sides
+        G = (rng.standard_normal(W.shape) * 1e-3).astype(np.float32)
+        W, m, v = orc.adam_step(W, G, m, v, R, lr, b1, b2, eps, t)
+        Wd, md, vd = _adam_f64(Wd, G, md, vd, lr, b1, b2, eps, t)
+        # m is a signed sum (cancellation: absolute bound on its scale); v is a sum of non-negative terms
+        assert np.allclose(m, md, rtol=0, atol=4e-7 * 5e-3) and np.allclose(v, vd, rtol=4e-6, atol=0)
+        # each step rounds w once (half an ulp of |w| < 0.25) on a move of about lr = 3e-5
+        assert np.allclose(W - Wd, 0, atol=t * (1.5e-8 + lr * 1e-5))
+
+
+def test_adam_step_closed_forms_and_invariants():
+    rng = np.random.default_rng(22)
+    R, B, N = 8, 3, 17
+    shape = (B * R, N)
+    W0 = (rng.standard_normal(shape) * 0.05).astype(np.float32)
+    G = (rng.standard_normal(shape) * 1e-2).astype(np.float32)
+    z = np.zeros(shape, np.float32)
+    lr = 2e-5
+    # first step from zero moments: the bias corrections cancel, the move is lr * g / (|g| + eps)
+    W1, m1, v1 = orc.adam_step(W0, G, z, z, R, lr, 0.9, 0.999, 1e-8, 1)
+    want = W0.astype(np.float64) - lr * G.astype(np.float64) / (np.abs(G.astype(np.float64)) + 1e-8)
+    assert np.allclose(W1, want, rtol=0, atol=lr * 2e-6 + 4e-9)
+    assert np.allclose(m1, 0.1 * G.astype(np.float64), rtol=1e-6) and np.allclose(v1, 0.001 * G.astype(np.float64) ** 2, rtol=1e-5)
+    # no gradient, no moments: nothing moves, bit for bit
+    W2, m2, v2 = orc.adam_step(W0, z, z, z, R, lr, 0.9, 0.999, 1e-8, 5)
+    assert np.array_equal(W2.view(np.uint32), W0.view(np.uint32)) and not m2.any() and not v2.any()
+    # a constant gradient: every step moves each weight by lr against the gradient's sign (eps negligible)
+    W, m, v = W0.copy(), z, z
+    for t in range(1, 21):
+        W, m, v = orc.adam_step(W, G, m, v, R, lr, 0.9, 0.999, 1e-12, t)
+    assert np.allclose(W, W0.astype(np.float64) - 20 * lr * np.sign(G), rtol=0, atol=20 * lr * 1e-5 + 1e-7)
+    # with eps = 0 the update does not see a rescaling of the gradients by a power of two
+    Wa, ma, va = orc.adam_step(W0, G, z, z, R, lr, 0.9, 0.999, 0.0, 1)
+    Wb, mb, vb = orc.adam_step(W0, 4 * G, z, z, R, lr, 0.9, 0.999, 0.0, 1)
+    assert np.array_equal(Wa.view(np.uint32), Wb.view(np.uint32))
+    assert np.array_equal(mb, 4 * ma) and np.array_equal(vb, 16 * va)
+    # beta1 = beta2 = 0: no memory, the move is lr * sign(g) whatever the old moments were
+    junk = np.abs(rng.standard_normal(shape)).astype(np.float32)
+    Wc, mc, vc = orc.adam_step(W0, G, junk, junk, R, lr, 0.0, 0.0, 0.0, 3)
+    assert np.array_equal(mc, G) and np.array_equal(vc, G * G)
+    assert np.allclose(Wc, W0.astype(np.float64) - lr * np.sign(G), rtol=0, atol=lr * 1e-6 + 4e-9)
+
+
+def test_adam_step_mask_and_regulariser():
+    rng = np.random.default_rng(23)
+    R, B, N = 4, 5, 23
+    shape = (B * R, N)
+    W0 = (rng.standard_normal(shape) * 0.05).astype(np.float32)
+    W0[0:R, 2] = 0.0                                    # an all-zero group
+    G = (rng.standard_normal(shape) * 1e-3).astype(np.float32)
+    m0 = (rng.standard_normal(shape) * 1e-3).astype(np.float32)
+    v0 = (rng.standard_normal(shape) ** 2 * 1e-6).astype(np.float32)
+    keep = (rng.random((B, N)) < 0.3).astype(np.uint8)
+    big = np.repeat(keep, R, axis=0).astype(bool)
+    hp = dict(lr=3e-5, beta1=0.9, beta2=0.999, eps=1e-8, t=4)
+    Wp, mp, vp = orc.adam_step(W0, G, m0, v0, R, **hp)
+    # retraining: the update, then W = W * Mask; the moments are those of the unmasked update
+    Wk, mk, vk = orc.adam_step(W0, G, m0, v0, R, keep=keep, **hp)
+    assert np.array_equal(Wk.view(np.uint32), orc.mask_weights(Wp, R, keep).view(np.uint32))
+    assert np.all(Wk.view(np.uint32)[~big] == 0) and np.array_equal(Wk[big], Wp[big])
+    assert np.array_equal(mk, mp) and np.array_equal(vk, vp)
+    # reweighted training: Adam on the mixed loss = Adam on G + gradient of the regulariser (Eq. 3, factors fixed)
+    lam = 1e-3
+    for mode in (orc.ALPHA_SQNORM, orc.ALPHA_NORM):
+        _, alpha = orc.norm_alpha(orc.sumsq(W0, R), 1e-6, mode)
+        Gmix, _ = orc.penalty_grad(W0, R, alpha, lam, mode, gdt=orc.F32, G0=G)
+        assert not np.array_equal(Gmix, G)
+        Wr, mr, vr = orc.adam_step(W0, G, m0, v0, R, alpha=alpha, lam=lam, mode=mode, **hp)
+        Ws, ms, vs = orc.adam_step(W0, Gmix, m0, v0, R, **hp)
+        for a, b in ((Wr, Ws), (mr, ms), (vr, vs)):
+            assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+        # lambda = 0 leaves the plain update
+        Wz, mz, vz = orc.adam_step(W0, G, m0, v0, R, alpha=alpha, lam=0.0, mode=mode, **hp)
+        assert np.array_equal(Wz, Wp) and np.array_equal(mz, mp) and np.array_equal(vz, vp)
+    # the regulariser pulls every weight of a non-zero group towards zero when there is no other gradient
+    _, alpha = orc.norm_alpha(orc.sumsq(W0, R), 1e-6, orc.ALPHA_SQNORM)
+    z = np.zeros(shape, np.float32)
+    Wq, _, _ = orc.adam_step(W0, z, z, z, R, alpha=alpha, lam=lam, mode=orc.ALPHA_SQNORM, lr=1e-4, t=1)
+    nz = W0 != 0
+    assert np.all(np.abs(Wq[nz]) < np.abs(W0[nz])) and np.all(Wq[~nz] == 0)
