@@ -247,6 +247,18 @@ def prune_path_c5(layers=24, reps=5, with_cpu=True):
             bsp.bsp_mask_weights(v["W"], R, v["k"])
 
     t["mask_weights"] = timed(mask_weights)
+    mom1, mom2 = torch.zeros_like(Wbuf), torch.zeros_like(Wbuf)
+    grad.normal_(0.0, 1e-3)
+
+    def adam(reg, masked):                           # the weight update of Alg. 2's two loops, whole state in place
+        for v in views:
+            off = v["W"].data_ptr() - Wbuf.data_ptr()
+            sl = slice(off // 4, off // 4 + v["W"].numel())
+            bsp.bsp_adam_step(v["W"], v["G"], mom1[sl].view_as(v["W"]), mom2[sl].view_as(v["W"]), R, 3e-5, t=3,
+                              alpha=v["a"] if reg else None, lam=lam, keep=v["k"] if masked else None)
+
+    t["adam_mixed_loss"] = timed(lambda: adam(True, False))
+    t["adam_masked"] = timed(lambda: adam(False, True))
     padded = sum(v["cap"] for v in views)
     # algorithmic bytes: W fp32 read once per stage that needs it, group arrays fp32, the mask 1 byte per group
     by = {"group_norms": 4.0 * params + 8.0 * groups,
@@ -256,7 +268,9 @@ def prune_path_c5(layers=24, reps=5, with_cpu=True):
           "pack_count": 1.0 * groups,
           "pack_fp32": 4.0 * params + 1.0 * groups + (4.0 * R + 4.0) * padded,
           "pack_bf16": 4.0 * params + 1.0 * groups + (2.0 * R + 4.0) * padded,
-          "mask_weights": 8.0 * params + 1.0 * groups}   # W read and written back, the mask read
+          "mask_weights": 8.0 * params + 1.0 * groups,   # W read and written back, the mask read
+          "adam_mixed_loss": 28.0 * params + 4.0 * groups,   # w, g, m, v read; w, m, v written; the factors read
+          "adam_masked": 28.0 * params + 1.0 * groups}
     stages = {k: {"us": round(t[k], 1), "gbs": round(by[k] / (t[k] * 1e-6) / 1e9, 1),
                   "frac_hbm_peak": round(by[k] / (t[k] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)} for k in t}
     cpu = None

@@ -106,6 +106,24 @@ int bsp_group_norms_grad(const void *W, int wdt, int64_t M, int64_t N, int32_t R
  * groups keep their bits.  W: [M, N] row-major of dtype wdt; keep: [M / R, N] uint8. */
 int bsp_mask_weights(void *W, int wdt, int64_t M, int64_t N, int32_t R, const uint8_t *keep, void *stream);
 
+/* ---- one weight update (Alg. 2: "update W ... using Adam"; in the retraining loop followed
+ * by W = W * Mask) ---------------------------------------------------------------------
+ * Adam as published (Kingma & Ba, Algorithm 1) on fp32 master weights W [M,N] with fp32
+ * moments m, v of the same shape, all updated in place; G [M,N] (dtype gdt) is the gradient
+ * of the prediction loss and is only read.  t >= 1 is the step count (bias corrections
+ * 1 - beta^t).  All arithmetic is fp32, one rounding per operation:
+ *   g <- fma(coef, w, g)   if alpha != NULL: the gradient of the regulariser (Eq. 3) with the
+ *                          factors alpha [B,N] fixed, coef as in bsp_penalty_grad (mode, lambda):
+ *                          Adam then minimises the mixed loss of the reweighted-training loop;
+ *   m <- beta1*m + (1-beta1)*g;   v <- beta2*v + ((1-beta2)*g)*g;
+ *   w <- w - (lr*(m/c1)) / (sqrt(v/c2) + eps);
+ *   w <- +0                if keep != NULL and keep[b][j] == 0 (the retraining loop's mask);
+ * the moments of a pruned weight keep evolving (the algorithm masks W only).
+ * B = M/R <= 65535.  Errors: NULL W/G/m/v, bad dtype or mode, M % R != 0, t < 1. */
+int bsp_adam_step(float *W, const void *G, int gdt, float *m, float *v, int64_t M, int64_t N, int32_t R,
+                  const float *alpha, float lambda, int mode, const uint8_t *keep, float lr, float beta1,
+                  float beta2, float eps, int64_t t, void *stream);
+
 /* ---- compact storage (Sec. 3.1: only the kept columns of a block are indexed) ----------
  * Layout.  For block b: cols_b = ascending j with keep[b, j] != 0; k_b = |cols_b| =
  * blk_cnt[b]; kp_b = k_b rounded up to a multiple of k_align (0 stays 0);

@@ -54,6 +54,7 @@ def lib():
     L.bsp_prune_mask_workspace_bytes.argtypes = [i64, i64, C.c_int]
     L.bsp_prune_mask_workspace_bytes.restype = sz
     L.bsp_mask_weights.argtypes = [vp, C.c_int, i64, i64, i32, vp, vp]
+    L.bsp_adam_step.argtypes = [vp, vp, C.c_int, vp, vp, i64, i64, i32, vp, f32, C.c_int, vp, f32, f32, f32, f32, i64, vp]
     L.bsp_group_norms_grad.argtypes = [vp, C.c_int, i64, i64, i32, f32, C.c_int, f32, C.c_int, vp, vp, vp, vp, vp]
     L.bsp_pack_count.argtypes = [vp, i64, i64, i32, vp, vp, vp]
     L.bsp_pack.argtypes = [vp, C.c_int, i64, i64, i32, vp, i32, vp, vp, i64, vp, vp, C.c_int, vp]
@@ -73,7 +74,7 @@ def lib():
     L.bsp_version.restype = C.c_char_p
     for name in ("bsp_group_norms", "bsp_penalty_grad", "bsp_prune_mask", "bsp_pack_count", "bsp_pack",
                  "bsp_packed_validate", "bsp_linear", "bsp_linear_plan", "bsp_linear_planned", "bsp_mask_weights",
-                 "bsp_group_norms_grad"):
+                 "bsp_group_norms_grad", "bsp_adam_step"):
         getattr(L, name).restype = C.c_int
     _LIB = L
     return L
@@ -137,6 +138,22 @@ def bsp_group_norms_grad(W, R, lam, eps=1e-6, mode=ALPHA_SQNORM, sumsq=None, nor
                                     _ptr(grad), _stream())
     _check(st, "bsp_group_norms_grad")
     return sumsq, norm, alpha, grad
+
+
+def bsp_adam_step(W, G, m, v, R, lr, beta1=0.9, beta2=0.999, eps=1e-8, t=1, alpha=None, lam=0.0, mode=ALPHA_SQNORM,
+                  keep=None):
+    """One Adam update of Alg. 2 in place on fp32 W, m, v: optional regulariser gradient (alpha, lam, mode) added
+    to G, optional W = W * Mask (keep)."""
+    M, N = W.shape
+    for x in (W, m, v):
+        if x.dtype != torch.float32 or x.shape != W.shape or not x.is_contiguous():
+            raise ValueError("W, m, v must be contiguous fp32 tensors of one shape")
+    if G.shape != W.shape or not G.is_contiguous():
+        raise ValueError("G must be contiguous and have the shape of W")
+    st = lib().bsp_adam_step(_ptr(W), _ptr(G), _DT[G.dtype], _ptr(m), _ptr(v), M, N, R, _ptr(alpha, torch.float32), lam,
+                             mode, _ptr(keep, torch.uint8), lr, beta1, beta2, eps, t, _stream())
+    _check(st, "bsp_adam_step")
+    return W, m, v
 
 
 def bsp_penalty_grad(W, R, alpha, lam, mode=ALPHA_SQNORM, grad=None, accumulate=False, want_penalty=False, ws=None):

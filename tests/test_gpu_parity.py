@@ -130,6 +130,52 @@ def test_group_norms_grad_one_pass(dtype, R, M, N, mode):
     assert torch.equal(G_sep.view(torch.uint8), G.view(torch.uint8))
 
 
+@pytest.mark.parametrize("gdt", ["f32", "bf16", "f16"])
+@pytest.mark.parametrize("R,M,N", [(16, 64, 512), (8, 32, 264), (5, 20, 77), (64, 128, 1028)])
+def test_adam_step_bit_exact(gdt, R, M, N):
+    """The Adam update of Alg. 2 (plain, on the mixed loss, and followed by W = W * Mask): fp32, one rounding per
+    operation on both sides, so W, m and v agree bit for bit over several steps with the state carried by each side."""
+    B = M // R
+    W0 = wl.normal(11 * R + N, (M, N), 0.05)
+    W0[0:R, 1] = 0.0
+    rng = np.random.default_rng(R * 1000 + N)
+    keep = (rng.random((B, N)) < 0.3).astype(np.uint8)
+    hp = dict(lr=3e-5, beta1=0.9, beta2=0.999, eps=1e-8)
+    lam = 1e-3
+    for mode, use_alpha, use_keep in ((orc.ALPHA_SQNORM, False, False), (orc.ALPHA_SQNORM, True, False),
+                                      (orc.ALPHA_NORM, True, False), (orc.ALPHA_SQNORM, False, True),
+                                      (orc.ALPHA_NORM, True, True)):
+        W, m, v = W0.copy(), np.zeros_like(W0), np.zeros_like(W0)
+        Wd, md, vd = dev(W), dev(m), dev(v)
+        _, alpha = orc.norm_alpha(orc.sumsq(W0, R), 1e-6, mode)
+        ad = dev(alpha) if use_alpha else None
+        kd = torch.from_numpy(keep).cuda() if use_keep else None
+        for t in (1, 2, 3, 1000):
+            G = wl.normal(100 + t, (M, N), 1e-3, gdt)
+            W, m, v = orc.adam_step(W, G, m, v, R, t=t, alpha=alpha if use_alpha else None, lam=lam, mode=mode,
+                                    keep=keep if use_keep else None, **hp)
+            bsp.bsp_adam_step(Wd, dev(G, gdt), md, vd, R, t=t, alpha=ad, lam=lam, mode=mode, keep=kd, **hp)
+            assert bits_equal(host(Wd), W), (mode, use_alpha, use_keep, t)
+            assert bits_equal(host(md), m) and bits_equal(host(vd), v)
+        if use_keep:
+            assert not host(Wd)[~np.repeat(keep, R, axis=0).astype(bool)].any()
+
+
+def test_adam_step_argument_checks():
+    W = torch.zeros(32, 64, device="cuda")
+    L = bsp.lib()
+    args = lambda **k: dict(dict(W=W.data_ptr(), G=W.data_ptr(), gdt=bsp.F32, m=W.data_ptr(), v=W.data_ptr(), M=32, N=64,
+                                 R=16, t=1), **k)
+
+    def call(a):
+        return L.bsp_adam_step(a["W"], a["G"], a["gdt"], a["m"], a["v"], a["M"], a["N"], a["R"], None, 0.0, 0, None,
+                               1e-5, 0.9, 0.999, 1e-8, a["t"], None)
+    assert call(args(W=None)) != 0 and call(args(G=None)) != 0 and call(args(m=None)) != 0 and call(args(v=None)) != 0
+    assert call(args(gdt=7)) != 0 and call(args(R=5)) != 0 and call(args(R=0)) != 0 and call(args(t=0)) != 0
+    torch.cuda.synchronize()
+    assert not W.any()
+
+
 # ------------------------------------------------------------------------------ masks
 def test_mask_threshold_bit_exact_with_ties():
     W = wl.normal(3, (64, 333), 0.02)
