@@ -35,6 +35,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
@@ -516,7 +517,13 @@ constexpr uint32_t kOutStageBytes = 4096;    // per wavefront: 64 token rows x 6
 // kOutElements8 the same for R == 8, whose plan deals the row-blocks in runs of 4.  A template parameter,
 // because the output code is inlined at every slot of the unrolled operand ring: it has to be small, and its
 // constants known.
-enum { kOutElements = 0, kOutStaged = 1, kOutStaged8 = 2, kOutElements8 = 3 };
+// kOutSwap (R == 16 * NFRAG): no staging buffer at all.  A pair of finished 16-row fragments (two row-blocks for
+// R = 16, the two halves of one for R = 32) is rounded to 8 bytes per lane each and re-dealt among the four
+// 16-lane rows of the wavefront with two lane-swap instructions per dword, after which every lane holds 16
+// contiguous bytes of a token's 64-byte run and the wavefront stores 16 token rows x 64 bytes per instruction.
+// The bias of the strip's rows waits in LDS as fp32 (behind the X tile) and is what an accumulator starts from.
+enum { kOutElements = 0, kOutStaged = 1, kOutStaged8 = 2, kOutElements8 = 3, kOutSwap = 4 };
+constexpr uint32_t kBiasTableBytes = 32768;  // at most: 8192 rows of a strip
 template <int DT, int NFRAG, int OUT>
 __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
     const uint16_t *__restrict__ X, int64_t T, int64_t M, int64_t N, int32_t R, int32_t npad,
@@ -525,6 +532,7 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
     int32_t B, int32_t max_step) {
     constexpr int NSUB = 4;
     constexpr bool FAST = OUT == kOutStaged || OUT == kOutStaged8;
+    constexpr bool SWAP = OUT == kOutSwap;
     // row-blocks of a wavefront's run: together 64 bytes per token row
     constexpr int NACC = plan_nacc(NFRAG, false, (OUT == kOutStaged8 || OUT == kOutElements8) ? 8 : 16 * NFRAG);
     constexpr int nacc_shift = NACC == 4 ? 2 : (NACC == 2 ? 1 : 0);
@@ -537,9 +545,19 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
     // The X tile is copied in by the first use (below): a wavefront first requests the operands of its
     // first RING steps, so that they travel while the tile is copied.  Every wavefront passes the barrier once.
     bool staged = false;
+    // kOutSwap: the bias of the strip's rows as fp32, behind the X tile (zeros without a bias and past row M)
+    float *btab = reinterpret_cast<float *>(smem_x + kXTileBytes);
+    const int64_t strip_row0 = (int64_t)g0 * (kPlanWaves * NACC) * R;
     auto stage_once = [&]() {
         if (staged) return;
         stage_x_tile<NSUB>(X, T, N, npad, t0);
+        if constexpr (SWAP) {
+            const int rows = ng * (kPlanWaves * NACC) * R;
+            for (int i = threadIdx.x; i < rows; i += kPlanWaves * 64) {
+                const int64_t r = strip_row0 + i;
+                btab[i] = (bias && r < M) ? elem<DT>::load(bias, r) : 0.0f;
+            }
+        }
         __syncthreads();
         staged = true;
     };
@@ -558,6 +576,31 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
 
     f32x4 acc[NFRAG][NSUB];
     uint32_t bs[NFRAG][8];  // bias of the current block as stored, 16 values per fragment (uniform)
+    // kOutSwap: the rounded fragment of the even row-block of a pair (R = 16) until the odd one is finished; the
+    // bias the next accumulator starts from (read one row-block ahead); the lane's place in a token's 64-byte
+    // run after the swap (row G of the wavefront takes bytes 16 G .. 16 G + 15), relative to the tile's first row
+    uint2 hold[NSUB];
+    f32x4 bnxt[NFRAG];
+    uint32_t yoff[NSUB];
+    bool tok[NSUB];
+    uint8_t *Ytile = reinterpret_cast<uint8_t *>(Y) + t0 * M * 2;
+#pragma unroll
+    for (int u = 0; u < NSUB; ++u) {
+        hold[u] = make_uint2(0u, 0u);
+        yoff[u] = (uint32_t)((16 * u + l16) * M * 2 + 16 * G);
+        tok[u] = t0 + 16 * u + l16 < T;
+    }
+    auto fetch_bias = [&](int64_t b) {  // of row-block b of this strip, from the LDS table
+        const int at = (int)(b * R - strip_row0) + 4 * G;
+#pragma unroll
+        for (int f = 0; f < NFRAG; ++f) bnxt[f] = *reinterpret_cast<const f32x4 *>(btab + at + 16 * f);
+    };
+    auto start_acc = [&]() {
+#pragma unroll
+        for (int f = 0; f < NFRAG; ++f)
+#pragma unroll
+            for (int u = 0; u < NSUB; ++u) acc[f][u] = bnxt[f];
+    };
     uint4 ra[RING][NFRAG];
     uint32_t rx[RING];
     uint4 xb[2][NSUB];  // X fragments of the current step (even / odd ping-pong, resolved by the unrolling)
@@ -590,7 +633,7 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
         for (int f = 0; f < NFRAG; ++f)
 #pragma unroll
             for (int i = 0; i < 8; ++i) bs[f][i] = 0u;  // +0 in both formats
-        if (FAST && bias && b < B) {
+        if (!SWAP && FAST && bias && b < B) {
 #pragma unroll
             for (int f = 0; f < NFRAG; ++f)
 #pragma unroll
@@ -601,7 +644,53 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
     // Output of the finished row-block b (the accumulators hold it).
     auto finish_block = [&](int64_t b) __attribute__((always_inline)) {
         if (b >= B) return;  // uniform
-        if constexpr (FAST) {
+        if constexpr (SWAP) {
+#pragma unroll
+            for (int f = 0; f < NFRAG; f += (NFRAG == 1 ? 1 : 2)) {
+                uint2 lo[NSUB], hi[NSUB];  // the 16-row fragments of output columns c0 .. c0 + 15 and c0 + 16 .. c0 + 31
+                bool lone = false;
+                int64_t c0;
+                if constexpr (NFRAG == 1) {
+                    if ((b & 1) == 0) {  // uniform
+#pragma unroll
+                        for (int u = 0; u < NSUB; ++u) {
+                            hold[u].x = cvt_pk<DT>(acc[0][u][0], acc[0][u][1]);
+                            hold[u].y = cvt_pk<DT>(acc[0][u][2], acc[0][u][3]);
+                        }
+                        if (b + 1 < B) return;
+                        lone = true;  // the last row-block of a layer with an odd number of them leaves alone
+                    }
+                    c0 = (b & ~(int64_t)1) * 16;
+#pragma unroll
+                    for (int u = 0; u < NSUB; ++u) {
+                        lo[u] = hold[u];
+                        hi[u].x = cvt_pk<DT>(acc[0][u][0], acc[0][u][1]);
+                        hi[u].y = cvt_pk<DT>(acc[0][u][2], acc[0][u][3]);
+                    }
+                } else {
+                    c0 = b * R + f * 16;
+#pragma unroll
+                    for (int u = 0; u < NSUB; ++u) {
+                        lo[u].x = cvt_pk<DT>(acc[f][u][0], acc[f][u][1]);
+                        lo[u].y = cvt_pk<DT>(acc[f][u][2], acc[f][u][3]);
+                        hi[u].x = cvt_pk<DT>(acc[f + 1][u][0], acc[f + 1][u][1]);
+                        hi[u].y = cvt_pk<DT>(acc[f + 1][u][2], acc[f + 1][u][3]);
+                    }
+                }
+                uint8_t *dst = Ytile + c0 * 2;  // uniform
+#pragma unroll
+                for (int u = 0; u < NSUB; ++u) {
+                    // rows of 16 lanes, before: lo = [a0 a1 a2 a3], hi = [b0 b1 b2 b3] (a_g = columns 4 g .. 4 g + 3 of
+                    // the first fragment); after the two swaps: first = [a0 a2 b0 b2], second = [a1 a3 b1 b3]
+                    const u32x2 px = __builtin_amdgcn_permlane32_swap(lo[u].x, hi[u].x, false, false);
+                    const u32x2 py = __builtin_amdgcn_permlane32_swap(lo[u].y, hi[u].y, false, false);
+                    const u32x2 qx = __builtin_amdgcn_permlane16_swap(px[0], px[1], false, false);
+                    const u32x2 qy = __builtin_amdgcn_permlane16_swap(py[0], py[1], false, false);
+                    if (tok[u] && !(lone && G >= 2))
+                        *reinterpret_cast<uint4 *>(dst + yoff[u]) = make_uint4(qx[0], qy[0], qx[1], qy[1]);
+                }
+            }
+        } else if constexpr (FAST) {
 #pragma unroll
             for (int f = 0; f < NFRAG; ++f) {
                 // A fragment of this block fills bpf bytes of a token row (32; 16 when R = 8 leaves the upper half
@@ -667,25 +756,10 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
         if (ea >= eb) continue;
         // (the clamps keep a malformed plan from driving the operand pointers out of the buffer)
         const int gs_hi = min(my[eb], max_step);
-        int gs = max(my[ea], 0);
+        int gs = min(max(my[ea], 0), gs_hi);
         int e = ea;                             // current entry, row-block block_of(e)
         int blk_end = min(my[ea + 1], gs_hi);   // first step past the current block
         int nxt_end = my[min(ea + 2, eb)];      // the same for the block after it, fetched one block ahead
-        clear_acc(acc);
-        load_bias(block_of(e));
-        // finished (possibly empty) row-blocks leave as soon as the stream has passed them
-        auto pass_boundaries = [&]() __attribute__((always_inline)) {
-            while (e < eb && blk_end <= gs) {
-                finish_block(block_of(e));
-                clear_acc(acc);
-                ++e;
-                blk_end = e < eb ? min(nxt_end, gs_hi) : 0x7fffffff;
-                nxt_end = my[min(e + 2, eb)];
-                if (e < eb) load_bias(block_of(e));
-            }
-        };
-        pass_boundaries();
-        if (gs >= gs_hi) continue;  // then e == eb: every block of the segment has been written
 
         // Per-lane operand pointers, advanced by a constant per RING steps.  The stream is read up
         // to RING steps past the segment's last step: those loads stay inside the plan buffer (its
@@ -693,6 +767,8 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
         // A fragment is stored as 4 planes of 64 dwords (dword k of every lane's 16 bytes together): a
         // 4-byte-per-lane load moves 256 contiguous bytes, the access width the vector memory
         // pipeline sustains best on this hardware (about 1.6x the bytes per clock of 16-byte loads).
+        // The first RING steps are requested before anything else, so that they travel while the X tile and
+        // the bias are copied in.
         const uint32_t *wp = wfrag + (int64_t)gs * (NFRAG * 256) + lane;
         const uint32_t *xp = xoff + (int64_t)gs * 16 + (lane >> 2);
 #pragma unroll
@@ -700,8 +776,43 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
 #pragma unroll
             for (int f = 0; f < NFRAG; ++f) ra[j][f] = load_frag(wp + (j * NFRAG + f) * 256);
             rx[j] = xp[j * 16];
+            // keep the order of the step loop (fragment, then offsets, slot by slot): the waits the compiler puts
+            // in front of each step count the loads issued after the wanted one on every path into the loop, and
+            // a different order here would make them wait for (nearly) everything
+            __builtin_amdgcn_sched_barrier(0);
         }
         stage_once();
+        if constexpr (SWAP) {
+            fetch_bias(block_of(e));
+            start_acc();
+            fetch_bias(block_of(min(e + 1, eb - 1)));
+        } else {
+            clear_acc(acc);
+            load_bias(block_of(e));
+        }
+        // finished (possibly empty) row-blocks leave as soon as the stream has passed them
+        auto pass_boundaries = [&]() __attribute__((always_inline)) {
+            while (e < eb && blk_end <= gs) {
+                finish_block(block_of(e));
+                ++e;
+                blk_end = e < eb ? min(nxt_end, gs_hi) : 0x7fffffff;
+                nxt_end = my[min(e + 2, eb)];
+                if constexpr (SWAP) {
+                    start_acc();  // with the bias of block e, fetched one block ago
+                    fetch_bias(block_of(min(e + 1, eb - 1)));
+                    // The scalar load above must not stay outstanding into the step loop: scalar loads return out
+                    // of order, and with one in flight every wait for an LDS read becomes a wait for all of them,
+                    // which undoes the one-step lead of the X fragment reads.  It has had the whole block end to
+                    // arrive; take it here.
+                    asm volatile("" : "+s"(nxt_end));
+                } else {
+                    clear_acc(acc);
+                    if (e < eb) load_bias(block_of(e));
+                }
+            }
+        };
+        pass_boundaries();
+        if (gs >= gs_hi) continue;  // then e == eb: every block of the segment has been written
         issue_reads(rx[0], xb[0]);
         bool done = false;
         while (!done) {
@@ -912,7 +1023,9 @@ int launch_planned(const TiledArgs &a, hipStream_t s) {
         if (a.R == 8 && fast) return launch_planned_1024<DT, NFRAG, kOutStaged8>(a, ntiles, NG, max_step, s);
         if (a.R == 8) return launch_planned_1024<DT, NFRAG, kOutElements8>(a, ntiles, NG, max_step, s);
     }
-    if (fast) return launch_planned_1024<DT, NFRAG, kOutStaged>(a, ntiles, NG, max_step, s);
+    // full fragments and 16-byte stores: the lane-swap output path (any bias address: it is read element by element)
+    if (a.R == 16 * NFRAG && (reinterpret_cast<uintptr_t>(a.Y) & 15) == 0)
+        return launch_planned_1024<DT, NFRAG, kOutSwap>(a, ntiles, NG, max_step, s);
     return launch_planned_1024<DT, NFRAG, kOutElements>(a, ntiles, NG, max_step, s);
 }
 
@@ -920,14 +1033,21 @@ template <int DT, int NFRAG, int OUT>
 int launch_planned_1024(const TiledArgs &a, int64_t ntiles, int64_t NG, int64_t max_step, hipStream_t s) {
     static thread_local size_t configured = 0;
     auto kern = linear_tiled_planned_kernel<DT, NFRAG, OUT>;
-    const size_t lds_planned = kXTileBytes + (size_t)kPlanWaves * kOutStageBytes;  // all 160 KiB of a compute unit
-    int st = raise_lds_limit(kern, lds_planned, configured);
-    if (st != BSP_OK) return st;
     int64_t nstrips = (256 + ntiles - 1) / ntiles;  // enough strips to give every compute unit a workgroup
     if (nstrips > NG) nstrips = NG;
     if (nstrips < 1) nstrips = 1;
     int64_t gps = (NG + nstrips - 1) / nstrips;
+    // behind the X tile: the per-wavefront staging buffers, or (lane-swap output) the fp32 bias of a strip's rows
+    size_t lds_planned = kXTileBytes + (size_t)kPlanWaves * kOutStageBytes;  // all 160 KiB of a compute unit
+    if constexpr (OUT == kOutSwap) {
+        const int64_t rows_per_group = (int64_t)kPlanWaves * plan_nacc(NFRAG, false, 16 * NFRAG) * 16 * NFRAG;
+        const int64_t max_gps = kBiasTableBytes / (4 * rows_per_group);  // >= 8
+        if (gps > max_gps) gps = max_gps;
+        lds_planned = kXTileBytes + (size_t)(gps * rows_per_group * 4);
+    }
     nstrips = (NG + gps - 1) / gps;
+    int st = raise_lds_limit(kern, lds_planned, configured);
+    if (st != BSP_OK) return st;
     if (ntiles * nstrips >= ((int64_t)1 << 31)) return BSP_ERR_SHAPE;
     kern<<<dim3((unsigned)(ntiles * nstrips)), dim3(kPlanWaves * 64), lds_planned, s>>>(
         a.X, a.T, a.M, a.N, a.R, a.npad, a.wptr, (const uint32_t *)a.wfrag, a.xoff, a.bias, a.Y, (int32_t)ntiles,

@@ -208,13 +208,14 @@ __device__ __forceinline__ void resolve_digit(const uint32_t *__restrict__ ws, i
 }
 
 // Histogram of digit PASS over the keys that share the digits found so far.
-template <int PASS>
+template <int PASS, int COPIES = 1>
 __global__ __launch_bounds__(kSelThreads) void mask_rank_hist_kernel(const float *__restrict__ s, int64_t n,
                                                                      int64_t per_wg, uint32_t P,
                                                                      uint32_t *__restrict__ ws) {
     // The leading digit (sign, exponent, two mantissa bits) takes only a handful of values, so its LDS
-    // counters are kept in 4 copies picked by the lane: fewer lanes collide on one address.
-    constexpr int COPIES = PASS == 0 ? 4 : 1;
+    // counters are kept in COPIES copies picked by the lane: fewer lanes collide on one address.  (4 copies on
+    // large inputs; 2 on small ones, whose launches are latency-bound anyway and then fit, with 17 KiB of LDS,
+    // beside a workgroup that holds most of a compute unit's LDS.)
     __shared__ uint32_t hist[kBins * COPIES];
     const int G = gridDim.x;
     uint32_t prefix = 0, want = P;
@@ -423,7 +424,10 @@ extern "C" int bsp_prune_mask(const float *sumsq, int64_t B, int64_t N, float t,
         if (ws_bytes < bsp_prune_mask_workspace_bytes(B, N, scope) || !aligned(ws, 4)) return BSP_ERR_CAPACITY;
         int64_t per_wg = (n + G - 1) / G;
         per_wg = (per_wg + 3) / 4 * 4;
-        mask_rank_hist_kernel<0><<<G, kSelThreads, 0, s>>>(sumsq, n, per_wg, (uint32_t)P, w);
+        if (n > ((int64_t)1 << 21))
+            mask_rank_hist_kernel<0, 4><<<G, kSelThreads, 0, s>>>(sumsq, n, per_wg, (uint32_t)P, w);
+        else
+            mask_rank_hist_kernel<0, 2><<<G, kSelThreads, 0, s>>>(sumsq, n, per_wg, (uint32_t)P, w);
         mask_rank_hist_kernel<1><<<G, kSelThreads, 0, s>>>(sumsq, n, per_wg, (uint32_t)P, w);
         mask_rank_hist_kernel<2><<<G, kSelThreads, 0, s>>>(sumsq, n, per_wg, (uint32_t)P, w);
     }

@@ -81,6 +81,9 @@ constexpr int kPackThreads = 1024;  // 16 wavefronts
 constexpr int kPackWaves = kPackThreads / kWave;
 constexpr int kPackMaxCols = 16384;  // widest layer for this kernel: the kept-column list is 16-bit in LDS
 
+__host__ __device__ inline size_t pack_lds_counts_bytes(int64_t N) { return (size_t)(((N + kWave - 1) / kWave + 1 + 3) / 4 * 4) * 4; }
+inline size_t pack_lds_bytes(int64_t N) { return pack_lds_counts_bytes(N) + (size_t)((N + 7) / 8 * 8) * 2; }
+
 template <int WDT, int VDT>
 __global__ __launch_bounds__(kPackThreads) void pack_positions_kernel(const void *__restrict__ W, int64_t N, int32_t R,
                                                                       const uint8_t *__restrict__ keep,
@@ -88,8 +91,12 @@ __global__ __launch_bounds__(kPackThreads) void pack_positions_kernel(const void
                                                                       const int32_t *__restrict__ blk_ptr,
                                                                       int64_t capacity_cols, int32_t *__restrict__ col_idx,
                                                                       void *__restrict__ vals) {
-    __shared__ int chunk_off[kPackMaxCols / kWave + 1];
-    __shared__ uint16_t s_cols[kPackMaxCols];
+    // LDS sized by the launch for this layer's width (the counts of the 64-column chunks, then the kept-column
+    // list): a narrow layer then leaves room for this kernel beside a workgroup that holds most of a compute
+    // unit's LDS
+    extern __shared__ __attribute__((aligned(16))) uint8_t pack_lds[];
+    int *chunk_off = reinterpret_cast<int *>(pack_lds);
+    uint16_t *s_cols = reinterpret_cast<uint16_t *>(pack_lds + pack_lds_counts_bytes(N));
     const int64_t b = blockIdx.x;
     const int64_t base = blk_ptr[b];
     const int kp = blk_ptr[b + 1] - blk_ptr[b];
@@ -312,7 +319,7 @@ extern "C" int bsp_pack(const void *W, int wdt, int64_t M, int64_t N, int32_t R,
     BSP_DISPATCH_DTYPE(wdt, WDT, {
         BSP_DISPATCH_DTYPE(vdt, VDT, {
             if (N <= kPackMaxCols)
-                pack_positions_kernel<WDT, VDT><<<dim3((unsigned)B, split), kPackThreads, 0, s>>>(
+                pack_positions_kernel<WDT, VDT><<<dim3((unsigned)B, split), kPackThreads, pack_lds_bytes(N), s>>>(
                     W, N, R, keep, blk_cnt, blk_ptr, capacity_cols, col_idx, vals);
             else
                 pack_kernel<WDT, VDT><<<dim3((unsigned)B, split), kPackThreads, 0, s>>>(W, N, R, keep, blk_cnt, blk_ptr,
