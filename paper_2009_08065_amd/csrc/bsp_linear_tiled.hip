@@ -861,7 +861,6 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_chunked_kernel(
     constexpr int NACC = plan_nacc(NFRAG, true, 16 * NFRAG);  // 4 / NFRAG; R = 8 (NFRAG = 1) has 4 too
     constexpr int RING = kPlanRing / NFRAG;
     static_assert(RING % 2 == 0, "the X fragment ping-pong needs an even ring");
-    __shared__ __attribute__((aligned(16))) uint8_t s_out[kPlanWaves][16 * kOutPitch];
     const int tile = blockIdx.x % ntiles, g = blockIdx.x / ntiles;
     const int64_t t0 = (int64_t)tile * (16 * NSUB);
     const int lane = threadIdx.x & 63;
@@ -948,9 +947,13 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_chunked_kernel(
         }
     }
 
+    // The output staging of a wavefront (16 rows of kOutPitch bytes) takes the place of the X chunk once every
+    // wavefront is done with it: the kernel then holds 128 KiB of LDS and leaves the rest of the compute unit's
+    // to small kernels of other streams.
+    __syncthreads();
     typedef QuadEpilogue<DT, NFRAG, NSUB, NACC> Ep;
     Ep ep;
-    ep.init(Y, bias, T, M, R, B, t0, lane, s_out[wave], fast_store != 0);
+    ep.init(Y, bias, T, M, R, B, t0, lane, smem_x + wave * (16 * kOutPitch), fast_store != 0);
     const int64_t b0 = ((int64_t)g * kPlanWaves + wave) * NACC;
     if (b0 < B) {
         typename Ep::Packed out;
@@ -1004,7 +1007,10 @@ int launch_planned(const TiledArgs &a, hipStream_t s) {
     const int64_t ntiles = (a.T + 63) / 64;
     const int64_t NG = (a.B + kPlanWaves * NACC - 1) / (kPlanWaves * NACC);
     // the staged store path: full fragments, and a bias that can be read in 4-byte words
-    const int32_t fast = ((a.R == 16 * NFRAG || a.R == 8) && (reinterpret_cast<uintptr_t>(a.bias) & 3) == 0) ? 1 : 0;
+    const int32_t fast = ((a.R == 16 * NFRAG || a.R == 8) && (reinterpret_cast<uintptr_t>(a.bias) & 3) == 0 &&
+                          (reinterpret_cast<uintptr_t>(a.Y) & 15) == 0)
+                             ? 1
+                             : 0;
     const int64_t max_step = a.plan_steps - plan_slack_steps();
     if (max_step < 0 || max_step > INT32_MAX) return BSP_ERR_CAPACITY;
     if (a.npad > 1024) {

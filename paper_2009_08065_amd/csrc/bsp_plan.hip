@@ -128,16 +128,18 @@ __global__ __launch_bounds__(kThreads) void plan_fill_kernel(int32_t R, int32_t 
                                                              const int32_t *__restrict__ col_idx,
                                                              const uint16_t *__restrict__ vals, int64_t capacity_cols,
                                                              int64_t cap_steps, const int32_t *__restrict__ wptr,
-                                                             uint32_t *__restrict__ wfrag, uint32_t *__restrict__ xoff) {
-    // columns and canonical positions are below 4096 + 32: 16 bits each; 0xffff marks a pad
-    __shared__ uint16_t cols[kMaxKp];
+                                                             uint32_t *__restrict__ wfrag, uint32_t *__restrict__ xoff,
+                                                             int32_t cols_cap) {
+    // columns and canonical positions are below 4096 + 32: 16 bits each; 0xffff marks a pad.  The list of a
+    // row-block's kept columns is sized by the launch for the layer's width (cols_cap entries).
+    extern __shared__ __attribute__((aligned(16))) uint16_t cols[];
     __shared__ uint16_t slotcol[kMaxChunk], slotsrc[kMaxChunk], ovfcol[kMaxChunk], ovfsrc[kMaxChunk];
     __shared__ int s_filled[8], s_hp[9], s_novf, s_cnt[kPlanMaxChunks];
     const int64_t b = blockIdx.x;
     const int base = blk_ptr[b];
     const int kp = blk_ptr[b + 1] - base;
     const int kb = blk_cnt[b];
-    if (kp <= 0 || kp > kMaxKp || kb > kp || kb < 0 || base < 0 || (int64_t)base + kp > capacity_cols) return;
+    if (kp <= 0 || kp > cols_cap || kb > kp || kb < 0 || base < 0 || (int64_t)base + kp > capacity_cols) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l16 = lane & 15, G = lane >> 4, qd = (lane >> 2) & 3, p = lane & 3;
     // the block's kept columns, fetched once with coalesced loads, and their count per chunk
@@ -319,10 +321,13 @@ extern "C" int bsp_linear_plan(int vdt, int64_t M, int64_t N, int32_t R, int32_t
     plan_scan_kernel<<<1, kPlanWaves * 64, 0, s>>>(ch.n > 1 ? steps_bq : nullptr, blk_cnt, blk_ptr, capacity_cols,
                                                    (int32_t)B, (int32_t)L.NG, nacc, ch.n, (int64_t)L.steps,
                                                    plan_slack_steps(), wptr, xoff);
-    if (capacity_cols > 0)
-        plan_fill_kernel<<<dim3((unsigned)B, (unsigned)ch.n), kThreads, 0, s>>>(R, nf, (int32_t)L.NG, nacc, ch.shift, ch.n, blk_cnt, blk_ptr,
-                                                          col_idx, (const uint16_t *)vals, capacity_cols,
-                                                          (int64_t)L.steps, wptr, wfrag, xoff);
+    if (capacity_cols > 0) {
+        // a row-block keeps at most N columns, padded to the alignment (at most 64)
+        const int32_t cols_cap = (int32_t)(N + 64 < kMaxKp ? (N + 64 + 7) / 8 * 8 : kMaxKp);
+        plan_fill_kernel<<<dim3((unsigned)B, (unsigned)ch.n), kThreads, (size_t)cols_cap * 2, s>>>(
+            R, nf, (int32_t)L.NG, nacc, ch.shift, ch.n, blk_cnt, blk_ptr, col_idx, (const uint16_t *)vals, capacity_cols,
+            (int64_t)L.steps, wptr, wfrag, xoff, cols_cap);
+    }
     return check_launch();
 }
 
