@@ -174,7 +174,9 @@ int bsp_linear(const void *X, int xdt, int64_t T, int64_t M, int64_t N, int32_t 
  * 32 <= N <= 4096, N % 8 == 0, k_align % 32 == 0), else 0; the other calls return
  * BSP_ERR_SHAPE for an unsupported layer and the caller stays with bsp_linear.
  * plan: device buffer of at least bsp_linear_plan_bytes(M, R, capacity_cols) bytes, 16-byte
- * aligned, where capacity_cols >= blk_ptr[B] is the same value in all three calls. */
+ * aligned, where capacity_cols >= blk_ptr[B] is the same value in all three calls.
+ * bsp_linear_planned wants X and Y 16-byte aligned too (BSP_ERR_SHAPE otherwise; bias: any
+ * address). */
 int bsp_linear_plan_supported(int xdt, int64_t N, int32_t k_align);
 size_t bsp_linear_plan_bytes(int64_t M, int32_t R, int64_t capacity_cols);
 int bsp_linear_plan(int vdt, int64_t M, int64_t N, int32_t R, int32_t k_align, const int32_t *blk_cnt,

@@ -502,27 +502,24 @@ __device__ __forceinline__ void clear_quad(f32x4 (&acc)[NACC][NFRAG][NSUB]) {
 // walks the groups of its strip.
 //
 // Output path.  The MFMA result layout gives a lane 4 consecutive output columns of one token, so a
-// store straight from the accumulators touches 16 token rows with 32 bytes each.  Instead a finished
-// 16-row fragment is rounded (bias added) and parked in a per-wavefront LDS buffer of 64 token rows x
-// 64 bytes; every second fragment (two row-blocks for R = 16, one for R = 32, half a one for R = 64)
-// the buffer holds 32 consecutive output columns of all 64 tokens and is written with 16-byte lanes,
-// 64 contiguous bytes per token row.  The LDS operations of a wavefront complete in order, so the
-// buffer needs no barrier.  (In the read, row = 16 i + lane / 4, so row / 4 % 4 is the lane's G.)
+// store straight from the accumulators touches 16 token rows with 32 bytes each.  OUT says how the output
+// leaves instead.  A template parameter, because the output code is inlined at every slot of the unrolled
+// operand ring: it has to be small, and its constants known.
+// kOutSwap (R == 16 * NFRAG): a pair of finished 16-row fragments (two row-blocks for R = 16, the two halves of
+// one for R = 32) is rounded to 8 bytes per lane each and re-dealt among the four 16-lane rows of the wavefront
+// with two lane-swap instructions per dword, after which every lane holds 16 contiguous bytes of a token's
+// 64-byte run and the wavefront stores 16 token rows x 64 bytes per instruction.  The bias of the strip's rows
+// waits in LDS as fp32 (behind the X tile) and is what an accumulator starts from.
+// kOutStaged8 (R == 8, NFRAG = 1, half fragments of 16 bytes, runs of 4 row-blocks): a finished fragment is
+// rounded (bias added) and parked in a per-wavefront LDS buffer of 64 token rows x 64 bytes; once the buffer holds
+// 32 consecutive output columns of all 64 tokens it is written with 16-byte lanes, 64 contiguous bytes per token
+// row.  The LDS operations of a wavefront complete in order, so the buffer needs no barrier.  (In the read,
+// row = 16 i + lane / 4, so row / 4 % 4 is the lane's G.)
+// kOutElements: any other R (or an output that cannot be written in 16-byte pieces), outputs stored one by one,
+// and kOutElements8 the same for R == 8, whose plan deals the row-blocks in runs of 4.
 constexpr uint32_t kXTileBytes = 4 * 32768;  // 64 tokens x 1024 columns
 constexpr uint32_t kOutStageBytes = 4096;    // per wavefront: 64 token rows x 64 bytes
-
-// OUT: how the output leaves.  kOutStaged: R == 16 * NFRAG, full fragments of 32 bytes per token row through the
-// staging buffer; kOutStaged8: R == 8 (NFRAG = 1), half fragments of 16 bytes, runs of 4 row-blocks;
-// kOutElements: any other R (or a bias that cannot be read in words), outputs stored one by one, and
-// kOutElements8 the same for R == 8, whose plan deals the row-blocks in runs of 4.  A template parameter,
-// because the output code is inlined at every slot of the unrolled operand ring: it has to be small, and its
-// constants known.
-// kOutSwap (R == 16 * NFRAG): no staging buffer at all.  A pair of finished 16-row fragments (two row-blocks for
-// R = 16, the two halves of one for R = 32) is rounded to 8 bytes per lane each and re-dealt among the four
-// 16-lane rows of the wavefront with two lane-swap instructions per dword, after which every lane holds 16
-// contiguous bytes of a token's 64-byte run and the wavefront stores 16 token rows x 64 bytes per instruction.
-// The bias of the strip's rows waits in LDS as fp32 (behind the X tile) and is what an accumulator starts from.
-enum { kOutElements = 0, kOutStaged = 1, kOutStaged8 = 2, kOutElements8 = 3, kOutSwap = 4 };
+enum { kOutElements = 0, kOutStaged8 = 2, kOutElements8 = 3, kOutSwap = 4 };
 constexpr uint32_t kBiasTableBytes = 32768;  // at most: 8192 rows of a strip
 template <int DT, int NFRAG, int OUT>
 __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
@@ -531,7 +528,7 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
     const void *__restrict__ bias, void *__restrict__ Y, int32_t ntiles, int32_t groups_per_strip, int32_t NG,
     int32_t B, int32_t max_step) {
     constexpr int NSUB = 4;
-    constexpr bool FAST = OUT == kOutStaged || OUT == kOutStaged8;
+    constexpr bool FAST = OUT == kOutStaged8;
     constexpr bool SWAP = OUT == kOutSwap;
     // row-blocks of a wavefront's run: together 64 bytes per token row
     constexpr int NACC = plan_nacc(NFRAG, false, (OUT == kOutStaged8 || OUT == kOutElements8) ? 8 : 16 * NFRAG);

@@ -375,6 +375,14 @@ def test_linear_planned_bias_at_odd_address(R):
     Y_ref, _ = orc.linear_packed(d["X"], p_ref, d["bias"], ydt=CODE["bf16"], n_threads=8)
     assert_y_close(host(bsp.bsp_linear_planned(Xd, p, bsp.bsp_linear_plan(p), bias_odd)), Y_ref, "bf16")
     assert_y_close(host(bsp.bsp_linear(Xd, p, bias_odd)), Y_ref, "bf16")
+    # an output that does not start on a 16-byte boundary is refused (and left untouched)
+    ybuf = torch.full((T * M + 1,), 7.0, dtype=torch.bfloat16, device="cuda")
+    Y_odd = ybuf[1:].view(T, M)
+    assert Y_odd.data_ptr() % 16 == 2
+    with pytest.raises(bsp.BspError):
+        bsp.bsp_linear_planned(Xd, p, bsp.bsp_linear_plan(p), bias_odd, Y=Y_odd)
+    torch.cuda.synchronize()
+    assert torch.all(ybuf == 7.0)
 
 
 def test_linear_wide_layer_many_tokens_ragged_strips():
