@@ -521,8 +521,8 @@ constexpr uint32_t kXTileBytes = 4 * 32768;  // 64 tokens x 1024 columns
 constexpr uint32_t kOutStageBytes = 4096;    // per wavefront: 64 token rows x 64 bytes
 enum { kOutElements = 0, kOutStaged8 = 2, kOutElements8 = 3, kOutSwap = 4 };
 constexpr uint32_t kBiasTableBytes = 32768;  // at most: 8192 rows of a strip
-template <int DT, int NFRAG, int OUT>
-__global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
+template <int DT, int NFRAG, int OUT, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void linear_tiled_planned_kernel(
     const uint16_t *__restrict__ X, int64_t T, int64_t M, int64_t N, int32_t R, int32_t npad,
     const int32_t *__restrict__ wptr, const uint32_t *__restrict__ wfrag, const uint32_t *__restrict__ xoff,
     const void *__restrict__ bias, void *__restrict__ Y, int32_t ntiles, int32_t groups_per_strip, int32_t NG,
@@ -533,7 +533,8 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
     // row-blocks of a wavefront's run: together 64 bytes per token row
     constexpr int NACC = plan_nacc(NFRAG, false, (OUT == kOutStaged8 || OUT == kOutElements8) ? 8 : 16 * NFRAG);
     constexpr int nacc_shift = NACC == 4 ? 2 : (NACC == 2 ? 1 : 0);
-    constexpr int RING = kPlanRing / NFRAG;        // the same bytes in flight for every fragment count
+    // the same bytes in flight for every fragment count; half of them with 16 wavefronts (registers), no less than 2 steps
+    constexpr int RING = WAVES == kPlanWavesWide ? (4 / NFRAG < 2 ? 2 : 4 / NFRAG) : kPlanRing / NFRAG;
     static_assert(RING % 2 == 0, "the X fragment ping-pong needs an even ring");
     const int tile = blockIdx.x % ntiles, strip = blockIdx.x / ntiles;
     const int64_t t0 = (int64_t)tile * (16 * NSUB);
@@ -544,13 +545,13 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
     bool staged = false;
     // kOutSwap: the bias of the strip's rows as fp32, behind the X tile (zeros without a bias and past row M)
     float *btab = reinterpret_cast<float *>(smem_x + kXTileBytes);
-    const int64_t strip_row0 = (int64_t)g0 * (kPlanWaves * NACC) * R;
+    const int64_t strip_row0 = (int64_t)g0 * (WAVES * NACC) * R;
     auto stage_once = [&]() {
         if (staged) return;
         stage_x_tile<NSUB>(X, T, N, npad, t0);
         if constexpr (SWAP) {
-            const int rows = ng * (kPlanWaves * NACC) * R;
-            for (int i = threadIdx.x; i < rows; i += kPlanWaves * 64) {
+            const int rows = ng * (WAVES * NACC) * R;
+            for (int i = threadIdx.x; i < rows; i += WAVES * 64) {
                 const int64_t r = strip_row0 + i;
                 btab[i] = (bias && r < M) ? elem<DT>::load(bias, r) : 0.0f;
             }
@@ -614,7 +615,7 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_planned_kernel(
     };
     auto load_frag = [&](const uint32_t *q) { return make_uint4(q[0], q[64], q[128], q[192]); };
     auto block_of = [&](int e) {
-        return ((((int64_t)(g0 + (e >> nacc_shift)) * kPlanWaves + wave)) << nacc_shift) + (e & (NACC - 1));
+        return ((((int64_t)(g0 + (e >> nacc_shift)) * WAVES + wave)) << nacc_shift) + (e & (NACC - 1));
     };
     auto widen = [](uint32_t h) {
         if constexpr (DT == BSP_BF16) return __uint_as_float(h << 16);
@@ -994,7 +995,7 @@ int launch_canonical(const TiledArgs &a, int waves, hipStream_t s) {
     return check_launch();
 }
 
-template <int DT, int NFRAG, int OUT>
+template <int DT, int NFRAG, int OUT, int WAVES>
 int launch_planned_1024(const TiledArgs &a, int64_t ntiles, int64_t NG, int64_t max_step, hipStream_t s);
 
 template <int DT, int NFRAG>
@@ -1002,7 +1003,8 @@ int launch_planned(const TiledArgs &a, hipStream_t s) {
     const int NACC = plan_nacc(NFRAG, a.npad > 1024, a.R);
     const size_t lds = 4 * (size_t)sub_stride<4>();  // 64 tokens x 1024 columns
     const int64_t ntiles = (a.T + 63) / 64;
-    const int64_t NG = (a.B + kPlanWaves * NACC - 1) / (kPlanWaves * NACC);
+    const int waves = plan_waves(a.N, a.R);  // as the plan was built
+    const int64_t NG = (a.B + waves * NACC - 1) / (waves * NACC);
     // the staged store path: full fragments, and a bias that can be read in 4-byte words
     const int32_t fast = ((a.R == 16 * NFRAG || a.R == 8) && (reinterpret_cast<uintptr_t>(a.bias) & 3) == 0 &&
                           (reinterpret_cast<uintptr_t>(a.Y) & 15) == 0)
@@ -1023,27 +1025,31 @@ int launch_planned(const TiledArgs &a, hipStream_t s) {
         return check_launch();
     }
     if constexpr (NFRAG == 1) {
-        if (a.R == 8 && fast) return launch_planned_1024<DT, NFRAG, kOutStaged8>(a, ntiles, NG, max_step, s);
-        if (a.R == 8) return launch_planned_1024<DT, NFRAG, kOutElements8>(a, ntiles, NG, max_step, s);
+        if (a.R == 8 && fast) return launch_planned_1024<DT, NFRAG, kOutStaged8, kPlanWaves>(a, ntiles, NG, max_step, s);
+        if (a.R == 8) return launch_planned_1024<DT, NFRAG, kOutElements8, kPlanWaves>(a, ntiles, NG, max_step, s);
     }
     // full fragments and 16-byte stores: the lane-swap output path (any bias address: it is read element by element)
-    if (a.R == 16 * NFRAG && (reinterpret_cast<uintptr_t>(a.Y) & 15) == 0)
-        return launch_planned_1024<DT, NFRAG, kOutSwap>(a, ntiles, NG, max_step, s);
-    return launch_planned_1024<DT, NFRAG, kOutElements>(a, ntiles, NG, max_step, s);
+    if (a.R == 16 * NFRAG && (reinterpret_cast<uintptr_t>(a.Y) & 15) == 0) {
+        // R = 16 and 32: 16 wavefronts (the plan has 16 streams); R = 64: 8
+        constexpr int WAVES = NFRAG <= 2 ? kPlanWavesWide : kPlanWaves;
+        if (waves == WAVES) return launch_planned_1024<DT, NFRAG, kOutSwap, WAVES>(a, ntiles, NG, max_step, s);
+    }
+    if (waves != kPlanWaves) return BSP_ERR_SHAPE;  // (a plan of 16 streams is only consumed by the path above)
+    return launch_planned_1024<DT, NFRAG, kOutElements, kPlanWaves>(a, ntiles, NG, max_step, s);
 }
 
-template <int DT, int NFRAG, int OUT>
+template <int DT, int NFRAG, int OUT, int WAVES>
 int launch_planned_1024(const TiledArgs &a, int64_t ntiles, int64_t NG, int64_t max_step, hipStream_t s) {
     static thread_local size_t configured = 0;
-    auto kern = linear_tiled_planned_kernel<DT, NFRAG, OUT>;
+    auto kern = linear_tiled_planned_kernel<DT, NFRAG, OUT, WAVES>;
     int64_t nstrips = (256 + ntiles - 1) / ntiles;  // enough strips to give every compute unit a workgroup
     if (nstrips > NG) nstrips = NG;
     if (nstrips < 1) nstrips = 1;
     int64_t gps = (NG + nstrips - 1) / nstrips;
     // behind the X tile: the per-wavefront staging buffers, or (lane-swap output) the fp32 bias of a strip's rows
-    size_t lds_planned = kXTileBytes + (size_t)kPlanWaves * kOutStageBytes;  // all 160 KiB of a compute unit
+    size_t lds_planned = kXTileBytes + (size_t)WAVES * kOutStageBytes;  // all 160 KiB of a compute unit
     if constexpr (OUT == kOutSwap) {
-        const int64_t rows_per_group = (int64_t)kPlanWaves * plan_nacc(NFRAG, false, 16 * NFRAG) * 16 * NFRAG;
+        const int64_t rows_per_group = (int64_t)WAVES * plan_nacc(NFRAG, false, 16 * NFRAG) * 16 * NFRAG;
         const int64_t max_gps = kBiasTableBytes / (4 * rows_per_group);  // >= 8
         if (gps > max_gps) gps = max_gps;
         lds_planned = kXTileBytes + (size_t)(gps * rows_per_group * 4);
@@ -1052,7 +1058,7 @@ int launch_planned_1024(const TiledArgs &a, int64_t ntiles, int64_t NG, int64_t 
     int st = raise_lds_limit(kern, lds_planned, configured);
     if (st != BSP_OK) return st;
     if (ntiles * nstrips >= ((int64_t)1 << 31)) return BSP_ERR_SHAPE;
-    kern<<<dim3((unsigned)(ntiles * nstrips)), dim3(kPlanWaves * 64), lds_planned, s>>>(
+    kern<<<dim3((unsigned)(ntiles * nstrips)), dim3(WAVES * 64), lds_planned, s>>>(
         a.X, a.T, a.M, a.N, a.R, a.npad, a.wptr, (const uint32_t *)a.wfrag, a.xoff, a.bias, a.Y, (int32_t)ntiles,
         (int32_t)gps, (int32_t)NG, (int32_t)a.B, (int32_t)max_step);
     return check_launch();

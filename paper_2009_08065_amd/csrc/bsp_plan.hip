@@ -10,13 +10,13 @@
 // byte offsets of the lane's transposing reads.
 //
 // Order of the steps: a wavefront of the layer kernel owns "quads" of nacc = 4 / nfrag consecutive
-// row-blocks (quad w of every group of kPlanWaves quads), so the plan keeps the steps of wavefront w
+// row-blocks (quad w of every group of `waves` quads), so the plan keeps the steps of wavefront w
 // contiguous, stream after stream, in the order it walks them: chunk by chunk (layers of more than
 // 1024 input columns are cut into chunks of 1024), group by group, block by block.
-// wptr[w][(q * NG + g) * nacc + i] is the step where block (g * kPlanWaves + w) * nacc + i starts in
+// wptr[w][(q * NG + g) * nacc + i] is the step where block (g * waves + w) * nacc + i starts in
 // chunk q; the last entry of a row is where stream w ends.
 //
-// Buffer layout (bytes): wptr int32 [kPlanWaves][4 * NG * nacc + 1], padded to 256 | fragments
+// Buffer layout (bytes): wptr int32 [waves][chunks * NG * nacc + 1], padded to 256 | fragments
 // [steps][nfrag][4][64] dwords (dword k of every lane's 16-byte fragment lies in plane k, so that
 // 4-byte-per-lane loads are contiguous) | offsets uint32 [steps][16] (one word per 4 lanes: the lanes
 // of a column differ by their token quad only), with steps = capacity_cols / 32
@@ -61,10 +61,10 @@ __global__ __launch_bounds__(kThreads) void plan_count_kernel(const int32_t *__r
     if (threadIdx.x < kPlanMaxChunks) steps_bq[b * kPlanMaxChunks + threadIdx.x] = (cnt[threadIdx.x] + 31) >> 5;
 }
 
-// One workgroup of kPlanWaves wavefronts: wavefront w scans the step counts of its blocks in
+// One workgroup with a wavefront per stream of the plan: wavefront w scans the step counts of its blocks in
 // stream order (chunk-major: all its blocks' steps of chunk 0, then chunk 1, ...).
 // steps_bq == nullptr (layers of one chunk): the count is ceil(blk_cnt / 32), taken from the storage itself.
-__global__ __launch_bounds__(kPlanWaves * 64) void plan_scan_kernel(const int32_t *__restrict__ steps_bq,
+__global__ __launch_bounds__(kPlanWavesWide * 64) void plan_scan_kernel(const int32_t *__restrict__ steps_bq,
                                                                     const int32_t *__restrict__ blk_cnt,
                                                                     const int32_t *__restrict__ blk_ptr,
                                                                     int64_t capacity_cols, int32_t B,
@@ -72,7 +72,8 @@ __global__ __launch_bounds__(kPlanWaves * 64) void plan_scan_kernel(const int32_
                                                                     int64_t cap_steps,
                                                                     int32_t slack_steps, int32_t *__restrict__ wptr,
                                                                     uint32_t *__restrict__ xoff) {
-    __shared__ int totals[kPlanWaves];
+    __shared__ int totals[kPlanWavesWide];
+    const int waves = blockDim.x >> 6;  // streams of this plan
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int per_chunk = NG * nacc;
     const int E = nchunks * per_chunk;  // entries of a stream: (chunk q, group g, block i of the quad)
@@ -81,7 +82,7 @@ __global__ __launch_bounds__(kPlanWaves * 64) void plan_scan_kernel(const int32_
     for (int ebase = 0; ebase < E; ebase += 64) {
         const int e = ebase + lane;
         const int q = e / per_chunk, gi = e % per_chunk;
-        const int64_t b = ((int64_t)(gi / nacc) * kPlanWaves + w) * nacc + gi % nacc;
+        const int64_t b = ((int64_t)(gi / nacc) * waves + w) * nacc + gi % nacc;
         int st = 0;
         if (e < E && b < B) {
             if (steps_bq) {
@@ -113,7 +114,7 @@ __global__ __launch_bounds__(kPlanWaves * 64) void plan_scan_kernel(const int32_
     for (int e = lane; e <= E; e += 64) mine[e] += wbase;
     // the layer kernel reads a few steps past the end of the last stream: give those steps the
     // LDS offset 0 (their values are never used, but the addresses must be valid)
-    if (w == kPlanWaves - 1) {
+    if (w == waves - 1) {
         const int64_t total = (int64_t)wbase + carry;
         if (total + slack_steps <= cap_steps)
             for (int i = lane; i < slack_steps * 16; i += 64) xoff[total * 16 + i] = 0u;
@@ -129,7 +130,7 @@ __global__ __launch_bounds__(kThreads) void plan_fill_kernel(int32_t R, int32_t 
                                                              const uint16_t *__restrict__ vals, int64_t capacity_cols,
                                                              int64_t cap_steps, const int32_t *__restrict__ wptr,
                                                              uint32_t *__restrict__ wfrag, uint32_t *__restrict__ xoff,
-                                                             int32_t cols_cap) {
+                                                             int32_t cols_cap, int32_t waves) {
     // columns and canonical positions are below 4096 + 32: 16 bits each; 0xffff marks a pad.  The list of a
     // row-block's kept columns is sized by the launch for the layer's width (cols_cap entries).
     extern __shared__ __attribute__((aligned(16))) uint16_t cols[];
@@ -225,8 +226,8 @@ __global__ __launch_bounds__(kThreads) void plan_fill_kernel(int32_t R, int32_t 
         __syncthreads();
         // per-lane operands of the chunk's steps
         const int E = nchunks * NG * nacc;
-        const int64_t quad = b / nacc;  // quad `quad % kPlanWaves` of group `quad / kPlanWaves`
-        const int64_t gs0 = wptr[(quad % kPlanWaves) * (E + 1) + ((int64_t)q * NG + quad / kPlanWaves) * nacc + b % nacc];
+        const int64_t quad = b / nacc;  // quad `quad % waves` of group `quad / waves`
+        const int64_t gs0 = wptr[(quad % waves) * (E + 1) + ((int64_t)q * NG + quad / waves) * nacc + b % nacc];
         if (gs0 < 0 || gs0 + nsteps > cap_steps) return;
         for (int s = wave; s < nsteps; s += kThreads / 64) {
             const int s1 = 32 * s + 8 * G + qd;
@@ -268,10 +269,11 @@ struct PlanLayout {
 inline PlanLayout plan_layout(int64_t M, int64_t N, int32_t R, int64_t capacity_cols) {
     PlanLayout L;
     const int64_t B = M / R;
-    const int64_t per_group = (int64_t)kPlanWaves * plan_nacc(nfrag_of(R), plan_chunks(N).n > 1, R);
+    const int64_t per_group = (int64_t)plan_waves(N, R) * plan_nacc(nfrag_of(R), plan_chunks(N).n > 1, R);
     L.NG = (B + per_group - 1) / per_group;
     L.steps = (size_t)((capacity_cols + 31) / 32) + (size_t)B * (kPlanMaxChunks - 1) + (size_t)plan_slack_steps();
-    // entries per stream <= chunks * (blocks rounded up to whole groups) / kPlanWaves, groups of at most 32 blocks
+    // entries per stream <= chunks * (blocks rounded up to whole groups) / streams, groups of at most 32 blocks
+    // (16 streams of a one-chunk layer need less than the 8 streams of a chunked one)
     L.wptr_bytes = ((size_t)kPlanWaves * (size_t)(kPlanMaxChunks * ((B + 31) / 32 * 4) + 1) * sizeof(int32_t) + 255) /
                    256 * 256;
     L.wfrag_bytes = L.steps * (size_t)nfrag_of(R) * 1024;
@@ -318,7 +320,8 @@ extern "C" int bsp_linear_plan(int vdt, int64_t M, int64_t N, int32_t R, int32_t
         plan_count_kernel<<<(unsigned)B, kThreads, 0, s>>>(blk_cnt, blk_ptr, col_idx, capacity_cols, ch.shift, ch.n,
                                                            steps_bq);
     const int32_t nacc = plan_nacc(nf, ch.n > 1, R);
-    plan_scan_kernel<<<1, kPlanWaves * 64, 0, s>>>(ch.n > 1 ? steps_bq : nullptr, blk_cnt, blk_ptr, capacity_cols,
+    const int waves = plan_waves(N, R);
+    plan_scan_kernel<<<1, waves * 64, 0, s>>>(ch.n > 1 ? steps_bq : nullptr, blk_cnt, blk_ptr, capacity_cols,
                                                    (int32_t)B, (int32_t)L.NG, nacc, ch.n, (int64_t)L.steps,
                                                    plan_slack_steps(), wptr, xoff);
     if (capacity_cols > 0) {
@@ -326,7 +329,7 @@ extern "C" int bsp_linear_plan(int vdt, int64_t M, int64_t N, int32_t R, int32_t
         const int32_t cols_cap = (int32_t)(N + 64 < kMaxKp ? (N + 64 + 7) / 8 * 8 : kMaxKp);
         plan_fill_kernel<<<dim3((unsigned)B, (unsigned)ch.n), kThreads, (size_t)cols_cap * 2, s>>>(
             R, nf, (int32_t)L.NG, nacc, ch.shift, ch.n, blk_cnt, blk_ptr, col_idx, (const uint16_t *)vals, capacity_cols,
-            (int64_t)L.steps, wptr, wfrag, xoff, cols_cap);
+            (int64_t)L.steps, wptr, wfrag, xoff, cols_cap, waves);
     }
     return check_launch();
 }
