@@ -533,8 +533,12 @@ __global__ __launch_bounds__(WAVES * 64) void linear_tiled_planned_kernel(
     // row-blocks of a wavefront's run: together 64 bytes per token row
     constexpr int NACC = plan_nacc(NFRAG, false, (OUT == kOutStaged8 || OUT == kOutElements8) ? 8 : 16 * NFRAG);
     constexpr int nacc_shift = NACC == 4 ? 2 : (NACC == 2 ? 1 : 0);
-    // the same bytes in flight for every fragment count; half of them with 16 wavefronts (registers), no less than 2 steps
-    constexpr int RING = WAVES == kPlanWavesWide ? (4 / NFRAG < 2 ? 2 : 4 / NFRAG) : kPlanRing / NFRAG;
+    // 8 wavefronts: the same bytes in flight for every fragment count, and the X fragments of the next step are read
+    // from LDS while this step's MFMAs run (two register sets).  16 wavefronts: a ring of 2 steps and one register
+    // set -- four wavefronts per SIMD cover for each other (measured as fast as a 4-step ring with two sets), and
+    // the kernel then needs under 96 registers, which leaves a quarter of the register file to other kernels.
+    constexpr bool LEAN = WAVES == kPlanWavesWide;
+    constexpr int RING = LEAN ? 2 : kPlanRing / NFRAG;
     static_assert(RING % 2 == 0, "the X fragment ping-pong needs an even ring");
     const int tile = blockIdx.x % ntiles, strip = blockIdx.x / ntiles;
     const int64_t t0 = (int64_t)tile * (16 * NSUB);
@@ -576,16 +580,15 @@ __global__ __launch_bounds__(WAVES * 64) void linear_tiled_planned_kernel(
     uint32_t bs[NFRAG][8];  // bias of the current block as stored, 16 values per fragment (uniform)
     // kOutSwap: the rounded fragment of the even row-block of a pair (R = 16) until the odd one is finished; the
     // bias the next accumulator starts from (read one row-block ahead); the lane's place in a token's 64-byte
-    // run after the swap (row G of the wavefront takes bytes 16 G .. 16 G + 15), relative to the tile's first row
+    // run after the swap (row G of the wavefront takes bytes 16 G .. 16 G + 15), relative to the sub-tile's first row
     uint2 hold[NSUB];
     f32x4 bnxt[NFRAG];
-    uint32_t yoff[NSUB];
     bool tok[NSUB];
     uint8_t *Ytile = reinterpret_cast<uint8_t *>(Y) + t0 * M * 2;
+    const uint32_t yoff = (uint32_t)(l16 * M * 2 + 16 * G);  // sub-tile u adds 16 u rows (uniform)
 #pragma unroll
     for (int u = 0; u < NSUB; ++u) {
         hold[u] = make_uint2(0u, 0u);
-        yoff[u] = (uint32_t)((16 * u + l16) * M * 2 + 16 * G);
         tok[u] = t0 + 16 * u + l16 < T;
     }
     auto fetch_bias = [&](int64_t b) {  // of row-block b of this strip, from the LDS table
@@ -685,7 +688,7 @@ __global__ __launch_bounds__(WAVES * 64) void linear_tiled_planned_kernel(
                     const u32x2 qx = __builtin_amdgcn_permlane16_swap(px[0], px[1], false, false);
                     const u32x2 qy = __builtin_amdgcn_permlane16_swap(py[0], py[1], false, false);
                     if (tok[u] && !(lone && G >= 2))
-                        *reinterpret_cast<uint4 *>(dst + yoff[u]) = make_uint4(qx[0], qy[0], qx[1], qy[1]);
+                        *reinterpret_cast<uint4 *>(dst + (int64_t)u * (32 * M) + yoff) = make_uint4(qx[0], qy[0], qx[1], qy[1]);
                 }
             }
         } else if constexpr (FAST) {
@@ -811,19 +814,20 @@ __global__ __launch_bounds__(WAVES * 64) void linear_tiled_planned_kernel(
         };
         pass_boundaries();
         if (gs >= gs_hi) continue;  // then e == eb: every block of the segment has been written
-        issue_reads(rx[0], xb[0]);
+        if constexpr (!LEAN) issue_reads(rx[0], xb[0]);
         bool done = false;
         while (!done) {
 #pragma unroll
             for (int j = 0; j < RING; ++j) {
                 // the LDS reads of the next step go out before this step's MFMAs (the scheduler
-                // would otherwise sink them below the MFMAs)
-                issue_reads(rx[(j + 1) % RING], xb[(j + 1) & 1]);
+                // would otherwise sink them below the MFMAs); with one register set, this step's own reads
+                if constexpr (LEAN) issue_reads(rx[j], xb[0]);
+                else issue_reads(rx[(j + 1) % RING], xb[(j + 1) & 1]);
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int u = 0; u < NSUB; ++u)
 #pragma unroll
-                    for (int f = 0; f < NFRAG; ++f) acc[f][u] = mfma16<DT>(ra[j][f], xb[j & 1][u], acc[f][u]);
+                    for (int f = 0; f < NFRAG; ++f) acc[f][u] = mfma16<DT>(ra[j][f], xb[LEAN ? 0 : (j & 1)][u], acc[f][u]);
                 __builtin_amdgcn_sched_barrier(0);
                 // refill this ring slot with step gs + RING
 #pragma unroll
