@@ -42,21 +42,22 @@ inline PlanChunks plan_chunks(int64_t N) {
     return PlanChunks{(int32_t)((npad + 1023) / 1024), 10};
 }
 // A wavefront of the planned kernels works on runs of nacc consecutive row-blocks, so that it can write 64
-// or 128 contiguous bytes per token row: 4 sixteen-row fragments' worth in the column-chunked kernel (which
-// holds all their accumulators and writes once, at the end), 2 in the kernel for layers of up to 1024 columns
-// (64 bytes per row are enough there).  R = 8 fills half a fragment, so 4 of its row-blocks make 64 bytes.
+// or 128 contiguous bytes per token row: 4 sixteen-row fragments' worth in the column-chunked kernel with 8
+// wavefronts (which holds all their accumulators and writes once, at the end), 2 with 16 wavefronts (R = 16, 32:
+// see plan_waves) and in the kernel for layers of up to 1024 columns (64 bytes per row are enough there).
+// R = 8 fills half a fragment, so 4 of its row-blocks make 64 bytes.
 constexpr int plan_nacc(int nfrag, bool chunked, int R) {
     if (R == 8) return 4;
-    const int frags = chunked ? 4 : 2;
+    const int frags = (chunked && R != 16 && R != 32) ? 4 : 2;
     return frags / nfrag > 0 ? frags / nfrag : 1;
 }
-// Streams of a plan = wavefronts of the workgroup that consumes it.  Layers of up to 1024 columns with
-// R = 16 or 32 run 16 wavefronts (4 per SIMD) on a shorter operand ring: their kernel stays within 128
-// registers, and the per-wavefront chains of dependent instructions overlap better (measured 10-14 % faster
-// than 8 wavefronts).  The column-chunked kernel (accumulators of 4 row-blocks) and the other R do not fit.
+// Streams of a plan = wavefronts of the workgroup that consumes it.  Layers with R = 16 or 32 run 16
+// wavefronts (4 per SIMD) on a short operand ring: their kernels stay within 128 registers, and the
+// per-wavefront chains of dependent instructions overlap better (measured 10-14 % faster than 8 wavefronts).
+// The other R do not fit (R = 64: four fragments of accumulators; R = 8 and odd sizes: their output paths).
 inline int plan_waves(int64_t N, int32_t R) {
-    const int64_t npad = (N + 255) / 256 * 256;
-    return (npad <= 1024 && (R == 16 || R == 32)) ? kPlanWavesWide : kPlanWaves;
+    (void)N;
+    return (R == 16 || R == 32) ? kPlanWavesWide : kPlanWaves;
 }
 // Steps the planned kernel may read past the last step of the storage (values unused).
 int plan_slack_steps();

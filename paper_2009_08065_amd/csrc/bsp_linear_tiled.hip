@@ -853,15 +853,19 @@ __global__ __launch_bounds__(WAVES * 64) void linear_tiled_planned_kernel(
 // tile, walks the input columns chunk by chunk (1024 columns of X in LDS at a time) and carries the
 // accumulators of its quads across the chunks, so the operand stream is read once per 64 tokens
 // whatever the layer width.  One group (a quad per wavefront) per workgroup.
-template <int DT, int NFRAG>
-__global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_chunked_kernel(
+template <int DT, int NFRAG, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void linear_tiled_chunked_kernel(
     const uint16_t *__restrict__ X, int64_t T, int64_t M, int64_t N, int32_t R, int32_t npad,
     const int32_t *__restrict__ wptr, const uint32_t *__restrict__ wfrag, const uint32_t *__restrict__ xoff,
     const void *__restrict__ bias, void *__restrict__ Y, int32_t ntiles, int32_t NG, int32_t B, int32_t nchunks,
     int32_t max_step, int32_t fast_store) {
     constexpr int NSUB = 4;
-    constexpr int NACC = plan_nacc(NFRAG, true, 16 * NFRAG);  // 4 / NFRAG; R = 8 (NFRAG = 1) has 4 too
-    constexpr int RING = kPlanRing / NFRAG;
+    // 8 wavefronts: runs of 4 / NFRAG row-blocks (R = 8 and the odd sizes, NFRAG = 1, have 4 too); 16 wavefronts
+    // (R = 16, 32): runs of 2 / NFRAG, a 2-step ring and one set of X fragment registers, as in the kernel above
+    constexpr bool LEAN = WAVES == kPlanWavesWide;
+    constexpr int NACC = LEAN ? 2 / NFRAG : (4 / NFRAG > 0 ? 4 / NFRAG : 1);
+    static_assert(!LEAN || NFRAG <= 2, "16 wavefronts: R = 16 or 32");
+    constexpr int RING = LEAN ? 2 : kPlanRing / NFRAG;
     static_assert(RING % 2 == 0, "the X fragment ping-pong needs an even ring");
     const int tile = blockIdx.x % ntiles, g = blockIdx.x / ntiles;
     const int64_t t0 = (int64_t)tile * (16 * NSUB);
@@ -923,14 +927,15 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_chunked_kernel(
         };
         int blk_end = ends[0];
         while (blk_end <= gs && cur < NACC - 1) blk_end = end_of(++cur);
-        issue_reads(rx[0], xb[0]);
+        if constexpr (!LEAN) issue_reads(rx[0], xb[0]);
         bool done = false;
         while (!done) {
 #pragma unroll
             for (int j = 0; j < RING; ++j) {
-                issue_reads(rx[(j + 1) % RING], xb[(j + 1) & 1]);
+                if constexpr (LEAN) issue_reads(rx[j], xb[0]);
+                else issue_reads(rx[(j + 1) % RING], xb[(j + 1) & 1]);
                 __builtin_amdgcn_sched_barrier(0);
-                step_mfma<DT, NFRAG, NSUB, NACC>(acc, cur, ra[j], xb[j & 1]);
+                step_mfma<DT, NFRAG, NSUB, NACC>(acc, cur, ra[j], xb[LEAN ? 0 : (j & 1)]);
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int f = 0; f < NFRAG; ++f) ra[j][f] = load_frag(wp + ((RING + j) * NFRAG + f) * 256);
@@ -956,7 +961,7 @@ __global__ __launch_bounds__(kPlanWaves * 64) void linear_tiled_chunked_kernel(
     typedef QuadEpilogue<DT, NFRAG, NSUB, NACC> Ep;
     Ep ep;
     ep.init(Y, bias, T, M, R, B, t0, lane, smem_x + wave * (16 * kOutPitch), fast_store != 0);
-    const int64_t b0 = ((int64_t)g * kPlanWaves + wave) * NACC;
+    const int64_t b0 = ((int64_t)g * WAVES + wave) * NACC;
     if (b0 < B) {
         typename Ep::Packed out;
         ep.load_bias(b0);
@@ -1017,16 +1022,25 @@ int launch_planned(const TiledArgs &a, hipStream_t s) {
     const int64_t max_step = a.plan_steps - plan_slack_steps();
     if (max_step < 0 || max_step > INT32_MAX) return BSP_ERR_CAPACITY;
     if (a.npad > 1024) {
-        static thread_local size_t configured = 0;
-        auto kern = linear_tiled_chunked_kernel<DT, NFRAG>;
-        int st = raise_lds_limit(kern, lds, configured);
-        if (st != BSP_OK) return st;
         if (ntiles * NG >= ((int64_t)1 << 31)) return BSP_ERR_SHAPE;
         const PlanChunks ch = plan_chunks(a.N);
-        kern<<<dim3((unsigned)(ntiles * NG)), dim3(kPlanWaves * 64), lds, s>>>(
-            a.X, a.T, a.M, a.N, a.R, a.npad, a.wptr, (const uint32_t *)a.wfrag, a.xoff, a.bias, a.Y, (int32_t)ntiles,
-            (int32_t)NG, (int32_t)a.B, ch.n, (int32_t)max_step, fast);
-        return check_launch();
+        auto go = [&](auto kern, size_t &configured, int w) {
+            int st = raise_lds_limit(kern, lds, configured);
+            if (st != BSP_OK) return st;
+            kern<<<dim3((unsigned)(ntiles * NG)), dim3(w * 64), lds, s>>>(
+                a.X, a.T, a.M, a.N, a.R, a.npad, a.wptr, (const uint32_t *)a.wfrag, a.xoff, a.bias, a.Y, (int32_t)ntiles,
+                (int32_t)NG, (int32_t)a.B, ch.n, (int32_t)max_step, fast);
+            return check_launch();
+        };
+        if constexpr (NFRAG <= 2) {
+            if (waves == kPlanWavesWide) {  // R = 16, 32
+                static thread_local size_t configured = 0;
+                return go(linear_tiled_chunked_kernel<DT, NFRAG, kPlanWavesWide>, configured, kPlanWavesWide);
+            }
+        }
+        if (waves != kPlanWaves) return BSP_ERR_SHAPE;
+        static thread_local size_t configured8 = 0;
+        return go(linear_tiled_chunked_kernel<DT, NFRAG, kPlanWaves>, configured8, kPlanWaves);
     }
     if constexpr (NFRAG == 1) {
         if (a.R == 8 && fast) return launch_planned_1024<DT, NFRAG, kOutStaged8, kPlanWaves>(a, ntiles, NG, max_step, s);
