@@ -346,7 +346,7 @@ def test_linear_wide_layers_in_column_chunks(dtype, R, T, M, N, p_keep):
 @pytest.mark.parametrize("dtype", ["bf16", "f16"])
 @pytest.mark.parametrize("R,T,M,N", [(16, 100, 80, 200), (16, 4100, 2128, 512), (32, 200, 224, 1024), (64, 130, 320, 640),
                                      (8, 130, 88, 512), (8, 300, 1048, 1024)])
-def test_linear_planned_output_staging(dtype, R, T, M, N):
+def test_linear_planned_output_paths(dtype, R, T, M, N):
     # layers of up to 1024 columns on the planned path: an odd number of row-blocks (the last one leaves
     # alone), several strips and groups, one and two fragments per staged row, ragged token tiles
     d = wl.layer(R + T + M, T, M, N, dtype)
