@@ -79,9 +79,14 @@ class Matrix:
     def penalty_grad(self, lam=1e-4):
         bsp.bsp_penalty_grad(self.W, self.R, self.alpha, lam, mode=bsp.ALPHA_SQNORM, grad=self.grad)
 
-    def prune_and_pack(self, eps=1e-6):
-        bsp.bsp_group_norms(self.W, self.R, eps=eps, mode=bsp.ALPHA_SQNORM, sumsq=self.sumsq, alpha=self.alpha,
-                            want=())
+    def prune_and_pack(self, eps=1e-6, lam=None):
+        """Norms and factors (with lam: and the regulariser's gradient, in the same pass over W), mask, pack, plan."""
+        if lam is None:
+            bsp.bsp_group_norms(self.W, self.R, eps=eps, mode=bsp.ALPHA_SQNORM, sumsq=self.sumsq, alpha=self.alpha,
+                                want=())
+        else:
+            bsp.bsp_group_norms_grad(self.W, self.R, lam, eps=eps, mode=bsp.ALPHA_SQNORM, sumsq=self.sumsq,
+                                     alpha=self.alpha, grad=self.grad, want=())
         bsp.bsp_prune_mask(self.sumsq, n_keep=self.n_keep, scope=bsp.SCOPE_MATRIX, keep=self.keep, ws=self.ws)
         bsp.bsp_pack_count(self.keep, self.k_align, blk_cnt=self.blk_cnt, blk_ptr=self.blk_ptr)
         L = bsp.lib()
@@ -94,11 +99,11 @@ class Matrix:
             bsp.bsp_linear_plan(self.packed, plan=self.plan)
 
     def whole_step(self):
-        """Norms, mask, pack, plan, layer; the regulariser's gradient last: it needs only the factors and
-        nothing in the step waits for it, so it is kept out of the chain that leads to the layer."""
-        self.prune_and_pack()
+        """Norms and factors with the regulariser's gradient (one pass over W: Alg. 2 at a milestone), mask, pack,
+        plan, layer.  A gradient launch of its own after the layer cost 15 us per step: every launch of a stream
+        queues behind the layer kernels of the other streams."""
+        self.prune_and_pack(lam=1e-4)
         self.linear()
-        self.penalty_grad()
 
     def linear(self):
         if self.use_plan:
@@ -510,8 +515,8 @@ def main():
                    "launch": {"overlap": "one HIP graph per matrix, the four replayed side by side on four streams",
                               "serial": "one HIP graph per step, matrices in turn",
                               "eager": "every kernel launched from Python"}[args.launch],
-                   "step": "group_norms + penalty_grad + prune_mask + pack_count + pack + linear_plan + linear, "
-                           "4 matrices"},
+                   "step": "group_norms_grad (norms, factors and regulariser gradient in one pass) + prune_mask + "
+                           "pack_count + pack + linear_plan + linear, 4 matrices"},
         "linear_only": {"cache_state": "cold: the four layers run in turn, so about 250 MB of other X / Y traffic "
                                        "(the size of the Infinity Cache) passes between two launches of one layer",
                         "ms": round(lin_total_ms, 4), "useful_tflops": round(achieved_tflops, 2),

@@ -18,13 +18,8 @@ constexpr int kWaves = kThreads / kWave;
 
 __device__ __forceinline__ int round_up(int k, int a) { return ((k + a - 1) / a) * a; }
 
-// One wavefront per row of keep[B, N] (kWaves rows per workgroup).
-__global__ __launch_bounds__(kThreads) void pack_count_kernel(const uint8_t *__restrict__ keep, int64_t B, int64_t N,
-                                                              int32_t *__restrict__ blk_cnt) {
-    const int lane = threadIdx.x & (kWave - 1);
-    const int64_t b = (int64_t)blockIdx.x * kWaves + threadIdx.x / kWave;
-    if (b >= B) return;  // whole wavefronts leave
-    const uint8_t *row = keep + b * N;
+// Kept flags of one row of keep, counted by one wavefront (the result in every lane).
+__device__ __forceinline__ int count_row(const uint8_t *__restrict__ row, int64_t N, int lane) {
     int cnt = 0;
     if (((reinterpret_cast<uintptr_t>(row) | (uintptr_t)N) & 15) == 0) {  // 16 flags per load
         for (int64_t j = (int64_t)lane * 16; j < N; j += kWave * 16) {
@@ -40,6 +35,16 @@ __global__ __launch_bounds__(kThreads) void pack_count_kernel(const uint8_t *__r
     }
 #pragma unroll
     for (int o = kWave / 2; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o, kWave);
+    return cnt;
+}
+
+// One wavefront per row of keep[B, N] (kWaves rows per workgroup).
+__global__ __launch_bounds__(kThreads) void pack_count_kernel(const uint8_t *__restrict__ keep, int64_t B, int64_t N,
+                                                              int32_t *__restrict__ blk_cnt) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t b = (int64_t)blockIdx.x * kWaves + threadIdx.x / kWave;
+    if (b >= B) return;  // whole wavefronts leave
+    const int cnt = count_row(keep + b * N, N, lane);
     if (lane == 0) blk_cnt[b] = cnt;
 }
 
@@ -69,6 +74,42 @@ __global__ __launch_bounds__(kScanThreads) void pack_scan_kernel(const int32_t *
         run += round_up(blk_cnt[b], k_align);
     }
     if (threadIdx.x == kScanThreads - 1) blk_ptr[B] = run;  // the last thread's run ends at B (or is empty)
+}
+
+// Small masks (at most kScanThreads rows and kSmallFlags flags): count and scan in one launch of one workgroup.
+// Its wavefronts count the rows in turn, then thread b owns row-block b in the scan.  Saves a launch where the
+// launches, not the bytes, are what takes the time.
+constexpr int64_t kSmallFlags = (int64_t)1 << 19;
+__global__ __launch_bounds__(kScanThreads) void pack_count_scan_kernel(const uint8_t *__restrict__ keep, int64_t B,
+                                                                       int64_t N, int32_t k_align,
+                                                                       int32_t *__restrict__ blk_cnt,
+                                                                       int32_t *__restrict__ blk_ptr) {
+    __shared__ int s_cnt[kScanThreads];
+    __shared__ int wsum[kScanThreads / kWave];
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    for (int64_t b = wave; b < B; b += kScanThreads / kWave) {
+        const int cnt = count_row(keep + b * N, N, lane);
+        if (lane == 0) s_cnt[b] = cnt;
+    }
+    __syncthreads();
+    const bool live = threadIdx.x < B;
+    const int cnt = live ? s_cnt[threadIdx.x] : 0;
+    const int mine = round_up(cnt, k_align);
+    int incl = mine;
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+        const int up = __shfl_up(incl, o, kWave);
+        if (lane >= o) incl += up;
+    }
+    if (lane == kWave - 1) wsum[wave] = incl;
+    __syncthreads();
+    int run = incl - mine;
+    for (int w = 0; w < wave; ++w) run += wsum[w];
+    if (live) {
+        blk_cnt[threadIdx.x] = cnt;
+        blk_ptr[threadIdx.x] = run;
+        if (threadIdx.x == B - 1) blk_ptr[B] = run + mine;
+    }
 }
 
 // Compaction in two stages.  Every workgroup first builds the ascending list of the row-block's kept columns
@@ -296,8 +337,12 @@ extern "C" int bsp_pack_count(const uint8_t *keep, int64_t B, int64_t N, int32_t
     if (B <= 0 || N <= 0 || N >= ((int64_t)1 << 31) - 64 || B >= ((int64_t)1 << 31) || !valid_align(k_align)) return BSP_ERR_SHAPE;
     if ((B * (N + 63)) >= ((int64_t)1 << 31)) return BSP_ERR_SHAPE;  // blk_ptr is int32
     hipStream_t s = (hipStream_t)stream;
-    pack_count_kernel<<<(unsigned)((B + kWaves - 1) / kWaves), kThreads, 0, s>>>(keep, B, N, blk_cnt);
-    pack_scan_kernel<<<1, kScanThreads, 0, s>>>(blk_cnt, B, k_align, blk_ptr);
+    if (B <= kScanThreads && B * N <= kSmallFlags) {
+        pack_count_scan_kernel<<<1, kScanThreads, 0, s>>>(keep, B, N, k_align, blk_cnt, blk_ptr);
+    } else {
+        pack_count_kernel<<<(unsigned)((B + kWaves - 1) / kWaves), kThreads, 0, s>>>(keep, B, N, blk_cnt);
+        pack_scan_kernel<<<1, kScanThreads, 0, s>>>(blk_cnt, B, k_align, blk_ptr);
+    }
     return check_launch();
 }
 
