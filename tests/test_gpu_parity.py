@@ -241,6 +241,18 @@ def test_pack_bit_exact(R, N, wdt, vdt, k_align):
         assert not bsp.bsp_packed_validate(bad)
 
 
+@pytest.mark.parametrize("B,N", [(1024, 512), (1025, 64), (700, 749), (1, 1), (1024, 513), (37, 14000)])
+@pytest.mark.parametrize("k_align", [1, 32])
+def test_pack_count_one_launch_and_two(B, N, k_align):
+    # small masks are counted and scanned by one workgroup, larger ones by a count launch and a scan launch
+    keep = wl.bernoulli_keep_mask(B * 7 + N, B, N, 0.3)
+    keep[B // 2, :] = 0
+    keep[keep != 0] = np.random.default_rng(B + N).integers(1, 256, size=int(np.count_nonzero(keep)), dtype=np.uint8)
+    cnt_ref, ptr_ref = orc.pack_count(keep, k_align)
+    cnt, ptr = bsp.bsp_pack_count(torch.from_numpy(keep).cuda(), k_align)
+    assert np.array_equal(host(cnt), cnt_ref) and np.array_equal(host(ptr), ptr_ref)
+
+
 def test_pack_all_empty_and_capacity_guard():
     W = wl.normal(1, (32, 64), 0.02)
     keep0 = torch.zeros((2, 64), dtype=torch.uint8, device="cuda")
