@@ -78,8 +78,9 @@ __global__ __launch_bounds__(kScanThreads) void pack_scan_kernel(const int32_t *
 
 // Small masks (at most kScanThreads rows and kSmallFlags flags): count and scan in one launch of one workgroup.
 // Its wavefronts count the rows in turn, then thread b owns row-block b in the scan.  Saves a launch where the
-// launches, not the bytes, are what takes the time.
-constexpr int64_t kSmallFlags = (int64_t)1 << 19;
+// launches, not the bytes, are what takes the time: up to 32 K flags.  (One compute unit reads slowly: on the
+// 0.25 M flags of a BERT-large matrix this kernel took 11 us against 3 + 3 for the two launches.)
+constexpr int64_t kSmallFlags = (int64_t)1 << 15;
 __global__ __launch_bounds__(kScanThreads) void pack_count_scan_kernel(const uint8_t *__restrict__ keep, int64_t B,
                                                                        int64_t N, int32_t k_align,
                                                                        int32_t *__restrict__ blk_cnt,

@@ -241,7 +241,7 @@ def test_pack_bit_exact(R, N, wdt, vdt, k_align):
         assert not bsp.bsp_packed_validate(bad)
 
 
-@pytest.mark.parametrize("B,N", [(1024, 512), (1025, 64), (700, 749), (1, 1), (1024, 513), (37, 14000)])
+@pytest.mark.parametrize("B,N", [(1024, 32), (1025, 31), (43, 749), (1, 1), (1024, 33), (37, 14000), (2, 16384)])
 @pytest.mark.parametrize("k_align", [1, 32])
 def test_pack_count_one_launch_and_two(B, N, k_align):
     # small masks are counted and scanned by one workgroup, larger ones by a count launch and a scan launch
