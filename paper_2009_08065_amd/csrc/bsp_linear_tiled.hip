@@ -43,9 +43,10 @@ typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
 constexpr int kMaxStripBlocks = 1024;  // row-blocks per strip (their blk_ptr slice is cached in LDS)
 constexpr int kRing = 4;               // steps of operands in flight per wavefront, canonical kernel
-constexpr int kPlanRing = 8;           // the same for the planned kernels, divided by the fragments per step.  Deeper
-                                       // rings were measured slower (4 to 8 steps are equal, 16 is 10 % slower):
-                                       // latency is covered, and more requests in flight only queue up
+constexpr int kPlanRing = 8;           // the same for the planned kernels with 8 wavefronts, divided by the fragments per
+                                       // step (with 16 wavefronts: 2 steps).  Deeper rings were measured slower (4 to 8
+                                       // steps are equal, 16 is 10 % slower): latency is covered, and more requests in
+                                       // flight only queue up
 
 // Distance in LDS between the 16-token sub-tiles of a workgroup's X tile: a constant, so that
 // sub-tile offsets fold into the immediate field of the LDS instructions.
@@ -338,13 +339,13 @@ __global__ __launch_bounds__(1024) void linear_tiled_canonical_kernel(
 // ---------------------------------------------------------------------------------------------
 // planned operands
 // ---------------------------------------------------------------------------------------------
-// A wavefront owns NACC = 4 / NFRAG consecutive row-blocks at a time (a "quad": 64 consecutive output
-// columns whatever R is) and keeps all their accumulators, so that it can write whole 128-byte lines
-// of Y: group g of a layer = kPlanWaves quads = blocks [g * 8 * NACC, (g + 1) * 8 * NACC), quad w of
-// the group belongs to wavefront w.  The plan stores the steps in exactly the order a wavefront walks
-// them (its quad of group 0 block by block, then group 1, ...; chunk-major for layers cut into column
-// chunks), so a wavefront streams its operands with constant address increments.
-// wptr[w][(q * NG + g) * NACC + i] = first step of block (g * 8 + w) * NACC + i inside chunk q.
+// A wavefront owns NACC consecutive row-blocks at a time (a run: 64 or 128 bytes of consecutive output
+// columns, see plan_nacc) and, in the column-chunked kernel, keeps all their accumulators, so that it can
+// write whole lines of Y: group g of a layer = `waves` runs = blocks [g * waves * NACC, (g + 1) * waves * NACC),
+// run w of the group belongs to wavefront w (waves = 8 or 16, see plan_waves).  The plan stores the steps in
+// exactly the order a wavefront walks them (its run of group 0 block by block, then group 1, ...; chunk-major
+// for layers cut into column chunks), so a wavefront streams its operands with constant address increments.
+// wptr[w][(q * NG + g) * NACC + i] = first step of block (g * waves + w) * NACC + i inside chunk q.
 
 constexpr int kOutPitch = 144;  // bytes per token row of a wavefront's output staging (128 + pad)
 
