@@ -408,6 +408,39 @@ def test_linear_wide_layer_many_tokens_ragged_strips():
     run_layer(d["X"], d["W"], d["bias"], R, keep, 32, "bf16", T_rows=[(0, 70), (2040, 2060), (4090, 4100)])
 
 
+def test_linear_seeded_random_shapes():
+    """Eighty seeded draws over block sizes, widths (one tile and column chunks), ragged token counts, densities,
+    alignments, dtypes, empty row-blocks, no bias: both layer entry points against the oracle."""
+    rng = np.random.default_rng(20250)
+    for it in range(80):
+        R = int(rng.choice([16, 16, 16, 32, 32, 64, 8, 4, 24]))
+        B = int(rng.integers(1, 70))
+        M = R * B
+        N = int(rng.choice([32, 64, 200, 256, 520, 768, 1000, 1024, 1032, 2048, 3000, 4096]))
+        T = int(rng.integers(1, 330))
+        dt = str(rng.choice(["bf16", "f16"]))
+        p_keep = float(rng.choice([0.05, 0.2, 0.5, 0.9]))
+        k_align = int(rng.choice([32, 64]))
+        d = wl.layer(1000 + it, T, M, N, dt)
+        keep = wl.bernoulli_keep_mask(5000 + it, B, N, p_keep)
+        if it % 7 == 0:
+            keep[int(rng.integers(0, B))] = 0          # an empty row-block
+        if it % 11 == 0:
+            keep[:] = 0                                 # nothing kept: the bias alone
+        use_bias = it % 3 != 0
+        p_ref = orc.pack(d["W"], R, keep, k_align, CODE[dt])
+        p = bsp.bsp_pack(dev(d["W"], dt), R, torch.from_numpy(keep).cuda(), k_align)
+        bias = dev(d["bias"], dt) if use_bias else None
+        Y_ref, _ = orc.linear_packed(d["X"], p_ref, d["bias"] if use_bias else None, ydt=CODE[dt], n_threads=8)
+        Xd = dev(d["X"], dt)
+        case = dict(it=it, R=R, B=B, N=N, T=T, dt=dt, p=p_keep, k_align=k_align, bias=use_bias)
+        try:
+            assert_y_close(host(bsp.bsp_linear_planned(Xd, p, bsp.bsp_linear_plan(p), bias)), Y_ref, dt)
+            assert_y_close(host(bsp.bsp_linear(Xd, p, bias)), Y_ref, dt)
+        except AssertionError as e:
+            raise AssertionError(f"{case}: {e}")
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_linear_keep_all_is_dense_gemm_keep_none_is_bias(dtype):
     d = wl.layer(77, 96, 64, 160, dtype)
