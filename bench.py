@@ -76,9 +76,6 @@ class Matrix:
             self.plan = torch.empty(bsp.lib().bsp_linear_plan_bytes(self.M, self.R, self.capacity), dtype=torch.uint8,
                                     device=dev)
 
-    def penalty_grad(self, lam=1e-4):
-        bsp.bsp_penalty_grad(self.W, self.R, self.alpha, lam, mode=bsp.ALPHA_SQNORM, grad=self.grad)
-
     def prune_and_pack(self, eps=1e-6, lam=None):
         """Norms and factors (with lam: and the regulariser's gradient, in the same pass over W), mask, pack, plan."""
         if lam is None:
