@@ -433,7 +433,7 @@ extern "C" int bsp_prune_mask(const float *sumsq, int64_t B, int64_t N, float t,
         mask_rank_hist_kernel<2><<<G, kSelThreads, 0, s>>>(sumsq, n, per_wg, (uint32_t)P, w);
     }
     int64_t ga = (n + (int64_t)kSelThreads * 16 - 1) / ((int64_t)kSelThreads * 16);
-    ga = ga < 1 ? 1 : (ga > 1024 ? 1024 : ga);
+    ga = ga < 1 ? 1 : (ga > 256 ? 256 : ga);  // a workgroup per compute unit at most: each starts by resolving the last digit
     mask_rank_apply_kernel<<<(unsigned)ga, kSelThreads, 0, s>>>(sumsq, n, (uint32_t)P, G, w, keep, t_used);
     return check_launch();
 }
