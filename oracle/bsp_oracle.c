@@ -310,6 +310,63 @@ void orc_linear_packed(const float *X, int64_t t0, int64_t t1, int64_t M, int64_
 }
 
 /* ------------------------------------------------------------------------------------ */
+/* The transposed product of the pruned layer.  With Wp the weight matrix with its pruned */
+/* groups zeroed (Alg. 1), the layer of Sec. 3.1 is Y = X Wp^T + bias; the chain rule     */
+/* gives the gradient with respect to its input as dX = dY Wp, and the same product is    */
+/* the layer itself when the groups are row segments of column blocks (the other division */
+/* of Alg. 1, the second regulariser of Sec. 3.2) and the matrix is kept transposed:      */
+/*   Z[t, j] = bias[j] + sum_{m ascending} U[t, m] * (keep[m / R, j] ? W[m, j] : 0)        */
+/* U: [T, M], Z: [T, N]; accumulated in double, then rounded to zdt.                      */
+/* ------------------------------------------------------------------------------------ */
+void orc_linear_t_dense(const float *U, const float *W, const uint8_t *keep, const float *bias,
+                        int64_t T, int64_t M, int64_t N, int32_t R, int32_t zdt, float *Z,
+                        double *Zd)
+{
+    for (int64_t t = 0; t < T; ++t)
+        for (int64_t j = 0; j < N; ++j) {
+            double acc = bias ? (double)bias[j] : 0.0;
+            for (int64_t m = 0; m < M; ++m) {
+                double w = keep[(m / R) * N + j] ? (double)W[m * N + j] : 0.0;
+                acc += (double)U[t * M + m] * w;
+            }
+            if (Zd) Zd[t * N + j] = acc;
+            if (Z) Z[t * N + j] = (float)orc_round(acc, zdt);
+        }
+}
+
+/* The same sum taken through the compact storage: the kept column c of row-block b adds  */
+/* sum_r U[t, bR + r] * vals[b, r, c] to Z[t, col_idx[b, c]]; row-blocks ascending, rows   */
+/* ascending, so every Z[t, j] is summed over m ascending as above.  Pad slots (c >= k_b)  */
+/* are not part of the matrix and are skipped.  Rows t0 .. t1-1 of U only.                */
+void orc_linear_t_packed(const float *U, int64_t t0, int64_t t1, int64_t M, int64_t N, int32_t R,
+                         const int32_t *blk_cnt, const int32_t *blk_ptr, const int32_t *col_idx,
+                         const float *vals, const float *bias, int32_t zdt, float *Z, double *Zd,
+                         int32_t n_threads)
+{
+    int64_t B = M / R;
+    if (n_threads < 1) n_threads = 1;
+#pragma omp parallel for num_threads(n_threads) schedule(static)
+    for (int64_t t = t0; t < t1; ++t) {
+        double *acc = (double *)malloc(sizeof(double) * (size_t)N);
+        for (int64_t j = 0; j < N; ++j) acc[j] = bias ? (double)bias[j] : 0.0;
+        for (int64_t b = 0; b < B; ++b) {
+            int64_t base = blk_ptr[b];
+            int32_t kp = blk_ptr[b + 1] - blk_ptr[b];
+            for (int32_t r = 0; r < R; ++r) {
+                double u = (double)U[t * M + b * R + r];
+                for (int32_t c = 0; c < blk_cnt[b]; ++c)
+                    acc[col_idx[base + c]] += u * (double)vals[R * base + (int64_t)r * kp + c];
+            }
+        }
+        for (int64_t j = 0; j < N; ++j) {
+            if (Zd) Zd[t * N + j] = acc[j];
+            if (Z) Z[t * N + j] = (float)orc_round(acc[j], zdt);
+        }
+        free(acc);
+    }
+}
+
+/* ------------------------------------------------------------------------------------ */
 /* Alg. 1's effect on the stored weights ("the group is set to zero") and the retraining  */
 /* step of Alg. 2 (W = W * Mask after every update): every weight of a pruned group       */
 /* becomes +0, every weight of a kept group is left as it is (bit for bit).  The mask is  */

@@ -162,6 +162,38 @@ def linear_packed(X, packed, bias, ydt=F32, t0=0, t1=None, n_threads=1):
     return Y, Yd
 
 
+def linear_t_dense(U, W, keep, bias, R, zdt=F32):
+    """Brute force transposed product: U times the matrix with pruned entries zeroed.  Returns (Z rounded, Z double)."""
+    U, W = _f32(U), _f32(W)
+    T, M = U.shape
+    N = W.shape[1]
+    assert W.shape[0] == M
+    keep = np.ascontiguousarray(keep, dtype=np.uint8)
+    bias = None if bias is None else _f32(bias)
+    Z = np.empty((T, N), dtype=np.float32)
+    Zd = np.empty((T, N), dtype=np.float64)
+    lib().orc_linear_t_dense(_p(U), _p(W), _p(keep), _p(bias), C.c_int64(T), C.c_int64(M), C.c_int64(N),
+                             C.c_int32(R), C.c_int32(zdt), _p(Z), _p(Zd))
+    return Z, Zd
+
+
+def linear_t_packed(U, packed, bias, zdt=F32, t0=0, t1=None, n_threads=1):
+    """The transposed product through the compact storage, rows t0..t1-1 of U.  Returns (Z, Zd) of full
+    shape [T, N]; rows outside [t0, t1) are left as NaN."""
+    U = _f32(U)
+    T, M = U.shape
+    N, R = packed["N"], packed["R"]
+    assert M == packed["M"]
+    t1 = T if t1 is None else t1
+    bias = None if bias is None else _f32(bias)
+    Z = np.full((T, N), np.nan, dtype=np.float32)
+    Zd = np.full((T, N), np.nan, dtype=np.float64)
+    lib().orc_linear_t_packed(_p(U), C.c_int64(t0), C.c_int64(t1), C.c_int64(M), C.c_int64(N), C.c_int32(R),
+                              _p(packed["blk_cnt"]), _p(packed["blk_ptr"]), _p(packed["col_idx"]),
+                              _p(packed["vals"]), _p(bias), C.c_int32(zdt), _p(Z), _p(Zd), C.c_int32(n_threads))
+    return Z, Zd
+
+
 def mask_weights(W, R, keep):
     """Returns a copy of W with every pruned group set to +0 (Alg. 1; the W = W * Mask step of Alg. 2)."""
     W = _f32(W).copy()

@@ -408,6 +408,100 @@ def test_linear_output_rounding_and_row_range():
     assert np.array_equal(Ymt, Y)
 
 
+# --------------------------------------------------------------------------- the transposed product
+def brute_force_transposed(U, W, keep, bias, R):
+    """Exact rational arithmetic: Z[t, j] = bias[j] + sum_m U[t, m] W[m, j] over the kept groups."""
+    from fractions import Fraction
+    T, M = U.shape
+    N = W.shape[1]
+    Z = np.zeros((T, N), np.float64)
+    for t in range(T):
+        for j in range(N):
+            acc = Fraction(float(bias[j])) if bias is not None else Fraction(0)
+            for m in range(M):
+                if keep[m // R, j]:
+                    acc += Fraction(float(U[t, m])) * Fraction(float(W[m, j]))
+            Z[t, j] = float(acc)
+    return Z
+
+
+@pytest.mark.parametrize("R", [1, 2, 4, 8])
+def test_linear_t_vs_exact_brute_force(R):
+    T, M, N = 3, 8, 10
+    U, W, bias = rand((T, M)), rand((M, N), 0.02), rand((N,), 0.02)
+    keep = wl.bernoulli_keep_mask(R + 20, M // R, N, 0.5)
+    want = brute_force_transposed(U, W, keep, bias, R)
+    Z, Zd = orc.linear_t_dense(U, W, keep, bias, R)
+    assert Zd.shape == (T, N)                            # orientation: U is [T, out], Z is [T, in]
+    assert np.allclose(Zd, want, rtol=0, atol=1e-15)
+    for k_align in (1, 8):
+        Zp, Zpd = orc.linear_t_packed(U, orc.pack(W, R, keep, k_align), bias)
+        assert np.array_equal(Zpd, Zd)                   # same order of the additions: bit for bit
+        assert np.array_equal(Zp, Zd.astype(np.float32))
+
+
+def test_linear_t_against_library_matmul_and_special_cases():
+    T, M, N, R = 9, 48, 40, 8
+    U, W, bias = rand((T, M)), rand((M, N), 0.02), rand((N,), 0.02)
+    keep = wl.bernoulli_keep_mask(6, M // R, N, 0.35)
+    Wz = W.astype(np.float64) * np.repeat(keep, R, axis=0)
+    want = (torch.from_numpy(U).double() @ torch.from_numpy(Wz) + torch.from_numpy(bias).double()).numpy()
+    _, Zd = orc.linear_t_packed(U, orc.pack(W, R, keep, 16), bias)
+    assert np.allclose(Zd, want, rtol=1e-12, atol=1e-15)
+    ones, zeros = np.ones_like(keep), np.zeros_like(keep)
+    _, Zall = orc.linear_t_packed(U, orc.pack(W, R, ones, 1), None)
+    assert np.allclose(Zall, (torch.from_numpy(U).double() @ torch.from_numpy(W).double()).numpy(), rtol=1e-12,
+                       atol=1e-15)
+    Z0, _ = orc.linear_t_packed(U, orc.pack(W, R, zeros, 16), bias)
+    assert np.array_equal(Z0, np.broadcast_to(bias, (T, N)))
+    # a column no block keeps receives the bias alone; a pad slot (k_align > 1) adds nothing to the last kept column
+    k1 = keep.copy()
+    k1[:, 7] = 0
+    Z1, _ = orc.linear_t_packed(U, orc.pack(W, R, k1, 16), bias)
+    assert np.array_equal(Z1[:, 7], np.broadcast_to(bias[7], (T,)))
+    Uinf = U.copy()
+    Uinf[0, 0] = np.inf                                  # would give inf * 0 = NaN if pads were multiplied in
+    kone = np.zeros_like(keep)
+    kone[0, 3] = 1
+    Zi, _ = orc.linear_t_packed(Uinf, orc.pack(np.abs(W) + 1, R, kone, 16), None)
+    assert np.isinf(Zi[0, 3]) and not np.isnan(Zi).any()
+
+
+def test_linear_t_is_the_adjoint_of_the_layer():
+    """<linear(X), U> = <X, linear_t(U)> without biases: the input gradient of the layer (chain rule), checked
+    against the layer's own oracle and against torch's autograd on the dense masked product."""
+    T, M, N, R = 6, 32, 28, 8
+    X, U, W = rand((T, N)), rand((T, M)), rand((M, N), 0.05)
+    keep = wl.bernoulli_keep_mask(3, M // R, N, 0.4)
+    p = orc.pack(W, R, keep, 8)
+    _, Yd = orc.linear_packed(X, p, None)
+    _, Zd = orc.linear_t_packed(U, p, None)
+    assert math.isclose(float((Yd * U).sum()), float((X * Zd).sum()), rel_tol=1e-12, abs_tol=1e-13)
+    Xt = torch.from_numpy(X).double().requires_grad_(True)
+    Wz = torch.from_numpy(W.astype(np.float64) * np.repeat(keep, R, axis=0))
+    (Xt @ Wz.T).backward(torch.from_numpy(U).double())
+    assert np.allclose(Zd, Xt.grad.numpy(), rtol=1e-12, atol=1e-15)
+    # the other variant of Alg. 1: groups are row segments of column blocks of V = W^T; its layer is X' V^T
+    V = np.ascontiguousarray(W.T)                       # [N, M]: V's column block b holds columns bR .. bR+R-1
+    Vz = V.astype(np.float64) * np.repeat(keep, R, axis=0).T
+    want = (torch.from_numpy(U).double() @ torch.from_numpy(Vz).T).numpy()
+    assert np.allclose(Zd, want, rtol=1e-12, atol=1e-15)
+
+
+def test_linear_t_rounding_row_range_and_threads():
+    T, M, N, R = 6, 32, 33, 16
+    U = wl.to_dtype_values(rand((T, M)), "bf16")
+    W = wl.to_dtype_values(rand((M, N), 0.02), "bf16")
+    bias = wl.to_dtype_values(rand((N,), 0.02), "bf16")
+    p = orc.pack(W, R, wl.bernoulli_keep_mask(9, M // R, N, 0.5), 16, orc.BF16)
+    Z, Zd = orc.linear_t_packed(U, p, bias, zdt=orc.BF16)
+    assert np.array_equal(Z.astype(np.float64), orc.round_to(Zd, orc.BF16))
+    Zs, _ = orc.linear_t_packed(U, p, bias, zdt=orc.BF16, t0=2, t1=4)
+    assert np.array_equal(Zs[2:4], Z[2:4]) and np.isnan(Zs[:2]).all() and np.isnan(Zs[4:]).all()
+    Zmt, _ = orc.linear_t_packed(U, p, bias, zdt=orc.BF16, n_threads=4)
+    assert np.array_equal(Zmt, Z)
+
+
 # --------------------------------------------------------------------------- end to end
 def test_chain_on_base_attention_projection():
     """norms -> percentile mask -> pack -> layer equals the dense layer with the mask's zeros."""
