@@ -161,6 +161,25 @@ int bsp_linear(const void *X, int xdt, int64_t T, int64_t M, int64_t N, int32_t 
                const int32_t *blk_cnt, const int32_t *blk_ptr, const int32_t *col_idx, const void *vals,
                const void *bias, void *Y, void *stream);
 
+/* ---- the transposed product of the pruned layer (Sec. 3.1: with Wp the matrix after Alg. 1
+ * the layer is Y = X Wp^T + bias, so the gradient with respect to its input is dX = dY Wp;
+ * the same product is the layer itself when the pruned groups are row segments of column
+ * blocks, the other division of Alg. 1 and the second regulariser of Sec. 3.2, and the matrix
+ * is stored transposed) ------------------------------------------------------------------
+ *   Z[t, n] = bias[n] + sum_{b, c < k_b : col_idx[blk_ptr[b] + c] == n}
+ *                       sum_{r < R} U[t, bR + r] * vals[b, r, c]
+ * U: [T, M], Z: [T, N], row-major contiguous, dtype udt; vals and bias (length N, may be
+ * NULL) have dtype udt too.  The compact storage is the one bsp_pack writes; pad slots
+ * (c >= k_b) are not part of the matrix and are never read as values.  A column that no
+ * row-block keeps receives the bias alone.  Products are accumulated in fp32 (matrix cores
+ * for bf16 / fp16 when R % 4 == 0, k_align >= 8, U 8-byte and col_idx 16-byte aligned; fp32
+ * multiply-adds otherwise), the bias is added in fp32 and the sum is rounded once to udt
+ * (RNE).  The order of the additions is unspecified and may differ from call to call.
+ * N <= 65535.  Errors: NULL U / blk_cnt / blk_ptr / Z, bad dtype, M % R != 0, R > 64. */
+int bsp_linear_transposed(const void *U, int udt, int64_t T, int64_t M, int64_t N, int32_t R, int32_t k_align,
+                          const int32_t *blk_cnt, const int32_t *blk_ptr, const int32_t *col_idx,
+                          const void *vals, const void *bias, void *Z, void *stream);
+
 /* ---- derived operand buffer for the layer (Sec. 4.4 names "matrix reorder and compact model
  * storage" as what makes the pruned model fast; the order of the kept columns inside a
  * row-block is free, so it is chosen for the hardware) ---------------------------------------

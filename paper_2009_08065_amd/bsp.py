@@ -60,6 +60,7 @@ def lib():
     L.bsp_pack.argtypes = [vp, C.c_int, i64, i64, i32, vp, i32, vp, vp, i64, vp, vp, C.c_int, vp]
     L.bsp_packed_validate.argtypes = [i64, i64, i32, i32, vp, vp, vp, i64, vp, vp]
     L.bsp_linear.argtypes = [vp, C.c_int, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp, vp, vp]
+    L.bsp_linear_transposed.argtypes = [vp, C.c_int, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp, vp, vp]
     L.bsp_linear_plan_supported.argtypes = [C.c_int, i64, i32]
     L.bsp_linear_plan_supported.restype = C.c_int
     L.bsp_linear_plan_bytes.argtypes = [i64, i32, i64]
@@ -73,7 +74,7 @@ def lib():
     L.bsp_last_hip_error.restype = C.c_int
     L.bsp_version.restype = C.c_char_p
     for name in ("bsp_group_norms", "bsp_penalty_grad", "bsp_prune_mask", "bsp_pack_count", "bsp_pack",
-                 "bsp_packed_validate", "bsp_linear", "bsp_linear_plan", "bsp_linear_planned", "bsp_mask_weights",
+                 "bsp_packed_validate", "bsp_linear", "bsp_linear_transposed", "bsp_linear_plan", "bsp_linear_planned", "bsp_mask_weights",
                  "bsp_group_norms_grad", "bsp_adam_step"):
         getattr(L, name).restype = C.c_int
     _LIB = L
@@ -272,6 +273,22 @@ def bsp_linear(X, p: Packed, bias=None, Y=None):
                           _stream())
     _check(st, "bsp_linear")
     return Y
+
+
+def bsp_linear_transposed(U, p: Packed, bias=None, Z=None):
+    T, M = U.shape
+    if M != p.M:
+        raise ValueError("U has the wrong number of columns")
+    if p.vals.dtype != U.dtype or (bias is not None and bias.dtype != U.dtype):
+        raise ValueError("U, vals and bias must share one dtype")
+    if Z is None:
+        Z = torch.empty((T, p.N), dtype=U.dtype, device=U.device)
+    has = p.total_cols > 0
+    st = lib().bsp_linear_transposed(_ptr(U), _DT[U.dtype], T, M, p.N, p.R, p.k_align, _ptr(p.blk_cnt),
+                                     _ptr(p.blk_ptr), _ptr(p.col_idx) if has else None,
+                                     _ptr(p.vals) if has else None, _ptr(bias), _ptr(Z), _stream())
+    _check(st, "bsp_linear_transposed")
+    return Z
 
 
 def bsp_linear_plan_supported(dtype, N, k_align) -> bool:

@@ -62,6 +62,11 @@ def test_host_side_argument_checks():
     assert L.bsp_linear(one, 1, 0, 16, 8, 16, 32, one, one, one, one, None, one, None) == OK  # no tokens
     assert L.bsp_linear(C.c_void_p(8), 1, 4, 16, 8, 16, 32, one, one, one, one, None, one, None) == SHAPE  # alignment
     assert L.bsp_linear(one, 5, 4, 16, 8, 16, 32, one, one, one, one, None, one, None) == DTYPE
+    assert L.bsp_linear_transposed(None, 1, 4, 16, 8, 16, 32, one, one, one, one, None, one, None) == NULL
+    assert L.bsp_linear_transposed(one, 1, 4, 24, 8, 16, 32, one, one, one, one, None, one, None) == SHAPE
+    assert L.bsp_linear_transposed(one, 1, 4, 16, 70000, 16, 32, one, one, one, one, None, one, None) == SHAPE
+    assert L.bsp_linear_transposed(one, 1, 0, 16, 8, 16, 32, one, one, one, one, None, one, None) == OK  # no tokens
+    assert L.bsp_linear_transposed(one, 7, 4, 16, 8, 16, 32, one, one, one, one, None, one, None) == DTYPE
     assert L.bsp_packed_validate(16, 8, 16, 16, None, one, one, 0, one, None) == NULL
     assert L.bsp_penalty_grad_workspace_bytes(32, 300, 16) == 2 * 2 * 8
     assert L.bsp_prune_mask_workspace_bytes(4, 100, 1) >= 2 * (2048 + 64) * 4   # two histogram slots at least

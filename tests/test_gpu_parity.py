@@ -443,6 +443,110 @@ def test_linear_seeded_random_shapes():
             raise AssertionError(f"{case}: {e}")
 
 
+# ------------------------------------------------------------------------------ the transposed product
+def run_transposed(U, W, bias, R, keep, k_align, dtype, T_rows=None):
+    code = CODE[dtype]
+    p_ref = orc.pack(W, R, keep, k_align, code)
+    p = bsp.bsp_pack(dev(W, dtype), R, torch.from_numpy(np.ascontiguousarray(keep)).cuda(), k_align)
+    pack_equal(p, p_ref)
+    Z = host(bsp.bsp_linear_transposed(dev(U, dtype), p, dev(bias, dtype)))
+    assert Z.shape == (U.shape[0], W.shape[1])
+    for (t0, t1) in (T_rows or [(0, U.shape[0])]):
+        Z_ref, _ = orc.linear_t_packed(U, p_ref, bias, zdt=code, t0=t0, t1=t1, n_threads=8)
+        assert_y_close(Z, Z_ref, dtype, rows=slice(t0, t1))
+    return Z, p_ref
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+@pytest.mark.parametrize("k_align", [1, 8, 32])
+@pytest.mark.parametrize("R,T,M,N,p_keep", [(16, 100, 64, 200, 0.5), (8, 70, 40, 333, 0.2), (32, 130, 96, 256, 0.33),
+                                            (1, 9, 7, 50, 0.5), (3, 65, 12, 100, 0.7), (64, 17, 128, 96, 0.4),
+                                            (4, 33, 36, 515, 0.6), (24, 64, 48, 1024, 0.25)])
+def test_linear_transposed_small_shapes(dtype, k_align, R, T, M, N, p_keep):
+    d = wl.layer(R * 1000 + T + 7, T, M, N, dtype)
+    U = wl.normal(R * 77 + T, (T, M), 1.0, dtype)
+    zb = wl.normal(R * 78 + T, (N,), 0.5, dtype)
+    keep = wl.bernoulli_keep_mask(T + N + 1, M // R, N, p_keep)
+    keep[0, :] = 0                                      # a row-block with nothing kept
+    if M // R > 1:
+        keep[1, :] = 1                                  # a dense row-block
+    keep[:, N // 2] = 0                                 # a column no row-block keeps: the bias alone
+    Z, _ = run_transposed(U, d["W"], zb, R, keep, k_align, dtype)
+    assert bits_equal(Z[:, N // 2], np.broadcast_to(zb[N // 2], (T,)))
+    Z, _ = run_transposed(U, d["W"], None, R, keep, k_align, dtype)
+    assert np.all(Z[:, N // 2] == 0)
+
+
+def test_linear_transposed_seeded_random_shapes():
+    """Sixty seeded draws over block sizes, widths (one column range and several, ragged last range), ragged token
+    counts, densities, alignments, dtypes, empty row-blocks, nothing kept, no bias."""
+    rng = np.random.default_rng(31337)
+    for it in range(60):
+        R = int(rng.choice([16, 16, 16, 32, 32, 64, 8, 4, 24, 12]))
+        B = int(rng.integers(1, 70))
+        M = R * B
+        N = int(rng.choice([32, 64, 200, 256, 257, 520, 768, 1000, 1024, 1032, 2048, 3000, 4096]))
+        T = int(rng.integers(1, 330))
+        dt = str(rng.choice(["bf16", "f16"]))
+        p_keep = float(rng.choice([0.05, 0.2, 0.5, 0.9]))
+        k_align = int(rng.choice([8, 16, 32, 64]))
+        W = wl.normal(2000 + it, (M, N), 0.02, dt)
+        U = wl.normal(3000 + it, (T, M), 1.0, dt)
+        zb = wl.normal(4000 + it, (N,), 0.5, dt) if it % 3 != 0 else None
+        keep = wl.bernoulli_keep_mask(6000 + it, B, N, p_keep)
+        if it % 7 == 0:
+            keep[int(rng.integers(0, B))] = 0
+        if it % 11 == 0:
+            keep[:] = 0
+        case = dict(it=it, R=R, B=B, N=N, T=T, dt=dt, p=p_keep, k_align=k_align, bias=zb is not None)
+        try:
+            run_transposed(U, W, zb, R, keep, k_align, dt)
+        except AssertionError as e:
+            raise AssertionError(f"{case}: {e}")
+
+
+def test_linear_transposed_more_row_blocks_than_one_table_pass():
+    R, B, N, T = 4, 2100, 300, 70
+    W = wl.normal(91, (R * B, N), 0.02, "bf16")
+    U = wl.normal(92, (T, R * B), 1.0, "bf16")
+    run_transposed(U, W, None, R, wl.bernoulli_keep_mask(93, B, N, 0.3), 8, "bf16")
+
+
+def test_linear_transposed_is_the_adjoint_of_the_layer_and_skips_pads():
+    T, M, N, R = 200, 256, 1024, 16
+    d = wl.layer(314, T, M, N, "bf16")
+    U = wl.normal(315, (T, M), 1.0, "bf16")
+    keep = wl.bernoulli_keep_mask(316, M // R, N, 0.3)
+    p = bsp.bsp_pack(dev(d["W"], "bf16"), R, torch.from_numpy(keep).cuda(), 32)
+    Y = bsp.bsp_linear(dev(d["X"], "bf16"), p, None).double().cpu().numpy()
+    Z = bsp.bsp_linear_transposed(dev(U, "bf16"), p, None).double().cpu().numpy()
+    lhs, rhs = float((Y * U).sum()), float((d["X"] * Z).sum())
+    scale = float(np.abs(Y * U).sum())
+    assert abs(lhs - rhs) <= 2e-3 * scale               # both sides carry one bf16 rounding per output
+    # an infinite input meets the pad slots (zero values) of its row-block: they must not be multiplied in
+    Ui = U.copy()
+    Ui[3, 5] = np.inf
+    Zi = host(bsp.bsp_linear_transposed(dev(Ui, "bf16"), p, None))
+    p_ref = orc.pack(d["W"], R, keep, 32, orc.BF16)
+    Zi_ref, _ = orc.linear_t_packed(Ui, p_ref, None, zdt=orc.BF16)
+    assert np.array_equal(np.isnan(Zi), np.isnan(Zi_ref)) and np.array_equal(np.isinf(Zi), np.isinf(Zi_ref))
+    fin = np.isfinite(Zi_ref)
+    assert fin[3].sum() > 0 and (~fin[3]).sum() > 0
+    assert_y_close(np.where(fin, Zi, 0.0), np.where(fin, Zi_ref, 0.0), "bf16")
+
+
+@pytest.mark.parametrize("R", [8, 16, 32])
+def test_config4_bert_large_layer_set_transposed(R):
+    """The input gradient of every BERT-large matrix at the benchmark's token count, on sampled token rows."""
+    for i, d in enumerate(wl.config4(R=R)):
+        W = d["W"]
+        s_ref = orc.sumsq(W, R)
+        k_ref, _ = orc.mask_rank(s_ref, d["n_keep"], orc.SCOPE_MATRIX)
+        T, M = d["X"].shape[0], W.shape[0]
+        U = wl.normal(7000 + 10 * R + i, (T, M), 1.0, "bf16")
+        run_transposed(U, W, None, R, k_ref, 32, "bf16", T_rows=[(0, 40), (5000, 5030), (T - 12, T)])
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_linear_keep_all_is_dense_gemm_keep_none_is_bias(dtype):
     d = wl.layer(77, 96, 64, 160, dtype)
