@@ -8,10 +8,15 @@
 //
 // Per row-block the product is a small dense one (tokens x R times R x kept columns) whose
 // result is scattered to the kept columns' positions.  A workgroup owns a tile of tokens x a
-// range of output columns as fp32 sums in LDS; its wavefronts walk the row-blocks, take the
-// kept columns that fall into the range 16 at a time through the matrix cores (contraction
-// depth R), and add the 16 x 16 results into the tile with LDS atomics, so no sum leaves the
-// compute unit before it is complete.  The tile is rounded once on the way out.
+// range of output columns as fp32 sums in LDS and walks the row-blocks; the kept columns of a
+// row-block that fall into the range go through the matrix cores 16 at a time (contraction
+// depth R), one such group and half of the tokens per wavefront, and the 16 x 16 results are
+// added to the tile with a plain read, add and write: inside one row-block the kept columns
+// are distinct, so no two wavefronts touch the same cell, and a workgroup barrier separates the
+// additions of one row-block from those of the next.  (LDS floating-point atomics would allow
+// any split of the work, but one ds_add_f32 of 64 lanes was measured at about 200 clocks here,
+// twelve times the read, add and write.)  No sum leaves the compute unit before it is complete;
+// the tile is rounded once on the way out.
 #include "bsp_common.h"
 
 namespace bsp {
@@ -21,12 +26,16 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kTok = 64;            // tokens per workgroup
+constexpr int kTok = 64;            // tokens per workgroup: two halves of 32
 constexpr int kCols = 256;          // output columns per workgroup
-constexpr int kPitch = kCols + 1;   // tile row pitch in words: the 16 tokens of one scatter hit 16 different banks
-constexpr int kWaves = 8;
+constexpr int kPitch = kTok + 4;    // tile pitch in words, one row per column: 16 columns at 4 tokens each reach all banks
+constexpr int kTileWords = (kCols + 1) * kPitch;  // row kCols is spare: lanes without a column add there
+constexpr int kWaves = 8;           // wavefront w: token half w % 2, group w / 2 of every four groups
 constexpr int kThreads = kWaves * kWave;
-constexpr int kTable = 1024;        // row-blocks per pass over the range table
+constexpr int kTable = 256;         // row-blocks per pass: one per thread (of the first 256) when the table is built
+constexpr int kMaxSlots = (kCols + 3 + 63) / 64;  // slots of a row-block: 64 positions each, the first aligned down to 4
+constexpr int kMaxSteps = kTable * kMaxSlots;
+constexpr int kDepth = 3;           // steps whose operands are in flight ahead of the one being computed
 
 template <int DT>
 struct mfma16;
@@ -45,10 +54,6 @@ struct mfma16<BSP_F16> {
     }
 };
 
-__device__ __forceinline__ void lds_add(float *p, float v) {
-    (void)__hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-}
-
 // first position p in [0, n) with a[p] >= key (a ascending), n if none
 __device__ __forceinline__ int lower_bound(const int32_t *__restrict__ a, int n, int key) {
     int lo = 0, hi = n;
@@ -63,12 +68,26 @@ __device__ __forceinline__ int lower_bound(const int32_t *__restrict__ a, int n,
 // Matrix-core kernel.  16-bit values, R % 4 == 0, R <= 64, k_align % 4 == 0, U 8-byte aligned.
 // grid.x = token tiles, grid.y = column ranges.  NK = contraction chunks of 16 (ceil(R / 16)).
 //
-// v_mfma_f32_16x16x16 with A = the value panel transposed (row = kept column, k = r) and
-// B = U (k = r, column = token): lane l supplies A[l % 16][4 (l / 16) ..+3] and
-// B[4 (l / 16) ..+3][l % 16], the latter four consecutive elements of a row of U; it receives
-// D[4 (l / 16) + i][l % 16], i.e. four kept columns of one token.
+// v_mfma_f32_16x16x16 with A = U (row = token, k = r) and B = the value panel (k = r, column =
+// kept column): lane l supplies A[l % 16][4 (l / 16) ..+3], four consecutive elements of a row
+// of U, and B[4 (l / 16) ..+3][l % 16]; it receives D[4 (l / 16) + i][l % 16], i.e. four
+// consecutive tokens of one kept column, which lie side by side in the tile (one row per
+// column): one 16-byte LDS read and one write add them.
+//
+// The work of a workgroup is a sequence of steps (row-block, slot): in a step wavefront w takes
+// group 4 slot + w / 2 of the row-block's groups of 16 kept columns (if there is one) for its
+// 32 tokens.  The sequence is written to LDS once per pass, it is the same for all wavefronts,
+// its loads are issued kDepth steps ahead into a ring of registers, and the barrier falls after
+// the last slot of a row-block.  A step has no branches: a lane or a wavefront without work
+// loads from clamped addresses, multiplies zeros and adds to a spare cell of its tile row.
 // ---------------------------------------------------------------------------------------
-template <int DT, int NK>
+struct BlockEntry {  // one row-block as seen from a column range
+    uint32_t lohi;   // positions [lo, hi) of its kept columns inside the range: lo | hi << 16
+    uint32_t base;   // blk_ptr[b]
+    uint32_t kp;     // padded number of kept columns: row pitch of the value panel
+};
+
+template <int DT, int NK, bool FULLK>  // FULLK: R == 16 NK, no lane of the contraction is past R
 __global__ __launch_bounds__(kThreads) void linear_t_mfma_kernel(const uint16_t *__restrict__ U, int64_t T, int64_t M,
                                                                  int64_t N, int64_t B, int32_t R,
                                                                  const int32_t *__restrict__ blk_cnt,
@@ -77,115 +96,158 @@ __global__ __launch_bounds__(kThreads) void linear_t_mfma_kernel(const uint16_t 
                                                                  const uint16_t *__restrict__ vals,
                                                                  const void *__restrict__ bias, void *__restrict__ Z) {
     extern __shared__ __align__(16) unsigned char smem[];
-    float *tile = reinterpret_cast<float *>(smem);                                    // [kTok][kPitch]
-    uint32_t *range = reinterpret_cast<uint32_t *>(smem + sizeof(float) * kTok * kPitch);  // [kTable]: lo | hi << 16
+    float *tile = reinterpret_cast<float *>(smem);  // [kCols + 1][kPitch]: cell of (column c, token t) at c kPitch + t
+    BlockEntry *table = reinterpret_cast<BlockEntry *>(smem + sizeof(float) * kTileWords);  // [kTable]
+    uint16_t *steps = reinterpret_cast<uint16_t *>(table + kTable);  // [kMaxSteps]: block | slot << 9 | last << 12
+    __shared__ int wave_sum[kWaves];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, kg = lane >> 4;
+    const int half = wave & 1, gsel = wave >> 1;
     const int64_t t0 = (int64_t)blockIdx.x * kTok;
     const int cr0 = (int)blockIdx.y * kCols;
 
-    for (int i = tid; i < kTok * kPitch; i += kThreads) tile[i] = 0.0f;
+    for (int i = tid; i < kTileWords; i += kThreads) tile[i] = 0.0f;
 
-    // this lane's rows of U (B operand), one per 16-token sub-tile; tokens past T read row 0 and are zeroed
-    const uint16_t *urow[4];
-    bool tok_ok[4];
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-        const int64_t t = t0 + 16 * s + l16;
-        tok_ok[s] = t < T;
-        urow[s] = U + (tok_ok[s] ? t : 0) * M + 4 * kg;
-    }
+    // this lane's two rows of U (A operands); a token past T reads row 0, and what it yields is never written out
+    const int64_t ta = t0 + 32 * half + l16, tb = ta + 16;
+    const uint16_t *urow_a = U + (ta < T ? ta : 0) * M;
+    const uint16_t *urow_b = U + (tb < T ? tb : 0) * M;
+    const int tcell = 32 * half + 4 * kg;  // the four tokens whose sums this lane receives, inside a tile row
+    const int spare = kCols * kPitch + tcell;
 
     for (int64_t bc = 0; bc < B; bc += kTable) {
         const int nb = (int)((B - bc) < kTable ? (B - bc) : kTable);
-        __syncthreads();  // the tile is zeroed / the previous pass has read the table
-        for (int i = tid; i < nb; i += kThreads) {
-            const int64_t b = bc + i;
-            const int32_t *cols = col_idx + blk_ptr[b];
+        __syncthreads();  // the tile is zeroed / the previous pass is done with the table
+        // Thread q describes the q-th row-block of this pass's order, which starts at another row-block in every
+        // workgroup: the workgroups resident at one time then do not all ask for the same value panels and the
+        // same column slice of U at once.
+        const int rot = (int)(((blockIdx.x + 5u * blockIdx.y) * 8u) % (unsigned)nb);
+        int my_i = 0, my_slots = 0;
+        if (tid < nb) {  // nb <= kTable
+            my_i = tid + rot < nb ? tid + rot : tid + rot - nb;
+            const int64_t b = bc + my_i;
+            const int32_t base = blk_ptr[b];
+            const int32_t *cols = col_idx + base;
             const int k = blk_cnt[b];
             const int lo = k ? lower_bound(cols, k, cr0) : 0;
             const int hi = k ? lower_bound(cols, k, cr0 + kCols) : 0;
-            range[i] = (uint32_t)lo | ((uint32_t)hi << 16);
+            table[my_i].lohi = (uint32_t)lo | ((uint32_t)hi << 16);
+            table[my_i].base = (uint32_t)base;
+            table[my_i].kp = (uint32_t)(blk_ptr[b + 1] - base);
+            my_slots = hi > lo ? (hi - (lo & ~3) + 63) >> 6 : 0;
         }
+        // exclusive prefix sum of the slots over the threads: where each row-block's steps go
+        int incl = my_slots;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int up = __shfl_up(incl, d, 64);
+            if (lane >= d) incl += up;
+        }
+        if (lane == 63) wave_sum[wave] = incl;
         __syncthreads();
+        int first = incl - my_slots, total = 0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            const int ws = wave_sum[w];
+            if (w < wave) first += ws;
+            total += ws;
+        }
+        for (int sl = 0; sl < my_slots; ++sl)
+            steps[first + sl] = (uint16_t)(my_i | (sl << 9) | ((sl + 1 == my_slots) << 12));
+        __syncthreads();
+        if (total == 0) continue;  // uniform: nothing of this pass falls into the range
 
-        for (int i = wave; i < nb; i += kWaves) {
-            const uint32_t lh = __builtin_amdgcn_readfirstlane(range[i]);
-            const int lo = (int)(lh & 0xffffu), hi = (int)(lh >> 16);
-            if (lo >= hi) continue;
-            const int64_t b = bc + i;
-            const int64_t base = blk_ptr[b];
-            const int kp = blk_ptr[b + 1] - blk_ptr[b];
-            const int32_t *cols = col_idx + base;
-            const uint16_t *panel = vals + (int64_t)R * base;
+        // ring of operands in flight
+        uint32_t ra[kDepth][NK][4];  // four values of the panel, one per 16-bit load
+        int rc[kDepth];              // the kept column whose sums this lane receives
+        uint2 rua[kDepth][NK], rub[kDepth][NK];
+        int s_lo[kDepth], s_hi[kDepth], s_g0[kDepth], s_last[kDepth];
 
-            uint2 ub[NK][4];
+        auto produce = [&](int st, int k) {
+            const uint32_t code = __builtin_amdgcn_readfirstlane((uint32_t)steps[k < total ? k : total - 1]);
+            const int i = (int)(code & 511u), slot = (int)((code >> 9) & 7u);
+            const BlockEntry e = table[i];
+            const uint32_t lohi = __builtin_amdgcn_readfirstlane(e.lohi);
+            const uint32_t base = __builtin_amdgcn_readfirstlane(e.base);
+            const uint32_t kp = __builtin_amdgcn_readfirstlane(e.kp);
+            const int lo = (int)(lohi & 0xffffu), hi = (int)(lohi >> 16);
+            const int g0 = (lo & ~3) + 16 * (4 * slot + gsel);
+            s_lo[st] = lo;
+            s_hi[st] = hi;
+            s_g0[st] = g0;
+            s_last[st] = (int)(code >> 12);
+            // every address is clamped into the row-block's own data; what a clamped lane loads is never used
+            const int gq = g0 < hi ? g0 : (lo & ~3);
+            const int pa = gq + l16;
+            const uint32_t pc = (uint32_t)((pa >= lo && pa < hi) ? pa : lo);
 #pragma unroll
             for (int kc = 0; kc < NK; ++kc) {
-                const bool k_ok = 16 * kc + 4 * kg < R;
-#pragma unroll
-                for (int s = 0; s < 4; ++s) {
-                    ub[kc][s] = make_uint2(0u, 0u);
-                    if (k_ok && tok_ok[s]) ub[kc][s] = *reinterpret_cast<const uint2 *>(urow[s] + b * R + 16 * kc);
-                }
+                const uint32_t r = (FULLK || 16 * kc + 4 * kg < R) ? 16 * kc + 4 * kg : 0;
+                const uint32_t q = (uint32_t)R * base + pc + r * kp;  // element index: fits (at most R * capacity)
+                ra[st][kc][0] = vals[q];
+                ra[st][kc][1] = vals[q + kp];
+                ra[st][kc][2] = vals[q + 2 * kp];
+                ra[st][kc][3] = vals[q + 3 * kp];
             }
+            rc[st] = col_idx[base + pc];
+            const uint32_t uoff = (uint32_t)(bc + i) * (uint32_t)R;  // < M
+#pragma unroll
+            for (int kc = 0; kc < NK; ++kc) {
+                // a lane past R reads the row-block's first rows
+                const uint32_t ko = (FULLK || 16 * kc + 4 * kg < R) ? 16 * kc + 4 * kg : 0;
+                rua[st][kc] = *reinterpret_cast<const uint2 *>(urow_a + (uoff + ko));
+                rub[st][kc] = *reinterpret_cast<const uint2 *>(urow_b + (uoff + ko));
+            }
+        };
+        auto consume = [&](int st) {
+            const int pa = s_g0[st] + l16;
+            const bool a_ok = pa >= s_lo[st] && pa < s_hi[st];  // false in every lane of a wavefront without a group
+            f32x4 acc_a = {0.f, 0.f, 0.f, 0.f}, acc_b = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kc = 0; kc < NK; ++kc) {
+                uint2 bv = make_uint2(ra[st][kc][0] | (ra[st][kc][1] << 16), ra[st][kc][2] | (ra[st][kc][3] << 16));
+                if (!FULLK && !(16 * kc + 4 * kg < R)) bv = make_uint2(0u, 0u);  // the contraction ends at R
+                acc_a = mfma16<DT>::run(rua[st][kc], bv, acc_a);
+                acc_b = mfma16<DT>::run(rub[st][kc], bv, acc_b);
+            }
+            // a lane without a column has multiplied clamped loads; its sums go to the spare row
+            const int cell = a_ok ? (rc[st] - cr0) * kPitch + tcell : spare;
+            f32x4 *pa4 = reinterpret_cast<f32x4 *>(tile + cell), *pb4 = reinterpret_cast<f32x4 *>(tile + cell + 16);
+            const f32x4 old_a = *pa4, old_b = *pb4;
+            *pa4 = old_a + acc_a;  // the kept columns of a row-block are distinct: no other lane has this cell
+            *pb4 = old_b + acc_b;
+            if (s_last[st]) __syncthreads();  // uniform; the next row-block may keep the same columns
+        };
 
-            for (int g0 = lo & ~3; g0 < hi; g0 += 16) {
-                // A operand: kept column g0 + l16, rows 16 kc + 4 kg ..+3 of the panel
-                const int pa = g0 + l16;
-                const bool a_ok = pa >= lo && pa < hi;
-                const uint16_t *ap = panel + (a_ok ? pa : lo);
-                uint2 av[NK];
 #pragma unroll
-                for (int kc = 0; kc < NK; ++kc) {
-                    const int r = 16 * kc + 4 * kg;
-                    av[kc] = make_uint2(0u, 0u);
-                    if (a_ok && r < R) {
-                        const uint16_t *q = ap + (int64_t)r * kp;
-                        av[kc].x = (uint32_t)q[0] | ((uint32_t)q[kp] << 16);
-                        av[kc].y = (uint32_t)q[2 * (int64_t)kp] | ((uint32_t)q[3 * (int64_t)kp] << 16);
-                    }
-                }
-                // the four kept columns whose sums this lane receives
-                const int pd = g0 + 4 * kg;
-                int4 cd = make_int4(0, 0, 0, 0);
-                if (pd < hi) cd = *reinterpret_cast<const int4 *>(cols + pd);  // pd + 3 < kp: kp % 4 == 0
-                const int cdv[4] = {cd.x, cd.y, cd.z, cd.w};
-
-                f32x4 acc[4];
+        for (int st = 0; st < kDepth; ++st) produce(st, st);
+        int k0 = 0;
+        for (; k0 + kDepth <= total; k0 += kDepth) {
 #pragma unroll
-                for (int s = 0; s < 4; ++s) {
-                    acc[s] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                    for (int kc = 0; kc < NK; ++kc) acc[s] = mfma16<DT>::run(av[kc], ub[kc][s], acc[s]);
-                }
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const int p = pd + v;
-                    if (p >= lo && p < hi) {
-                        float *dst = tile + l16 * kPitch + (cdv[v] - cr0);
-#pragma unroll
-                        for (int s = 0; s < 4; ++s) lds_add(dst + 16 * s * kPitch, acc[s][v]);
-                    }
-                }
+            for (int st = 0; st < kDepth; ++st) {
+                consume(st);
+                produce(st, k0 + st + kDepth);
             }
         }
+#pragma unroll
+        for (int st = 0; st < kDepth; ++st)
+            if (k0 + st < total) consume(st);
     }
     __syncthreads();
 
-    // write the tile out: bias added in fp32, one rounding
+    // write the tile out: bias added in fp32, one rounding.  Consecutive lanes take consecutive tokens (consecutive
+    // banks); a lane writes 8 columns of its token's row.
     const int ncol = (int)((N - cr0) < kCols ? (N - cr0) : kCols);
     if (ncol == kCols && (N & 7) == 0 && (reinterpret_cast<uintptr_t>(Z) & 15) == 0) {
-        // 8 columns per lane: a wavefront writes two rows of 512 bytes
         for (int i = tid; i < kTok * (kCols / 8); i += kThreads) {
-            const int tok = i / (kCols / 8), c8 = (i % (kCols / 8)) * 8;
+            const int tok = i % kTok, c8 = (i / kTok) * 8;
             const int64_t t = t0 + tok;
             if (t >= T) continue;
             uint32_t w[4];
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                float v0 = tile[tok * kPitch + c8 + 2 * q], v1 = tile[tok * kPitch + c8 + 2 * q + 1];
+                float v0 = tile[(c8 + 2 * q) * kPitch + tok], v1 = tile[(c8 + 2 * q + 1) * kPitch + tok];
                 if (bias) {
                     v0 += elem<DT>::load(bias, cr0 + c8 + 2 * q);
                     v1 += elem<DT>::load(bias, cr0 + c8 + 2 * q + 1);
@@ -196,10 +258,10 @@ __global__ __launch_bounds__(kThreads) void linear_t_mfma_kernel(const uint16_t 
         }
     } else {
         for (int i = tid; i < kTok * kCols; i += kThreads) {
-            const int tok = i / kCols, c = i % kCols;
+            const int tok = i % kTok, c = i / kTok;
             const int64_t t = t0 + tok;
             if (t >= T || c >= ncol) continue;
-            float v = tile[tok * kPitch + c];
+            float v = tile[c * kPitch + tok];
             if (bias) v += elem<DT>::load(bias, cr0 + c);
             elem<DT>::store(Z, t * N + cr0 + c, v);
         }
@@ -210,7 +272,7 @@ __global__ __launch_bounds__(kThreads) void linear_t_mfma_kernel(const uint16_t 
 // General kernel: any dtype, any R in [1, 64], any k_align.  Same tile, fp32 fused
 // multiply-adds; a thread owns one kept column of the row-block at a time and walks the tokens.
 // ---------------------------------------------------------------------------------------
-constexpr int kGenTok = 32, kGenThreads = 256;
+constexpr int kGenTok = 32, kGenThreads = 256, kGenPitch = kCols + 1;
 
 template <int DT>
 __global__ __launch_bounds__(kGenThreads) void linear_t_general_kernel(const void *__restrict__ U, int64_t T, int64_t M,
@@ -221,12 +283,12 @@ __global__ __launch_bounds__(kGenThreads) void linear_t_general_kernel(const voi
                                                                       const void *__restrict__ vals,
                                                                       const void *__restrict__ bias,
                                                                       void *__restrict__ Z) {
-    __shared__ float tile[kGenTok][kPitch];
+    __shared__ float tile[kGenTok][kGenPitch];
     __shared__ float us[kGenTok][64];
     const int tid = threadIdx.x;
     const int64_t t0 = (int64_t)blockIdx.x * kGenTok;
     const int cr0 = (int)blockIdx.y * kCols;
-    for (int i = tid; i < kGenTok * kPitch; i += kGenThreads) (&tile[0][0])[i] = 0.0f;
+    for (int i = tid; i < kGenTok * kGenPitch; i += kGenThreads) (&tile[0][0])[i] = 0.0f;
     for (int64_t b = 0; b < B; ++b) {
         const int k = blk_cnt[b];
         if (k == 0) continue;  // uniform over the workgroup
@@ -267,29 +329,32 @@ __global__ __launch_bounds__(kGenThreads) void linear_t_general_kernel(const voi
     }
 }
 
-template <int DT>
-void launch_mfma(int nk, dim3 grid, size_t lds, hipStream_t s, const uint16_t *U, int64_t T, int64_t M, int64_t N,
-                 int64_t B, int32_t R, const int32_t *blk_cnt, const int32_t *blk_ptr, const int32_t *col_idx,
-                 const uint16_t *vals, const void *bias, void *Z) {
-#define BSP_LT_CASE(NK)                                                                                             \
-    case NK: {                                                                                                      \
-        auto k = linear_t_mfma_kernel<DT, NK>;                                                                      \
-        static bool raised = false; /* per instantiation: dynamic LDS above 64 KB must be asked for once */         \
-        if (!raised) {                                                                                              \
-            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, \
-                                      (int)lds);                                                                    \
-            raised = true;                                                                                          \
-        }                                                                                                           \
-        k<<<grid, kThreads, lds, s>>>(U, T, M, N, B, R, blk_cnt, blk_ptr, col_idx, vals, bias, Z);                  \
-    } break;
-    switch (nk) {
-        BSP_LT_CASE(1)
-        BSP_LT_CASE(2)
-        BSP_LT_CASE(3)
-        default:
-        BSP_LT_CASE(4)
+template <int DT, int NK, bool FULLK>
+void launch_mfma_one(dim3 grid, size_t lds, hipStream_t s, const uint16_t *U, int64_t T, int64_t M, int64_t N,
+                     int64_t B, int32_t R, const int32_t *blk_cnt, const int32_t *blk_ptr, const int32_t *col_idx,
+                     const uint16_t *vals, const void *bias, void *Z) {
+    auto k = linear_t_mfma_kernel<DT, NK, FULLK>;
+    static bool raised = false;  // per instantiation: dynamic LDS above 64 KB must be asked for once
+    if (!raised) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)lds);
+        raised = true;
     }
-#undef BSP_LT_CASE
+    k<<<grid, kThreads, lds, s>>>(U, T, M, N, B, R, blk_cnt, blk_ptr, col_idx, vals, bias, Z);
+}
+
+template <int DT>
+void launch_mfma(dim3 grid, size_t lds, hipStream_t s, const uint16_t *U, int64_t T, int64_t M, int64_t N, int64_t B,
+                 int32_t R, const int32_t *blk_cnt, const int32_t *blk_ptr, const int32_t *col_idx,
+                 const uint16_t *vals, const void *bias, void *Z) {
+#define BSP_LT_ARGS grid, lds, s, U, T, M, N, B, R, blk_cnt, blk_ptr, col_idx, vals, bias, Z
+    switch ((R + 15) / 16) {
+        case 1: R == 16 ? launch_mfma_one<DT, 1, true>(BSP_LT_ARGS) : launch_mfma_one<DT, 1, false>(BSP_LT_ARGS); break;
+        case 2: R == 32 ? launch_mfma_one<DT, 2, true>(BSP_LT_ARGS) : launch_mfma_one<DT, 2, false>(BSP_LT_ARGS); break;
+        case 3: R == 48 ? launch_mfma_one<DT, 3, true>(BSP_LT_ARGS) : launch_mfma_one<DT, 3, false>(BSP_LT_ARGS); break;
+        default: R == 64 ? launch_mfma_one<DT, 4, true>(BSP_LT_ARGS) : launch_mfma_one<DT, 4, false>(BSP_LT_ARGS); break;
+    }
+#undef BSP_LT_ARGS
 }
 
 }  // namespace
@@ -310,19 +375,19 @@ extern "C" int bsp_linear_transposed(const void *U, int udt, int64_t T, int64_t 
     const int64_t ranges = (N + kCols - 1) / kCols;
     if (ranges > 65535 || N > 65535) return BSP_ERR_SHAPE;  // kept-column positions travel as 16 bits
     hipStream_t s = (hipStream_t)stream;
+    // the matrix-core kernel indexes the storage with 32 bits: at most M (N + k_align) values
     const bool mfma_ok = udt != BSP_F32 && R % 4 == 0 && k_align % 4 == 0 && col_idx && vals && aligned(U, 8) &&
-                         aligned(col_idx, 16);
+                         aligned(col_idx, 16) && (double)M * (double)(N + 64) < 4.0e9;
     if (mfma_ok) {
         const int64_t tiles = (T + kTok - 1) / kTok;
         if (tiles >= ((int64_t)1 << 31)) return BSP_ERR_SHAPE;
         const dim3 grid((unsigned)tiles, (unsigned)ranges);
-        const size_t lds = sizeof(float) * kTok * kPitch + sizeof(uint32_t) * kTable;
-        const int nk = (R + 15) / 16;
+        const size_t lds = sizeof(float) * kTileWords + sizeof(BlockEntry) * kTable + sizeof(uint16_t) * kMaxSteps;
         if (udt == BSP_BF16)
-            launch_mfma<BSP_BF16>(nk, grid, lds, s, (const uint16_t *)U, T, M, N, B, R, blk_cnt, blk_ptr, col_idx,
+            launch_mfma<BSP_BF16>(grid, lds, s, (const uint16_t *)U, T, M, N, B, R, blk_cnt, blk_ptr, col_idx,
                                   (const uint16_t *)vals, bias, Z);
         else
-            launch_mfma<BSP_F16>(nk, grid, lds, s, (const uint16_t *)U, T, M, N, B, R, blk_cnt, blk_ptr, col_idx,
+            launch_mfma<BSP_F16>(grid, lds, s, (const uint16_t *)U, T, M, N, B, R, blk_cnt, blk_ptr, col_idx,
                                  (const uint16_t *)vals, bias, Z);
     } else {
         const int64_t tiles = (T + kGenTok - 1) / kGenTok;
