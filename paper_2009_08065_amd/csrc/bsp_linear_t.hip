@@ -25,17 +25,24 @@ namespace {
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kTok = 64;            // tokens per workgroup: two halves of 32
 constexpr int kCols = 256;          // output columns per workgroup
-constexpr int kPitch = kTok + 4;    // tile pitch in words, one row per column: 16 columns at 4 tokens each reach all banks
-constexpr int kTileWords = (kCols + 1) * kPitch;  // row kCols is spare: lanes without a column add there
-constexpr int kWaves = 8;           // wavefront w: token half w % 2, group w / 2 of every four groups
+constexpr int kTileWords = (kCols + 1) * kTok;  // one row per column; row kCols is spare: lanes without a column add there
+constexpr int kWaves = 8;           // wavefront w: token half w % 2, group w / 2 of the step's four groups
 constexpr int kThreads = kWaves * kWave;
-constexpr int kTable = 256;         // row-blocks per pass: one per thread (of the first 256) when the table is built
+constexpr int kTable = 128;         // row-blocks per pass: one per thread (of the first 128) when the table is built
 constexpr int kMaxSlots = (kCols + 3 + 63) / 64;  // slots of a row-block: 64 positions each, the first aligned down to 4
 constexpr int kMaxSteps = kTable * kMaxSlots;
-constexpr int kDepth = 3;           // steps whose operands are in flight ahead of the one being computed
+constexpr int kDepth = 4;           // steps whose operands are on their way from memory (even: LDS buffers alternate)
+
+// LDS bytes of the matrix-core kernel for NK contraction chunks of 16: tile, table, step list, two operand buffers
+constexpr int stage_pitch(int nk) { return 32 * nk + 8; }  // bytes per position / per token: 16 nk values and a pad
+constexpr size_t stage_bytes(int nk) { return (size_t)2 * 64 * stage_pitch(nk); }  // value panel and U piece
+constexpr size_t mfma_lds_bytes(int nk) {
+    return sizeof(float) * kTileWords + 12 * kTable + 2 * kMaxSteps + 2 * stage_bytes(nk);
+}
 
 template <int DT>
 struct mfma16;
@@ -65,21 +72,26 @@ __device__ __forceinline__ int lower_bound(const int32_t *__restrict__ a, int n,
 }
 
 // ---------------------------------------------------------------------------------------
-// Matrix-core kernel.  16-bit values, R % 4 == 0, R <= 64, k_align % 4 == 0, U 8-byte aligned.
+// Matrix-core kernel.  16-bit values, R % 4 == 0, R <= 64, k_align % 8 == 0, U 4-byte aligned.
 // grid.x = token tiles, grid.y = column ranges.  NK = contraction chunks of 16 (ceil(R / 16)).
 //
 // v_mfma_f32_16x16x16 with A = U (row = token, k = r) and B = the value panel (k = r, column =
-// kept column): lane l supplies A[l % 16][4 (l / 16) ..+3], four consecutive elements of a row
-// of U, and B[4 (l / 16) ..+3][l % 16]; it receives D[4 (l / 16) + i][l % 16], i.e. four
-// consecutive tokens of one kept column, which lie side by side in the tile (one row per
-// column): one 16-byte LDS read and one write add them.
+// kept column): lane l supplies A[l % 16][4 (l / 16) ..+3] and B[4 (l / 16) ..+3][l % 16]; it
+// receives D[4 (l / 16) + i][l % 16], i.e. four consecutive tokens of one kept column, which
+// lie side by side in the tile (one row per column, rotated by 4 (column % 16) words so that
+// the 16 columns of a group reach all banks): one 16-byte LDS read and one write add them.
 //
-// The work of a workgroup is a sequence of steps (row-block, slot): in a step wavefront w takes
-// group 4 slot + w / 2 of the row-block's groups of 16 kept columns (if there is one) for its
-// 32 tokens.  The sequence is written to LDS once per pass, it is the same for all wavefronts,
-// its loads are issued kDepth steps ahead into a ring of registers, and the barrier falls after
-// the last slot of a row-block.  A step has no branches: a lane or a wavefront without work
-// loads from clamped addresses, multiplies zeros and adds to a spare cell of its tile row.
+// The work of a workgroup is a sequence of steps (row-block, slot), a slot being 64 positions
+// of the row-block's kept columns in the range, i.e. four groups of 16: in a step wavefront w
+// takes group w / 2 for its 32 tokens.  The sequence is written to LDS once per pass.  The
+// operands of a step are fetched by the whole workgroup, 4 bytes per thread and operand with
+// whole cache lines per instruction (the address unit, not the matrix cores, bounds this
+// kernel): the R x 64 piece of the value panel and the 64 x R piece of U go kDepth steps ahead
+// into registers, one step ahead into LDS (the panel transposed on the way), and from there
+// every wavefront reads its operands with one 8-byte read each.  A barrier ends every step: it
+// orders the additions of one row-block before those of the next and the LDS buffers' reuse.
+// A step has no branches: a lane without work loads from clamped addresses and adds to the
+// spare row of the tile.
 // ---------------------------------------------------------------------------------------
 struct BlockEntry {  // one row-block as seen from a column range
     uint32_t lohi;   // positions [lo, hi) of its kept columns inside the range: lo | hi << 16
@@ -87,7 +99,11 @@ struct BlockEntry {  // one row-block as seen from a column range
     uint32_t kp;     // padded number of kept columns: row pitch of the value panel
 };
 
-template <int DT, int NK, bool FULLK>  // FULLK: R == 16 NK, no lane of the contraction is past R
+struct StepMeta {  // wave-uniform description of a step
+    int lo, hi, gbase;  // the row-block's range and the first position of the slot
+};
+
+template <int DT, int NK, bool FULLK>  // FULLK: R == 16 NK, no row of the contraction is past R
 __global__ __launch_bounds__(kThreads) void linear_t_mfma_kernel(const uint16_t *__restrict__ U, int64_t T, int64_t M,
                                                                  int64_t N, int64_t B, int32_t R,
                                                                  const int32_t *__restrict__ blk_cnt,
@@ -95,10 +111,13 @@ __global__ __launch_bounds__(kThreads) void linear_t_mfma_kernel(const uint16_t 
                                                                  const int32_t *__restrict__ col_idx,
                                                                  const uint16_t *__restrict__ vals,
                                                                  const void *__restrict__ bias, void *__restrict__ Z) {
+    constexpr int kSP = stage_pitch(NK);
     extern __shared__ __align__(16) unsigned char smem[];
-    float *tile = reinterpret_cast<float *>(smem);  // [kCols + 1][kPitch]: cell of (column c, token t) at c kPitch + t
+    float *tile = reinterpret_cast<float *>(smem);  // cell of (column c, token t): c kTok + (t + 4 c) % kTok
     BlockEntry *table = reinterpret_cast<BlockEntry *>(smem + sizeof(float) * kTileWords);  // [kTable]
-    uint16_t *steps = reinterpret_cast<uint16_t *>(table + kTable);  // [kMaxSteps]: block | slot << 9 | last << 12
+    uint16_t *steps = reinterpret_cast<uint16_t *>(table + kTable);  // [kMaxSteps]: block | slot << 9
+    unsigned char *stage = reinterpret_cast<unsigned char *>(steps + kMaxSteps);
+    // buffer p: value panel [64 positions][kSP] at stage + p stage_bytes, U piece [64 tokens][kSP] behind it
     __shared__ int wave_sum[kWaves];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -109,16 +128,23 @@ __global__ __launch_bounds__(kThreads) void linear_t_mfma_kernel(const uint16_t 
 
     for (int i = tid; i < kTileWords; i += kThreads) tile[i] = 0.0f;
 
-    // this lane's two rows of U (A operands); a token past T reads row 0, and what it yields is never written out
-    const int64_t ta = t0 + 32 * half + l16, tb = ta + 16;
-    const uint16_t *urow_a = U + (ta < T ? ta : 0) * M;
-    const uint16_t *urow_b = U + (tb < T ? tb : 0) * M;
-    const int tcell = 32 * half + 4 * kg;  // the four tokens whose sums this lane receives, inside a tile row
-    const int spare = kCols * kPitch + tcell;
+    // as a loader: two positions of panel row 16 j + tid / 32, and two elements of token tid / 8
+    const int ld_row = tid >> 5, ld_pos = (tid & 31) * 2;
+    const int ld_tok = tid >> 3, ld_el = (tid & 7) * 2;
+    const uint16_t *ld_urow = U + (t0 + ld_tok < T ? t0 + ld_tok : 0) * M;  // a token past T reads row 0
+    // byte offsets inside a buffer.  Lanes l and l + 32 hold rows 2 wave and 2 wave + 1 of the same two positions:
+    // they exchange halves, so that each writes one position's pair of rows as one word.
+    const bool upper = lane >= 32;
+    const int st_v = (ld_pos + (upper ? 1 : 0)) * kSP + wave * 4;
+    const int st_u = 64 * kSP + ld_tok * kSP + ld_el * 2;
+    // as a consumer
+    const int rd_b = (16 * gsel + l16) * kSP + kg * 8;
+    const int rd_a = 64 * kSP + (32 * half + l16) * kSP + kg * 8;
+    const int tcell = 32 * half + 4 * kg;  // the four tokens whose sums this lane receives
 
     for (int64_t bc = 0; bc < B; bc += kTable) {
         const int nb = (int)((B - bc) < kTable ? (B - bc) : kTable);
-        __syncthreads();  // the tile is zeroed / the previous pass is done with the table
+        __syncthreads();  // the tile is zeroed / the previous pass is done with the table and the buffers
         // Thread q describes the q-th row-block of this pass's order, which starts at another row-block in every
         // workgroup: the workgroups resident at one time then do not all ask for the same value panels and the
         // same column slice of U at once.
@@ -153,92 +179,112 @@ __global__ __launch_bounds__(kThreads) void linear_t_mfma_kernel(const uint16_t 
             if (w < wave) first += ws;
             total += ws;
         }
-        for (int sl = 0; sl < my_slots; ++sl)
-            steps[first + sl] = (uint16_t)(my_i | (sl << 9) | ((sl + 1 == my_slots) << 12));
+        for (int sl = 0; sl < my_slots; ++sl) steps[first + sl] = (uint16_t)(my_i | (sl << 9));
         __syncthreads();
         if (total == 0) continue;  // uniform: nothing of this pass falls into the range
 
-        // ring of operands in flight
-        uint32_t ra[kDepth][NK][4];  // four values of the panel, one per 16-bit load
-        int rc[kDepth];              // the kept column whose sums this lane receives
-        uint2 rua[kDepth][NK], rub[kDepth][NK];
-        int s_lo[kDepth], s_hi[kDepth], s_g0[kDepth], s_last[kDepth];
+        // ring of loads on their way, slot s: the steps k with k % kDepth == s
+        uint32_t rv[kDepth][NK], ru[kDepth][NK];  // this thread's pieces of the value panel and of U
+        int rc[kDepth];                           // the kept column whose sums this lane receives
+        StepMeta rm[kDepth];
 
-        auto produce = [&](int st, int k) {
+        auto issue = [&](int s, int k) {  // the loads of step k (clamped to the last one)
             const uint32_t code = __builtin_amdgcn_readfirstlane((uint32_t)steps[k < total ? k : total - 1]);
-            const int i = (int)(code & 511u), slot = (int)((code >> 9) & 7u);
+            const int i = (int)(code & 511u), slot = (int)(code >> 9);
             const BlockEntry e = table[i];
             const uint32_t lohi = __builtin_amdgcn_readfirstlane(e.lohi);
             const uint32_t base = __builtin_amdgcn_readfirstlane(e.base);
             const uint32_t kp = __builtin_amdgcn_readfirstlane(e.kp);
             const int lo = (int)(lohi & 0xffffu), hi = (int)(lohi >> 16);
-            const int g0 = (lo & ~3) + 16 * (4 * slot + gsel);
-            s_lo[st] = lo;
-            s_hi[st] = hi;
-            s_g0[st] = g0;
-            s_last[st] = (int)(code >> 12);
+            const int gbase = (lo & ~3) + 64 * slot;
+            rm[s].lo = lo;
+            rm[s].hi = hi;
+            rm[s].gbase = gbase;
             // every address is clamped into the row-block's own data; what a clamped lane loads is never used
-            const int gq = g0 < hi ? g0 : (lo & ~3);
-            const int pa = gq + l16;
-            const uint32_t pc = (uint32_t)((pa >= lo && pa < hi) ? pa : lo);
-#pragma unroll
-            for (int kc = 0; kc < NK; ++kc) {
-                const uint32_t r = (FULLK || 16 * kc + 4 * kg < R) ? 16 * kc + 4 * kg : 0;
-                const uint32_t q = (uint32_t)R * base + pc + r * kp;  // element index: fits (at most R * capacity)
-                ra[st][kc][0] = vals[q];
-                ra[st][kc][1] = vals[q + kp];
-                ra[st][kc][2] = vals[q + 2 * kp];
-                ra[st][kc][3] = vals[q + 3 * kp];
-            }
-            rc[st] = col_idx[base + pc];
+            const uint32_t pv = (uint32_t)gbase + ld_pos < kp - 2 ? (uint32_t)gbase + ld_pos : kp - 2;  // even: 4-byte aligned
             const uint32_t uoff = (uint32_t)(bc + i) * (uint32_t)R;  // < M
 #pragma unroll
-            for (int kc = 0; kc < NK; ++kc) {
-                // a lane past R reads the row-block's first rows
-                const uint32_t ko = (FULLK || 16 * kc + 4 * kg < R) ? 16 * kc + 4 * kg : 0;
-                rua[st][kc] = *reinterpret_cast<const uint2 *>(urow_a + (uoff + ko));
-                rub[st][kc] = *reinterpret_cast<const uint2 *>(urow_b + (uoff + ko));
+            for (int j = 0; j < NK; ++j) {
+                const uint32_t r = (FULLK || 16 * j + ld_row < R) ? 16 * j + ld_row : 0;
+                rv[s][j] = *reinterpret_cast<const uint32_t *>(vals + ((uint32_t)R * base + r * kp + pv));
+                const uint32_t el = (FULLK || 16 * j + ld_el < R) ? 16 * j + ld_el : 0;  // past R: the block's first
+                ru[s][j] = *reinterpret_cast<const uint32_t *>(ld_urow + (uoff + el));
             }
+            const int pa = gbase + 16 * gsel + l16;
+            rc[s] = col_idx[base + (uint32_t)((pa >= lo && pa < hi) ? pa : lo)];
         };
-        auto consume = [&](int st) {
-            const int pa = s_g0[st] + l16;
-            const bool a_ok = pa >= s_lo[st] && pa < s_hi[st];  // false in every lane of a wavefront without a group
+        StepMeta cur;
+        int cur_col;
+        auto to_lds = [&](int s, int par) {  // step k's pieces into buffer par; its column and description to cur
+            unsigned char *buf = stage + par * stage_bytes(NK);
+#pragma unroll
+            for (int j = 0; j < NK; ++j) {
+                uint32_t u = ru[s][j];
+                const u32x2 xy = __builtin_amdgcn_permlane32_swap(rv[s][j], rv[s][j], false, false);  // rows 2w, 2w + 1
+                uint32_t v = upper ? (xy.x >> 16) | (xy.y & 0xffff0000u) : (xy.x & 0xffffu) | (xy.y << 16);
+                if (!FULLK && !(16 * j + 2 * wave < R)) v = 0u;  // the contraction ends at R (a multiple of 4)
+                if (!FULLK && !(16 * j + ld_el < R)) u = 0u;
+                *reinterpret_cast<uint32_t *>(buf + st_v + 32 * j) = v;
+                *reinterpret_cast<uint32_t *>(buf + st_u + 32 * j) = u;
+            }
+            cur = rm[s];
+            cur_col = rc[s];
+        };
+        auto consume = [&](int par) {
+            const unsigned char *buf = stage + par * stage_bytes(NK);
+            const int pa = cur.gbase + 16 * gsel + l16;
+            const bool a_ok = pa >= cur.lo && pa < cur.hi;  // false in every lane of a wavefront without a group
             f32x4 acc_a = {0.f, 0.f, 0.f, 0.f}, acc_b = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int kc = 0; kc < NK; ++kc) {
-                uint2 bv = make_uint2(ra[st][kc][0] | (ra[st][kc][1] << 16), ra[st][kc][2] | (ra[st][kc][3] << 16));
-                if (!FULLK && !(16 * kc + 4 * kg < R)) bv = make_uint2(0u, 0u);  // the contraction ends at R
-                acc_a = mfma16<DT>::run(rua[st][kc], bv, acc_a);
-                acc_b = mfma16<DT>::run(rub[st][kc], bv, acc_b);
+                const uint2 bv = *reinterpret_cast<const uint2 *>(buf + rd_b + 32 * kc);
+                const uint2 ua = *reinterpret_cast<const uint2 *>(buf + rd_a + 32 * kc);
+                const uint2 ub = *reinterpret_cast<const uint2 *>(buf + rd_a + 16 * kSP + 32 * kc);
+                acc_a = mfma16<DT>::run(ua, bv, acc_a);
+                acc_b = mfma16<DT>::run(ub, bv, acc_b);
             }
             // a lane without a column has multiplied clamped loads; its sums go to the spare row
-            const int cell = a_ok ? (rc[st] - cr0) * kPitch + tcell : spare;
-            f32x4 *pa4 = reinterpret_cast<f32x4 *>(tile + cell), *pb4 = reinterpret_cast<f32x4 *>(tile + cell + 16);
+            const int c = a_ok ? cur_col - cr0 : kCols;
+            const int rot = a_ok ? 4 * c : 0;
+            f32x4 *pa4 = reinterpret_cast<f32x4 *>(tile + c * kTok + ((tcell + rot) & (kTok - 1)));
+            f32x4 *pb4 = reinterpret_cast<f32x4 *>(tile + c * kTok + ((tcell + 16 + rot) & (kTok - 1)));
             const f32x4 old_a = *pa4, old_b = *pb4;
             *pa4 = old_a + acc_a;  // the kept columns of a row-block are distinct: no other lane has this cell
             *pb4 = old_b + acc_b;
-            if (s_last[st]) __syncthreads();  // uniform; the next row-block may keep the same columns
         };
 
 #pragma unroll
-        for (int st = 0; st < kDepth; ++st) produce(st, st);
+        for (int s = 0; s < kDepth; ++s) issue(s, s);
+        to_lds(0, 0);
+        issue(0, kDepth);
+        __syncthreads();
+        // iteration k: step k + 1 goes to LDS, step k + 1 + kDepth is asked for, step k is computed
         int k0 = 0;
         for (; k0 + kDepth <= total; k0 += kDepth) {
 #pragma unroll
-            for (int st = 0; st < kDepth; ++st) {
-                consume(st);
-                produce(st, k0 + st + kDepth);
+            for (int j = 0; j < kDepth; ++j) {
+                const int cons_par = j & 1;
+                consume(cons_par);
+                to_lds((j + 1) % kDepth, cons_par ^ 1);
+                issue((j + 1) % kDepth, k0 + j + 1 + kDepth);
+                __syncthreads();
             }
         }
 #pragma unroll
-        for (int st = 0; st < kDepth; ++st)
-            if (k0 + st < total) consume(st);
+        for (int j = 0; j < kDepth; ++j) {
+            if (k0 + j < total) {  // uniform
+                consume(j & 1);
+                to_lds((j + 1) % kDepth, (j & 1) ^ 1);
+                __syncthreads();
+            }
+        }
     }
     __syncthreads();
 
     // write the tile out: bias added in fp32, one rounding.  Consecutive lanes take consecutive tokens (consecutive
     // banks); a lane writes 8 columns of its token's row.
     const int ncol = (int)((N - cr0) < kCols ? (N - cr0) : kCols);
+    auto cell_of = [&](int c, int tok) { return c * kTok + ((tok + 4 * c) & (kTok - 1)); };
     if (ncol == kCols && (N & 7) == 0 && (reinterpret_cast<uintptr_t>(Z) & 15) == 0) {
         for (int i = tid; i < kTok * (kCols / 8); i += kThreads) {
             const int tok = i % kTok, c8 = (i / kTok) * 8;
@@ -247,7 +293,7 @@ __global__ __launch_bounds__(kThreads) void linear_t_mfma_kernel(const uint16_t 
             uint32_t w[4];
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                float v0 = tile[(c8 + 2 * q) * kPitch + tok], v1 = tile[(c8 + 2 * q + 1) * kPitch + tok];
+                float v0 = tile[cell_of(c8 + 2 * q, tok)], v1 = tile[cell_of(c8 + 2 * q + 1, tok)];
                 if (bias) {
                     v0 += elem<DT>::load(bias, cr0 + c8 + 2 * q);
                     v1 += elem<DT>::load(bias, cr0 + c8 + 2 * q + 1);
@@ -261,7 +307,7 @@ __global__ __launch_bounds__(kThreads) void linear_t_mfma_kernel(const uint16_t 
             const int tok = i % kTok, c = i / kTok;
             const int64_t t = t0 + tok;
             if (t >= T || c >= ncol) continue;
-            float v = tile[c * kPitch + tok];
+            float v = tile[cell_of(c, tok)];
             if (bias) v += elem<DT>::load(bias, cr0 + c);
             elem<DT>::store(Z, t * N + cr0 + c, v);
         }
@@ -376,13 +422,13 @@ extern "C" int bsp_linear_transposed(const void *U, int udt, int64_t T, int64_t 
     if (ranges > 65535 || N > 65535) return BSP_ERR_SHAPE;  // kept-column positions travel as 16 bits
     hipStream_t s = (hipStream_t)stream;
     // the matrix-core kernel indexes the storage with 32 bits: at most M (N + k_align) values
-    const bool mfma_ok = udt != BSP_F32 && R % 4 == 0 && k_align % 4 == 0 && col_idx && vals && aligned(U, 8) &&
-                         aligned(col_idx, 16) && (double)M * (double)(N + 64) < 4.0e9;
+    const bool mfma_ok = udt != BSP_F32 && R % 4 == 0 && k_align % 8 == 0 && col_idx && vals && aligned(U, 4) &&
+                         aligned(vals, 4) && (double)M * (double)(N + 64) < 4.0e9;
     if (mfma_ok) {
         const int64_t tiles = (T + kTok - 1) / kTok;
         if (tiles >= ((int64_t)1 << 31)) return BSP_ERR_SHAPE;
         const dim3 grid((unsigned)tiles, (unsigned)ranges);
-        const size_t lds = sizeof(float) * kTileWords + sizeof(BlockEntry) * kTable + sizeof(uint16_t) * kMaxSteps;
+        const size_t lds = mfma_lds_bytes((R + 15) / 16);
         if (udt == BSP_BF16)
             launch_mfma<BSP_BF16>(grid, lds, s, (const uint16_t *)U, T, M, N, B, R, blk_cnt, blk_ptr, col_idx,
                                   (const uint16_t *)vals, bias, Z);
