@@ -148,6 +148,53 @@ def cpu_baseline(mats):
                       f"on {cores} threads; single thread: 256 tokens of the QKV matrix"}
 
 
+def transposed_product(mats, reps=10, with_cpu=True):
+    """The transposed product Z = U Wp (input gradient of the layer; the layer of the row-segment variant on a
+    transposed matrix) on the same four compact storages: U is a synthetic [tokens, M] bf16 tensor, every launch
+    between two events on the launch stream.  Algorithmic bytes: U read once, Z written once, the storage read once."""
+    out, tot_us, tot_flops = {}, 0.0, 0.0
+    for m in mats:
+        U = torch.randn((m.T, m.M), device="cuda").to(torch.bfloat16)
+        Z = torch.empty((m.T, m.N), dtype=torch.bfloat16, device="cuda")
+        for _ in range(3):
+            bsp.bsp_linear_transposed(U, m.packed, None, Z)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            bsp.bsp_linear_transposed(U, m.packed, None, Z)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / reps * 1e3
+        padded = int(m.blk_ptr[-1].item())
+        by = 2.0 * m.T * m.M + 2.0 * m.T * m.N + 2.0 * m.R * padded + 4.0 * padded
+        tf = m.useful_flops() / us / 1e6
+        out[m.name] = {"shape": [m.M, m.N], "us": round(us, 1), "useful_tflops": round(tf, 2),
+                       "frac_mfma_peak": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
+                       "hbm_gbs": round(by / us / 1e3, 1), "frac_hbm_peak": round(by / us / 1e3 / HBM_PEAK_GBS, 4)}
+        tot_us += us
+        tot_flops += m.useful_flops()
+        del U, Z
+    res = {"kernel": "linear_t_mfma_kernel", "per_matrix": out, "us": round(tot_us, 1),
+           "useful_tflops": round(tot_flops / tot_us / 1e6, 2),
+           "frac_mfma_peak": round(tot_flops / tot_us / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4),
+           "bound": "lds: every product of R weights is one 4-byte read-add-write of the fp32 tile"}
+    if with_cpu:
+        from oracle import bsp_oracle as orc
+        m = mats[1]
+        cores = min(len(os.sched_getaffinity(0)), 16)
+        p = orc.pack(m.W.float().cpu().numpy(), m.R, m.keep.cpu().numpy(), m.k_align, orc.BF16)
+        rows = 1024
+        U1 = np.random.default_rng(1).standard_normal((rows, m.M)).astype(np.float32)
+        t = time.perf_counter()
+        orc.linear_t_packed(U1, p, None, zdt=orc.BF16, n_threads=cores)
+        secs = time.perf_counter() - t
+        res["cpu_oracle"] = {"value": round(2.0 * rows * m.R * int(p["blk_cnt"].sum()) / secs / 1e12, 5),
+                             "unit": "TFLOP/s", "cores": cores,
+                             "sample": f"{rows} token rows of the {m.name} matrix, {secs:.1f} s"}
+    return res
+
+
 def prune_path_c5(layers=24, reps=5, with_cpu=True):
     """HBM rate of the pruning pipeline on the 24-layer BERT-large weight set (fp32, 302 M parameters, R = 16):
     group norms + reweighting factors, regulariser gradient, one global percentile over all 18.9 M groups (5x),
@@ -365,6 +412,8 @@ def main():
                          "profiler's memory counters)")
     ap.add_argument("--no-grid", action="store_true",
                     help="skip the layer-only table over BERT-base / BERT-large shapes and compression rates")
+    ap.add_argument("--no-transposed", action="store_true",
+                    help="skip the timing of the transposed product (input gradient) on the same storages")
     ap.add_argument("--no-c5", action="store_true",
                     help="skip the bandwidth measurement of the pruning pipeline on the 302 M parameter weight set")
     args = ap.parse_args()
@@ -533,6 +582,8 @@ def main():
         out["cpu_baseline"] = cpu_baseline(mats)
     if not args.no_grid:
         out["linear_grid"] = linear_grid()
+    if not args.no_transposed:
+        out["transposed_product"] = transposed_product(mats, with_cpu=not args.no_cpu_baseline)
     if not args.no_c5:
         del mats
         torch.cuda.empty_cache()
