@@ -15,6 +15,9 @@
  *     with gamma_g = 1 / (||W_g||_2 + eps), refreshed at milestones (Alg. 2).
  *   - Sec. 3.1 (storage remark) and Sec. 4.4: only the kept groups and one index per kept
  *     group need to be stored; the layer is then a smaller dense product.
+ *   - The same layer read backwards: its input gradient dX = dY Wp (chain rule), which is
+ *     also the layer of Alg. 1's other division (row segments of column blocks) when the
+ *     matrix is kept transposed.
  *
  * Conventions.  W is row-major [M, N] = [out_features, in_features]; Y = X W^T + bias.
  * A row-block b holds rows bR .. bR+R-1; group g = (b, j) is the R weights W[bR+r, j].

@@ -535,6 +535,40 @@ def test_linear_transposed_is_the_adjoint_of_the_layer_and_skips_pads():
     assert_y_close(np.where(fin, Zi, 0.0), np.where(fin, Zi_ref, 0.0), "bf16")
 
 
+@pytest.mark.parametrize("C", [16, 32])
+def test_row_segment_variant_end_to_end_on_transposed_storage(C):
+    """The other division of Alg. 1: V [out, in] is cut into column blocks of C columns and a group is one row's
+    segment inside a column block.  Stored transposed (V^T is [in, out], its row-blocks are V's column blocks),
+    the same entry points compute its norms, percentile mask and compact storage, and the transposed product is
+    its layer Y = X Vp^T + bias.  Checked against definitions written directly on V."""
+    T, out_f, in_f = 150, 384, 512
+    V = wl.normal(811 + C, (out_f, in_f), 0.05, "bf16")
+    X = wl.normal(812 + C, (T, in_f), 1.0, "bf16")
+    bias = wl.normal(813 + C, (out_f,), 0.5, "bf16")
+    Vt = np.ascontiguousarray(V.T)
+    # norms of the row segments, straight from V
+    seg = (V.astype(np.float64).reshape(out_f, in_f // C, C) ** 2).sum(axis=2)          # [out, in / C]
+    s, _, _ = bsp.bsp_group_norms(dev(Vt, "bf16"), C)                                   # [in / C, out]
+    assert np.allclose(host(s).T, seg, rtol=1e-6, atol=0)
+    assert bits_equal(host(s), orc.sumsq(Vt, C))
+    # keep the n_keep largest segments of the whole matrix
+    n_keep = seg.size // 3
+    keep, _ = bsp.bsp_prune_mask(s, n_keep=n_keep, scope=bsp.SCOPE_MATRIX)
+    keep_h = host(keep)
+    assert keep_h.sum() == n_keep
+    thr = np.sort(host(s).ravel())[::-1][n_keep - 1]
+    assert np.array_equal(keep_h, (host(s) >= thr).astype(np.uint8))                    # no ties in this draw
+    p = bsp.bsp_pack(dev(Vt, "bf16"), C, keep, 32)
+    Y = host(bsp.bsp_linear_transposed(dev(X, "bf16"), p, dev(bias, "bf16")))
+    Vp = V.astype(np.float64) * np.repeat(keep_h.T, C, axis=1)                          # pruned segments zeroed
+    want = X.astype(np.float64) @ Vp.T + bias
+    assert_y_close(Y, orc.round_to(want, orc.BF16), "bf16")
+    # and the input gradient of that layer is the forward entry point on the same storage
+    G = wl.normal(814 + C, (T, out_f), 1.0, "bf16")
+    dX = host(bsp.bsp_linear(dev(G, "bf16"), p, None))
+    assert_y_close(dX, G.astype(np.float64) @ Vp, "bf16")
+
+
 @pytest.mark.parametrize("R", [8, 16, 32])
 def test_config4_bert_large_layer_set_transposed(R):
     """The input gradient of every BERT-large matrix at the benchmark's token count, on sampled token rows."""
