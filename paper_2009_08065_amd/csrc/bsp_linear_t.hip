@@ -135,6 +135,7 @@ __global__ __launch_bounds__(kThreads) void linear_t_mfma_kernel(const uint16_t 
     // byte offsets inside a buffer.  Lanes l and l + 32 hold rows 2 wave and 2 wave + 1 of the same two positions:
     // they exchange halves, so that each writes one position's pair of rows as one word.
     const bool upper = lane >= 32;
+    const uint32_t pair_sel = upper ? 0x07060302u : 0x05040100u;  // bytes of {row 2w + 1, row 2w}: the halves of one position
     const int st_v = (ld_pos + (upper ? 1 : 0)) * kSP + wave * 4;
     const int st_u = 64 * kSP + ld_tok * kSP + ld_el * 2;
     // as a consumer
@@ -188,13 +189,32 @@ __global__ __launch_bounds__(kThreads) void linear_t_mfma_kernel(const uint16_t 
         int rc[kDepth];                           // the kept column whose sums this lane receives
         StepMeta rm[kDepth];
 
-        auto issue = [&](int s, int k) {  // the loads of step k (clamped to the last one)
-            const uint32_t code = __builtin_amdgcn_readfirstlane((uint32_t)steps[k < total ? k : total - 1]);
-            const int i = (int)(code & 511u), slot = (int)(code >> 9);
-            const BlockEntry e = table[i];
-            const uint32_t lohi = __builtin_amdgcn_readfirstlane(e.lohi);
-            const uint32_t base = __builtin_amdgcn_readfirstlane(e.base);
-            const uint32_t kp = __builtin_amdgcn_readfirstlane(e.kp);
+        // The description of a step comes from LDS in two dependent reads (step list, then table); both are started
+        // one call of issue() early, so that no call waits for a read of its own: pre_e is the table entry of the
+        // step the next call loads (pre_i, pre_slot: its row-block and slot), pre_code the list entry after it.
+        auto step_code = [&](int k) { return (uint32_t)steps[k < total ? k : total - 1]; };
+        uint32_t pre_i, pre_slot, pre_code;
+        BlockEntry pre_e;
+        {
+            const uint32_t c0 = __builtin_amdgcn_readfirstlane(step_code(0));
+            pre_i = c0 & 511u;
+            pre_slot = c0 >> 9;
+            pre_e = table[pre_i];
+            pre_code = step_code(1);
+        }
+        auto issue = [&](int s, int k) {  // the loads of step k (clamped to the last one); calls come with k ascending
+            const uint32_t lohi = __builtin_amdgcn_readfirstlane(pre_e.lohi);
+            const uint32_t base = __builtin_amdgcn_readfirstlane(pre_e.base);
+            const uint32_t kp = __builtin_amdgcn_readfirstlane(pre_e.kp);
+            const uint32_t i = pre_i;
+            const int slot = (int)pre_slot;
+            {  // the reads for the next calls
+                const uint32_t c1 = __builtin_amdgcn_readfirstlane(pre_code);
+                pre_i = c1 & 511u;
+                pre_slot = c1 >> 9;
+                pre_e = table[pre_i];
+                pre_code = step_code(k + 2);
+            }
             const int lo = (int)(lohi & 0xffffu), hi = (int)(lohi >> 16);
             const int gbase = (lo & ~3) + 64 * slot;
             rm[s].lo = lo;
@@ -202,7 +222,7 @@ __global__ __launch_bounds__(kThreads) void linear_t_mfma_kernel(const uint16_t 
             rm[s].gbase = gbase;
             // every address is clamped into the row-block's own data; what a clamped lane loads is never used
             const uint32_t pv = (uint32_t)gbase + ld_pos < kp - 2 ? (uint32_t)gbase + ld_pos : kp - 2;  // even: 4-byte aligned
-            const uint32_t uoff = (uint32_t)(bc + i) * (uint32_t)R;  // < M
+            const uint32_t uoff = ((uint32_t)bc + i) * (uint32_t)R;  // < M
 #pragma unroll
             for (int j = 0; j < NK; ++j) {
                 const uint32_t r = (FULLK || 16 * j + ld_row < R) ? 16 * j + ld_row : 0;
@@ -221,7 +241,7 @@ __global__ __launch_bounds__(kThreads) void linear_t_mfma_kernel(const uint16_t 
             for (int j = 0; j < NK; ++j) {
                 uint32_t u = ru[s][j];
                 const u32x2 xy = __builtin_amdgcn_permlane32_swap(rv[s][j], rv[s][j], false, false);  // rows 2w, 2w + 1
-                uint32_t v = upper ? (xy.x >> 16) | (xy.y & 0xffff0000u) : (xy.x & 0xffffu) | (xy.y << 16);
+                uint32_t v = __builtin_amdgcn_perm(xy.y, xy.x, pair_sel);  // low lanes: the first position, upper: the second
                 if (!FULLK && !(16 * j + 2 * wave < R)) v = 0u;  // the contraction ends at R (a multiple of 4)
                 if (!FULLK && !(16 * j + ld_el < R)) u = 0u;
                 *reinterpret_cast<uint32_t *>(buf + st_v + 32 * j) = v;
@@ -234,6 +254,12 @@ __global__ __launch_bounds__(kThreads) void linear_t_mfma_kernel(const uint16_t 
             const unsigned char *buf = stage + par * stage_bytes(NK);
             const int pa = cur.gbase + 16 * gsel + l16;
             const bool a_ok = pa >= cur.lo && pa < cur.hi;  // false in every lane of a wavefront without a group
+            // a lane without a column multiplies clamped loads; its sums go to the spare row
+            const int c = a_ok ? cur_col - cr0 : kCols;
+            const int rot = a_ok ? 4 * c : 0;
+            f32x4 *pa4 = reinterpret_cast<f32x4 *>(tile + c * kTok + ((tcell + rot) & (kTok - 1)));
+            f32x4 *pb4 = reinterpret_cast<f32x4 *>(tile + c * kTok + ((tcell + 16 + rot) & (kTok - 1)));
+            const f32x4 old_a = *pa4, old_b = *pb4;  // read beside the operands: the products need not wait for them
             f32x4 acc_a = {0.f, 0.f, 0.f, 0.f}, acc_b = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int kc = 0; kc < NK; ++kc) {
@@ -243,12 +269,6 @@ __global__ __launch_bounds__(kThreads) void linear_t_mfma_kernel(const uint16_t 
                 acc_a = mfma16<DT>::run(ua, bv, acc_a);
                 acc_b = mfma16<DT>::run(ub, bv, acc_b);
             }
-            // a lane without a column has multiplied clamped loads; its sums go to the spare row
-            const int c = a_ok ? cur_col - cr0 : kCols;
-            const int rot = a_ok ? 4 * c : 0;
-            f32x4 *pa4 = reinterpret_cast<f32x4 *>(tile + c * kTok + ((tcell + rot) & (kTok - 1)));
-            f32x4 *pb4 = reinterpret_cast<f32x4 *>(tile + c * kTok + ((tcell + 16 + rot) & (kTok - 1)));
-            const f32x4 old_a = *pa4, old_b = *pb4;
             *pa4 = old_a + acc_a;  // the kept columns of a row-block are distinct: no other lane has this cell
             *pb4 = old_b + acc_b;
         };
