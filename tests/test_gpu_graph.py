@@ -31,6 +31,7 @@ def test_graph_replays_match_eager():
     vals = torch.empty(R * cap, dtype=torch.bfloat16, device=dev)
     plan = torch.empty(bsp.lib().bsp_linear_plan_bytes(M, R, cap), dtype=torch.uint8, device=dev)
     Y = torch.empty((T, M), dtype=torch.bfloat16, device=dev)
+    Z = torch.empty((T, N), dtype=torch.bfloat16, device=dev)     # the input gradient of the layer for dY = Y
     p = bsp.Packed(M, N, R, 32, cnt, ptr, col, vals, cap)
 
     def path():
@@ -44,20 +45,22 @@ def test_graph_replays_match_eager():
         assert st == 0
         bsp.bsp_linear_plan(p, plan=plan)
         bsp.bsp_linear_planned(X, p, plan, bias, Y=Y)
+        bsp.bsp_linear_transposed(Y, p, None, Z=Z)
 
     want = []
     for Xi in Xs:                       # eager reference (also the warm-up before capture)
         X.copy_(Xi)
         path()
         torch.cuda.synchronize()
-        want.append((Y.clone(), keep.clone(), grad.clone()))
+        want.append((Y.clone(), keep.clone(), grad.clone(), Z.clone()))
     g = torch.cuda.CUDAGraph()
     with torch.cuda.graph(g):
         path()
     for rep in range(2):
-        for Xi, (y_ref, k_ref, g_ref) in zip(Xs, want):
+        for Xi, (y_ref, k_ref, g_ref, z_ref) in zip(Xs, want):
             X.copy_(Xi)
-            Y.zero_(); keep.zero_(); grad.zero_(); col.zero_(); plan.zero_()   # eager work between replays
+            Y.zero_(); keep.zero_(); grad.zero_(); col.zero_(); plan.zero_(); Z.zero_()   # eager work between replays
             g.replay()
             torch.cuda.synchronize()
             assert torch.equal(Y, y_ref) and torch.equal(keep, k_ref) and torch.equal(grad, g_ref)
+            assert torch.equal(Z, z_ref)

@@ -726,3 +726,8 @@ def test_determinism_run_to_run():
     y1 = bsp.bsp_linear(Xd, p, bd).clone()
     y2 = bsp.bsp_linear(Xd, p, bd)
     assert torch.equal(y1, y2)
+    # the transposed product adds each cell's terms in one fixed order (steps in turn, a barrier between them)
+    Ud = dev(wl.normal(55, (512, 1024), 1.0, "bf16"), "bf16")
+    z1 = bsp.bsp_linear_transposed(Ud, p, bd).clone()
+    z2 = bsp.bsp_linear_transposed(Ud, p, bd)
+    assert torch.equal(z1, z2)
