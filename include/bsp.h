@@ -172,9 +172,10 @@ int bsp_linear(const void *X, int xdt, int64_t T, int64_t M, int64_t N, int32_t 
  * NULL) have dtype udt too.  The compact storage is the one bsp_pack writes; pad slots
  * (c >= k_b) are not part of the matrix and are never read as values.  A column that no
  * row-block keeps receives the bias alone.  Products are accumulated in fp32 (matrix cores
- * for bf16 / fp16 when R % 4 == 0, k_align >= 8, U 8-byte and col_idx 16-byte aligned; fp32
- * multiply-adds otherwise), the bias is added in fp32 and the sum is rounded once to udt
- * (RNE).  The order of the additions is unspecified and may differ from call to call.
+ * for bf16 / fp16 when R % 4 == 0, k_align >= 8, U and vals 4-byte aligned and
+ * M * (N + 64) < 4e9; fp32 multiply-adds otherwise), the bias is added in fp32 and the sum
+ * is rounded once to udt (RNE).  The order of the additions is unspecified but fixed for
+ * given arguments: two calls give the same bits.
  * N <= 65535.  Errors: NULL U / blk_cnt / blk_ptr / Z, bad dtype, M % R != 0, R > 64. */
 int bsp_linear_transposed(const void *U, int udt, int64_t T, int64_t M, int64_t N, int32_t R, int32_t k_align,
                           const int32_t *blk_cnt, const int32_t *blk_ptr, const int32_t *col_idx,

@@ -90,8 +90,9 @@ __device__ __forceinline__ int lower_bound(const int32_t *__restrict__ a, int n,
 // into registers, one step ahead into LDS (the panel transposed on the way), and from there
 // every wavefront reads its operands with one 8-byte read each.  A barrier ends every step: it
 // orders the additions of one row-block before those of the next and the LDS buffers' reuse.
-// A step has no branches: a lane without work loads from clamped addresses and adds to the
-// spare row of the tile.
+// The loads of a step have no branches (a lane without work loads from clamped addresses and,
+// inside a group, adds to the spare row of the tile); for R <= 16 a wavefront whose group lies
+// past the row-block's range skips the products and the additions.
 // ---------------------------------------------------------------------------------------
 struct BlockEntry {  // one row-block as seen from a column range
     uint32_t lohi;   // positions [lo, hi) of its kept columns inside the range: lo | hi << 16
@@ -251,9 +252,12 @@ __global__ __launch_bounds__(kThreads) void linear_t_mfma_kernel(const uint16_t 
             cur_col = rc[s];
         };
         auto consume = [&](int par) {
+            // wave-uniform: no group of this slot for this wavefront (measured: 0.20 -> 0.16 ms at 10x for R = 16, but
+            // 9 % slower with the larger buffers of R >= 32, where one workgroup fills the compute unit)
+            if (NK == 1 && cur.gbase + 16 * gsel >= cur.hi) return;
             const unsigned char *buf = stage + par * stage_bytes(NK);
             const int pa = cur.gbase + 16 * gsel + l16;
-            const bool a_ok = pa >= cur.lo && pa < cur.hi;  // false in every lane of a wavefront without a group
+            const bool a_ok = pa >= cur.lo && pa < cur.hi;
             // a lane without a column multiplies clamped loads; its sums go to the spare row
             const int c = a_ok ? cur_col - cr0 : kCols;
             const int rot = a_ok ? 4 * c : 0;
