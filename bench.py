@@ -36,6 +36,7 @@ import paper_2009_08065_amd as bsp  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
+LDS_PEAK_GBS = 256 * 256 * 2.4  # 256 compute units x 256 B/clk (ds_read_b128 measured at 246) x 2.4 GHz = 157 286 GB/s
 # HBM bytes per launch of linear_tiled_planned_kernel on this workload (average of its three launches), from the
 # FETCH_SIZE / WRITE_SIZE counter runs summarised in profiles/linear_kernels_bert_large_r16_hbm_traffic.md
 # (31.5 MB read + 45.5 MB written; the algorithmic figure is 62.8 MB).  Void once that kernel changes.
@@ -152,7 +153,7 @@ def transposed_product(mats, reps=10, with_cpu=True):
     """The transposed product Z = U Wp (input gradient of the layer; the layer of the row-segment variant on a
     transposed matrix) on the same four compact storages: U is a synthetic [tokens, M] bf16 tensor, every launch
     between two events on the launch stream.  Algorithmic bytes: U read once, Z written once, the storage read once."""
-    out, tot_us, tot_flops = {}, 0.0, 0.0
+    out, tot_us, tot_flops, lds_bytes = {}, 0.0, 0.0, 0.0
     for m in mats:
         U = torch.randn((m.T, m.M), device="cuda").to(torch.bfloat16)
         Z = torch.empty((m.T, m.N), dtype=torch.bfloat16, device="cuda")
@@ -169,7 +170,10 @@ def transposed_product(mats, reps=10, with_cpu=True):
         padded = int(m.blk_ptr[-1].item())
         by = 2.0 * m.T * m.M + 2.0 * m.T * m.N + 2.0 * m.R * padded + 4.0 * padded
         tf = m.useful_flops() / us / 1e6
+        lds = 8.0 * m.T * m.kept_cols    # one fp32 cell read and written per token, kept column and row-block
+        lds_bytes += lds
         out[m.name] = {"shape": [m.M, m.N], "us": round(us, 1), "useful_tflops": round(tf, 2),
+                       "lds_gbs": round(lds / us / 1e3, 1),
                        "frac_mfma_peak": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
                        "hbm_gbs": round(by / us / 1e3, 1), "frac_hbm_peak": round(by / us / 1e3 / HBM_PEAK_GBS, 4)}
         tot_us += us
@@ -178,20 +182,24 @@ def transposed_product(mats, reps=10, with_cpu=True):
     res = {"kernel": "linear_t_mfma_kernel", "per_matrix": out, "us": round(tot_us, 1),
            "useful_tflops": round(tot_flops / tot_us / 1e6, 2),
            "frac_mfma_peak": round(tot_flops / tot_us / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4),
-           "bound": "lds: every product of R weights is one 4-byte read-add-write of the fp32 tile"}
+           "roofline": {"bound": "lds", "achieved": round(lds_bytes / tot_us / 1e3, 1), "peak": LDS_PEAK_GBS,
+                        "unit": "GB/s", "frac": round(lds_bytes / tot_us / 1e3 / LDS_PEAK_GBS, 4),
+                        "note": "algorithmic LDS bytes: every product of R weights is one 4-byte read and one 4-byte "
+                                "write of the fp32 tile; peak = 256 compute units x 256 B/clk x 2.4 GHz"}}
     if with_cpu:
         from oracle import bsp_oracle as orc
-        m = mats[1]
+        m = mats[2]
         cores = min(len(os.sched_getaffinity(0)), 16)
         p = orc.pack(m.W.float().cpu().numpy(), m.R, m.keep.cpu().numpy(), m.k_align, orc.BF16)
-        rows = 1024
+        rows = m.T
         U1 = np.random.default_rng(1).standard_normal((rows, m.M)).astype(np.float32)
         t = time.perf_counter()
         orc.linear_t_packed(U1, p, None, zdt=orc.BF16, n_threads=cores)
         secs = time.perf_counter() - t
         res["cpu_oracle"] = {"value": round(2.0 * rows * m.R * int(p["blk_cnt"].sum()) / secs / 1e12, 5),
                              "unit": "TFLOP/s", "cores": cores,
-                             "sample": f"{rows} token rows of the {m.name} matrix, {secs:.1f} s"}
+                             "sample": f"oracle transposed product (fp64, OpenMP over token rows), {rows} token rows of "
+                                       f"the {m.name} matrix, {secs:.2f} s"}
     return res
 
 

@@ -170,7 +170,7 @@ int bsp_linear(const void *X, int xdt, int64_t T, int64_t M, int64_t N, int32_t 
  *                       sum_{r < R} U[t, bR + r] * vals[b, r, c]
  * U: [T, M], Z: [T, N], row-major contiguous, dtype udt; vals and bias (length N, may be
  * NULL) have dtype udt too.  The compact storage is the one bsp_pack writes; pad slots
- * (c >= k_b) are not part of the matrix and are never read as values.  A column that no
+ * (c >= k_b) are not part of the matrix and add nothing, whatever U holds.  A column that no
  * row-block keeps receives the bias alone.  Products are accumulated in fp32 (matrix cores
  * for bf16 / fp16 when R % 4 == 0, k_align >= 8, U and vals 4-byte aligned and
  * M * (N + 64) < 4e9; fp32 multiply-adds otherwise), the bias is added in fp32 and the sum
