@@ -461,7 +461,8 @@ def run_transposed(U, W, bias, R, keep, k_align, dtype, T_rows=None):
 @pytest.mark.parametrize("k_align", [1, 8, 32])
 @pytest.mark.parametrize("R,T,M,N,p_keep", [(16, 100, 64, 200, 0.5), (8, 70, 40, 333, 0.2), (32, 130, 96, 256, 0.33),
                                             (1, 9, 7, 50, 0.5), (3, 65, 12, 100, 0.7), (64, 17, 128, 96, 0.4),
-                                            (4, 33, 36, 515, 0.6), (24, 64, 48, 1024, 0.25)])
+                                            (4, 33, 36, 515, 0.6), (24, 64, 48, 1024, 0.25), (48, 40, 96, 300, 0.5),
+                                            (40, 50, 80, 260, 0.4), (64, 200, 192, 520, 0.9)])
 def test_linear_transposed_small_shapes(dtype, k_align, R, T, M, N, p_keep):
     d = wl.layer(R * 1000 + T + 7, T, M, N, dtype)
     U = wl.normal(R * 77 + T, (T, M), 1.0, dtype)
@@ -510,6 +511,18 @@ def test_linear_transposed_more_row_blocks_than_one_table_pass():
     W = wl.normal(91, (R * B, N), 0.02, "bf16")
     U = wl.normal(92, (T, R * B), 1.0, "bf16")
     run_transposed(U, W, None, R, wl.bernoulli_keep_mask(93, B, N, 0.3), 8, "bf16")
+
+
+def test_linear_transposed_passes_without_any_kept_column():
+    """300 row-blocks are walked in three passes of the range table; here the whole first pass and, in one column
+    range, every pass keeps nothing."""
+    R, B, N, T = 8, 300, 600, 90
+    W = wl.normal(94, (R * B, N), 0.02, "f16")
+    U = wl.normal(95, (T, R * B), 1.0, "f16")
+    keep = wl.bernoulli_keep_mask(96, B, N, 0.4)
+    keep[:128] = 0
+    keep[:, 256:512] = 0
+    run_transposed(U, W, wl.normal(97, (N,), 0.5, "f16"), R, keep, 16, "f16")
 
 
 def test_linear_transposed_is_the_adjoint_of_the_layer_and_skips_pads():
