@@ -260,7 +260,8 @@ __global__ __launch_bounds__(kThreads) void linear_t_mfma_kernel(const uint16_t 
             const bool a_ok = pa >= cur.lo && pa < cur.hi;
             // a lane without a column multiplies clamped loads; its sums go to the spare row
             const int c = a_ok ? cur_col - cr0 : kCols;
-            const int rot = a_ok ? 4 * c : 0;
+            static_assert((4 * kCols) % kTok == 0, "the spare row must not be rotated");
+            const int rot = 4 * c;
             f32x4 *pa4 = reinterpret_cast<f32x4 *>(tile + c * kTok + ((tcell + rot) & (kTok - 1)));
             f32x4 *pb4 = reinterpret_cast<f32x4 *>(tile + c * kTok + ((tcell + 16 + rot) & (kTok - 1)));
             const f32x4 old_a = *pa4, old_b = *pb4;  // read beside the operands: the products need not wait for them
