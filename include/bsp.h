@@ -175,7 +175,9 @@ int bsp_linear(const void *X, int xdt, int64_t T, int64_t M, int64_t N, int32_t 
  * for bf16 / fp16 when R % 4 == 0, k_align >= 8, U and vals 4-byte aligned and
  * M * (N + 64) < 4e9; fp32 multiply-adds otherwise), the bias is added in fp32 and the sum
  * is rounded once to udt (RNE).  The order of the additions is unspecified but fixed for
- * given arguments: two calls give the same bits.
+ * given arguments: two calls give the same bits.  The storage must be well formed
+ * (bsp_packed_validate); a malformed one gives unspecified values in Z but no access
+ * outside the buffers as long as blk_ptr and blk_cnt are consistent with their sizes.
  * N <= 65535.  Errors: NULL U / blk_cnt / blk_ptr / Z, bad dtype, M % R != 0, R > 64. */
 int bsp_linear_transposed(const void *U, int udt, int64_t T, int64_t M, int64_t N, int32_t R, int32_t k_align,
                           const int32_t *blk_cnt, const int32_t *blk_ptr, const int32_t *col_idx,

@@ -257,7 +257,8 @@ __global__ __launch_bounds__(kThreads) void linear_t_mfma_kernel(const uint16_t 
             if (NK == 1 && cur.gbase + 16 * gsel >= cur.hi) return;
             const unsigned char *buf = stage + par * stage_bytes(NK);
             const int pa = cur.gbase + 16 * gsel + l16;
-            const bool a_ok = pa >= cur.lo && pa < cur.hi;
+            // (the column test only matters for a malformed storage: it keeps every write inside the tile)
+            const bool a_ok = pa >= cur.lo && pa < cur.hi && (unsigned)(cur_col - cr0) < (unsigned)kCols;
             // a lane without a column multiplies clamped loads; its sums go to the spare row
             const int c = a_ok ? cur_col - cr0 : kCols;
             static_assert((4 * kCols) % kTok == 0, "the spare row must not be rotated");
