@@ -36,6 +36,7 @@ constexpr int kTable = 128;         // row-blocks per pass: one per thread (of t
 constexpr int kMaxSlots = (kCols + 3 + 63) / 64;  // slots of a row-block: 64 positions each, the first aligned down to 4
 constexpr int kMaxSteps = kTable * kMaxSlots;
 constexpr int kDepth = 4;           // steps whose operands are on their way from memory (even: LDS buffers alternate)
+static_assert(kDepth % 2 == 0, "step k uses LDS buffer k % 2, and the unrolled loop starts at multiples of kDepth");
 
 // LDS bytes of the matrix-core kernel for NK contraction chunks of 16: tile, table, step list, two operand buffers
 constexpr int stage_pitch(int nk) { return 32 * nk + 8; }  // bytes per position / per token: 16 nk values and a pad
