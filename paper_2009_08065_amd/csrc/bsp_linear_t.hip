@@ -148,10 +148,11 @@ __global__ __launch_bounds__(kThreads) void linear_t_mfma_kernel(const uint16_t 
     for (int64_t bc = 0; bc < B; bc += kTable) {
         const int nb = (int)((B - bc) < kTable ? (B - bc) : kTable);
         __syncthreads();  // the tile is zeroed / the previous pass is done with the table and the buffers
-        // Thread q describes the q-th row-block of this pass's order, which starts at another row-block in every
-        // workgroup: the workgroups resident at one time then do not all ask for the same value panels and the
-        // same column slice of U at once.
-        const int rot = (int)(((blockIdx.x + 5u * blockIdx.y) * 8u) % (unsigned)nb);
+        // Thread q describes the q-th row-block of this pass's order, which starts at another row-block for every
+        // token tile: the workgroups resident at one time then do not all ask for the same value panels at once,
+        // while the workgroups of one token tile (one per column range, on the same L2) walk the same rows of U in
+        // the same order and share their fetches.
+        const int rot = (int)((blockIdx.x * 8u) % (unsigned)nb);
         int my_i = 0, my_slots = 0;
         if (tid < nb) {  // nb <= kTable
             my_i = tid + rot < nb ? tid + rot : tid + rot - nb;
