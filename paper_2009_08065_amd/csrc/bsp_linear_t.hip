@@ -74,7 +74,7 @@ __device__ __forceinline__ int lower_bound(const int32_t *__restrict__ a, int n,
 
 // ---------------------------------------------------------------------------------------
 // Matrix-core kernel.  16-bit values, R % 4 == 0, R <= 64, k_align % 8 == 0, U 4-byte aligned.
-// grid.x = token tiles, grid.y = column ranges.  NK = contraction chunks of 16 (ceil(R / 16)).
+// One workgroup per (token tile, column range).  NK = contraction chunks of 16 (ceil(R / 16)).
 //
 // v_mfma_f32_16x16x16 with A = U (row = token, k = r) and B = the value panel (k = r, column =
 // kept column): lane l supplies A[l % 16][4 (l / 16) ..+3] and B[4 (l / 16) ..+3][l % 16]; it
@@ -125,8 +125,15 @@ __global__ __launch_bounds__(kThreads) void linear_t_mfma_kernel(const uint16_t 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, kg = lane >> 4;
     const int half = wave & 1, gsel = wave >> 1;
-    const int64_t t0 = (int64_t)blockIdx.x * kTok;
-    const int cr0 = (int)blockIdx.y * kCols;
+    // Workgroup ids go round the 8 XCDs (each with an L2 of its own): id % 8 names the XCD.  The column ranges of
+    // one token tile take consecutive places on one XCD, so that they run at the same time and share the tile's
+    // rows of U in that L2.
+    const uint32_t nranges = (uint32_t)((N + kCols - 1) / kCols);
+    const uint32_t place = blockIdx.x >> 3;
+    const uint32_t tile_id = (place / nranges) * 8u + (blockIdx.x & 7u);
+    const int64_t t0 = (int64_t)tile_id * kTok;
+    if (t0 >= T) return;  // the grid is rounded up to whole rounds of the XCDs (uniform: before any barrier)
+    const int cr0 = (int)(place % nranges) * kCols;
 
     for (int i = tid; i < kTileWords; i += kThreads) tile[i] = 0.0f;
 
@@ -152,7 +159,7 @@ __global__ __launch_bounds__(kThreads) void linear_t_mfma_kernel(const uint16_t 
         // token tile: the workgroups resident at one time then do not all ask for the same value panels at once,
         // while the workgroups of one token tile (one per column range, on the same L2) walk the same rows of U in
         // the same order and share their fetches.
-        const int rot = (int)((blockIdx.x * 8u) % (unsigned)nb);
+        const int rot = (int)((tile_id * 8u) % (unsigned)nb);
         int my_i = 0, my_slots = 0;
         if (tid < nb) {  // nb <= kTable
             my_i = tid + rot < nb ? tid + rot : tid + rot - nb;
@@ -454,8 +461,9 @@ extern "C" int bsp_linear_transposed(const void *U, int udt, int64_t T, int64_t 
                          aligned(vals, 4) && (double)M * (double)(N + 64) < 4.0e9;
     if (mfma_ok) {
         const int64_t tiles = (T + kTok - 1) / kTok;
-        if (tiles >= ((int64_t)1 << 31)) return BSP_ERR_SHAPE;
-        const dim3 grid((unsigned)tiles, (unsigned)ranges);
+        const int64_t wgs = (tiles + 7) / 8 * 8 * ranges;  // whole rounds of the 8 XCDs
+        if (wgs >= ((int64_t)1 << 31)) return BSP_ERR_SHAPE;
+        const dim3 grid((unsigned)wgs);
         const size_t lds = mfma_lds_bytes((R + 15) / 16);
         if (udt == BSP_BF16)
             launch_mfma<BSP_BF16>(grid, lds, s, (const uint16_t *)U, T, M, N, B, R, blk_cnt, blk_ptr, col_idx,
