@@ -412,7 +412,6 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--path", choices=["planned", "canonical"], default="planned",
                     help="layer operands: the derived plan buffer (default) or the compact storage itself")
-    ap.add_argument("--waves", type=int, default=0, help="experiment: wavefronts per workgroup of the tiled kernel")
     ap.add_argument("--launch", choices=["overlap", "serial", "eager"], default="overlap",
                     help="overlap: one HIP graph, a branch per matrix; serial: one HIP graph, matrices in turn; "
                          "eager: every kernel launched from Python")
@@ -434,8 +433,6 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
 
-    if args.waves:
-        bsp.lib().bsp_debug_set_tiled_waves(args.waves)
     if args.copy_probe:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
         dst = torch.empty_like(src)

@@ -41,9 +41,13 @@ def lib():
     if _LIB is not None:
         return _LIB
     path = library_path()
+    from . import build as _build
     if not os.path.exists(path):
-        from . import build as _build
         _build.build(force=True)
+    elif _build.stale():
+        # a built library is loaded as it is (GPU runs must not compile); say so when a source is newer
+        import warnings
+        warnings.warn("libbsp.so is older than its sources: run `python -m paper_2009_08065_amd.build`")
     L = C.CDLL(path)
     i64, i32, f32, vp, sz = C.c_int64, C.c_int32, C.c_float, C.c_void_p, C.c_size_t
     L.bsp_group_norms.argtypes = [vp, C.c_int, i64, i64, i32, f32, C.c_int, vp, vp, vp, vp]

@@ -28,10 +28,18 @@ def _compile(src):
     return obj
 
 
+def _inputs():
+    return [os.path.join(CSRC, f) for f in sorted(os.listdir(CSRC)) if f.endswith((".hip", ".h"))] + [
+        os.path.join(INCLUDE, "bsp.h")]
+
+
+def stale() -> bool:
+    """True when libbsp.so is missing or older than one of its sources."""
+    return not os.path.exists(LIB) or any(os.path.getmtime(LIB) < os.path.getmtime(s) for s in _inputs())
+
+
 def build(force: bool = True) -> str:
-    srcs = [os.path.join(CSRC, s) for s in SOURCES] + [os.path.join(CSRC, "bsp_common.h"), os.path.join(CSRC, "bsp_linear_internal.h"),
-                                                       os.path.join(INCLUDE, "bsp.h")]
-    if not force and os.path.exists(LIB) and all(os.path.getmtime(LIB) >= os.path.getmtime(s) for s in srcs):
+    if not force and not stale():
         return LIB
     os.makedirs(OBJ_DIR, exist_ok=True)
     with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:

@@ -28,7 +28,6 @@ struct TiledArgs {
 // True when the tiled kernel can take this layer (16-bit floats, kp_b % 32 == 0, X tile fits in LDS).
 bool tiled_supported(int xdt, int64_t N, int32_t k_align);
 int launch_linear_tiled(const TiledArgs &args, bool plan, hipStream_t s);
-void set_tiled_waves(int waves);
 // Column chunks of a plan: layers with more than 1024 (padded) input columns are cut into chunks of
 // 1024 columns, the width of X that fits in LDS next to 64 tokens; narrower layers are one chunk.
 constexpr int kPlanMaxChunks = 4;

@@ -411,29 +411,35 @@ __global__ __launch_bounds__(kGenThreads) void linear_t_general_kernel(const voi
 }
 
 template <int DT, int NK, bool FULLK>
-void launch_mfma_one(dim3 grid, size_t lds, hipStream_t s, const uint16_t *U, int64_t T, int64_t M, int64_t N,
+int launch_mfma_one(dim3 grid, size_t lds, hipStream_t s, const uint16_t *U, int64_t T, int64_t M, int64_t N,
                      int64_t B, int32_t R, const int32_t *blk_cnt, const int32_t *blk_ptr, const int32_t *col_idx,
                      const uint16_t *vals, const void *bias, void *Z) {
     auto k = linear_t_mfma_kernel<DT, NK, FULLK>;
-    static bool raised = false;  // per instantiation: dynamic LDS above 64 KB must be asked for once
-    if (!raised) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  (int)lds);
-        raised = true;
+    // per instantiation and thread: dynamic LDS above 64 KB must be asked for (repeating the call is harmless)
+    static thread_local size_t configured = 0;
+    if (lds > configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)lds);
+        if (e != hipSuccess) {
+            set_last_hip_error((int)e);
+            return BSP_ERR_HIP;
+        }
+        configured = lds;
     }
     k<<<grid, kThreads, lds, s>>>(U, T, M, N, B, R, blk_cnt, blk_ptr, col_idx, vals, bias, Z);
+    return BSP_OK;
 }
 
 template <int DT>
-void launch_mfma(dim3 grid, size_t lds, hipStream_t s, const uint16_t *U, int64_t T, int64_t M, int64_t N, int64_t B,
+int launch_mfma(dim3 grid, size_t lds, hipStream_t s, const uint16_t *U, int64_t T, int64_t M, int64_t N, int64_t B,
                  int32_t R, const int32_t *blk_cnt, const int32_t *blk_ptr, const int32_t *col_idx,
                  const uint16_t *vals, const void *bias, void *Z) {
 #define BSP_LT_ARGS grid, lds, s, U, T, M, N, B, R, blk_cnt, blk_ptr, col_idx, vals, bias, Z
     switch ((R + 15) / 16) {
-        case 1: R == 16 ? launch_mfma_one<DT, 1, true>(BSP_LT_ARGS) : launch_mfma_one<DT, 1, false>(BSP_LT_ARGS); break;
-        case 2: R == 32 ? launch_mfma_one<DT, 2, true>(BSP_LT_ARGS) : launch_mfma_one<DT, 2, false>(BSP_LT_ARGS); break;
-        case 3: R == 48 ? launch_mfma_one<DT, 3, true>(BSP_LT_ARGS) : launch_mfma_one<DT, 3, false>(BSP_LT_ARGS); break;
-        default: R == 64 ? launch_mfma_one<DT, 4, true>(BSP_LT_ARGS) : launch_mfma_one<DT, 4, false>(BSP_LT_ARGS); break;
+        case 1: return R == 16 ? launch_mfma_one<DT, 1, true>(BSP_LT_ARGS) : launch_mfma_one<DT, 1, false>(BSP_LT_ARGS);
+        case 2: return R == 32 ? launch_mfma_one<DT, 2, true>(BSP_LT_ARGS) : launch_mfma_one<DT, 2, false>(BSP_LT_ARGS);
+        case 3: return R == 48 ? launch_mfma_one<DT, 3, true>(BSP_LT_ARGS) : launch_mfma_one<DT, 3, false>(BSP_LT_ARGS);
+        default: return R == 64 ? launch_mfma_one<DT, 4, true>(BSP_LT_ARGS) : launch_mfma_one<DT, 4, false>(BSP_LT_ARGS);
     }
 #undef BSP_LT_ARGS
 }
@@ -465,12 +471,12 @@ extern "C" int bsp_linear_transposed(const void *U, int udt, int64_t T, int64_t 
         if (wgs >= ((int64_t)1 << 31)) return BSP_ERR_SHAPE;
         const dim3 grid((unsigned)wgs);
         const size_t lds = mfma_lds_bytes((R + 15) / 16);
-        if (udt == BSP_BF16)
-            launch_mfma<BSP_BF16>(grid, lds, s, (const uint16_t *)U, T, M, N, B, R, blk_cnt, blk_ptr, col_idx,
-                                  (const uint16_t *)vals, bias, Z);
-        else
-            launch_mfma<BSP_F16>(grid, lds, s, (const uint16_t *)U, T, M, N, B, R, blk_cnt, blk_ptr, col_idx,
-                                 (const uint16_t *)vals, bias, Z);
+        const int st = udt == BSP_BF16
+                           ? launch_mfma<BSP_BF16>(grid, lds, s, (const uint16_t *)U, T, M, N, B, R, blk_cnt, blk_ptr,
+                                                   col_idx, (const uint16_t *)vals, bias, Z)
+                           : launch_mfma<BSP_F16>(grid, lds, s, (const uint16_t *)U, T, M, N, B, R, blk_cnt, blk_ptr,
+                                                  col_idx, (const uint16_t *)vals, bias, Z);
+        if (st != BSP_OK) return st;
     } else {
         const int64_t tiles = (T + kGenTok - 1) / kGenTok;
         if (tiles >= ((int64_t)1 << 31)) return BSP_ERR_SHAPE;

@@ -1101,8 +1101,7 @@ int launch_nfrag(const TiledArgs &a, int waves, hipStream_t s) {
 
 }  // namespace
 
-static int g_tiled_waves = 16;
-void set_tiled_waves(int w) { g_tiled_waves = (w == 4 || w == 8 || w == 16) ? w : 16; }
+constexpr int kCanonicalWaves = 16;  // wavefronts per workgroup of the kernel on the compact storage
 
 int plan_slack_steps() { return kPlanRing; }
 
@@ -1117,8 +1116,8 @@ int launch_linear_tiled(const TiledArgs &args, bool plan, hipStream_t s) {
     TiledArgs a = args;
     a.npad = (int32_t)((a.N + 255) / 256 * 256);
     if (a.xdt == BSP_BF16)
-        return plan ? launch_nfrag<BSP_BF16, true>(a, g_tiled_waves, s) : launch_nfrag<BSP_BF16, false>(a, g_tiled_waves, s);
-    return plan ? launch_nfrag<BSP_F16, true>(a, g_tiled_waves, s) : launch_nfrag<BSP_F16, false>(a, g_tiled_waves, s);
+        return plan ? launch_nfrag<BSP_BF16, true>(a, kCanonicalWaves, s) : launch_nfrag<BSP_BF16, false>(a, kCanonicalWaves, s);
+    return plan ? launch_nfrag<BSP_F16, true>(a, kCanonicalWaves, s) : launch_nfrag<BSP_F16, false>(a, kCanonicalWaves, s);
 }
 
 }  // namespace bsp

@@ -274,7 +274,7 @@ inline PlanLayout plan_layout(int64_t M, int64_t N, int32_t R, int64_t capacity_
     L.steps = (size_t)((capacity_cols + 31) / 32) + (size_t)B * (kPlanMaxChunks - 1) + (size_t)plan_slack_steps();
     // entries per stream <= chunks * (blocks rounded up to whole groups) / streams, groups of at most 32 blocks
     // (16 streams of a one-chunk layer need less than the 8 streams of a chunked one)
-    L.wptr_bytes = ((size_t)kPlanWaves * (size_t)(kPlanMaxChunks * ((B + 31) / 32 * 4) + 1) * sizeof(int32_t) + 255) /
+    L.wptr_bytes = ((size_t)kPlanWavesWide * (size_t)(kPlanMaxChunks * ((B + 31) / 32 * 4) + 1) * sizeof(int32_t) + 255) /
                    256 * 256;
     L.wfrag_bytes = L.steps * (size_t)nfrag_of(R) * 1024;
     L.xoff_bytes = L.steps * 64;
@@ -355,6 +355,3 @@ extern "C" int bsp_linear_planned(const void *X, int xdt, int64_t T, int64_t M, 
     a.Y = Y;
     return launch_linear_tiled(a, true, (hipStream_t)stream);
 }
-
-// Experiment hook (not part of the documented ABI): wavefronts per workgroup of the canonical tiled kernel.
-extern "C" void bsp_debug_set_tiled_waves(int waves) { set_tiled_waves(waves); }
