@@ -14,7 +14,8 @@
  *   group  g = (b, j): the R weights W[bR .. bR+R-1, j].
  *   Every data pointer is a DEVICE pointer owned by the caller unless marked "host".
  *   The library allocates nothing and keeps no state between calls; scratch memory is
- *   passed in by the caller (see the *_workspace_bytes queries).
+ *   passed in by the caller (see the *_workspace_bytes queries).  The one exception is
+ *   bsp_prune_mask_static, whose scratch is a device array inside the library.
  *   Every call validates its arguments on the host, then enqueues its kernels on
  *   `stream` (a hipStream_t passed as void*; NULL = the default stream) and returns
  *   without waiting.  Return value: a bsp_status; nothing is launched unless it is BSP_OK.
@@ -91,6 +92,20 @@ size_t bsp_penalty_grad_workspace_bytes(int64_t M, int64_t N, int32_t R);
 int bsp_prune_mask(const float *sumsq, int64_t B, int64_t N, float t, int64_t n_keep, int scope,
                    uint8_t *keep, float *t_used, void *ws, size_t ws_bytes, void *stream);
 size_t bsp_prune_mask_workspace_bytes(int64_t B, int64_t N, int scope);
+
+/* ---- the same call for callers that cannot allocate (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc) ------------------------------------------
+ * bsp_prune_mask with its scratch taken from a device array inside the library instead of a
+ * workspace argument: same arguments otherwise, same kernels, same results bit for bit.  The
+ * call allocates and frees nothing.  The array (about 4.1 MiB, held on every GPU the library
+ * runs on until the process ends) serves every size the workspace form accepts: B*N < 2^31;
+ * larger inputs return BSP_ERR_SHAPE, a workspace need above the array BSP_ERR_CAPACITY.
+ * The array's device address is looked up on the first call on a device (make that call
+ * outside a graph capture).  All calls on one GPU share the array, whatever their stream:
+ * calls that overlap on one GPU race; order them on one stream or with events.  Nothing has
+ * to be cleared between calls (every launch overwrites what the next one reads). */
+int bsp_prune_mask_static(const float *sumsq, int64_t B, int64_t N, float t, int64_t n_keep, int scope,
+                          uint8_t *keep, float *t_used, void *stream);
 
 /* ---- refresh and gradient in one pass (Alg. 2 at a milestone: "update gamma", then the
  * regulariser term of the next step's gradient with the new factors) --------------------

@@ -55,6 +55,7 @@ def lib():
     L.bsp_penalty_grad_workspace_bytes.argtypes = [i64, i64, i32]
     L.bsp_penalty_grad_workspace_bytes.restype = sz
     L.bsp_prune_mask.argtypes = [vp, i64, i64, f32, i64, C.c_int, vp, vp, vp, sz, vp]
+    L.bsp_prune_mask_static.argtypes = [vp, i64, i64, f32, i64, C.c_int, vp, vp, vp]
     L.bsp_prune_mask_workspace_bytes.argtypes = [i64, i64, C.c_int]
     L.bsp_prune_mask_workspace_bytes.restype = sz
     L.bsp_mask_weights.argtypes = [vp, C.c_int, i64, i64, i32, vp, vp]
@@ -199,6 +200,16 @@ def bsp_prune_mask(sumsq, t=0.0, n_keep=-1, scope=SCOPE_BLOCK, keep=None, t_used
     st = lib().bsp_prune_mask(_ptr(sumsq, torch.float32), B, N, t, n_keep, scope, _ptr(keep, torch.uint8),
                               _ptr(t_used, torch.float32), _ptr(ws), ws_bytes, _stream())
     _check(st, "bsp_prune_mask")
+    return keep, t_used
+
+
+def bsp_prune_mask_static(sumsq, keep, t=0.0, n_keep=-1, scope=SCOPE_BLOCK, t_used=None):
+    """bsp_prune_mask for callers that cannot allocate: the outputs are the caller's, the scratch is the library's
+    own device array.  Calls on one GPU must not overlap."""
+    B, N = sumsq.shape
+    st = lib().bsp_prune_mask_static(_ptr(sumsq, torch.float32), B, N, t, n_keep, scope, _ptr(keep, torch.uint8),
+                                     _ptr(t_used, torch.float32), _stream())
+    _check(st, "bsp_prune_mask_static")
     return keep, t_used
 
 

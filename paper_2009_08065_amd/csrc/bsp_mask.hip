@@ -9,6 +9,8 @@
 //                     its share and flushes the non-empty bins to a global histogram; the next
 //                     launch starts by locating the digit that holds the wanted rank.
 // The final pass writes keep = (sumsq > threshold).
+#include <mutex>
+
 #include "bsp_common.h"
 
 namespace bsp {
@@ -402,8 +404,9 @@ extern "C" size_t bsp_prune_mask_workspace_bytes(int64_t B, int64_t N, int scope
     return ((size_t)kStateWords + 2 * (size_t)select_slots(B * N) * kSlot) * sizeof(uint32_t);
 }
 
-extern "C" int bsp_prune_mask(const float *sumsq, int64_t B, int64_t N, float t, int64_t n_keep, int scope,
-                              uint8_t *keep, float *t_used, void *ws, size_t ws_bytes, void *stream) {
+namespace {
+int prune_mask_launch(const float *sumsq, int64_t B, int64_t N, float t, int64_t n_keep, int scope, uint8_t *keep,
+                      float *t_used, void *ws, size_t ws_bytes, void *stream) {
     if (!sumsq || !keep) return BSP_ERR_NULL;
     if (B <= 0 || N <= 0 || B * N >= ((int64_t)1 << 31)) return BSP_ERR_SHAPE;
     if (scope != BSP_SCOPE_BLOCK && scope != BSP_SCOPE_MATRIX) return BSP_ERR_DTYPE;
@@ -436,6 +439,60 @@ extern "C" int bsp_prune_mask(const float *sumsq, int64_t B, int64_t N, float t,
     ga = ga < 1 ? 1 : (ga > 256 ? 256 : ga);  // a workgroup per compute unit at most: each starts by resolving the last digit
     mask_rank_apply_kernel<<<(unsigned)ga, kSelThreads, 0, s>>>(sumsq, n, (uint32_t)P, G, w, keep, t_used);
     return check_launch();
+}
+
+// Scratch of the entry point that allocates nothing: the percentile's state words and histogram slots at their
+// largest (kMaxSlots workgroups per histogram launch, two slot arrays), about 4.1 MiB per GPU.  In host code the
+// name below is only a handle; the array's device address is looked up once per device.
+constexpr size_t kStaticScratchWords = (size_t)kStateWords + 2 * (size_t)kMaxSlots * kSlot;
+constexpr int kMaxDevices = 64;
+}  // namespace
+
+static __device__ __align__(256) uint32_t scratch[kStaticScratchWords];
+
+namespace {
+std::mutex g_scratch_lock;
+uint32_t *g_scratch_ptr[kMaxDevices];  // per device, filled on the first call there
+
+int static_scratch(uint32_t **out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) {
+        set_last_hip_error((int)e);
+        return BSP_ERR_HIP;
+    }
+    if (dev < 0 || dev >= kMaxDevices) return BSP_ERR_SHAPE;
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));  // the address of this device's copy of the array
+        if (e != hipSuccess || !p) {
+            set_last_hip_error((int)e);
+            return BSP_ERR_HIP;
+        }
+        g_scratch_ptr[dev] = (uint32_t *)p;
+    }
+    *out = g_scratch_ptr[dev];
+    return BSP_OK;
+}
+}  // namespace
+
+extern "C" int bsp_prune_mask(const float *sumsq, int64_t B, int64_t N, float t, int64_t n_keep, int scope,
+                              uint8_t *keep, float *t_used, void *ws, size_t ws_bytes, void *stream) {
+    return prune_mask_launch(sumsq, B, N, t, n_keep, scope, keep, t_used, ws, ws_bytes, stream);
+}
+
+extern "C" int bsp_prune_mask_static(const float *sumsq, int64_t B, int64_t N, float t, int64_t n_keep, int scope,
+                                     uint8_t *keep, float *t_used, void *stream) {
+    if (B <= 0 || N <= 0 || B * N >= ((int64_t)1 << 31)) return BSP_ERR_SHAPE;  // beyond what the scratch serves
+    if (bsp_prune_mask_workspace_bytes(B, N, scope) > kStaticScratchWords * sizeof(uint32_t)) return BSP_ERR_CAPACITY;
+    uint32_t *ws = nullptr;
+    const int st = static_scratch(&ws);
+    if (st != BSP_OK) return st;
+    // every histogram launch overwrites the state words and all the slots the next launch reads, so nothing of
+    // the previous call's contents has to be cleared
+    return prune_mask_launch(sumsq, B, N, t, n_keep, scope, keep, t_used, ws, kStaticScratchWords * sizeof(uint32_t),
+                             stream);
 }
 
 extern "C" int bsp_mask_weights(void *W, int wdt, int64_t M, int64_t N, int32_t R, const uint8_t *keep, void *stream) {
