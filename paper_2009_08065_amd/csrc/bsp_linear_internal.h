@@ -21,6 +21,7 @@ struct TiledArgs {
     const void *wfrag;        // planned source: [step][fragment][lane] 16-byte panel fragments
     const uint32_t *xoff;     // planned source: [step][lane] two 16-bit LDS byte offsets
     int64_t plan_steps;       // planned source: steps the fragment / offset regions hold (slack included)
+    int64_t capacity_cols;    // planned source: the caller's bound on the padded kept columns of the storage
     const void *bias;
     void *Y;
 };

@@ -351,6 +351,7 @@ extern "C" int bsp_linear_planned(const void *X, int xdt, int64_t T, int64_t M, 
     a.wfrag = (const uint8_t *)plan + L.wptr_bytes;
     a.xoff = (const uint32_t *)((const uint8_t *)plan + L.wptr_bytes + L.wfrag_bytes);
     a.plan_steps = (int64_t)L.steps;
+    a.capacity_cols = capacity_cols;
     a.bias = bias;
     a.Y = Y;
     return launch_linear_tiled(a, true, (hipStream_t)stream);
