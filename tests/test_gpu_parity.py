@@ -35,6 +35,13 @@ def bits_equal(gpu_f32, ref_f32):
     return np.array_equal(a, b)
 
 
+# What the arithmetic allows, far inside the stated tolerance: both sides round one fp32 / fp64 sum to the output
+# type, so they differ by at most one unit in the last place of that type where the sums straddle a rounding
+# boundary (2^-7 relative for bf16, 2^-10 for fp16), plus the fp32 accumulation error of the kernel, which is of
+# the order sqrt(k) 2^-24 of the rms of the outputs (k <= 4096 terms): 1e-3 rms leaves two decimal orders of room.
+ULP = {"bf16": 2.0 ** -7, "f16": 2.0 ** -10}
+
+
 def assert_y_close(y_gpu, y_ref, dtype, rows=None):
     y_ref = y_ref.astype(np.float64)
     y_gpu = y_gpu.astype(np.float64)
@@ -42,7 +49,9 @@ def assert_y_close(y_gpu, y_ref, dtype, rows=None):
         y_ref, y_gpu = y_ref[rows], y_gpu[rows]
     rms = np.sqrt(np.mean(y_ref ** 2))
     err = np.abs(y_gpu - y_ref)
-    bound = TOL[dtype] * (np.abs(y_ref) + rms)
+    bound = TOL[dtype] * (np.abs(y_ref) + rms)          # the stated tolerance: max relative error, rms as the floor
+    if dtype in ULP:
+        bound = np.minimum(bound, ULP[dtype] * np.abs(y_ref) + 1e-3 * rms)
     if not np.all(err <= bound):     # (an all-zero reference has bound 0 and must be matched exactly)
         with np.errstate(divide="ignore", invalid="ignore"):
             worst = np.nanmax(np.where(err > bound, err / bound, 0.0))
@@ -314,11 +323,11 @@ def run_layer(X, W, bias, R, keep, k_align, dtype, T_rows=None):
 
 def _check_y(Y, X, p_ref, bias, code, dtype, T_rows):
     if T_rows is None:
-        Y_ref, _ = orc.linear_packed(X, p_ref, bias, ydt=code, n_threads=8)
+        Y_ref, _ = orc.linear_packed(X, p_ref, bias, ydt=code, n_threads=16)
         assert_y_close(Y, Y_ref, dtype)
     else:
         for (t0, t1) in T_rows:
-            Y_ref, _ = orc.linear_packed(X, p_ref, bias, ydt=code, t0=t0, t1=t1, n_threads=8)
+            Y_ref, _ = orc.linear_packed(X, p_ref, bias, ydt=code, t0=t0, t1=t1, n_threads=16)
             assert_y_close(Y, Y_ref, dtype, rows=slice(t0, t1))
 
 
@@ -386,7 +395,7 @@ def test_linear_planned_bias_at_odd_address(R):
     bias_odd = holder[1:]
     assert bias_odd.data_ptr() % 4 == 2
     Xd = dev(d["X"], "bf16")
-    Y_ref, _ = orc.linear_packed(d["X"], p_ref, d["bias"], ydt=CODE["bf16"], n_threads=8)
+    Y_ref, _ = orc.linear_packed(d["X"], p_ref, d["bias"], ydt=CODE["bf16"], n_threads=16)
     assert_y_close(host(bsp.bsp_linear_planned(Xd, p, bsp.bsp_linear_plan(p), bias_odd)), Y_ref, "bf16")
     assert_y_close(host(bsp.bsp_linear(Xd, p, bias_odd)), Y_ref, "bf16")
     # an output that does not start on a 16-byte boundary is refused (and left untouched)
@@ -433,7 +442,7 @@ def test_linear_seeded_random_shapes():
         p_ref = orc.pack(d["W"], R, keep, k_align, CODE[dt])
         p = bsp.bsp_pack(dev(d["W"], dt), R, torch.from_numpy(keep).cuda(), k_align)
         bias = dev(d["bias"], dt) if use_bias else None
-        Y_ref, _ = orc.linear_packed(d["X"], p_ref, d["bias"] if use_bias else None, ydt=CODE[dt], n_threads=8)
+        Y_ref, _ = orc.linear_packed(d["X"], p_ref, d["bias"] if use_bias else None, ydt=CODE[dt], n_threads=16)
         Xd = dev(d["X"], dt)
         case = dict(it=it, R=R, B=B, N=N, T=T, dt=dt, p=p_keep, k_align=k_align, bias=use_bias)
         try:
@@ -452,7 +461,7 @@ def run_transposed(U, W, bias, R, keep, k_align, dtype, T_rows=None):
     Z = host(bsp.bsp_linear_transposed(dev(U, dtype), p, dev(bias, dtype)))
     assert Z.shape == (U.shape[0], W.shape[1])
     for (t0, t1) in (T_rows or [(0, U.shape[0])]):
-        Z_ref, _ = orc.linear_t_packed(U, p_ref, bias, zdt=code, t0=t0, t1=t1, n_threads=8)
+        Z_ref, _ = orc.linear_t_packed(U, p_ref, bias, zdt=code, t0=t0, t1=t1, n_threads=16)
         assert_y_close(Z, Z_ref, dtype, rows=slice(t0, t1))
     return Z, p_ref
 
@@ -591,7 +600,8 @@ def test_config4_bert_large_layer_set_transposed(R):
         k_ref, _ = orc.mask_rank(s_ref, d["n_keep"], orc.SCOPE_MATRIX)
         T, M = d["X"].shape[0], W.shape[0]
         U = wl.normal(7000 + 10 * R + i, (T, M), 1.0, "bf16")
-        run_transposed(U, W, None, R, k_ref, 32, "bf16", T_rows=[(0, 40), (5000, 5030), (T - 12, T)])
+        run_transposed(U, W, None, R, k_ref, 32, "bf16",
+                       T_rows=None if R == 16 else [(0, 40), (5000, 5030), (T - 12, T)])   # R = 16: every token row
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -625,6 +635,7 @@ def test_config2_bf16_ffn_up_full_chain():
 
 
 def chain_matrix(d, k_align=32, rows=((0, 48), (5000, 5040), (8180, 8192))):
+    """rows=None: every token row is compared (the oracle needs about a second per matrix on 16 threads)."""
     W, R = d["W"], d["R"]
     Wd = dev(W, "bf16")
     s, _, _ = bsp.bsp_group_norms(Wd, R)
@@ -634,7 +645,8 @@ def chain_matrix(d, k_align=32, rows=((0, 48), (5000, 5040), (8180, 8192))):
     k_ref, t_ref = orc.mask_rank(s_ref, d["n_keep"], orc.SCOPE_MATRIX)
     assert np.array_equal(host(keep), k_ref) and bits_equal(host(t_used), t_ref)
     T = d["X"].shape[0]
-    rows = [(min(a, T - 1), min(b, T)) for a, b in rows]
+    if rows is not None:
+        rows = [(min(a, T - 1), min(b, T)) for a, b in rows]
     run_layer(d["X"], W, d["bias"], R, k_ref, k_align, "bf16", T_rows=rows)
 
 
@@ -645,8 +657,10 @@ def test_config3_bert_base_layer_set():
 
 @pytest.mark.parametrize("R", [8, 16, 32])
 def test_config4_bert_large_layer_set(R):
+    """The benchmark's set at its full size, in the launch configuration the benchmark times.  R = 16 (the benchmark's
+    block size): all 8192 token rows of all four matrices, element by element; R = 8, 32: sampled token rows."""
     for d in wl.config4(R=R):
-        chain_matrix(d)
+        chain_matrix(d, rows=None if R == 16 else ((0, 48), (5000, 5040), (8180, 8192)))
 
 
 def test_config5_full_weight_set_sampled():
