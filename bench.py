@@ -121,6 +121,122 @@ class Matrix:
         return 2.0 * self.T * self.N + 2.0 * self.T * self.M + 2.0 * self.R * padded + 4.0 * padded + 2.0 * self.M
 
 
+def time_layers(mats, steps, warmup):
+    """The layer launches of the set, in turn on the launch stream, each between two events: [steps, matrices] ms."""
+    evs = [[[torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)] for _ in mats]
+           for _ in range(steps)]
+    for _ in range(warmup):
+        for m in mats:
+            m.linear()
+    torch.cuda.synchronize()
+    for s_i in range(steps):
+        for i, m in enumerate(mats):
+            evs[s_i][i][0].record()
+            m.linear()
+            evs[s_i][i][1].record()
+    torch.cuda.synchronize()
+    return np.array([[e[0].elapsed_time(e[1]) for e in ev] for ev in evs])
+
+
+def per_matrix_report(mats, lin_avg_ms):
+    out = {}
+    for m, ms in zip(mats, lin_avg_ms):
+        by = m.linear_bytes()
+        out[m.name] = {
+            "shape": [m.M, m.N], "kept_cols": m.kept_cols,
+            "rate": round(bsp.bsp_compression_rate(m.M, m.N, m.R, m.kept_cols), 4),
+            "us": round(float(ms) * 1e3, 2),
+            "useful_tflops": round(m.useful_flops() / (ms * 1e-3) / 1e12, 2),
+            "dense_equiv_tflops": round(m.dense_flops() / (ms * 1e-3) / 1e12, 2),
+            "hbm_gbs": round(by / (ms * 1e-3) / 1e9, 1),
+            "frac_mfma_peak": round(m.useful_flops() / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+            "frac_hbm_peak": round(by / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        }
+    return out
+
+
+def prepared_set(descs, scope=None):
+    """Matrices of a workload with the storage and plan built once (kept counts read back for the accounting)."""
+    mats = [Matrix(d) for d in descs]
+    for m in mats:
+        m.prune_and_pack()
+        m.linear()
+    torch.cuda.synchronize()
+    for m in mats:
+        m.kept_cols = int(m.blk_cnt.sum().item())
+    return mats
+
+
+def linear_only_set(descs, steps, warmup, label):
+    """Layer-only timing of a whole set (one entry per matrix and the set's totals)."""
+    mats = prepared_set(descs)
+    ms = time_layers(mats, steps, warmup).mean(axis=0)
+    useful = sum(m.useful_flops() for m in mats)
+    tot = float(ms.sum())
+    res = {"workload": label, "ms": round(tot, 4), "useful_tflops": round(useful / (tot * 1e-3) / 1e12, 2),
+           "frac_mfma_peak": round(useful / (tot * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+           "frac_hbm_peak": round(sum(m.linear_bytes() for m in mats) / (tot * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+           "per_matrix": per_matrix_report(mats, ms)}
+    del mats
+    return res
+
+
+def config1_latency(reps=5, launches=200):
+    """Config 1 (BERT-base attention projection, fp32, 128 tokens, half of the columns kept per block): a
+    latency case.  `launches` calls recorded into one HIP graph, the graph replayed `reps` times between two
+    events; the median over the replays, per call."""
+    c = wl.config1()
+    W = torch.from_numpy(c["W"]).cuda()
+    X = torch.from_numpy(c["X"]).cuda()
+    b = torch.from_numpy(c["bias"]).cuda()
+    p = bsp.bsp_pack(W, c["R"], torch.from_numpy(c["keep"]).cuda(), 32)
+    Y = torch.empty((X.shape[0], W.shape[0]), dtype=torch.float32, device="cuda")
+    bsp.bsp_linear(X, p, b, Y=Y)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for _ in range(launches):
+            bsp.bsp_linear(X, p, b, Y=Y)
+    g.replay()
+    torch.cuda.synchronize()
+    us = []
+    for _ in range(reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(); g.replay(); e1.record()
+        torch.cuda.synchronize()
+        us.append(e0.elapsed_time(e1) * 1e3 / launches)
+    kept = int(p.blk_cnt.sum().item())
+    med = float(np.median(us))
+    flops = 2.0 * X.shape[0] * c["R"] * kept
+    return {"workload": "config 1: X 128x768, W 768x768, fp32, R = 16, 384 of 768 columns kept per block",
+            "dtype": "f32", "us_per_call": round(med, 2), "useful_gflops": round(flops / med / 1e3, 1),
+            "note": "launch-bound: 75 MFLOP of useful work per call"}
+
+
+def config2_layer(c, steps):
+    """Config 2 (BERT-base FFN up-projection, 4096 tokens, the top 256 of 768 groups of every row-block: 3x)."""
+    d = dict(c)
+    per_block = d["n_keep"]
+    d["n_keep"] = per_block * (d["M"] // d["R"])     # what the storage has to hold
+    m = Matrix(d)
+    bsp.bsp_group_norms(m.W, m.R, eps=1e-6, mode=bsp.ALPHA_SQNORM, sumsq=m.sumsq, alpha=m.alpha, want=())
+    bsp.bsp_prune_mask(m.sumsq, n_keep=per_block, scope=bsp.SCOPE_BLOCK, keep=m.keep)
+    bsp.bsp_pack_count(m.keep, m.k_align, blk_cnt=m.blk_cnt, blk_ptr=m.blk_ptr)
+    st = bsp.lib().bsp_pack(m.W.data_ptr(), bsp.BF16, m.M, m.N, m.R, m.keep.data_ptr(), m.k_align,
+                            m.blk_cnt.data_ptr(), m.blk_ptr.data_ptr(), m.capacity, m.col_idx.data_ptr(),
+                            m.vals.data_ptr(), bsp.BF16, torch.cuda.current_stream().cuda_stream)
+    if st != 0:
+        raise bsp.BspError(st, "bsp_pack")
+    if m.use_plan:
+        bsp.bsp_linear_plan(m.packed, plan=m.plan)
+    m.linear()
+    torch.cuda.synchronize()
+    m.kept_cols = int(m.blk_cnt.sum().item())
+    ms = time_layers([m], steps, 5).mean(axis=0)
+    return {"workload": "config 2: X 4096x768, W 3072x768, bf16, R = 16, block-scope percentile, 256 of 768 kept (3x)",
+            "per_matrix": per_matrix_report([m], ms)}
+
+
 def cpu_baseline(mats):
     """The CPU oracle's layer on the same workload (all four matrices, all tokens: about a
     second per matrix on this machine's host cores), timed as it stands."""
@@ -153,7 +269,7 @@ def transposed_product(mats, reps=10, with_cpu=True):
     """The transposed product Z = U Wp (input gradient of the layer; the layer of the row-segment variant on a
     transposed matrix) on the same four compact storages: U is a synthetic [tokens, M] bf16 tensor, every launch
     between two events on the launch stream.  Algorithmic bytes: U read once, Z written once, the storage read once."""
-    out, tot_us, tot_flops, lds_bytes = {}, 0.0, 0.0, 0.0
+    out, tot_us, tot_flops, lds_bytes, hbm_bytes = {}, 0.0, 0.0, 0.0, 0.0
     for m in mats:
         gen = torch.Generator(device="cuda").manual_seed(4200 + m.M + m.N)   # seeded: the stand-in for an output gradient
         U = torch.randn((m.T, m.M), device="cuda", generator=gen).to(torch.bfloat16)
@@ -173,6 +289,7 @@ def transposed_product(mats, reps=10, with_cpu=True):
         tf = m.useful_flops() / us / 1e6
         lds = 8.0 * m.T * m.kept_cols    # one fp32 cell read and written per token, kept column and row-block
         lds_bytes += lds
+        hbm_bytes += by
         out[m.name] = {"shape": [m.M, m.N], "us": round(us, 1), "useful_tflops": round(tf, 2),
                        "lds_gbs": round(lds / us / 1e3, 1),
                        "frac_mfma_peak": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
@@ -183,10 +300,13 @@ def transposed_product(mats, reps=10, with_cpu=True):
     res = {"kernel": "linear_t_mfma_kernel", "per_matrix": out, "us": round(tot_us, 1),
            "useful_tflops": round(tot_flops / tot_us / 1e6, 2),
            "frac_mfma_peak": round(tot_flops / tot_us / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4),
-           "roofline": {"bound": "lds", "achieved": round(lds_bytes / tot_us / 1e3, 1), "peak": LDS_PEAK_GBS,
-                        "unit": "GB/s", "frac": round(lds_bytes / tot_us / 1e3 / LDS_PEAK_GBS, 4),
-                        "note": "algorithmic LDS bytes: every product of R weights is one 4-byte read and one 4-byte "
-                                "write of the fp32 tile; peak = 256 compute units x 256 B/clk x 2.4 GHz"}}
+           # the method's traffic: U read once, Z written once, the storage read once (the same pair of roofs as the layer)
+           "roofline": {"bound": "hbm", "achieved": round(hbm_bytes / tot_us / 1e3, 1), "peak": HBM_PEAK_GBS,
+                        "unit": "GB/s", "frac": round(hbm_bytes / tot_us / 1e3 / HBM_PEAK_GBS, 4), "traffic": None},
+           "lds_diagnostic": {"achieved_gbs": round(lds_bytes / tot_us / 1e3, 1), "peak_gbs": LDS_PEAK_GBS,
+                              "frac": round(lds_bytes / tot_us / 1e3 / LDS_PEAK_GBS, 4),
+                              "note": "what this design moves through LDS: one fp32 cell of the tile read and written per "
+                                      "token, kept column and row-block; 256 compute units x 256 B/clk x 2.4 GHz"}}
     if with_cpu:
         from oracle import bsp_oracle as orc
         m = mats[2]
@@ -422,6 +542,11 @@ def main():
                     help="skip the layer-only table over BERT-base / BERT-large shapes and compression rates")
     ap.add_argument("--no-transposed", action="store_true",
                     help="skip the timing of the transposed product (input gradient) on the same storages")
+    ap.add_argument("--only", choices=["layer", "transposed"], default=None,
+                    help="run nothing but the layer launches (or the transposed product's) of the workload, `--steps` "
+                         "times in turn: the command the kernel profiles under profiles/ are taken with")
+    ap.add_argument("--no-sets", action="store_true",
+                    help="skip the layer-only lines of R = 8 and R = 32 and of configs 1 to 3")
     ap.add_argument("--no-c5", action="store_true",
                     help="skip the bandwidth measurement of the pruning pipeline on the 302 M parameter weight set")
     args = ap.parse_args()
@@ -446,6 +571,14 @@ def main():
     torch.cuda.synchronize()
     for m in mats:
         m.kept_cols = int(m.blk_cnt.sum().item())
+    if args.only == "layer":
+        ms = time_layers(mats, args.steps, args.warmup).mean(axis=0)
+        print(json.dumps({"only": "layer", "block_rows": args.R, "per_matrix": per_matrix_report(mats, ms)}))
+        return
+    if args.only == "transposed":
+        print(json.dumps({"only": "transposed", "block_rows": args.R,
+                          "transposed_product": transposed_product(mats, reps=args.steps, with_cpu=False)}))
+        return
 
     graphs, side_streams = [], []
     if args.launch == "serial":
@@ -461,7 +594,7 @@ def main():
             with torch.cuda.graph(g):
                 m.whole_step()
             graphs.append(g)
-        pool = [torch.cuda.Stream() for _ in range(8)]   # default priority
+        pool = [torch.cuda.Stream() for _ in range(4)]   # default priority
 
     def step():
         if args.launch == "eager":
@@ -487,18 +620,7 @@ def main():
         torch.cuda.synchronize()
 
     if args.launch == "overlap":
-        # streams are spread over a few hardware queues in creation order, and two streams on one queue
-        # run in turn: try three choices of four streams for a few steps and keep the quickest
-        best = None
-        for first in (0, 2, 4):
-            side_streams = pool[first:first + 4]
-            run_steps(2)
-            t0 = time.perf_counter()
-            run_steps(5)
-            dt = time.perf_counter() - t0
-            if best is None or dt < best[0]:
-                best = (dt, first)
-        side_streams = pool[best[1]:best[1] + 4]
+        side_streams = pool[:4]   # always the first four streams created: no search for a lucky choice
 
     run_steps(args.warmup)
     t0 = time.perf_counter()
@@ -506,39 +628,15 @@ def main():
     wall = time.perf_counter() - t0
 
     # second pass: the layer launches alone, each between two events on the launch stream
-    evs = [[[torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)] for _ in mats]
-           for _ in range(args.steps)]
-    for _ in range(args.warmup):
-        for m in mats:
-            m.linear()
-    torch.cuda.synchronize()
-    for s_i in range(args.steps):
-        for i, m in enumerate(mats):
-            evs[s_i][i][0].record()
-            m.linear()
-            evs[s_i][i][1].record()
-    torch.cuda.synchronize()
-
     ms_per_step = wall * 1e3 / args.steps
-    lin_ms = np.array([[e[0].elapsed_time(e[1]) for e in ev] for ev in evs])       # [steps, matrices]
+    lin_ms = time_layers(mats, args.steps, args.warmup)                             # [steps, matrices]
     lin_avg = lin_ms.mean(axis=0)
     useful = sum(m.useful_flops() for m in mats)
     dense = sum(m.dense_flops() for m in mats)
     lin_bytes = [m.linear_bytes() for m in mats]
     lin_total_ms = float(lin_avg.sum())
 
-    per_matrix = {}
-    for m, ms, by in zip(mats, lin_avg, lin_bytes):
-        per_matrix[m.name] = {
-            "shape": [m.M, m.N], "kept_cols": m.kept_cols,
-            "rate": round(bsp.bsp_compression_rate(m.M, m.N, m.R, m.kept_cols), 4),
-            "us": round(float(ms) * 1e3, 2),
-            "useful_tflops": round(m.useful_flops() / (ms * 1e-3) / 1e12, 2),
-            "dense_equiv_tflops": round(m.dense_flops() / (ms * 1e-3) / 1e12, 2),
-            "hbm_gbs": round(by / (ms * 1e-3) / 1e9, 1),
-            "frac_mfma_peak": round(m.useful_flops() / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
-            "frac_hbm_peak": round(by / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-        }
+    per_matrix = per_matrix_report(mats, lin_avg)
 
     # the layer kernel that takes the most time per step: algorithmic bytes of its launches over their durations
     def kernel_of(m):
@@ -586,6 +684,22 @@ def main():
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(mats)
+    if not args.no_sets:
+        k = max(10, args.steps // 4)
+        sets = {}
+        for R in (8, 16, 32):
+            if R != args.R:
+                sets["config4_R%d" % R] = linear_only_set(
+                    wl.config4(R=R), k, 5, "config 4 (BERT-large set, 8192 tokens, 5x) with row-blocks of %d rows" % R)
+        sets["config3"] = linear_only_set(
+            wl.config3(), k, 5, "config 3 (BERT-base set, 8192 tokens, R = 16, per-matrix rate drawn from 1.5x, 2x, "
+                                "3x, 5x, matrix-scope percentile), the four layers timed in turn")
+        sets["config3"]["rates"] = {d["name"]: "%d/%d" % d["rate"] for d in wl.config3(tokens=16)}
+        c2 = wl.config2()
+        c2.update(name="ffn_up", T=c2["X"].shape[0])
+        sets["config2"] = config2_layer(c2, k)
+        sets["config1"] = config1_latency()
+        out["linear_only_sets"] = sets
     if not args.no_grid:
         out["linear_grid"] = linear_grid()
     if not args.no_transposed:

@@ -150,6 +150,78 @@ __global__ __launch_bounds__(kThreads) void linear_mfma_direct_kernel(const uint
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// fp32 matrix-core kernel, direct-gather form: a workgroup of four wavefronts = 16 tokens x one row-block.
+// v_mfma_f32_16x16x4_f32 with A = value panel (16 rows x 4 kept columns: lane (row, k) holds one value),
+// B = gathered X (4 kept columns x 16 tokens: lane (token, k) holds one value).  The kept columns of the
+// row-block are dealt to the four wavefronts in quarters (a layer of this kind is a latency case: a few
+// hundred kept columns, little work, so the chain of dependent loads is what is cut), their partial sums
+// meet in LDS.  Any R, any k_align.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void linear_f32_mfma_kernel(const float *__restrict__ X, int64_t T, int64_t M,
+                                                                   int64_t N, int32_t R,
+                                                                   const int32_t *__restrict__ blk_ptr,
+                                                                   const int32_t *__restrict__ col_idx,
+                                                                   const float *__restrict__ vals,
+                                                                   const float *__restrict__ bias,
+                                                                   float *__restrict__ Y) {
+    __shared__ float red[3][4][64];  // partial sums of wavefronts 1 .. 3: [wavefront][register][lane]
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l16 = lane & 15, g = lane >> 4;
+    const int64_t b = blockIdx.y;
+    const int64_t t = (int64_t)blockIdx.x * 16 + l16;  // this lane's token (B operand / output column)
+    const int64_t base = blk_ptr[b];
+    const int kp = blk_ptr[b + 1] - blk_ptr[b];
+    const bool tok_ok = t < T;
+    const float *xrow = X + (tok_ok ? t : 0) * N;
+    const int nsteps = (kp + 3) >> 2, per = (nsteps + 3) >> 2;
+    const int s_lo = wave * per, s_hi = min(nsteps, s_lo + per);
+    for (int sub = 0; sub * 16 < R; ++sub) {
+        const int r = sub * 16 + l16;  // this lane's panel row (A operand)
+        const bool row_ok = r < R;
+        const float *wrow = vals + (int64_t)R * base + (int64_t)(row_ok ? r : 0) * kp;
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        constexpr int kU = 8;  // steps whose loads are in flight together
+        for (int s0 = s_lo; s0 < s_hi; s0 += kU) {
+            float a[kU], x[kU];
+            int c[kU];
+#pragma unroll
+            for (int u = 0; u < kU; ++u) {
+                const int k = 4 * (s0 + u) + g;
+                const bool ok = s0 + u < s_hi && k < kp;
+                c[u] = ok ? col_idx[base + k] : 0;
+                a[u] = (ok && row_ok) ? wrow[k] : 0.0f;
+            }
+#pragma unroll
+            for (int u = 0; u < kU; ++u) {
+                const int k = 4 * (s0 + u) + g;
+                const bool ok = s0 + u < s_hi && k < kp;
+                x[u] = (ok && tok_ok) ? xrow[c[u]] : 0.0f;
+            }
+#pragma unroll
+            for (int u = 0; u < kU; ++u) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u], x[u], acc, 0, 0, 0);
+        }
+        if (wave > 0) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) red[wave - 1][v][lane] = acc[v];
+        }
+        __syncthreads();
+        if (wave == 0 && tok_ok) {
+            // acc[v] = Y[t, bR + sub*16 + 4g + v] before the bias
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int rr = sub * 16 + 4 * g + v;
+                if (rr < R) {
+                    const int64_t m = b * R + rr;
+                    const float sum = ((acc[v] + red[0][v][lane]) + red[1][v][lane]) + red[2][v][lane];
+                    Y[t * M + m] = sum + (bias ? bias[m] : 0.0f);
+                }
+            }
+        }
+        __syncthreads();  // the partial sums are reused by the next 16 rows
+    }
+}
+
 }  // namespace
 }  // namespace bsp
 
@@ -190,6 +262,11 @@ extern "C" int bsp_linear(const void *X, int xdt, int64_t T, int64_t M, int64_t 
         else
             linear_mfma_direct_kernel<BSP_F16><<<grid, kThreads, 0, s>>>((const uint16_t *)X, T, M, N, R, blk_ptr,
                                                                          col_idx, (const uint16_t *)vals, bias, Y);
+    } else if (xdt == BSP_F32) {
+        const int64_t tiles16 = (T + 15) / 16;
+        if (tiles16 >= ((int64_t)1 << 31)) return BSP_ERR_SHAPE;
+        linear_f32_mfma_kernel<<<dim3((unsigned)tiles16, (unsigned)B, 1), kThreads, 0, s>>>(
+            (const float *)X, T, M, N, R, blk_ptr, col_idx, (const float *)vals, (const float *)bias, (float *)Y);
     } else {
         BSP_DISPATCH_DTYPE(xdt, DT, {
             linear_general_kernel<DT><<<grid, kThreads, 0, s>>>(X, T, M, N, R, blk_ptr, col_idx, vals, bias, Y);
