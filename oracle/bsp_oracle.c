@@ -450,3 +450,106 @@ double orc_compression_rate(int64_t M, int64_t N, int32_t R, int64_t kept_cols_t
     if (kept_cols_total <= 0) return INFINITY;
     return ((double)M * (double)N) / ((double)R * (double)kept_cols_total);
 }
+
+/* ------------------------------------------------------------------------------------ */
+/* Epilogue of a layer (Sec. 4.4 names the operations around the pruned product as what  */
+/* a deployed layer fuses; the Transformer blocks of Sec. 4.2 follow the FFN              */
+/* up-projection with GELU and the attention-output and FFN down-projections with a       */
+/* residual addition).  Element-wise, on the unrounded sums Yd (bias already added):      */
+/*   y = Yd;  act == 1: y = 0.5 y (1 + erf(y / sqrt 2))  (the exact GELU, BERT's form);    */
+/*   residual != NULL: y += residual;  then one rounding to ydt.                          */
+/* ------------------------------------------------------------------------------------ */
+void orc_epilogue(const double *Yd, const float *residual, int64_t n, int32_t act, int32_t ydt,
+                  float *Y, double *Ye)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        double y = Yd[i];
+        if (act == 1) y = 0.5 * y * (1.0 + erf(y / sqrt(2.0)));
+        if (residual) y += (double)residual[i];
+        if (Ye) Ye[i] = y;
+        if (Y) Y[i] = (float)orc_round(y, ydt);
+    }
+}
+
+/* ------------------------------------------------------------------------------------ */
+/* Gradient of the layer with respect to its kept weights (Alg. 2 updates W from the      */
+/* gradient of the loss; for Y = X Wp^T + bias of Sec. 3.1 the chain rule gives           */
+/* dW[m, j] = sum_t dY[t, m] X[t, j], needed on kept groups only), in the layout of the   */
+/* value panels:                                                                          */
+/*   dvals[R*blk_ptr[b] + r*kp_b + c] = sum_{t ascending} dY[t, bR + r] * X[t, col_idx[b, c]]  c < k_b */
+/*                                    = +0                                                   pad  */
+/* accumulated in double, then rounded to gdt.  Dd (double, same layout) is optional.     */
+/* ------------------------------------------------------------------------------------ */
+void orc_linear_dvals(const float *X, const float *dY, int64_t T, int64_t M, int64_t N, int32_t R,
+                      const int32_t *blk_cnt, const int32_t *blk_ptr, const int32_t *col_idx,
+                      int32_t gdt, float *D, double *Dd, int32_t n_threads)
+{
+    int64_t B = M / R;
+    if (n_threads < 1) n_threads = 1;
+#pragma omp parallel for num_threads(n_threads) schedule(dynamic, 1)
+    for (int64_t b = 0; b < B; ++b) {
+        int64_t base = blk_ptr[b];
+        int32_t kp = blk_ptr[b + 1] - blk_ptr[b], kb = blk_cnt[b];
+        for (int32_t r = 0; r < R; ++r)
+            for (int32_t c = 0; c < kp; ++c) {
+                double acc = 0.0;
+                if (c < kb) {
+                    int64_t j = col_idx[base + c];
+                    for (int64_t t = 0; t < T; ++t)
+                        acc += (double)dY[t * M + b * R + r] * (double)X[t * N + j];
+                }
+                int64_t at = R * base + (int64_t)r * kp + c;
+                if (Dd) Dd[at] = acc;
+                if (D) D[at] = (c < kb) ? (float)orc_round(acc, gdt) : 0.0f;
+            }
+    }
+}
+
+/* ------------------------------------------------------------------------------------ */
+/* Whole-block pruning, the comparison of Sec. 4.4 / Table 4 ("block sparse": a block is  */
+/* kept or removed as a whole).  A tile = the R rows of row-block b times the C columns   */
+/* jC .. jC + C - 1.  Its sum of squares is the sum of its C column-group sums, added in  */
+/* fp32, columns ascending, starting from +0 (the group sums s[b, j] are those of          */
+/* orc_sumsq, so both sides build on bit-identical inputs).  N % C == 0.                   */
+/*   ts[b, jt] = (((s[b, jtC] + s[b, jtC+1]) + ...) + s[b, jtC + C - 1])                    */
+/* The decision (threshold or percentile) is then Alg. 1's, taken on ts by the functions  */
+/* above, and orc_expand_tile_mask spreads a tile's decision over its C columns.          */
+/* ------------------------------------------------------------------------------------ */
+void orc_tile_sumsq(const float *s, int64_t B, int64_t N, int32_t C, float *ts)
+{
+    int64_t NT = N / C;
+    for (int64_t b = 0; b < B; ++b)
+        for (int64_t jt = 0; jt < NT; ++jt) {
+            float acc = 0.0f;
+            for (int32_t c = 0; c < C; ++c) acc = acc + s[b * N + jt * C + c];
+            ts[b * NT + jt] = acc;
+        }
+}
+
+void orc_expand_tile_mask(const uint8_t *tkeep, int64_t B, int64_t N, int32_t C, uint8_t *keep)
+{
+    int64_t NT = N / C;
+    for (int64_t b = 0; b < B; ++b)
+        for (int64_t j = 0; j < N; ++j) keep[b * N + j] = tkeep[b * NT + j / C] ? 1 : 0;
+}
+
+/* ------------------------------------------------------------------------------------ */
+/* Group sums of the other division (Eq. 2; Alg. 1 as printed: the matrix is cut into     */
+/* column blocks of C columns and the norm is taken over each row of a block), on the     */
+/* matrix as it is stored:  s[m, q] = sum_{c ascending} W[m, qC + c]^2, fp32, one fused    */
+/* multiply-add per element, starting from +0: the same canonical chain as orc_sumsq,     */
+/* along a row segment instead of a column segment.  W: [M, N], N % C == 0; s: [M, N/C].   */
+/* ------------------------------------------------------------------------------------ */
+void orc_rowseg_sumsq(const float *W, int64_t M, int64_t N, int32_t C, float *s)
+{
+    int64_t Q = N / C;
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t q = 0; q < Q; ++q) {
+            float acc = 0.0f;
+            for (int32_t c = 0; c < C; ++c) {
+                float w = W[m * N + q * C + c];
+                acc = fmaf(w, w, acc);
+            }
+            s[m * Q + q] = acc;
+        }
+}

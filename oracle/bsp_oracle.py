@@ -227,3 +227,67 @@ def adam_step(W, G, m, v, R, lr, beta1=0.9, beta2=0.999, eps=1e-8, t=1, alpha=No
 
 def compression_rate(M, N, R, kept_cols_total):
     return lib().orc_compression_rate(M, N, R, kept_cols_total)
+
+
+ACT_NONE, ACT_GELU = 0, 1
+
+
+def epilogue(Yd, act=ACT_NONE, residual=None, ydt=F32):
+    """Element-wise tail of a layer on its unrounded sums: optional exact (erf) GELU, optional residual addition,
+    one rounding.  Returns (Y rounded, Y double)."""
+    Yd = np.ascontiguousarray(Yd, dtype=np.float64)
+    res = None if residual is None else _f32(residual)
+    assert res is None or res.shape == Yd.shape
+    Y = np.empty(Yd.shape, dtype=np.float32)
+    Ye = np.empty(Yd.shape, dtype=np.float64)
+    lib().orc_epilogue(_p(Yd), _p(res), C.c_int64(Yd.size), C.c_int32(act), C.c_int32(ydt), _p(Y), _p(Ye))
+    return Y, Ye
+
+
+def linear_packed_fused(X, packed, bias, act=ACT_NONE, residual=None, ydt=F32, n_threads=1):
+    """The layer followed by its epilogue: (Y rounded, Y double)."""
+    _, Yd = linear_packed(X, packed, bias, ydt=ydt, n_threads=n_threads)
+    return epilogue(Yd, act, residual, ydt)
+
+
+def linear_dvals(X, dY, packed, gdt=F32, n_threads=1):
+    """Gradient with respect to the kept weights, in the layout of the value panels: (D rounded, D double)."""
+    X, dY = _f32(X), _f32(dY)
+    T, N = X.shape
+    M, R = packed["M"], packed["R"]
+    assert dY.shape == (T, M) and N == packed["N"]
+    n = R * int(packed["blk_ptr"][-1])
+    D = np.empty(n, dtype=np.float32)
+    Dd = np.empty(n, dtype=np.float64)
+    lib().orc_linear_dvals(_p(X), _p(dY), C.c_int64(T), C.c_int64(M), C.c_int64(N), C.c_int32(R),
+                           _p(packed["blk_cnt"]), _p(packed["blk_ptr"]), _p(packed["col_idx"]), C.c_int32(gdt),
+                           _p(D), _p(Dd), C.c_int32(n_threads))
+    return D, Dd
+
+
+def tile_sumsq(s, Ct):
+    """Sums of squares of the R x Ct tiles from the column-group sums s [B, N] (fp32, columns ascending)."""
+    s = _f32(s)
+    B, N = s.shape
+    assert N % Ct == 0
+    ts = np.empty((B, N // Ct), dtype=np.float32)
+    lib().orc_tile_sumsq(_p(s), C.c_int64(B), C.c_int64(N), C.c_int32(Ct), _p(ts))
+    return ts
+
+
+def expand_tile_mask(tkeep, Ct):
+    tkeep = np.ascontiguousarray(tkeep, dtype=np.uint8)
+    B, NT = tkeep.shape
+    keep = np.empty((B, NT * Ct), dtype=np.uint8)
+    lib().orc_expand_tile_mask(_p(tkeep), C.c_int64(B), C.c_int64(NT * Ct), C.c_int32(Ct), _p(keep))
+    return keep
+
+
+def rowseg_sumsq(W, Cs):
+    """Sums of squares of the row segments of Cs columns (the other division of Alg. 1), fp32 canonical chain."""
+    W = _f32(W)
+    M, N = W.shape
+    assert N % Cs == 0
+    s = np.empty((M, N // Cs), dtype=np.float32)
+    lib().orc_rowseg_sumsq(_p(W), C.c_int64(M), C.c_int64(N), C.c_int32(Cs), _p(s))
+    return s

@@ -490,6 +490,7 @@ __device__ __forceinline__ void clear_quad(f32x4 (&acc)[NACC][NFRAG][NSUB]) {
 // row = 16 i + lane / 4, so row / 4 % 4 is the lane's G.)
 // kOutElements: any other R (or an output that cannot be written in 16-byte pieces), outputs stored one by one,
 // and kOutElements8 the same for R == 8, whose plan deals the row-blocks in runs of 4.
+constexpr int kLeanGroup = 3;                // steps per operand group of the 16-wavefront kernels
 constexpr uint32_t kXTileBytes = 4 * 32768;  // 64 tokens x 1024 columns
 constexpr uint32_t kOutStageBytes = 4096;    // per wavefront: 64 token rows x 64 bytes
 enum { kOutElements = 0, kOutStaged8 = 2, kOutElements8 = 3, kOutSwap = 4 };
@@ -511,7 +512,12 @@ __global__ __launch_bounds__(WAVES * 64) void linear_tiled_planned_kernel(
     // set -- four wavefronts per SIMD cover for each other (measured as fast as a 4-step ring with two sets), and
     // the kernel then needs under 96 registers, which leaves a quarter of the register file to other kernels.
     constexpr bool LEAN = WAVES == kPlanWavesWide;
-    constexpr int RING = LEAN ? 2 : kPlanRing / NFRAG;
+    // 16 wavefronts: the operands travel in two groups of kLeanGroup steps.  A group is requested as a whole, right
+    // after the wavefront has made sure that the other group has arrived, and used one group of products later: the
+    // only wait for operands is then one with nothing else in flight, the form the compiler's conservative wait
+    // insertion (a wait for all loads at every loop head) costs nothing in.  With a slot refilled right behind its
+    // products, as before, every step waited for the loads of the step before it: one L2 round trip per step.
+    constexpr int RING = LEAN ? 2 * kLeanGroup : kPlanRing / NFRAG;
     static_assert(RING % 2 == 0, "the X fragment ping-pong needs an even ring");
     const int tile = blockIdx.x % ntiles, strip = blockIdx.x / ntiles;
     const int64_t t0 = (int64_t)tile * (16 * NSUB);
@@ -746,7 +752,7 @@ __global__ __launch_bounds__(WAVES * 64) void linear_tiled_planned_kernel(
         const uint32_t *wp = wfrag + (int64_t)gs * (NFRAG * 256) + lane;
         const uint32_t *xp = xoff + (int64_t)gs * 16 + (lane >> 2);
 #pragma unroll
-        for (int j = 0; j < RING; ++j) {
+        for (int j = 0; j < (LEAN ? kLeanGroup : RING); ++j) {
 #pragma unroll
             for (int f = 0; f < NFRAG; ++f) ra[j][f] = load_frag(wp + (j * NFRAG + f) * 256);
             rx[j] = xp[j * 16];
@@ -787,8 +793,54 @@ __global__ __launch_bounds__(WAVES * 64) void linear_tiled_planned_kernel(
         };
         pass_boundaries();
         if (gs >= gs_hi) continue;  // then e == eb: every block of the segment has been written
-        if constexpr (!LEAN) issue_reads(rx[0], xb[0]);
         bool done = false;
+        if constexpr (LEAN) {
+            while (!done) {
+                static_for<0, 2>([&](auto hc) __attribute__((always_inline)) {
+                    constexpr int h = decltype(hc)::value;
+                    if (done) return;  // uniform
+                    // this group must have arrived before the other one is requested again
+#pragma unroll
+                    for (int j = 0; j < kLeanGroup; ++j) {
+#pragma unroll
+                        for (int f = 0; f < NFRAG; ++f)
+                            asm volatile("" ::"v"(ra[h * kLeanGroup + j][f].x), "v"(ra[h * kLeanGroup + j][f].y),
+                                         "v"(ra[h * kLeanGroup + j][f].z), "v"(ra[h * kLeanGroup + j][f].w));
+                        asm volatile("" ::"v"(rx[h * kLeanGroup + j]));
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int j = 0; j < kLeanGroup; ++j) {
+#pragma unroll
+                        for (int f = 0; f < NFRAG; ++f)
+                            ra[(1 - h) * kLeanGroup + j][f] = load_frag(wp + ((kLeanGroup + j) * NFRAG + f) * 256);
+                        rx[(1 - h) * kLeanGroup + j] = xp[(kLeanGroup + j) * 16];
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int j = 0; j < kLeanGroup; ++j) {
+                        if (done) break;  // uniform
+                        issue_reads(rx[h * kLeanGroup + j], xb[0]);
+                        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                        for (int u = 0; u < NSUB; ++u)
+#pragma unroll
+                            for (int f = 0; f < NFRAG; ++f)
+                                acc[f][u] = mfma16<DT>(ra[h * kLeanGroup + j][f], xb[0][u], acc[f][u]);
+                        __builtin_amdgcn_sched_barrier(0);
+                        ++gs;
+                        if (gs >= blk_end) {  // uniform
+                            pass_boundaries();
+                            if (e >= eb) done = true;
+                        }
+                    }
+                    wp += kLeanGroup * NFRAG * 256;
+                    xp += kLeanGroup * 16;
+                });
+            }
+            continue;
+        }
+        if constexpr (!LEAN) issue_reads(rx[0], xb[0]);
         while (!done) {
 #pragma unroll
             for (int j = 0; j < RING; ++j) {
@@ -891,6 +943,44 @@ __global__ __launch_bounds__(WAVES * 64) void linear_tiled_chunked_kernel(
         __syncthreads();
         if (!work) continue;  // no barrier below this line inside the chunk
 
+        if constexpr (LEAN) {
+            // The loop over the wavefront's row-blocks is unrolled, so that each block's products go to its own
+            // accumulator registers by name (chosen at run time, the sets are merged after every step: 16 register
+            // moves per step, on hardware whose vector ALU does not run beside the matrix cores).  The operand ring
+            // runs on across the block ends: `par` is the ring slot of the next step.
+            int par = 0;
+            static_for<0, NACC>([&](auto kc) __attribute__((always_inline)) {
+                constexpr int k = decltype(kc)::value;
+                const int end_k = min(ends[k], gs_hi);
+                auto step = [&](auto jc) __attribute__((always_inline)) {
+                    constexpr int j = decltype(jc)::value;
+                    issue_reads(rx[j], xb[0]);
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int u = 0; u < NSUB; ++u)
+#pragma unroll
+                        for (int f = 0; f < NFRAG; ++f) acc[k][f][u] = mfma16<DT>(ra[j][f], xb[0][u], acc[k][f][u]);
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int f = 0; f < NFRAG; ++f) ra[j][f] = load_frag(wp + ((RING + j) * NFRAG + f) * 256);
+                    rx[j] = xp[(RING + j) * 16];
+                    ++gs;
+                };
+                for (;;) {
+                    if (par == 0) {
+                        if (gs >= end_k) break;
+                        step(std::integral_constant<int, 0>{});
+                        par = 1;
+                    }
+                    if (gs >= end_k) break;
+                    step(std::integral_constant<int, 1>{});
+                    par = 0;
+                    wp += RING * NFRAG * 256;
+                    xp += RING * 16;
+                }
+            });
+            continue;
+        }
         int cur = 0;
         auto end_of = [&](int k) {
             int v = ends[0];

@@ -1,6 +1,8 @@
 // Device helpers shared by the matrix-core kernels of the layer: operand types, the 16x16x32 matrix
 // instruction, the transposing LDS read and the packed conversion to 16-bit floats.
 #pragma once
+#include <type_traits>
+
 #include "bsp_common.h"
 
 namespace bsp {
@@ -48,6 +50,16 @@ __device__ __forceinline__ uint32_t cvt_pk(float a, float b) {
 }
 
 extern __shared__ __attribute__((aligned(16))) uint8_t smem_x[];
+
+// f(integral_constant<int, I>) for I = B .. E - 1: a loop whose index is a constant inside the body, so that
+// register arrays indexed by it stay in registers.
+template <int B, int E, typename F>
+__device__ __forceinline__ void static_for(F &&f) {
+    if constexpr (B < E) {
+        f(std::integral_constant<int, B>{});
+        static_for<B + 1, E>(f);
+    }
+}
 
 }  // namespace
 }  // namespace bsp

@@ -657,3 +657,139 @@ def test_adam_step_mask_and_regulariser():
     Wq, _, _ = orc.adam_step(W0, z, z, z, R, alpha=alpha, lam=lam, mode=orc.ALPHA_SQNORM, lr=1e-4, t=1)
     nz = W0 != 0
     assert np.all(np.abs(Wq[nz]) < np.abs(W0[nz])) and np.all(Wq[~nz] == 0)
+
+
+# --------------------------------------------------------------------------- epilogue of a layer
+def test_epilogue_gelu_is_the_exact_erf_form():
+    y = np.concatenate([rand(2000, 2.0), np.linspace(-8, 8, 401).astype(np.float32)]).astype(np.float64)
+    got = orc.epilogue(y, orc.ACT_GELU)[1]
+    want = np.array([0.5 * v * (1.0 + math.erf(v / math.sqrt(2.0))) for v in y])   # the interpreter's own erf
+    assert np.allclose(got, want, rtol=1e-14, atol=1e-300)
+    # closed forms: gelu(0) = 0; gelu(1) = Phi(1), the textbook value of the normal distribution function;
+    # gelu(x) - gelu(-x) = x (Phi(x) + Phi(-x) = 1); far out it is the identity / zero
+    assert orc.epilogue(np.array([0.0]), orc.ACT_GELU)[1][0] == 0.0
+    assert abs(orc.epilogue(np.array([1.0]), orc.ACT_GELU)[1][0] - 0.8413447460685429) < 1e-15
+    pos, neg = orc.epilogue(np.abs(y), orc.ACT_GELU)[1], orc.epilogue(-np.abs(y), orc.ACT_GELU)[1]
+    assert np.allclose(pos - neg, np.abs(y), rtol=1e-14, atol=1e-15)
+    far = orc.epilogue(np.array([40.0, -40.0]), orc.ACT_GELU)[1]
+    assert far[0] == 40.0 and far[1] == 0.0
+    # not the tanh approximation: the two differ by about 1e-4 at x = 2
+    tanh_form = 0.5 * 2.0 * (1.0 + math.tanh(math.sqrt(2.0 / math.pi) * (2.0 + 0.044715 * 8.0)))
+    assert abs(orc.epilogue(np.array([2.0]), orc.ACT_GELU)[1][0] - tanh_form) > 5e-5
+
+
+def test_epilogue_order_residual_and_single_rounding():
+    y, res = rand((7, 9), 1.5).astype(np.float64), wl.to_dtype_values(rand((7, 9)), "bf16")
+    plain = orc.epilogue(y)[1]
+    assert np.array_equal(plain, y)                                               # nothing asked: the sums themselves
+    assert np.array_equal(orc.epilogue(y, residual=res)[1], y + res.astype(np.float64))
+    both = orc.epilogue(y, orc.ACT_GELU, res)[1]
+    assert np.array_equal(both, orc.epilogue(y, orc.ACT_GELU)[1] + res.astype(np.float64))   # activation, then residual
+    assert not np.allclose(both, orc.epilogue(y + res, orc.ACT_GELU)[1])
+    # one rounding, after the addition: 1 + 2^-8 is a tie in bf16 (-> 1), the residual 2^-20 lifts it above the tie
+    one = np.array([1.0 + 2.0 ** -8]); r = np.array([2.0 ** -20], dtype=np.float32)
+    assert orc.epilogue(one, residual=r, ydt=orc.BF16)[0][0] == np.float32(1.0 + 2.0 ** -7)
+    assert orc.round_to(one, orc.BF16)[0] + r[0] != np.float32(1.0 + 2.0 ** -7)
+    # rounded output == the layer's own rounding when nothing is asked
+    d = wl.layer(5, 6, 8, 12, "bf16")
+    keep = wl.bernoulli_keep_mask(6, 2, 12, 0.5)
+    p = orc.pack(d["W"], 4, keep, 1, orc.BF16)
+    Y, Yd = orc.linear_packed(d["X"], p, d["bias"], ydt=orc.BF16)
+    assert np.array_equal(orc.linear_packed_fused(d["X"], p, d["bias"], ydt=orc.BF16)[0], Y)
+
+
+# --------------------------------------------------------------------------- gradient of the kept weights
+def test_dvals_exact_rational_brute_force_and_pads():
+    from fractions import Fraction
+    T, M, N, R = 5, 6, 7, 3
+    X, dY, W = rand((T, N)), rand((T, M)), rand((M, N))
+    keep = wl.bernoulli_keep_mask(3, M // R, N, 0.6)
+    keep[1, :] = 0
+    keep[1, 2] = 1
+    for k_align in (1, 8):
+        p = orc.pack(W, R, keep, k_align, orc.F32)
+        D, Dd = orc.linear_dvals(X, dY, p)
+        for b in range(M // R):
+            base, kp, kb = int(p["blk_ptr"][b]), int(p["blk_ptr"][b + 1] - p["blk_ptr"][b]), int(p["blk_cnt"][b])
+            for r in range(R):
+                for c in range(kp):
+                    at = R * base + r * kp + c
+                    if c >= kb:
+                        assert D[at] == 0.0 and not np.signbit(D[at]) and Dd[at] == 0.0   # a pad: exactly +0
+                        continue
+                    j = int(p["col_idx"][base + c])
+                    want = sum(Fraction(float(dY[t, b * R + r])) * Fraction(float(X[t, j])) for t in range(T))
+                    assert abs(Fraction(float(Dd[at])) - want) <= abs(want) * Fraction(1, 10 ** 14)
+                    assert D[at] == np.float32(float(want))
+
+
+def test_dvals_is_the_gradient_of_the_layer():
+    T, M, N, R = 9, 8, 11, 4
+    X, dY, W = rand((T, N)), rand((T, M)), rand((M, N))
+    keep = wl.bernoulli_keep_mask(4, M // R, N, 0.5)
+    p = orc.pack(W, R, keep, 8, orc.F32)
+    D, Dd = orc.linear_dvals(X, dY, p)
+    # torch's autograd on the dense masked product, gathered at the kept positions
+    Wt = torch.tensor(W.astype(np.float64), requires_grad=True)
+    mask = torch.tensor(np.repeat(keep, R, axis=0).astype(np.float64))
+    (torch.tensor(dY.astype(np.float64)) * (torch.tensor(X.astype(np.float64)) @ (Wt * mask).T)).sum().backward()
+    G = Wt.grad.numpy()
+    ref = orc.pack(G.astype(np.float32), R, keep, 8, orc.F32)
+    assert np.allclose(Dd, ref["vals"].astype(np.float64), rtol=1e-6, atol=1e-6)
+    # adjointness: <dY, layer(X; V)> = <V, dvals> for any panel values V on the same pattern, pads included (they are 0)
+    V = rand(ref["vals"].shape)
+    for b in range(M // R):                                           # pads of V must be 0 for the layer to ignore them
+        base, kp, kb = int(p["blk_ptr"][b]), int(p["blk_ptr"][b + 1] - p["blk_ptr"][b]), int(p["blk_cnt"][b])
+        for r in range(R):
+            V[R * base + r * kp + kb: R * base + (r + 1) * kp] = 0.0
+    q = dict(p); q["vals"] = V
+    _, Yd = orc.linear_packed(X, q, None)
+    assert abs((dY.astype(np.float64) * Yd).sum() - (V.astype(np.float64) * Dd).sum()) < 1e-9
+    # keep all: the dense product dY^T X, row-block by row-block
+    pa = orc.pack(W, R, np.ones_like(keep), 1, orc.F32)
+    Da = orc.linear_dvals(X, dY, pa)[1].reshape(M, N)
+    assert np.allclose(Da, dY.astype(np.float64).T @ X.astype(np.float64), rtol=1e-13, atol=1e-13)
+    # rounding to a 16-bit type is one rounding of the double sum
+    Db, Dbd = orc.linear_dvals(X, dY, p, gdt=orc.BF16)
+    assert np.array_equal(Db.astype(np.float64), orc.round_to(Dbd, orc.BF16))
+
+
+# --------------------------------------------------------------------------- whole-block pruning (Table 4's comparison)
+def test_tile_sumsq_and_whole_block_mask():
+    B, N, R = 5, 24, 4
+    W = rand((B * R, N), 0.02)
+    s = orc.sumsq(W, R)
+    assert np.array_equal(orc.tile_sumsq(s, 1), s)                                   # tiles of one column: the groups
+    for Ct in (2, 4, 8, 24):
+        ts = orc.tile_sumsq(s, Ct)
+        # replay of the stated order in numpy fp32, and the plain definition in fp64
+        want = np.zeros((B, N // Ct), dtype=np.float32)
+        for c in range(Ct):
+            want = (want + s[:, c::Ct]).astype(np.float32)
+        assert np.array_equal(ts, want)
+        tiles = (W.astype(np.float64) ** 2).reshape(B, R, N // Ct, Ct).sum(axis=(1, 3))
+        assert np.allclose(ts, tiles, rtol=1e-5)
+        tk, _ = orc.mask_rank(ts, ts.size // 2, orc.SCOPE_MATRIX)
+        keep = orc.expand_tile_mask(tk, Ct)
+        assert keep.shape == (B, N) and keep.sum() == Ct * tk.sum()
+        assert np.array_equal(keep.reshape(B, N // Ct, Ct).min(axis=2), keep.reshape(B, N // Ct, Ct).max(axis=2))
+        assert np.array_equal(keep[:, ::Ct], tk)
+    # one tile per row-block: whole row-blocks go (the coarsest structure); kept tiles beat pruned ones
+    ts = orc.tile_sumsq(s, N)
+    tk, _ = orc.mask_rank(ts, 2, orc.SCOPE_MATRIX)
+    assert tk.sum() == 2 and ts[tk == 1].min() > ts[tk == 0].max()
+    ones = np.ones((2 * R, 8), np.float32)
+    assert np.array_equal(orc.tile_sumsq(orc.sumsq(ones, R), 4), np.full((2, 2), 4.0 * R, np.float32))
+
+
+# --------------------------------------------------------------------------- the other division: row segments
+def test_rowseg_sumsq_is_the_column_group_sum_of_the_transposed_matrix():
+    for (M, N, Cs) in ((6, 12, 3), (16, 64, 16), (5, 40, 8), (3, 7, 7), (4, 9, 1)):
+        W = rand((M, N), 0.5)
+        got = orc.rowseg_sumsq(W, Cs)
+        # the same chain of fused multiply-adds, read along rows: bit for bit the pinned column-group sums of W^T
+        assert np.array_equal(got, orc.sumsq(np.ascontiguousarray(W.T), Cs).T)
+        assert np.allclose(got, (W.astype(np.float64) ** 2).reshape(M, N // Cs, Cs).sum(axis=2), rtol=1e-6)
+    assert np.array_equal(orc.rowseg_sumsq(np.ones((2, 8), np.float32), 4), np.full((2, 2), 4.0, np.float32))
+    one_hot = np.zeros((1, 8), np.float32); one_hot[0, 5] = -3.0
+    assert np.array_equal(orc.rowseg_sumsq(one_hot, 4), np.array([[0.0, 9.0]], np.float32))
