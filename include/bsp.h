@@ -121,6 +121,32 @@ int bsp_group_norms_grad(const void *W, int wdt, int64_t M, int64_t N, int32_t R
  * groups keep their bits.  W: [M, N] row-major of dtype wdt; keep: [M / R, N] uint8. */
 int bsp_mask_weights(void *W, int wdt, int64_t M, int64_t N, int32_t R, const uint8_t *keep, void *stream);
 
+/* ---- whole-block pruning (the "block sparse" comparison of Sec. 4.4 / Table 4: a block is kept
+ * or removed as a whole) ----------------------------------------------------------------------
+ * A tile is the R rows of a row-block times C consecutive columns (N % C == 0).  bsp_tile_sumsq
+ * adds the C column-group sums of every tile in fp32, columns ascending, starting from +0:
+ * sumsq [B, N] (as written by bsp_group_norms) -> tile_sumsq [B, N / C].  The decision is then
+ * bsp_prune_mask on tile_sumsq (threshold or percentile, any scope), and bsp_expand_tile_mask
+ * spreads it over the columns: keep[b, j] = tile_keep[b, j / C] != 0, the mask bsp_pack and the
+ * layer take.  C = 1 is the column-granular method itself. */
+int bsp_tile_sumsq(const float *sumsq, int64_t B, int64_t N, int32_t C, float *tile_sumsq, void *stream);
+int bsp_expand_tile_mask(const uint8_t *tile_keep, int64_t B, int64_t N, int32_t C, uint8_t *keep, void *stream);
+
+/* ---- the other division (Sec. 3.2, Eq. 2; Alg. 1 as printed: column blocks of C columns, a group
+ * is a row of a block) on the matrix as it is stored ---------------------------------------------
+ * bsp_rowseg_norms: for every row segment sumsq[m, q] = sum_c W[m, qC + c]^2 in fp32, one fused
+ * multiply-add per element, columns ascending (bit for bit what bsp_group_norms gives for the
+ * transposed matrix with R = C); norm and alpha as in bsp_group_norms.  Outputs [M, N / C] fp32,
+ * each may be NULL.  1 <= C <= 64, N % C == 0.  The decision is bsp_prune_mask on sumsq
+ * (B = M, N = N / C).  bsp_mask_weights_rowseg zeroes the pruned segments in place
+ * (keep_seg [M, N / C], 1 = kept); applied together with bsp_mask_weights it leaves the matrix
+ * pruned by both divisions at once (Sec. 3.1: "row pruning and column pruning on each block"),
+ * which bsp_pack then stores by its kept column groups. */
+int bsp_rowseg_norms(const void *W, int wdt, int64_t M, int64_t N, int32_t C, float eps, int mode, float *sumsq,
+                     float *norm, float *alpha, void *stream);
+int bsp_mask_weights_rowseg(void *W, int wdt, int64_t M, int64_t N, int32_t C, const uint8_t *keep_seg,
+                            void *stream);
+
 /* ---- one weight update (Alg. 2: "update W ... using Adam"; in the retraining loop followed
  * by W = W * Mask) ---------------------------------------------------------------------
  * Adam as published (Kingma & Ba, Algorithm 1) on fp32 master weights W [M,N] with fp32

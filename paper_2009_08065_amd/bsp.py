@@ -59,6 +59,10 @@ def lib():
     L.bsp_prune_mask_workspace_bytes.argtypes = [i64, i64, C.c_int]
     L.bsp_prune_mask_workspace_bytes.restype = sz
     L.bsp_mask_weights.argtypes = [vp, C.c_int, i64, i64, i32, vp, vp]
+    L.bsp_tile_sumsq.argtypes = [vp, i64, i64, i32, vp, vp]
+    L.bsp_expand_tile_mask.argtypes = [vp, i64, i64, i32, vp, vp]
+    L.bsp_rowseg_norms.argtypes = [vp, C.c_int, i64, i64, i32, f32, C.c_int, vp, vp, vp, vp]
+    L.bsp_mask_weights_rowseg.argtypes = [vp, C.c_int, i64, i64, i32, vp, vp]
     L.bsp_adam_step.argtypes = [vp, vp, C.c_int, vp, vp, i64, i64, i32, vp, f32, C.c_int, vp, f32, f32, f32, f32, i64, vp]
     L.bsp_group_norms_grad.argtypes = [vp, C.c_int, i64, i64, i32, f32, C.c_int, f32, C.c_int, vp, vp, vp, vp, vp]
     L.bsp_pack_count.argtypes = [vp, i64, i64, i32, vp, vp, vp]
@@ -218,6 +222,41 @@ def bsp_mask_weights(W, R, keep):
     M, N = W.shape
     st = lib().bsp_mask_weights(_ptr(W), _DT[W.dtype], M, N, R, _ptr(keep, torch.uint8), _stream())
     _check(st, "bsp_mask_weights")
+    return W
+
+
+def bsp_tile_sumsq(sumsq, Ct, out=None):
+    """Sums of squares of the R x Ct tiles from the column-group sums [B, N] (whole-block pruning)."""
+    B, N = sumsq.shape
+    if out is None:
+        out = torch.empty((B, N // Ct), dtype=torch.float32, device=sumsq.device)
+    _check(lib().bsp_tile_sumsq(_ptr(sumsq, torch.float32), B, N, Ct, _ptr(out, torch.float32), _stream()), "bsp_tile_sumsq")
+    return out
+
+
+def bsp_expand_tile_mask(tile_keep, Ct, out=None):
+    B, NT = tile_keep.shape
+    if out is None:
+        out = torch.empty((B, NT * Ct), dtype=torch.uint8, device=tile_keep.device)
+    _check(lib().bsp_expand_tile_mask(_ptr(tile_keep, torch.uint8), B, NT * Ct, Ct, _ptr(out, torch.uint8), _stream()),
+           "bsp_expand_tile_mask")
+    return out
+
+
+def bsp_rowseg_norms(W, Cs, eps=1e-6, mode=ALPHA_SQNORM):
+    """Returns (sumsq, norm, alpha), each [M, N / Cs] fp32: the groups are row segments of Cs columns."""
+    M, N = W.shape
+    outs = [torch.empty((M, N // Cs), dtype=torch.float32, device=W.device) for _ in range(3)]
+    _check(lib().bsp_rowseg_norms(_ptr(W), _DT[W.dtype], M, N, Cs, eps, mode, _ptr(outs[0]), _ptr(outs[1]), _ptr(outs[2]),
+                                  _stream()), "bsp_rowseg_norms")
+    return tuple(outs)
+
+
+def bsp_mask_weights_rowseg(W, Cs, keep_seg):
+    """In place: zero every pruned row segment of W.  Returns W."""
+    M, N = W.shape
+    _check(lib().bsp_mask_weights_rowseg(_ptr(W), _DT[W.dtype], M, N, Cs, _ptr(keep_seg, torch.uint8), _stream()),
+           "bsp_mask_weights_rowseg")
     return W
 
 

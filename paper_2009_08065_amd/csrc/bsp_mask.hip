@@ -380,6 +380,34 @@ __global__ __launch_bounds__(kThreads) void mask_weights_kernel(void *__restrict
     if (keep[(m / R) * N + j] == 0) ((E *)W)[m * N + j] = E(0);
 }
 
+// ------------------------------------------------------------------ whole-block pruning and the other division
+// Sum of squares of the R x C tiles from the column-group sums: fp32, columns ascending, starting from +0.
+__global__ __launch_bounds__(kThreads) void tile_sumsq_kernel(const float *__restrict__ s, int64_t tiles, int32_t C,
+                                                              float *__restrict__ ts) {
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= tiles) return;
+    const float *p = s + i * C;  // the tiles of a row of the group array lie end to end (N % C == 0)
+    float acc = 0.0f;
+    for (int c = 0; c < C; ++c) acc = acc + p[c];
+    ts[i] = acc;
+}
+
+// keep[b, j] = tkeep[b, j / C] != 0
+__global__ __launch_bounds__(kThreads) void expand_tile_mask_kernel(const uint8_t *__restrict__ tkeep, int64_t n,
+                                                                    int32_t C, uint8_t *__restrict__ keep) {
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i < n) keep[i] = tkeep[i / C] != 0;  // (flat index / C = flat tile index, since N % C == 0)
+}
+
+// W[m, j] = +0 where keep_seg[m, j / C] == 0 (row segments of C columns)
+template <int DT>
+__global__ __launch_bounds__(kThreads) void mask_weights_rowseg_kernel(void *__restrict__ W, int64_t n, int32_t C,
+                                                                       const uint8_t *__restrict__ keep_seg) {
+    using E = typename elem<DT>::type;
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i < n && keep_seg[i / C] == 0) ((E *)W)[i] = E(0);
+}
+
 // Workgroups of the histogram launches: about 16384 elements each (measured best on 0.25 M groups: fewer slots to
 // sum at the start of the next launch weigh more than the shorter read), at most kMaxSlots.
 inline int select_slots(int64_t n) {
@@ -510,6 +538,39 @@ extern "C" int bsp_mask_weights(void *W, int wdt, int64_t M, int64_t N, int32_t 
         else
             mask_weights_kernel<DT><<<dim3((unsigned)((N + kThreads - 1) / kThreads), gy, gz), kThreads, 0, s>>>(W, M, N,
                                                                                                               R, keep);
+    });
+    return check_launch();
+}
+
+extern "C" int bsp_tile_sumsq(const float *sumsq, int64_t B, int64_t N, int32_t C, float *tile_sumsq, void *stream) {
+    if (!sumsq || !tile_sumsq) return BSP_ERR_NULL;
+    if (B <= 0 || N <= 0 || C < 1 || C > N || N % C != 0 || B * N >= ((int64_t)1 << 31)) return BSP_ERR_SHAPE;
+    const int64_t tiles = B * (N / C);
+    tile_sumsq_kernel<<<(unsigned)((tiles + kThreads - 1) / kThreads), kThreads, 0, (hipStream_t)stream>>>(sumsq, tiles, C,
+                                                                                                     tile_sumsq);
+    return check_launch();
+}
+
+extern "C" int bsp_expand_tile_mask(const uint8_t *tile_keep, int64_t B, int64_t N, int32_t C, uint8_t *keep,
+                                    void *stream) {
+    if (!tile_keep || !keep) return BSP_ERR_NULL;
+    if (B <= 0 || N <= 0 || C < 1 || C > N || N % C != 0 || B * N >= ((int64_t)1 << 31)) return BSP_ERR_SHAPE;
+    const int64_t n = B * N;
+    expand_tile_mask_kernel<<<(unsigned)((n + kThreads - 1) / kThreads), kThreads, 0, (hipStream_t)stream>>>(tile_keep, n, C,
+                                                                                                       keep);
+    return check_launch();
+}
+
+extern "C" int bsp_mask_weights_rowseg(void *W, int wdt, int64_t M, int64_t N, int32_t C, const uint8_t *keep_seg,
+                                       void *stream) {
+    if (!W || !keep_seg) return BSP_ERR_NULL;
+    if (!valid_dtype(wdt)) return BSP_ERR_DTYPE;
+    if (M <= 0 || N <= 0 || C < 1 || C > N || N % C != 0 || M * N >= ((int64_t)1 << 40)) return BSP_ERR_SHAPE;
+    const int64_t n = M * N;
+    const int64_t grid = (n + kThreads - 1) / kThreads;
+    if (grid >= ((int64_t)1 << 31)) return BSP_ERR_SHAPE;
+    BSP_DISPATCH_DTYPE(wdt, DT, {
+        mask_weights_rowseg_kernel<DT><<<(unsigned)grid, kThreads, 0, (hipStream_t)stream>>>(W, n, C, keep_seg);
     });
     return check_launch();
 }

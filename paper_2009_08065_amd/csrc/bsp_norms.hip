@@ -171,6 +171,38 @@ __global__ __launch_bounds__(kThreads) void group_norms_kernel(const void *__res
     }
 }
 
+// Group sums of the other division (Eq. 2; Alg. 1 as printed): a group is a row segment of C columns.  In the
+// flat row-major array the groups are consecutive runs of C elements, so a workgroup takes 256 groups = 256 C
+// contiguous elements, copies them with coalesced loads into LDS (one group per padded row: the stride C + 1 keeps
+// the lanes on different banks) and every lane then walks its own group with one fused multiply-add per element,
+// columns ascending: the same chain as the column groups', and bit for bit what group_norms gives on the
+// transposed matrix.  (A cross-lane shuffle tree would be shorter, but it adds in another order.)
+template <int DT>
+__global__ __launch_bounds__(kThreads) void rowseg_norms_kernel(const void *__restrict__ W, int64_t groups, int32_t C,
+                                                                float eps, int mode, float *__restrict__ sumsq,
+                                                                float *__restrict__ norm, float *__restrict__ alpha) {
+    extern __shared__ float seg[];  // [kThreads][C + 1]
+    const int64_t g0 = (int64_t)blockIdx.x * kThreads;
+    const int ng = (int)((groups - g0) < kThreads ? (groups - g0) : kThreads);
+    const int n = ng * C;
+    for (int e = threadIdx.x; e < n; e += kThreads) {
+        const int i = e / C, c = e - i * C;
+        seg[i * (C + 1) + c] = elem<DT>::load(W, g0 * C + e);
+    }
+    __syncthreads();
+    if ((int)threadIdx.x >= ng) return;
+    float acc = 0.0f;
+    const float *mine = seg + threadIdx.x * (C + 1);
+    for (int c = 0; c < C; ++c) acc = __builtin_fmaf(mine[c], mine[c], acc);
+    const int64_t o = g0 + threadIdx.x;
+    if (sumsq) sumsq[o] = acc;
+    if (norm || alpha) {
+        const float root = __builtin_sqrtf(acc);
+        if (norm) norm[o] = root;
+        if (alpha) alpha[o] = alpha_of(acc, root, eps, mode);
+    }
+}
+
 // Refresh and gradient in one pass over W (Alg. 2 at a milestone: the factors are recomputed and the next
 // step's regulariser gradient uses them).  The same arithmetic as group_norms_kernel followed by the gradient
 // kernels, operation for operation, so the results are bit-identical to the two separate calls; the R = RT
@@ -424,6 +456,34 @@ extern "C" int bsp_group_norms(const void *W, int wdt, int64_t M, int64_t N, int
             group_norms_kernel<DT, V><<<grid_for(N, V, B), kThreads, 0, s>>>(W, N, R, eps, mode, sumsq, norm, alpha);
         else
             group_norms_kernel<DT, 1><<<grid_for(N, 1, B), kThreads, 0, s>>>(W, N, R, eps, mode, sumsq, norm, alpha);
+    });
+    return check_launch();
+}
+
+extern "C" int bsp_rowseg_norms(const void *W, int wdt, int64_t M, int64_t N, int32_t C, float eps, int mode,
+                                float *sumsq, float *norm, float *alpha, void *stream) {
+    if (!W) return BSP_ERR_NULL;
+    if (!valid_dtype(wdt)) return BSP_ERR_DTYPE;
+    if (M <= 0 || N <= 0 || C < 1 || C > 64 || N % C != 0 || M * (N / C) >= ((int64_t)1 << 31)) return BSP_ERR_SHAPE;
+    if (mode != BSP_ALPHA_SQNORM && mode != BSP_ALPHA_NORM) return BSP_ERR_DTYPE;
+    if (!sumsq && !norm && !alpha) return BSP_OK;
+    const int64_t groups = M * (N / C);
+    const unsigned grid = (unsigned)((groups + kThreads - 1) / kThreads);
+    const size_t lds = (size_t)kThreads * (C + 1) * sizeof(float);
+    hipStream_t s = (hipStream_t)stream;
+    BSP_DISPATCH_DTYPE(wdt, DT, {
+        // (C = 64 needs 65 KB of dynamic LDS, above the default limit)
+        auto kern = rowseg_norms_kernel<DT>;
+        static thread_local size_t configured = 0;
+        if (lds > 65536 && lds > configured) {
+            hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) {
+                set_last_hip_error((int)e);
+                return BSP_ERR_HIP;
+            }
+            configured = lds;
+        }
+        kern<<<grid, kThreads, lds, s>>>(W, groups, C, eps, mode, sumsq, norm, alpha);
     });
     return check_launch();
 }
