@@ -29,6 +29,9 @@ struct TiledArgs {
 // True when the tiled kernel can take this layer (16-bit floats, kp_b % 32 == 0, X tile fits in LDS).
 bool tiled_supported(int xdt, int64_t N, int32_t k_align);
 int launch_linear_tiled(const TiledArgs &args, bool plan, hipStream_t s);
+// The planned kernel for R = 16 and layers of up to 1024 input columns (16-bit floats, a plan of 16 streams, Y
+// aligned to 16 bytes); NG = groups of the plan, max_step = steps the plan holds without its read-ahead slack.
+int launch_linear_steploop16(const TiledArgs &args, int64_t NG, int64_t max_step, hipStream_t s);
 // Column chunks of a plan: layers with more than 1024 (padded) input columns are cut into chunks of
 // 1024 columns, the width of X that fits in LDS next to 64 tokens; narrower layers are one chunk.
 constexpr int kPlanMaxChunks = 4;
@@ -63,10 +66,18 @@ inline int plan_waves(int64_t N, int32_t R) {
 int plan_slack_steps();
 
 // Placement of X column c inside a 16-token sub-tile held in LDS, shared by the copy-in of the
-// tiled kernel and by the plan builder: byte offset of token quad p (tokens 4p .. 4p+3).
+// tiled kernels and by the plan builder: byte offset of token quad p (tokens 4p .. 4p+3).
 __host__ __device__ inline uint32_t lds_col_offset(uint32_t c, uint32_t p) {
     const uint32_t row = (c & ~31u) | ((c >> 2) & 7u) | ((c & 3u) << 3);
     return row * 32u + ((p ^ ((c >> 5) & 3u)) << 3);
+}
+// The same for the 64-token tiles (four sub-tiles, up to 1024 columns) of the planned kernels: columns 0 .. 511
+// fill the first 64 KiB of the tile and columns 512 .. 1023 the second, and sub-tile u of either half lies
+// u * kSubStride4 bytes further on -- all four sub-tiles of a column are then within the 64 KiB that the immediate
+// offset of an LDS instruction reaches, so one address register per column serves the whole tile.
+constexpr uint32_t kSubStride4 = 16384u;
+__host__ __device__ inline uint32_t lds_col_offset4(uint32_t c, uint32_t p) {
+    return (c >> 9) * 65536u + lds_col_offset(c & 511u, p);
 }
 // LDS bank group (8 banks of 4 bytes = one 32-byte row) that column c lands in.
 __host__ __device__ inline uint32_t lds_bank_group(uint32_t c) { return (c >> 2) & 7u; }

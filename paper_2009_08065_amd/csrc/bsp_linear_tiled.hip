@@ -28,6 +28,7 @@
 #include "bsp_common.h"
 #include "bsp_linear_internal.h"
 #include "bsp_mfma_device.h"
+#include "bsp_tile_device.h"
 
 namespace bsp {
 namespace {
@@ -38,74 +39,6 @@ constexpr int kPlanRing = 8;           // the same for the planned kernels with 
                                        // step (with 16 wavefronts: 2 steps).  Deeper rings were measured slower (4 to 8
                                        // steps are equal, 16 is 10 % slower): latency is covered, and more requests in
                                        // flight only queue up
-
-// 16 bytes of Y leave as a streaming store: Y is written once, and as ordinary stores its 50 to 70 MB per layer
-// push the operand stream and the tiles of X, which other workgroups are about to read, out of the L2
-// (measured on the BERT-large set at 5x: 8 to 12 % shorter launches).
-__device__ __forceinline__ void store_y16(void *p, uint4 v) {
-    __builtin_nontemporal_store(u32x4{v.x, v.y, v.z, v.w}, reinterpret_cast<u32x4 *>(p));
-}
-
-// Distance in LDS between the 16-token sub-tiles of a workgroup's X tile: a constant, so that
-// sub-tile offsets fold into the immediate field of the LDS instructions.
-template <int NSUB>
-constexpr uint32_t sub_stride() { return NSUB == 4 ? 32768u : 65536u; }
-
-// Copy the workgroup's X tile into LDS, transposed.  Unit of work = 4 columns x 4 tokens per
-// lane (four 8-byte loads, a 4x4 transpose of 16-bit values in registers, four 8-byte LDS
-// stores); all the loads of a batch are issued before the first store so their latencies overlap.
-// The tile holds columns [col0, col0 + width) of X (width a multiple of 4), at LDS columns 0 .. width-1.
-template <int NSUB>
-__device__ __forceinline__ void stage_x_chunk(const uint16_t *__restrict__ X, int64_t T, int64_t N, int32_t col0,
-                                              int32_t width, int64_t t0) {
-    constexpr int kBatch = 4;
-    const int cquads = width >> 2;
-    const int units = cquads * (4 * NSUB);
-    for (int u0 = threadIdx.x; u0 < units; u0 += blockDim.x * kBatch) {
-        uint2 a[kBatch][4];
-#pragma unroll
-        for (int k = 0; k < kBatch; ++k) {
-            const int u = u0 + k * blockDim.x;
-            const int cq = u % cquads, tq = u / cquads;
-            const int c = cq << 2;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int64_t t = t0 + 4 * tq + i;
-                a[k][i] = (u < units && t < T && col0 + c < N)
-                              ? *reinterpret_cast<const uint2 *>(X + t * N + col0 + c)
-                              : make_uint2(0u, 0u);
-            }
-        }
-#pragma unroll
-        for (int k = 0; k < kBatch; ++k) {
-            const int u = u0 + k * blockDim.x;
-            if (u >= units) break;
-            const int cq = u % cquads, tq = u / cquads;
-            const int c = cq << 2;
-            const uint32_t sub = (uint32_t)(tq >> 2), pq = (uint32_t)(tq & 3);
-            uint8_t *dst = smem_x + sub * sub_stride<NSUB>() + lds_col_offset((uint32_t)c, pq);
-            uint2 w;  // columns c+1 .. c+3 lie 8, 16, 24 LDS rows further on
-            w.x = (a[k][0].x & 0xffffu) | (a[k][1].x << 16);
-            w.y = (a[k][2].x & 0xffffu) | (a[k][3].x << 16);
-            *reinterpret_cast<uint2 *>(dst) = w;
-            w.x = (a[k][0].x >> 16) | (a[k][1].x & 0xffff0000u);
-            w.y = (a[k][2].x >> 16) | (a[k][3].x & 0xffff0000u);
-            *reinterpret_cast<uint2 *>(dst + 8 * 32) = w;
-            w.x = (a[k][0].y & 0xffffu) | (a[k][1].y << 16);
-            w.y = (a[k][2].y & 0xffffu) | (a[k][3].y << 16);
-            *reinterpret_cast<uint2 *>(dst + 16 * 32) = w;
-            w.x = (a[k][0].y >> 16) | (a[k][1].y & 0xffff0000u);
-            w.y = (a[k][2].y >> 16) | (a[k][3].y & 0xffff0000u);
-            *reinterpret_cast<uint2 *>(dst + 24 * 32) = w;
-        }
-    }
-}
-
-template <int NSUB>
-__device__ __forceinline__ void stage_x_tile(const uint16_t *__restrict__ X, int64_t T, int64_t N, int32_t npad,
-                                             int64_t t0) {
-    stage_x_chunk<NSUB>(X, T, N, 0, npad, t0);
-}
 
 // This wavefront's share of the strip: a contiguous run [b_lo, b_hi) of row-blocks holding about
 // 1 / nwaves of the strip's padded kept columns (lower bounds on the cached blk_ptr slice).
@@ -289,7 +222,7 @@ __global__ __launch_bounds__(1024) void linear_tiled_canonical_kernel(
             if (gs < gs_hi) {
                 const StepOps<NFRAG> cur = ring[j];
                 if (gs + kRing < gs_hi) fetch(gs + kRing, ring[j]);
-                const uint32_t o1 = lds_col_offset(cur.c1, (uint32_t)p), o2 = lds_col_offset(cur.c2, (uint32_t)p);
+                const uint32_t o1 = tile_col_offset<NSUB>(cur.c1, (uint32_t)p), o2 = tile_col_offset<NSUB>(cur.c2, (uint32_t)p);
                 uint4 xb[NSUB];
 #pragma unroll
                 for (int u = 0; u < NSUB; ++u) {
@@ -491,7 +424,6 @@ __device__ __forceinline__ void clear_quad(f32x4 (&acc)[NACC][NFRAG][NSUB]) {
 // kOutElements: any other R (or an output that cannot be written in 16-byte pieces), outputs stored one by one,
 // and kOutElements8 the same for R == 8, whose plan deals the row-blocks in runs of 4.
 constexpr int kLeanGroup = 3;                // steps per operand group of the 16-wavefront kernels
-constexpr uint32_t kXTileBytes = 4 * 32768;  // 64 tokens x 1024 columns
 constexpr uint32_t kOutStageBytes = 4096;    // per wavefront: 64 token rows x 64 bytes
 enum { kOutElements = 0, kOutStaged8 = 2, kOutElements8 = 3, kOutSwap = 4 };
 constexpr uint32_t kBiasTableBytes = 32768;  // at most: 8192 rows of a strip
@@ -595,7 +527,7 @@ __global__ __launch_bounds__(WAVES * 64) void linear_tiled_planned_kernel(
             dst[u] = make_uint4(lo.x, lo.y, hi.x, hi.y);
         }
     };
-    auto load_frag = [&](const uint32_t *q) { return make_uint4(q[0], q[64], q[128], q[192]); };
+    auto load_frag = [&](const uint32_t *q) { return *reinterpret_cast<const uint4 *>(q); };
     auto block_of = [&](int e) {
         return ((((int64_t)(g0 + (e >> nacc_shift)) * WAVES + wave)) << nacc_shift) + (e & (NACC - 1));
     };
@@ -744,12 +676,10 @@ __global__ __launch_bounds__(WAVES * 64) void linear_tiled_planned_kernel(
         // Per-lane operand pointers, advanced by a constant per RING steps.  The stream is read up
         // to RING steps past the segment's last step: those loads stay inside the plan buffer (its
         // size includes that slack) and their values are never used.
-        // A fragment is stored as 4 planes of 64 dwords (dword k of every lane's 16 bytes together): a
-        // 4-byte-per-lane load moves 256 contiguous bytes, the access width the vector memory
-        // pipeline sustains best on this hardware (about 1.6x the bytes per clock of 16-byte loads).
+        // A fragment is stored lane by lane, 16 bytes each: one load instruction per fragment.
         // The first RING steps are requested before anything else, so that they travel while the X tile and
         // the bias are copied in.
-        const uint32_t *wp = wfrag + (int64_t)gs * (NFRAG * 256) + lane;
+        const uint32_t *wp = wfrag + (int64_t)gs * (NFRAG * 256) + lane * 4;
         const uint32_t *xp = xoff + (int64_t)gs * 16 + (lane >> 2);
 #pragma unroll
         for (int j = 0; j < (LEAN ? kLeanGroup : RING); ++j) {
@@ -914,7 +844,7 @@ __global__ __launch_bounds__(WAVES * 64) void linear_tiled_chunked_kernel(
             dst[u] = make_uint4(lo.x, lo.y, hi.x, hi.y);
         }
     };
-    auto load_frag = [&](const uint32_t *q) { return make_uint4(q[0], q[64], q[128], q[192]); };
+    auto load_frag = [&](const uint32_t *q) { return *reinterpret_cast<const uint4 *>(q); };
 
     for (int q = 0; q < nchunks; ++q) {
         // the wavefront's step range of this chunk and where each of its row-blocks ends
@@ -928,7 +858,7 @@ __global__ __launch_bounds__(WAVES * 64) void linear_tiled_chunked_kernel(
         gs = max(gs, 0);
         gs_hi = min(gs_hi, max_step);
         const bool work = gs < gs_hi;
-        const uint32_t *wp = wfrag + (int64_t)gs * (NFRAG * 256) + lane;
+        const uint32_t *wp = wfrag + (int64_t)gs * (NFRAG * 256) + lane * 4;
         const uint32_t *xp = xoff + (int64_t)gs * 16 + (lane >> 2);
         if (work) {  // operands of the first RING steps travel while the chunk of X is copied in
 #pragma unroll
@@ -1033,21 +963,9 @@ __global__ __launch_bounds__(WAVES * 64) void linear_tiled_chunked_kernel(
     }
 }
 
-template <typename K>
-int raise_lds_limit(K kern, size_t lds, size_t &configured) {
-    if (lds <= configured) return BSP_OK;
-    hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) {
-        set_last_hip_error((int)e);
-        return BSP_ERR_HIP;
-    }
-    configured = lds;
-    return BSP_OK;
-}
-
 template <int DT, int NFRAG, int NSUB>
 int launch_canonical(const TiledArgs &a, int waves, hipStream_t s) {
-    const size_t lds = (size_t)(NSUB - 1) * sub_stride<NSUB>() + (size_t)a.npad * 32;
+    const size_t lds = tile_bytes<NSUB>(a.npad);
     static thread_local size_t configured = 0;  // per instantiation and thread
     const int64_t ntiles = (a.T + 16 * NSUB - 1) / (16 * NSUB);
     int64_t nstrips = (256 + ntiles - 1) / ntiles;  // enough strips to give every compute unit a workgroup
@@ -1073,7 +991,7 @@ int launch_planned_1024(const TiledArgs &a, int64_t ntiles, int64_t NG, int64_t 
 template <int DT, int NFRAG>
 int launch_planned(const TiledArgs &a, hipStream_t s) {
     const int NACC = plan_nacc(NFRAG, a.npad > 1024, a.R);
-    const size_t lds = 4 * (size_t)sub_stride<4>();  // 64 tokens x 1024 columns
+    const size_t lds = kXTileBytes;  // 64 tokens x 1024 columns
     const int64_t ntiles = (a.T + 63) / 64;
     const int waves = plan_waves(a.N, a.R);  // as the plan was built
     const int64_t NG = (a.B + waves * NACC - 1) / (waves * NACC);
@@ -1113,6 +1031,8 @@ int launch_planned(const TiledArgs &a, hipStream_t s) {
     if (a.R == 16 * NFRAG && (reinterpret_cast<uintptr_t>(a.Y) & 15) == 0) {
         // R = 16 and 32: 16 wavefronts (the plan has 16 streams); R = 64: 8
         constexpr int WAVES = NFRAG <= 2 ? kPlanWavesWide : kPlanWaves;
+        // R = 16: the kernel whose step loop is written in assembly
+        if (NFRAG == 1 && waves == kPlanWavesWide) return launch_linear_steploop16(a, NG, max_step, s);
         if (waves == WAVES) return launch_planned_1024<DT, NFRAG, kOutSwap, WAVES>(a, ntiles, NG, max_step, s);
     }
     if (waves != kPlanWaves) return BSP_ERR_SHAPE;  // (a plan of 16 streams is only consumed by the path above)
@@ -1165,7 +1085,7 @@ int launch_nfrag(const TiledArgs &a, int waves, hipStream_t s) {
 
 constexpr int kCanonicalWaves = 16;  // wavefronts per workgroup of the kernel on the compact storage
 
-int plan_slack_steps() { return kPlanRing; }
+int plan_slack_steps() { return 16; }  // covers the read-ahead of every kernel that consumes a plan
 
 bool tiled_supported(int xdt, int64_t N, int32_t k_align) {
     if (xdt != BSP_BF16 && xdt != BSP_F16) return false;

@@ -17,8 +17,7 @@
 // chunk q; the last entry of a row is where stream w ends.
 //
 // Buffer layout (bytes): wptr int32 [waves][chunks * NG * nacc + 1], padded to 256 | fragments
-// [steps][nfrag][4][64] dwords (dword k of every lane's 16-byte fragment lies in plane k, so that
-// 4-byte-per-lane loads are contiguous) | offsets uint32 [steps][16] (one word per 4 lanes: the lanes
+// [steps][nfrag][64] lanes x 16 bytes (a lane's 8 values of its row) | offsets uint32 [steps][16] (one word per 4 lanes: the lanes
 // of a column differ by their token quad only), with steps = capacity_cols / 32
 // + 3 per row-block (every chunk pads its columns to a multiple of 32 on its own) + read-ahead slack.
 // Integer work only; deterministic.
@@ -91,7 +90,9 @@ __global__ __launch_bounds__(kPlanWavesWide * 64) void plan_scan_kernel(const in
                 const int base = blk_ptr[b], kp = blk_ptr[b + 1] - base, kb = blk_cnt[b];
                 const bool ok = kp > 0 && kp <= kMaxKp && kb >= 0 && kb <= kp && base >= 0 &&
                                 (int64_t)base + kp <= capacity_cols;
-                st = ok ? (kb + 31) >> 5 : 0;
+                // a layer of one chunk gives every row-block at least one step: an empty (or malformed) block gets
+                // a step of zero weights, so that a wavefront's step loop never meets a block without steps
+                st = ok && kb > 0 ? (kb + 31) >> 5 : 1;
             }
         }
         int incl = st;
@@ -140,9 +141,22 @@ __global__ __launch_bounds__(kThreads) void plan_fill_kernel(int32_t R, int32_t 
     const int base = blk_ptr[b];
     const int kp = blk_ptr[b + 1] - base;
     const int kb = blk_cnt[b];
-    if (kp <= 0 || kp > cols_cap || kb > kp || kb < 0 || base < 0 || (int64_t)base + kp > capacity_cols) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l16 = lane & 15, G = lane >> 4, qd = (lane >> 2) & 3, p = lane & 3;
+    if (kp <= 0 || kb <= 0 || kp > cols_cap || kb > kp || base < 0 || (int64_t)base + kp > capacity_cols) {
+        // one-chunk layers: the single step of an empty block holds zero weights and the LDS offset 0
+        if (nchunks == 1 && wave == 0) {
+            const int E1 = NG * nacc;
+            const int64_t quad = b / nacc;
+            const int64_t gs0 = wptr[(quad % waves) * (E1 + 1) + (quad / waves) * nacc + b % nacc];
+            if (gs0 >= 0 && gs0 + 1 <= cap_steps) {
+                for (int f = 0; f < nfrag; ++f)
+                    *reinterpret_cast<uint4 *>(wfrag + (gs0 * nfrag + f) * 256 + lane * 4) = make_uint4(0u, 0u, 0u, 0u);
+                if (lane < 16) xoff[gs0 * 16 + lane] = 0u;
+            }
+        }
+        return;
+    }
     // the block's kept columns, fetched once with coalesced loads, and their count per chunk
     if (threadIdx.x < kPlanMaxChunks) s_cnt[threadIdx.x] = 0;
     __syncthreads();
@@ -231,8 +245,8 @@ __global__ __launch_bounds__(kThreads) void plan_fill_kernel(int32_t R, int32_t 
         if (gs0 < 0 || gs0 + nsteps > cap_steps) return;
         for (int s = wave; s < nsteps; s += kThreads / 64) {
             const int s1 = 32 * s + 8 * G + qd;
-            const uint32_t o1 = lds_col_offset((uint32_t)slotcol[s1], (uint32_t)p);
-            const uint32_t o2 = lds_col_offset((uint32_t)slotcol[s1 + 4], (uint32_t)p);
+            const uint32_t o1 = lds_col_offset4((uint32_t)slotcol[s1], (uint32_t)p);
+            const uint32_t o2 = lds_col_offset4((uint32_t)slotcol[s1 + 4], (uint32_t)p);
             // offsets are multiples of 8 bytes; the 4 lanes of a column (token quads p = 0 .. 3) differ by
             // p in both halves (the swizzle is an exclusive-or on those bits), so p = 0 stands for all four
             if (p == 0) xoff[(gs0 + s) * 16 + (lane >> 2)] = (o1 >> 3) | ((o2 >> 3) << 16);
@@ -248,8 +262,7 @@ __global__ __launch_bounds__(kThreads) void plan_fill_kernel(int32_t R, int32_t 
                         w[i >> 1] |= v << (16 * (i & 1));
                     }
                 }
-#pragma unroll
-                for (int k = 0; k < 4; ++k) wfrag[(((gs0 + s) * nfrag + f) * 4 + k) * 64 + lane] = w[k];
+                *reinterpret_cast<uint4 *>(wfrag + ((gs0 + s) * nfrag + f) * 256 + lane * 4) = make_uint4(w[0], w[1], w[2], w[3]);
             }
         }
     }
@@ -324,7 +337,7 @@ extern "C" int bsp_linear_plan(int vdt, int64_t M, int64_t N, int32_t R, int32_t
     plan_scan_kernel<<<1, waves * 64, 0, s>>>(ch.n > 1 ? steps_bq : nullptr, blk_cnt, blk_ptr, capacity_cols,
                                                    (int32_t)B, (int32_t)L.NG, nacc, ch.n, (int64_t)L.steps,
                                                    plan_slack_steps(), wptr, xoff);
-    if (capacity_cols > 0) {
+    if (capacity_cols > 0 || ch.n == 1) {  // (one-chunk layers: empty row-blocks get their step of zero weights)
         // a row-block keeps at most N columns, padded to the alignment (at most 64)
         const int32_t cols_cap = (int32_t)(N + 64 < kMaxKp ? (N + 64 + 7) / 8 * 8 : kMaxKp);
         plan_fill_kernel<<<dim3((unsigned)B, (unsigned)ch.n), kThreads, (size_t)cols_cap * 2, s>>>(
