@@ -31,7 +31,7 @@ bool tiled_supported(int xdt, int64_t N, int32_t k_align);
 int launch_linear_tiled(const TiledArgs &args, bool plan, hipStream_t s);
 // The planned kernel for R = 16 and layers of up to 1024 input columns (16-bit floats, a plan of 16 streams, Y
 // aligned to 16 bytes); NG = groups of the plan, max_step = steps the plan holds without its read-ahead slack.
-int launch_linear_steploop16(const TiledArgs &args, int64_t NG, int64_t max_step, hipStream_t s);
+int launch_linear_steploop16(const TiledArgs &args, int64_t max_step, hipStream_t s);
 // Column chunks of a plan: layers with more than 1024 (padded) input columns are cut into chunks of
 // 1024 columns, the width of X that fits in LDS next to 64 tokens; narrower layers are one chunk.
 constexpr int kPlanMaxChunks = 4;
@@ -61,6 +61,34 @@ constexpr int plan_nacc(int nfrag, bool chunked, int R) {
 inline int plan_waves(int64_t N, int32_t R) {
     (void)N;
     return (R == 16 || R == 32) ? kPlanWavesWide : kPlanWaves;
+}
+// Which row-block a plan's entry (group g, wavefront w, place i in the run) stands for, and back.  Plain plans deal
+// runs of nacc blocks round robin: block (g * waves + w) * nacc + i.  Paired plans (R = 16, one column chunk: the
+// kernel with the assembly loop) deal runs of 2 blocks so that the runs of one wavefront in groups 2 s and 2 s + 1 are
+// neighbours -- four consecutive row-blocks, 128 bytes of a token's output row, which that kernel stores together as
+// whole lines whenever both groups fall into its strip -- while the unit that balances the wavefronts stays a run.
+inline bool plan_paired(int32_t R, bool chunked) { return R == 16 && !chunked; }
+__host__ __device__ inline int64_t plan_block(int64_t g, int w, int i, int waves, int nacc, bool paired) {
+    if (paired) return (g >> 1) * (4 * waves) + 4 * w + 2 * (int)(g & 1) + i;
+    return (g * waves + w) * nacc + i;
+}
+__host__ __device__ inline void plan_entry(int64_t b, int waves, int nacc, bool paired, int64_t &g, int &w, int &i) {
+    if (paired) {
+        const int r = (int)(b % (4 * waves));
+        g = 2 * (b / (4 * waves)) + ((r >> 1) & 1);
+        w = r >> 2;
+        i = r & 1;
+    } else {
+        const int64_t run = b / nacc;
+        g = run / waves;
+        w = (int)(run % waves);
+        i = (int)(b % nacc);
+    }
+}
+// Groups of a plan.
+inline int64_t plan_groups(int64_t B, int waves, int nacc, bool paired) {
+    if (paired) return 2 * ((B + 4 * waves - 1) / (4 * waves));
+    return (B + (int64_t)waves * nacc - 1) / ((int64_t)waves * nacc);
 }
 // Steps the planned kernel may read past the last step of the storage (values unused).
 int plan_slack_steps();

@@ -15,9 +15,19 @@
 // A row-block ends where its step counter runs out (the counts of up to 8 row-blocks travel in a 64-bit scalar,
 // 8 bits each).  The block end is a subroutine: rounding to the output type, for the second block of a pair the
 // lane re-deal (v_permlane32_swap / v_permlane16_swap) that turns two 16-row fragments into 16 token rows x 64
-// contiguous bytes, the stores, the accumulators' restart from the bias (kept as fp32 in LDS behind the tile, read
-// one block ahead), and the jump back to the step after the one that ended the block.  Row-blocks without kept
-// columns have one step of zero weights in the plan, so a block never has zero steps.
+// contiguous bytes, the accumulators' restart from the bias (kept as fp32 in LDS behind the tile, read one block
+// ahead), and the jump back to the step after the one that ended the block.  Row-blocks without kept columns have
+// one step of zero weights in the plan, so a block never has zero steps.
+//
+// Output: the plan deals the row-blocks in pairs (the unit that balances the wavefronts), but so that the pairs of
+// one wavefront in groups 2 s and 2 s + 1 are neighbours (see plan_block): four consecutive row-blocks, a quad,
+// 128 bytes of a token's output row.  A wavefront keeps the first pair's rounded output in registers and stores
+// when the quad is complete.  Before that the two pairs trade half of their lanes (row rotation by 8 with a bank
+// mask, DPP), after which the lanes of a 16-lane row hold the whole 128 bytes of token rows 0-7 (first register
+// set) or 8-15 (second): every store instruction then writes 8 whole lines.  A pair whose partner belongs to
+// another strip leaves alone, 16 token rows x 64 bytes per instruction.  Written pair by pair (64-byte pieces at a stride of the row length, the other half
+// of a line arriving a few microseconds later from the same wavefront), the stores of the BERT-large QKV layer
+// lengthened its launch by 5 us of 23; line by line they cost 2.
 #include "bsp_common.h"
 #include "bsp_linear_internal.h"
 #include "bsp_mfma_device.h"
@@ -31,13 +41,18 @@ namespace {
 //   v16-31   panel fragments of four steps          v32-35  offset words of four steps
 //   v36-51 / v52-67  X fragments, even / odd step   v68-70  LDS addresses, scratch
 //   v71 lane * 16, v72 (lane / 4) * 4, v73 token-quad mask, v74 = 3
-//   v76-91   output: per sub-tile u the rounded fragments of an even (v[76+4u], v[77+4u]) and an odd row-block
-//   v92-95   byte offset of the lane's 16 output bytes per sub-tile, v96-99 bias the next block starts from,
-//   v100 / v101 LDS address of the next bias read and its upper bound
+//   v76-91   output of the quad's first pair: per sub-tile u the rounded fragments of its even (v[76+4u], v[77+4u])
+//            and odd row-block, 16 contiguous bytes of a token row after the re-deal; v92-107 the second pair's
+//   v108-111 byte offset of the lane's 16 output bytes per sub-tile when a pair leaves alone, v118-121 when a quad
+//   leaves (whole lines), v112-115 bias the next block starts from, v116 / v117 LDS address of the next bias read
+//   and its upper bound
 //   s[40:41] fragment pointer, s[42:43] offset pointer (both four steps ahead), s44 steps left in the block - 1,
-//   s45 blocks left - 1, s[46:47] step counts still to come, s[48:55] token masks of the sub-tiles, s[56:57] where
-//   the current pair of row-blocks goes, s58 parity of the current block, s59 resume point, s60 bias stride,
-//   s[62:63] scratch
+//   s45 blocks left - 1, s[46:47] step counts still to come, s[48:55] token masks of the sub-tiles (a pair alone),
+//   s[68:75] / s[76:83] the same for the two stores of a quad's sub-tile, s[56:57] where the current quad of
+//   row-blocks goes and s[66:67] the same 8 token rows further on, s58 place of the current block in its quad, s59
+//   resume point, s60 bias stride, s61 bytes of 16 token rows of Y, s[62:63] scratch, s[64:65] all ones once the
+//   first pair of the quad in the registers is this call's own (a call may start with the second pair of a quad),
+//   s84 token rows of the tile, s85 bytes of a token row
 #define SL_W(J) "v[16+4*" #J ":19+4*" #J "]"
 #define SL_O(J) "v[32+" #J "]"
 #define SL_XP(P, U, H) "v[36+16*" #P "+4*" #U "+2*" #H ":37+16*" #P "+4*" #U "+2*" #H "]"
@@ -74,25 +89,57 @@ namespace {
     "s_cbranch_scc1 Lend" #J "_%=\n"                     \
     "Lres" #J "_%=:\n"
 #define SL_ACC_FROM_BIAS                                                                        \
-    "v_mov_b32 v0, v96\n v_mov_b32 v1, v97\n v_mov_b32 v2, v98\n v_mov_b32 v3, v99\n"           \
-    "v_mov_b32 v4, v96\n v_mov_b32 v5, v97\n v_mov_b32 v6, v98\n v_mov_b32 v7, v99\n"           \
-    "v_mov_b32 v8, v96\n v_mov_b32 v9, v97\n v_mov_b32 v10, v98\n v_mov_b32 v11, v99\n"         \
-    "v_mov_b32 v12, v96\n v_mov_b32 v13, v97\n v_mov_b32 v14, v98\n v_mov_b32 v15, v99\n"
+    "v_mov_b32 v0, v112\n v_mov_b32 v1, v113\n v_mov_b32 v2, v114\n v_mov_b32 v3, v115\n"           \
+    "v_mov_b32 v4, v112\n v_mov_b32 v5, v113\n v_mov_b32 v6, v114\n v_mov_b32 v7, v115\n"           \
+    "v_mov_b32 v8, v112\n v_mov_b32 v9, v113\n v_mov_b32 v10, v114\n v_mov_b32 v11, v115\n"         \
+    "v_mov_b32 v12, v112\n v_mov_b32 v13, v113\n v_mov_b32 v14, v114\n v_mov_b32 v15, v115\n"
 #define SL_NEXT_COUNT "s_bfe_u32 s44, s46, 0x80000\n s_lshr_b64 s[46:47], s[46:47], 8\n s_sub_u32 s44, s44, 1\n"
-// rounded accumulators of sub-tile U into words H, H + 1 of its output quad (H = 0: even block, 2: odd block)
-#define SL_CVT(CVT, U, H)                                                    \
-    CVT " v[76+4*" #U "+" #H "], v[4*" #U "], v[4*" #U "+1]\n"                 \
-    CVT " v[77+4*" #U "+" #H "], v[4*" #U "+2], v[4*" #U "+3]\n"
-#define SL_SWAP(OP, U)                                      \
-    OP " v[76+4*" #U "], v[78+4*" #U "]\n"                    \
-    OP " v[77+4*" #U "], v[79+4*" #U "]\n"
-#define SL_SWAPS                                                                                              \
-    "s_nop 1\n"                                                                                               \
-    SL_SWAP("v_permlane32_swap_b32", 0) SL_SWAP("v_permlane32_swap_b32", 1) SL_SWAP("v_permlane32_swap_b32", 2) \
-    SL_SWAP("v_permlane32_swap_b32", 3) "s_nop 1\n"                                                           \
-    SL_SWAP("v_permlane16_swap_b32", 0) SL_SWAP("v_permlane16_swap_b32", 1) SL_SWAP("v_permlane16_swap_b32", 2) \
-    SL_SWAP("v_permlane16_swap_b32", 3) "s_nop 1\n"
-#define SL_STORE(U) "global_store_dwordx4 v[92+" #U "], v[76+4*" #U ":79+4*" #U "], s[56:57] nt\n"
+// rounded accumulators of sub-tile U into words H, H + 1 of its output quad of registers (H = 0: even block, 2: odd
+// block), Q = 76 for the first pair of a quad of row-blocks, 92 for the second
+#define SL_CVT(CVT, Q, U, H)                                                          \
+    CVT " v[" #Q "+4*" #U "+" #H "], v[4*" #U "], v[4*" #U "+1]\n"                       \
+    CVT " v[" #Q "+1+4*" #U "+" #H "], v[4*" #U "+2], v[4*" #U "+3]\n"
+#define SL_CVT4(CVT, Q, H) SL_CVT(CVT, Q, 0, H) SL_CVT(CVT, Q, 1, H) SL_CVT(CVT, Q, 2, H) SL_CVT(CVT, Q, 3, H)
+#define SL_SWAP(OP, Q, U)                                        \
+    OP " v[" #Q "+4*" #U "], v[" #Q "+2+4*" #U "]\n"                \
+    OP " v[" #Q "+1+4*" #U "], v[" #Q "+3+4*" #U "]\n"
+#define SL_SWAPS(Q)                                                                                                   \
+    "s_nop 1\n"                                                                                                       \
+    SL_SWAP("v_permlane32_swap_b32", Q, 0) SL_SWAP("v_permlane32_swap_b32", Q, 1) SL_SWAP("v_permlane32_swap_b32", Q, 2) \
+    SL_SWAP("v_permlane32_swap_b32", Q, 3) "s_nop 1\n"                                                                \
+    SL_SWAP("v_permlane16_swap_b32", Q, 0) SL_SWAP("v_permlane16_swap_b32", Q, 1) SL_SWAP("v_permlane16_swap_b32", Q, 2) \
+    SL_SWAP("v_permlane16_swap_b32", Q, 3) "s_nop 1\n"
+#define SL_STORE(Q, U, OFF) \
+    "global_store_dwordx4 v[108+" #U "], v[" #Q "+4*" #U ":" #Q "+3+4*" #U "], s[56:57] offset:" #OFF " nt\n"
+// The two pairs of sub-tile U trade lanes: lanes 8-15 of every 16-lane row of the first pair's registers take what
+// lanes 0-7 of the second pair's hold, and the other way round (DPP: a move from the lane 8 places round the row,
+// written where the bank mask allows).  v68-70, v75 carry the second pair's words meanwhile.
+#define SL_TRADE(U)                                                                                        \
+    "v_mov_b32 v68, v[92+4*" #U "]\n v_mov_b32 v69, v[93+4*" #U "]\n"                                        \
+    "v_mov_b32 v70, v[94+4*" #U "]\n v_mov_b32 v75, v[95+4*" #U "]\n"                                        \
+    "v_mov_b32_dpp v[92+4*" #U "], v[76+4*" #U "] row_ror:8 row_mask:0xf bank_mask:0x3\n"                     \
+    "v_mov_b32_dpp v[93+4*" #U "], v[77+4*" #U "] row_ror:8 row_mask:0xf bank_mask:0x3\n"                     \
+    "v_mov_b32_dpp v[94+4*" #U "], v[78+4*" #U "] row_ror:8 row_mask:0xf bank_mask:0x3\n"                     \
+    "v_mov_b32_dpp v[95+4*" #U "], v[79+4*" #U "] row_ror:8 row_mask:0xf bank_mask:0x3\n"                     \
+    "v_mov_b32_dpp v[76+4*" #U "], v68 row_ror:8 row_mask:0xf bank_mask:0xc\n"                               \
+    "v_mov_b32_dpp v[77+4*" #U "], v69 row_ror:8 row_mask:0xf bank_mask:0xc\n"                               \
+    "v_mov_b32_dpp v[78+4*" #U "], v70 row_ror:8 row_mask:0xf bank_mask:0xc\n"                               \
+    "v_mov_b32_dpp v[79+4*" #U "], v75 row_ror:8 row_mask:0xf bank_mask:0xc\n"
+// the stores of a quad's sub-tile U: token rows 0-7 (mask s[MA:MA+1]), then rows 8-15 (mask s[MB:MB+1])
+#define SL_STORE_QUAD(U, MA, MB)                                                                                 \
+    "s_mov_b64 exec, s[" #MA ":" #MA "+1]\n"                                                                     \
+    "global_store_dwordx4 v[118+" #U "], v[76+4*" #U ":79+4*" #U "], s[56:57] nt\n"                                \
+    "s_mov_b64 exec, s[" #MB ":" #MB "+1]\n"                                                                     \
+    "global_store_dwordx4 v[118+" #U "], v[92+4*" #U ":95+4*" #U "], s[66:67] nt\n"
+#define SL_STORE_PAIR(Q, U, M, OFF) "s_mov_b64 exec, s[" #M ":" #M "+1]\n" SL_STORE(Q, U, OFF)
+// the same for the lanes of the first two 16-lane rows only (a block without a partner: 32 bytes per token row)
+#define SL_STORE_HALF(Q, U, M, OFF) "s_mov_b32 s62, s" #M "\n s_mov_b64 exec, s[62:63]\n" SL_STORE(Q, U, OFF)
+#define SL_STORE_FIRST(U, M) "s_and_b64 exec, s[" #M ":" #M "+1], s[64:65]\n" SL_STORE(76, U, 0)
+// token masks of sub-tile U from the row numbers in v68 (a pair alone), v75 and v69 (the two stores of a quad)
+#define SL_MASKS(U)                                                                              \
+    "v_cmp_gt_u32 s[48+2*" #U ":49+2*" #U "], s84, v68\n v_add_u32 v68, 16, v68\n"                 \
+    "v_cmp_gt_u32 s[68+2*" #U ":69+2*" #U "], s84, v75\n v_add_u32 v75, 16, v75\n"                 \
+    "v_cmp_gt_u32 s[76+2*" #U ":77+2*" #U "], s84, v69\n v_add_u32 v69, 16, v69\n"
 
 #define SL_CLOBBERS                                                                                                     \
     "v0", "v1", "v2", "v3", "v4", "v5", "v6", "v7", "v8", "v9", "v10", "v11", "v12", "v13", "v14", "v15", "v16", "v17",   \
@@ -101,84 +148,109 @@ namespace {
         "v50", "v51", "v52", "v53", "v54", "v55", "v56", "v57", "v58", "v59", "v60", "v61", "v62", "v63", "v64", "v65",   \
         "v66", "v67", "v68", "v69", "v70", "v71", "v72", "v73", "v74", "v75", "v76", "v77", "v78", "v79", "v80", "v81",   \
         "v82", "v83", "v84", "v85", "v86", "v87", "v88", "v89", "v90", "v91", "v92", "v93", "v94", "v95", "v96", "v97",   \
-        "v98", "v99", "v100", "v101", "s40", "s41", "s42", "s43", "s44", "s45", "s46", "s47", "s48", "s49", "s50", "s51", \
-        "s52", "s53", "s54", "s55", "s56", "s57", "s58", "s59", "s60", "s61", "s62", "s63", "scc", "memory"
+        "v98", "v99", "v100", "v101", "v102", "v103", "v104", "v105", "v106", "v107", "v108", "v109", "v110", "v111", "v112",   \
+        "v113", "v114", "v115", "v116", "v117", "v118", "v119", "v120", "v121", "s40", "s41", "s42", "s43", "s44", "s45", "s46", "s47", "s48", "s49", "s50", "s51", \
+        "s52", "s53", "s54", "s55", "s56", "s57", "s58", "s59", "s60", "s61", "s62", "s63", "s64", "s65", "s66", "s67", "s68", "s69", "s70", "s71", "s72", "s73", "s74", "s75", "s76",  \
+        "s77", "s78", "s79", "s80", "s81", "s82", "s83", "s84", "s85", "scc", "memory"
 
-// The whole walk of up to 8 row-blocks of one wavefront.  MFMA / CVT are the mnemonics of the layer's type.
+// The whole walk of up to 8 row-blocks (two quads) of one wavefront.  MFMA / CVT are the mnemonics of the layer's type.
 #define SL_WALK(MFMA, CVT)                                                                                           \
     asm volatile(                                                                                                    \
         "s_mov_b64 s[40:41], %[wb]\n s_mov_b64 s[42:43], %[ob]\n s_mov_b64 s[56:57], %[yb]\n"                        \
-        "s_mov_b64 s[46:47], %[cnt]\n s_sub_u32 s45, %[nb], 1\n"                                                     \
-        "s_mov_b64 s[48:49], %[m0]\n s_mov_b64 s[50:51], %[m1]\n s_mov_b64 s[52:53], %[m2]\n s_mov_b64 s[54:55], %[m3]\n" \
-        "v_mov_b32 v71, %[wl]\n v_mov_b32 v72, %[ol]\n v_mov_b32 v73, %[pm]\n v_mov_b32 v74, 3\n"                    \
-        "v_mov_b32 v92, %[y0]\n v_mov_b32 v93, %[y1]\n v_mov_b32 v94, %[y2]\n v_mov_b32 v95, %[y3]\n"                \
-        "v_mov_b32 v100, %[ba]\n v_mov_b32 v101, %[bl]\n"                                                            \
+        "s_mov_b64 s[46:47], %[cnt]\n s_sub_u32 s45, %[nb], 1\n s_mov_b32 s61, %[rs]\n s_mov_b32 s84, %[nr]\n"      \
+        "s_lshr_b32 s85, s61, 4\n s_lshr_b32 s62, s61, 1\n s_add_u32 s66, s56, s62\n s_addc_u32 s67, s57, 0\n"      \
+        /* a call starts with the first (k0 = 0) or the second pair (k0 = 2) of a quad */                           \
+        "s_mov_b32 s58, %[k0]\n s_mov_b32 s63, 0\n s_cmp_eq_u32 s58, 0\n s_cselect_b64 s[64:65], -1, 0\n"             \
+        "s_cselect_b32 s60, 64, 0xf40\n" /* from the second bias to the third: the next block, or the next quad */   \
+        /* lane constants: 16 * lane, 4 * (lane / 4), the token quad in both halves of a word, 3 */                  \
+        "v_mbcnt_lo_u32_b32 v70, -1, 0\n v_mbcnt_hi_u32_b32 v70, -1, v70\n"                                         \
+        "v_lshlrev_b32 v71, 4, v70\n v_and_b32 v72, 0xfc, v70\n"                                                    \
+        "v_and_b32 v73, 3, v70\n v_lshl_or_b32 v73, v73, 16, v73\n v_mov_b32 v74, 3\n"                             \
+        /* where a lane's 16 bytes go, and which token rows are there.  A pair alone: token row l16 of the sub-tile, */ \
+        /* bytes 16 G; a quad: token row l16 % 8 (first store; 8 rows further on in the second), bytes 64 (l16 / 8) */ \
+        /* + 16 G of the 128 */                                                                                      \
+        "v_and_b32 v68, 15, v70\n v_lshrrev_b32 v69, 4, v70\n v_and_b32 v75, 7, v70\n"                              \
+        "v_mul_lo_u32 v108, v68, s85\n v_lshl_add_u32 v108, v69, 4, v108\n"                                         \
+        "v_add_u32 v109, s61, v108\n v_add_u32 v110, s61, v109\n v_add_u32 v111, s61, v110\n"                       \
+        "v_mul_lo_u32 v118, v75, s85\n v_lshl_add_u32 v118, v69, 4, v118\n"                                         \
+        "v_lshrrev_b32 v69, 3, v68\n v_lshl_add_u32 v118, v69, 6, v118\n"                                           \
+        "v_add_u32 v119, s61, v118\n v_add_u32 v120, s61, v119\n v_add_u32 v121, s61, v120\n"                       \
+        "v_add_u32 v69, 8, v75\n"                                                                                    \
+        SL_MASKS(0) SL_MASKS(1) SL_MASKS(2) SL_MASKS(3)                                                              \
+        "v_mov_b32 v116, %[ba]\n v_mov_b32 v117, %[bl]\n"                                                           \
         SL_LOAD(0) SL_LOAD(1) SL_LOAD(2) SL_LOAD(3) SL_ADVANCE                                                       \
         /* the first block starts from its bias; the second block's is read ahead */                                 \
-        "ds_read_b128 v[96:99], v100\n"                                                                              \
-        "v_add_u32 v100, 64, v100\n v_min_u32 v100, v100, v101\n"                                                    \
+        "ds_read_b128 v[112:115], v116\n"                                                                           \
+        "v_add_u32 v116, 64, v116\n v_min_u32 v116, v116, v117\n"                                                   \
         "s_waitcnt lgkmcnt(0)\n"                                                                                     \
         SL_ACC_FROM_BIAS                                                                                             \
-        "ds_read_b128 v[96:99], v100\n"                                                                              \
-        "v_add_u32 v100, 0x7c0, v100\n v_min_u32 v100, v100, v101\n"                                                 \
+        "ds_read_b128 v[112:115], v116\n"                                                                           \
+        "v_add_u32 v116, s60, v116\n v_min_u32 v116, v116, v117\n"                                                  \
         SL_NEXT_COUNT                                                                                                \
-        "s_mov_b32 s58, 0\n"                                                                                         \
         "s_waitcnt vmcnt(7)\n"                                                                                       \
         SL_ADDR(0) SL_RD(0, 0, 0) SL_RD(0, 1, 16384) SL_RD(0, 2, 32768) SL_RD(0, 3, 49152)                           \
         "Ltop%=:\n"                                                                                                  \
         SL_STEP(MFMA, 0, 1, 0, 1) SL_STEP(MFMA, 1, 2, 1, 0) SL_STEP(MFMA, 2, 3, 0, 1) SL_STEP(MFMA, 3, 0, 1, 0)      \
         SL_ADVANCE                                                                                                   \
         "s_branch Ltop%=\n"                                                                                          \
-        "Lend0_%=: s_mov_b32 s59, 0\n s_branch Lblk%=\n"                                                              \
-        "Lend1_%=: s_mov_b32 s59, 1\n s_branch Lblk%=\n"                                                              \
-        "Lend2_%=: s_mov_b32 s59, 2\n s_branch Lblk%=\n"                                                              \
-        "Lend3_%=: s_mov_b32 s59, 3\n"                                                                                \
-        /* ---- end of a row-block ---- */                                                                           \
+        "Lend0_%=: s_mov_b32 s59, 0\n s_branch Lblk%=\n"                                                            \
+        "Lend1_%=: s_mov_b32 s59, 1\n s_branch Lblk%=\n"                                                            \
+        "Lend2_%=: s_mov_b32 s59, 2\n s_branch Lblk%=\n"                                                            \
+        "Lend3_%=: s_mov_b32 s59, 3\n"                                                                               \
+        /* ---- end of a row-block: s58 = its place in the quad ---- */                                              \
         "Lblk%=:\n"                                                                                                  \
-        "s_nop 15\n s_nop 7\n" /* the last matrix instruction has written its result */                              \
-        "s_cmp_eq_u32 s58, 0\n"                                                                                      \
-        "s_cbranch_scc0 Lodd%=\n"                                                                                    \
-        SL_CVT(CVT, 0, 0) SL_CVT(CVT, 1, 0) SL_CVT(CVT, 2, 0) SL_CVT(CVT, 3, 0)                                      \
-        "s_mov_b32 s58, 1\n s_movk_i32 s60, 64\n"                                                                    \
-        "s_branch Lcom%=\n"                                                                                          \
-        "Lodd%=:\n"                                                                                                  \
-        SL_CVT(CVT, 0, 2) SL_CVT(CVT, 1, 2) SL_CVT(CVT, 2, 2) SL_CVT(CVT, 3, 2)                                      \
-        SL_SWAPS                                                                                                     \
-        "s_mov_b64 exec, s[48:49]\n" SL_STORE(0) "s_mov_b64 exec, s[50:51]\n" SL_STORE(1)                            \
-        "s_mov_b64 exec, s[52:53]\n" SL_STORE(2) "s_mov_b64 exec, s[54:55]\n" SL_STORE(3)                            \
+        "s_nop 15\n s_nop 7\n" /* the last matrix instruction has written its result */                             \
+        "s_movk_i32 s60, 64\n"                                                                                       \
+        "s_cmp_eq_u32 s58, 0\n s_cbranch_scc1 Lk0_%=\n s_cmp_eq_u32 s58, 1\n s_cbranch_scc1 Lk1_%=\n"               \
+        "s_cmp_eq_u32 s58, 2\n s_cbranch_scc1 Lk2_%=\n"                                                             \
+        /* last block of the quad: the quad leaves (or its second pair alone, if the first is not this call's) */    \
+        SL_CVT4(CVT, 92, 2) SL_SWAPS(92)                                                                             \
+        "s_cmp_eq_u64 s[64:65], 0\n s_cbranch_scc1 Lsecond%=\n"                                                     \
+        SL_TRADE(0) SL_TRADE(1) SL_TRADE(2) SL_TRADE(3)                                                              \
+        SL_STORE_QUAD(0, 68, 76) SL_STORE_QUAD(1, 70, 78) SL_STORE_QUAD(2, 72, 80) SL_STORE_QUAD(3, 74, 82)          \
+        "s_branch Lleft%=\n"                                                                                         \
+        "Lsecond%=:\n"                                                                                               \
+        SL_STORE_PAIR(92, 0, 48, 64) SL_STORE_PAIR(92, 1, 50, 64) SL_STORE_PAIR(92, 2, 52, 64) SL_STORE_PAIR(92, 3, 54, 64) \
+        "Lleft%=:\n"                                                                                                 \
         "s_mov_b64 exec, -1\n"                                                                                       \
-        "s_add_u32 s56, s56, 1024\n s_addc_u32 s57, s57, 0\n"                                                        \
-        "s_mov_b32 s58, 0\n s_movk_i32 s60, 0x7c0\n"                                                                 \
+        "s_add_u32 s56, s56, 2048\n s_addc_u32 s57, s57, 0\n s_add_u32 s66, s66, 2048\n s_addc_u32 s67, s67, 0\n"   \
+        "s_mov_b32 s58, 0\n s_mov_b64 s[64:65], -1\n s_branch Lcom%=\n"                                                                      \
+        "Lk0_%=:\n" SL_CVT4(CVT, 76, 0) "s_mov_b32 s58, 1\n s_branch Lcom%=\n"                                      \
+        /* (the bias read two blocks ahead of block 1 is the first block's of the next group's quad) */              \
+        "Lk1_%=:\n" SL_CVT4(CVT, 76, 2) SL_SWAPS(76) "s_mov_b32 s58, 2\n s_movk_i32 s60, 0xf40\n s_branch Lcom%=\n" \
+        "Lk2_%=:\n" SL_CVT4(CVT, 92, 0) "s_mov_b32 s58, 3\n"                                                        \
         "Lcom%=:\n"                                                                                                  \
         "s_sub_u32 s45, s45, 1\n"                                                                                    \
         "s_cbranch_scc1 Ldone%=\n"                                                                                   \
         SL_ACC_FROM_BIAS                                                                                             \
-        "ds_read_b128 v[96:99], v100\n"                                                                              \
-        "v_add_u32 v100, s60, v100\n v_min_u32 v100, v100, v101\n"                                                   \
+        "ds_read_b128 v[112:115], v116\n"                                                                           \
+        "v_add_u32 v116, s60, v116\n v_min_u32 v116, v116, v117\n"                                                  \
         SL_NEXT_COUNT                                                                                                \
-        "s_cmp_eq_u32 s59, 0\n s_cbranch_scc1 Lres0_%=\n s_cmp_eq_u32 s59, 1\n s_cbranch_scc1 Lres1_%=\n"              \
-        "s_cmp_eq_u32 s59, 2\n s_cbranch_scc1 Lres2_%=\n s_branch Lres3_%=\n"                                          \
-        /* ---- the last block is done; an even one without a partner leaves alone (its 32 bytes per token) ---- */   \
+        "s_cmp_eq_u32 s59, 0\n s_cbranch_scc1 Lres0_%=\n s_cmp_eq_u32 s59, 1\n s_cbranch_scc1 Lres1_%=\n"           \
+        "s_cmp_eq_u32 s59, 2\n s_cbranch_scc1 Lres2_%=\n s_branch Lres3_%=\n"                                       \
+        /* ---- the last block is done; what an unfinished quad holds leaves now: s58 blocks of it ---- */           \
         "Ldone%=:\n"                                                                                                 \
-        "s_cmp_eq_u32 s58, 1\n"                                                                                      \
-        "s_cbranch_scc0 Lfin%=\n"                                                                                    \
-        SL_SWAPS                                                                                                     \
-        "s_mov_b32 s63, 0\n"                                                                                         \
-        "s_mov_b32 s62, s48\n s_mov_b64 exec, s[62:63]\n" SL_STORE(0)                                                \
-        "s_mov_b32 s62, s50\n s_mov_b64 exec, s[62:63]\n" SL_STORE(1)                                                \
-        "s_mov_b32 s62, s52\n s_mov_b64 exec, s[62:63]\n" SL_STORE(2)                                                \
-        "s_mov_b32 s62, s54\n s_mov_b64 exec, s[62:63]\n" SL_STORE(3)                                                \
+        "s_cmp_eq_u32 s58, 0\n s_cbranch_scc1 Lfin%=\n"                                                             \
+        "s_cmp_eq_u32 s58, 1\n s_cbranch_scc0 Lpair%=\n"                                                            \
+        SL_SWAPS(76) /* one block: the 32 bytes per token row it has */                                              \
+        SL_STORE_HALF(76, 0, 48, 0) SL_STORE_HALF(76, 1, 50, 0) SL_STORE_HALF(76, 2, 52, 0) SL_STORE_HALF(76, 3, 54, 0) \
+        "s_branch Lfin%=\n"                                                                                          \
+        "Lpair%=:\n"                                                                                                 \
+        SL_STORE_FIRST(0, 48) SL_STORE_FIRST(1, 50) SL_STORE_FIRST(2, 52) SL_STORE_FIRST(3, 54)                      \
         "s_mov_b64 exec, -1\n"                                                                                       \
+        "s_cmp_eq_u32 s58, 3\n s_cbranch_scc0 Lfin%=\n"                                                             \
+        SL_SWAPS(92)                                                                                                 \
+        SL_STORE_HALF(92, 0, 48, 64) SL_STORE_HALF(92, 1, 50, 64) SL_STORE_HALF(92, 2, 52, 64) SL_STORE_HALF(92, 3, 54, 64) \
         "Lfin%=:\n"                                                                                                  \
+        "s_mov_b64 exec, -1\n"                                                                                       \
         "s_waitcnt vmcnt(0) lgkmcnt(0)\n"                                                                            \
         :                                                                                                            \
-        : [wb] "s"(wb), [ob] "s"(ob), [yb] "s"(yb), [cnt] "s"(counts), [nb] "s"(nb), [m0] "s"(tmask[0]),             \
-          [m1] "s"(tmask[1]), [m2] "s"(tmask[2]), [m3] "s"(tmask[3]), [wl] "v"(wl), [ol] "v"(ol), [pm] "v"(pm),      \
-          [y0] "v"(yoff[0]), [y1] "v"(yoff[1]), [y2] "v"(yoff[2]), [y3] "v"(yoff[3]), [ba] "v"(ba), [bl] "v"(bl)     \
+        : [wb] "s"(wb), [ob] "s"(ob), [yb] "s"(yb), [cnt] "s"(counts), [nb] "s"(nb), [rs] "s"(rs), [k0] "s"(k0),     \
+          [nr] "s"(nr), [ba] "v"(ba), [bl] "v"(bl)                                                                   \
         : SL_CLOBBERS)
 
 constexpr int kSlWaves = 16;   // wavefronts per workgroup = streams of the plan
-constexpr int kSlNacc = 2;     // consecutive row-blocks of a wavefront per group: 64 bytes of a token's output row
+constexpr int kSlNacc = 2;     // consecutive row-blocks of a wavefront per group (paired plans: see plan_block)
 constexpr int kSlBatch = 8;    // row-blocks per call of the loop (their step counts fill a 64-bit scalar)
 
 template <int DT>
@@ -197,30 +269,25 @@ __global__ __launch_bounds__(kSlWaves * 64) void linear_steploop16_kernel(
     // the X tile, and behind it the bias of the strip's rows as fp32 (zeros without a bias and past row M)
     stage_x_tile<4>(X, T, N, npad, t0);
     float *btab = reinterpret_cast<float *>(smem_x + kXTileBytes);
-    const int64_t strip_row0 = (int64_t)g0 * (kSlWaves * kSlNacc * 16);
-    const int rows = ng * (kSlWaves * kSlNacc * 16);
+    // (for the rows of the quads the strip's groups fall into: 64 row-blocks per two groups)
+    const int64_t strip_row0 = (int64_t)(g0 >> 1) * (4 * kSlWaves * 16);
+    const int rows = (((g0 + ng - 1) >> 1) - (g0 >> 1) + 1) * (4 * kSlWaves * 16);
     for (int i = threadIdx.x; i < rows; i += kSlWaves * 64) {
         const int64_t r = strip_row0 + i;
         btab[i] = (bias && r < M) ? elem<DT>::load(bias, r) : 0.0f;
     }
     __syncthreads();
 
-    // this wavefront's entries of the strip: entry e is row-block ((g0 + e / 2) * 16 + wave) * 2 + e % 2; the
-    // blocks grow with e, so the entries inside the layer are a prefix
+    // this wavefront's entries of the strip: entry e is place e % 2 of its pair in group g0 + e / 2; the blocks grow
+    // with e, so the entries inside the layer are a prefix
     const int32_t *my = wptr + (int64_t)wave * ((int64_t)NG * kSlNacc + 1) + (int64_t)g0 * kSlNacc;
     int nvalid = 0;
     for (int e = 0; e < ng * kSlNacc; ++e)
-        if ((((int64_t)(g0 + (e >> 1)) * kSlWaves + wave) << 1) + (e & 1) < B) nvalid = e + 1;
+        if (plan_block(g0 + (e >> 1), wave, e & 1, kSlWaves, kSlNacc, true) < B) nvalid = e + 1;
     if (nvalid == 0) return;  // (after the barrier)
 
-    uint64_t tmask[4];
-    uint32_t yoff[4];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        tmask[u] = __ballot(t0 + 16 * u + l16 < T);
-        yoff[u] = (uint32_t)((16 * u + l16) * M * 2 + 16 * G);
-    }
-    const uint32_t wl = lane * 16, ol = (lane >> 2) * 4, pm = (uint32_t)(lane & 3) * 0x10001u;
+    const uint32_t rs = (uint32_t)(32 * M);                   // bytes of 16 token rows of Y
+    const int nr = (int)min((int64_t)64, T - t0);             // token rows of the tile
     const uint32_t bl = kXTileBytes + (uint32_t)rows * 4 - 16;
     uint8_t *Ytile = reinterpret_cast<uint8_t *>(Y) + t0 * M * 2;
 
@@ -241,9 +308,12 @@ __global__ __launch_bounds__(kSlWaves * 64) void linear_steploop16_kernel(
                                 ((uint64_t)__builtin_amdgcn_readfirstlane((uint32_t)(packed >> 32)) << 32);
         const uint8_t *wb = wfrag + (int64_t)first * 1024;
         const uint8_t *ob = xoff + (int64_t)first * 64;
-        const int64_t pair_col = ((int64_t)(g0 + (e0 >> 1)) * kSlWaves + wave) * (kSlNacc * 16);
-        uint8_t *yb = Ytile + pair_col * 2;
-        const uint32_t ba = kXTileBytes + (uint32_t)((pair_col - strip_row0) + 4 * G) * 4;
+        // the batch starts with the first (k0 = 0) or the second pair (k0 = 2) of a quad of row-blocks
+        const int gfirst = g0 + (e0 >> 1);
+        const int k0 = __builtin_amdgcn_readfirstlane(2 * (gfirst & 1));
+        const int64_t quad_col = ((int64_t)(gfirst >> 1) * (4 * kSlWaves) + 4 * wave) * 16;
+        uint8_t *yb = Ytile + quad_col * 2;
+        const uint32_t ba = kXTileBytes + (uint32_t)((quad_col + 16 * k0 - strip_row0) + 4 * G) * 4;
         if constexpr (DT == BSP_BF16) SL_WALK("v_mfma_f32_16x16x32_bf16", "v_cvt_pk_bf16_f32");
         else SL_WALK("v_mfma_f32_16x16x32_f16", "v_cvt_pk_f16_f32");
     }
@@ -251,19 +321,21 @@ __global__ __launch_bounds__(kSlWaves * 64) void linear_steploop16_kernel(
 
 }  // namespace
 
-// Launch for R = 16, a plan of 16 streams, npad <= 1024, Y aligned to 16 bytes.
-int launch_linear_steploop16(const TiledArgs &a, int64_t NG, int64_t max_step, hipStream_t s) {
+// Launch for R = 16, a paired plan of 16 streams, npad <= 1024, Y aligned to 16 bytes.
+int launch_linear_steploop16(const TiledArgs &a, int64_t max_step, hipStream_t s) {
+    const int64_t NG = plan_groups(a.B, kSlWaves, kSlNacc, true);
     const int64_t ntiles = (a.T + 63) / 64;
     int64_t nstrips = (256 + ntiles - 1) / ntiles;  // enough strips to give every compute unit a workgroup
     if (nstrips > NG) nstrips = NG;
     if (nstrips < 1) nstrips = 1;
     int64_t gps = (NG + nstrips - 1) / nstrips;
-    const int64_t rows_per_group = kSlWaves * kSlNacc * 16;
-    const int64_t max_gps = 32768 / (4 * rows_per_group);  // the bias table fills what LDS the tile leaves
+    // the fp32 bias of the strip's quads fills what LDS the tile leaves: 4 KiB per two groups, and a strip of gps
+    // groups touches at most gps / 2 + 1 of them
+    const int64_t max_gps = 14;
     if (gps > max_gps) gps = max_gps;
     nstrips = (NG + gps - 1) / gps;
     if (ntiles * nstrips >= ((int64_t)1 << 31)) return BSP_ERR_SHAPE;
-    const size_t lds = kXTileBytes + (size_t)(gps * rows_per_group * 4);
+    const size_t lds = kXTileBytes + (size_t)(gps / 2 + 1) * (4 * kSlWaves * 16 * 4);
     auto go = [&](auto kern, size_t &configured) {
         int st = raise_lds_limit(kern, lds, configured);
         if (st != BSP_OK) return st;

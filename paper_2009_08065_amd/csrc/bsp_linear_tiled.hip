@@ -437,7 +437,7 @@ __global__ __launch_bounds__(WAVES * 64) void linear_tiled_planned_kernel(
     constexpr bool FAST = OUT == kOutStaged8;
     constexpr bool SWAP = OUT == kOutSwap;
     // row-blocks of a wavefront's run: together 64 bytes per token row
-    constexpr int NACC = plan_nacc(NFRAG, false, (OUT == kOutStaged8 || OUT == kOutElements8) ? 8 : 16 * NFRAG);
+    constexpr int NACC = plan_nacc(NFRAG, false, (OUT == kOutStaged8 || OUT == kOutElements8) ? 8 : 0);
     constexpr int nacc_shift = NACC == 4 ? 2 : (NACC == 2 ? 1 : 0);
     // 8 wavefronts: the same bytes in flight for every fragment count, and the X fragments of the next step are read
     // from LDS while this step's MFMAs run (two register sets).  16 wavefronts: a ring of 2 steps and one register
@@ -1031,9 +1031,12 @@ int launch_planned(const TiledArgs &a, hipStream_t s) {
     if (a.R == 16 * NFRAG && (reinterpret_cast<uintptr_t>(a.Y) & 15) == 0) {
         // R = 16 and 32: 16 wavefronts (the plan has 16 streams); R = 64: 8
         constexpr int WAVES = NFRAG <= 2 ? kPlanWavesWide : kPlanWaves;
-        // R = 16: the kernel whose step loop is written in assembly
-        if (NFRAG == 1 && waves == kPlanWavesWide) return launch_linear_steploop16(a, NG, max_step, s);
-        if (waves == WAVES) return launch_planned_1024<DT, NFRAG, kOutSwap, WAVES>(a, ntiles, NG, max_step, s);
+        if constexpr (NFRAG == 1) {  // R = 16: the kernel whose step loop is written in assembly (its plans are paired)
+            if (waves == kPlanWavesWide) return launch_linear_steploop16(a, max_step, s);
+            return BSP_ERR_SHAPE;
+        } else {
+            if (waves == WAVES) return launch_planned_1024<DT, NFRAG, kOutSwap, WAVES>(a, ntiles, NG, max_step, s);
+        }
     }
     if (waves != kPlanWaves) return BSP_ERR_SHAPE;  // (a plan of 16 streams is only consumed by the path above)
     return launch_planned_1024<DT, NFRAG, kOutElements, kPlanWaves>(a, ntiles, NG, max_step, s);

@@ -68,7 +68,7 @@ __global__ __launch_bounds__(kPlanWavesWide * 64) void plan_scan_kernel(const in
                                                                     const int32_t *__restrict__ blk_ptr,
                                                                     int64_t capacity_cols, int32_t B,
                                                                     int32_t NG, int32_t nacc, int32_t nchunks,
-                                                                    int64_t cap_steps,
+                                                                    int32_t paired, int64_t cap_steps,
                                                                     int32_t slack_steps, int32_t *__restrict__ wptr,
                                                                     uint32_t *__restrict__ xoff) {
     __shared__ int totals[kPlanWavesWide];
@@ -81,7 +81,7 @@ __global__ __launch_bounds__(kPlanWavesWide * 64) void plan_scan_kernel(const in
     for (int ebase = 0; ebase < E; ebase += 64) {
         const int e = ebase + lane;
         const int q = e / per_chunk, gi = e % per_chunk;
-        const int64_t b = ((int64_t)(gi / nacc) * waves + w) * nacc + gi % nacc;
+        const int64_t b = plan_block(gi / nacc, w, gi % nacc, waves, nacc, paired != 0);
         int st = 0;
         if (e < E && b < B) {
             if (steps_bq) {
@@ -131,7 +131,7 @@ __global__ __launch_bounds__(kThreads) void plan_fill_kernel(int32_t R, int32_t 
                                                              const uint16_t *__restrict__ vals, int64_t capacity_cols,
                                                              int64_t cap_steps, const int32_t *__restrict__ wptr,
                                                              uint32_t *__restrict__ wfrag, uint32_t *__restrict__ xoff,
-                                                             int32_t cols_cap, int32_t waves) {
+                                                             int32_t cols_cap, int32_t waves, int32_t paired) {
     // columns and canonical positions are below 4096 + 32: 16 bits each; 0xffff marks a pad.  The list of a
     // row-block's kept columns is sized by the launch for the layer's width (cols_cap entries).
     extern __shared__ __attribute__((aligned(16))) uint16_t cols[];
@@ -147,8 +147,10 @@ __global__ __launch_bounds__(kThreads) void plan_fill_kernel(int32_t R, int32_t 
         // one-chunk layers: the single step of an empty block holds zero weights and the LDS offset 0
         if (nchunks == 1 && wave == 0) {
             const int E1 = NG * nacc;
-            const int64_t quad = b / nacc;
-            const int64_t gs0 = wptr[(quad % waves) * (E1 + 1) + (quad / waves) * nacc + b % nacc];
+            int64_t eg;
+            int ew, ei;
+            plan_entry(b, waves, nacc, paired != 0, eg, ew, ei);
+            const int64_t gs0 = wptr[(int64_t)ew * (E1 + 1) + eg * nacc + ei];
             if (gs0 >= 0 && gs0 + 1 <= cap_steps) {
                 for (int f = 0; f < nfrag; ++f)
                     *reinterpret_cast<uint4 *>(wfrag + (gs0 * nfrag + f) * 256 + lane * 4) = make_uint4(0u, 0u, 0u, 0u);
@@ -240,8 +242,10 @@ __global__ __launch_bounds__(kThreads) void plan_fill_kernel(int32_t R, int32_t 
         __syncthreads();
         // per-lane operands of the chunk's steps
         const int E = nchunks * NG * nacc;
-        const int64_t quad = b / nacc;  // quad `quad % waves` of group `quad / waves`
-        const int64_t gs0 = wptr[(quad % waves) * (E + 1) + ((int64_t)q * NG + quad / waves) * nacc + b % nacc];
+        int64_t eg;
+        int ew, ei;
+        plan_entry(b, waves, nacc, paired != 0, eg, ew, ei);
+        const int64_t gs0 = wptr[(int64_t)ew * (E + 1) + ((int64_t)q * NG + eg) * nacc + ei];
         if (gs0 < 0 || gs0 + nsteps > cap_steps) return;
         for (int s = wave; s < nsteps; s += kThreads / 64) {
             const int s1 = 32 * s + 8 * G + qd;
@@ -282,8 +286,8 @@ struct PlanLayout {
 inline PlanLayout plan_layout(int64_t M, int64_t N, int32_t R, int64_t capacity_cols) {
     PlanLayout L;
     const int64_t B = M / R;
-    const int64_t per_group = (int64_t)plan_waves(N, R) * plan_nacc(nfrag_of(R), plan_chunks(N).n > 1, R);
-    L.NG = (B + per_group - 1) / per_group;
+    const bool chunked = plan_chunks(N).n > 1;
+    L.NG = plan_groups(B, plan_waves(N, R), plan_nacc(nfrag_of(R), chunked, R), plan_paired(R, chunked));
     L.steps = (size_t)((capacity_cols + 31) / 32) + (size_t)B * (kPlanMaxChunks - 1) + (size_t)plan_slack_steps();
     // entries per stream <= chunks * (blocks rounded up to whole groups) / streams, groups of at most 32 blocks
     // (16 streams of a one-chunk layer need less than the 8 streams of a chunked one)
@@ -335,14 +339,15 @@ extern "C" int bsp_linear_plan(int vdt, int64_t M, int64_t N, int32_t R, int32_t
     const int32_t nacc = plan_nacc(nf, ch.n > 1, R);
     const int waves = plan_waves(N, R);
     plan_scan_kernel<<<1, waves * 64, 0, s>>>(ch.n > 1 ? steps_bq : nullptr, blk_cnt, blk_ptr, capacity_cols,
-                                                   (int32_t)B, (int32_t)L.NG, nacc, ch.n, (int64_t)L.steps,
+                                                   (int32_t)B, (int32_t)L.NG, nacc, ch.n, plan_paired(R, ch.n > 1) ? 1 : 0,
+                                                   (int64_t)L.steps,
                                                    plan_slack_steps(), wptr, xoff);
     if (capacity_cols > 0 || ch.n == 1) {  // (one-chunk layers: empty row-blocks get their step of zero weights)
         // a row-block keeps at most N columns, padded to the alignment (at most 64)
         const int32_t cols_cap = (int32_t)(N + 64 < kMaxKp ? (N + 64 + 7) / 8 * 8 : kMaxKp);
         plan_fill_kernel<<<dim3((unsigned)B, (unsigned)ch.n), kThreads, (size_t)cols_cap * 2, s>>>(
             R, nf, (int32_t)L.NG, nacc, ch.shift, ch.n, blk_cnt, blk_ptr, col_idx, (const uint16_t *)vals, capacity_cols,
-            (int64_t)L.steps, wptr, wfrag, xoff, cols_cap, waves);
+            (int64_t)L.steps, wptr, wfrag, xoff, cols_cap, waves, plan_paired(R, ch.n > 1) ? 1 : 0);
     }
     return check_launch();
 }
