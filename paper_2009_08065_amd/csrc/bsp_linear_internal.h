@@ -17,7 +17,7 @@ struct TiledArgs {
     const int32_t *blk_ptr;
     const int32_t *col_idx;   // canonical source
     const uint16_t *vals;     // canonical source
-    const int32_t *wptr;      // planned source: [waves][chunks * NG * nacc + 1] first step of (chunk q, block (g * waves + w) * nacc + i) at [w][(q * NG + g) * nacc + i]
+    const int32_t *wptr;      // planned source: [waves][chunks * NG * nacc + 1] first step of (chunk q, block (g * waves + w) * nacc + i) at [w][(g * chunks + q) * nacc + i]
     const void *wfrag;        // planned source: [step][fragment][lane] 16-byte panel fragments
     const uint32_t *xoff;     // planned source: [step][lane] two 16-bit LDS byte offsets
     int64_t plan_steps;       // planned source: steps the fragment / offset regions hold (slack included)
@@ -32,18 +32,25 @@ int launch_linear_tiled(const TiledArgs &args, bool plan, hipStream_t s);
 // The planned kernel for R = 16 and layers of up to 1024 input columns (16-bit floats, a plan of 16 streams, Y
 // aligned to 16 bytes); NG = groups of the plan, max_step = steps the plan holds without its read-ahead slack.
 int launch_linear_steploop16(const TiledArgs &args, int64_t max_step, hipStream_t s);
+// The same for R = 16 and wider layers (up to 4096 input columns), whose plans are cut into chunks of 512 columns.
+int launch_linear_stream16(const TiledArgs &args, int64_t max_step, hipStream_t s);
 // Column chunks of a plan: layers with more than 1024 (padded) input columns are cut into chunks of
 // 1024 columns, the width of X that fits in LDS next to 64 tokens; narrower layers are one chunk.
-constexpr int kPlanMaxChunks = 4;
+// R = 16: chunks of 512 columns, two of which are in LDS at a time -- one being used, one being filled.
+constexpr int kPlanMaxChunks = 8;
 struct PlanChunks {
     int32_t n;      // number of chunks
     int32_t shift;  // column >> shift = chunk
 };
-inline PlanChunks plan_chunks(int64_t N) {
+inline PlanChunks plan_chunks(int64_t N, int32_t R) {
     const int64_t npad = (N + 255) / 256 * 256;
     if (npad <= 1024) return PlanChunks{1, 30};
+    if (R == 16) return PlanChunks{(int32_t)((npad + 511) / 512), 9};
     return PlanChunks{(int32_t)((npad + 1023) / 1024), 10};
 }
+// Chunked plans of R = 16 give every (row-block, chunk) at least one step (of zero weights where the block keeps
+// no column of the chunk), as one-chunk plans give every row-block: the assembly loops never meet an empty run.
+inline bool plan_min_one_step(int32_t R, bool chunked) { return !chunked || R == 16; }
 // A wavefront of the planned kernels works on runs of nacc consecutive row-blocks, so that it can write 64
 // or 128 contiguous bytes per token row: 4 sixteen-row fragments' worth in the column-chunked kernel with 8
 // wavefronts (which holds all their accumulators and writes once, at the end), 2 with 16 wavefronts (R = 16, 32:
@@ -51,6 +58,7 @@ inline PlanChunks plan_chunks(int64_t N) {
 // R = 8 fills half a fragment, so 4 of its row-blocks make 64 bytes.
 constexpr int plan_nacc(int nfrag, bool chunked, int R) {
     if (R == 8) return 4;
+    if (R == 16 && chunked) return 4;  // (8 wavefronts that hold the accumulators of 4 row-blocks each)
     const int frags = (chunked && R != 16 && R != 32) ? 4 : 2;
     return frags / nfrag > 0 ? frags / nfrag : 1;
 }
@@ -59,7 +67,7 @@ constexpr int plan_nacc(int nfrag, bool chunked, int R) {
 // per-wavefront chains of dependent instructions overlap better (measured 10-14 % faster than 8 wavefronts).
 // The other R do not fit (R = 64: four fragments of accumulators; R = 8 and odd sizes: their output paths).
 inline int plan_waves(int64_t N, int32_t R) {
-    (void)N;
+    if (R == 16 && plan_chunks(N, R).n > 1) return kPlanWaves;  // beside them run the wavefronts that copy X in
     return (R == 16 || R == 32) ? kPlanWavesWide : kPlanWaves;
 }
 // Which row-block a plan's entry (group g, wavefront w, place i in the run) stands for, and back.  Plain plans deal

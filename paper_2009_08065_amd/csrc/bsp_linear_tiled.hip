@@ -250,7 +250,7 @@ __global__ __launch_bounds__(1024) void linear_tiled_canonical_kernel(
 // run w of the group belongs to wavefront w (waves = 8 or 16, see plan_waves).  The plan stores the steps in
 // exactly the order a wavefront walks them (its run of group 0 block by block, then group 1, ...; chunk-major
 // for layers cut into column chunks), so a wavefront streams its operands with constant address increments.
-// wptr[w][(q * NG + g) * NACC + i] = first step of block (g * waves + w) * NACC + i inside chunk q.
+// wptr[w][(g * chunks + q) * NACC + i] = first step of block (g * waves + w) * NACC + i inside chunk q.
 
 constexpr int kOutPitch = 144;  // bytes per token row of a wavefront's output staging (128 + pad)
 
@@ -848,7 +848,7 @@ __global__ __launch_bounds__(WAVES * 64) void linear_tiled_chunked_kernel(
 
     for (int q = 0; q < nchunks; ++q) {
         // the wavefront's step range of this chunk and where each of its row-blocks ends
-        const int32_t *ent = my + ((int64_t)q * NG + g) * NACC;
+        const int32_t *ent = my + ((int64_t)g * nchunks + q) * NACC;
         int gs = __builtin_amdgcn_readfirstlane(ent[0]);
         int ends[NACC];
 #pragma unroll
@@ -1003,8 +1003,11 @@ int launch_planned(const TiledArgs &a, hipStream_t s) {
     const int64_t max_step = a.plan_steps - plan_slack_steps();
     if (max_step < 0 || max_step > INT32_MAX) return BSP_ERR_CAPACITY;
     if (a.npad > 1024) {
+        if constexpr (NFRAG == 1) {  // R = 16: the kernel that streams X through LDS beside the products
+            if (a.R == 16) return launch_linear_stream16(a, max_step, s);
+        }
         if (ntiles * NG >= ((int64_t)1 << 31)) return BSP_ERR_SHAPE;
-        const PlanChunks ch = plan_chunks(a.N);
+        const PlanChunks ch = plan_chunks(a.N, a.R);
         auto go = [&](auto kern, size_t &configured, int w) {
             int st = raise_lds_limit(kern, lds, configured);
             if (st != BSP_OK) return st;

@@ -13,8 +13,9 @@
 // row-blocks (quad w of every group of `waves` quads), so the plan keeps the steps of wavefront w
 // contiguous, stream after stream, in the order it walks them: chunk by chunk (layers of more than
 // 1024 input columns are cut into chunks of 1024), group by group, block by block.
-// wptr[w][(q * NG + g) * nacc + i] is the step where block (g * waves + w) * nacc + i starts in
-// chunk q; the last entry of a row is where stream w ends.
+// wptr[w][(g * chunks + q) * nacc + i] is the step where block (g * waves + w) * nacc + i starts in
+// chunk q (a stream holds a group's runs chunk after chunk, then the next group's); the last entry of a row is
+// where stream w ends.
 //
 // Buffer layout (bytes): wptr int32 [waves][chunks * NG * nacc + 1], padded to 256 | fragments
 // [steps][nfrag][64] lanes x 16 bytes (a lane's 8 values of its row) | offsets uint32 [steps][16] (one word per 4 lanes: the lanes
@@ -42,7 +43,8 @@ __global__ __launch_bounds__(kThreads) void plan_count_kernel(const int32_t *__r
                                                               const int32_t *__restrict__ blk_ptr,
                                                               const int32_t *__restrict__ col_idx,
                                                               int64_t capacity_cols, int32_t chunk_shift,
-                                                              int32_t nchunks, int32_t *__restrict__ steps_bq) {
+                                                              int32_t nchunks, int32_t min_one,
+                                                              int32_t *__restrict__ steps_bq) {
     __shared__ int cnt[kPlanMaxChunks];
     const int64_t b = blockIdx.x;
     const int base = blk_ptr[b];
@@ -57,7 +59,11 @@ __global__ __launch_bounds__(kThreads) void plan_count_kernel(const int32_t *__r
             if (q >= 0 && q < nchunks) atomicAdd(&cnt[q], 1);
         }
     __syncthreads();
-    if (threadIdx.x < kPlanMaxChunks) steps_bq[b * kPlanMaxChunks + threadIdx.x] = (cnt[threadIdx.x] + 31) >> 5;
+    if (threadIdx.x < kPlanMaxChunks) {
+        int st = (cnt[threadIdx.x] + 31) >> 5;
+        if (min_one && (int)threadIdx.x < nchunks && st == 0) st = 1;  // (also for malformed blocks: zero weights)
+        steps_bq[b * kPlanMaxChunks + threadIdx.x] = st;
+    }
 }
 
 // One workgroup with a wavefront per stream of the plan: wavefront w scans the step counts of its blocks in
@@ -68,8 +74,10 @@ __global__ __launch_bounds__(kPlanWavesWide * 64) void plan_scan_kernel(const in
                                                                     const int32_t *__restrict__ blk_ptr,
                                                                     int64_t capacity_cols, int32_t B,
                                                                     int32_t NG, int32_t nacc, int32_t nchunks,
-                                                                    int32_t paired, int64_t cap_steps,
+                                                                    int32_t paired, int32_t min_one, int32_t nfrag,
+                                                                    int64_t cap_steps,
                                                                     int32_t slack_steps, int32_t *__restrict__ wptr,
+                                                                    uint32_t *__restrict__ wfrag,
                                                                     uint32_t *__restrict__ xoff) {
     __shared__ int totals[kPlanWavesWide];
     const int waves = blockDim.x >> 6;  // streams of this plan
@@ -80,9 +88,13 @@ __global__ __launch_bounds__(kPlanWavesWide * 64) void plan_scan_kernel(const in
     int carry = 0;
     for (int ebase = 0; ebase < E; ebase += 64) {
         const int e = ebase + lane;
-        const int q = e / per_chunk, gi = e % per_chunk;
-        const int64_t b = plan_block(gi / nacc, w, gi % nacc, waves, nacc, paired != 0);
+        // stream order: group by group, inside a group chunk by chunk, inside a chunk the run's blocks
+        const int eg = e / (nchunks * nacc), q = (e / nacc) % nchunks;
+        const int64_t b = plan_block(eg, w, e % nacc, waves, nacc, paired != 0);
         int st = 0;
+        // (chunked plans that give every run a step give one to the runs past the layer's last row-block too, so
+        // that all streams of a group have the same shape; their step of zero weights is written below)
+        if (e < E && b >= B && steps_bq && min_one) st = 1;
         if (e < E && b < B) {
             if (steps_bq) {
                 st = steps_bq[b * kPlanMaxChunks + q];
@@ -113,6 +125,18 @@ __global__ __launch_bounds__(kPlanWavesWide * 64) void plan_scan_kernel(const in
     for (int k = 0; k < w; ++k) wbase += totals[k];
     __syncthreads();  // the stores above are visible to the whole workgroup now
     for (int e = lane; e <= E; e += 64) mine[e] += wbase;
+    if (steps_bq && min_one) {
+        __syncthreads();
+        for (int e = 0; e < E; ++e) {  // uniform over the wavefront
+            const int eg = e / (nchunks * nacc);
+            if (plan_block(eg, w, e % nacc, waves, nacc, paired != 0) < B) continue;
+            const int64_t gs = mine[e];
+            if (gs < 0 || gs + 1 > cap_steps) continue;
+            for (int f = 0; f < nfrag; ++f)
+                *reinterpret_cast<uint4 *>(wfrag + (gs * nfrag + f) * 256 + lane * 4) = make_uint4(0u, 0u, 0u, 0u);
+            if (lane < 16) xoff[gs * 16 + lane] = 0u;
+        }
+    }
     // the layer kernel reads a few steps past the end of the last stream: give those steps the
     // LDS offset 0 (their values are never used, but the addresses must be valid)
     if (w == waves - 1) {
@@ -131,7 +155,8 @@ __global__ __launch_bounds__(kThreads) void plan_fill_kernel(int32_t R, int32_t 
                                                              const uint16_t *__restrict__ vals, int64_t capacity_cols,
                                                              int64_t cap_steps, const int32_t *__restrict__ wptr,
                                                              uint32_t *__restrict__ wfrag, uint32_t *__restrict__ xoff,
-                                                             int32_t cols_cap, int32_t waves, int32_t paired) {
+                                                             int32_t cols_cap, int32_t waves, int32_t paired,
+                                                             int32_t min_one) {
     // columns and canonical positions are below 4096 + 32: 16 bits each; 0xffff marks a pad.  The list of a
     // row-block's kept columns is sized by the launch for the layer's width (cols_cap entries).
     extern __shared__ __attribute__((aligned(16))) uint16_t cols[];
@@ -143,20 +168,22 @@ __global__ __launch_bounds__(kThreads) void plan_fill_kernel(int32_t R, int32_t 
     const int kb = blk_cnt[b];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l16 = lane & 15, G = lane >> 4, qd = (lane >> 2) & 3, p = lane & 3;
-    if (kp <= 0 || kb <= 0 || kp > cols_cap || kb > kp || base < 0 || (int64_t)base + kp > capacity_cols) {
-        // one-chunk layers: the single step of an empty block holds zero weights and the LDS offset 0
-        if (nchunks == 1 && wave == 0) {
-            const int E1 = NG * nacc;
-            int64_t eg;
-            int ew, ei;
-            plan_entry(b, waves, nacc, paired != 0, eg, ew, ei);
-            const int64_t gs0 = wptr[(int64_t)ew * (E1 + 1) + eg * nacc + ei];
-            if (gs0 >= 0 && gs0 + 1 <= cap_steps) {
-                for (int f = 0; f < nfrag; ++f)
-                    *reinterpret_cast<uint4 *>(wfrag + (gs0 * nfrag + f) * 256 + lane * 4) = make_uint4(0u, 0u, 0u, 0u);
-                if (lane < 16) xoff[gs0 * 16 + lane] = 0u;
-            }
+    // the single step of an empty (row-block, chunk) of a plan that gives each of them one: zero weights, LDS offset 0
+    auto zero_step = [&]() {
+        if (!min_one || wave != 0) return;
+        const int E1 = nchunks * NG * nacc;
+        int64_t eg;
+        int ew, ei;
+        plan_entry(b, waves, nacc, paired != 0, eg, ew, ei);
+        const int64_t gs0 = wptr[(int64_t)ew * (E1 + 1) + (eg * nchunks + blockIdx.y) * nacc + ei];
+        if (gs0 >= 0 && gs0 + 1 <= cap_steps) {
+            for (int f = 0; f < nfrag; ++f)
+                *reinterpret_cast<uint4 *>(wfrag + (gs0 * nfrag + f) * 256 + lane * 4) = make_uint4(0u, 0u, 0u, 0u);
+            if (lane < 16) xoff[gs0 * 16 + lane] = 0u;
         }
+    };
+    if (kp <= 0 || kb <= 0 || kp > cols_cap || kb > kp || base < 0 || (int64_t)base + kp > capacity_cols) {
+        zero_step();
         return;
     }
     // the block's kept columns, fetched once with coalesced loads, and their count per chunk
@@ -175,8 +202,10 @@ __global__ __launch_bounds__(kThreads) void plan_fill_kernel(int32_t R, int32_t 
         int lo = 0;  // canonical position of the chunk's first kept column (columns ascend, so chunks are runs)
         for (int k = 0; k < q; ++k) lo += s_cnt[k];
         const int cq = s_cnt[q];
-        if (cq <= 0) return;    // uniform
-        if (cq > 1024) return;  // malformed storage (duplicate columns): nothing is written
+        if (cq <= 0 || cq > 1024) {  // uniform; (more than 1024: malformed storage, duplicate columns)
+            zero_step();
+            return;
+        }
         const int nsteps = (cq + 31) >> 5;
         const int S = nsteps * 4;  // sets of 8 columns
         const int col0 = q << chunk_shift;
@@ -245,12 +274,14 @@ __global__ __launch_bounds__(kThreads) void plan_fill_kernel(int32_t R, int32_t 
         int64_t eg;
         int ew, ei;
         plan_entry(b, waves, nacc, paired != 0, eg, ew, ei);
-        const int64_t gs0 = wptr[(int64_t)ew * (E + 1) + ((int64_t)q * NG + eg) * nacc + ei];
+        const int64_t gs0 = wptr[(int64_t)ew * (E + 1) + (eg * nchunks + q) * nacc + ei];
         if (gs0 < 0 || gs0 + nsteps > cap_steps) return;
         for (int s = wave; s < nsteps; s += kThreads / 64) {
             const int s1 = 32 * s + 8 * G + qd;
-            const uint32_t o1 = lds_col_offset4((uint32_t)slotcol[s1], (uint32_t)p);
-            const uint32_t o2 = lds_col_offset4((uint32_t)slotcol[s1 + 4], (uint32_t)p);
+            // (chunks of 512 columns alternate between the two halves of the tile)
+            const uint32_t half = chunk_shift == 9 ? (uint32_t)(q & 1) * 512u : 0u;
+            const uint32_t o1 = lds_col_offset4(half + (uint32_t)slotcol[s1], (uint32_t)p);
+            const uint32_t o2 = lds_col_offset4(half + (uint32_t)slotcol[s1 + 4], (uint32_t)p);
             // offsets are multiples of 8 bytes; the 4 lanes of a column (token quads p = 0 .. 3) differ by
             // p in both halves (the swizzle is an exclusive-or on those bits), so p = 0 stands for all four
             if (p == 0) xoff[(gs0 + s) * 16 + (lane >> 2)] = (o1 >> 3) | ((o2 >> 3) << 16);
@@ -286,9 +317,11 @@ struct PlanLayout {
 inline PlanLayout plan_layout(int64_t M, int64_t N, int32_t R, int64_t capacity_cols) {
     PlanLayout L;
     const int64_t B = M / R;
-    const bool chunked = plan_chunks(N).n > 1;
+    const bool chunked = plan_chunks(N, R).n > 1;
     L.NG = plan_groups(B, plan_waves(N, R), plan_nacc(nfrag_of(R), chunked, R), plan_paired(R, chunked));
-    L.steps = (size_t)((capacity_cols + 31) / 32) + (size_t)B * (kPlanMaxChunks - 1) + (size_t)plan_slack_steps();
+    // (+ a step per run of a last group that reaches past the layer, for the plans that give every run one)
+    L.steps = (size_t)((capacity_cols + 31) / 32) + (size_t)B * (kPlanMaxChunks - 1) +
+              (size_t)kPlanWaves * 4 * kPlanMaxChunks + (size_t)plan_slack_steps();
     // entries per stream <= chunks * (blocks rounded up to whole groups) / streams, groups of at most 32 blocks
     // (16 streams of a one-chunk layer need less than the 8 streams of a chunked one)
     L.wptr_bytes = ((size_t)kPlanWavesWide * (size_t)(kPlanMaxChunks * ((B + 31) / 32 * 4) + 1) * sizeof(int32_t) + 255) /
@@ -328,26 +361,27 @@ extern "C" int bsp_linear_plan(int vdt, int64_t M, int64_t N, int32_t R, int32_t
     uint32_t *wfrag = (uint32_t *)((uint8_t *)plan + L.wptr_bytes);
     uint32_t *xoff = (uint32_t *)((uint8_t *)plan + L.wptr_bytes + L.wfrag_bytes);
     hipStream_t s = (hipStream_t)stream;
-    const PlanChunks ch = plan_chunks(N);
+    const PlanChunks ch = plan_chunks(N, R);
+    const int32_t min_one = plan_min_one_step(R, ch.n > 1) ? 1 : 0;
     // step counts per (row-block, chunk) are parked at the start of the offsets region: the scan has
     // consumed them before the fill kernel overwrites that region
     int32_t *steps_bq = (int32_t *)xoff;
     if ((size_t)B * kPlanMaxChunks * sizeof(int32_t) > L.xoff_bytes) return BSP_ERR_CAPACITY;
     if (ch.n > 1)  // a layer of one chunk needs no count: its steps per row-block follow from blk_cnt
         plan_count_kernel<<<(unsigned)B, kThreads, 0, s>>>(blk_cnt, blk_ptr, col_idx, capacity_cols, ch.shift, ch.n,
-                                                           steps_bq);
+                                                           min_one, steps_bq);
     const int32_t nacc = plan_nacc(nf, ch.n > 1, R);
     const int waves = plan_waves(N, R);
     plan_scan_kernel<<<1, waves * 64, 0, s>>>(ch.n > 1 ? steps_bq : nullptr, blk_cnt, blk_ptr, capacity_cols,
                                                    (int32_t)B, (int32_t)L.NG, nacc, ch.n, plan_paired(R, ch.n > 1) ? 1 : 0,
-                                                   (int64_t)L.steps,
-                                                   plan_slack_steps(), wptr, xoff);
-    if (capacity_cols > 0 || ch.n == 1) {  // (one-chunk layers: empty row-blocks get their step of zero weights)
+                                                   min_one, nf, (int64_t)L.steps,
+                                                   plan_slack_steps(), wptr, wfrag, xoff);
+    if (capacity_cols > 0 || min_one) {  // (empty row-blocks may get a step of zero weights)
         // a row-block keeps at most N columns, padded to the alignment (at most 64)
         const int32_t cols_cap = (int32_t)(N + 64 < kMaxKp ? (N + 64 + 7) / 8 * 8 : kMaxKp);
         plan_fill_kernel<<<dim3((unsigned)B, (unsigned)ch.n), kThreads, (size_t)cols_cap * 2, s>>>(
             R, nf, (int32_t)L.NG, nacc, ch.shift, ch.n, blk_cnt, blk_ptr, col_idx, (const uint16_t *)vals, capacity_cols,
-            (int64_t)L.steps, wptr, wfrag, xoff, cols_cap, waves, plan_paired(R, ch.n > 1) ? 1 : 0);
+            (int64_t)L.steps, wptr, wfrag, xoff, cols_cap, waves, plan_paired(R, ch.n > 1) ? 1 : 0, min_one);
     }
     return check_launch();
 }
