@@ -43,8 +43,7 @@ __global__ __launch_bounds__(kThreads) void plan_count_kernel(const int32_t *__r
                                                               const int32_t *__restrict__ blk_ptr,
                                                               const int32_t *__restrict__ col_idx,
                                                               int64_t capacity_cols, int32_t chunk_shift,
-                                                              int32_t nchunks, int32_t min_one,
-                                                              int32_t *__restrict__ steps_bq) {
+                                                              int32_t nchunks, int32_t *__restrict__ steps_bq) {
     __shared__ int cnt[kPlanMaxChunks];
     const int64_t b = blockIdx.x;
     const int base = blk_ptr[b];
@@ -60,9 +59,7 @@ __global__ __launch_bounds__(kThreads) void plan_count_kernel(const int32_t *__r
         }
     __syncthreads();
     if (threadIdx.x < kPlanMaxChunks) {
-        int st = (cnt[threadIdx.x] + 31) >> 5;
-        if (min_one && (int)threadIdx.x < nchunks && st == 0) st = 1;  // (also for malformed blocks: zero weights)
-        steps_bq[b * kPlanMaxChunks + threadIdx.x] = st;
+        steps_bq[b * kPlanMaxChunks + threadIdx.x] = (cnt[threadIdx.x] + 31) >> 5;
     }
 }
 
@@ -75,7 +72,7 @@ __global__ __launch_bounds__(kPlanWavesWide * 64) void plan_scan_kernel(const in
                                                                     int64_t capacity_cols, int32_t B,
                                                                     int32_t NG, int32_t nacc, int32_t nchunks,
                                                                     int32_t paired, int32_t min_one, int32_t nfrag,
-                                                                    int64_t cap_steps,
+                                                                    int32_t virt, int64_t cap_steps,
                                                                     int32_t slack_steps, int32_t *__restrict__ wptr,
                                                                     uint32_t *__restrict__ wfrag,
                                                                     uint32_t *__restrict__ xoff) {
@@ -96,16 +93,20 @@ __global__ __launch_bounds__(kPlanWavesWide * 64) void plan_scan_kernel(const in
         // that all streams of a group have the same shape; their step of zero weights is written below)
         if (e < E && b >= B && steps_bq && min_one) st = 1;
         if (e < E && b < B) {
-            if (steps_bq) {
-                st = steps_bq[b * kPlanMaxChunks + q];
-            } else {  // the same validity test as the count and fill kernels make
-                const int base = blk_ptr[b], kp = blk_ptr[b + 1] - base, kb = blk_cnt[b];
+            // steps of a stored row-block (zero for an empty or malformed one: the same validity test as the count
+            // and fill kernels make)
+            auto stored_steps = [&](int64_t sb) {
+                if (steps_bq) return steps_bq[sb * kPlanMaxChunks + q];
+                const int base = blk_ptr[sb], kp = blk_ptr[sb + 1] - base, kb = blk_cnt[sb];
                 const bool ok = kp > 0 && kp <= kMaxKp && kb >= 0 && kb <= kp && base >= 0 &&
                                 (int64_t)base + kp <= capacity_cols;
-                // a layer of one chunk gives every row-block at least one step: an empty (or malformed) block gets
-                // a step of zero weights, so that a wavefront's step loop never meets a block without steps
-                st = ok && kb > 0 ? (kb + 31) >> 5 : 1;
-            }
+                return ok && kb > 0 ? (kb + 31) >> 5 : 0;
+            };
+            // (virt: B counts blocks of 16 rows, each made of the stored row-blocks 2 b and 2 b + 1)
+            st = virt ? stored_steps(2 * b) + stored_steps(2 * b + 1) : stored_steps(b);
+            // plans that give every run a step: an empty (or malformed) block gets a step of zero weights, so that
+            // a wavefront's step loop never meets a block without steps
+            if (min_one && st == 0) st = 1;
         }
         int incl = st;
 #pragma unroll
@@ -156,25 +157,43 @@ __global__ __launch_bounds__(kThreads) void plan_fill_kernel(int32_t R, int32_t 
                                                              int64_t cap_steps, const int32_t *__restrict__ wptr,
                                                              uint32_t *__restrict__ wfrag, uint32_t *__restrict__ xoff,
                                                              int32_t cols_cap, int32_t waves, int32_t paired,
-                                                             int32_t min_one) {
+                                                             int32_t min_one, int32_t virt) {
     // columns and canonical positions are below 4096 + 32: 16 bits each; 0xffff marks a pad.  The list of a
     // row-block's kept columns is sized by the launch for the layer's width (cols_cap entries).
     extern __shared__ __attribute__((aligned(16))) uint16_t cols[];
     __shared__ uint16_t slotcol[kMaxChunk], slotsrc[kMaxChunk], ovfcol[kMaxChunk], ovfsrc[kMaxChunk];
-    __shared__ int s_filled[8], s_hp[9], s_novf, s_cnt[kPlanMaxChunks];
-    const int64_t b = blockIdx.x;
+    __shared__ int s_filled[8], s_hp[9], s_novf, s_cnt[kPlanMaxChunks], s_other;
+    const int64_t b = blockIdx.x;  // the stored row-block
     const int base = blk_ptr[b];
     const int kp = blk_ptr[b + 1] - base;
     const int kb = blk_cnt[b];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l16 = lane & 15, G = lane >> 4, qd = (lane >> 2) & 3, p = lane & 3;
+    // virt: the plan's block pb = b / 2 has 16 rows; this stored block of 8 fills its upper (even b) or lower fragment
+    // rows, and its steps follow (odd b) the steps of its partner inside the chunk
+    const int64_t pb = virt ? b >> 1 : b;
+    if (threadIdx.x == 0) s_other = 0;
+    __syncthreads();
+    if (virt) {  // kept columns of the partner inside this chunk (zero for a malformed partner)
+        const int64_t ob = b ^ 1;
+        const int obase = blk_ptr[ob], okp = blk_ptr[ob + 1] - obase, okb = blk_cnt[ob];
+        if (okp > 0 && okb > 0 && okp <= cols_cap && okb <= okp && obase >= 0 && (int64_t)obase + okp <= capacity_cols) {
+            int n = 0;
+            for (int i = threadIdx.x; i < okb; i += kThreads) n += ((col_idx[obase + i] >> chunk_shift) == (int)blockIdx.y) ? 1 : 0;
+            if (n) atomicAdd(&s_other, n);
+        }
+        __syncthreads();
+    }
+    const int other_steps = (s_other + 31) >> 5;
     // the single step of an empty (row-block, chunk) of a plan that gives each of them one: zero weights, LDS offset 0
+    // (virt: written by the even partner when both are empty)
     auto zero_step = [&]() {
         if (!min_one || wave != 0) return;
+        if (virt && ((b & 1) || other_steps > 0)) return;
         const int E1 = nchunks * NG * nacc;
         int64_t eg;
         int ew, ei;
-        plan_entry(b, waves, nacc, paired != 0, eg, ew, ei);
+        plan_entry(pb, waves, nacc, paired != 0, eg, ew, ei);
         const int64_t gs0 = wptr[(int64_t)ew * (E1 + 1) + (eg * nchunks + blockIdx.y) * nacc + ei];
         if (gs0 >= 0 && gs0 + 1 <= cap_steps) {
             for (int f = 0; f < nfrag; ++f)
@@ -273,9 +292,10 @@ __global__ __launch_bounds__(kThreads) void plan_fill_kernel(int32_t R, int32_t 
         const int E = nchunks * NG * nacc;
         int64_t eg;
         int ew, ei;
-        plan_entry(b, waves, nacc, paired != 0, eg, ew, ei);
-        const int64_t gs0 = wptr[(int64_t)ew * (E + 1) + (eg * nchunks + q) * nacc + ei];
+        plan_entry(pb, waves, nacc, paired != 0, eg, ew, ei);
+        const int64_t gs0 = wptr[(int64_t)ew * (E + 1) + (eg * nchunks + q) * nacc + ei] + ((virt && (b & 1)) ? other_steps : 0);
         if (gs0 < 0 || gs0 + nsteps > cap_steps) return;
+        const int row0 = (virt && (b & 1)) ? 8 : 0;  // fragment row of the stored block's first row
         for (int s = wave; s < nsteps; s += kThreads / 64) {
             const int s1 = 32 * s + 8 * G + qd;
             // (chunks of 512 columns alternate between the two halves of the tile)
@@ -286,9 +306,9 @@ __global__ __launch_bounds__(kThreads) void plan_fill_kernel(int32_t R, int32_t 
             // p in both halves (the swizzle is an exclusive-or on those bits), so p = 0 stands for all four
             if (p == 0) xoff[(gs0 + s) * 16 + (lane >> 2)] = (o1 >> 3) | ((o2 >> 3) << 16);
             for (int f = 0; f < nfrag; ++f) {
-                const int r = f * 16 + l16;
+                const int r = f * 16 + l16 - row0;
                 uint32_t w[4] = {0u, 0u, 0u, 0u};
-                if (r < R) {
+                if (r >= 0 && r < R) {
                     const uint16_t *row = vals + (int64_t)R * base + (int64_t)r * kp;
 #pragma unroll
                     for (int i = 0; i < 8; ++i) {
@@ -316,9 +336,10 @@ struct PlanLayout {
 // depend on N; NG is the number of groups for the grouping the layer's width selects.
 inline PlanLayout plan_layout(int64_t M, int64_t N, int32_t R, int64_t capacity_cols) {
     PlanLayout L;
-    const int64_t B = M / R;
-    const bool chunked = plan_chunks(N, R).n > 1;
-    L.NG = plan_groups(B, plan_waves(N, R), plan_nacc(nfrag_of(R), chunked, R), plan_paired(R, chunked));
+    const int64_t B = M / R;  // stored row-blocks (the sizes below follow them)
+    const int32_t Re = plan_virtual16(R, M) ? 16 : R;  // block height the plan is laid out for
+    const bool chunked = plan_chunks(N, Re).n > 1;
+    L.NG = plan_groups(M / Re, plan_waves(N, Re), plan_nacc(nfrag_of(Re), chunked, Re), plan_paired(Re, chunked));
     // (+ a step per run of a last group that reaches past the layer, for the plans that give every run one)
     L.steps = (size_t)((capacity_cols + 31) / 32) + (size_t)B * (kPlanMaxChunks - 1) +
               (size_t)kPlanWaves * 4 * kPlanMaxChunks + (size_t)plan_slack_steps();
@@ -355,33 +376,37 @@ extern "C" int bsp_linear_plan(int vdt, int64_t M, int64_t N, int32_t R, int32_t
     if (capacity_cols > 0 && (!col_idx || !vals)) return BSP_ERR_NULL;
     const PlanLayout L = plan_layout(M, N, R, capacity_cols);
     if (plan_bytes < L.total() || !aligned(plan, 16)) return BSP_ERR_CAPACITY;
-    const int64_t B = M / R;
-    const int nf = nfrag_of(R);
+    const bool virt = plan_virtual16(R, M);
+    const int32_t Re = virt ? 16 : R;   // block height of the plan
+    const int64_t Bs = M / R;           // stored row-blocks
+    const int64_t B = M / Re;           // the plan's row-blocks
+    const int nf = nfrag_of(Re);
     int32_t *wptr = (int32_t *)plan;
     uint32_t *wfrag = (uint32_t *)((uint8_t *)plan + L.wptr_bytes);
     uint32_t *xoff = (uint32_t *)((uint8_t *)plan + L.wptr_bytes + L.wfrag_bytes);
     hipStream_t s = (hipStream_t)stream;
-    const PlanChunks ch = plan_chunks(N, R);
-    const int32_t min_one = plan_min_one_step(R, ch.n > 1) ? 1 : 0;
+    const PlanChunks ch = plan_chunks(N, Re);
+    const int32_t min_one = plan_min_one_step(Re, ch.n > 1) ? 1 : 0;
+    const int32_t paired = plan_paired(Re, ch.n > 1) ? 1 : 0;
     // step counts per (row-block, chunk) are parked at the start of the offsets region: the scan has
     // consumed them before the fill kernel overwrites that region
     int32_t *steps_bq = (int32_t *)xoff;
-    if ((size_t)B * kPlanMaxChunks * sizeof(int32_t) > L.xoff_bytes) return BSP_ERR_CAPACITY;
+    if ((size_t)Bs * kPlanMaxChunks * sizeof(int32_t) > L.xoff_bytes) return BSP_ERR_CAPACITY;
     if (ch.n > 1)  // a layer of one chunk needs no count: its steps per row-block follow from blk_cnt
-        plan_count_kernel<<<(unsigned)B, kThreads, 0, s>>>(blk_cnt, blk_ptr, col_idx, capacity_cols, ch.shift, ch.n,
-                                                           min_one, steps_bq);
-    const int32_t nacc = plan_nacc(nf, ch.n > 1, R);
-    const int waves = plan_waves(N, R);
+        plan_count_kernel<<<(unsigned)Bs, kThreads, 0, s>>>(blk_cnt, blk_ptr, col_idx, capacity_cols, ch.shift, ch.n,
+                                                            steps_bq);
+    const int32_t nacc = plan_nacc(nf, ch.n > 1, Re);
+    const int waves = plan_waves(N, Re);
     plan_scan_kernel<<<1, waves * 64, 0, s>>>(ch.n > 1 ? steps_bq : nullptr, blk_cnt, blk_ptr, capacity_cols,
-                                                   (int32_t)B, (int32_t)L.NG, nacc, ch.n, plan_paired(R, ch.n > 1) ? 1 : 0,
-                                                   min_one, nf, (int64_t)L.steps,
-                                                   plan_slack_steps(), wptr, wfrag, xoff);
+                                                   (int32_t)B, (int32_t)L.NG, nacc, ch.n, paired, min_one, nf,
+                                                   virt ? 1 : 0, (int64_t)L.steps, plan_slack_steps(), wptr, wfrag,
+                                                   xoff);
     if (capacity_cols > 0 || min_one) {  // (empty row-blocks may get a step of zero weights)
         // a row-block keeps at most N columns, padded to the alignment (at most 64)
         const int32_t cols_cap = (int32_t)(N + 64 < kMaxKp ? (N + 64 + 7) / 8 * 8 : kMaxKp);
-        plan_fill_kernel<<<dim3((unsigned)B, (unsigned)ch.n), kThreads, (size_t)cols_cap * 2, s>>>(
+        plan_fill_kernel<<<dim3((unsigned)Bs, (unsigned)ch.n), kThreads, (size_t)cols_cap * 2, s>>>(
             R, nf, (int32_t)L.NG, nacc, ch.shift, ch.n, blk_cnt, blk_ptr, col_idx, (const uint16_t *)vals, capacity_cols,
-            (int64_t)L.steps, wptr, wfrag, xoff, cols_cap, waves, plan_paired(R, ch.n > 1) ? 1 : 0, min_one);
+            (int64_t)L.steps, wptr, wfrag, xoff, cols_cap, waves, paired, min_one, virt ? 1 : 0);
     }
     return check_launch();
 }
@@ -398,7 +423,9 @@ extern "C" int bsp_linear_planned(const void *X, int xdt, int64_t T, int64_t M, 
     TiledArgs a{};
     a.xdt = xdt;
     a.X = (const uint16_t *)X;
-    a.T = T; a.M = M; a.N = N; a.B = M / R; a.R = R;
+    // (row-blocks of 8 rows in a layer of even block count: the plan is the one of blocks of 16 rows)
+    const int32_t Re = plan_virtual16(R, M) ? 16 : R;
+    a.T = T; a.M = M; a.N = N; a.B = M / Re; a.R = Re;
     a.wptr = (const int32_t *)plan;
     a.wfrag = (const uint8_t *)plan + L.wptr_bytes;
     a.xoff = (const uint32_t *)((const uint8_t *)plan + L.wptr_bytes + L.wfrag_bytes);
