@@ -53,6 +53,9 @@ typedef enum { BSP_ALPHA_SQNORM = 0, BSP_ALPHA_NORM = 1 } bsp_alpha_mode;
  * row-block), or all B*N groups together (one matrix, or several matrices with equal R
  * whose group arrays lie end to end). */
 typedef enum { BSP_SCOPE_BLOCK = 0, BSP_SCOPE_MATRIX = 1 } bsp_scope;
+/* What a layer does to its sums before it rounds them (bsp_linear_planned_fused):
+ * BSP_ACT_GELU  y = 0.5 y (1 + erf(y / sqrt 2)), the exact form (BERT's) */
+typedef enum { BSP_ACT_NONE = 0, BSP_ACT_GELU = 1 } bsp_activation;
 
 /* ---- group norms and reweighting factors (Sec. 3.2, Eq. 3; Alg. 1 norm step) ---------
  * For every group: sumsq = sum_r W[bR+r, j]^2 accumulated in fp32 with one fused
@@ -247,6 +250,21 @@ int bsp_linear_plan(int vdt, int64_t M, int64_t N, int32_t R, int32_t k_align, c
                     void *plan, size_t plan_bytes, void *stream);
 int bsp_linear_planned(const void *X, int xdt, int64_t T, int64_t M, int64_t N, int32_t R, int32_t k_align,
                        const void *plan, int64_t capacity_cols, const void *bias, void *Y, void *stream);
+
+/* ---- the layer with its epilogue: Sec. 4.4 (what a deployed layer fuses), Sec. 4.2 (the networks) --------
+ * Y = round(act(X Wp^T + bias) + residual): the Transformer blocks the paper prunes follow the FFN up-projection
+ * with GELU and the attention-output and FFN down-projections with a residual addition; done inside the layer
+ * kernel, on the fp32 sums and before the one rounding, either saves a pass over Y (one read and one write of
+ * T x M values; a residual: two reads and a write).
+ * Arguments as bsp_linear_planned, plus: act a bsp_activation; residual: device pointer [T, M] row-major of the
+ * type of X, 8-byte aligned, or NULL.  Fused are: the activation for row-blocks of 16 rows (and of 8 rows when
+ * M % 16 == 0), any planned width; the residual for the layers whose kernel writes its output once, at its end:
+ * R = 16 (or 8, M % 16 == 0) and either more than 1024 input columns or more than 512 input columns and at most
+ * 64 sixteen-row blocks (M <= 1024).  Any other request returns BSP_ERR_SHAPE and writes nothing: the caller runs
+ * bsp_linear_planned and its own element-wise pass. */
+int bsp_linear_planned_fused(const void *X, int xdt, int64_t T, int64_t M, int64_t N, int32_t R, int32_t k_align,
+                             const void *plan, int64_t capacity_cols, const void *bias, int act,
+                             const void *residual, void *Y, void *stream);
 
 /* ---- helpers (host only) -------------------------------------------------------------- */
 /* dense parameters / kept parameters = M*N / (R * kept_cols_total) (Sec. 4.4: 1.428x <=> 30 % sparsity) */

@@ -76,6 +76,7 @@ def lib():
     L.bsp_linear_plan_bytes.restype = sz
     L.bsp_linear_plan.argtypes = [C.c_int, i64, i64, i32, i32, vp, vp, vp, vp, i64, vp, sz, vp]
     L.bsp_linear_planned.argtypes = [vp, C.c_int, i64, i64, i64, i32, i32, vp, i64, vp, vp, vp]
+    L.bsp_linear_planned_fused.argtypes = [vp, C.c_int, i64, i64, i64, i32, i32, vp, i64, vp, C.c_int, vp, vp, vp]
     L.bsp_compression_rate.argtypes = [i64, i64, i32, i64]
     L.bsp_compression_rate.restype = C.c_double
     L.bsp_status_string.argtypes = [C.c_int]
@@ -83,7 +84,7 @@ def lib():
     L.bsp_last_hip_error.restype = C.c_int
     L.bsp_version.restype = C.c_char_p
     for name in ("bsp_group_norms", "bsp_penalty_grad", "bsp_prune_mask", "bsp_pack_count", "bsp_pack",
-                 "bsp_packed_validate", "bsp_linear", "bsp_linear_transposed", "bsp_linear_plan", "bsp_linear_planned", "bsp_mask_weights",
+                 "bsp_packed_validate", "bsp_linear", "bsp_linear_transposed", "bsp_linear_plan", "bsp_linear_planned", "bsp_linear_planned_fused", "bsp_mask_weights",
                  "bsp_group_norms_grad", "bsp_adam_step"):
         getattr(L, name).restype = C.c_int
     _LIB = L
@@ -373,6 +374,27 @@ def bsp_linear_planned(X, p: Packed, plan, bias=None, Y=None):
     st = lib().bsp_linear_planned(_ptr(X), _DT[X.dtype], T, p.M, N, p.R, p.k_align, _ptr(plan),
                                   p.total_cols, _ptr(bias), _ptr(Y), _stream())
     _check(st, "bsp_linear_planned")
+    return Y
+
+
+ACT_NONE, ACT_GELU = 0, 1
+
+
+def bsp_linear_planned_fused(X, p: Packed, plan, bias=None, act=ACT_NONE, residual=None, Y=None):
+    """Y = round(act(X Wp^T + bias) + residual) in the layer kernel (raises BspError where that layer is not fused)."""
+    T, N = X.shape
+    if N != p.N:
+        raise ValueError("X has the wrong number of columns")
+    if bias is not None and bias.dtype != X.dtype:
+        raise ValueError("X and bias must share one dtype")
+    if residual is not None and (residual.dtype != X.dtype or tuple(residual.shape) != (T, p.M)
+                                 or not residual.is_contiguous()):
+        raise ValueError("residual must be a contiguous [T, M] tensor of the dtype of X")
+    if Y is None:
+        Y = torch.empty((T, p.M), dtype=X.dtype, device=X.device)
+    st = lib().bsp_linear_planned_fused(_ptr(X), _DT[X.dtype], T, p.M, N, p.R, p.k_align, _ptr(plan),
+                                        p.total_cols, _ptr(bias), act, _ptr(residual), _ptr(Y), _stream())
+    _check(st, "bsp_linear_planned_fused")
     return Y
 
 

@@ -24,6 +24,8 @@ struct TiledArgs {
     int64_t capacity_cols;    // planned source: the caller's bound on the padded kept columns of the storage
     const void *bias;
     void *Y;
+    int act;                  // bsp_activation applied to the sums before they are rounded (the planned kernels of R = 16)
+    const void *residual;     // [T, M], type of X, added after the activation (only the kernel that streams X), or null
 };
 
 // True when the tiled kernel can take this layer (16-bit floats, kp_b % 32 == 0, X tile fits in LDS).
@@ -36,16 +38,20 @@ int launch_linear_steploop16(const TiledArgs &args, int64_t max_step, hipStream_
 int launch_linear_stream16(const TiledArgs &args, int64_t max_step, hipStream_t s);
 // Column chunks of a plan: layers with more than 1024 (padded) input columns are cut into chunks of
 // 1024 columns, the width of X that fits in LDS next to 64 tokens; narrower layers are one chunk.
-// R = 16: chunks of 512 columns, two of which are in LDS at a time -- one being used, one being filled.
+// R = 16: chunks of 512 columns, two of which are in LDS at a time -- one being used, one being filled.  Layers of
+// R = 16 with few row-blocks (up to 64: the attention output projection) are planned that way from 513 columns
+// on: with so few blocks the kernel for narrow layers would give a wavefront one or two pairs of row-blocks per
+// workgroup, and the kernel that streams X runs them as fast and writes its output once, at its end -- which is
+// where a residual can be added without a load in the step loop.
 constexpr int kPlanMaxChunks = 8;
 struct PlanChunks {
     int32_t n;      // number of chunks
     int32_t shift;  // column >> shift = chunk
 };
-inline PlanChunks plan_chunks(int64_t N, int32_t R) {
+inline PlanChunks plan_chunks(int64_t N, int32_t R, int64_t M) {
     const int64_t npad = (N + 255) / 256 * 256;
+    if (R == 16 && (npad > 1024 || (npad > 512 && M / 16 <= 64))) return PlanChunks{(int32_t)((npad + 511) / 512), 9};
     if (npad <= 1024) return PlanChunks{1, 30};
-    if (R == 16) return PlanChunks{(int32_t)((npad + 511) / 512), 9};
     return PlanChunks{(int32_t)((npad + 1023) / 1024), 10};
 }
 // Row-blocks of 8 rows ride the kernels written for 16 when the layer's height allows it: two neighbouring row-blocks
@@ -70,8 +76,8 @@ constexpr int plan_nacc(int nfrag, bool chunked, int R) {
 // wavefronts (4 per SIMD) on a short operand ring: their kernels stay within 128 registers, and the
 // per-wavefront chains of dependent instructions overlap better (measured 10-14 % faster than 8 wavefronts).
 // The other R do not fit (R = 64: four fragments of accumulators; R = 8 and odd sizes: their output paths).
-inline int plan_waves(int64_t N, int32_t R) {
-    if (R == 16 && plan_chunks(N, R).n > 1) return kPlanWaves;  // beside them run the wavefronts that copy X in
+inline int plan_waves(int64_t N, int32_t R, int64_t M) {
+    if (R == 16 && plan_chunks(N, R, M).n > 1) return kPlanWaves;  // beside them run the wavefronts that copy X in
     return (R == 16 || R == 32) ? kPlanWavesWide : kPlanWaves;
 }
 // Which row-block a plan's entry (group g, wavefront w, place i in the run) stands for, and back.  Plain plans deal

@@ -141,6 +141,28 @@ namespace {
     "v_cmp_gt_u32 s[68+2*" #U ":69+2*" #U "], s84, v75\n v_add_u32 v75, 16, v75\n"                 \
     "v_cmp_gt_u32 s[76+2*" #U ":77+2*" #U "], s84, v69\n v_add_u32 v69, 16, v69\n"
 
+// GELU of the finished sums of a row-block, in place (Sec. 4.2's networks follow the FFN up-projection with it):
+// y = 0.5 v (1 + erf(v / sqrt 2)), the error function by the rational approximation 7.1.26 of Abramowitz and Stegun,
+// erf z = 1 - (a1 t + .. + a5 t^5) exp(-z^2), t = 1 / (1 + p z), z >= 0 (absolute error below 1.5e-7, far inside the
+// rounding of a 16-bit output).  18 instructions per value; v68-70 and v75 are free at a block end, s86 = 0x7fffffff,
+// s87 = p.  (A result of v_exp / v_rcp is not used by the instruction right behind it.)
+#define SL_GELU1(V)                                                                         \
+    "v_and_b32 v68, 0x7fffffff, " V "\n v_mul_f32 v68, 0x3f3504f3, v68\n" /* z = |v| / sqrt 2 */ \
+    "v_mul_f32 v75, v68, v68\n v_mul_f32 v75, 0xbfb8aa3b, v75\n v_exp_f32 v75, v75\n" /* exp(-z^2) */ \
+    "v_fma_f32 v69, v68, s87, 1.0\n v_rcp_f32 v69, v69\n" /* t */                           \
+    "v_mov_b32 v70, 0x3f87dc22\n"                                                           \
+    "v_fmaak_f32 v70, v69, v70, 0xbfba00e3\n v_fmaak_f32 v70, v69, v70, 0x3fb5f0e3\n"        \
+    "v_fmaak_f32 v70, v69, v70, 0xbe91a98e\n v_fmaak_f32 v70, v69, v70, 0x3e827906\n"        \
+    "v_mul_f32 v70, v70, v69\n"                                                             \
+    "v_fma_f32 v68, -v70, v75, 1.0\n v_bfi_b32 v68, s86, v68, " V "\n" /* erf(v / sqrt 2) */ \
+    "v_add_f32 v68, 1.0, v68\n v_mul_f32 v68, v68, " V "\n v_mul_f32 " V ", 0.5, v68\n"
+#define SL_GELU16                                                                                     \
+    "s_mov_b32 s86, 0x7fffffff\n s_mov_b32 s87, 0x3ea7ba05\n"                                         \
+    SL_GELU1("v0") SL_GELU1("v1") SL_GELU1("v2") SL_GELU1("v3") SL_GELU1("v4") SL_GELU1("v5")         \
+    SL_GELU1("v6") SL_GELU1("v7") SL_GELU1("v8") SL_GELU1("v9") SL_GELU1("v10") SL_GELU1("v11")       \
+    SL_GELU1("v12") SL_GELU1("v13") SL_GELU1("v14") SL_GELU1("v15")
+#define SL_NO_ACT ""
+
 #define SL_CLOBBERS                                                                                                     \
     "v0", "v1", "v2", "v3", "v4", "v5", "v6", "v7", "v8", "v9", "v10", "v11", "v12", "v13", "v14", "v15", "v16", "v17",   \
         "v18", "v19", "v20", "v21", "v22", "v23", "v24", "v25", "v26", "v27", "v28", "v29", "v30", "v31", "v32", "v33",   \
@@ -151,10 +173,11 @@ namespace {
         "v98", "v99", "v100", "v101", "v102", "v103", "v104", "v105", "v106", "v107", "v108", "v109", "v110", "v111", "v112",   \
         "v113", "v114", "v115", "v116", "v117", "v118", "v119", "v120", "v121", "s40", "s41", "s42", "s43", "s44", "s45", "s46", "s47", "s48", "s49", "s50", "s51", \
         "s52", "s53", "s54", "s55", "s56", "s57", "s58", "s59", "s60", "s61", "s62", "s63", "s64", "s65", "s66", "s67", "s68", "s69", "s70", "s71", "s72", "s73", "s74", "s75", "s76",  \
-        "s77", "s78", "s79", "s80", "s81", "s82", "s83", "s84", "s85", "scc", "memory"
+        "s77", "s78", "s79", "s80", "s81", "s82", "s83", "s84", "s85", "s86", "s87", "scc", "memory"
 
-// The whole walk of up to 8 row-blocks (two quads) of one wavefront.  MFMA / CVT are the mnemonics of the layer's type.
-#define SL_WALK(MFMA, CVT)                                                                                           \
+// The whole walk of up to 8 row-blocks (two quads) of one wavefront.  MFMA / CVT are the mnemonics of the layer's type,
+// ACT what happens to a block's finished sums before they are rounded (SL_NO_ACT or SL_GELU16).
+#define SL_WALK(MFMA, CVT, ACT)                                                                                         \
     asm volatile(                                                                                                    \
         "s_mov_b64 s[40:41], %[wb]\n s_mov_b64 s[42:43], %[ob]\n s_mov_b64 s[56:57], %[yb]\n"                        \
         "s_mov_b64 s[46:47], %[cnt]\n s_sub_u32 s45, %[nb], 1\n s_mov_b32 s61, %[rs]\n s_mov_b32 s84, %[nr]\n"      \
@@ -200,6 +223,7 @@ namespace {
         /* ---- end of a row-block: s58 = its place in the quad ---- */                                              \
         "Lblk%=:\n"                                                                                                  \
         "s_nop 15\n s_nop 7\n" /* the last matrix instruction has written its result */                             \
+        ACT                                                                                                          \
         "s_movk_i32 s60, 64\n"                                                                                       \
         "s_cmp_eq_u32 s58, 0\n s_cbranch_scc1 Lk0_%=\n s_cmp_eq_u32 s58, 1\n s_cbranch_scc1 Lk1_%=\n"               \
         "s_cmp_eq_u32 s58, 2\n s_cbranch_scc1 Lk2_%=\n"                                                             \
@@ -253,7 +277,7 @@ constexpr int kSlWaves = 16;   // wavefronts per workgroup = streams of the plan
 constexpr int kSlNacc = 2;     // consecutive row-blocks of a wavefront per group (paired plans: see plan_block)
 constexpr int kSlBatch = 8;    // row-blocks per call of the loop (their step counts fill a 64-bit scalar)
 
-template <int DT>
+template <int DT, int ACT>
 __global__ __launch_bounds__(kSlWaves * 64) void linear_steploop16_kernel(
     const uint16_t *__restrict__ X, int64_t T, int64_t M, int64_t N, int32_t npad, const int32_t *__restrict__ wptr,
     const uint8_t *__restrict__ wfrag, const uint8_t *__restrict__ xoff, const void *__restrict__ bias,
@@ -314,8 +338,10 @@ __global__ __launch_bounds__(kSlWaves * 64) void linear_steploop16_kernel(
         const int64_t quad_col = ((int64_t)(gfirst >> 1) * (4 * kSlWaves) + 4 * wave) * 16;
         uint8_t *yb = Ytile + quad_col * 2;
         const uint32_t ba = kXTileBytes + (uint32_t)((quad_col + 16 * k0 - strip_row0) + 4 * G) * 4;
-        if constexpr (DT == BSP_BF16) SL_WALK("v_mfma_f32_16x16x32_bf16", "v_cvt_pk_bf16_f32");
-        else SL_WALK("v_mfma_f32_16x16x32_f16", "v_cvt_pk_f16_f32");
+        if constexpr (DT == BSP_BF16 && ACT == BSP_ACT_NONE) SL_WALK("v_mfma_f32_16x16x32_bf16", "v_cvt_pk_bf16_f32", SL_NO_ACT);
+        else if constexpr (DT == BSP_BF16) SL_WALK("v_mfma_f32_16x16x32_bf16", "v_cvt_pk_bf16_f32", SL_GELU16);
+        else if constexpr (ACT == BSP_ACT_NONE) SL_WALK("v_mfma_f32_16x16x32_f16", "v_cvt_pk_f16_f32", SL_NO_ACT);
+        else SL_WALK("v_mfma_f32_16x16x32_f16", "v_cvt_pk_f16_f32", SL_GELU16);
     }
 }
 
@@ -344,12 +370,22 @@ int launch_linear_steploop16(const TiledArgs &a, int64_t max_step, hipStream_t s
             (int32_t)ntiles, (int32_t)gps, (int32_t)NG, (int32_t)a.B, (int32_t)max_step);
         return check_launch();
     };
+    if (a.residual) return BSP_ERR_SHAPE;  // (a residual is added by the kernel that writes its output at its end)
+    if (a.act != BSP_ACT_NONE && a.act != BSP_ACT_GELU) return BSP_ERR_SHAPE;
+    if (a.xdt == BSP_BF16 && a.act == BSP_ACT_NONE) {
+        static thread_local size_t configured = 0;
+        return go(linear_steploop16_kernel<BSP_BF16, BSP_ACT_NONE>, configured);
+    }
     if (a.xdt == BSP_BF16) {
         static thread_local size_t configured = 0;
-        return go(linear_steploop16_kernel<BSP_BF16>, configured);
+        return go(linear_steploop16_kernel<BSP_BF16, BSP_ACT_GELU>, configured);
+    }
+    if (a.act == BSP_ACT_NONE) {
+        static thread_local size_t configured = 0;
+        return go(linear_steploop16_kernel<BSP_F16, BSP_ACT_NONE>, configured);
     }
     static thread_local size_t configured = 0;
-    return go(linear_steploop16_kernel<BSP_F16>, configured);
+    return go(linear_steploop16_kernel<BSP_F16, BSP_ACT_GELU>, configured);
 }
 
 }  // namespace bsp

@@ -190,7 +190,8 @@ template <int DT>
 __global__ __launch_bounds__(kStThreads) void linear_stream16_kernel(
     const uint16_t *__restrict__ X, int64_t T, int64_t M, int64_t N, int32_t npad, const int32_t *__restrict__ wptr,
     const uint8_t *__restrict__ wfrag, const uint8_t *__restrict__ xoff, const void *__restrict__ bias,
-    void *__restrict__ Y, int32_t ntiles, int32_t NG, int32_t B, int32_t nq, int32_t max_step) {
+    void *__restrict__ Y, int32_t ntiles, int32_t NG, int32_t B, int32_t nq, int32_t max_step, int32_t act,
+    const uint16_t *__restrict__ residual) {
     const int tile = blockIdx.x % ntiles, g = blockIdx.x / ntiles;
     const int64_t t0 = (int64_t)tile * 64;
     const int lane = threadIdx.x & 63;
@@ -257,7 +258,7 @@ __global__ __launch_bounds__(kStThreads) void linear_stream16_kernel(
     if constexpr (DT == BSP_BF16) ST_WALK("v_mfma_f32_16x16x32_bf16");
     else ST_WALK("v_mfma_f32_16x16x32_f16");
 
-    // ---- output: bias, rounding, lane re-deal, whole lines ----
+    // ---- output: bias, activation, residual, rounding, lane re-deal, whole lines ----
     if (b0 >= B) return;
     uint2 half[kStNacc][4];  // rounded: block a, sub-tile u: columns 4 G .. 4 G + 3 of token 16 u + l16
 #pragma unroll
@@ -269,8 +270,24 @@ __global__ __launch_bounds__(kStThreads) void linear_stream16_kernel(
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            half[a][u].x = cvt_pk<DT>(acc[a][u][0] + bv[0], acc[a][u][1] + bv[1]);
-            half[a][u].y = cvt_pk<DT>(acc[a][u][2] + bv[2], acc[a][u][3] + bv[3]);
+            float y[4];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                y[v] = acc[a][u][v] + bv[v];
+                if (act == BSP_ACT_GELU) y[v] = 0.5f * y[v] * (1.0f + erff(y[v] * 0.70710678118654752f));
+            }
+            const int64_t t = t0 + 16 * u + l16;
+            if (residual && t < T && b0 + a < B) {  // the lane's 4 columns of token t: 8 bytes
+                const uint2 rw = *reinterpret_cast<const uint2 *>(residual + t * M + (b0 + a) * 16 + 4 * G);
+                const uint32_t h[4] = {rw.x & 0xffffu, rw.x >> 16, rw.y & 0xffffu, rw.y >> 16};
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    if constexpr (DT == BSP_BF16) y[v] += __uint_as_float(h[v] << 16);
+                    else y[v] += (float)__builtin_bit_cast(_Float16, (uint16_t)h[v]);
+                }
+            }
+            half[a][u].x = cvt_pk<DT>(y[0], y[1]);
+            half[a][u].y = cvt_pk<DT>(y[2], y[3]);
         }
     }
     uint8_t *Yq = reinterpret_cast<uint8_t *>(Y) + t0 * M * 2 + b0 * 32;  // the quad's 128 bytes of the tile's first row
@@ -321,17 +338,20 @@ __global__ __launch_bounds__(kStThreads) void linear_stream16_kernel(
 
 // Launch for R = 16, 1024 < npad <= 4096, a plan of 8 streams cut into chunks of 512 columns, Y aligned to 16 bytes.
 int launch_linear_stream16(const TiledArgs &a, int64_t max_step, hipStream_t s) {
-    const PlanChunks ch = plan_chunks(a.N, a.R);
+    const PlanChunks ch = plan_chunks(a.N, a.R, a.M);
     const int64_t NG = plan_groups(a.B, kStComputeWaves, kStNacc, false);
     const int64_t ntiles = (a.T + 63) / 64;
     if (ntiles * NG >= ((int64_t)1 << 31) || ch.n > kPlanMaxChunks) return BSP_ERR_SHAPE;
+    if (a.act != BSP_ACT_NONE && a.act != BSP_ACT_GELU) return BSP_ERR_SHAPE;
+    if (a.residual && !aligned(a.residual, 8)) return BSP_ERR_SHAPE;
     const size_t lds = kXTileBytes;
     auto go = [&](auto kern, size_t &configured) {
         int st = raise_lds_limit(kern, lds, configured);
         if (st != BSP_OK) return st;
         kern<<<dim3((unsigned)(ntiles * NG)), dim3(kStThreads), lds, s>>>(
             a.X, a.T, a.M, a.N, a.npad, a.wptr, (const uint8_t *)a.wfrag, (const uint8_t *)a.xoff, a.bias, a.Y,
-            (int32_t)ntiles, (int32_t)NG, (int32_t)a.B, ch.n, (int32_t)max_step);
+            (int32_t)ntiles, (int32_t)NG, (int32_t)a.B, ch.n, (int32_t)max_step, (int32_t)a.act,
+            (const uint16_t *)a.residual);
         return check_launch();
     };
     if (a.xdt == BSP_BF16) {

@@ -990,10 +990,11 @@ int launch_planned_1024(const TiledArgs &a, int64_t ntiles, int64_t NG, int64_t 
 
 template <int DT, int NFRAG>
 int launch_planned(const TiledArgs &a, hipStream_t s) {
-    const int NACC = plan_nacc(NFRAG, a.npad > 1024, a.R);
+    const bool chunked = plan_chunks(a.N, a.R, a.M).n > 1;
+    const int NACC = plan_nacc(NFRAG, chunked, a.R);
     const size_t lds = kXTileBytes;  // 64 tokens x 1024 columns
     const int64_t ntiles = (a.T + 63) / 64;
-    const int waves = plan_waves(a.N, a.R);  // as the plan was built
+    const int waves = plan_waves(a.N, a.R, a.M);  // as the plan was built
     const int64_t NG = (a.B + waves * NACC - 1) / (waves * NACC);
     // the staged store path: full fragments, and a bias that can be read in 4-byte words
     const int32_t fast = ((a.R == 16 * NFRAG || a.R == 8) && (reinterpret_cast<uintptr_t>(a.bias) & 3) == 0 &&
@@ -1002,12 +1003,12 @@ int launch_planned(const TiledArgs &a, hipStream_t s) {
                              : 0;
     const int64_t max_step = a.plan_steps - plan_slack_steps();
     if (max_step < 0 || max_step > INT32_MAX) return BSP_ERR_CAPACITY;
-    if (a.npad > 1024) {
+    if (chunked) {
         if constexpr (NFRAG == 1) {  // R = 16: the kernel that streams X through LDS beside the products
             if (a.R == 16) return launch_linear_stream16(a, max_step, s);
         }
         if (ntiles * NG >= ((int64_t)1 << 31)) return BSP_ERR_SHAPE;
-        const PlanChunks ch = plan_chunks(a.N, a.R);
+        const PlanChunks ch = plan_chunks(a.N, a.R, a.M);
         auto go = [&](auto kern, size_t &configured, int w) {
             int st = raise_lds_limit(kern, lds, configured);
             if (st != BSP_OK) return st;

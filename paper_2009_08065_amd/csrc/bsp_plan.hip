@@ -338,8 +338,8 @@ inline PlanLayout plan_layout(int64_t M, int64_t N, int32_t R, int64_t capacity_
     PlanLayout L;
     const int64_t B = M / R;  // stored row-blocks (the sizes below follow them)
     const int32_t Re = plan_virtual16(R, M) ? 16 : R;  // block height the plan is laid out for
-    const bool chunked = plan_chunks(N, Re).n > 1;
-    L.NG = plan_groups(M / Re, plan_waves(N, Re), plan_nacc(nfrag_of(Re), chunked, Re), plan_paired(Re, chunked));
+    const bool chunked = plan_chunks(N, Re, M).n > 1;
+    L.NG = plan_groups(M / Re, plan_waves(N, Re, M), plan_nacc(nfrag_of(Re), chunked, Re), plan_paired(Re, chunked));
     // (+ a step per run of a last group that reaches past the layer, for the plans that give every run one)
     L.steps = (size_t)((capacity_cols + 31) / 32) + (size_t)B * (kPlanMaxChunks - 1) +
               (size_t)kPlanWaves * 4 * kPlanMaxChunks + (size_t)plan_slack_steps();
@@ -385,7 +385,7 @@ extern "C" int bsp_linear_plan(int vdt, int64_t M, int64_t N, int32_t R, int32_t
     uint32_t *wfrag = (uint32_t *)((uint8_t *)plan + L.wptr_bytes);
     uint32_t *xoff = (uint32_t *)((uint8_t *)plan + L.wptr_bytes + L.wfrag_bytes);
     hipStream_t s = (hipStream_t)stream;
-    const PlanChunks ch = plan_chunks(N, Re);
+    const PlanChunks ch = plan_chunks(N, Re, M);
     const int32_t min_one = plan_min_one_step(Re, ch.n > 1) ? 1 : 0;
     const int32_t paired = plan_paired(Re, ch.n > 1) ? 1 : 0;
     // step counts per (row-block, chunk) are parked at the start of the offsets region: the scan has
@@ -396,7 +396,7 @@ extern "C" int bsp_linear_plan(int vdt, int64_t M, int64_t N, int32_t R, int32_t
         plan_count_kernel<<<(unsigned)Bs, kThreads, 0, s>>>(blk_cnt, blk_ptr, col_idx, capacity_cols, ch.shift, ch.n,
                                                             steps_bq);
     const int32_t nacc = plan_nacc(nf, ch.n > 1, Re);
-    const int waves = plan_waves(N, Re);
+    const int waves = plan_waves(N, Re, M);
     plan_scan_kernel<<<1, waves * 64, 0, s>>>(ch.n > 1 ? steps_bq : nullptr, blk_cnt, blk_ptr, capacity_cols,
                                                    (int32_t)B, (int32_t)L.NG, nacc, ch.n, paired, min_one, nf,
                                                    virt ? 1 : 0, (int64_t)L.steps, plan_slack_steps(), wptr, wfrag,
@@ -413,7 +413,16 @@ extern "C" int bsp_linear_plan(int vdt, int64_t M, int64_t N, int32_t R, int32_t
 
 extern "C" int bsp_linear_planned(const void *X, int xdt, int64_t T, int64_t M, int64_t N, int32_t R, int32_t k_align,
                                   const void *plan, int64_t capacity_cols, const void *bias, void *Y, void *stream) {
+    return bsp_linear_planned_fused(X, xdt, T, M, N, R, k_align, plan, capacity_cols, bias, BSP_ACT_NONE, nullptr, Y,
+                                    stream);
+}
+
+extern "C" int bsp_linear_planned_fused(const void *X, int xdt, int64_t T, int64_t M, int64_t N, int32_t R,
+                                        int32_t k_align, const void *plan, int64_t capacity_cols, const void *bias,
+                                        int act, const void *residual, void *Y, void *stream) {
     if (!X || !plan || !Y) return BSP_ERR_NULL;
+    if (act != BSP_ACT_NONE && act != BSP_ACT_GELU) return BSP_ERR_SHAPE;
+    if (residual && !aligned(residual, 8)) return BSP_ERR_SHAPE;
     if (T < 0 || M <= 0 || N <= 0 || R < 1 || R > 64 || M % R != 0 || M / R > 65535) return BSP_ERR_SHAPE;
     if (!tiled_supported(xdt, N, k_align)) return BSP_ERR_SHAPE;
     if (capacity_cols < 0) return BSP_ERR_CAPACITY;
@@ -433,5 +442,12 @@ extern "C" int bsp_linear_planned(const void *X, int xdt, int64_t T, int64_t M, 
     a.capacity_cols = capacity_cols;
     a.bias = bias;
     a.Y = Y;
+    a.act = act;
+    a.residual = residual;
+    if (act != BSP_ACT_NONE || residual) {
+        // fused by the two kernels of 16-row blocks only; the residual by the one that writes its output at its end
+        if (Re != 16) return BSP_ERR_SHAPE;
+        if (residual && plan_chunks(N, Re, M).n <= 1) return BSP_ERR_SHAPE;
+    }
     return launch_linear_tiled(a, true, (hipStream_t)stream);
 }

@@ -452,6 +452,53 @@ def test_linear_seeded_random_shapes():
             raise AssertionError(f"{case}: {e}")
 
 
+# ------------------------------------------------------------------------------ the layer with its epilogue
+FUSED_CASES = [
+    # (dtype, R, T, M, N, act, residual): the kernel for narrow layers (activation only) ...
+    ("bf16", 16, 200, 1536, 768, True, False), ("f16", 16, 77, 512 + 16, 1000, True, False),
+    ("bf16", 8, 130, 1280, 512, True, False),
+    # ... and the kernel that streams X (wide layers; layers of few row-blocks): activation, residual, both
+    ("bf16", 16, 150, 256, 2048, False, True), ("bf16", 16, 333, 1024, 1024, False, True),
+    ("f16", 16, 100, 96, 4096, True, True), ("bf16", 8, 65, 336, 3000, True, True),
+    ("bf16", 16, 64, 1024, 768, True, False),
+]
+
+
+@pytest.mark.parametrize("dtype,R,T,M,N,act,with_res", FUSED_CASES)
+def test_linear_fused_epilogue(dtype, R, T, M, N, act, with_res):
+    """Exact GELU and residual inside the layer kernel against the oracle's layer followed by its epilogue (one
+    rounding); also with an empty row-block and without a bias."""
+    d = wl.layer(7000 + T + N, T, M, N, dtype)
+    keep = wl.bernoulli_keep_mask(7100 + M, M // R, N, 0.25)
+    keep[1, :] = 0
+    res = wl.layer(7200 + T, T, 16, M, dtype)["X"] if with_res else None   # a [T, M] tensor of N(0, 1) values
+    p_ref = orc.pack(d["W"], R, keep, 32, CODE[dtype])
+    p = bsp.bsp_pack(dev(d["W"], dtype), R, torch.from_numpy(keep).cuda(), 32)
+    plan = bsp.bsp_linear_plan(p)
+    code = orc.ACT_GELU if act else orc.ACT_NONE
+    for bias in (d["bias"], None):
+        Y_ref, _ = orc.linear_packed_fused(d["X"], p_ref, bias, act=code, residual=res, ydt=CODE[dtype], n_threads=16)
+        Y = bsp.bsp_linear_planned_fused(dev(d["X"], dtype), p, plan, dev(bias, dtype),
+                                         act=bsp.ACT_GELU if act else bsp.ACT_NONE, residual=dev(res, dtype))
+        assert_y_close(host(Y), Y_ref, dtype)
+
+
+def test_linear_fused_epilogue_refuses_what_is_not_fused():
+    """Row-blocks of other heights, and a residual for a layer whose kernel stores block by block: an error and
+    nothing written."""
+    for (R, M, N, act, with_res) in [(32, 256, 512, bsp.ACT_GELU, False), (16, 2048, 1024, bsp.ACT_NONE, True),
+                                     (16, 256, 512, 7, False)]:
+        d = wl.layer(7300 + R, 64, M, N, "bf16")
+        keep = wl.bernoulli_keep_mask(7301, M // R, N, 0.3)
+        p = bsp.bsp_pack(dev(d["W"], "bf16"), R, torch.from_numpy(keep).cuda(), 32)
+        plan = bsp.bsp_linear_plan(p)
+        Y = torch.full((64, M), 3.0, dtype=torch.bfloat16, device="cuda")
+        res = torch.zeros((64, M), dtype=torch.bfloat16, device="cuda") if with_res else None
+        with pytest.raises(bsp.BspError):
+            bsp.bsp_linear_planned_fused(dev(d["X"], "bf16"), p, plan, None, act=act, residual=res, Y=Y)
+        assert float(Y.float().min()) == 3.0 and float(Y.float().max()) == 3.0
+
+
 # ------------------------------------------------------------------------------ the transposed product
 def run_transposed(U, W, bias, R, keep, k_align, dtype, T_rows=None):
     code = CODE[dtype]
