@@ -37,10 +37,10 @@ import paper_2009_08065_amd as bsp  # noqa: E402
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
 LDS_PEAK_GBS = 256 * 256 * 2.4  # 256 compute units x 256 B/clk (ds_read_b128 measured at 246) x 2.4 GHz = 157 286 GB/s
-# HBM bytes per launch of linear_tiled_planned_kernel on this workload (average of its three launches), from the
-# FETCH_SIZE / WRITE_SIZE counter runs summarised in profiles/linear_kernels_bert_large_r16_hbm_traffic.md
-# (31.5 MB read + 45.5 MB written; the algorithmic figure is 62.8 MB).  Void once that kernel changes.
-PLANNED_KERNEL_HBM_BYTES_PER_LAUNCH = 77.0e6
+# HBM bytes per launch of the dominant layer kernel on this workload (average of its launches), from the FETCH_SIZE /
+# WRITE_SIZE counter runs summarised in profiles/linear_kernels_bert_large_r16_hbm_traffic.md; None = not measured
+# for the kernel as it stands.
+DOMINANT_KERNEL_HBM_BYTES_PER_LAUNCH = {"linear_steploop16_kernel": None, "linear_stream16_kernel": None}
 
 
 class Matrix:
@@ -138,6 +138,23 @@ def time_layers(mats, steps, warmup):
     return np.array([[e[0].elapsed_time(e[1]) for e in ev] for ev in evs])
 
 
+def time_set_back_to_back(mats, steps, warmup):
+    """The same launches with no event between them: ms per pass over the set (what a stream of layers costs; the
+    per-launch figures above each carry the few microseconds between an event and the start of a kernel)."""
+    for _ in range(warmup):
+        for m in mats:
+            m.linear()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        for m in mats:
+            m.linear()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / steps
+
+
 def per_matrix_report(mats, lin_avg_ms):
     out = {}
     for m, ms in zip(mats, lin_avg_ms):
@@ -173,7 +190,8 @@ def linear_only_set(descs, steps, warmup, label):
     ms = time_layers(mats, steps, warmup).mean(axis=0)
     useful = sum(m.useful_flops() for m in mats)
     tot = float(ms.sum())
-    res = {"workload": label, "ms": round(tot, 4), "useful_tflops": round(useful / (tot * 1e-3) / 1e12, 2),
+    res = {"workload": label, "ms": round(tot, 4), "ms_back_to_back": round(time_set_back_to_back(mats, steps, 2), 4),
+           "useful_tflops": round(useful / (tot * 1e-3) / 1e12, 2),
            "frac_mfma_peak": round(useful / (tot * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
            "frac_hbm_peak": round(sum(m.linear_bytes() for m in mats) / (tot * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
            "per_matrix": per_matrix_report(mats, ms)}
@@ -235,6 +253,66 @@ def config2_layer(c, steps):
     ms = time_layers([m], steps, 5).mean(axis=0)
     return {"workload": "config 2: X 4096x768, W 3072x768, bf16, R = 16, block-scope percentile, 256 of 768 kept (3x)",
             "per_matrix": per_matrix_report([m], ms)}
+
+
+def fused_epilogue(mats, steps):
+    """The layers with their epilogue inside the kernel (Sec. 4.4; Sec. 4.2's networks: GELU behind the FFN
+    up-projection, a residual behind the attention output and the FFN down-projection) beside the plain layer:
+    microseconds per call, and the bytes of the element-wise pass that the fusion saves."""
+    by_name = {m.name: m for m in mats}
+    out = {}
+    for name, act, with_res in (("ffn_up", bsp.ACT_GELU, False), ("attn_out", bsp.ACT_NONE, True),
+                                ("ffn_down", bsp.ACT_NONE, True)):
+        m = by_name[name]
+        res = torch.randn((m.T, m.M), device="cuda", generator=torch.Generator(device="cuda").manual_seed(77)
+                          ).to(torch.bfloat16) if with_res else None
+        def call():
+            bsp.bsp_linear_planned_fused(m.X, m.packed, m.plan, m.bias, act=act, residual=res, Y=m.Y)
+        us = {}
+        for label, fn in (("plain", m.linear), ("fused", call)):
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+            for e0, e1 in ev:       # the other layers pass in between: cold caches, as in `linear_only`
+                for o in mats:
+                    if o is not m:
+                        o.linear()
+                e0.record(); fn(); e1.record()
+            torch.cuda.synchronize()
+            us[label] = float(np.mean([e0.elapsed_time(e1) for e0, e1 in ev])) * 1e3
+        saved = (2 + (1 if with_res else 0)) * 2.0 * m.T * m.M   # the pass it replaces: read Y (+ residual), write Y
+        out[name] = {"epilogue": ("gelu" if act == bsp.ACT_GELU else "") + ("residual" if with_res else ""),
+                     "us_plain": round(us["plain"], 2), "us_fused": round(us["fused"], 2),
+                     "bytes_of_the_pass_saved": saved,
+                     "us_of_that_pass_at_hbm_peak": round(saved / HBM_PEAK_GBS / 1e3, 2)}
+    return out
+
+
+def whole_block_mode(steps, Ct=32, R=16):
+    """The comparison structure of Sec. 4.4 / Table 4 (a tile of R rows x Ct columns is kept or removed as a whole)
+    on the BERT-large set at 5x, through the same storage, plan and layer kernels: kept columns then come in runs of
+    Ct, and the layer's time is the bound the column-granular structure is measured against."""
+    mats = []
+    for d in wl.config4(R=R):
+        m = Matrix(d)
+        bsp.bsp_group_norms(m.W, m.R, eps=1e-6, mode=bsp.ALPHA_SQNORM, sumsq=m.sumsq, alpha=m.alpha, want=())
+        ts = bsp.bsp_tile_sumsq(m.sumsq, Ct)
+        tk, _ = bsp.bsp_prune_mask(ts, n_keep=ts.numel() // 5, scope=bsp.SCOPE_MATRIX)
+        m.keep = bsp.bsp_expand_tile_mask(tk, Ct)
+        bsp.bsp_pack_count(m.keep, m.k_align, blk_cnt=m.blk_cnt, blk_ptr=m.blk_ptr)
+        st = bsp.lib().bsp_pack(m.W.data_ptr(), bsp.BF16, m.M, m.N, m.R, m.keep.data_ptr(), m.k_align,
+                                m.blk_cnt.data_ptr(), m.blk_ptr.data_ptr(), m.capacity, m.col_idx.data_ptr(),
+                                m.vals.data_ptr(), bsp.BF16, torch.cuda.current_stream().cuda_stream)
+        if st != 0:
+            raise bsp.BspError(st, "bsp_pack")
+        bsp.bsp_linear_plan(m.packed, plan=m.plan)
+        m.linear()
+        torch.cuda.synchronize()
+        m.kept_cols = int(m.blk_cnt.sum().item())
+        mats.append(m)
+    ms = time_layers(mats, steps, 3).mean(axis=0)
+    return {"tile": [R, Ct], "ms": round(float(ms.sum()), 4), "per_matrix": per_matrix_report(mats, ms)}
 
 
 def cpu_baseline(mats):
@@ -642,6 +720,9 @@ def main():
     def kernel_of(m):
         if not m.use_plan:
             return "bsp_linear (compact storage)"
+        if m.R in (8, 16) and m.M % 16 == 0:   # the kernels of 16-row blocks: which one, the plan's chunking decides
+            streams_x = m.N > 1024 or (m.N > 512 and m.M // 16 <= 64)
+            return "linear_stream16_kernel" if streams_x else "linear_steploop16_kernel"
         return "linear_tiled_planned_kernel" if m.N <= 1024 else "linear_tiled_chunked_kernel"
     fam = {}
     for m, ms, by in zip(mats, lin_avg, lin_bytes):
@@ -669,7 +750,9 @@ def main():
                            "pack_count + pack + linear_plan + linear, 4 matrices"},
         "linear_only": {"cache_state": "cold: the four layers run in turn, so about 250 MB of other X / Y traffic "
                                        "(the size of the Infinity Cache) passes between two launches of one layer",
-                        "ms": round(lin_total_ms, 4), "useful_tflops": round(achieved_tflops, 2),
+                        "ms": round(lin_total_ms, 4),
+                        "ms_back_to_back": round(time_set_back_to_back(mats, args.steps, 2), 4),
+                        "useful_tflops": round(achieved_tflops, 2),
                         "dense_equiv_tflops": round(dense / (lin_total_ms * 1e-3) / 1e12, 2),
                         "frac_mfma_peak": round(achieved_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
                         "per_matrix": per_matrix},
@@ -677,8 +760,7 @@ def main():
                      "avg_launch_us": round(dom["ms"] * 1e3 / len(dom["launches"]), 2), "bound": "hbm",
                      "achieved": round(achieved_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved_gbs / HBM_PEAK_GBS, 4),
-                     "traffic": PLANNED_KERNEL_HBM_BYTES_PER_LAUNCH if dom_name == "linear_tiled_planned_kernel"
-                     and args.R == 16 else None},
+                     "traffic": DOMINANT_KERNEL_HBM_BYTES_PER_LAUNCH.get(dom_name) if args.R == 16 else None},
         "roofline_mfma": {"bound": "mfma", "achieved": round(achieved_tflops, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
                           "unit": "TFLOP/s", "frac": round(achieved_tflops / MFMA_BF16_PEAK_TFLOPS, 4)},
     }
@@ -700,6 +782,9 @@ def main():
         sets["config2"] = config2_layer(c2, k)
         sets["config1"] = config1_latency()
         out["linear_only_sets"] = sets
+        if args.R == 16:
+            out["fused_epilogue"] = fused_epilogue(mats, k)
+            out["whole_block_mode"] = whole_block_mode(k)
     if not args.no_grid:
         out["linear_grid"] = linear_grid()
     if not args.no_transposed:

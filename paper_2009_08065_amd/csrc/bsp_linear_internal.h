@@ -7,6 +7,7 @@ namespace bsp {
 
 constexpr int kPlanWaves = 8;       // wavefronts per workgroup of a planned kernel = streams of a plan ...
 constexpr int kPlanWavesWide = 16;  // ... and where the registers allow it: see plan_waves()
+#define kPlanWaves16 16             // ... of the kernel for R = 16 and narrow layers (a macro: its assembly needs the literal)
 
 struct TiledArgs {
     int xdt;
@@ -78,7 +79,8 @@ constexpr int plan_nacc(int nfrag, bool chunked, int R) {
 // The other R do not fit (R = 64: four fragments of accumulators; R = 8 and odd sizes: their output paths).
 inline int plan_waves(int64_t N, int32_t R, int64_t M) {
     if (R == 16 && plan_chunks(N, R, M).n > 1) return kPlanWaves;  // beside them run the wavefronts that copy X in
-    return (R == 16 || R == 32) ? kPlanWavesWide : kPlanWaves;
+    if (R == 16) return kPlanWaves16;
+    return R == 32 ? kPlanWavesWide : kPlanWaves;
 }
 // Which row-block a plan's entry (group g, wavefront w, place i in the run) stands for, and back.  Plain plans deal
 // runs of nacc blocks round robin: block (g * waves + w) * nacc + i.  Paired plans (R = 16, one column chunk: the

@@ -53,6 +53,11 @@ namespace {
 //   resume point, s60 bias stride, s61 bytes of 16 token rows of Y, s[62:63] scratch, s[64:65] all ones once the
 //   first pair of the quad in the registers is this call's own (a call may start with the second pair of a quad),
 //   s84 token rows of the tile, s85 bytes of a token row
+#define SL_STR2(x) #x
+#define SL_STR(x) SL_STR2(x)
+#define SL_WAVES kPlanWaves16          // wavefronts per workgroup = streams of the plan (a literal: it enters the assembly)
+#define SL_QUAD_BIAS "(4*" SL_STR(SL_WAVES) "-3)*64"  // LDS bytes from a quad's last bias piece to the next quad's first
+#define SL_QUAD_Y SL_STR(SL_WAVES) "*128"             // bytes from a wavefront's quad to its next one in a token row
 #define SL_W(J) "v[16+4*" #J ":19+4*" #J "]"
 #define SL_O(J) "v[32+" #J "]"
 #define SL_XP(P, U, H) "v[36+16*" #P "+4*" #U "+2*" #H ":37+16*" #P "+4*" #U "+2*" #H "]"
@@ -184,7 +189,7 @@ namespace {
         "s_lshr_b32 s85, s61, 4\n s_lshr_b32 s62, s61, 1\n s_add_u32 s66, s56, s62\n s_addc_u32 s67, s57, 0\n"      \
         /* a call starts with the first (k0 = 0) or the second pair (k0 = 2) of a quad */                           \
         "s_mov_b32 s58, %[k0]\n s_mov_b32 s63, 0\n s_cmp_eq_u32 s58, 0\n s_cselect_b64 s[64:65], -1, 0\n"             \
-        "s_cselect_b32 s60, 64, 0xf40\n" /* from the second bias to the third: the next block, or the next quad */   \
+        "s_mov_b32 s62, " SL_QUAD_BIAS "\n s_cselect_b32 s60, 64, s62\n" /* second bias to third: next block or next quad */ \
         /* lane constants: 16 * lane, 4 * (lane / 4), the token quad in both halves of a word, 3 */                  \
         "v_mbcnt_lo_u32_b32 v70, -1, 0\n v_mbcnt_hi_u32_b32 v70, -1, v70\n"                                         \
         "v_lshlrev_b32 v71, 4, v70\n v_and_b32 v72, 0xfc, v70\n"                                                    \
@@ -237,11 +242,11 @@ namespace {
         SL_STORE_PAIR(92, 0, 48, 64) SL_STORE_PAIR(92, 1, 50, 64) SL_STORE_PAIR(92, 2, 52, 64) SL_STORE_PAIR(92, 3, 54, 64) \
         "Lleft%=:\n"                                                                                                 \
         "s_mov_b64 exec, -1\n"                                                                                       \
-        "s_add_u32 s56, s56, 2048\n s_addc_u32 s57, s57, 0\n s_add_u32 s66, s66, 2048\n s_addc_u32 s67, s67, 0\n"   \
+        "s_add_u32 s56, s56, " SL_QUAD_Y "\n s_addc_u32 s57, s57, 0\n s_add_u32 s66, s66, " SL_QUAD_Y "\n s_addc_u32 s67, s67, 0\n" \
         "s_mov_b32 s58, 0\n s_mov_b64 s[64:65], -1\n s_branch Lcom%=\n"                                                                      \
         "Lk0_%=:\n" SL_CVT4(CVT, 76, 0) "s_mov_b32 s58, 1\n s_branch Lcom%=\n"                                      \
         /* (the bias read two blocks ahead of block 1 is the first block's of the next group's quad) */              \
-        "Lk1_%=:\n" SL_CVT4(CVT, 76, 2) SL_SWAPS(76) "s_mov_b32 s58, 2\n s_movk_i32 s60, 0xf40\n s_branch Lcom%=\n" \
+        "Lk1_%=:\n" SL_CVT4(CVT, 76, 2) SL_SWAPS(76) "s_mov_b32 s58, 2\n s_movk_i32 s60, " SL_QUAD_BIAS "\n s_branch Lcom%=\n" \
         "Lk2_%=:\n" SL_CVT4(CVT, 92, 0) "s_mov_b32 s58, 3\n"                                                        \
         "Lcom%=:\n"                                                                                                  \
         "s_sub_u32 s45, s45, 1\n"                                                                                    \
@@ -273,7 +278,7 @@ namespace {
           [nr] "s"(nr), [ba] "v"(ba), [bl] "v"(bl)                                                                   \
         : SL_CLOBBERS)
 
-constexpr int kSlWaves = 16;   // wavefronts per workgroup = streams of the plan
+constexpr int kSlWaves = SL_WAVES;
 constexpr int kSlNacc = 2;     // consecutive row-blocks of a wavefront per group (paired plans: see plan_block)
 constexpr int kSlBatch = 8;    // row-blocks per call of the loop (their step counts fill a 64-bit scalar)
 

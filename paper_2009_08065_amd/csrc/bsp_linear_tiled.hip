@@ -1036,7 +1036,7 @@ int launch_planned(const TiledArgs &a, hipStream_t s) {
         // R = 16 and 32: 16 wavefronts (the plan has 16 streams); R = 64: 8
         constexpr int WAVES = NFRAG <= 2 ? kPlanWavesWide : kPlanWaves;
         if constexpr (NFRAG == 1) {  // R = 16: the kernel whose step loop is written in assembly (its plans are paired)
-            if (waves == kPlanWavesWide) return launch_linear_steploop16(a, max_step, s);
+            if (waves == kPlanWaves16) return launch_linear_steploop16(a, max_step, s);
             return BSP_ERR_SHAPE;
         } else {
             if (waves == WAVES) return launch_planned_1024<DT, NFRAG, kOutSwap, WAVES>(a, ntiles, NG, max_step, s);

@@ -128,7 +128,8 @@ __global__ __launch_bounds__(kPlanWavesWide * 64) void plan_scan_kernel(const in
     for (int e = lane; e <= E; e += 64) mine[e] += wbase;
     if (steps_bq && min_one) {
         __syncthreads();
-        for (int e = 0; e < E; ++e) {  // uniform over the wavefront
+        // (such runs can only be in the last group: its entries close the stream)
+        for (int e = max(0, E - nchunks * nacc); e < E; ++e) {  // uniform over the wavefront
             const int eg = e / (nchunks * nacc);
             if (plan_block(eg, w, e % nacc, waves, nacc, paired != 0) < B) continue;
             const int64_t gs = mine[e];
