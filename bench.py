@@ -38,9 +38,10 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
 LDS_PEAK_GBS = 256 * 256 * 2.4  # 256 compute units x 256 B/clk (ds_read_b128 measured at 246) x 2.4 GHz = 157 286 GB/s
 # HBM bytes per launch of the dominant layer kernel on this workload (average of its launches), from the FETCH_SIZE /
-# WRITE_SIZE counter runs summarised in profiles/linear_kernels_bert_large_r16_hbm_traffic.md; None = not measured
-# for the kernel as it stands.
-DOMINANT_KERNEL_HBM_BYTES_PER_LAUNCH = {"linear_steploop16_kernel": None, "linear_stream16_kernel": None}
+# WRITE_SIZE counter runs summarised in profiles/layer_kernels_bert_large_r16_per_launch.md (QKV 80.2 MB and FFN-up
+# 99.5 MB for the step-loop kernel, attention-out 41.6 MB and FFN-down 105.1 MB for the streaming one); None = not
+# measured for the kernel as it stands.
+DOMINANT_KERNEL_HBM_BYTES_PER_LAUNCH = {"linear_steploop16_kernel": 89.9e6, "linear_stream16_kernel": 73.4e6}
 
 
 class Matrix:
