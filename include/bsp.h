@@ -227,6 +227,30 @@ int bsp_linear_transposed(const void *U, int udt, int64_t T, int64_t M, int64_t 
                           const int32_t *blk_cnt, const int32_t *blk_ptr, const int32_t *col_idx,
                           const void *vals, const void *bias, void *Z, void *stream);
 
+/* ---- gradient with respect to the kept weights (Alg. 2 updates W from the gradient of the
+ * loss; for the layer Y = X Wp^T + bias of Sec. 3.1 the chain rule gives
+ * dW[m, j] = sum_t dY[t, m] X[t, j], and only the kept groups need it) --------------------------
+ *   D[R*blk_ptr[b] + r*kp_b + c] = sum_t dY[t, b*R + r] * X[t, col_idx[b, c]]   c < k_b
+ *                                = +0                                            pad slots
+ * in the layout of the value panels (kp_b = blk_ptr[b+1] - blk_ptr[b]), so that an optimiser can
+ * walk vals and D side by side.  All pointers are device pointers.  X: [T, N], dY: [T, M],
+ * row-major contiguous, dtype xdt; D: R * blk_ptr[B] elements of dtype gdt (at most
+ * R * capacity_cols; the caller owns it, every element is written).  bf16 / fp16 inputs with
+ * R % 8 == 0, R <= 64, N % 4 == 0, X 8-byte and dY 16-byte aligned go through the matrix cores:
+ * products exact, sums in fp32 (per tile of 32 tokens inside the matrix instruction, tiles in
+ * ascending order inside a range of tokens, then the ranges in ascending order), rounded once to
+ * gdt (RNE); two calls with the same arguments give the same bits.  That path needs ws: device
+ * scratch of at least bsp_linear_dvals_workspace_bytes(M, N, R, capacity_cols) bytes, 256-byte
+ * aligned (contents undefined before and after).  Other arguments (fp32 inputs, other R, ws ==
+ * NULL) take a plain kernel that adds fp32 products token by token.  T == 0 gives zeros.
+ * Returns BSP_OK, BSP_ERR_NULL, BSP_ERR_DTYPE, BSP_ERR_SHAPE (M % R != 0, bad k_align, sizes
+ * past 32-bit indices), BSP_ERR_CAPACITY (ws_bytes too small) or BSP_ERR_HIP.  The storage must
+ * be well formed (bsp_packed_validate) with ascending columns inside a row-block. */
+size_t bsp_linear_dvals_workspace_bytes(int64_t M, int64_t N, int32_t R, int64_t capacity_cols);
+int bsp_linear_dvals(const void *X, const void *dY, int xdt, int64_t T, int64_t M, int64_t N, int32_t R,
+                     int32_t k_align, const int32_t *blk_cnt, const int32_t *blk_ptr, const int32_t *col_idx,
+                     int64_t capacity_cols, void *D, int gdt, void *ws, size_t ws_bytes, void *stream);
+
 /* ---- derived operand buffer for the layer (Sec. 4.4 names "matrix reorder and compact model
  * storage" as what makes the pruned model fast; the order of the kept columns inside a
  * row-block is free, so it is chosen for the hardware) ---------------------------------------

@@ -70,6 +70,9 @@ def lib():
     L.bsp_packed_validate.argtypes = [i64, i64, i32, i32, vp, vp, vp, i64, vp, vp]
     L.bsp_linear.argtypes = [vp, C.c_int, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp, vp, vp]
     L.bsp_linear_transposed.argtypes = [vp, C.c_int, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp, vp, vp]
+    L.bsp_linear_dvals_workspace_bytes.argtypes = [i64, i64, i32, i64]
+    L.bsp_linear_dvals_workspace_bytes.restype = sz
+    L.bsp_linear_dvals.argtypes = [vp, vp, C.c_int, i64, i64, i64, i32, i32, vp, vp, vp, i64, vp, C.c_int, vp, sz, vp]
     L.bsp_linear_plan_supported.argtypes = [C.c_int, i64, i32]
     L.bsp_linear_plan_supported.restype = C.c_int
     L.bsp_linear_plan_bytes.argtypes = [i64, i32, i64]
@@ -84,7 +87,8 @@ def lib():
     L.bsp_last_hip_error.restype = C.c_int
     L.bsp_version.restype = C.c_char_p
     for name in ("bsp_group_norms", "bsp_penalty_grad", "bsp_prune_mask", "bsp_pack_count", "bsp_pack",
-                 "bsp_packed_validate", "bsp_linear", "bsp_linear_transposed", "bsp_linear_plan", "bsp_linear_planned", "bsp_linear_planned_fused", "bsp_mask_weights",
+                 "bsp_packed_validate", "bsp_linear", "bsp_linear_transposed", "bsp_linear_dvals", "bsp_linear_plan", "bsp_linear_planned", "bsp_linear_planned_fused",
+                 "bsp_mask_weights",
                  "bsp_group_norms_grad", "bsp_adam_step"):
         getattr(L, name).restype = C.c_int
     _LIB = L
@@ -344,6 +348,27 @@ def bsp_linear_transposed(U, p: Packed, bias=None, Z=None):
                                      _ptr(p.vals) if has else None, _ptr(bias), _ptr(Z), _stream())
     _check(st, "bsp_linear_transposed")
     return Z
+
+
+def bsp_linear_dvals(X, dY, p: Packed, out_dtype=None, D=None, ws=None):
+    """Gradient with respect to the kept weights, in the layout of p.vals: a tensor of R * p.total_cols elements."""
+    T, N = X.shape
+    if N != p.N or dY.shape != (T, p.M):
+        raise ValueError("X must be [T, N] and dY [T, M]")
+    if dY.dtype != X.dtype:
+        raise ValueError("X and dY must share one dtype")
+    out_dtype = out_dtype or X.dtype
+    if D is None:
+        D = torch.empty(p.R * p.total_cols, dtype=out_dtype, device=X.device)
+    need = lib().bsp_linear_dvals_workspace_bytes(p.M, p.N, p.R, p.total_cols)
+    if ws is None:
+        ws = torch.empty(max(need, 256), dtype=torch.uint8, device=X.device)
+    has = p.total_cols > 0
+    st = lib().bsp_linear_dvals(_ptr(X), _ptr(dY), _DT[X.dtype], T, p.M, p.N, p.R, p.k_align, _ptr(p.blk_cnt),
+                                _ptr(p.blk_ptr), _ptr(p.col_idx) if has else None, p.total_cols,
+                                _ptr(D) if has else None, _DT[D.dtype], _ptr(ws), ws.numel(), _stream())
+    _check(st, "bsp_linear_dvals")
+    return D
 
 
 def bsp_linear_plan_supported(dtype, N, k_align) -> bool:

@@ -9,7 +9,7 @@ INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libbsp.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 SOURCES = ["bsp_api.hip", "bsp_norms.hip", "bsp_mask.hip", "bsp_pack.hip", "bsp_linear.hip", "bsp_linear_tiled.hip", "bsp_linear_steploop.hip", "bsp_linear_stream16.hip",
-           "bsp_plan.hip", "bsp_adam.hip", "bsp_linear_t.hip"]
+           "bsp_plan.hip", "bsp_adam.hip", "bsp_linear_t.hip", "bsp_linear_dvals.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off", "-fno-fast-math",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

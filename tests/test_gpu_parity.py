@@ -651,6 +651,99 @@ def test_config4_bert_large_layer_set_transposed(R):
                        T_rows=None if R == 16 else [(0, 40), (5000, 5030), (T - 12, T)])   # R = 16: every token row
 
 
+# ------------------------------------------------------------------------------ the weight gradient
+def run_dvals(X, dY, W, R, keep, k_align, dtype, gdt=None):
+    """bsp_linear_dvals against the oracle on the same storage: kept positions to the layer's tolerance (one rounding
+    of an fp32 / fp64 sum to gdt), pad slots exactly +0."""
+    gdt = gdt or dtype
+    p_ref = orc.pack(W, R, keep, k_align, CODE[dtype])
+    p = bsp.bsp_pack(dev(W, dtype), R, torch.from_numpy(np.ascontiguousarray(keep)).cuda(), k_align)
+    pack_equal(p, p_ref)
+    D = bsp.bsp_linear_dvals(dev(X, dtype), dev(dY, dtype), p, out_dtype=TDT[gdt])
+    D_ref, _ = orc.linear_dvals(X, dY, p_ref, gdt=CODE[gdt], n_threads=16)
+    D = host(D)
+    assert D.shape == D_ref.shape == (R * int(p_ref["blk_ptr"][-1]),)
+    if D.size:
+        assert_y_close(D, D_ref, gdt)
+    ptr, cnt = p_ref["blk_ptr"], p_ref["blk_cnt"]
+    for b in range(len(cnt)):                            # pad slots: +0, whatever X and dY hold
+        kp = int(ptr[b + 1] - ptr[b])
+        panel = D[R * int(ptr[b]):R * int(ptr[b + 1])].reshape(R, kp)
+        assert bits_equal(panel[:, int(cnt[b]):], np.zeros((R, kp - int(cnt[b])), np.float32))
+    return D, p
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
+@pytest.mark.parametrize("R,T,M,N,p_keep,k_align", [
+    (16, 100, 64, 200, 0.5, 32), (16, 257, 320, 1024, 0.2, 32), (8, 70, 40, 332, 0.2, 8), (32, 130, 96, 256, 0.33, 16),
+    (64, 33, 128, 96, 0.4, 64), (16, 64, 48, 2048, 0.25, 32), (24, 90, 48, 1000, 0.3, 1), (16, 31, 512, 1100, 0.05, 32),
+    (4, 33, 36, 516, 0.6, 8), (3, 65, 12, 100, 0.7, 1), (16, 300, 32, 4096, 0.9, 32), (40, 50, 80, 260, 0.4, 8)])
+def test_linear_dvals_small_shapes(dtype, R, T, M, N, p_keep, k_align):
+    """Block heights with one to four 16-row slabs and half a slab, widths of one to four column ranges with a ragged
+    last range, ragged token tiles, an empty and a dense row-block (several items), both kernels (fp32 inputs and
+    the odd block heights take the plain one)."""
+    d = wl.layer(R * 1000 + T + 11, T, M, N, dtype)
+    dY = wl.normal(R * 79 + T, (T, M), 1.0, dtype)
+    keep = wl.bernoulli_keep_mask(T + N + 3, M // R, N, p_keep)
+    keep[0, :] = 0
+    if M // R > 1:
+        keep[1, :] = 1
+    run_dvals(d["X"], dY, d["W"], R, keep, k_align, dtype)
+    if dtype != "f32":
+        run_dvals(d["X"], dY, d["W"], R, keep, k_align, dtype, gdt="f32")   # the sums themselves, unrounded
+
+
+def test_linear_dvals_seeded_random_shapes():
+    rng = np.random.default_rng(4242)
+    for it in range(40):
+        R = int(rng.choice([16, 16, 16, 32, 8, 64, 48, 24]))
+        B = int(rng.integers(1, 60))
+        M = R * B
+        N = int(rng.choice([32, 64, 200, 256, 520, 768, 1000, 1024, 1028, 2048, 3000, 4096]))
+        T = int(rng.integers(1, 700))
+        dt = str(rng.choice(["bf16", "f16"]))
+        p_keep = float(rng.choice([0.02, 0.2, 0.5, 0.95]))
+        k_align = int(rng.choice([1, 8, 16, 32, 64]))
+        W = wl.normal(12000 + it, (M, N), 0.02, dt)
+        X = wl.normal(13000 + it, (T, N), 1.0, dt)
+        dY = wl.normal(14000 + it, (T, M), 1.0, dt)
+        keep = wl.bernoulli_keep_mask(16000 + it, B, N, p_keep)
+        if it % 7 == 0:
+            keep[int(rng.integers(0, B))] = 0
+        if it % 11 == 0:
+            keep[:] = 0
+        case = dict(it=it, R=R, B=B, N=N, T=T, dt=dt, p=p_keep, k_align=k_align)
+        try:
+            run_dvals(X, dY, W, R, keep, k_align, dt, gdt="f32" if it % 3 == 0 else None)
+        except AssertionError as e:
+            raise AssertionError(f"{case}: {e}")
+
+
+def test_linear_dvals_same_bits_twice_and_is_the_gradient_of_the_layer():
+    T, M, N, R = 1000, 256, 1024, 16
+    d = wl.layer(414, T, M, N, "bf16")
+    dY = wl.normal(415, (T, M), 1.0, "bf16")
+    keep = wl.bernoulli_keep_mask(416, M // R, N, 0.3)
+    D, p = run_dvals(d["X"], dY, d["W"], R, keep, 32, "bf16", gdt="f32")
+    D2 = host(bsp.bsp_linear_dvals(dev(d["X"], "bf16"), dev(dY, "bf16"), p, out_dtype=torch.float32))
+    assert bits_equal(D, D2)
+    # <dY, layer(X; V)> = <V, D> for the panel values V of the storage (pads are zero on both sides)
+    Y = bsp.bsp_linear(dev(d["X"], "bf16"), p, None).double().cpu().numpy()
+    lhs = float((Y * dY).sum())
+    V = p.vals.double().cpu().numpy()
+    rhs = float((V * D.astype(np.float64)).sum())
+    assert abs(lhs - rhs) <= 2e-3 * float(np.abs(Y * dY).sum())      # Y carries one bf16 rounding per output
+
+
+def test_config4_bert_large_layer_set_dvals():
+    """The weight gradient of every BERT-large matrix at the benchmark's size (8192 tokens, 5x), every kept position."""
+    for i, d in enumerate(wl.config4(R=16)):
+        W = d["W"]
+        k_ref, _ = orc.mask_rank(orc.sumsq(W, 16), d["n_keep"], orc.SCOPE_MATRIX)
+        dY = wl.normal(7100 + i, (d["X"].shape[0], W.shape[0]), 1.0, "bf16")
+        run_dvals(d["X"], dY, W, 16, k_ref, 32, "bf16")
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_linear_keep_all_is_dense_gemm_keep_none_is_bias(dtype):
     d = wl.layer(77, 96, 64, 160, dtype)
