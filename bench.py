@@ -403,6 +403,62 @@ def transposed_product(mats, reps=10, with_cpu=True):
     return res
 
 
+def weight_gradient(mats, reps=10, with_cpu=True):
+    """The gradient with respect to the kept weights, D = dY^T X on the kept positions (Alg. 2's weight update), on
+    the same four compact storages: dY is a synthetic [tokens, M] bf16 tensor, bf16 output in the layout of the value
+    panels, every call (three launches: item list, partial sums, ordered sum) between two events on the launch stream.
+    Algorithmic bytes: X and dY read once, the column indices read once, D written once."""
+    out, tot_us, tot_flops, hbm_bytes = {}, 0.0, 0.0, 0.0
+    for m in mats:
+        gen = torch.Generator(device="cuda").manual_seed(5200 + m.M + m.N)   # seeded: the stand-in for an output gradient
+        dY = torch.randn((m.T, m.M), device="cuda", generator=gen).to(torch.bfloat16)
+        padded = int(m.blk_ptr[-1].item())
+        D = torch.empty(m.R * padded, dtype=torch.bfloat16, device="cuda")
+        ws = torch.empty(bsp.lib().bsp_linear_dvals_workspace_bytes(m.M, m.N, m.R, m.capacity), dtype=torch.uint8,
+                         device="cuda")
+        for _ in range(3):
+            bsp.bsp_linear_dvals(m.X, dY, m.packed, D=D, ws=ws)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            bsp.bsp_linear_dvals(m.X, dY, m.packed, D=D, ws=ws)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / reps * 1e3
+        by = 2.0 * m.T * m.N + 2.0 * m.T * m.M + 2.0 * m.R * padded + 4.0 * padded
+        tf = m.useful_flops() / us / 1e6
+        hbm_bytes += by
+        out[m.name] = {"shape": [m.M, m.N], "us": round(us, 1), "useful_tflops": round(tf, 2),
+                       "frac_mfma_peak": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
+                       "hbm_gbs": round(by / us / 1e3, 1), "frac_hbm_peak": round(by / us / 1e3 / HBM_PEAK_GBS, 4)}
+        tot_us += us
+        tot_flops += m.useful_flops()
+        del dY, D, ws
+    res = {"kernels": ["dvals_items_kernel", "dvals_partial_kernel", "dvals_reduce_kernel"], "per_matrix": out,
+           "us": round(tot_us, 1), "useful_tflops": round(tot_flops / tot_us / 1e6, 2),
+           "frac_mfma_peak": round(tot_flops / tot_us / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4),
+           "roofline": {"bound": "hbm", "achieved": round(hbm_bytes / tot_us / 1e3, 1), "peak": HBM_PEAK_GBS,
+                        "unit": "GB/s", "frac": round(hbm_bytes / tot_us / 1e3 / HBM_PEAK_GBS, 4), "traffic": None}}
+    if with_cpu:
+        from oracle import bsp_oracle as orc
+        m = mats[1]
+        cores = min(len(os.sched_getaffinity(0)), 16)
+        p = orc.pack(m.W.float().cpu().numpy(), m.R, m.keep.cpu().numpy(), m.k_align, orc.BF16)
+        rows = 2048
+        rng = np.random.default_rng(2)
+        X1 = rng.standard_normal((rows, m.N)).astype(np.float32)
+        dY1 = rng.standard_normal((rows, m.M)).astype(np.float32)
+        t = time.perf_counter()
+        orc.linear_dvals(X1, dY1, p, gdt=orc.BF16, n_threads=cores)
+        secs = time.perf_counter() - t
+        res["cpu_oracle"] = {"value": round(2.0 * rows * m.R * int(p["blk_cnt"].sum()) / secs / 1e12, 5),
+                             "unit": "TFLOP/s", "cores": cores,
+                             "sample": f"oracle weight gradient (fp64, OpenMP over row-blocks), {rows} token rows of "
+                                       f"the {m.name} matrix, {secs:.2f} s"}
+    return res
+
+
 def prune_path_c5(layers=24, reps=5, with_cpu=True):
     """HBM rate of the pruning pipeline on the 24-layer BERT-large weight set (fp32, 302 M parameters, R = 16):
     group norms + reweighting factors, regulariser gradient, one global percentile over all 18.9 M groups (5x),
@@ -620,8 +676,9 @@ def main():
     ap.add_argument("--no-grid", action="store_true",
                     help="skip the layer-only table over BERT-base / BERT-large shapes and compression rates")
     ap.add_argument("--no-transposed", action="store_true",
-                    help="skip the timing of the transposed product (input gradient) on the same storages")
-    ap.add_argument("--only", choices=["layer", "transposed"], default=None,
+                    help="skip the timing of the transposed product (input gradient) and of the weight gradient on the same "
+                         "storages")
+    ap.add_argument("--only", choices=["layer", "transposed", "dvals"], default=None,
                     help="run nothing but the layer launches (or the transposed product's) of the workload, `--steps` "
                          "times in turn: the command the kernel profiles under profiles/ are taken with")
     ap.add_argument("--no-sets", action="store_true",
@@ -653,6 +710,10 @@ def main():
     if args.only == "layer":
         ms = time_layers(mats, args.steps, args.warmup).mean(axis=0)
         print(json.dumps({"only": "layer", "block_rows": args.R, "per_matrix": per_matrix_report(mats, ms)}))
+        return
+    if args.only == "dvals":
+        print(json.dumps({"only": "dvals", "block_rows": args.R,
+                          "weight_gradient": weight_gradient(mats, reps=args.steps, with_cpu=False)}))
         return
     if args.only == "transposed":
         print(json.dumps({"only": "transposed", "block_rows": args.R,
@@ -790,6 +851,7 @@ def main():
         out["linear_grid"] = linear_grid()
     if not args.no_transposed:
         out["transposed_product"] = transposed_product(mats, with_cpu=not args.no_cpu_baseline)
+        out["weight_gradient"] = weight_gradient(mats, with_cpu=not args.no_cpu_baseline)
     if not args.no_c5:
         del mats
         torch.cuda.empty_cache()

@@ -31,6 +31,7 @@ constexpr int kDvThreads = kDvWaves * kWave;
 constexpr int kDvXUnits = 2048 / kDvThreads;  // units of 4 columns x 4 tokens a thread copies per tile
 constexpr int kDvGroups = 16;            // groups of 16 kept columns per item
 constexpr int kDvReduceThreads = kDvGroups * kWave;  // the second pass: one wavefront per group of an item
+constexpr int kDvQuads = kDvGroups / 4;
 constexpr int kDvItemCols = kDvGroups * 16;
 constexpr int kDvItemFloats = kDvGroups * 256;
 constexpr uint32_t kDvXBytes = kDvRange * 64;     // 64 KiB
@@ -59,10 +60,12 @@ inline int64_t dv_max_units(int64_t max_items) { return max_items / 16 > kDvUnit
 // one lane of the copy-in holds (c .. c + 3) lie 8 rows apart, so that the lanes of a wavefront, which hold
 // consecutive column quads, write consecutive rows.
 __device__ __forceinline__ uint32_t dv_row(uint32_t c) { return (c & ~31u) | ((c >> 2) & 7u) | ((c & 3u) << 3); }
-// byte offset of tokens 8 kg .. 8 kg + 7 of column c: the four 16-byte pieces of a row rotate with the column's
-// group of 32, which spreads the copy-in's stores over the banks
+// byte offset of tokens 8 kg .. 8 kg + 7 of column c: the four 16-byte pieces of a row rotate with bits 4 to 6 of the
+// column, so that 16 consecutive lanes of the copy-in (16 consecutive column quads, one 8-byte store each) fall
+// into 16 different 16-byte bank groups
 __device__ __forceinline__ uint32_t dv_x_offset(uint32_t c, uint32_t kg) {
-    return dv_row(c) * 64u + ((kg ^ ((c >> 5) & 3u)) << 4);
+    const uint32_t sw = ((c >> 5) & 3u) ^ (((c >> 4) & 1u) << 1);
+    return dv_row(c) * 64u + ((kg ^ sw) << 4);
 }
 
 __device__ __forceinline__ int dv_lower_bound(const int32_t *a, int n, int v) {  // first i with a[i] >= v
@@ -162,7 +165,12 @@ __global__ __launch_bounds__(kDvThreads) void dvals_partial_kernel(const uint16_
     // 4 p4 .. 4 p4 + 3; the second read takes the token 4 further on)
     const uint32_t a_off = kDvXBytes + (uint32_t)(8 * kg + qd) * 32u + (uint32_t)p4 * 8u;
 
-    for (int unit = blockIdx.x; unit < strips * S; unit += gridDim.x) {
+    // Workgroup ids go round the 8 XCDs (each with an L2 of its own): the units of one XCD are consecutive, so the
+    // strips of one range of tokens, which read the same rows of X, mostly share an L2.
+    const int total_units = strips * S, per_xcd = (total_units + 7) / 8;
+    for (int u0 = blockIdx.x; u0 < per_xcd * 8; u0 += gridDim.x) {
+        const int unit = (u0 & 7) * per_xcd + (u0 >> 3);
+        if (unit >= total_units) continue;  // (the same for the whole workgroup)
         const int strip = unit % strips, s = unit / strips;
         int ncols[kDvPerWave], ng[kDvPerWave];
         int64_t row0[kDvPerWave];
@@ -262,28 +270,38 @@ __global__ __launch_bounds__(kDvThreads) void dvals_partial_kernel(const uint16_
             commit();
             __syncthreads();
             if (tile + 1 < tile1) issue_tile(tile + 1);
-            static_for<0, kDvPerWave>([&](auto I) {
-                if (ng[I.value] > 0) {
-                    const uint32_t ao = a_off + (uint32_t)(kDvPerWave * wave + I.value) * 1024u;
-                    const uint2 lo = tr_read(smem_x, ao);
-                    const uint2 hi = tr_read(smem_x, ao + 4 * 32);
-                    const uint4 a = make_uint4(lo.x, lo.y, hi.x, hi.y);
-                    // four groups at a time: their reads are issued together and a group past the item's last one
-                    // multiplies some column into an accumulator that is never written out
-                    static_for<0, kDvGroups / 4>([&](auto Q) {
-                        if (4 * Q.value < ng[I.value]) {
-                            uint32_t w0 = xoff[I.value][2 * Q.value], w1 = xoff[I.value][2 * Q.value + 1];
-                            asm volatile("" : "+v"(w0), "+v"(w1));  // (unpacked once before the loop they cost 16 registers)
-                            const uint4 b0 = *reinterpret_cast<const uint4 *>(xt + (w0 & 0xffffu));
-                            const uint4 b1 = *reinterpret_cast<const uint4 *>(xt + (w0 >> 16));
-                            const uint4 b2 = *reinterpret_cast<const uint4 *>(xt + (w1 & 0xffffu));
-                            const uint4 b3 = *reinterpret_cast<const uint4 *>(xt + (w1 >> 16));
-                            acc[I.value][4 * Q.value] = mfma16<DT>(a, b0, acc[I.value][4 * Q.value]);
-                            acc[I.value][4 * Q.value + 1] = mfma16<DT>(a, b1, acc[I.value][4 * Q.value + 1]);
-                            acc[I.value][4 * Q.value + 2] = mfma16<DT>(a, b2, acc[I.value][4 * Q.value + 2]);
-                            acc[I.value][4 * Q.value + 3] = mfma16<DT>(a, b3, acc[I.value][4 * Q.value + 3]);
-                        }
-                    });
+            // The wavefront's groups go four at a time (a quad): the reads of the next quad are on their way while
+            // the current one is multiplied; a group past the item's last one multiplies some column into an
+            // accumulator that is never written out.
+            uint4 a[kDvPerWave];
+#pragma unroll
+            for (int i = 0; i < kDvPerWave; ++i) {
+                const uint32_t ao = a_off + (uint32_t)(kDvPerWave * wave + i) * 1024u;
+                const uint2 lo = tr_read(smem_x, ao);
+                const uint2 hi = tr_read(smem_x, ao + 4 * 32);
+                a[i] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+            }
+            uint4 bq[2][4];
+            auto read_quad = [&](auto QD, uint4(&dst)[4]) {
+                constexpr int I = QD.value / kDvQuads, Q = QD.value % kDvQuads;
+                if (4 * Q < ng[I]) {
+                    uint32_t w0 = xoff[I][2 * Q], w1 = xoff[I][2 * Q + 1];
+                    asm volatile("" : "+v"(w0), "+v"(w1));  // (unpacked once before the loop they cost 32 registers)
+                    dst[0] = *reinterpret_cast<const uint4 *>(xt + (w0 & 0xffffu));
+                    dst[1] = *reinterpret_cast<const uint4 *>(xt + (w0 >> 16));
+                    dst[2] = *reinterpret_cast<const uint4 *>(xt + (w1 & 0xffffu));
+                    dst[3] = *reinterpret_cast<const uint4 *>(xt + (w1 >> 16));
+                }
+            };
+            read_quad(std::integral_constant<int, 0>{}, bq[0]);
+            static_for<0, kDvPerWave * kDvQuads>([&](auto QD) {
+                constexpr int I = QD.value / kDvQuads, Q = QD.value % kDvQuads;
+                if constexpr (QD.value + 1 < kDvPerWave * kDvQuads)
+                    read_quad(std::integral_constant<int, QD.value + 1>{}, bq[(QD.value + 1) & 1]);
+                if (4 * Q < ng[I]) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        acc[I][4 * Q + j] = mfma16<DT>(a[I], bq[QD.value & 1][j], acc[I][4 * Q + j]);
                 }
             });
             __syncthreads();  // every wavefront is done with the tile before the next one is written
