@@ -4,6 +4,8 @@ None of these tests touches the GPU library."""
 import itertools
 import math
 
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -293,22 +295,38 @@ def test_pack_rounds_values_to_bf16():
     assert np.array_equal(pb["col_idx"], p32["col_idx"])
 
 
+def golden(name):
+    """Records of a fixture under tests/golden/: {key: [values as float lists, one per occurrence]}."""
+    out = {}
+    with open(os.path.join(os.path.dirname(__file__), "golden", name)) as f:
+        for line in f:
+            line = line.split("#")[0].split()
+            if line:
+                out.setdefault(line[0], []).append([float(v) for v in line[1:]])
+    return out
+
+
 def test_compression_rate_and_storage_accounting():
-    # Sec. 4.4: 1.428x <=> 30 % sparsity; 2.0x <=> 50 %; 5x <=> 80 %
-    assert orc.compression_rate(768, 768, 16, int(48 * 768 * 0.7)) == pytest.approx(1 / 0.7, rel=1e-3)
+    g = golden("sec4_storage_and_rates.txt")
+    # Sec. 4.2 / 4.4: 1.428x <=> 30 % sparsity; 2.0x <=> 50 %; 5x <=> 80 % (the printed pairs)
+    for sparsity, rate in g["rate_of_sparsity"]:
+        kept = int(round(48 * 768 * (1.0 - sparsity)))
+        assert orc.compression_rate(768, 768, 16, kept) == pytest.approx(rate, rel=1e-3)
     assert round(orc.compression_rate(100, 100, 10, 70 * 10), 3) == 1.429
     assert orc.compression_rate(768, 768, 16, 48 * 384) == 2.0
     assert orc.compression_rate(1000, 10, 10, 200) == 5.0
-    # Sec. 4.4 worked example: 8x8 matrix, 4 row-blocks... read as 4x4 blocks => groups of 4 weights,
-    # 16 groups, half kept: values 32 + one index/flag per group 16 = 48 words; COO 3 words per non-zero = 96
-    W = rand((8, 8)) + np.float32(3.0)
-    keep = wl.random_keep_mask(1, 2, 8, 4)
-    p = orc.pack(W, 4, keep, 1)
+    # Sec. 4.4 worked example: 8x8 matrix, 4x4 blocks => groups of 4 weights, 16 groups, half kept: the values
+    # and one index word per group against three words per non-zero in the COO format
+    (m, n), (br, _), (sp,) = g["storage_example_matrix"][0], g["storage_example_block"][0], g["storage_example_sparsity"][0]
+    m, n, br = int(m), int(n), int(br)
+    W = rand((m, n)) + np.float32(3.0)
+    keep = wl.random_keep_mask(1, m // br, n, int(n * (1.0 - sp)))
+    p = orc.pack(W, br, keep, 1)
     nnz = int(np.count_nonzero(unpack(p)))
-    assert nnz == 32 and p["vals"].size == 32
     n_groups = keep.size
-    assert p["vals"].size + n_groups == 48
-    assert 3 * nnz == 96
+    assert n_groups == g["storage_example_bsp_indices"][0][0]
+    assert p["vals"].size == nnz and nnz + n_groups == g["storage_example_bsp_words"][0][0]
+    assert 3 * nnz == g["storage_example_coo_words"][0][0]
 
 
 # --------------------------------------------------------------------------- the layer
