@@ -406,8 +406,10 @@ def transposed_product(mats, reps=10, with_cpu=True):
 def weight_gradient(mats, reps=10, with_cpu=True):
     """The gradient with respect to the kept weights, D = dY^T X on the kept positions (Alg. 2's weight update), on
     the same four compact storages: dY is a synthetic [tokens, M] bf16 tensor, bf16 output in the layout of the value
-    panels, every call (three launches: item list, partial sums, ordered sum) between two events on the launch stream.
-    Algorithmic bytes: X and dY read once, the column indices read once, D written once."""
+    panels.  `us` is a call that reuses the work list of its workspace (two launches: partial sums, ordered sum: the
+    retraining loop of Alg. 2, where the mask is fixed), `us_first_call` one that builds the list too; ten calls between
+    two events on the launch stream.  Algorithmic bytes: X and dY read once, the column indices read once, D written
+    once."""
     out, tot_us, tot_flops, hbm_bytes = {}, 0.0, 0.0, 0.0
     for m in mats:
         gen = torch.Generator(device="cuda").manual_seed(5200 + m.M + m.N)   # seeded: the stand-in for an output gradient
@@ -416,21 +418,24 @@ def weight_gradient(mats, reps=10, with_cpu=True):
         D = torch.empty(m.R * padded, dtype=torch.bfloat16, device="cuda")
         ws = torch.empty(bsp.lib().bsp_linear_dvals_workspace_bytes(m.M, m.N, m.R, m.capacity), dtype=torch.uint8,
                          device="cuda")
-        for _ in range(3):
-            bsp.bsp_linear_dvals(m.X, dY, m.packed, D=D, ws=ws)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(reps):
-            bsp.bsp_linear_dvals(m.X, dY, m.packed, D=D, ws=ws)
-        e1.record()
-        torch.cuda.synchronize()
-        us = e0.elapsed_time(e1) / reps * 1e3
+        def timed(state):
+            for _ in range(3):
+                bsp.bsp_linear_dvals(m.X, dY, m.packed, D=D, ws=ws, ws_state=bsp.DVALS_BUILD)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                bsp.bsp_linear_dvals(m.X, dY, m.packed, D=D, ws=ws, ws_state=state)
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps * 1e3
+        us_first = timed(bsp.DVALS_BUILD)
+        us = timed(bsp.DVALS_REUSE)
         by = 2.0 * m.T * m.N + 2.0 * m.T * m.M + 2.0 * m.R * padded + 4.0 * padded
         tf = m.useful_flops() / us / 1e6
         hbm_bytes += by
-        out[m.name] = {"shape": [m.M, m.N], "us": round(us, 1), "useful_tflops": round(tf, 2),
-                       "frac_mfma_peak": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
+        out[m.name] = {"shape": [m.M, m.N], "us": round(us, 1), "us_first_call": round(us_first, 1),
+                       "useful_tflops": round(tf, 2), "frac_mfma_peak": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
                        "hbm_gbs": round(by / us / 1e3, 1), "frac_hbm_peak": round(by / us / 1e3 / HBM_PEAK_GBS, 4)}
         tot_us += us
         tot_flops += m.useful_flops()

@@ -241,15 +241,20 @@ int bsp_linear_transposed(const void *U, int udt, int64_t T, int64_t M, int64_t 
  * ascending order inside a range of tokens, then the ranges in ascending order), rounded once to
  * gdt (RNE); two calls with the same arguments give the same bits.  That path needs ws: device
  * scratch of at least bsp_linear_dvals_workspace_bytes(M, N, R, capacity_cols) bytes, 256-byte
- * aligned (contents undefined before and after).  Other arguments (fp32 inputs, other R, ws ==
+ * aligned.  Its head holds a work list derived from the storage alone (not from X, dY or T):
+ * ws_state = BSP_DVALS_BUILD builds it (one more launch, 10 to 30 us), BSP_DVALS_REUSE states
+ * that the last call with this ws had the same storage and M, N, R, capacity_cols and reuses it
+ * -- the case of Alg. 2's retraining, where the mask is fixed while W is updated step after step.
+ * The rest of ws is undefined before and after.  Other arguments (fp32 inputs, other R, ws ==
  * NULL) take a plain kernel that adds fp32 products token by token.  T == 0 gives zeros.
  * Returns BSP_OK, BSP_ERR_NULL, BSP_ERR_DTYPE, BSP_ERR_SHAPE (M % R != 0, bad k_align, sizes
  * past 32-bit indices), BSP_ERR_CAPACITY (ws_bytes too small) or BSP_ERR_HIP.  The storage must
  * be well formed (bsp_packed_validate) with ascending columns inside a row-block. */
+typedef enum { BSP_DVALS_BUILD = 0, BSP_DVALS_REUSE = 1 } bsp_dvals_ws_state;
 size_t bsp_linear_dvals_workspace_bytes(int64_t M, int64_t N, int32_t R, int64_t capacity_cols);
 int bsp_linear_dvals(const void *X, const void *dY, int xdt, int64_t T, int64_t M, int64_t N, int32_t R,
                      int32_t k_align, const int32_t *blk_cnt, const int32_t *blk_ptr, const int32_t *col_idx,
-                     int64_t capacity_cols, void *D, int gdt, void *ws, size_t ws_bytes, void *stream);
+                     int64_t capacity_cols, void *D, int gdt, void *ws, size_t ws_bytes, int ws_state, void *stream);
 
 /* ---- derived operand buffer for the layer (Sec. 4.4 names "matrix reorder and compact model
  * storage" as what makes the pruned model fast; the order of the kept columns inside a

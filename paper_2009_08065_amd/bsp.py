@@ -72,7 +72,7 @@ def lib():
     L.bsp_linear_transposed.argtypes = [vp, C.c_int, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp, vp, vp]
     L.bsp_linear_dvals_workspace_bytes.argtypes = [i64, i64, i32, i64]
     L.bsp_linear_dvals_workspace_bytes.restype = sz
-    L.bsp_linear_dvals.argtypes = [vp, vp, C.c_int, i64, i64, i64, i32, i32, vp, vp, vp, i64, vp, C.c_int, vp, sz, vp]
+    L.bsp_linear_dvals.argtypes = [vp, vp, C.c_int, i64, i64, i64, i32, i32, vp, vp, vp, i64, vp, C.c_int, vp, sz, C.c_int, vp]
     L.bsp_linear_plan_supported.argtypes = [C.c_int, i64, i32]
     L.bsp_linear_plan_supported.restype = C.c_int
     L.bsp_linear_plan_bytes.argtypes = [i64, i32, i64]
@@ -350,8 +350,12 @@ def bsp_linear_transposed(U, p: Packed, bias=None, Z=None):
     return Z
 
 
-def bsp_linear_dvals(X, dY, p: Packed, out_dtype=None, D=None, ws=None):
-    """Gradient with respect to the kept weights, in the layout of p.vals: a tensor of R * p.total_cols elements."""
+DVALS_BUILD, DVALS_REUSE = 0, 1
+
+
+def bsp_linear_dvals(X, dY, p: Packed, out_dtype=None, D=None, ws=None, ws_state=DVALS_BUILD):
+    """Gradient with respect to the kept weights, in the layout of p.vals: a tensor of R * p.total_cols elements.
+    ws_state=DVALS_REUSE: ws is the workspace of an earlier call on the same storage (its work list is reused)."""
     T, N = X.shape
     if N != p.N or dY.shape != (T, p.M):
         raise ValueError("X must be [T, N] and dY [T, M]")
@@ -366,7 +370,7 @@ def bsp_linear_dvals(X, dY, p: Packed, out_dtype=None, D=None, ws=None):
     has = p.total_cols > 0
     st = lib().bsp_linear_dvals(_ptr(X), _ptr(dY), _DT[X.dtype], T, p.M, p.N, p.R, p.k_align, _ptr(p.blk_cnt),
                                 _ptr(p.blk_ptr), _ptr(p.col_idx) if has else None, p.total_cols,
-                                _ptr(D) if has else None, _DT[D.dtype], _ptr(ws), ws.numel(), _stream())
+                                _ptr(D) if has else None, _DT[D.dtype], _ptr(ws), ws.numel(), ws_state, _stream())
     _check(st, "bsp_linear_dvals")
     return D
 

@@ -46,8 +46,8 @@ struct DvItem {
     int32_t sq;     // slab | column range << 8
 };
 
-// header of the workspace, written by the item kernel: items (a multiple of 16), strips, token ranges, tiles per range
-enum { kHdrItems = 0, kHdrStrips = 1, kHdrRanges = 2, kHdrTiles = 3 };
+// header of the workspace, written by the item kernel: items (a multiple of 16), strips
+enum { kHdrItems = 0, kHdrStrips = 1 };
 
 __host__ __device__ inline int64_t dv_max_items(int64_t B, int64_t N, int32_t R, int64_t capacity_cols) {
     const int64_t nslab = (R + 15) / 16, nr = (N + kDvRange - 1) / kDvRange;
@@ -68,6 +68,15 @@ __device__ __forceinline__ uint32_t dv_x_offset(uint32_t c, uint32_t kg) {
     return dv_row(c) * 64u + ((kg ^ sw) << 4);
 }
 
+// Bank group of column c: the 16 lanes of one pass of a 16-byte LDS read are conflict-free exactly when their
+// columns differ in this number (row modulo 4, and the rotation of the row's pieces).
+__device__ __forceinline__ uint32_t dv_class(uint32_t c) {
+    const uint32_t sw = ((c >> 5) & 3u) ^ (((c >> 4) & 1u) << 1);
+    return (((c >> 2) & 3u) << 2) | sw;
+}
+// some column of bank group k (for lanes without a column)
+__device__ __forceinline__ uint32_t dv_class_column(uint32_t k) { return ((k >> 2) << 2) | ((k & 3u) << 5); }
+
 __device__ __forceinline__ int dv_lower_bound(const int32_t *a, int n, int v) {  // first i with a[i] >= v
     int lo = 0, hi = n;
     while (lo < hi) {
@@ -78,15 +87,20 @@ __device__ __forceinline__ int dv_lower_bound(const int32_t *a, int n, int v) { 
     return lo;
 }
 
-// One workgroup lists the items: column ranges in turn, row-blocks ascending inside a range, every range rounded up
-// to whole strips with fillers.
+// Lists the items: column ranges in turn, row-blocks ascending inside a range, every range rounded up to whole strips
+// with fillers.  Every workgroup of the launch builds the whole list (the same values from every one of them: the
+// list is short and a workgroup cannot wait for another), then the wavefronts of all workgroups share the second
+// part, one item at a time.
 __global__ __launch_bounds__(kDvThreads) void dvals_items_kernel(int64_t B, int32_t nslab, int32_t nr,
                                                                 const int32_t *__restrict__ blk_cnt,
                                                                 const int32_t *__restrict__ blk_ptr,
-                                                                const int32_t *__restrict__ col_idx, int32_t ntiles,
+                                                                const int32_t *__restrict__ col_idx,
                                                                 int32_t max_items, int32_t *__restrict__ hdr,
-                                                                DvItem *__restrict__ items) {
+                                                                DvItem *__restrict__ items,
+                                                                uint16_t *__restrict__ perm,
+                                                                int32_t *__restrict__ groups) {
     __shared__ int s_scan[kDvThreads];
+    __shared__ uint16_t s_perm[kDvThreads / kWave][kDvItemCols];
     const int tid = threadIdx.x;
     int run = 0;
     for (int q = 0; q < nr; ++q) {
@@ -126,21 +140,92 @@ __global__ __launch_bounds__(kDvThreads) void dvals_items_kernel(int64_t B, int3
         run = padded;
     }
     if (run > max_items) run = max_items;  // (cannot happen: max_items bounds the count)
-    if (tid == 0) {
-        const int strips = run / 16;
-        int S = 0, tpu = 1;
-        if (strips > 0) {
-            int want = kDvUnits / strips;
-            if (want < 1) want = 1;
-            if (want > ntiles) want = ntiles;
-            tpu = (ntiles + want - 1) / want;
-            S = (ntiles + tpu - 1) / tpu;
+    __syncthreads();  // the item records are complete (and visible to the whole workgroup)
+
+    // Deal every item's columns to (group, lane) slots.  The first m groups take one column of every bank group, in
+    // the lane of that number: their LDS reads are conflict-free.  Columns of bank groups that hold more than m fill
+    // the groups behind them in any order.  m is the largest number for which one group more than the item's columns
+    // need (16 at most) is enough.  perm[slot] = place of the column among the item's columns, 0xffff = none.
+    {
+        const int lane = tid & (kWave - 1), wave = tid / kWave;
+        const uint64_t below = ((uint64_t)1 << lane) - 1;
+        for (int it = blockIdx.x * (kDvThreads / kWave) + wave; it < run; it += gridDim.x * (kDvThreads / kWave)) {
+            const DvItem item = items[it];
+            if (item.ncols == 0) {  // a filler
+#pragma unroll
+                for (int e = 0; e < 4; ++e) perm[(int64_t)it * kDvItemCols + lane + kWave * e] = 0xffffu;
+                if (lane == 0) groups[it] = 0;
+                continue;
+            }
+            const int ncols = item.ncols, col0 = ((item.sq >> 8) & 0xffff) * kDvRange;
+            int cls[4], rk[4] = {0, 0, 0, 0};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int j = lane + kWave * e;
+                cls[e] = j < ncols ? (int)dv_class((uint32_t)(col_idx[item.pos0 + j] - col0)) : 16;
+            }
+            int mycnt = 0;  // lane k < 16: columns of bank group k
+            for (int k = 0; k < 16; ++k) {
+                int running = 0;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const uint64_t mask = __ballot(cls[e] == k);
+                    if (cls[e] == k) rk[e] = running + __popcll(mask & below);
+                    running += __popcll(mask);
+                }
+                if (lane == k) mycnt = running;
+            }
+            const int budget = min(16, (ncols + 15) / 16 + 1);
+            int m = 16, tail = 0;
+            for (; m >= 0; --m) {
+                int over = lane < 16 ? max(0, mycnt - m) : 0;
+#pragma unroll
+                for (int o = 1; o < 16; o <<= 1) over += __shfl_xor(over, o, kWave);
+                tail = over;  // (the same in lanes 0 .. 15; lane 0 decides)
+                tail = __shfl(tail, 0, kWave);
+                if (m + (tail + 15) / 16 <= budget) break;
+            }
+            if (m < 0) m = 0;  // (m = 0 always fits)
+            int ovf = lane < 16 ? max(0, mycnt - m) : 0, pre = ovf;  // exclusive prefix of the overflow per bank group
+#pragma unroll
+            for (int o = 1; o < 16; o <<= 1) {
+                const int up = __shfl_up(pre, o, kWave);
+                if ((lane & 15) >= o) pre += up;
+            }
+            pre -= ovf;
+            uint16_t *mine = s_perm[wave];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) mine[lane + kWave * e] = 0xffffu;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int start = __shfl(pre, cls[e] & 15, kWave);
+                if (cls[e] < 16) {
+                    const int slot = rk[e] < m ? rk[e] * 16 + cls[e] : m * 16 + start + rk[e] - m;
+                    mine[slot] = (uint16_t)(lane + kWave * e);
+                }
+            }
+            // (one wavefront's LDS operations complete in order)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) perm[(int64_t)it * kDvItemCols + lane + kWave * e] = mine[lane + kWave * e];
+            if (lane == 0) groups[it] = m + (tail + 15) / 16;
         }
-        hdr[kHdrItems] = run;
-        hdr[kHdrStrips] = strips;
-        hdr[kHdrRanges] = S;
-        hdr[kHdrTiles] = tpu;
     }
+    if (tid == 0 && blockIdx.x == 0) {
+        hdr[kHdrItems] = run;
+        hdr[kHdrStrips] = run / 16;
+    }
+}
+
+// Token ranges of a call: as many as give about kDvUnits workgroups, whole tiles each.  tiles_per_range, ranges.
+__device__ __forceinline__ void dv_ranges(int strips, int ntiles, int &tpu, int &S) {
+    tpu = 1;
+    S = 0;
+    if (strips <= 0) return;
+    int want = kDvUnits / strips;
+    if (want < 1) want = 1;
+    if (want > ntiles) want = ntiles;
+    tpu = (ntiles + want - 1) / want;
+    S = (ntiles + tpu - 1) / tpu;
 }
 
 template <int DT>
@@ -150,11 +235,15 @@ __global__ __launch_bounds__(kDvThreads) void dvals_partial_kernel(const uint16_
                                                                   const int32_t *__restrict__ col_idx,
                                                                   const int32_t *__restrict__ hdr,
                                                                   const DvItem *__restrict__ items,
+                                                                  const uint16_t *__restrict__ perm,
+                                                                  const int32_t *__restrict__ groups,
                                                                   float *__restrict__ partial) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, kg = lane >> 4, qd = (lane >> 2) & 3, p4 = lane & 3;
-    const int strips = hdr[kHdrStrips], S = hdr[kHdrRanges], tpu = hdr[kHdrTiles];
+    const int strips = hdr[kHdrStrips];
     const int ntiles = (int)((T + kDvTok - 1) / kDvTok);
+    int tpu, S;
+    dv_ranges(strips, ntiles, tpu, S);
     uint8_t *xt = smem_x;
     uint8_t *yt = smem_x + kDvXBytes;
     // as a loader of X: kDvXUnits units of 4 columns x 4 tokens; as a loader of dY: half a token's 16 rows of each of
@@ -179,19 +268,21 @@ __global__ __launch_bounds__(kDvThreads) void dvals_partial_kernel(const uint16_
         f32x4 acc[kDvPerWave][kDvGroups];
 #pragma unroll
         for (int i = 0; i < kDvPerWave; ++i) {
-            const DvItem *mine = items + (int64_t)strip * kDvStrip + kDvPerWave * wave + i;
+            const int64_t it = (int64_t)strip * kDvStrip + kDvPerWave * wave + i;
+            const DvItem *mine = items + it;
             const int ib = __builtin_amdgcn_readfirstlane(mine->b);
             const int ipos = __builtin_amdgcn_readfirstlane(mine->pos0);
             const int isq = __builtin_amdgcn_readfirstlane(mine->sq);
             ncols[i] = __builtin_amdgcn_readfirstlane(mine->ncols);
-            ng[i] = (ncols[i] + 15) >> 4;
-            col0 = (isq >> 8) * kDvRange;  // the column range is the same for all items of a strip
+            ng[i] = __builtin_amdgcn_readfirstlane(groups[it]);
+            col0 = ((isq >> 8) & 0xffff) * kDvRange;  // the column range is the same for all items of a strip
             row0[i] = (int64_t)ib * R + 16 * (isq & 0xff);
 #pragma unroll
             for (int g = 0; g < kDvGroups; ++g) {
-                const int p = 16 * g + l16;
-                const int c = p < ncols[i] ? col_idx[ipos + p] - col0 : 0;
-                const uint32_t o = dv_x_offset((uint32_t)c, (uint32_t)kg);
+                // the column dealt to this lane's slot; a lane without one reads a column of its own bank group
+                const uint32_t pj = g < ng[i] ? perm[it * kDvItemCols + 16 * g + l16] : 0xffffu;
+                const uint32_t c = pj != 0xffffu ? (uint32_t)(col_idx[ipos + (int)pj] - col0) : dv_class_column((uint32_t)l16);
+                const uint32_t o = dv_x_offset(c, (uint32_t)kg);
                 xoff[i][g >> 1] = (g & 1) ? (xoff[i][g >> 1] | (o << 16)) : o;
                 acc[i][g] = f32x4{0.f, 0.f, 0.f, 0.f};
             }
@@ -323,8 +414,10 @@ __global__ __launch_bounds__(kDvReduceThreads) void dvals_reduce_kernel(int64_t 
                                                                  const int32_t *__restrict__ blk_ptr,
                                                                  const int32_t *__restrict__ hdr,
                                                                  const DvItem *__restrict__ items,
+                                                                 const uint16_t *__restrict__ perm,
+                                                                 const int32_t *__restrict__ groups,
                                                                  const float *__restrict__ partial, int32_t max_items,
-                                                                 void *__restrict__ D) {
+                                                                 int32_t ntiles, void *__restrict__ D) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l16 = lane & 15, kg = lane >> 4;
     const int64_t id = blockIdx.x;
     if (id >= max_items) {
@@ -337,9 +430,11 @@ __global__ __launch_bounds__(kDvReduceThreads) void dvals_reduce_kernel(int64_t 
         return;
     }
     if (id >= hdr[kHdrItems]) return;
-    const int strips = hdr[kHdrStrips], S = hdr[kHdrRanges];
+    const int strips = hdr[kHdrStrips];
+    int tpu, S;
+    dv_ranges(strips, ntiles, tpu, S);
     const DvItem it = items[id];
-    if (16 * wave >= it.ncols) return;  // whole wavefronts leave
+    if (wave >= groups[id]) return;  // whole wavefronts leave: wavefront g adds group g
     const int64_t strip = id >> 4;
     const int w = (int)(id & 15);
     f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -351,9 +446,9 @@ __global__ __launch_bounds__(kDvReduceThreads) void dvals_reduce_kernel(int64_t 
     const int64_t base = blk_ptr[it.b];
     const int kp = blk_ptr[it.b + 1] - blk_ptr[it.b];
     const int slab = it.sq & 0xff;
-    const int p = 16 * wave + l16;
-    if (p >= it.ncols) return;
-    const int64_t cpos = it.pos0 - base + p;
+    const uint32_t pj = perm[id * kDvItemCols + 16 * wave + l16];  // the column dealt to this lane's slot
+    if (pj == 0xffffu) return;
+    const int64_t cpos = it.pos0 - base + (int64_t)pj;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const int r = 16 * slab + 4 * kg + j;
@@ -385,14 +480,16 @@ __global__ __launch_bounds__(256) void dvals_plain_kernel(const void *__restrict
 
 struct DvLayout {
     int64_t max_items, max_units;
-    size_t items_at, partial_at, total;
+    size_t items_at, groups_at, perm_at, partial_at, total;
 };
 DvLayout dv_layout(int64_t M, int64_t N, int32_t R, int64_t capacity_cols) {
     DvLayout L;
     L.max_items = dv_max_items(M / R, N, R, capacity_cols);
     L.max_units = dv_max_units(L.max_items);
     L.items_at = kDvHeaderBytes;
-    L.partial_at = (L.items_at + (size_t)L.max_items * sizeof(DvItem) + 255) / 256 * 256;
+    L.groups_at = (L.items_at + (size_t)L.max_items * sizeof(DvItem) + 255) / 256 * 256;
+    L.perm_at = (L.groups_at + (size_t)L.max_items * sizeof(int32_t) + 255) / 256 * 256;
+    L.partial_at = L.perm_at + (size_t)L.max_items * kDvItemCols * sizeof(uint16_t);
     L.total = L.partial_at + (size_t)L.max_units * 16 * kDvItemFloats * sizeof(float);
     return L;
 }
@@ -412,13 +509,14 @@ int dv_raise_lds(K kern, size_t lds) {
 
 template <int DT>
 int launch_partial(hipStream_t s, const void *X, const void *dY, int64_t T, int64_t M, int64_t N, int32_t R,
-                   const int32_t *col_idx, const int32_t *hdr, const DvItem *items, float *partial) {
+                   const int32_t *col_idx, const int32_t *hdr, const DvItem *items, const uint16_t *perm,
+                   const int32_t *groups, float *partial) {
     auto k = dvals_partial_kernel<DT>;
     const size_t lds = kDvXBytes + kDvYBytes;
     const int st = dv_raise_lds(k, lds);
     if (st != BSP_OK) return st;
     k<<<kDvUnits, kDvThreads, lds, s>>>((const uint16_t *)X, (const uint16_t *)dY, T, M, N, R, col_idx, hdr, items,
-                                        partial);
+                                        perm, groups, partial);
     return BSP_OK;
 }
 
@@ -435,10 +533,11 @@ extern "C" size_t bsp_linear_dvals_workspace_bytes(int64_t M, int64_t N, int32_t
 extern "C" int bsp_linear_dvals(const void *X, const void *dY, int xdt, int64_t T, int64_t M, int64_t N, int32_t R,
                                 int32_t k_align, const int32_t *blk_cnt, const int32_t *blk_ptr,
                                 const int32_t *col_idx, int64_t capacity_cols, void *D, int gdt, void *ws,
-                                size_t ws_bytes, void *stream) {
+                                size_t ws_bytes, int ws_state, void *stream) {
     if (!blk_cnt || !blk_ptr) return BSP_ERR_NULL;
     if (!valid_dtype(xdt) || !valid_dtype(gdt)) return BSP_ERR_DTYPE;
     if (T < 0 || M <= 0 || N <= 0 || R < 1 || M % R != 0 || capacity_cols < 0) return BSP_ERR_SHAPE;
+    if (ws_state != BSP_DVALS_BUILD && ws_state != BSP_DVALS_REUSE) return BSP_ERR_SHAPE;
     if (!(k_align == 1 || k_align == 8 || k_align == 16 || k_align == 32 || k_align == 64)) return BSP_ERR_SHAPE;
     if (capacity_cols == 0) return BSP_OK;  // nothing kept: D is empty
     if (!D || !col_idx || (T > 0 && (!X || !dY))) return BSP_ERR_NULL;
@@ -455,16 +554,22 @@ extern "C" int bsp_linear_dvals(const void *X, const void *dY, int xdt, int64_t 
         if (ws_bytes < L.total) return BSP_ERR_CAPACITY;
         int32_t *hdr = (int32_t *)ws;
         DvItem *items = (DvItem *)((uint8_t *)ws + L.items_at);
+        uint16_t *perm = (uint16_t *)((uint8_t *)ws + L.perm_at);
+        int32_t *groups = (int32_t *)((uint8_t *)ws + L.groups_at);
         float *partial = (float *)((uint8_t *)ws + L.partial_at);
         const int32_t nslab = (R + 15) / 16, nr = (int32_t)((N + kDvRange - 1) / kDvRange);
-        dvals_items_kernel<<<1, kDvThreads, 0, s>>>(B, nslab, nr, blk_cnt, blk_ptr, col_idx, (int32_t)ntiles,
-                                                    (int32_t)L.max_items, hdr, items);
-        const int st = xdt == BSP_BF16 ? launch_partial<BSP_BF16>(s, X, dY, T, M, N, R, col_idx, hdr, items, partial)
-                                       : launch_partial<BSP_F16>(s, X, dY, T, M, N, R, col_idx, hdr, items, partial);
+        // a wavefront per item in the second part, in at most 64 workgroups
+        int64_t lg = (L.max_items + kDvThreads / kWave - 1) / (kDvThreads / kWave);
+        lg = lg < 1 ? 1 : (lg > 64 ? 64 : lg);
+        if (ws_state == BSP_DVALS_BUILD)
+            dvals_items_kernel<<<(unsigned)lg, kDvThreads, 0, s>>>(B, nslab, nr, blk_cnt, blk_ptr, col_idx,
+                                                                   (int32_t)L.max_items, hdr, items, perm, groups);
+        const int st = xdt == BSP_BF16 ? launch_partial<BSP_BF16>(s, X, dY, T, M, N, R, col_idx, hdr, items, perm, groups, partial)
+                                       : launch_partial<BSP_F16>(s, X, dY, T, M, N, R, col_idx, hdr, items, perm, groups, partial);
         if (st != BSP_OK) return st;
         const unsigned grid = (unsigned)(L.max_items + B);
         BSP_DISPATCH_DTYPE(gdt, GDT, (dvals_reduce_kernel<GDT><<<grid, kDvReduceThreads, 0, s>>>(
-                                         B, R, blk_cnt, blk_ptr, hdr, items, partial, (int32_t)L.max_items, D)));
+                                         B, R, blk_cnt, blk_ptr, hdr, items, perm, groups, partial, (int32_t)L.max_items, (int32_t)ntiles, D)));
         return check_launch();
     }
     if (B > 0x7fffffff) return BSP_ERR_SHAPE;

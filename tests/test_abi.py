@@ -70,15 +70,16 @@ def test_host_side_argument_checks():
     assert L.bsp_linear_transposed(one, 1, 0, 16, 8, 16, 32, one, one, one, one, None, one, None) == OK  # no tokens
     assert L.bsp_linear_transposed(one, 7, 4, 16, 8, 16, 32, one, one, one, one, None, one, None) == DTYPE
     # (X, dY, xdt, T, M, N, R, k_align, blk_cnt, blk_ptr, col_idx, capacity_cols, D, gdt, ws, ws_bytes, stream)
-    assert L.bsp_linear_dvals(one, one, 1, 4, 16, 8, 16, 32, None, one, one, 32, one, 1, None, 0, None) == NULL
-    assert L.bsp_linear_dvals(one, one, 1, 4, 24, 8, 16, 32, one, one, one, 32, one, 1, None, 0, None) == SHAPE  # M % R
-    assert L.bsp_linear_dvals(one, one, 1, 4, 16, 8, 16, 5, one, one, one, 32, one, 1, None, 0, None) == SHAPE   # k_align
-    assert L.bsp_linear_dvals(one, one, 7, 4, 16, 8, 16, 32, one, one, one, 32, one, 1, None, 0, None) == DTYPE
-    assert L.bsp_linear_dvals(one, one, 1, 4, 16, 8, 16, 32, one, one, one, 32, one, 9, None, 0, None) == DTYPE
-    assert L.bsp_linear_dvals(one, one, 1, 4, 16, 8, 16, 32, one, one, None, 0, None, 1, None, 0, None) == OK    # nothing kept
-    assert L.bsp_linear_dvals(one, one, 1, 4, 16, 8, 16, 32, one, one, one, 32, None, 1, None, 0, None) == NULL  # no D
+    assert L.bsp_linear_dvals(one, one, 1, 4, 16, 8, 16, 32, None, one, one, 32, one, 1, None, 0, 0, None) == NULL
+    assert L.bsp_linear_dvals(one, one, 1, 4, 24, 8, 16, 32, one, one, one, 32, one, 1, None, 0, 0, None) == SHAPE  # M % R
+    assert L.bsp_linear_dvals(one, one, 1, 4, 16, 8, 16, 5, one, one, one, 32, one, 1, None, 0, 0, None) == SHAPE   # k_align
+    assert L.bsp_linear_dvals(one, one, 7, 4, 16, 8, 16, 32, one, one, one, 32, one, 1, None, 0, 0, None) == DTYPE
+    assert L.bsp_linear_dvals(one, one, 1, 4, 16, 8, 16, 32, one, one, one, 32, one, 9, None, 0, 0, None) == DTYPE
+    assert L.bsp_linear_dvals(one, one, 1, 4, 16, 8, 16, 32, one, one, None, 0, None, 1, None, 0, 0, None) == OK    # nothing kept
+    assert L.bsp_linear_dvals(one, one, 1, 4, 16, 8, 16, 32, one, one, one, 32, None, 1, None, 0, 0, None) == NULL  # no D
     ws = C.c_void_p(4096)
-    assert L.bsp_linear_dvals(C.c_void_p(64), C.c_void_p(64), 1, 4, 16, 8, 16, 32, one, one, one, 32, one, 1, ws, 16, None) == CAP
+    assert L.bsp_linear_dvals(C.c_void_p(64), C.c_void_p(64), 1, 4, 16, 8, 16, 32, one, one, one, 32, one, 1, ws, 16, 0, None) == CAP
+    assert L.bsp_linear_dvals(one, one, 1, 4, 16, 8, 16, 32, one, one, one, 32, one, 1, None, 0, 5, None) == SHAPE  # ws_state
     assert L.bsp_linear_dvals_workspace_bytes(3072, 1024, 16, 45000) > 256 * 16 * 4096 * 4      # 256 units of partial sums
     assert L.bsp_linear_dvals_workspace_bytes(3072, 1024, 5, 45000) == 0                         # M % R
     assert L.bsp_packed_validate(16, 8, 16, 16, None, one, one, 0, one, None) == NULL

@@ -727,6 +727,17 @@ def test_linear_dvals_same_bits_twice_and_is_the_gradient_of_the_layer():
     D, p = run_dvals(d["X"], dY, d["W"], R, keep, 32, "bf16", gdt="f32")
     D2 = host(bsp.bsp_linear_dvals(dev(d["X"], "bf16"), dev(dY, "bf16"), p, out_dtype=torch.float32))
     assert bits_equal(D, D2)
+    # the work list of a workspace serves later calls on the same storage, whatever the tokens
+    ws = torch.empty(bsp.lib().bsp_linear_dvals_workspace_bytes(M, N, R, p.total_cols), dtype=torch.uint8, device="cuda")
+    D3 = host(bsp.bsp_linear_dvals(dev(d["X"], "bf16"), dev(dY, "bf16"), p, out_dtype=torch.float32, ws=ws))
+    D4 = host(bsp.bsp_linear_dvals(dev(d["X"], "bf16"), dev(dY, "bf16"), p, out_dtype=torch.float32, ws=ws,
+                                   ws_state=bsp.DVALS_REUSE))
+    assert bits_equal(D, D3) and bits_equal(D, D4)
+    Xs, dYs = d["X"][:333], dY[:333]
+    D5 = host(bsp.bsp_linear_dvals(dev(Xs, "bf16"), dev(dYs, "bf16"), p, out_dtype=torch.bfloat16, ws=ws,
+                                   ws_state=bsp.DVALS_REUSE))
+    p_ref = orc.pack(d["W"], R, keep, 32, orc.BF16)
+    assert_y_close(D5, orc.linear_dvals(Xs, dYs, p_ref, gdt=orc.BF16, n_threads=16)[0], "bf16")
     # <dY, layer(X; V)> = <V, D> for the panel values V of the storage (pads are zero on both sides)
     Y = bsp.bsp_linear(dev(d["X"], "bf16"), p, None).double().cpu().numpy()
     lhs = float((Y * dY).sum())
