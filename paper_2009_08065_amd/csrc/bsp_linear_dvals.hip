@@ -10,12 +10,11 @@
 //
 // Work units.  The kept columns of a row-block that fall into one range of 1024 columns of X are cut into groups of
 // 16 (one matrix-core result of 16 rows x 16 columns each, fp32) and up to 16 groups of one 16-row slab of a
-// row-block form an item: what one wavefront accumulates (64 registers).  A strip is 16 consecutive items of one
-// column range: what a workgroup of 16 wavefronts accumulates while it walks a run of token tiles.  Per tile of 32
-// tokens the workgroup copies the range's columns of X into LDS transposed (64 bytes per column: a lane's operand,
-// 8 consecutive tokens of its own kept column, is one 16-byte read) and every wavefront its slab's 16 columns of dY
-// untransposed (the transposing LDS read delivers the other operand); the global loads of tile i + 1 are in flight
-// while tile i is multiplied.
+// row-block form an item: what one wavefront accumulates (64 registers).  A strip is 12 consecutive items of one
+// column range: what a workgroup accumulates while it walks a run of token tiles.  Per tile of 32 tokens the range's
+// columns of X go into LDS transposed (64 bytes per column: a lane's operand, 8 consecutive tokens of its own kept
+// column, is one 16-byte read) and the items' 16 columns of dY untransposed (the transposing LDS read delivers the
+// other operand).
 #include "bsp_common.h"
 #include "bsp_mfma_device.h"
 
@@ -24,18 +23,20 @@ namespace {
 
 constexpr int kDvTok = 32;               // tokens per tile: the contraction depth of one matrix instruction
 constexpr int kDvRange = 1024;           // columns of X a tile holds
-constexpr int kDvStrip = 16;             // items of a strip = of a workgroup
-constexpr int kDvWaves = 8;              // each with 2 items: 128 accumulator registers of the 256 a wavefront may hold
-constexpr int kDvPerWave = kDvStrip / kDvWaves;
+constexpr int kDvStrip = 12;             // items of a strip = of a workgroup: one per multiplying wavefront
+constexpr int kDvLoadWaves = 4;          // wavefronts that copy the tiles in
+constexpr int kDvWaves = kDvStrip + kDvLoadWaves;
 constexpr int kDvThreads = kDvWaves * kWave;
-constexpr int kDvXUnits = 2048 / kDvThreads;  // units of 4 columns x 4 tokens a thread copies per tile
+constexpr int kDvLoadThreads = kDvLoadWaves * kWave;
+static_assert(kDvLoadThreads == 256, "a copying thread owns 4 columns of the tile");
+constexpr int kDvYPieces = kDvStrip * 64 / kDvLoadThreads;  // 16-byte pieces of dY a copying thread moves per tile
 constexpr int kDvGroups = 16;            // groups of 16 kept columns per item
 constexpr int kDvReduceThreads = kDvGroups * kWave;  // the second pass: one wavefront per group of an item
 constexpr int kDvQuads = kDvGroups / 4;
 constexpr int kDvItemCols = kDvGroups * 16;
 constexpr int kDvItemFloats = kDvGroups * 256;
 constexpr uint32_t kDvXBytes = kDvRange * 64;     // 64 KiB
-constexpr uint32_t kDvYBytes = kDvStrip * 1024;   // 16 KiB: per item 32 tokens x 16 rows
+constexpr uint32_t kDvYBytes = kDvStrip * 1024;   // 12 KiB: per item 32 tokens x 16 rows
 constexpr int kDvUnits = 256;            // workgroups of the product: one per compute unit
 constexpr size_t kDvHeaderBytes = 256;
 
@@ -46,15 +47,17 @@ struct DvItem {
     int32_t sq;     // slab | column range << 8
 };
 
-// header of the workspace, written by the item kernel: items (a multiple of 16), strips
+// header of the workspace, written by the item kernel: items (a multiple of kDvStrip), strips
 enum { kHdrItems = 0, kHdrStrips = 1 };
 
 __host__ __device__ inline int64_t dv_max_items(int64_t B, int64_t N, int32_t R, int64_t capacity_cols) {
     const int64_t nslab = (R + 15) / 16, nr = (N + kDvRange - 1) / kDvRange;
-    const int64_t n = nslab * (capacity_cols / kDvItemCols + nr * B) + 16 * nr;
-    return (n + 15) / 16 * 16;
+    const int64_t n = nslab * (capacity_cols / kDvItemCols + nr * B) + kDvStrip * nr;
+    return (n + kDvStrip - 1) / kDvStrip * kDvStrip;
 }
-inline int64_t dv_max_units(int64_t max_items) { return max_items / 16 > kDvUnits ? max_items / 16 : kDvUnits; }
+inline int64_t dv_max_units(int64_t max_items) {
+    return max_items / kDvStrip > kDvUnits ? max_items / kDvStrip : kDvUnits;
+}
 
 // LDS row of column c (local to its range) in the transposed tile: inside every 32 columns the four columns that
 // one lane of the copy-in holds (c .. c + 3) lie 8 rows apart, so that the lanes of a wavefront, which hold
@@ -98,6 +101,7 @@ __global__ __launch_bounds__(kDvThreads) void dvals_items_kernel(int64_t B, int3
                                                                 int32_t max_items, int32_t *__restrict__ hdr,
                                                                 DvItem *__restrict__ items,
                                                                 uint16_t *__restrict__ perm,
+                                                                uint16_t *__restrict__ slotcol,
                                                                 int32_t *__restrict__ groups) {
     __shared__ int s_scan[kDvThreads];
     __shared__ uint16_t s_perm[kDvThreads / kWave][kDvItemCols];
@@ -135,7 +139,7 @@ __global__ __launch_bounds__(kDvThreads) void dvals_items_kernel(int64_t B, int3
             run += s_scan[kDvThreads - 1];
             __syncthreads();  // s_scan is rewritten by the next pass
         }
-        const int padded = (run + 15) & ~15;
+        const int padded = (run + kDvStrip - 1) / kDvStrip * kDvStrip;
         for (int i = run + tid; i < padded && i < max_items; i += kDvThreads) items[i] = DvItem{0, 0, 0, q << 8};
         run = padded;
     }
@@ -153,7 +157,10 @@ __global__ __launch_bounds__(kDvThreads) void dvals_items_kernel(int64_t B, int3
             const DvItem item = items[it];
             if (item.ncols == 0) {  // a filler
 #pragma unroll
-                for (int e = 0; e < 4; ++e) perm[(int64_t)it * kDvItemCols + lane + kWave * e] = 0xffffu;
+                for (int e = 0; e < 4; ++e) {
+                    perm[(int64_t)it * kDvItemCols + lane + kWave * e] = 0xffffu;
+                    slotcol[(int64_t)it * kDvItemCols + lane + kWave * e] = (uint16_t)dv_class_column((uint32_t)(lane & 15));
+                }
                 if (lane == 0) groups[it] = 0;
                 continue;
             }
@@ -206,13 +213,21 @@ __global__ __launch_bounds__(kDvThreads) void dvals_items_kernel(int64_t B, int3
             }
             // (one wavefront's LDS operations complete in order)
 #pragma unroll
-            for (int e = 0; e < 4; ++e) perm[(int64_t)it * kDvItemCols + lane + kWave * e] = mine[lane + kWave * e];
+            for (int e = 0; e < 4; ++e) {
+                // slotcol: the slot's column inside the range -- what the product needs; a slot without a column
+                // names a column of its lane's bank group, so that it does not disturb the others' reads
+                const int sl = lane + kWave * e;
+                const uint32_t pj = mine[sl];
+                perm[(int64_t)it * kDvItemCols + sl] = (uint16_t)pj;
+                slotcol[(int64_t)it * kDvItemCols + sl] =
+                    (uint16_t)(pj != 0xffffu ? (uint32_t)(col_idx[item.pos0 + (int)pj] - col0) : dv_class_column((uint32_t)(sl & 15)));
+            }
             if (lane == 0) groups[it] = m + (tail + 15) / 16;
         }
     }
     if (tid == 0 && blockIdx.x == 0) {
         hdr[kHdrItems] = run;
-        hdr[kHdrStrips] = run / 16;
+        hdr[kHdrStrips] = run / kDvStrip;
     }
 }
 
@@ -228,181 +243,169 @@ __device__ __forceinline__ void dv_ranges(int strips, int ntiles, int &tpu, int 
     S = (ntiles + tpu - 1) / tpu;
 }
 
+// Twelve wavefronts multiply (one item each), four copy the tiles in: a wavefront that issues a tile's loads is held
+// for as long as the load path needs to deliver them (about 2000 clocks for a tile: 45 bytes per clock and compute
+// unit), and a wavefront cannot multiply meanwhile, so the two kinds of work belong to different wavefronts.  Two tile
+// buffers in LDS, one workgroup barrier per tile: while tile i is multiplied out of one buffer, the copying
+// wavefronts write tile i + 1 into the other (every wavefront finished reading it before the barrier that ended
+// tile i - 1) and then issue the loads of tile i + 2, which have a whole tile's time to arrive.
 template <int DT>
 __global__ __launch_bounds__(kDvThreads) void dvals_partial_kernel(const uint16_t *__restrict__ X,
                                                                   const uint16_t *__restrict__ dY, int64_t T, int64_t M,
                                                                   int64_t N, int32_t R,
-                                                                  const int32_t *__restrict__ col_idx,
                                                                   const int32_t *__restrict__ hdr,
                                                                   const DvItem *__restrict__ items,
-                                                                  const uint16_t *__restrict__ perm,
+                                                                  const uint16_t *__restrict__ slotcol,
                                                                   const int32_t *__restrict__ groups,
                                                                   float *__restrict__ partial) {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l16 = lane & 15, kg = lane >> 4, qd = (lane >> 2) & 3, p4 = lane & 3;
     const int strips = hdr[kHdrStrips];
     const int ntiles = (int)((T + kDvTok - 1) / kDvTok);
     int tpu, S;
     dv_ranges(strips, ntiles, tpu, S);
-    uint8_t *xt = smem_x;
-    uint8_t *yt = smem_x + kDvXBytes;
-    // as a loader of X: kDvXUnits units of 4 columns x 4 tokens; as a loader of dY: half a token's 16 rows of each of
-    // the wavefront's own slabs
-    const int cq = tid & 255, tq0 = tid >> 8;
-    const int y_tok = lane >> 1, y_half = lane & 1;
-    // as a consumer: the lane's address inside a slab's dY rows for the transposing read (token 8 kg + qd, rows
-    // 4 p4 .. 4 p4 + 3; the second read takes the token 4 further on)
-    const uint32_t a_off = kDvXBytes + (uint32_t)(8 * kg + qd) * 32u + (uint32_t)p4 * 8u;
+    constexpr uint32_t kBuf = kDvXBytes + kDvYBytes;
+    const bool loader = wave >= kDvStrip;
+    const int ltid = tid - kDvStrip * kWave;  // as a copying thread: columns 4 ltid .. 4 ltid + 3 of the tile
 
     // Workgroup ids go round the 8 XCDs (each with an L2 of its own): the units of one XCD are consecutive, so the
     // strips of one range of tokens, which read the same rows of X, mostly share an L2.
+    // (one unit per workgroup: the launch has a workgroup for every unit a storage of this capacity can have)
     const int total_units = strips * S, per_xcd = (total_units + 7) / 8;
-    for (int u0 = blockIdx.x; u0 < per_xcd * 8; u0 += gridDim.x) {
+    {
+        const int u0 = blockIdx.x;
         const int unit = (u0 & 7) * per_xcd + (u0 >> 3);
-        if (unit >= total_units) continue;  // (the same for the whole workgroup)
+        if (u0 >= per_xcd * 8 || unit >= total_units) return;  // (the same for the whole workgroup, before any barrier)
         const int strip = unit % strips, s = unit / strips;
-        int ncols[kDvPerWave], ng[kDvPerWave];
-        int64_t row0[kDvPerWave];
-        int col0 = 0;
-        uint32_t xoff[kDvPerWave][kDvGroups / 2];  // LDS offsets of the lane's columns, two 16-bit halves per register
-        f32x4 acc[kDvPerWave][kDvGroups];
-#pragma unroll
-        for (int i = 0; i < kDvPerWave; ++i) {
-            const int64_t it = (int64_t)strip * kDvStrip + kDvPerWave * wave + i;
-            const DvItem *mine = items + it;
-            const int ib = __builtin_amdgcn_readfirstlane(mine->b);
-            const int ipos = __builtin_amdgcn_readfirstlane(mine->pos0);
-            const int isq = __builtin_amdgcn_readfirstlane(mine->sq);
-            ncols[i] = __builtin_amdgcn_readfirstlane(mine->ncols);
-            ng[i] = __builtin_amdgcn_readfirstlane(groups[it]);
-            col0 = ((isq >> 8) & 0xffff) * kDvRange;  // the column range is the same for all items of a strip
-            row0[i] = (int64_t)ib * R + 16 * (isq & 0xff);
-#pragma unroll
-            for (int g = 0; g < kDvGroups; ++g) {
-                // the column dealt to this lane's slot; a lane without one reads a column of its own bank group
-                const uint32_t pj = g < ng[i] ? perm[it * kDvItemCols + 16 * g + l16] : 0xffffu;
-                const uint32_t c = pj != 0xffffu ? (uint32_t)(col_idx[ipos + (int)pj] - col0) : dv_class_column((uint32_t)l16);
-                const uint32_t o = dv_x_offset(c, (uint32_t)kg);
-                xoff[i][g >> 1] = (g & 1) ? (xoff[i][g >> 1] | (o << 16)) : o;
-                acc[i][g] = f32x4{0.f, 0.f, 0.f, 0.f};
-            }
-        }
-
         const int tile0 = s * tpu, tile1 = tile0 + tpu < ntiles ? tile0 + tpu : ntiles;
-        uint2 xa[kDvXUnits][4];
-        uint4 ya[kDvPerWave];
-        // Addresses are a uniform base and a 32-bit byte offset per lane (32 rows of X or dY stay far below 4 GB).
-        // Columns past N and, for R = 8, the upper half of the last row-block's slab are read from the nearest valid
-        // place instead (nothing reads those LDS cells, or only into result rows that are not written); tokens
-        // past T must be zeros in both operands: only the last tile can hold some and takes the guarded loads.
-        const int cqc = col0 + 4 * cq + 4 <= N ? 4 * cq : (int)(N - col0 - 4);
-        uint32_t xv[kDvXUnits], yv[kDvPerWave];
-#pragma unroll
-        for (int k = 0; k < kDvXUnits; ++k)
-            xv[k] = 2u * ((uint32_t)(4 * (tq0 + (kDvThreads / 256) * k)) * (uint32_t)N + (uint32_t)cqc);
-#pragma unroll
-        for (int i = 0; i < kDvPerWave; ++i)
-            yv[i] = 2u * ((uint32_t)y_tok * (uint32_t)M + (row0[i] + 8 * y_half + 8 <= M ? 8u * (uint32_t)y_half : 0u));
-        auto issue = [&](int tile, auto full) {
-            const int64_t t0 = (int64_t)tile * kDvTok;
-            const int left = (int)(T - t0);  // tokens of this tile when it is the last one
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                int64_t xbase = 2 * ((t0 + i) * N + col0);
-                asm volatile("" : "+s"(xbase));  // stays a scalar: the loads take X + xbase beside the lane's 32-bit offset
-                const uint8_t *xrow = reinterpret_cast<const uint8_t *>(X) + xbase;
-#pragma unroll
-                for (int k = 0; k < kDvXUnits; ++k) {
-                    const int t = 4 * (tq0 + (kDvThreads / 256) * k) + i;
-                    xa[k][i] = (full.value || t < left) ? *reinterpret_cast<const uint2 *>(xrow + xv[k])
-                                                        : make_uint2(0u, 0u);
-                }
-            }
-#pragma unroll
-            for (int i = 0; i < kDvPerWave; ++i) {
-                int64_t ybase = 2 * (t0 * M + row0[i]);
-                asm volatile("" : "+s"(ybase));
-                const uint8_t *yrow = reinterpret_cast<const uint8_t *>(dY) + ybase;
-                ya[i] = (full.value || y_tok < left) ? *reinterpret_cast<const uint4 *>(yrow + yv[i])
-                                                     : make_uint4(0u, 0u, 0u, 0u);
-            }
-        };
-        auto issue_tile = [&](int tile) {
-            if ((int64_t)(tile + 1) * kDvTok <= T) issue(tile, std::true_type{});
-            else issue(tile, std::false_type{});
-        };
-        auto commit = [&]() {
-#pragma unroll
-            for (int k = 0; k < kDvXUnits; ++k) {
-                const uint32_t tq = (uint32_t)(tq0 + (kDvThreads / 256) * k);
-                const uint32_t c = 4u * (uint32_t)cq;
-                uint8_t *dst = xt + dv_x_offset(c, tq >> 1) + (tq & 1u) * 8u;  // columns c + 1 .. c + 3: 8, 16, 24 rows on
-                uint2 w;
-                w.x = (xa[k][0].x & 0xffffu) | (xa[k][1].x << 16);
-                w.y = (xa[k][2].x & 0xffffu) | (xa[k][3].x << 16);
-                *reinterpret_cast<uint2 *>(dst) = w;
-                w.x = (xa[k][0].x >> 16) | (xa[k][1].x & 0xffff0000u);
-                w.y = (xa[k][2].x >> 16) | (xa[k][3].x & 0xffff0000u);
-                *reinterpret_cast<uint2 *>(dst + 8 * 64) = w;
-                w.x = (xa[k][0].y & 0xffffu) | (xa[k][1].y << 16);
-                w.y = (xa[k][2].y & 0xffffu) | (xa[k][3].y << 16);
-                *reinterpret_cast<uint2 *>(dst + 16 * 64) = w;
-                w.x = (xa[k][0].y >> 16) | (xa[k][1].y & 0xffff0000u);
-                w.y = (xa[k][2].y >> 16) | (xa[k][3].y & 0xffff0000u);
-                *reinterpret_cast<uint2 *>(dst + 24 * 64) = w;
-            }
-#pragma unroll
-            for (int i = 0; i < kDvPerWave; ++i)
-                *reinterpret_cast<uint4 *>(yt + (kDvPerWave * wave + i) * 1024 + y_tok * 32 + y_half * 16) = ya[i];
-        };
+        // the column range is the same for all items of a strip
+        const int col0 = ((__builtin_amdgcn_readfirstlane(items[(int64_t)strip * kDvStrip].sq) >> 8) & 0xffff) * kDvRange;
 
-        issue_tile(tile0);
-        for (int tile = tile0; tile < tile1; ++tile) {
-            commit();
-            __syncthreads();
-            if (tile + 1 < tile1) issue_tile(tile + 1);
-            // The wavefront's groups go four at a time (a quad): the reads of the next quad are on their way while
-            // the current one is multiplied; a group past the item's last one multiplies some column into an
-            // accumulator that is never written out.
-            uint4 a[kDvPerWave];
+        if (loader) {
+            // ---------------------------------------------------------------- copying wavefronts
+            // X: the thread's 4 columns x 32 tokens, one 8-byte load per token; columns past N are read from the last
+            // valid place instead (nothing reads those LDS cells).  dY: kDvYPieces pieces of 8 rows of one token.
+            // Tokens past T must be zeros in both operands (only the last tile can hold some).
+            const int cqc = col0 + 4 * ltid + 4 <= N ? 4 * ltid : (int)(N - col0 - 4);
+            uint32_t yoff[kDvYPieces];  // byte offset of the piece from the tile's first token row of dY
+            uint32_t ydst[kDvYPieces];
 #pragma unroll
-            for (int i = 0; i < kDvPerWave; ++i) {
-                const uint32_t ao = a_off + (uint32_t)(kDvPerWave * wave + i) * 1024u;
-                const uint2 lo = tr_read(smem_x, ao);
-                const uint2 hi = tr_read(smem_x, ao + 4 * 32);
-                a[i] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+            for (int e = 0; e < kDvYPieces; ++e) {
+                const int pc = ltid + kDvLoadThreads * e, it = pc >> 6, tok = (pc & 63) >> 1, half = pc & 1;
+                const DvItem *rec = items + (int64_t)strip * kDvStrip + it;
+                const int64_t row0 = (int64_t)rec->b * R + 16 * (rec->sq & 0xff);
+                // (for R = 8 the upper half of the last row-block's slab lies past M: its rows are never written out)
+                const int64_t row = row0 + 8 * half + 8 <= M ? row0 + 8 * half : row0;
+                yoff[e] = 2u * ((uint32_t)tok * (uint32_t)M + (uint32_t)row);
+                ydst[e] = kDvXBytes + (uint32_t)it * 1024u + (uint32_t)tok * 32u + (uint32_t)half * 16u;
             }
-            uint4 bq[2][4];
-            auto read_quad = [&](auto QD, uint4(&dst)[4]) {
-                constexpr int I = QD.value / kDvQuads, Q = QD.value % kDvQuads;
-                if (4 * Q < ng[I]) {
-                    uint32_t w0 = xoff[I][2 * Q], w1 = xoff[I][2 * Q + 1];
-                    asm volatile("" : "+v"(w0), "+v"(w1));  // (unpacked once before the loop they cost 32 registers)
-                    dst[0] = *reinterpret_cast<const uint4 *>(xt + (w0 & 0xffffu));
-                    dst[1] = *reinterpret_cast<const uint4 *>(xt + (w0 >> 16));
-                    dst[2] = *reinterpret_cast<const uint4 *>(xt + (w1 & 0xffffu));
-                    dst[3] = *reinterpret_cast<const uint4 *>(xt + (w1 >> 16));
+            uint2 xa[kDvTok];
+            uint4 ya[kDvYPieces];
+            auto issue = [&](int tile) {
+                const int64_t t0 = (int64_t)tile * kDvTok;
+                const int left = (int)(T - t0 < kDvTok ? T - t0 : kDvTok);
+                const uint8_t *xrow = reinterpret_cast<const uint8_t *>(X + t0 * N + col0) + 2 * cqc;
+#pragma unroll
+                for (int t = 0; t < kDvTok; ++t) {
+                    xa[t] = t < left ? *reinterpret_cast<const uint2 *>(xrow) : make_uint2(0u, 0u);  // (t < left: uniform)
+                    xrow += 2 * N;
+                }
+                const uint8_t *yrow = reinterpret_cast<const uint8_t *>(dY + t0 * M);
+#pragma unroll
+                for (int e = 0; e < kDvYPieces; ++e) {
+                    const int tok = ((ltid + kDvLoadThreads * e) & 63) >> 1;
+                    ya[e] = tok < left ? *reinterpret_cast<const uint4 *>(yrow + yoff[e]) : make_uint4(0u, 0u, 0u, 0u);
                 }
             };
-            read_quad(std::integral_constant<int, 0>{}, bq[0]);
-            static_for<0, kDvPerWave * kDvQuads>([&](auto QD) {
-                constexpr int I = QD.value / kDvQuads, Q = QD.value % kDvQuads;
-                if constexpr (QD.value + 1 < kDvPerWave * kDvQuads)
-                    read_quad(std::integral_constant<int, QD.value + 1>{}, bq[(QD.value + 1) & 1]);
-                if (4 * Q < ng[I]) {
+            auto commit = [&](uint32_t buf) {
+                uint8_t *base = smem_x + buf * kBuf;
+                // column c + j, tokens 8 g .. 8 g + 7: the j-th 16-bit field of eight consecutive loads
 #pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        acc[I][4 * Q + j] = mfma16<DT>(a[I], bq[QD.value & 1][j], acc[I][4 * Q + j]);
+                for (int j = 0; j < 4; ++j) {
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        uint32_t w[4];
+#pragma unroll
+                        for (int h = 0; h < 4; ++h) {
+                            const uint2 lo = xa[8 * g + 2 * h], hi = xa[8 * g + 2 * h + 1];
+                            const uint32_t a = j < 2 ? lo.x : lo.y, bb = j < 2 ? hi.x : hi.y;
+                            w[h] = (j & 1) ? ((a >> 16) | (bb & 0xffff0000u)) : ((a & 0xffffu) | (bb << 16));
+                        }
+                        *reinterpret_cast<uint4 *>(base + dv_x_offset(4u * (uint32_t)ltid + (uint32_t)j, (uint32_t)g)) =
+                            make_uint4(w[0], w[1], w[2], w[3]);
+                    }
                 }
-            });
-            __syncthreads();  // every wavefront is done with the tile before the next one is written
-        }
-        static_for<0, kDvPerWave>([&](auto I) {
-            float *dst = partial + ((int64_t)unit * kDvStrip + kDvPerWave * wave + I.value) * kDvItemFloats + lane * 4;
+#pragma unroll
+                for (int e = 0; e < kDvYPieces; ++e) *reinterpret_cast<uint4 *>(base + ydst[e]) = ya[e];
+            };
+            __syncthreads();
+            issue(tile0);
+            commit(0);
+            if (tile0 + 1 < tile1) issue(tile0 + 1);
+            __syncthreads();
+            for (int tile = tile0; tile < tile1; ++tile) {
+                const uint32_t cur = (uint32_t)(tile - tile0) & 1u;
+                if (tile + 1 < tile1) {
+                    commit(cur ^ 1u);
+                    if (tile + 2 < tile1) issue(tile + 2);
+                }
+                __syncthreads();
+            }
+        } else {
+            // ---------------------------------------------------------------- multiplying wavefronts
+            const int64_t it = (int64_t)strip * kDvStrip + wave;
+            const int ng = __builtin_amdgcn_readfirstlane(groups[it]);
+            uint32_t xoff[kDvGroups / 2];  // LDS offsets of the lane's columns, two 16-bit halves per register
+            f32x4 acc[kDvGroups];
+#pragma unroll
+            for (int g = 0; g < kDvGroups; ++g) {
+                // the column dealt to this lane's slot (the list names one for empty slots too)
+                const uint32_t c = g < ng ? (uint32_t)slotcol[it * kDvItemCols + 16 * g + l16] : dv_class_column((uint32_t)l16);
+                const uint32_t o = dv_x_offset(c, (uint32_t)kg);
+                xoff[g >> 1] = (g & 1) ? (xoff[g >> 1] | (o << 16)) : o;
+                acc[g] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+            // the lane's address inside the item's dY rows for the transposing read (token 8 kg + qd, rows 4 p4 ..
+            // 4 p4 + 3; the second read takes the token 4 further on)
+            const uint32_t a_off = kDvXBytes + (uint32_t)wave * 1024u + (uint32_t)(8 * kg + qd) * 32u + (uint32_t)p4 * 8u;
+            __syncthreads();
+            __syncthreads();
+            for (int tile = tile0; tile < tile1; ++tile) {
+                const uint8_t *xt = smem_x + ((uint32_t)(tile - tile0) & 1u) * kBuf;
+                // The item's groups go four at a time (a quad): the reads of the next quad are on their way while
+                // the current one is multiplied; a group past the item's last one multiplies some column into an
+                // accumulator that is never written out.
+                const uint2 lo = tr_read(xt, a_off);
+                const uint2 hi = tr_read(xt, a_off + 4 * 32);
+                const uint4 a = make_uint4(lo.x, lo.y, hi.x, hi.y);
+                uint4 bq[2][4];
+                auto read_quad = [&](auto Q, uint4(&dst)[4]) {
+                    if (4 * Q.value < ng) {
+                        uint32_t w0 = xoff[2 * Q.value], w1 = xoff[2 * Q.value + 1];
+                        asm volatile("" : "+v"(w0), "+v"(w1));  // (unpacked once before the loop they cost 16 registers)
+                        dst[0] = *reinterpret_cast<const uint4 *>(xt + (w0 & 0xffffu));
+                        dst[1] = *reinterpret_cast<const uint4 *>(xt + (w0 >> 16));
+                        dst[2] = *reinterpret_cast<const uint4 *>(xt + (w1 & 0xffffu));
+                        dst[3] = *reinterpret_cast<const uint4 *>(xt + (w1 >> 16));
+                    }
+                };
+                read_quad(std::integral_constant<int, 0>{}, bq[0]);
+                static_for<0, kDvQuads>([&](auto Q) {
+                    if constexpr (Q.value + 1 < kDvQuads)
+                        read_quad(std::integral_constant<int, Q.value + 1>{}, bq[(Q.value + 1) & 1]);
+                    if (4 * Q.value < ng) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) acc[4 * Q.value + j] = mfma16<DT>(a, bq[Q.value & 1][j], acc[4 * Q.value + j]);
+                    }
+                });
+                __syncthreads();
+            }
+            float *dst = partial + ((int64_t)unit * kDvStrip + wave) * kDvItemFloats + lane * 4;
             static_for<0, kDvGroups>([&](auto G) {
-                if (G.value < ng[I.value]) *reinterpret_cast<f32x4 *>(dst + G.value * 256) = acc[I.value][G.value];
+                if (G.value < ng) *reinterpret_cast<f32x4 *>(dst + G.value * 256) = acc[G.value];
             });
-        });
+        }
     }
 }
 
@@ -435,11 +438,11 @@ __global__ __launch_bounds__(kDvReduceThreads) void dvals_reduce_kernel(int64_t 
     dv_ranges(strips, ntiles, tpu, S);
     const DvItem it = items[id];
     if (wave >= groups[id]) return;  // whole wavefronts leave: wavefront g adds group g
-    const int64_t strip = id >> 4;
-    const int w = (int)(id & 15);
+    const int64_t strip = id / kDvStrip;
+    const int w = (int)(id % kDvStrip);
     f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
     for (int s = 0; s < S; ++s) {
-        const float *src = partial + ((s * strips + strip) * 16 + w) * kDvItemFloats + wave * 256 + lane * 4;
+        const float *src = partial + ((s * strips + strip) * kDvStrip + w) * kDvItemFloats + wave * 256 + lane * 4;
         const f32x4 v = *reinterpret_cast<const f32x4 *>(src);
         acc = s == 0 ? v : acc + v;
     }
@@ -480,7 +483,7 @@ __global__ __launch_bounds__(256) void dvals_plain_kernel(const void *__restrict
 
 struct DvLayout {
     int64_t max_items, max_units;
-    size_t items_at, groups_at, perm_at, partial_at, total;
+    size_t items_at, groups_at, perm_at, slotcol_at, partial_at, total;
 };
 DvLayout dv_layout(int64_t M, int64_t N, int32_t R, int64_t capacity_cols) {
     DvLayout L;
@@ -489,8 +492,9 @@ DvLayout dv_layout(int64_t M, int64_t N, int32_t R, int64_t capacity_cols) {
     L.items_at = kDvHeaderBytes;
     L.groups_at = (L.items_at + (size_t)L.max_items * sizeof(DvItem) + 255) / 256 * 256;
     L.perm_at = (L.groups_at + (size_t)L.max_items * sizeof(int32_t) + 255) / 256 * 256;
-    L.partial_at = L.perm_at + (size_t)L.max_items * kDvItemCols * sizeof(uint16_t);
-    L.total = L.partial_at + (size_t)L.max_units * 16 * kDvItemFloats * sizeof(float);
+    L.slotcol_at = L.perm_at + (size_t)L.max_items * kDvItemCols * sizeof(uint16_t);
+    L.partial_at = L.slotcol_at + (size_t)L.max_items * kDvItemCols * sizeof(uint16_t);
+    L.total = L.partial_at + (size_t)L.max_units * kDvStrip * kDvItemFloats * sizeof(float);
     return L;
 }
 
@@ -509,14 +513,14 @@ int dv_raise_lds(K kern, size_t lds) {
 
 template <int DT>
 int launch_partial(hipStream_t s, const void *X, const void *dY, int64_t T, int64_t M, int64_t N, int32_t R,
-                   const int32_t *col_idx, const int32_t *hdr, const DvItem *items, const uint16_t *perm,
-                   const int32_t *groups, float *partial) {
+                   const int32_t *hdr, const DvItem *items, const uint16_t *slotcol, const int32_t *groups,
+                   float *partial, int64_t grid) {
     auto k = dvals_partial_kernel<DT>;
-    const size_t lds = kDvXBytes + kDvYBytes;
+    const size_t lds = 2 * (size_t)(kDvXBytes + kDvYBytes);  // two tile buffers, 152 KiB
     const int st = dv_raise_lds(k, lds);
     if (st != BSP_OK) return st;
-    k<<<kDvUnits, kDvThreads, lds, s>>>((const uint16_t *)X, (const uint16_t *)dY, T, M, N, R, col_idx, hdr, items,
-                                        perm, groups, partial);
+    k<<<(unsigned)grid, kDvThreads, lds, s>>>((const uint16_t *)X, (const uint16_t *)dY, T, M, N, R, hdr, items, slotcol,
+                                        groups, partial);
     return BSP_OK;
 }
 
@@ -555,6 +559,7 @@ extern "C" int bsp_linear_dvals(const void *X, const void *dY, int xdt, int64_t 
         int32_t *hdr = (int32_t *)ws;
         DvItem *items = (DvItem *)((uint8_t *)ws + L.items_at);
         uint16_t *perm = (uint16_t *)((uint8_t *)ws + L.perm_at);
+        uint16_t *slotcol = (uint16_t *)((uint8_t *)ws + L.slotcol_at);
         int32_t *groups = (int32_t *)((uint8_t *)ws + L.groups_at);
         float *partial = (float *)((uint8_t *)ws + L.partial_at);
         const int32_t nslab = (R + 15) / 16, nr = (int32_t)((N + kDvRange - 1) / kDvRange);
@@ -563,9 +568,10 @@ extern "C" int bsp_linear_dvals(const void *X, const void *dY, int xdt, int64_t 
         lg = lg < 1 ? 1 : (lg > 64 ? 64 : lg);
         if (ws_state == BSP_DVALS_BUILD)
             dvals_items_kernel<<<(unsigned)lg, kDvThreads, 0, s>>>(B, nslab, nr, blk_cnt, blk_ptr, col_idx,
-                                                                   (int32_t)L.max_items, hdr, items, perm, groups);
-        const int st = xdt == BSP_BF16 ? launch_partial<BSP_BF16>(s, X, dY, T, M, N, R, col_idx, hdr, items, perm, groups, partial)
-                                       : launch_partial<BSP_F16>(s, X, dY, T, M, N, R, col_idx, hdr, items, perm, groups, partial);
+                                                                   (int32_t)L.max_items, hdr, items, perm, slotcol, groups);
+        const int64_t pgrid = (L.max_units + 7) / 8 * 8;  // whole rounds of the 8 XCDs
+        const int st = xdt == BSP_BF16 ? launch_partial<BSP_BF16>(s, X, dY, T, M, N, R, hdr, items, slotcol, groups, partial, pgrid)
+                                       : launch_partial<BSP_F16>(s, X, dY, T, M, N, R, hdr, items, slotcol, groups, partial, pgrid);
         if (st != BSP_OK) return st;
         const unsigned grid = (unsigned)(L.max_items + B);
         BSP_DISPATCH_DTYPE(gdt, GDT, (dvals_reduce_kernel<GDT><<<grid, kDvReduceThreads, 0, s>>>(

@@ -80,7 +80,7 @@ def test_host_side_argument_checks():
     ws = C.c_void_p(4096)
     assert L.bsp_linear_dvals(C.c_void_p(64), C.c_void_p(64), 1, 4, 16, 8, 16, 32, one, one, one, 32, one, 1, ws, 16, 0, None) == CAP
     assert L.bsp_linear_dvals(one, one, 1, 4, 16, 8, 16, 32, one, one, one, 32, one, 1, None, 0, 5, None) == SHAPE  # ws_state
-    assert L.bsp_linear_dvals_workspace_bytes(3072, 1024, 16, 45000) > 256 * 16 * 4096 * 4      # 256 units of partial sums
+    assert L.bsp_linear_dvals_workspace_bytes(3072, 1024, 16, 45000) > 256 * 12 * 4096 * 4      # 256 units of partial sums
     assert L.bsp_linear_dvals_workspace_bytes(3072, 1024, 5, 45000) == 0                         # M % R
     assert L.bsp_packed_validate(16, 8, 16, 16, None, one, one, 0, one, None) == NULL
     assert L.bsp_penalty_grad_workspace_bytes(32, 300, 16) == 2 * 2 * 8
