@@ -122,6 +122,65 @@ class Matrix:
         return 2.0 * self.T * self.N + 2.0 * self.T * self.M + 2.0 * self.R * padded + 4.0 * padded + 2.0 * self.M
 
 
+def streams_on_different_queues(want=4, candidates=12):
+    """`want` streams (default priority) of which no two share a hardware queue, and what the probe saw.
+
+    HIP deals its streams to a few hardware queues (4 per process here), and two streams on one queue run their
+    kernels strictly one after the other.  Which streams share a queue is a property of the process (the order in
+    which torch and HIP created them), not of the workload, so it is found before anything is timed, with a probe that
+    knows nothing of the benchmark: a graph of 24 tiny dependent kernels takes t alone; replayed on two streams at the
+    same time it takes 1.4 to 1.8 t when they are on different queues (the launches themselves do not overlap
+    fully) and 2 t, to within 4 %, when they share one -- as two replays on one stream do, which is the yardstick:
+    a pair below 0.955 of that is on two queues.  Streams are taken in creation order, each one kept if it overlaps with
+    all those kept before."""
+    pool = [torch.cuda.Stream() for _ in range(candidates)]
+    bufs = [torch.zeros(256, device="cuda") for _ in range(2)]
+    graphs = []
+    for b in bufs:
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for _ in range(24):
+                b.add_(1.0)
+        graphs.append(g)
+
+    def timed(pairs, reps=30):
+        best = float("inf")
+        for _ in range(5):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                for g, st in pairs:
+                    with torch.cuda.stream(st):
+                        g.replay()
+            torch.cuda.synchronize()
+            best = min(best, (time.perf_counter() - t0) / reps)
+        return best
+
+    for st in pool:                      # first use of a stream (queue set-up) stays out of the timings
+        with torch.cuda.stream(st):
+            graphs[0].replay()
+    torch.cuda.synchronize()
+    alone = timed([(graphs[0], pool[0])])
+    serial = timed([(graphs[0], pool[0]), (graphs[1], pool[0])])    # one stream: one after the other by construction
+    kept, shared = [pool[0]], []
+    for i in range(1, candidates):
+        if len(kept) == want:
+            break
+        ok = all(timed([(graphs[0], k), (graphs[1], pool[i])]) < 0.955 * serial for k in kept)
+        if ok:
+            kept.append(pool[i])
+        else:
+            shared.append(i)
+    found = len(kept)
+    for st in pool:                      # fewer queues than wanted: fill up in creation order
+        if len(kept) == want:
+            break
+        if st not in kept:
+            kept.append(st)
+    return kept, {"streams_probed": candidates, "on_different_queues": found, "sharing_a_queue_with_an_earlier_one": shared,
+                  "probe_us_alone": round(alone * 1e6, 1), "probe_us_two_on_one_stream": round(serial * 1e6, 1)}
+
+
 def time_layers(mats, steps, warmup):
     """The layer launches of the set, in turn on the launch stream, each between two events: [steps, matrices] ms."""
     evs = [[[torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)] for _ in mats]
@@ -739,7 +798,7 @@ def main():
             with torch.cuda.graph(g):
                 m.whole_step()
             graphs.append(g)
-        pool = [torch.cuda.Stream() for _ in range(4)]   # default priority
+        pool, stream_probe = streams_on_different_queues(4)   # default priority
 
     def step():
         if args.launch == "eager":
@@ -765,7 +824,7 @@ def main():
         torch.cuda.synchronize()
 
     if args.launch == "overlap":
-        side_streams = pool[:4]   # always the first four streams created: no search for a lucky choice
+        side_streams = pool[:4]   # chosen by the queue probe above, before anything of the benchmark ran on them
 
     run_steps(args.warmup)
     t0 = time.perf_counter()
@@ -810,7 +869,10 @@ def main():
                                "down 1024x4096; 8192 tokens; 5x compression; matrix-scope percentile mask",
                    "block_rows": args.R, "k_align": 32, "tokens": 8192,
                    "layer_path": args.path,
-                   "launch": {"overlap": "one HIP graph per matrix, the four replayed side by side on four streams",
+                   "stream_probe": stream_probe if args.launch == "overlap" else None,
+                   "launch": {"overlap": "one HIP graph per matrix, the four replayed side by side on four streams of "
+                                         "which no two share a hardware queue (found by a probe of tiny kernels "
+                                         "before the timed region)",
                               "serial": "one HIP graph per step, matrices in turn",
                               "eager": "every kernel launched from Python"}[args.launch],
                    "step": "group_norms_grad (norms, factors and regulariser gradient in one pass) + prune_mask + "
