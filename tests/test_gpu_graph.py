@@ -32,6 +32,9 @@ def test_graph_replays_match_eager():
     plan = torch.empty(bsp.lib().bsp_linear_plan_bytes(M, R, cap), dtype=torch.uint8, device=dev)
     Y = torch.empty((T, M), dtype=torch.bfloat16, device=dev)
     Z = torch.empty((T, N), dtype=torch.bfloat16, device=dev)     # the input gradient of the layer for dY = Y
+    Yf = torch.empty((T, M), dtype=torch.bfloat16, device=dev)    # the layer with GELU in its epilogue
+    D = torch.empty(R * cap, dtype=torch.bfloat16, device=dev)    # the weight gradient for dY = Y
+    dws = torch.empty(bsp.lib().bsp_linear_dvals_workspace_bytes(M, N, R, cap), dtype=torch.uint8, device=dev)
     p = bsp.Packed(M, N, R, 32, cnt, ptr, col, vals, cap)
 
     def path():
@@ -46,21 +49,28 @@ def test_graph_replays_match_eager():
         bsp.bsp_linear_plan(p, plan=plan)
         bsp.bsp_linear_planned(X, p, plan, bias, Y=Y)
         bsp.bsp_linear_transposed(Y, p, None, Z=Z)
+        bsp.bsp_linear_planned_fused(X, p, plan, bias, act=bsp.ACT_GELU, Y=Yf)
+        # (D is as long as the storage's capacity; the call writes the R * blk_ptr[B] elements that are in use)
+        st = bsp.lib().bsp_linear_dvals(X.data_ptr(), Y.data_ptr(), bsp.BF16, T, M, N, R, 32, cnt.data_ptr(),
+                                        ptr.data_ptr(), col.data_ptr(), cap, D.data_ptr(), bsp.BF16, dws.data_ptr(),
+                                        dws.numel(), bsp.DVALS_BUILD, torch.cuda.current_stream().cuda_stream)
+        assert st == 0
 
     want = []
     for Xi in Xs:                       # eager reference (also the warm-up before capture)
         X.copy_(Xi)
         path()
         torch.cuda.synchronize()
-        want.append((Y.clone(), keep.clone(), grad.clone(), Z.clone()))
+        want.append((Y.clone(), keep.clone(), grad.clone(), Z.clone(), Yf.clone(), D[:R * int(ptr[-1])].clone()))
     g = torch.cuda.CUDAGraph()
     with torch.cuda.graph(g):
         path()
     for rep in range(2):
-        for Xi, (y_ref, k_ref, g_ref, z_ref) in zip(Xs, want):
+        for Xi, (y_ref, k_ref, g_ref, z_ref, yf_ref, d_ref) in zip(Xs, want):
             X.copy_(Xi)
             Y.zero_(); keep.zero_(); grad.zero_(); col.zero_(); plan.zero_(); Z.zero_()   # eager work between replays
+            Yf.zero_(); D.zero_(); dws.zero_()
             g.replay()
             torch.cuda.synchronize()
             assert torch.equal(Y, y_ref) and torch.equal(keep, k_ref) and torch.equal(grad, g_ref)
-            assert torch.equal(Z, z_ref)
+            assert torch.equal(Z, z_ref) and torch.equal(Yf, yf_ref) and torch.equal(D[:d_ref.numel()], d_ref)
