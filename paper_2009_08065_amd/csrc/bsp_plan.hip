@@ -63,88 +63,115 @@ __global__ __launch_bounds__(kThreads) void plan_count_kernel(const int32_t *__r
     }
 }
 
-// One workgroup with a wavefront per stream of the plan: wavefront w scans the step counts of its blocks in
-// stream order (chunk-major: all its blocks' steps of chunk 0, then chunk 1, ...).
-// steps_bq == nullptr (layers of one chunk): the count is ceil(blk_cnt / 32), taken from the storage itself.
-__global__ __launch_bounds__(kPlanWavesWide * 64) void plan_scan_kernel(const int32_t *__restrict__ steps_bq,
-                                                                    const int32_t *__restrict__ blk_cnt,
-                                                                    const int32_t *__restrict__ blk_ptr,
-                                                                    int64_t capacity_cols, int32_t B,
-                                                                    int32_t NG, int32_t nacc, int32_t nchunks,
-                                                                    int32_t paired, int32_t min_one, int32_t nfrag,
-                                                                    int32_t virt, int64_t cap_steps,
-                                                                    int32_t slack_steps, int32_t *__restrict__ wptr,
-                                                                    uint32_t *__restrict__ wfrag,
-                                                                    uint32_t *__restrict__ xoff) {
-    __shared__ int totals[kPlanWavesWide];
-    const int waves = blockDim.x >> 6;  // streams of this plan
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const int per_chunk = NG * nacc;
-    const int E = nchunks * per_chunk;  // entries of a stream: (chunk q, group g, block i of the quad)
-    int32_t *mine = wptr + (int64_t)w * (E + 1);
-    int carry = 0;
-    for (int ebase = 0; ebase < E; ebase += 64) {
-        const int e = ebase + lane;
-        // stream order: group by group, inside a group chunk by chunk, inside a chunk the run's blocks
-        const int eg = e / (nchunks * nacc), q = (e / nacc) % nchunks;
-        const int64_t b = plan_block(eg, w, e % nacc, waves, nacc, paired != 0);
-        int st = 0;
-        // (chunked plans that give every run a step give one to the runs past the layer's last row-block too, so
-        // that all streams of a group have the same shape; their step of zero weights is written below)
-        if (e < E && b >= B && steps_bq && min_one) st = 1;
-        if (e < E && b < B) {
-            // steps of a stored row-block (zero for an empty or malformed one: the same validity test as the count
-            // and fill kernels make)
-            auto stored_steps = [&](int64_t sb) {
-                if (steps_bq) return steps_bq[sb * kPlanMaxChunks + q];
-                const int base = blk_ptr[sb], kp = blk_ptr[sb + 1] - base, kb = blk_cnt[sb];
-                const bool ok = kp > 0 && kp <= kMaxKp && kb >= 0 && kb <= kp && base >= 0 &&
-                                (int64_t)base + kp <= capacity_cols;
-                return ok && kb > 0 ? (kb + 31) >> 5 : 0;
-            };
-            // (virt: B counts blocks of 16 rows, each made of the stored row-blocks 2 b and 2 b + 1)
-            st = virt ? stored_steps(2 * b) + stored_steps(2 * b + 1) : stored_steps(b);
-            // plans that give every run a step: an empty (or malformed) block gets a step of zero weights, so that
-            // a wavefront's step loop never meets a block without steps
-            if (min_one && st == 0) st = 1;
-        }
-        int incl = st;
+// What fixes the order and the sizes of a plan's streams.
+struct PlanShape {
+    const int32_t *steps_bq;  // steps per (stored row-block, chunk) of a chunked plan, else nullptr
+    const int32_t *blk_cnt, *blk_ptr;
+    int64_t capacity_cols;
+    int32_t B, NG, nacc, nchunks, paired, min_one, virt, waves;
+    __device__ int entries() const { return nchunks * NG * nacc; }  // of a stream: (group g, chunk q, block i of the run)
+};
+
+// Steps of entry e of stream w.  Stream order: group by group, inside a group chunk by chunk, inside a chunk the
+// run's blocks.
+__device__ inline int plan_entry_steps(const PlanShape &P, int w, int e) {
+    const int eg = e / (P.nchunks * P.nacc), q = (e / P.nacc) % P.nchunks;
+    const int64_t b = plan_block(eg, w, e % P.nacc, P.waves, P.nacc, P.paired != 0);
+    // (chunked plans that give every run a step give one to the runs past the layer's last row-block too, so
+    // that all streams of a group have the same shape; their step of zero weights is written by the scan)
+    if (b >= P.B) return (P.steps_bq && P.min_one) ? 1 : 0;
+    // steps of a stored row-block (zero for an empty or malformed one: the same validity test as the count
+    // and fill kernels make)
+    auto stored_steps = [&](int64_t sb) {
+        if (P.steps_bq) return P.steps_bq[sb * kPlanMaxChunks + q];
+        const int base = P.blk_ptr[sb], kp = P.blk_ptr[sb + 1] - base, kb = P.blk_cnt[sb];
+        const bool ok = kp > 0 && kp <= kMaxKp && kb >= 0 && kb <= kp && base >= 0 &&
+                        (int64_t)base + kp <= P.capacity_cols;
+        return ok && kb > 0 ? (kb + 31) >> 5 : 0;
+    };
+    // (virt: B counts blocks of 16 rows, each made of the stored row-blocks 2 b and 2 b + 1)
+    int st = P.virt ? stored_steps(2 * b) + stored_steps(2 * b + 1) : stored_steps(b);
+    // plans that give every run a step: an empty (or malformed) block gets a step of zero weights, so that
+    // a wavefront's step loop never meets a block without steps
+    if (P.min_one && st == 0) st = 1;
+    return st;
+}
+
+// The step where entry `ee` of stream `ew` starts: the steps of all streams before it and of the entries before it in
+// its own stream, added up by the whole workgroup (every thread must call; the plan's streams hold a few hundred
+// entries in all).  The workgroups that fill the plan find their places this way instead of waiting for the table.
+__device__ inline int plan_start(const PlanShape &P, int ew, int ee) {
+    __shared__ int s_part[kThreads / 64];
+    const int E = P.entries();
+    int acc = 0;
+    for (int idx = threadIdx.x; idx < ew * E + ee; idx += blockDim.x) acc += plan_entry_steps(P, idx / E, idx % E);
 #pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const int up = __shfl_up(incl, o, 64);
-            if (lane >= o) incl += up;
-        }
-        if (e < E) mine[e] = carry + incl - st;
-        carry += __shfl(incl, 63, 64);
-    }
-    if (lane == 0) {
-        mine[E] = carry;
-        totals[w] = carry;
-    }
+    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+    __syncthreads();  // (s_part may still be read from an earlier call)
+    if ((threadIdx.x & 63) == 0) s_part[threadIdx.x >> 6] = acc;
     __syncthreads();
-    int wbase = 0;
-    for (int k = 0; k < w; ++k) wbase += totals[k];
-    __syncthreads();  // the stores above are visible to the whole workgroup now
-    for (int e = lane; e <= E; e += 64) mine[e] += wbase;
-    if (steps_bq && min_one) {
-        __syncthreads();
-        // (such runs can only be in the last group: its entries close the stream)
-        for (int e = max(0, E - nchunks * nacc); e < E; ++e) {  // uniform over the wavefront
-            const int eg = e / (nchunks * nacc);
-            if (plan_block(eg, w, e % nacc, waves, nacc, paired != 0) < B) continue;
-            const int64_t gs = mine[e];
-            if (gs < 0 || gs + 1 > cap_steps) continue;
-            for (int f = 0; f < nfrag; ++f)
-                *reinterpret_cast<uint4 *>(wfrag + (gs * nfrag + f) * 256 + lane * 4) = make_uint4(0u, 0u, 0u, 0u);
-            if (lane < 16) xoff[gs * 16 + lane] = 0u;
+    int total = 0;
+    for (int k = 0; k < (int)(blockDim.x >> 6); ++k) total += s_part[k];
+    return total;
+}
+
+// The table of the streams, by one workgroup (its wavefronts take the streams in turn): wptr[w][e] = first step of
+// entry e of stream w, wptr[w][E] = end of stream w; the zero steps of runs past the layer's end; valid offsets for
+// the steps a layer kernel reads past the end of the last stream.
+__device__ inline void plan_write_table(const PlanShape &P, int32_t nfrag, int64_t cap_steps, int32_t slack_steps,
+                                        int32_t *__restrict__ wptr, uint32_t *__restrict__ wfrag,
+                                        uint32_t *__restrict__ xoff) {
+    __shared__ int totals[kPlanWavesWide];
+    const int waves = P.waves, nw = blockDim.x >> 6;  // streams of the plan, wavefronts of this workgroup
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int E = P.entries();
+    for (int w = wv; w < waves; w += nw) {
+        int32_t *mine = wptr + (int64_t)w * (E + 1);
+        int carry = 0;
+        for (int ebase = 0; ebase < E; ebase += 64) {
+            const int e = ebase + lane;
+            const int st = e < E ? plan_entry_steps(P, w, e) : 0;
+            int incl = st;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const int up = __shfl_up(incl, o, 64);
+                if (lane >= o) incl += up;
+            }
+            if (e < E) mine[e] = carry + incl - st;
+            carry += __shfl(incl, 63, 64);
+        }
+        if (lane == 0) {
+            mine[E] = carry;
+            totals[w] = carry;
         }
     }
-    // the layer kernel reads a few steps past the end of the last stream: give those steps the
-    // LDS offset 0 (their values are never used, but the addresses must be valid)
-    if (w == waves - 1) {
-        const int64_t total = (int64_t)wbase + carry;
-        if (total + slack_steps <= cap_steps)
-            for (int i = lane; i < slack_steps * 16; i += 64) xoff[total * 16 + i] = 0u;
+    __syncthreads();  // (the stores above are visible to the whole workgroup now)
+    for (int w = wv; w < waves; w += nw) {
+        int32_t *mine = wptr + (int64_t)w * (E + 1);
+        int wbase = 0;
+        for (int k = 0; k < w; ++k) wbase += totals[k];
+        for (int e = lane; e <= E; e += 64) mine[e] += wbase;
+        if (P.steps_bq && P.min_one) {
+            // (runs past the layer's end can only be in the last group: its entries close the stream)
+            for (int e = max(0, E - P.nchunks * P.nacc); e < E; ++e) {  // uniform over the wavefront
+                const int eg = e / (P.nchunks * P.nacc);
+                if (plan_block(eg, w, e % P.nacc, waves, P.nacc, P.paired != 0) < P.B) continue;
+                // where the entry starts: the stream's base and the steps of its entries before it (a handful)
+                int64_t gs = wbase;
+                for (int k = 0; k < e; ++k) gs += plan_entry_steps(P, w, k);
+                if (gs < 0 || gs + 1 > cap_steps) continue;
+                for (int f = 0; f < nfrag; ++f)
+                    *reinterpret_cast<uint4 *>(wfrag + (gs * nfrag + f) * 256 + lane * 4) = make_uint4(0u, 0u, 0u, 0u);
+                if (lane < 16) xoff[gs * 16 + lane] = 0u;
+            }
+        }
+        // the layer kernel reads a few steps past the end of the last stream: give those steps the
+        // LDS offset 0 (their values are never used, but the addresses must be valid)
+        if (w == waves - 1) {
+            const int64_t total = (int64_t)wbase + totals[w];
+            if (total + slack_steps <= cap_steps)
+                for (int i = lane; i < slack_steps * 16; i += 64) xoff[total * 16 + i] = 0u;
+        }
     }
 }
 
@@ -155,15 +182,25 @@ __global__ __launch_bounds__(kThreads) void plan_fill_kernel(int32_t R, int32_t 
                                                              const int32_t *__restrict__ blk_ptr,
                                                              const int32_t *__restrict__ col_idx,
                                                              const uint16_t *__restrict__ vals, int64_t capacity_cols,
-                                                             int64_t cap_steps, const int32_t *__restrict__ wptr,
+                                                             int64_t cap_steps, int32_t *__restrict__ wptr,
                                                              uint32_t *__restrict__ wfrag, uint32_t *__restrict__ xoff,
                                                              int32_t cols_cap, int32_t waves, int32_t paired,
-                                                             int32_t min_one, int32_t virt) {
+                                                             int32_t min_one, int32_t virt, int32_t B,
+                                                             const int32_t *__restrict__ steps_bq,
+                                                             int32_t slack_steps) {
     // columns and canonical positions are below 4096 + 32: 16 bits each; 0xffff marks a pad.  The list of a
     // row-block's kept columns is sized by the launch for the layer's width (cols_cap entries).
     extern __shared__ __attribute__((aligned(16))) uint16_t cols[];
     __shared__ uint16_t slotcol[kMaxChunk], slotsrc[kMaxChunk], ovfcol[kMaxChunk], ovfsrc[kMaxChunk];
     __shared__ int s_filled[8], s_hp[9], s_novf, s_cnt[kPlanMaxChunks], s_other;
+    PlanShape P;
+    P.steps_bq = steps_bq; P.blk_cnt = blk_cnt; P.blk_ptr = blk_ptr; P.capacity_cols = capacity_cols;
+    P.B = B; P.NG = NG; P.nacc = nacc; P.nchunks = nchunks; P.paired = paired; P.min_one = min_one; P.virt = virt;
+    P.waves = waves;
+    if (blockIdx.x == gridDim.x - 1) {  // the workgroup behind the row-blocks writes the table of the streams
+        if (blockIdx.y == 0) plan_write_table(P, nfrag, cap_steps, slack_steps, wptr, wfrag, xoff);
+        return;
+    }
     const int64_t b = blockIdx.x;  // the stored row-block
     const int base = blk_ptr[b];
     const int kp = blk_ptr[b + 1] - base;
@@ -173,6 +210,11 @@ __global__ __launch_bounds__(kThreads) void plan_fill_kernel(int32_t R, int32_t 
     // virt: the plan's block pb = b / 2 has 16 rows; this stored block of 8 fills its upper (even b) or lower fragment
     // rows, and its steps follow (odd b) the steps of its partner inside the chunk
     const int64_t pb = virt ? b >> 1 : b;
+    // the step where this (block, chunk) starts in its stream
+    int64_t my_eg;
+    int my_ew, my_ei;
+    plan_entry(pb, waves, nacc, paired != 0, my_eg, my_ew, my_ei);
+    const int64_t start = plan_start(P, my_ew, (int)((my_eg * nchunks + blockIdx.y) * nacc + my_ei));
     if (threadIdx.x == 0) s_other = 0;
     __syncthreads();
     if (virt) {  // kept columns of the partner inside this chunk (zero for a malformed partner)
@@ -191,11 +233,7 @@ __global__ __launch_bounds__(kThreads) void plan_fill_kernel(int32_t R, int32_t 
     auto zero_step = [&]() {
         if (!min_one || wave != 0) return;
         if (virt && ((b & 1) || other_steps > 0)) return;
-        const int E1 = nchunks * NG * nacc;
-        int64_t eg;
-        int ew, ei;
-        plan_entry(pb, waves, nacc, paired != 0, eg, ew, ei);
-        const int64_t gs0 = wptr[(int64_t)ew * (E1 + 1) + (eg * nchunks + blockIdx.y) * nacc + ei];
+        const int64_t gs0 = start;
         if (gs0 >= 0 && gs0 + 1 <= cap_steps) {
             for (int f = 0; f < nfrag; ++f)
                 *reinterpret_cast<uint4 *>(wfrag + (gs0 * nfrag + f) * 256 + lane * 4) = make_uint4(0u, 0u, 0u, 0u);
@@ -290,11 +328,7 @@ __global__ __launch_bounds__(kThreads) void plan_fill_kernel(int32_t R, int32_t 
         }
         __syncthreads();
         // per-lane operands of the chunk's steps
-        const int E = nchunks * NG * nacc;
-        int64_t eg;
-        int ew, ei;
-        plan_entry(pb, waves, nacc, paired != 0, eg, ew, ei);
-        const int64_t gs0 = wptr[(int64_t)ew * (E + 1) + (eg * nchunks + q) * nacc + ei] + ((virt && (b & 1)) ? other_steps : 0);
+        const int64_t gs0 = start + ((virt && (b & 1)) ? other_steps : 0);
         if (gs0 < 0 || gs0 + nsteps > cap_steps) return;
         const int row0 = (virt && (b & 1)) ? 8 : 0;  // fragment row of the stored block's first row
         for (int s = wave; s < nsteps; s += kThreads / 64) {
@@ -328,8 +362,8 @@ inline int nfrag_of(int32_t R) { return R <= 16 ? 1 : (R <= 32 ? 2 : 4); }
 
 struct PlanLayout {
     int64_t NG;
-    size_t steps, wptr_bytes, wfrag_bytes, xoff_bytes;
-    size_t total() const { return wptr_bytes + wfrag_bytes + xoff_bytes; }
+    size_t steps, wptr_bytes, wfrag_bytes, xoff_bytes, cnt_bytes;
+    size_t total() const { return wptr_bytes + wfrag_bytes + xoff_bytes + cnt_bytes; }
 };
 // Sized for the worst case of kPlanMaxChunks column chunks, so that the size does not depend on N:
 // every (row-block, chunk) pads its columns to a multiple of 32 on its own.
@@ -350,6 +384,8 @@ inline PlanLayout plan_layout(int64_t M, int64_t N, int32_t R, int64_t capacity_
                    256 * 256;
     L.wfrag_bytes = L.steps * (size_t)nfrag_of(R) * 1024;
     L.xoff_bytes = L.steps * 64;
+    // step counts per (row-block, chunk) of a chunked plan: read by the workgroups that fill the plan
+    L.cnt_bytes = ((size_t)B * kPlanMaxChunks * sizeof(int32_t) + 255) / 256 * 256;
     return L;
 }
 
@@ -389,26 +425,20 @@ extern "C" int bsp_linear_plan(int vdt, int64_t M, int64_t N, int32_t R, int32_t
     const PlanChunks ch = plan_chunks(N, Re, M);
     const int32_t min_one = plan_min_one_step(Re, ch.n > 1) ? 1 : 0;
     const int32_t paired = plan_paired(Re, ch.n > 1) ? 1 : 0;
-    // step counts per (row-block, chunk) are parked at the start of the offsets region: the scan has
-    // consumed them before the fill kernel overwrites that region
-    int32_t *steps_bq = (int32_t *)xoff;
-    if ((size_t)Bs * kPlanMaxChunks * sizeof(int32_t) > L.xoff_bytes) return BSP_ERR_CAPACITY;
+    int32_t *steps_bq = (int32_t *)((uint8_t *)plan + L.wptr_bytes + L.wfrag_bytes + L.xoff_bytes);
     if (ch.n > 1)  // a layer of one chunk needs no count: its steps per row-block follow from blk_cnt
         plan_count_kernel<<<(unsigned)Bs, kThreads, 0, s>>>(blk_cnt, blk_ptr, col_idx, capacity_cols, ch.shift, ch.n,
                                                             steps_bq);
     const int32_t nacc = plan_nacc(nf, ch.n > 1, Re);
     const int waves = plan_waves(N, Re, M);
-    plan_scan_kernel<<<1, waves * 64, 0, s>>>(ch.n > 1 ? steps_bq : nullptr, blk_cnt, blk_ptr, capacity_cols,
-                                                   (int32_t)B, (int32_t)L.NG, nacc, ch.n, paired, min_one, nf,
-                                                   virt ? 1 : 0, (int64_t)L.steps, plan_slack_steps(), wptr, wfrag,
-                                                   xoff);
-    if (capacity_cols > 0 || min_one) {  // (empty row-blocks may get a step of zero weights)
-        // a row-block keeps at most N columns, padded to the alignment (at most 64)
-        const int32_t cols_cap = (int32_t)(N + 64 < kMaxKp ? (N + 64 + 7) / 8 * 8 : kMaxKp);
-        plan_fill_kernel<<<dim3((unsigned)Bs, (unsigned)ch.n), kThreads, (size_t)cols_cap * 2, s>>>(
-            R, nf, (int32_t)L.NG, nacc, ch.shift, ch.n, blk_cnt, blk_ptr, col_idx, (const uint16_t *)vals, capacity_cols,
-            (int64_t)L.steps, wptr, wfrag, xoff, cols_cap, waves, paired, min_one, virt ? 1 : 0);
-    }
+    // One launch fills the plan: a workgroup per (stored row-block, chunk), each finding its place in its stream by
+    // adding up the step counts before it, and one more that writes the table of the streams.
+    // a row-block keeps at most N columns, padded to the alignment (at most 64)
+    const int32_t cols_cap = (int32_t)(N + 64 < kMaxKp ? (N + 64 + 7) / 8 * 8 : kMaxKp);
+    plan_fill_kernel<<<dim3((unsigned)Bs + 1, (unsigned)ch.n), kThreads, (size_t)cols_cap * 2, s>>>(
+        R, nf, (int32_t)L.NG, nacc, ch.shift, ch.n, blk_cnt, blk_ptr, col_idx, (const uint16_t *)vals, capacity_cols,
+        (int64_t)L.steps, wptr, wfrag, xoff, cols_cap, waves, paired, min_one, virt ? 1 : 0, (int32_t)B,
+        ch.n > 1 ? steps_bq : nullptr, plan_slack_steps());
     return check_launch();
 }
 
