@@ -407,7 +407,7 @@ def transposed_product(mats, reps=10, with_cpu=True):
     """The transposed product Z = U Wp (input gradient of the layer; the layer of the row-segment variant on a
     transposed matrix) on the same four compact storages: U is a synthetic [tokens, M] bf16 tensor, every launch
     between two events on the launch stream.  Algorithmic bytes: U read once, Z written once, the storage read once."""
-    out, tot_us, tot_flops, lds_bytes, hbm_bytes = {}, 0.0, 0.0, 0.0, 0.0
+    out, tot_us, tot_flops, lds_bytes, hbm_bytes, tot_dense_us = {}, 0.0, 0.0, 0.0, 0.0, 0.0
     for m in mats:
         gen = torch.Generator(device="cuda").manual_seed(4200 + m.M + m.N)   # seeded: the stand-in for an output gradient
         U = torch.randn((m.T, m.M), device="cuda", generator=gen).to(torch.bfloat16)
@@ -422,6 +422,20 @@ def transposed_product(mats, reps=10, with_cpu=True):
         e1.record()
         torch.cuda.synchronize()
         us = e0.elapsed_time(e1) / reps * 1e3
+        # the same product as a dense one on the masked matrix (bsp_linear_transposed_dense: rocBLAS), which spends
+        # 1 / density times the FLOPs
+        Wm = m.W.clone()
+        bsp.bsp_mask_weights(Wm, m.R, m.keep)
+        for _ in range(3):
+            bsp.bsp_linear_transposed_dense(U, Wm, None, Z)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            bsp.bsp_linear_transposed_dense(U, Wm, None, Z)
+        e1.record()
+        torch.cuda.synchronize()
+        us_dense = e0.elapsed_time(e1) / reps * 1e3
+        del Wm
         padded = int(m.blk_ptr[-1].item())
         by = 2.0 * m.T * m.M + 2.0 * m.T * m.N + 2.0 * m.R * padded + 4.0 * padded
         tf = m.useful_flops() / us / 1e6
@@ -429,14 +443,20 @@ def transposed_product(mats, reps=10, with_cpu=True):
         lds_bytes += lds
         hbm_bytes += by
         out[m.name] = {"shape": [m.M, m.N], "us": round(us, 1), "useful_tflops": round(tf, 2),
+                       "dense_on_masked_matrix_us": round(us_dense, 1),
+                       "dense_on_masked_matrix_useful_tflops": round(m.useful_flops() / us_dense / 1e6, 1),
+                       "dense_on_masked_matrix_dense_tflops": round(m.dense_flops() / us_dense / 1e6, 1),
                        "lds_gbs": round(lds / us / 1e3, 1),
                        "frac_mfma_peak": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
                        "hbm_gbs": round(by / us / 1e3, 1), "frac_hbm_peak": round(by / us / 1e3 / HBM_PEAK_GBS, 4)}
         tot_us += us
+        tot_dense_us += us_dense
         tot_flops += m.useful_flops()
         del U, Z
     res = {"kernel": "linear_t_mfma_kernel", "per_matrix": out, "us": round(tot_us, 1),
            "useful_tflops": round(tot_flops / tot_us / 1e6, 2),
+           "dense_on_masked_matrix": {"entry_point": "bsp_linear_transposed_dense (rocBLAS)", "us": round(tot_dense_us, 1),
+                                      "useful_tflops": round(tot_flops / tot_dense_us / 1e6, 2)},
            "frac_mfma_peak": round(tot_flops / tot_us / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4),
            # the method's traffic: U read once, Z written once, the storage read once (the same pair of roofs as the layer)
            "roofline": {"bound": "hbm", "achieved": round(hbm_bytes / tot_us / 1e3, 1), "peak": HBM_PEAK_GBS,

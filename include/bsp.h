@@ -227,6 +227,18 @@ int bsp_linear_transposed(const void *U, int udt, int64_t T, int64_t M, int64_t 
                           const int32_t *blk_cnt, const int32_t *blk_ptr, const int32_t *col_idx,
                           const void *vals, const void *bias, void *Z, void *stream);
 
+/* The same product from the masked dense matrix instead of the compact storage (Sec. 3.1: dX = dY Wp
+ * with Wp the matrix after Alg. 1, i.e. W after bsp_mask_weights):
+ *   Z[t, n] = bias[n] + sum_m U[t, m] * Wm[m, n]      U: [T, M], Wm: [M, N], Z: [T, N], one dtype udt
+ * It multiplies the pruned zeros too (1 / density times the work) but as one plain dense product,
+ * which is handed to rocBLAS (fp32 accumulation, bias added in fp32, one rounding): up to about
+ * 16x compression that is the faster way on this machine.  rocBLAS is loaded on the first call (the
+ * other entry points do not need it) and, unlike them, allocates device memory of its own and keeps
+ * a handle per device; calls are serialised per process.  Returns BSP_ERR_HIP when rocBLAS cannot
+ * be loaded or fails; BSP_ERR_NULL, BSP_ERR_DTYPE, BSP_ERR_SHAPE (a size of 2^31 or more). */
+int bsp_linear_transposed_dense(const void *U, int udt, int64_t T, int64_t M, int64_t N, const void *Wm,
+                                const void *bias, void *Z, void *stream);
+
 /* ---- gradient with respect to the kept weights (Alg. 2 updates W from the gradient of the
  * loss; for the layer Y = X Wp^T + bias of Sec. 3.1 the chain rule gives
  * dW[m, j] = sum_t dY[t, m] X[t, j], and only the kept groups need it) --------------------------

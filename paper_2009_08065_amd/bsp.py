@@ -70,6 +70,7 @@ def lib():
     L.bsp_packed_validate.argtypes = [i64, i64, i32, i32, vp, vp, vp, i64, vp, vp]
     L.bsp_linear.argtypes = [vp, C.c_int, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp, vp, vp]
     L.bsp_linear_transposed.argtypes = [vp, C.c_int, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp, vp, vp]
+    L.bsp_linear_transposed_dense.argtypes = [vp, C.c_int, i64, i64, i64, vp, vp, vp, vp]
     L.bsp_linear_dvals_workspace_bytes.argtypes = [i64, i64, i32, i64]
     L.bsp_linear_dvals_workspace_bytes.restype = sz
     L.bsp_linear_dvals.argtypes = [vp, vp, C.c_int, i64, i64, i64, i32, i32, vp, vp, vp, i64, vp, C.c_int, vp, sz, C.c_int, vp]
@@ -87,7 +88,7 @@ def lib():
     L.bsp_last_hip_error.restype = C.c_int
     L.bsp_version.restype = C.c_char_p
     for name in ("bsp_group_norms", "bsp_penalty_grad", "bsp_prune_mask", "bsp_pack_count", "bsp_pack",
-                 "bsp_packed_validate", "bsp_linear", "bsp_linear_transposed", "bsp_linear_dvals", "bsp_linear_plan", "bsp_linear_planned", "bsp_linear_planned_fused",
+                 "bsp_packed_validate", "bsp_linear", "bsp_linear_transposed", "bsp_linear_transposed_dense", "bsp_linear_dvals", "bsp_linear_plan", "bsp_linear_planned", "bsp_linear_planned_fused",
                  "bsp_mask_weights",
                  "bsp_group_norms_grad", "bsp_adam_step"):
         getattr(L, name).restype = C.c_int
@@ -347,6 +348,19 @@ def bsp_linear_transposed(U, p: Packed, bias=None, Z=None):
                                      _ptr(p.blk_ptr), _ptr(p.col_idx) if has else None,
                                      _ptr(p.vals) if has else None, _ptr(bias), _ptr(Z), _stream())
     _check(st, "bsp_linear_transposed")
+    return Z
+
+
+def bsp_linear_transposed_dense(U, Wm, bias=None, Z=None):
+    """Z = U Wm (+ bias) with Wm the masked dense matrix [M, N]: the transposed product as a dense library product."""
+    T, M = U.shape
+    if Wm.shape[0] != M or Wm.dtype != U.dtype or (bias is not None and bias.dtype != U.dtype):
+        raise ValueError("U [T, M], Wm [M, N] and bias must fit and share one dtype")
+    N = Wm.shape[1]
+    if Z is None:
+        Z = torch.empty((T, N), dtype=U.dtype, device=U.device)
+    st = lib().bsp_linear_transposed_dense(_ptr(U), _DT[U.dtype], T, M, N, _ptr(Wm), _ptr(bias), _ptr(Z), _stream())
+    _check(st, "bsp_linear_transposed_dense")
     return Z
 
 

@@ -9,7 +9,7 @@ INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libbsp.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 SOURCES = ["bsp_api.hip", "bsp_norms.hip", "bsp_mask.hip", "bsp_pack.hip", "bsp_linear.hip", "bsp_linear_tiled.hip", "bsp_linear_steploop.hip", "bsp_linear_stream16.hip",
-           "bsp_plan.hip", "bsp_adam.hip", "bsp_linear_t.hip", "bsp_linear_dvals.hip"]
+           "bsp_plan.hip", "bsp_adam.hip", "bsp_linear_t.hip", "bsp_linear_t_dense.hip", "bsp_linear_dvals.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off", "-fno-fast-math",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -44,7 +44,7 @@ def build(force: bool = True) -> str:
     os.makedirs(OBJ_DIR, exist_ok=True)
     with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
         objs = list(ex.map(_compile, SOURCES))
-    subprocess.run([_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], check=True)
+    subprocess.run([_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs, "-ldl"], check=True)
     return LIB
 
 

@@ -69,6 +69,10 @@ def test_host_side_argument_checks():
     assert L.bsp_linear_transposed(one, 1, 4, 16, 70000, 16, 32, one, one, one, one, None, one, None) == SHAPE
     assert L.bsp_linear_transposed(one, 1, 0, 16, 8, 16, 32, one, one, one, one, None, one, None) == OK  # no tokens
     assert L.bsp_linear_transposed(one, 7, 4, 16, 8, 16, 32, one, one, one, one, None, one, None) == DTYPE
+    assert L.bsp_linear_transposed_dense(None, 1, 4, 16, 8, one, None, one, None) == NULL
+    assert L.bsp_linear_transposed_dense(one, 9, 4, 16, 8, one, None, one, None) == DTYPE
+    assert L.bsp_linear_transposed_dense(one, 1, 4, 0, 8, one, None, one, None) == SHAPE
+    assert L.bsp_linear_transposed_dense(one, 1, 0, 16, 8, one, None, one, None) == OK       # no tokens
     # (X, dY, xdt, T, M, N, R, k_align, blk_cnt, blk_ptr, col_idx, capacity_cols, D, gdt, ws, ws_bytes, stream)
     assert L.bsp_linear_dvals(one, one, 1, 4, 16, 8, 16, 32, None, one, one, 32, one, 1, None, 0, 0, None) == NULL
     assert L.bsp_linear_dvals(one, one, 1, 4, 24, 8, 16, 32, one, one, one, 32, one, 1, None, 0, 0, None) == SHAPE  # M % R

@@ -651,6 +651,24 @@ def test_config4_bert_large_layer_set_transposed(R):
                        T_rows=None if R == 16 else [(0, 40), (5000, 5030), (T - 12, T)])   # R = 16: every token row
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
+@pytest.mark.parametrize("R,T,M,N,p_keep", [(16, 200, 256, 1024, 0.2), (8, 70, 40, 333, 0.5), (32, 130, 96, 256, 0.33)])
+def test_linear_transposed_dense_on_the_masked_matrix(dtype, R, T, M, N, p_keep):
+    """The same product as a dense one on W after Alg. 1 (bsp_mask_weights), against the oracle's transposed product
+    on the compact storage of the same mask."""
+    d = wl.layer(R * 1000 + T + 13, T, M, N, dtype)
+    U = wl.normal(R * 81 + T, (T, M), 1.0, dtype)
+    zb = wl.normal(R * 82 + T, (N,), 0.5, dtype)
+    keep = wl.bernoulli_keep_mask(T + N + 5, M // R, N, p_keep)
+    Wm = dev(d["W"], dtype)
+    bsp.bsp_mask_weights(Wm, R, torch.from_numpy(keep).cuda())
+    p_ref = orc.pack(d["W"], R, keep, 32, CODE[dtype])
+    for bias in (zb, None):
+        Z = host(bsp.bsp_linear_transposed_dense(dev(U, dtype), Wm, dev(bias, dtype)))
+        Z_ref, _ = orc.linear_t_packed(U, p_ref, bias, zdt=CODE[dtype], n_threads=16)
+        assert_y_close(Z, Z_ref, dtype)
+
+
 # ------------------------------------------------------------------------------ the weight gradient
 def run_dvals(X, dY, W, R, keep, k_align, dtype, gdt=None):
     """bsp_linear_dvals against the oracle on the same storage: kept positions to the layer's tolerance (one rounding
