@@ -14,8 +14,9 @@
  *   group  g = (b, j): the R weights W[bR .. bR+R-1, j].
  *   Every data pointer is a DEVICE pointer owned by the caller unless marked "host".
  *   The library allocates nothing and keeps no state between calls; scratch memory is
- *   passed in by the caller (see the *_workspace_bytes queries).  The one exception is
- *   bsp_prune_mask_static, whose scratch is a device array inside the library.
+ *   passed in by the caller (see the *_workspace_bytes queries).  The two exceptions are
+ *   bsp_prune_mask_static, whose scratch is a device array inside the library, and
+ *   bsp_linear_transposed_dense, which hands a dense product to rocBLAS.
  *   Every call validates its arguments on the host, then enqueues its kernels on
  *   `stream` (a hipStream_t passed as void*; NULL = the default stream) and returns
  *   without waiting.  Return value: a bsp_status; nothing is launched unless it is BSP_OK.
