@@ -712,6 +712,22 @@ def linear_grid(T=8192, R=16, reps=3):
               ("large_qkv", 3072, 1024), ("large_out", 1024, 1024), ("large_up", 4096, 1024), ("large_down", 1024, 4096)]
     out = {}
     for si, (name, M, N) in enumerate(shapes):
+        # for comparison: the unpruned layer as a dense library product (torch.matmul on the same X and W)
+        d0 = wl.layer(900 + si, T, M, N, "bf16")
+        Xd = torch.from_numpy(d0["X"]).to(torch.bfloat16).cuda()
+        Wd = torch.from_numpy(d0["W"]).to(torch.bfloat16).cuda()
+        Yd = torch.empty((T, M), dtype=torch.bfloat16, device="cuda")
+        for _ in range(3):
+            torch.matmul(Xd, Wd.t(), out=Yd)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10 * reps):
+            torch.matmul(Xd, Wd.t(), out=Yd)
+        e1.record()
+        torch.cuda.synchronize()
+        dense_us = e0.elapsed_time(e1) * 1e3 / (10 * reps)
+        del Xd, Wd, Yd
         for num, den in ((3, 2), (2, 1), (3, 1), (5, 1)):
             d = wl.layer(900 + si, T, M, N, "bf16")
             d.update(name=name, M=M, N=N, R=R, T=T, n_keep=(M // R) * N * den // num)
@@ -736,6 +752,8 @@ def linear_grid(T=8192, R=16, reps=3):
             tf = m.useful_flops() / sec / 1e12
             roof = min(MFMA_BF16_PEAK_TFLOPS, HBM_PEAK_GBS * 1e-3 * m.useful_flops() / m.linear_bytes())
             out["%s@%.1fx" % (name, num / den)] = {"us": round(sec * 1e6, 1), "useful_tflops": round(tf, 1),
+                                                  "dense_library_us": round(dense_us, 1),
+                                                  "speedup_over_dense": round(dense_us / (sec * 1e6), 2),
                                                   "frac_mfma_peak": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
                                                   "frac_of_lower_roof": round(tf / roof, 4)}
             del m, g
