@@ -56,8 +56,9 @@ inline PlanChunks plan_chunks(int64_t N, int32_t R, int64_t M) {
     return PlanChunks{(int32_t)((npad + 1023) / 1024), 10};
 }
 // Row-blocks of 8 rows ride the kernels written for 16 when the layer's height allows it: two neighbouring row-blocks
-// form one block of 16 rows whose steps are the first's (weights in fragment rows 0-7, zeros in rows 8-15) followed
-// by the second's (rows 8-15), all accumulated into one fragment.  Every plan parameter is then the one of R = 16.
+// form one block of 16 rows that keeps the union of their columns; a step's fragment holds the first one's weights in
+// rows 0-7 and the second one's in rows 8-15, with zeros where only the other one keeps the column.  Every plan
+// parameter is then the one of R = 16.
 inline bool plan_virtual16(int32_t R, int64_t M) { return R == 8 && M % 16 == 0; }
 // Chunked plans of R = 16 give every (row-block, chunk) at least one step (of zero weights where the block keeps
 // no column of the chunk), as one-chunk plans give every row-block: the assembly loops never meet an empty run.

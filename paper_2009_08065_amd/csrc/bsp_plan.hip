@@ -37,27 +37,43 @@ __device__ __forceinline__ int slot_index(int set, int group) {
     return 32 * (set >> 2) + ((set >> 1) & 1) * 16 + (set & 1) * 4 + (group >> 2) * 8 + (group & 3);
 }
 
-// Steps of every (row-block, column chunk): ceil(kept columns of the block inside the chunk / 32).
-// One workgroup per row-block; the result goes to steps_bq[b * kPlanMaxChunks + q].
+// Steps of every (row-block of the plan, column chunk): ceil(kept columns of the block inside the chunk / 32).
+// One workgroup per block; the result goes to steps_bq[b * kPlanMaxChunks + q].  virt: the plan's block b is made
+// of the stored row-blocks 2 b and 2 b + 1 (8 rows each) and keeps the union of their columns.
 __global__ __launch_bounds__(kThreads) void plan_count_kernel(const int32_t *__restrict__ blk_cnt,
                                                               const int32_t *__restrict__ blk_ptr,
                                                               const int32_t *__restrict__ col_idx,
                                                               int64_t capacity_cols, int32_t chunk_shift,
-                                                              int32_t nchunks, int32_t *__restrict__ steps_bq) {
+                                                              int32_t nchunks, int32_t virt,
+                                                              int32_t *__restrict__ steps_bq) {
     __shared__ int cnt[kPlanMaxChunks];
+    __shared__ uint32_t seen[(kMaxKp + 31) / 32];  // columns of the first stored block (virt)
     const int64_t b = blockIdx.x;
-    const int base = blk_ptr[b];
-    const int kp = blk_ptr[b + 1] - base;
-    const int kb = blk_cnt[b];
     if (threadIdx.x < kPlanMaxChunks) cnt[threadIdx.x] = 0;
+    for (int i = threadIdx.x; i < (kMaxKp + 31) / 32; i += kThreads) seen[i] = 0u;
     __syncthreads();
-    const bool ok = kp > 0 && kp <= kMaxKp && kb >= 0 && kb <= kp && base >= 0 && (int64_t)base + kp <= capacity_cols;
-    if (ok)
-        for (int i = threadIdx.x; i < kb; i += kThreads) {
-            const int q = col_idx[base + i] >> chunk_shift;
-            if (q >= 0 && q < nchunks) atomicAdd(&cnt[q], 1);
-        }
-    __syncthreads();
+    for (int j = 0; j < (virt ? 2 : 1); ++j) {
+        const int64_t sb = virt ? 2 * b + j : b;
+        const int base = blk_ptr[sb];
+        const int kp = blk_ptr[sb + 1] - base;
+        const int kb = blk_cnt[sb];
+        const bool ok = kp > 0 && kp <= kMaxKp && kb >= 0 && kb <= kp && base >= 0 && (int64_t)base + kp <= capacity_cols;
+        if (ok)
+            for (int i = threadIdx.x; i < kb; i += kThreads) {
+                const int c = col_idx[base + i];
+                const int q = c >> chunk_shift;
+                if (c < 0 || c >= kMaxKp || q >= nchunks) continue;
+                if (!virt) {
+                    atomicAdd(&cnt[q], 1);
+                } else if (j == 0) {
+                    atomicOr(&seen[c >> 5], 1u << (c & 31));
+                    atomicAdd(&cnt[q], 1);
+                } else if (!((seen[c >> 5] >> (c & 31)) & 1u)) {
+                    atomicAdd(&cnt[q], 1);
+                }
+            }
+        __syncthreads();
+    }
     if (threadIdx.x < kPlanMaxChunks) {
         steps_bq[b * kPlanMaxChunks + threadIdx.x] = (cnt[threadIdx.x] + 31) >> 5;
     }
@@ -65,10 +81,12 @@ __global__ __launch_bounds__(kThreads) void plan_count_kernel(const int32_t *__r
 
 // What fixes the order and the sizes of a plan's streams.
 struct PlanShape {
-    const int32_t *steps_bq;  // steps per (stored row-block, chunk) of a chunked plan, else nullptr
+    const int32_t *steps_bq;  // steps per (block of the plan, chunk) where a count launch made them (chunked plans,
+                              // plans of paired 8-row blocks), else nullptr
     const int32_t *blk_cnt, *blk_ptr;
     int64_t capacity_cols;
     int32_t B, NG, nacc, nchunks, paired, min_one, virt, waves;
+    __device__ bool chunked() const { return nchunks > 1; }
     __device__ int entries() const { return nchunks * NG * nacc; }  // of a stream: (group g, chunk q, block i of the run)
 };
 
@@ -79,7 +97,7 @@ __device__ inline int plan_entry_steps(const PlanShape &P, int w, int e) {
     const int64_t b = plan_block(eg, w, e % P.nacc, P.waves, P.nacc, P.paired != 0);
     // (chunked plans that give every run a step give one to the runs past the layer's last row-block too, so
     // that all streams of a group have the same shape; their step of zero weights is written by the scan)
-    if (b >= P.B) return (P.steps_bq && P.min_one) ? 1 : 0;
+    if (b >= P.B) return (P.chunked() && P.min_one) ? 1 : 0;
     // steps of a stored row-block (zero for an empty or malformed one: the same validity test as the count
     // and fill kernels make)
     auto stored_steps = [&](int64_t sb) {
@@ -89,8 +107,8 @@ __device__ inline int plan_entry_steps(const PlanShape &P, int w, int e) {
                         (int64_t)base + kp <= P.capacity_cols;
         return ok && kb > 0 ? (kb + 31) >> 5 : 0;
     };
-    // (virt: B counts blocks of 16 rows, each made of the stored row-blocks 2 b and 2 b + 1)
-    int st = P.virt ? stored_steps(2 * b) + stored_steps(2 * b + 1) : stored_steps(b);
+    // (virt: B counts blocks of 16 rows, each the union of the stored row-blocks 2 b and 2 b + 1: always counted)
+    int st = stored_steps(b);
     // plans that give every run a step: an empty (or malformed) block gets a step of zero weights, so that
     // a wavefront's step loop never meets a block without steps
     if (P.min_one && st == 0) st = 1;
@@ -151,7 +169,7 @@ __device__ inline void plan_write_table(const PlanShape &P, int32_t nfrag, int64
         int wbase = 0;
         for (int k = 0; k < w; ++k) wbase += totals[k];
         for (int e = lane; e <= E; e += 64) mine[e] += wbase;
-        if (P.steps_bq && P.min_one) {
+        if (P.chunked() && P.min_one) {
             // (runs past the layer's end can only be in the last group: its entries close the stream)
             for (int e = max(0, E - P.nchunks * P.nacc); e < E; ++e) {  // uniform over the wavefront
                 const int eg = e / (P.nchunks * P.nacc);
@@ -175,7 +193,10 @@ __device__ inline void plan_write_table(const PlanShape &P, int32_t nfrag, int64
     }
 }
 
-// One workgroup per (row-block, column chunk): order the chunk's kept columns and write its steps.
+// One workgroup per (block of the plan, column chunk): order the chunk's kept columns and write its steps; one more
+// workgroup behind them writes the table of the streams.  virt: the block is made of two stored row-blocks of 8 rows;
+// its kept columns are the union of theirs, and a step's fragment holds the first one's weights in rows 0-7 and the
+// second one's in rows 8-15 (zeros where only the other one keeps the column).
 __global__ __launch_bounds__(kThreads) void plan_fill_kernel(int32_t R, int32_t nfrag, int32_t NG, int32_t nacc,
                                                              int32_t chunk_shift,
                                                              int32_t nchunks, const int32_t *__restrict__ blk_cnt,
@@ -188,11 +209,14 @@ __global__ __launch_bounds__(kThreads) void plan_fill_kernel(int32_t R, int32_t 
                                                              int32_t min_one, int32_t virt, int32_t B,
                                                              const int32_t *__restrict__ steps_bq,
                                                              int32_t slack_steps) {
-    // columns and canonical positions are below 4096 + 32: 16 bits each; 0xffff marks a pad.  The list of a
-    // row-block's kept columns is sized by the launch for the layer's width (cols_cap entries).
-    extern __shared__ __attribute__((aligned(16))) uint16_t cols[];
+    // columns and canonical positions are below 4096 + 32: 16 bits each; 0xffff marks "none".  The lists of the
+    // stored blocks' kept columns are sized by the launch for the layer's width (cols_cap entries each).
+    extern __shared__ __attribute__((aligned(16))) uint16_t cols[];  // [1 or 2][cols_cap]
     __shared__ uint16_t slotcol[kMaxChunk], slotsrc[kMaxChunk], ovfcol[kMaxChunk], ovfsrc[kMaxChunk];
-    __shared__ int s_filled[8], s_hp[9], s_novf, s_cnt[kPlanMaxChunks], s_other;
+    // the chunk's kept columns (virt: the union, ascending): column inside the chunk, place in either block's panel
+    __shared__ uint16_t ucol[kMaxChunk], usrc[2][kMaxChunk];
+    __shared__ uint16_t mark[2][1024];  // virt: per column of the chunk its place in either block's panel
+    __shared__ int s_filled[8], s_hp[9], s_novf, s_cnt[2][kPlanMaxChunks], s_wcnt[kThreads / 64];
     PlanShape P;
     P.steps_bq = steps_bq; P.blk_cnt = blk_cnt; P.blk_ptr = blk_ptr; P.capacity_cols = capacity_cols;
     P.B = B; P.NG = NG; P.nacc = nacc; P.nchunks = nchunks; P.paired = paired; P.min_one = min_one; P.virt = virt;
@@ -201,159 +225,192 @@ __global__ __launch_bounds__(kThreads) void plan_fill_kernel(int32_t R, int32_t 
         if (blockIdx.y == 0) plan_write_table(P, nfrag, cap_steps, slack_steps, wptr, wfrag, xoff);
         return;
     }
-    const int64_t b = blockIdx.x;  // the stored row-block
-    const int base = blk_ptr[b];
-    const int kp = blk_ptr[b + 1] - base;
-    const int kb = blk_cnt[b];
+    const int64_t pb = blockIdx.x;  // the plan's block
+    const int q = blockIdx.y;
+    const int nsrc = virt ? 2 : 1;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l16 = lane & 15, G = lane >> 4, qd = (lane >> 2) & 3, p = lane & 3;
-    // virt: the plan's block pb = b / 2 has 16 rows; this stored block of 8 fills its upper (even b) or lower fragment
-    // rows, and its steps follow (odd b) the steps of its partner inside the chunk
-    const int64_t pb = virt ? b >> 1 : b;
     // the step where this (block, chunk) starts in its stream
     int64_t my_eg;
     int my_ew, my_ei;
     plan_entry(pb, waves, nacc, paired != 0, my_eg, my_ew, my_ei);
-    const int64_t start = plan_start(P, my_ew, (int)((my_eg * nchunks + blockIdx.y) * nacc + my_ei));
-    if (threadIdx.x == 0) s_other = 0;
-    __syncthreads();
-    if (virt) {  // kept columns of the partner inside this chunk (zero for a malformed partner)
-        const int64_t ob = b ^ 1;
-        const int obase = blk_ptr[ob], okp = blk_ptr[ob + 1] - obase, okb = blk_cnt[ob];
-        if (okp > 0 && okb > 0 && okp <= cols_cap && okb <= okp && obase >= 0 && (int64_t)obase + okp <= capacity_cols) {
-            int n = 0;
-            for (int i = threadIdx.x; i < okb; i += kThreads) n += ((col_idx[obase + i] >> chunk_shift) == (int)blockIdx.y) ? 1 : 0;
-            if (n) atomicAdd(&s_other, n);
-        }
-        __syncthreads();
+    const int64_t start = plan_start(P, my_ew, (int)((my_eg * nchunks + q) * nacc + my_ei));
+    // the stored blocks (a malformed one counts as empty)
+    int base[2] = {0, 0}, kp[2] = {0, 0}, kb[2] = {0, 0};
+    bool ok[2] = {false, false};
+    for (int j = 0; j < nsrc; ++j) {
+        const int64_t sb = virt ? 2 * pb + j : pb;
+        base[j] = blk_ptr[sb];
+        kp[j] = blk_ptr[sb + 1] - base[j];
+        kb[j] = blk_cnt[sb];
+        ok[j] = kp[j] > 0 && kb[j] > 0 && kp[j] <= cols_cap && kb[j] <= kp[j] && base[j] >= 0 &&
+                (int64_t)base[j] + kp[j] <= capacity_cols;
     }
-    const int other_steps = (s_other + 31) >> 5;
-    // the single step of an empty (row-block, chunk) of a plan that gives each of them one: zero weights, LDS offset 0
-    // (virt: written by the even partner when both are empty)
+    // the single step of an empty (block, chunk) of a plan that gives each of them one: zero weights, LDS offset 0
     auto zero_step = [&]() {
         if (!min_one || wave != 0) return;
-        if (virt && ((b & 1) || other_steps > 0)) return;
-        const int64_t gs0 = start;
-        if (gs0 >= 0 && gs0 + 1 <= cap_steps) {
+        if (start >= 0 && start + 1 <= cap_steps) {
             for (int f = 0; f < nfrag; ++f)
-                *reinterpret_cast<uint4 *>(wfrag + (gs0 * nfrag + f) * 256 + lane * 4) = make_uint4(0u, 0u, 0u, 0u);
-            if (lane < 16) xoff[gs0 * 16 + lane] = 0u;
+                *reinterpret_cast<uint4 *>(wfrag + (start * nfrag + f) * 256 + lane * 4) = make_uint4(0u, 0u, 0u, 0u);
+            if (lane < 16) xoff[start * 16 + lane] = 0u;
         }
     };
-    if (kp <= 0 || kb <= 0 || kp > cols_cap || kb > kp || base < 0 || (int64_t)base + kp > capacity_cols) {
+    if (!ok[0] && !ok[1]) {
         zero_step();
         return;
     }
-    // the block's kept columns, fetched once with coalesced loads, and their count per chunk
-    if (threadIdx.x < kPlanMaxChunks) s_cnt[threadIdx.x] = 0;
+    // the blocks' kept columns, fetched once with coalesced loads, and their counts per chunk
+    if (threadIdx.x < 2 * kPlanMaxChunks) s_cnt[threadIdx.x / kPlanMaxChunks][threadIdx.x % kPlanMaxChunks] = 0;
     __syncthreads();
-    for (int i = threadIdx.x; i < kb; i += kThreads) {
-        const int c = col_idx[base + i];
-        cols[i] = (uint16_t)c;
-        const int q = c >> chunk_shift;
-        if (q >= 0 && q < nchunks) atomicAdd(&s_cnt[q], 1);
+    for (int j = 0; j < nsrc; ++j) {
+        if (!ok[j]) continue;
+        for (int i = threadIdx.x; i < kb[j]; i += kThreads) {
+            const int c = col_idx[base[j] + i];
+            cols[j * cols_cap + i] = (uint16_t)c;
+            const int cq = c >> chunk_shift;
+            if (cq >= 0 && cq < nchunks) atomicAdd(&s_cnt[j][cq], 1);
+        }
     }
     __syncthreads();
-
-    {
-        const int q = blockIdx.y;
-        int lo = 0;  // canonical position of the chunk's first kept column (columns ascend, so chunks are runs)
-        for (int k = 0; k < q; ++k) lo += s_cnt[k];
-        const int cq = s_cnt[q];
-        if (cq <= 0 || cq > 1024) {  // uniform; (more than 1024: malformed storage, duplicate columns)
-            zero_step();
-            return;
+    const int col0 = q << chunk_shift;
+    int lo[2] = {0, 0}, cqj[2] = {0, 0};  // canonical position of the chunk's first kept column (columns ascend, so
+                                          // chunks are runs), and the run's length
+    for (int j = 0; j < nsrc; ++j) {
+        for (int k = 0; k < q; ++k) lo[j] += s_cnt[j][k];
+        cqj[j] = ok[j] ? s_cnt[j][q] : 0;
+        if (cqj[j] > 1024) cqj[j] = 0;  // (more than 1024: malformed storage, duplicate columns)
+    }
+    int cq = 0;  // kept columns of the plan's block inside the chunk
+    if (!virt) {
+        cq = cqj[0];
+        for (int i = threadIdx.x; i < cq; i += kThreads) {
+            ucol[i] = (uint16_t)((int)cols[lo[0] + i] - col0);
+            usrc[0][i] = (uint16_t)(lo[0] + i);
         }
-        const int nsteps = (cq + 31) >> 5;
-        const int S = nsteps * 4;  // sets of 8 columns
-        const int col0 = q << chunk_shift;
-        if (wave == 0) {
-            int cnt[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-            int novf = 0;
-            const uint64_t lt = (1ull << lane) - 1ull;
-            for (int i0 = 0; i0 < cq; i0 += 64) {
-                const int i = i0 + lane;
-                const bool valid = i < cq;
-                const int col = valid ? (int)cols[lo + i] - col0 : 0;  // column inside the chunk
-                const int g = (int)lds_bank_group((uint32_t)col);
-                int rank = 0;
-#pragma unroll
-                for (int gg = 0; gg < 8; ++gg) {
-                    const uint64_t m = __ballot(valid && g == gg);
-                    if (g == gg) rank = cnt[gg] + __popcll(m & lt);
-                    cnt[gg] += __popcll(m);
-                }
-                const bool over = valid && rank >= S;
-                const uint64_t mo = __ballot(over);
-                if (valid && !over) {
-                    const int slot = slot_index(rank, g);
-                    slotcol[slot] = (uint16_t)col;
-                    slotsrc[slot] = (uint16_t)(lo + i);
-                } else if (over) {
-                    const int oi = novf + __popcll(mo & lt);
-                    ovfcol[oi] = (uint16_t)col;
-                    ovfsrc[oi] = (uint16_t)(lo + i);
-                }
-                novf += __popcll(mo);
-            }
-            if (lane == 0) {
-                int run = 0;
-                for (int g = 0; g < 8; ++g) {
-                    const int f = cnt[g] < S ? cnt[g] : S;
-                    s_filled[g] = f;
-                    s_hp[g] = run;
-                    run += S - f;
-                }
-                s_hp[8] = run;
-                s_novf = novf;
-            }
-        }
+    } else {
+        for (int i = threadIdx.x; i < 2 * 1024; i += kThreads) mark[i >> 10][i & 1023] = 0xffffu;
         __syncthreads();
-        // gaps: group g lacks a column in sets filled[g] .. S-1; gap e takes overflow column e, else a zero pad
-        const int H = s_hp[8], novf = s_novf;
-        for (int e = threadIdx.x; e < H; e += kThreads) {
-            int g = 0;
-#pragma unroll
-            for (int gg = 1; gg < 8; ++gg)
-                if (s_hp[gg] <= e) g = gg;
-            const int set = s_filled[g] + (e - s_hp[g]);
-            const int slot = slot_index(set, g);
-            if (e < novf) {
-                slotcol[slot] = ovfcol[e];
-                slotsrc[slot] = ovfsrc[e];
-            } else {
-                slotcol[slot] = (uint16_t)(g << 2);  // any column of bank group g; its weight is zero
-                slotsrc[slot] = 0xffffu;
+        for (int j = 0; j < 2; ++j)
+            for (int i = threadIdx.x; i < cqj[j]; i += kThreads) {
+                const int c = (int)cols[j * cols_cap + lo[j] + i] - col0;
+                if (c >= 0 && c < 1024) mark[j][c] = (uint16_t)(lo[j] + i);
             }
-        }
         __syncthreads();
-        // per-lane operands of the chunk's steps
-        const int64_t gs0 = start + ((virt && (b & 1)) ? other_steps : 0);
-        if (gs0 < 0 || gs0 + nsteps > cap_steps) return;
-        const int row0 = (virt && (b & 1)) ? 8 : 0;  // fragment row of the stored block's first row
-        for (int s = wave; s < nsteps; s += kThreads / 64) {
-            const int s1 = 32 * s + 8 * G + qd;
-            // (chunks of 512 columns alternate between the two halves of the tile)
-            const uint32_t half = chunk_shift == 9 ? (uint32_t)(q & 1) * 512u : 0u;
-            const uint32_t o1 = lds_col_offset4(half + (uint32_t)slotcol[s1], (uint32_t)p);
-            const uint32_t o2 = lds_col_offset4(half + (uint32_t)slotcol[s1 + 4], (uint32_t)p);
-            // offsets are multiples of 8 bytes; the 4 lanes of a column (token quads p = 0 .. 3) differ by
-            // p in both halves (the swizzle is an exclusive-or on those bits), so p = 0 stands for all four
-            if (p == 0) xoff[(gs0 + s) * 16 + (lane >> 2)] = (o1 >> 3) | ((o2 >> 3) << 16);
-            for (int f = 0; f < nfrag; ++f) {
-                const int r = f * 16 + l16 - row0;
-                uint32_t w[4] = {0u, 0u, 0u, 0u};
-                if (r >= 0 && r < R) {
-                    const uint16_t *row = vals + (int64_t)R * base + (int64_t)r * kp;
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) {
-                        const uint32_t src = slotsrc[32 * s + 8 * G + i];
-                        const uint32_t v = src != 0xffffu ? (uint32_t)row[src] : 0u;
-                        w[i >> 1] |= v << (16 * (i & 1));
-                    }
-                }
-                *reinterpret_cast<uint4 *>(wfrag + ((gs0 + s) * nfrag + f) * 256 + lane * 4) = make_uint4(w[0], w[1], w[2], w[3]);
+        const uint64_t lt = (1ull << lane) - 1ull;
+        for (int c0 = 0; c0 < 1024; c0 += kThreads) {  // the union in ascending order
+            const int c = c0 + threadIdx.x;
+            const uint16_t ma = mark[0][c], mb = mark[1][c];
+            const bool present = ma != 0xffffu || mb != 0xffffu;
+            const uint64_t m = __ballot(present);
+            if (lane == 0) s_wcnt[wave] = __popcll(m);
+            __syncthreads();
+            int at = cq;
+            for (int w = 0; w < wave; ++w) at += s_wcnt[w];
+            if (present) {
+                at += __popcll(m & lt);
+                ucol[at] = (uint16_t)c;
+                usrc[0][at] = ma;
+                usrc[1][at] = mb;
             }
+            for (int w = 0; w < kThreads / 64; ++w) cq += s_wcnt[w];
+            __syncthreads();
+        }
+    }
+    __syncthreads();
+    if (cq <= 0) {  // uniform
+        zero_step();
+        return;
+    }
+    const int nsteps = (cq + 31) >> 5;
+    const int S = nsteps * 4;  // sets of 8 columns
+    if (wave == 0) {
+        int cnt[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        int novf = 0;
+        const uint64_t lt = (1ull << lane) - 1ull;
+        for (int i0 = 0; i0 < cq; i0 += 64) {
+            const int i = i0 + lane;
+            const bool valid = i < cq;
+            const int col = valid ? (int)ucol[i] : 0;  // column inside the chunk
+            const int g = (int)lds_bank_group((uint32_t)col);
+            int rank = 0;
+#pragma unroll
+            for (int gg = 0; gg < 8; ++gg) {
+                const uint64_t m = __ballot(valid && g == gg);
+                if (g == gg) rank = cnt[gg] + __popcll(m & lt);
+                cnt[gg] += __popcll(m);
+            }
+            const bool over = valid && rank >= S;
+            const uint64_t mo = __ballot(over);
+            if (valid && !over) {
+                const int slot = slot_index(rank, g);
+                slotcol[slot] = (uint16_t)col;
+                slotsrc[slot] = (uint16_t)i;
+            } else if (over) {
+                const int oi = novf + __popcll(mo & lt);
+                ovfcol[oi] = (uint16_t)col;
+                ovfsrc[oi] = (uint16_t)i;
+            }
+            novf += __popcll(mo);
+        }
+        if (lane == 0) {
+            int run = 0;
+            for (int g = 0; g < 8; ++g) {
+                const int f = cnt[g] < S ? cnt[g] : S;
+                s_filled[g] = f;
+                s_hp[g] = run;
+                run += S - f;
+            }
+            s_hp[8] = run;
+            s_novf = novf;
+        }
+    }
+    __syncthreads();
+    // gaps: group g lacks a column in sets filled[g] .. S-1; gap e takes overflow column e, else a zero pad
+    const int H = s_hp[8], novf = s_novf;
+    for (int e = threadIdx.x; e < H; e += kThreads) {
+        int g = 0;
+#pragma unroll
+        for (int gg = 1; gg < 8; ++gg)
+            if (s_hp[gg] <= e) g = gg;
+        const int set = s_filled[g] + (e - s_hp[g]);
+        const int slot = slot_index(set, g);
+        if (e < novf) {
+            slotcol[slot] = ovfcol[e];
+            slotsrc[slot] = ovfsrc[e];
+        } else {
+            slotcol[slot] = (uint16_t)(g << 2);  // any column of bank group g; its weight is zero
+            slotsrc[slot] = 0xffffu;
+        }
+    }
+    __syncthreads();
+    // per-lane operands of the chunk's steps
+    const int64_t gs0 = start;
+    if (gs0 < 0 || gs0 + nsteps > cap_steps) return;
+    for (int s = wave; s < nsteps; s += kThreads / 64) {
+        const int s1 = 32 * s + 8 * G + qd;
+        // (chunks of 512 columns alternate between the two halves of the tile)
+        const uint32_t half = chunk_shift == 9 ? (uint32_t)(q & 1) * 512u : 0u;
+        const uint32_t o1 = lds_col_offset4(half + (uint32_t)slotcol[s1], (uint32_t)p);
+        const uint32_t o2 = lds_col_offset4(half + (uint32_t)slotcol[s1 + 4], (uint32_t)p);
+        // offsets are multiples of 8 bytes; the 4 lanes of a column (token quads p = 0 .. 3) differ by
+        // p in both halves (the swizzle is an exclusive-or on those bits), so p = 0 stands for all four
+        if (p == 0) xoff[(gs0 + s) * 16 + (lane >> 2)] = (o1 >> 3) | ((o2 >> 3) << 16);
+        for (int f = 0; f < nfrag; ++f) {
+            // the fragment row's stored block and its row there
+            const int fr = f * 16 + l16;
+            const int j = virt ? fr >> 3 : 0, r = virt ? fr & 7 : fr;
+            uint32_t w[4] = {0u, 0u, 0u, 0u};
+            if (r < R && j < nsrc && ok[j]) {
+                const uint16_t *row = vals + (int64_t)R * base[j] + (int64_t)r * kp[j];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const uint32_t u = slotsrc[32 * s + 8 * G + i];
+                    const uint32_t src = u != 0xffffu ? (uint32_t)usrc[j][u] : 0xffffu;
+                    const uint32_t v = src != 0xffffu ? (uint32_t)row[src] : 0u;
+                    w[i >> 1] |= v << (16 * (i & 1));
+                }
+            }
+            *reinterpret_cast<uint4 *>(wfrag + ((gs0 + s) * nfrag + f) * 256 + lane * 4) = make_uint4(w[0], w[1], w[2], w[3]);
         }
     }
 }
@@ -415,7 +472,6 @@ extern "C" int bsp_linear_plan(int vdt, int64_t M, int64_t N, int32_t R, int32_t
     if (plan_bytes < L.total() || !aligned(plan, 16)) return BSP_ERR_CAPACITY;
     const bool virt = plan_virtual16(R, M);
     const int32_t Re = virt ? 16 : R;   // block height of the plan
-    const int64_t Bs = M / R;           // stored row-blocks
     const int64_t B = M / Re;           // the plan's row-blocks
     const int nf = nfrag_of(Re);
     int32_t *wptr = (int32_t *)plan;
@@ -426,19 +482,21 @@ extern "C" int bsp_linear_plan(int vdt, int64_t M, int64_t N, int32_t R, int32_t
     const int32_t min_one = plan_min_one_step(Re, ch.n > 1) ? 1 : 0;
     const int32_t paired = plan_paired(Re, ch.n > 1) ? 1 : 0;
     int32_t *steps_bq = (int32_t *)((uint8_t *)plan + L.wptr_bytes + L.wfrag_bytes + L.xoff_bytes);
-    if (ch.n > 1)  // a layer of one chunk needs no count: its steps per row-block follow from blk_cnt
-        plan_count_kernel<<<(unsigned)Bs, kThreads, 0, s>>>(blk_cnt, blk_ptr, col_idx, capacity_cols, ch.shift, ch.n,
-                                                            steps_bq);
+    // a layer of one chunk needs no count (its steps per row-block follow from blk_cnt) unless its blocks are unions
+    const bool counted = ch.n > 1 || virt;
+    if (counted)
+        plan_count_kernel<<<(unsigned)B, kThreads, 0, s>>>(blk_cnt, blk_ptr, col_idx, capacity_cols, ch.shift, ch.n,
+                                                           virt ? 1 : 0, steps_bq);
     const int32_t nacc = plan_nacc(nf, ch.n > 1, Re);
     const int waves = plan_waves(N, Re, M);
-    // One launch fills the plan: a workgroup per (stored row-block, chunk), each finding its place in its stream by
+    // One launch fills the plan: a workgroup per (block of the plan, chunk), each finding its place in its stream by
     // adding up the step counts before it, and one more that writes the table of the streams.
     // a row-block keeps at most N columns, padded to the alignment (at most 64)
     const int32_t cols_cap = (int32_t)(N + 64 < kMaxKp ? (N + 64 + 7) / 8 * 8 : kMaxKp);
-    plan_fill_kernel<<<dim3((unsigned)Bs + 1, (unsigned)ch.n), kThreads, (size_t)cols_cap * 2, s>>>(
+    plan_fill_kernel<<<dim3((unsigned)B + 1, (unsigned)ch.n), kThreads, (size_t)cols_cap * 2 * (virt ? 2 : 1), s>>>(
         R, nf, (int32_t)L.NG, nacc, ch.shift, ch.n, blk_cnt, blk_ptr, col_idx, (const uint16_t *)vals, capacity_cols,
         (int64_t)L.steps, wptr, wfrag, xoff, cols_cap, waves, paired, min_one, virt ? 1 : 0, (int32_t)B,
-        ch.n > 1 ? steps_bq : nullptr, plan_slack_steps());
+        counted ? steps_bq : nullptr, plan_slack_steps());
     return check_launch();
 }
 
