@@ -282,6 +282,53 @@ constexpr int kSlWaves = SL_WAVES;
 constexpr int kSlNacc = 2;     // consecutive row-blocks of a wavefront per group (paired plans: see plan_block)
 constexpr int kSlBatch = 8;    // row-blocks per call of the loop (their step counts fill a 64-bit scalar)
 
+// The copy-in of a whole tile (64 token rows inside X) of a layer whose rows are whole 16-byte pieces: wavefront w
+// takes the token quad 4 w .. 4 w + 3 and its lanes the row's 8-column pieces, 64 of them (1 KiB of a row) per round.
+// A lane loads its piece of the four rows with four 16-byte loads, turns the 8 x 4 values into eight 8-byte
+// [column][4 tokens] pieces with 16 byte-permutes, and writes them at one address plus constant offsets: the 8 columns
+// share their 32-column group (so the rotation of their token quads), columns 0 - 3 lie 8 LDS rows apart and columns
+// 4 - 7 one row behind them.  No bounds tests, no divisions: 70 vector instructions per lane for the tile against
+// 390 of the general copy-in.  (The stores of one instruction meet 4 of the 8 bank groups: 2 lanes per bank.)
+__device__ __forceinline__ void stage_x_tile64_rows16(const uint16_t *__restrict__ X, int64_t N, int32_t npad,
+                                                      int64_t t0) {
+    const int lane = threadIdx.x & 63;
+    const int tq = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int octs = (int)(N >> 3), octs_pad = npad >> 3;
+    const uint8_t *r0 = reinterpret_cast<const uint8_t *>(X + (t0 + 4 * tq) * N);
+    const int64_t rb = N * 2;
+    uint8_t *sub = smem_x + (uint32_t)(tq >> 2) * kSubStride4;
+    const uint32_t pq = (uint32_t)(tq & 3);
+    uint4 a[2][4];
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        const int o = lane + 64 * k;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            a[k][i] = o < octs ? *reinterpret_cast<const uint4 *>(r0 + i * rb + (int64_t)o * 16) : make_uint4(0u, 0u, 0u, 0u);
+    }
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        const int o = lane + 64 * k;
+        if (o >= octs_pad) continue;
+        uint8_t *dst = sub + lds_col_offset4((uint32_t)o * 8u, pq);
+        const uint32_t w[4][4] = {{a[k][0].x, a[k][1].x, a[k][2].x, a[k][3].x},
+                                  {a[k][0].y, a[k][1].y, a[k][2].y, a[k][3].y},
+                                  {a[k][0].z, a[k][1].z, a[k][2].z, a[k][3].z},
+                                  {a[k][0].w, a[k][1].w, a[k][2].w, a[k][3].w}};
+#pragma unroll
+        for (int j2 = 0; j2 < 4; ++j2) {  // the column pair 2 j2, 2 j2 + 1 of the piece
+            uint2 lo, hi;
+            lo.x = __builtin_amdgcn_perm(w[j2][1], w[j2][0], 0x05040100u);
+            lo.y = __builtin_amdgcn_perm(w[j2][3], w[j2][2], 0x05040100u);
+            hi.x = __builtin_amdgcn_perm(w[j2][1], w[j2][0], 0x07060302u);
+            hi.y = __builtin_amdgcn_perm(w[j2][3], w[j2][2], 0x07060302u);
+            const uint32_t at = (uint32_t)(j2 >> 1) * 32u + (uint32_t)(j2 & 1) * (16u * 32u);
+            *reinterpret_cast<uint2 *>(dst + at) = lo;
+            *reinterpret_cast<uint2 *>(dst + at + 8u * 32u) = hi;
+        }
+    }
+}
+
 template <int DT, int ACT>
 __global__ __launch_bounds__(kSlWaves * 64) void linear_steploop16_kernel(
     const uint16_t *__restrict__ X, int64_t T, int64_t M, int64_t N, int32_t npad, const int32_t *__restrict__ wptr,
@@ -296,7 +343,8 @@ __global__ __launch_bounds__(kSlWaves * 64) void linear_steploop16_kernel(
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
 
     // the X tile, and behind it the bias of the strip's rows as fp32 (zeros without a bias and past row M)
-    stage_x_tile<4>(X, T, N, npad, t0);
+    if (t0 + 64 <= T && (N & 7) == 0 && npad <= 1024) stage_x_tile64_rows16(X, N, npad, t0);  // (uniform)
+    else stage_x_tile<4>(X, T, N, npad, t0);
     float *btab = reinterpret_cast<float *>(smem_x + kXTileBytes);
     // (for the rows of the quads the strip's groups fall into: 64 row-blocks per two groups)
     const int64_t strip_row0 = (int64_t)(g0 >> 1) * (4 * kSlWaves * 16);
