@@ -86,8 +86,8 @@ class Matrix:
         else:
             bsp.bsp_group_norms_grad(self.W, self.R, lam, eps=eps, mode=bsp.ALPHA_SQNORM, sumsq=self.sumsq,
                                      alpha=self.alpha, grad=self.grad, want=())
-        bsp.bsp_prune_mask(self.sumsq, n_keep=self.n_keep, scope=bsp.SCOPE_MATRIX, keep=self.keep, ws=self.ws)
-        bsp.bsp_pack_count(self.keep, self.k_align, blk_cnt=self.blk_cnt, blk_ptr=self.blk_ptr)
+        bsp.bsp_prune_mask_count(self.sumsq, n_keep=self.n_keep, scope=bsp.SCOPE_MATRIX, k_align=self.k_align,
+                                 keep=self.keep, ws=self.ws, blk_cnt=self.blk_cnt, blk_ptr=self.blk_ptr)
         L = bsp.lib()
         st = L.bsp_pack(self.W.data_ptr(), bsp.BF16, self.M, self.N, self.R, self.keep.data_ptr(), self.k_align,
                         self.blk_cnt.data_ptr(), self.blk_ptr.data_ptr(), self.capacity, self.col_idx.data_ptr(),

@@ -188,6 +188,18 @@ int bsp_pack(const void *W, int wdt, int64_t M, int64_t N, int32_t R, const uint
              int32_t k_align, const int32_t *blk_cnt, const int32_t *blk_ptr, int64_t capacity_cols,
              int32_t *col_idx, void *vals, int vdt, void *stream);
 
+/* The prune decision (Alg. 1, Sec. 3.1 percentile) and the sizes of its compact storage
+ * (Sec. 3.1) in one call: keep, t_used as bsp_prune_mask writes them for the same
+ * (sumsq, t, n_keep, scope), blk_cnt and blk_ptr as bsp_pack_count writes them for that keep
+ * and k_align -- the same integers.  For the matrix-scope percentile the launch that writes
+ * the mask also counts each row's kept groups and its last workgroup adds the counts up: two
+ * launches fewer than the two calls, which is what matters on the small arrays of one weight
+ * matrix.  The other forms run the two stages one after the other.  Arguments, workspace and
+ * errors as in the two calls; all buffers are the caller's (device memory). */
+int bsp_prune_mask_count(const float *sumsq, int64_t B, int64_t N, float t, int64_t n_keep, int scope,
+                         uint8_t *keep, float *t_used, int32_t k_align, int32_t *blk_cnt,
+                         int32_t *blk_ptr, void *ws, size_t ws_bytes, void *stream);
+
 /* Debug check of a compact storage: blk_ptr starts at 0 and grows by kp_b, indices in
  * [0, N), strictly ascending over the first k_b slots, pads as specified.  Synchronises
  * the stream.  Returns BSP_OK or BSP_ERR_FORMAT.  flag: device int32 scratch (1 element). */

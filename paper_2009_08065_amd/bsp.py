@@ -56,6 +56,7 @@ def lib():
     L.bsp_penalty_grad_workspace_bytes.restype = sz
     L.bsp_prune_mask.argtypes = [vp, i64, i64, f32, i64, C.c_int, vp, vp, vp, sz, vp]
     L.bsp_prune_mask_static.argtypes = [vp, i64, i64, f32, i64, C.c_int, vp, vp, vp]
+    L.bsp_prune_mask_count.argtypes = [vp, i64, i64, f32, i64, C.c_int, vp, vp, i32, vp, vp, vp, sz, vp]
     L.bsp_prune_mask_workspace_bytes.argtypes = [i64, i64, C.c_int]
     L.bsp_prune_mask_workspace_bytes.restype = sz
     L.bsp_mask_weights.argtypes = [vp, C.c_int, i64, i64, i32, vp, vp]
@@ -90,7 +91,7 @@ def lib():
     for name in ("bsp_group_norms", "bsp_penalty_grad", "bsp_prune_mask", "bsp_pack_count", "bsp_pack",
                  "bsp_packed_validate", "bsp_linear", "bsp_linear_transposed", "bsp_linear_transposed_dense", "bsp_linear_dvals", "bsp_linear_plan", "bsp_linear_planned", "bsp_linear_planned_fused",
                  "bsp_mask_weights",
-                 "bsp_group_norms_grad", "bsp_adam_step"):
+                 "bsp_group_norms_grad", "bsp_adam_step", "bsp_prune_mask_count"):
         getattr(L, name).restype = C.c_int
     _LIB = L
     return L
@@ -276,6 +277,30 @@ def bsp_pack_count(keep, k_align=32, blk_cnt=None, blk_ptr=None):
                               _ptr(blk_ptr, torch.int32), _stream())
     _check(st, "bsp_pack_count")
     return blk_cnt, blk_ptr
+
+
+def bsp_prune_mask_count(sumsq, t=0.0, n_keep=-1, scope=SCOPE_BLOCK, k_align=32, keep=None, t_used=None, ws=None,
+                         blk_cnt=None, blk_ptr=None):
+    """bsp_prune_mask and bsp_pack_count in one call.  Returns (keep, t_used, blk_cnt, blk_ptr)."""
+    B, N = sumsq.shape
+    dev = sumsq.device
+    if keep is None:
+        keep = torch.empty((B, N), dtype=torch.uint8, device=dev)
+    if blk_cnt is None:
+        blk_cnt = torch.empty(B, dtype=torch.int32, device=dev)
+    if blk_ptr is None:
+        blk_ptr = torch.empty(B + 1, dtype=torch.int32, device=dev)
+    ws_bytes = 0
+    if n_keep >= 0:
+        need = lib().bsp_prune_mask_workspace_bytes(B, N, scope)
+        if ws is None and need:
+            ws = torch.empty(need, dtype=torch.uint8, device=dev)
+        ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    st = lib().bsp_prune_mask_count(_ptr(sumsq, torch.float32), B, N, t, n_keep, scope, _ptr(keep, torch.uint8),
+                                    _ptr(t_used, torch.float32), k_align, _ptr(blk_cnt, torch.int32),
+                                    _ptr(blk_ptr, torch.int32), _ptr(ws), ws_bytes, _stream())
+    _check(st, "bsp_prune_mask_count")
+    return keep, t_used, blk_cnt, blk_ptr
 
 
 @dataclass

@@ -141,6 +141,7 @@ constexpr int kCoarse = 64;     // coarse sums per digit
 constexpr int kSlot = kBins + kCoarse;
 constexpr int kMaxSlots = 256;  // workgroups of a histogram launch
 constexpr int kStateWords = 16; // state[k] = {key bits fixed after k digits, rank wanted inside them}, k = 1..3
+constexpr int kDoneWord = 8;    // state word that counts the workgroups of mask_rank_apply_count_kernel that are done
 
 __device__ __forceinline__ int pass_shift(int pass) { return pass == 0 ? 21 : (pass == 1 ? 10 : 0); }
 __device__ __forceinline__ int pass_bits(int pass) { return pass == 2 ? 10 : 11; }
@@ -227,6 +228,9 @@ __global__ __launch_bounds__(kSelThreads) void mask_rank_hist_kernel(const float
             ws[2 * PASS] = prefix;
             ws[2 * PASS + 1] = want;
         }
+    } else {
+        // the counter of the launch that writes the mask together with the storage's sizes starts at zero
+        if (blockIdx.x == 0 && threadIdx.x == 0) ws[kDoneWord] = 0u;
     }
     for (int i = threadIdx.x; i < kBins * COPIES; i += kSelThreads) hist[i] = 0;
     __syncthreads();
@@ -321,6 +325,89 @@ __global__ __launch_bounds__(kSelThreads) void mask_rank_apply_kernel(const floa
             for (int e = 0; e < 16 && i + e < n; ++e) keep[i + e] = s[i + e] > thr;
         }
     }
+}
+
+// The mask of the percentile together with the sizes of its compact storage: keep = (sumsq > threshold), blk_cnt[b] =
+// kept groups of row b, blk_ptr = exclusive sums of the counts rounded up to k_align.  A wavefront takes whole rows
+// (it has a row's flags in registers when it writes them, so the count is a population count away); the workgroup
+// that finishes last -- elected by a counter that the first histogram launch of the same call has cleared -- adds
+// up the counts.  Nothing waits on another workgroup.  Integer results: the same as the separate launches'.
+__global__ __launch_bounds__(kSelThreads) void mask_rank_apply_count_kernel(const float *__restrict__ s, int64_t B,
+                                                                            int64_t N, uint32_t P, int G,
+                                                                            uint32_t *__restrict__ ws,
+                                                                            uint8_t *__restrict__ keep,
+                                                                            float *__restrict__ t_used,
+                                                                            int32_t k_align,
+                                                                            int32_t *__restrict__ blk_cnt,
+                                                                            int32_t *__restrict__ blk_ptr) {
+    __shared__ int sh_last, wsum[kSelThreads / kWave];
+    uint32_t prefix, want;
+    resolve_digit(ws, 2, G, P, prefix, want);
+    const float thr = from_key(prefix);
+    if (t_used && blockIdx.x == 0 && threadIdx.x == 0) *t_used = thr;
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    constexpr int kRows = kSelThreads / kWave;  // rows a workgroup works on at a time
+    const bool vec = ((reinterpret_cast<uintptr_t>(s) & 15) | (reinterpret_cast<uintptr_t>(keep) & 3) | (uintptr_t)(N & 3)) == 0;
+    for (int64_t b = (int64_t)blockIdx.x * kRows + wave; b < B; b += (int64_t)gridDim.x * kRows) {
+        const float *row = s + b * N;
+        uint8_t *krow = keep + b * N;
+        int cnt = 0;
+        if (vec) {
+            for (int64_t j = (int64_t)lane * 4; j < N; j += kWave * 4) {
+                const float4 q = *reinterpret_cast<const float4 *>(row + j);
+                const uint32_t w = (uint32_t)(q.x > thr) | ((uint32_t)(q.y > thr) << 8) | ((uint32_t)(q.z > thr) << 16) |
+                                   ((uint32_t)(q.w > thr) << 24);
+                *reinterpret_cast<uint32_t *>(krow + j) = w;
+                cnt += __popc(w);
+            }
+        } else {
+            for (int64_t j = lane; j < N; j += kWave) {
+                const bool k = row[j] > thr;
+                krow[j] = k;
+                cnt += k;
+            }
+        }
+#pragma unroll
+        for (int o = kWave / 2; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o, kWave);
+        if (lane == 0) blk_cnt[b] = cnt;
+    }
+    // The counts of this workgroup are visible on the device before it reports that it is done.  One thread fences for
+    // the workgroup, after the barrier that orders its wavefronts' stores before it (a device-wide fence writes the
+    // L2 of the workgroup's XCD back and costs microseconds while a layer kernel fills that L2: one per workgroup, not
+    // one per thread), and one thread of the elected workgroup fences before the barrier behind which all read.
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        __threadfence();
+        const uint32_t done = atomicAdd(&ws[kDoneWord], 1u);
+        sh_last = done == gridDim.x - 1;
+        if (sh_last) __threadfence();
+    }
+    __syncthreads();
+    if (!sh_last) return;  // (uniform)
+    // the last workgroup: every thread owns a run of consecutive row-blocks
+    const int64_t per = (B + kSelThreads - 1) / kSelThreads;
+    const int64_t lo = (int64_t)threadIdx.x * per, hi = lo + per < B ? lo + per : B;
+    auto padded = [&](int64_t b) {
+        const int c = __atomic_load_n(&blk_cnt[b], __ATOMIC_RELAXED);  // (written by other workgroups of this launch)
+        return (c + k_align - 1) / k_align * k_align;
+    };
+    int mine = 0;
+    for (int64_t b = lo; b < hi; ++b) mine += padded(b);
+    int incl = mine;
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+        const int up = __shfl_up(incl, o, kWave);
+        if (lane >= o) incl += up;
+    }
+    if (lane == kWave - 1) wsum[wave] = incl;
+    __syncthreads();
+    int run = incl - mine;
+    for (int w = 0; w < wave; ++w) run += wsum[w];
+    for (int64_t b = lo; b < hi; ++b) {
+        blk_ptr[b] = run;
+        run += padded(b);
+    }
+    if (threadIdx.x == kSelThreads - 1) blk_ptr[B] = run;  // the last thread's run ends at B (or is empty)
 }
 
 // ------------------------------------------------------------------ masked weights
@@ -521,6 +608,42 @@ extern "C" int bsp_prune_mask_static(const float *sumsq, int64_t B, int64_t N, f
     // the previous call's contents has to be cleared
     return prune_mask_launch(sumsq, B, N, t, n_keep, scope, keep, t_used, ws, kStaticScratchWords * sizeof(uint32_t),
                              stream);
+}
+
+extern "C" int bsp_prune_mask_count(const float *sumsq, int64_t B, int64_t N, float t, int64_t n_keep, int scope,
+                                    uint8_t *keep, float *t_used, int32_t k_align, int32_t *blk_cnt, int32_t *blk_ptr,
+                                    void *ws, size_t ws_bytes, void *stream) {
+    if (!sumsq || !keep || !blk_cnt || !blk_ptr) return BSP_ERR_NULL;
+    if (B <= 0 || N <= 0 || B * N >= ((int64_t)1 << 31) || (B * (N + 63)) >= ((int64_t)1 << 31)) return BSP_ERR_SHAPE;
+    if (k_align != 1 && k_align != 8 && k_align != 16 && k_align != 32 && k_align != 64) return BSP_ERR_SHAPE;
+    const int64_t n = B * N;
+    const int64_t P = n_keep >= 0 ? (n - n_keep > 0 ? n - n_keep : 0) : 0;
+    if (n_keep < 0 || scope != BSP_SCOPE_MATRIX || P == 0) {
+        // the forms whose mask comes from one launch (a given threshold, the row-block scope, nothing to prune):
+        // the two stages one after the other
+        const int st = prune_mask_launch(sumsq, B, N, t, n_keep, scope, keep, t_used, ws, ws_bytes, stream);
+        if (st != BSP_OK) return st;
+        return bsp_pack_count(keep, B, N, k_align, blk_cnt, blk_ptr, stream);
+    }
+    if (!ws) return BSP_ERR_NULL;
+    if (ws_bytes < bsp_prune_mask_workspace_bytes(B, N, scope) || !aligned(ws, 4)) return BSP_ERR_CAPACITY;
+    hipStream_t s = (hipStream_t)stream;
+    uint32_t *w = (uint32_t *)ws;
+    const int G = select_slots(n);
+    int64_t per_wg = (n + G - 1) / G;
+    per_wg = (per_wg + 3) / 4 * 4;
+    if (n > ((int64_t)1 << 21))
+        mask_rank_hist_kernel<0, 4><<<G, kSelThreads, 0, s>>>(sumsq, n, per_wg, (uint32_t)P, w);
+    else
+        mask_rank_hist_kernel<0, 2><<<G, kSelThreads, 0, s>>>(sumsq, n, per_wg, (uint32_t)P, w);
+    mask_rank_hist_kernel<1><<<G, kSelThreads, 0, s>>>(sumsq, n, per_wg, (uint32_t)P, w);
+    mask_rank_hist_kernel<2><<<G, kSelThreads, 0, s>>>(sumsq, n, per_wg, (uint32_t)P, w);
+    constexpr int kRows = kSelThreads / kWave;
+    int64_t ga = (B + kRows - 1) / kRows;
+    ga = ga > 256 ? 256 : ga;  // a workgroup per compute unit at most: each starts by resolving the last digit
+    mask_rank_apply_count_kernel<<<(unsigned)ga, kSelThreads, 0, s>>>(sumsq, B, N, (uint32_t)P, G, w, keep, t_used,
+                                                                     k_align, blk_cnt, blk_ptr);
+    return check_launch();
 }
 
 extern "C" int bsp_mask_weights(void *W, int wdt, int64_t M, int64_t N, int32_t R, const uint8_t *keep, void *stream) {

@@ -52,6 +52,10 @@ def test_host_side_argument_checks():
     assert L.bsp_prune_mask(one, 2, 8, 0.0, 3, 1, one, None, one, 4, None) == CAP
     assert L.bsp_prune_mask(one, 2, 8, 0.0, 3, 9, one, None, one, 1 << 20, None) == DTYPE
     assert L.bsp_prune_mask_static(one, 1 << 20, 1 << 20, 0.0, 5, 1, one, None, None) == SHAPE   # beyond its scratch
+    assert L.bsp_prune_mask_count(one, 2, 8, 0.0, 3, 1, one, None, 32, None, one, one, 1 << 20, None) == NULL
+    assert L.bsp_prune_mask_count(one, 2, 8, 0.0, 3, 1, one, None, 5, one, one, one, 1 << 20, None) == SHAPE
+    assert L.bsp_prune_mask_count(one, 2, 8, 0.0, 3, 1, one, None, 32, one, one, one, 4, None) == CAP
+    assert L.bsp_prune_mask_count(one, 2, 8, 0.0, 3, 1, one, None, 32, one, one, None, 0, None) == NULL
     assert L.bsp_prune_mask_static(one, 0, 8, 0.0, -1, 0, one, None, None) == SHAPE
     assert L.bsp_pack_count(one, 2, 8, 3, one, one, None) == SHAPE                           # k_align
     assert L.bsp_pack_count(None, 2, 8, 16, one, one, None) == NULL

@@ -219,6 +219,35 @@ def test_mask_rank_bit_exact(scope, B, N):
         assert bits_equal(host(t_used), t_ref), n_keep
 
 
+@pytest.mark.parametrize("scope", [orc.SCOPE_BLOCK, orc.SCOPE_MATRIX])
+@pytest.mark.parametrize("B,N,k_align", [(48, 768, 32), (7, 1000, 8), (3, 65, 1), (1, 1, 32), (64, 4096, 32),
+                                         (256, 1024, 32), (1500, 258, 16), (33, 2047, 64)])
+def test_mask_and_storage_sizes_in_one_call(scope, B, N, k_align):
+    # the mask of bsp_prune_mask and the counts of bsp_pack_count from one call: the oracle's mask, its counts
+    W = wl.normal(B * 3 + N, (B * 4, N), 0.02)
+    s = orc.sumsq(W, 4)
+    if N > 8:
+        s[0, 1] = s[0, 2] = s[0, 3]
+    n = N if scope == orc.SCOPE_BLOCK else B * N
+    sd = dev(s)
+    ws = torch.empty(max(bsp.lib().bsp_prune_mask_workspace_bytes(B, N, scope), 16), dtype=torch.uint8, device="cuda")
+    for n_keep in sorted({0, n // 5, n // 2, n - 1, n}):
+        ws.random_(0, 256)                              # nothing in the workspace has to be cleared by the caller
+        t_used = torch.empty(B if scope == orc.SCOPE_BLOCK else 1, dtype=torch.float32, device="cuda")
+        keep, t_used, cnt, ptr = bsp.bsp_prune_mask_count(sd, n_keep=n_keep, scope=scope, k_align=k_align,
+                                                          t_used=t_used, ws=ws)
+        k_ref, t_ref = orc.mask_rank(s, n_keep, scope)
+        cnt_ref, ptr_ref = orc.pack_count(k_ref, k_align)
+        assert np.array_equal(host(keep), k_ref), n_keep
+        assert bits_equal(host(t_used), t_ref), n_keep
+        assert np.array_equal(host(cnt), cnt_ref) and np.array_equal(host(ptr), ptr_ref), n_keep
+    # the threshold form
+    keep, _, cnt, ptr = bsp.bsp_prune_mask_count(sd, t=0.04, k_align=k_align)
+    k_ref = orc.mask_threshold(s, 0.04)
+    cnt_ref, ptr_ref = orc.pack_count(k_ref, k_align)
+    assert np.array_equal(host(keep), k_ref) and np.array_equal(host(cnt), cnt_ref) and np.array_equal(host(ptr), ptr_ref)
+
+
 def test_mask_rank_wide_range_and_negative_values():
     rng = np.random.default_rng(11)
     s = (rng.standard_normal((16, 500)) * np.exp(rng.uniform(-30, 30, (16, 500)))).astype(np.float32)
