@@ -411,6 +411,32 @@ def test_linear_planned_output_paths(dtype, R, T, M, N):
     run_layer(d["X"], d["W"], None, R, keep, 32, dtype, T_rows=rows)
 
 
+@pytest.mark.parametrize("T,M,N", [(130, 96, 512), (70, 160, 1024), (100, 64, 2048), (65, 208, 3000), (64, 32, 777)])
+def test_linear_planned_pairs_of_8_row_blocks(T, M, N):
+    # 8-row blocks in a layer of even block count: a block of the plan is the union of two stored blocks' columns.
+    # Pairs with the same columns, with disjoint columns, with one or both blocks empty, a full block beside a
+    # sparse one; one chunk and several
+    R, B = 8, M // 8
+    d = wl.layer(T + M + N, T, M, N, "bf16")
+    keep = wl.bernoulli_keep_mask(T + M + N + 1, B, N, 0.22)
+    keep[1, :] = keep[0, :]                              # the same columns
+    keep[2, :] = 0
+    keep[2, ::5] = 1
+    keep[3, :] = 0
+    keep[3, 1::5] = 1                                    # disjoint
+    if B >= 8:
+        keep[4, :] = 0                                   # first of the pair empty
+        keep[6, :] = 0
+        keep[7, :] = 0                                   # both empty
+    if B >= 12:
+        keep[9, :] = 0                                   # second of the pair empty
+        keep[10, :] = 1                                  # everything kept beside a sparse block
+        keep[11, :] = 0
+        keep[11, N - 1] = 1
+    run_layer(d["X"], d["W"], d["bias"], R, keep, 32, "bf16")
+    run_layer(d["X"], d["W"], None, R, keep, 64, "bf16")
+
+
 @pytest.mark.parametrize("R", [16, 8])
 def test_linear_planned_bias_at_odd_address(R):
     # a bias that starts on a 2-byte boundary cannot be read in 4-byte words: the element-wise output path
