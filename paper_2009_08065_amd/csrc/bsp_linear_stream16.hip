@@ -186,6 +186,77 @@ __device__ __forceinline__ void chunk_commit(const ChunkRegs &r, int32_t width, 
     }
 }
 
+// The same for a whole tile (64 token rows inside X) of a layer whose rows are whole 16-byte pieces: copying
+// wavefront w takes the token quads w and w + 8 and its lanes the 64 eight-column pieces of the chunk's 512 columns
+// (1 KiB of a row per load instruction).  Four 16-byte loads per quad, 16 byte-permutes, eight 8-byte LDS stores at
+// one address plus constant offsets (the 8 columns share their 32-column group; columns 0 - 3 lie 8 LDS rows apart,
+// columns 4 - 7 one row behind them); no bounds tests, no divisions.  The copying wavefronts share their SIMDs'
+// issue slots with the multiplying ones, so what they do not execute the others can.
+struct ChunkRegs16 {
+    uint4 a[2][4];
+};
+__device__ __forceinline__ void chunk_issue(ChunkRegs16 &r, const uint16_t *__restrict__ X, int64_t T, int64_t N,
+                                            int32_t col0, int32_t width, int64_t t0, int j) {
+    const int lane = j & 63, wl = j >> 6;
+    const int64_t c = (int64_t)col0 + 8 * lane;
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        const uint16_t *row = X + (t0 + 4 * (wl + kStLoadWaves * k)) * N + c;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            r.a[k][i] = c < N ? *reinterpret_cast<const uint4 *>(row + i * N) : make_uint4(0u, 0u, 0u, 0u);
+    }
+}
+__device__ __forceinline__ void chunk_commit(const ChunkRegs16 &r, int32_t width, uint32_t half, int j) {
+    const int lane = j & 63, wl = j >> 6;
+    if (8 * lane >= width) return;
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        const uint32_t tq = (uint32_t)(wl + kStLoadWaves * k);
+        uint8_t *dst = smem_x + (tq >> 2) * kSubStride4 + lds_col_offset4(half * kStChunk + 8u * (uint32_t)lane, tq & 3u);
+        const uint32_t w[4][4] = {{r.a[k][0].x, r.a[k][1].x, r.a[k][2].x, r.a[k][3].x},
+                                  {r.a[k][0].y, r.a[k][1].y, r.a[k][2].y, r.a[k][3].y},
+                                  {r.a[k][0].z, r.a[k][1].z, r.a[k][2].z, r.a[k][3].z},
+                                  {r.a[k][0].w, r.a[k][1].w, r.a[k][2].w, r.a[k][3].w}};
+#pragma unroll
+        for (int j2 = 0; j2 < 4; ++j2) {  // the column pair 2 j2, 2 j2 + 1 of the piece
+            uint2 lo, hi;
+            lo.x = __builtin_amdgcn_perm(w[j2][1], w[j2][0], 0x05040100u);
+            lo.y = __builtin_amdgcn_perm(w[j2][3], w[j2][2], 0x05040100u);
+            hi.x = __builtin_amdgcn_perm(w[j2][1], w[j2][0], 0x07060302u);
+            hi.y = __builtin_amdgcn_perm(w[j2][3], w[j2][2], 0x07060302u);
+            const uint32_t at = (uint32_t)(j2 >> 1) * 32u + (uint32_t)(j2 & 1) * (16u * 32u);
+            *reinterpret_cast<uint2 *>(dst + at) = lo;
+            *reinterpret_cast<uint2 *>(dst + at + 8u * 32u) = hi;
+        }
+    }
+}
+
+// The copying wavefronts' loop.  Two register sets: the loads of chunks k + 1 and k + 2 travel while chunk k is
+// written and handed over (with one set a chunk's loads would be requested only after the previous chunk's had
+// arrived).
+template <typename Regs>
+__device__ __forceinline__ void copy_chunks(const uint16_t *__restrict__ X, int64_t T, int64_t N, int32_t npad,
+                                            int32_t nq, int64_t t0, int j) {
+    Regs ra, rb;
+    auto width_of = [&](int k) { return min(kStChunk, npad - k * kStChunk); };
+    chunk_issue(ra, X, T, N, 0, width_of(0), t0, j);
+    if (nq > 1) chunk_issue(rb, X, T, N, kStChunk, width_of(1), t0, j);
+    for (int k = 0; k < nq; k += 2) {
+        chunk_commit(ra, width_of(k), 0u, j);
+        __syncthreads();  // barrier k: chunk k is written; the multiplying wavefronts are done with chunk k - 1
+        if (k + 1 < nq) {
+            chunk_commit(rb, width_of(k + 1), 1u, j);
+            // the loads of the next two chunks leave together: while loads that miss the L2 are under way, the
+            // compute unit's later loads (the operand streams of the multiplying wavefronts, which hit) wait
+            // behind them, so there are as few such episodes as the registers allow
+            if (k + 2 < nq) chunk_issue(ra, X, T, N, (k + 2) * kStChunk, width_of(k + 2), t0, j);
+            if (k + 3 < nq) chunk_issue(rb, X, T, N, (k + 3) * kStChunk, width_of(k + 3), t0, j);
+            __syncthreads();  // barrier k + 1
+        }
+    }
+}
+
 template <int DT>
 __global__ __launch_bounds__(kStThreads) void linear_stream16_kernel(
     const uint16_t *__restrict__ X, int64_t T, int64_t M, int64_t N, int32_t npad, const int32_t *__restrict__ wptr,
@@ -200,25 +271,9 @@ __global__ __launch_bounds__(kStThreads) void linear_stream16_kernel(
     if (wave >= kStComputeWaves) {
         // ---- the copying wavefronts: chunk k into half k % 2, handed over by barrier k ----
         const int j = (int)threadIdx.x - kStComputeWaves * 64;
-        // two register sets: the loads of chunks k + 1 and k + 2 travel while chunk k is written and handed over
-        // (with one set a chunk's loads would be requested only after the previous chunk's had arrived)
-        ChunkRegs ra, rb;
-        auto width_of = [&](int k) { return min(kStChunk, npad - k * kStChunk); };
-        chunk_issue(ra, X, T, N, 0, width_of(0), t0, j);
-        if (nq > 1) chunk_issue(rb, X, T, N, kStChunk, width_of(1), t0, j);
-        for (int k = 0; k < nq; k += 2) {
-            chunk_commit(ra, width_of(k), 0u, j);
-            __syncthreads();  // barrier k: chunk k is written; the multiplying wavefronts are done with chunk k - 1
-            if (k + 1 < nq) {
-                chunk_commit(rb, width_of(k + 1), 1u, j);
-                // the loads of the next two chunks leave together: while loads that miss the L2 are under way, the
-                // compute unit's later loads (the operand streams of the multiplying wavefronts, which hit) wait
-                // behind them, so there are as few such episodes as the registers allow
-                if (k + 2 < nq) chunk_issue(ra, X, T, N, (k + 2) * kStChunk, width_of(k + 2), t0, j);
-                if (k + 3 < nq) chunk_issue(rb, X, T, N, (k + 3) * kStChunk, width_of(k + 3), t0, j);
-                __syncthreads();  // barrier k + 1
-            }
-        }
+        // whole tiles of layers whose rows are whole 16-byte pieces take the copy without bounds tests (uniform)
+        if (t0 + 64 <= T && (N & 7) == 0) copy_chunks<ChunkRegs16>(X, T, N, npad, nq, t0, j);
+        else copy_chunks<ChunkRegs>(X, T, N, npad, nq, t0, j);
         return;
     }
 
