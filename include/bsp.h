@@ -311,10 +311,10 @@ int bsp_linear_planned(const void *X, int xdt, int64_t T, int64_t M, int64_t N, 
  * kernel, on the fp32 sums and before the one rounding, either saves a pass over Y (one read and one write of
  * T x M values; a residual: two reads and a write).
  * Arguments as bsp_linear_planned, plus: act a bsp_activation; residual: device pointer [T, M] row-major of the
- * type of X, 8-byte aligned, or NULL.  Fused are: the activation for row-blocks of 16 rows (and of 8 rows when
- * M % 16 == 0), any planned width; the residual for the layers whose kernel writes its output once, at its end:
- * R = 16 (or 8, M % 16 == 0) and either more than 1024 input columns or more than 512 input columns and at most
- * 64 sixteen-row blocks (M <= 1024).  Any other request returns BSP_ERR_SHAPE and writes nothing: the caller runs
+ * type of X, 8-byte aligned, or NULL.  Fused are: the activation for the row-blocks that run in the kernels of
+ * 16-row blocks -- R = 16, 32, 48, 64, and R = 8 when M % 16 == 0 -- at any planned width; the residual for those
+ * of them whose kernel writes its output once, at its end: more than 1024 input columns, or more than 512 input
+ * columns and M <= 1024.  Any other request returns BSP_ERR_SHAPE and writes nothing: the caller runs
  * bsp_linear_planned and its own element-wise pass. */
 int bsp_linear_planned_fused(const void *X, int xdt, int64_t T, int64_t M, int64_t N, int32_t R, int32_t k_align,
                              const void *plan, int64_t capacity_cols, const void *bias, int act,

@@ -60,6 +60,13 @@ inline PlanChunks plan_chunks(int64_t N, int32_t R, int64_t M) {
 // rows 0-7 and the second one's in rows 8-15, with zeros where only the other one keeps the column.  Every plan
 // parameter is then the one of R = 16.
 inline bool plan_virtual16(int32_t R, int64_t M) { return R == 8 && M % 16 == 0; }
+// Row-blocks of 32, 48 or 64 rows ride them too: a block of the plan is one 16-row slab of a stored row-block (the
+// stored block's kept columns, the slab's rows of its panel), so such a layer runs as the layer of 16-row blocks with
+// the same kept columns does.  (The slabs of a block gather the same columns of X from LDS once each; a kernel that
+// shared the gather would need a step loop of its own per block height.)
+inline int plan_split16(int32_t R) { return (R > 16 && R % 16 == 0) ? R / 16 : 1; }
+// Height of the blocks a layer's plan is made of.
+inline int32_t plan_block_rows(int32_t R, int64_t M) { return (plan_virtual16(R, M) || plan_split16(R) > 1) ? 16 : R; }
 // Chunked plans of R = 16 give every (row-block, chunk) at least one step (of zero weights where the block keeps
 // no column of the chunk), as one-chunk plans give every row-block: the assembly loops never meet an empty run.
 inline bool plan_min_one_step(int32_t R, bool chunked) { return !chunked || R == 16; }

@@ -39,12 +39,13 @@ __device__ __forceinline__ int slot_index(int set, int group) {
 
 // Steps of every (row-block of the plan, column chunk): ceil(kept columns of the block inside the chunk / 32).
 // One workgroup per block; the result goes to steps_bq[b * kPlanMaxChunks + q].  virt: the plan's block b is made
-// of the stored row-blocks 2 b and 2 b + 1 (8 rows each) and keeps the union of their columns.
+// of the stored row-blocks 2 b and 2 b + 1 (8 rows each) and keeps the union of their columns; split > 1: the
+// plan's block b is a 16-row slab of the stored row-block b / split.
 __global__ __launch_bounds__(kThreads) void plan_count_kernel(const int32_t *__restrict__ blk_cnt,
                                                               const int32_t *__restrict__ blk_ptr,
                                                               const int32_t *__restrict__ col_idx,
                                                               int64_t capacity_cols, int32_t chunk_shift,
-                                                              int32_t nchunks, int32_t virt,
+                                                              int32_t nchunks, int32_t virt, int32_t split,
                                                               int32_t *__restrict__ steps_bq) {
     __shared__ int cnt[kPlanMaxChunks];
     __shared__ uint32_t seen[(kMaxKp + 31) / 32];  // columns of the first stored block (virt)
@@ -53,7 +54,7 @@ __global__ __launch_bounds__(kThreads) void plan_count_kernel(const int32_t *__r
     for (int i = threadIdx.x; i < (kMaxKp + 31) / 32; i += kThreads) seen[i] = 0u;
     __syncthreads();
     for (int j = 0; j < (virt ? 2 : 1); ++j) {
-        const int64_t sb = virt ? 2 * b + j : b;
+        const int64_t sb = virt ? 2 * b + j : b / split;
         const int base = blk_ptr[sb];
         const int kp = blk_ptr[sb + 1] - base;
         const int kb = blk_cnt[sb];
@@ -85,7 +86,7 @@ struct PlanShape {
                               // plans of paired 8-row blocks), else nullptr
     const int32_t *blk_cnt, *blk_ptr;
     int64_t capacity_cols;
-    int32_t B, NG, nacc, nchunks, paired, min_one, virt, waves;
+    int32_t B, NG, nacc, nchunks, paired, min_one, virt, split, waves;
     __device__ bool chunked() const { return nchunks > 1; }
     __device__ int entries() const { return nchunks * NG * nacc; }  // of a stream: (group g, chunk q, block i of the run)
 };
@@ -107,8 +108,9 @@ __device__ inline int plan_entry_steps(const PlanShape &P, int w, int e) {
                         (int64_t)base + kp <= P.capacity_cols;
         return ok && kb > 0 ? (kb + 31) >> 5 : 0;
     };
-    // (virt: B counts blocks of 16 rows, each the union of the stored row-blocks 2 b and 2 b + 1: always counted)
-    int st = stored_steps(b);
+    // (virt: B counts blocks of 16 rows, each the union of the stored row-blocks 2 b and 2 b + 1: always counted;
+    // split: the slabs of a stored row-block have its steps)
+    int st = stored_steps(P.steps_bq ? b : b / P.split);
     // plans that give every run a step: an empty (or malformed) block gets a step of zero weights, so that
     // a wavefront's step loop never meets a block without steps
     if (P.min_one && st == 0) st = 1;
@@ -196,7 +198,8 @@ __device__ inline void plan_write_table(const PlanShape &P, int32_t nfrag, int64
 // One workgroup per (block of the plan, column chunk): order the chunk's kept columns and write its steps; one more
 // workgroup behind them writes the table of the streams.  virt: the block is made of two stored row-blocks of 8 rows;
 // its kept columns are the union of theirs, and a step's fragment holds the first one's weights in rows 0-7 and the
-// second one's in rows 8-15 (zeros where only the other one keeps the column).
+// second one's in rows 8-15 (zeros where only the other one keeps the column).  split > 1: the block is a 16-row slab
+// of the stored row-block pb / split: that block's columns, the slab's rows of its panel.
 __global__ __launch_bounds__(kThreads) void plan_fill_kernel(int32_t R, int32_t nfrag, int32_t NG, int32_t nacc,
                                                              int32_t chunk_shift,
                                                              int32_t nchunks, const int32_t *__restrict__ blk_cnt,
@@ -206,7 +209,7 @@ __global__ __launch_bounds__(kThreads) void plan_fill_kernel(int32_t R, int32_t 
                                                              int64_t cap_steps, int32_t *__restrict__ wptr,
                                                              uint32_t *__restrict__ wfrag, uint32_t *__restrict__ xoff,
                                                              int32_t cols_cap, int32_t waves, int32_t paired,
-                                                             int32_t min_one, int32_t virt, int32_t B,
+                                                             int32_t min_one, int32_t virt, int32_t split, int32_t B,
                                                              const int32_t *__restrict__ steps_bq,
                                                              int32_t slack_steps) {
     // columns and canonical positions are below 4096 + 32: 16 bits each; 0xffff marks "none".  The lists of the
@@ -220,6 +223,7 @@ __global__ __launch_bounds__(kThreads) void plan_fill_kernel(int32_t R, int32_t 
     PlanShape P;
     P.steps_bq = steps_bq; P.blk_cnt = blk_cnt; P.blk_ptr = blk_ptr; P.capacity_cols = capacity_cols;
     P.B = B; P.NG = NG; P.nacc = nacc; P.nchunks = nchunks; P.paired = paired; P.min_one = min_one; P.virt = virt;
+    P.split = split;
     P.waves = waves;
     if (blockIdx.x == gridDim.x - 1) {  // the workgroup behind the row-blocks writes the table of the streams
         if (blockIdx.y == 0) plan_write_table(P, nfrag, cap_steps, slack_steps, wptr, wfrag, xoff);
@@ -239,7 +243,7 @@ __global__ __launch_bounds__(kThreads) void plan_fill_kernel(int32_t R, int32_t 
     int base[2] = {0, 0}, kp[2] = {0, 0}, kb[2] = {0, 0};
     bool ok[2] = {false, false};
     for (int j = 0; j < nsrc; ++j) {
-        const int64_t sb = virt ? 2 * pb + j : pb;
+        const int64_t sb = virt ? 2 * pb + j : pb / split;
         base[j] = blk_ptr[sb];
         kp[j] = blk_ptr[sb + 1] - base[j];
         kb[j] = blk_cnt[sb];
@@ -398,7 +402,8 @@ __global__ __launch_bounds__(kThreads) void plan_fill_kernel(int32_t R, int32_t 
         for (int f = 0; f < nfrag; ++f) {
             // the fragment row's stored block and its row there
             const int fr = f * 16 + l16;
-            const int j = virt ? fr >> 3 : 0, r = virt ? fr & 7 : fr;
+            // (split: the plan's block is the slab pb % split of its stored block)
+            const int j = virt ? fr >> 3 : 0, r = virt ? fr & 7 : 16 * (int)(pb % split) + fr;
             uint32_t w[4] = {0u, 0u, 0u, 0u};
             if (r < R && j < nsrc && ok[j]) {
                 const uint16_t *row = vals + (int64_t)R * base[j] + (int64_t)r * kp[j];
@@ -428,21 +433,26 @@ struct PlanLayout {
 // depend on N; NG is the number of groups for the grouping the layer's width selects.
 inline PlanLayout plan_layout(int64_t M, int64_t N, int32_t R, int64_t capacity_cols) {
     PlanLayout L;
-    const int64_t B = M / R;  // stored row-blocks (the sizes below follow them)
-    const int32_t Re = plan_virtual16(R, M) ? 16 : R;  // block height the plan is laid out for
+    const int64_t B = M / R;  // stored row-blocks
+    const int32_t Re = plan_block_rows(R, M);  // block height the plan is laid out for
+    const int64_t Bp = M / Re;                 // blocks of the plan
+    const int64_t Bm = B > Bp ? B : Bp;
+    const int split = plan_split16(R);
     const bool chunked = plan_chunks(N, Re, M).n > 1;
-    L.NG = plan_groups(M / Re, plan_waves(N, Re, M), plan_nacc(nfrag_of(Re), chunked, Re), plan_paired(Re, chunked));
+    L.NG = plan_groups(Bp, plan_waves(N, Re, M), plan_nacc(nfrag_of(Re), chunked, Re), plan_paired(Re, chunked));
+    // every (stored row-block, chunk) pads its columns to a multiple of 32 on its own and has a step even when it is
+    // empty; the slabs of a split row-block repeat its steps
     // (+ a step per run of a last group that reaches past the layer, for the plans that give every run one)
-    L.steps = (size_t)((capacity_cols + 31) / 32) + (size_t)B * (kPlanMaxChunks - 1) +
+    L.steps = (size_t)split * ((size_t)((capacity_cols + 31) / 32) + (size_t)B * kPlanMaxChunks) +
               (size_t)kPlanWaves * 4 * kPlanMaxChunks + (size_t)plan_slack_steps();
     // entries per stream <= chunks * (blocks rounded up to whole groups) / streams, groups of at most 32 blocks
     // (16 streams of a one-chunk layer need less than the 8 streams of a chunked one)
-    L.wptr_bytes = ((size_t)kPlanWavesWide * (size_t)(kPlanMaxChunks * ((B + 31) / 32 * 4) + 1) * sizeof(int32_t) + 255) /
+    L.wptr_bytes = ((size_t)kPlanWavesWide * (size_t)(kPlanMaxChunks * ((Bm + 31) / 32 * 4) + 1) * sizeof(int32_t) + 255) /
                    256 * 256;
-    L.wfrag_bytes = L.steps * (size_t)nfrag_of(R) * 1024;
+    L.wfrag_bytes = L.steps * (size_t)nfrag_of(Re) * 1024;
     L.xoff_bytes = L.steps * 64;
-    // step counts per (row-block, chunk) of a chunked plan: read by the workgroups that fill the plan
-    L.cnt_bytes = ((size_t)B * kPlanMaxChunks * sizeof(int32_t) + 255) / 256 * 256;
+    // step counts per (block of the plan, chunk) where a launch counts them: read by the workgroups that fill the plan
+    L.cnt_bytes = ((size_t)Bm * kPlanMaxChunks * sizeof(int32_t) + 255) / 256 * 256;
     return L;
 }
 
@@ -471,7 +481,8 @@ extern "C" int bsp_linear_plan(int vdt, int64_t M, int64_t N, int32_t R, int32_t
     const PlanLayout L = plan_layout(M, N, R, capacity_cols);
     if (plan_bytes < L.total() || !aligned(plan, 16)) return BSP_ERR_CAPACITY;
     const bool virt = plan_virtual16(R, M);
-    const int32_t Re = virt ? 16 : R;   // block height of the plan
+    const int split = plan_split16(R);
+    const int32_t Re = plan_block_rows(R, M);  // block height of the plan
     const int64_t B = M / Re;           // the plan's row-blocks
     const int nf = nfrag_of(Re);
     int32_t *wptr = (int32_t *)plan;
@@ -486,7 +497,7 @@ extern "C" int bsp_linear_plan(int vdt, int64_t M, int64_t N, int32_t R, int32_t
     const bool counted = ch.n > 1 || virt;
     if (counted)
         plan_count_kernel<<<(unsigned)B, kThreads, 0, s>>>(blk_cnt, blk_ptr, col_idx, capacity_cols, ch.shift, ch.n,
-                                                           virt ? 1 : 0, steps_bq);
+                                                           virt ? 1 : 0, split, steps_bq);
     const int32_t nacc = plan_nacc(nf, ch.n > 1, Re);
     const int waves = plan_waves(N, Re, M);
     // One launch fills the plan: a workgroup per (block of the plan, chunk), each finding its place in its stream by
@@ -495,7 +506,7 @@ extern "C" int bsp_linear_plan(int vdt, int64_t M, int64_t N, int32_t R, int32_t
     const int32_t cols_cap = (int32_t)(N + 64 < kMaxKp ? (N + 64 + 7) / 8 * 8 : kMaxKp);
     plan_fill_kernel<<<dim3((unsigned)B + 1, (unsigned)ch.n), kThreads, (size_t)cols_cap * 2 * (virt ? 2 : 1), s>>>(
         R, nf, (int32_t)L.NG, nacc, ch.shift, ch.n, blk_cnt, blk_ptr, col_idx, (const uint16_t *)vals, capacity_cols,
-        (int64_t)L.steps, wptr, wfrag, xoff, cols_cap, waves, paired, min_one, virt ? 1 : 0, (int32_t)B,
+        (int64_t)L.steps, wptr, wfrag, xoff, cols_cap, waves, paired, min_one, virt ? 1 : 0, split, (int32_t)B,
         counted ? steps_bq : nullptr, plan_slack_steps());
     return check_launch();
 }
@@ -521,8 +532,8 @@ extern "C" int bsp_linear_planned_fused(const void *X, int xdt, int64_t T, int64
     TiledArgs a{};
     a.xdt = xdt;
     a.X = (const uint16_t *)X;
-    // (row-blocks of 8 rows in a layer of even block count: the plan is the one of blocks of 16 rows)
-    const int32_t Re = plan_virtual16(R, M) ? 16 : R;
+    // (pairs of 8-row blocks, slabs of 32-, 48- and 64-row blocks: the plan is the one of blocks of 16 rows)
+    const int32_t Re = plan_block_rows(R, M);
     a.T = T; a.M = M; a.N = N; a.B = M / Re; a.R = Re;
     a.wptr = (const int32_t *)plan;
     a.wfrag = (const uint8_t *)plan + L.wptr_bytes;

@@ -437,6 +437,22 @@ def test_linear_planned_pairs_of_8_row_blocks(T, M, N):
     run_layer(d["X"], d["W"], None, R, keep, 64, "bf16")
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("R,T,M,N", [(32, 130, 96, 512), (32, 4100, 2144, 1024), (64, 70, 320, 2048), (48, 65, 240, 3000),
+                                     (64, 100, 64, 777), (32, 64, 1056, 4096)])
+def test_linear_planned_slabs_of_tall_row_blocks(dtype, R, T, M, N):
+    # 32-, 48- and 64-row blocks: a block of the plan is a 16-row slab of a stored block.  An empty block, a full
+    # block, an odd number of stored blocks, one chunk and several, ragged token tiles
+    d = wl.layer(R + T + M + N, T, M, N, dtype)
+    keep = wl.bernoulli_keep_mask(R + T + M + N + 1, M // R, N, 0.22)
+    keep[0, :] = 0
+    if M // R > 2:
+        keep[2, :] = 1
+    rows = None if T < 1000 else [(0, 70), (2040, 2060), (4090, 4100)]
+    run_layer(d["X"], d["W"], d["bias"], R, keep, 32, dtype, T_rows=rows)
+    run_layer(d["X"], d["W"], None, R, keep, 64, dtype, T_rows=rows)
+
+
 @pytest.mark.parametrize("R", [16, 8])
 def test_linear_planned_bias_at_odd_address(R):
     # a bias that starts on a 2-byte boundary cannot be read in 4-byte words: the element-wise output path
@@ -516,6 +532,9 @@ FUSED_CASES = [
     ("bf16", 16, 150, 256, 2048, False, True), ("bf16", 16, 333, 1024, 1024, False, True),
     ("f16", 16, 100, 96, 4096, True, True), ("bf16", 8, 65, 336, 3000, True, True),
     ("bf16", 16, 64, 1024, 768, True, False),
+    # row-blocks of 32, 48 and 64 rows run as their 16-row slabs
+    ("bf16", 32, 130, 1280, 512, True, False), ("f16", 64, 70, 320, 2048, True, True),
+    ("bf16", 48, 65, 480, 1024, False, True), ("bf16", 32, 100, 2144, 3000, True, True),
 ]
 
 
@@ -541,7 +560,7 @@ def test_linear_fused_epilogue(dtype, R, T, M, N, act, with_res):
 def test_linear_fused_epilogue_refuses_what_is_not_fused():
     """Row-blocks of other heights, and a residual for a layer whose kernel stores block by block: an error and
     nothing written."""
-    for (R, M, N, act, with_res) in [(32, 256, 512, bsp.ACT_GELU, False), (16, 2048, 1024, bsp.ACT_NONE, True),
+    for (R, M, N, act, with_res) in [(24, 240, 512, bsp.ACT_GELU, False), (16, 2048, 1024, bsp.ACT_NONE, True),
                                      (16, 256, 512, 7, False)]:
         d = wl.layer(7300 + R, 64, M, N, "bf16")
         keep = wl.bernoulli_keep_mask(7301, M // R, N, 0.3)
