@@ -74,3 +74,38 @@ def test_graph_replays_match_eager():
             torch.cuda.synchronize()
             assert torch.equal(Y, y_ref) and torch.equal(keep, k_ref) and torch.equal(grad, g_ref)
             assert torch.equal(Z, z_ref) and torch.equal(Yf, yf_ref) and torch.equal(D[:d_ref.numel()], d_ref)
+
+
+def test_graph_replays_of_the_mask_with_its_storage_sizes():
+    """bsp_prune_mask_count elects its last workgroup through a counter that the call's first launch clears: replays of
+    a captured call (the workspace trashed in between) give the mask and the sizes of the separate calls."""
+    B, N, k_align = 192, 1024, 32
+    dev = "cuda"
+    ws = torch.empty(bsp.lib().bsp_prune_mask_workspace_bytes(B, N, bsp.SCOPE_MATRIX), dtype=torch.uint8, device=dev)
+    sumsq = torch.empty((B, N), dtype=torch.float32, device=dev)
+    keep = torch.empty((B, N), dtype=torch.uint8, device=dev)
+    cnt = torch.empty(B, dtype=torch.int32, device=dev)
+    ptr = torch.empty(B + 1, dtype=torch.int32, device=dev)
+    n_keep = B * N // 5
+    inputs = [torch.from_numpy(wl.normal(500 + i, (B, N), 1.0) ** 2).float().cuda() for i in range(3)]
+    want = []
+    for s in inputs:
+        k, _ = bsp.bsp_prune_mask(s, n_keep=n_keep, scope=bsp.SCOPE_MATRIX)
+        c, p = bsp.bsp_pack_count(k, k_align)
+        want.append((k.clone(), c.clone(), p.clone()))
+    sumsq.copy_(inputs[0])
+    bsp.bsp_prune_mask_count(sumsq, n_keep=n_keep, scope=bsp.SCOPE_MATRIX, k_align=k_align, keep=keep, ws=ws,
+                             blk_cnt=cnt, blk_ptr=ptr)               # warm-up before capture
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        bsp.bsp_prune_mask_count(sumsq, n_keep=n_keep, scope=bsp.SCOPE_MATRIX, k_align=k_align, keep=keep, ws=ws,
+                                 blk_cnt=cnt, blk_ptr=ptr)
+    for rep in range(3):
+        for s, (k_ref, c_ref, p_ref) in zip(inputs, want):
+            sumsq.copy_(s)
+            keep.zero_(); cnt.zero_(); ptr.zero_(); ws.random_(0, 256)   # eager work between replays
+            g.replay()
+            g.replay()                                                   # twice in a row on one stream
+            torch.cuda.synchronize()
+            assert torch.equal(keep, k_ref) and torch.equal(cnt, c_ref) and torch.equal(ptr, p_ref)
