@@ -215,6 +215,25 @@ def time_set_back_to_back(mats, steps, warmup):
     return e0.elapsed_time(e1) / steps
 
 
+def compact_storage_layers(mats, steps):
+    """The same layers through bsp_linear, on the compact storage itself (no derived buffer): microseconds per launch,
+    in turn, each between two events."""
+    evs = [[[torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)] for _ in mats]
+           for _ in range(steps)]
+    for m in mats:
+        bsp.bsp_linear(m.X, m.packed, m.bias, Y=m.Y)
+    torch.cuda.synchronize()
+    for s_i in range(steps):
+        for i, m in enumerate(mats):
+            evs[s_i][i][0].record()
+            bsp.bsp_linear(m.X, m.packed, m.bias, Y=m.Y)
+            evs[s_i][i][1].record()
+    torch.cuda.synchronize()
+    ms = np.array([[e[0].elapsed_time(e[1]) for e in ev] for ev in evs]).mean(axis=0)
+    return {"entry_point": "bsp_linear", "ms": round(float(ms.sum()), 4),
+            "us": {m.name: round(float(v) * 1e3, 2) for m, v in zip(mats, ms)}}
+
+
 def per_matrix_report(mats, lin_avg_ms):
     out = {}
     for m, ms in zip(mats, lin_avg_ms):
@@ -884,7 +903,9 @@ def main():
     def kernel_of(m):
         if not m.use_plan:
             return "bsp_linear (compact storage)"
-        if m.R in (8, 16) and m.M % 16 == 0:   # the kernels of 16-row blocks: which one, the plan's chunking decides
+        # the kernels of 16-row blocks (pairs of 8-row blocks, slabs of 32-, 48- and 64-row blocks ride them): which
+        # one, the plan's chunking decides
+        if m.R in (16, 32, 48, 64) or (m.R == 8 and m.M % 16 == 0):
             streams_x = m.N > 1024 or (m.N > 512 and m.M // 16 <= 64)
             return "linear_stream16_kernel" if streams_x else "linear_steploop16_kernel"
         return "linear_tiled_planned_kernel" if m.N <= 1024 else "linear_tiled_chunked_kernel"
@@ -913,8 +934,8 @@ def main():
                                          "before the timed region)",
                               "serial": "one HIP graph per step, matrices in turn",
                               "eager": "every kernel launched from Python"}[args.launch],
-                   "step": "group_norms_grad (norms, factors and regulariser gradient in one pass) + prune_mask + "
-                           "pack_count + pack + linear_plan + linear, 4 matrices"},
+                   "step": "group_norms_grad (norms, factors and regulariser gradient in one pass) + prune_mask_count "
+                           "(mask and storage sizes) + pack + linear_plan + linear, 4 matrices"},
         "linear_only": {"cache_state": "cold: the four layers run in turn, so about 250 MB of other X / Y traffic "
                                        "(the size of the Infinity Cache) passes between two launches of one layer",
                         "ms": round(lin_total_ms, 4),
@@ -922,7 +943,8 @@ def main():
                         "useful_tflops": round(achieved_tflops, 2),
                         "dense_equiv_tflops": round(dense / (lin_total_ms * 1e-3) / 1e12, 2),
                         "frac_mfma_peak": round(achieved_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
-                        "per_matrix": per_matrix},
+                        "per_matrix": per_matrix,
+                        "on_the_compact_storage": compact_storage_layers(mats, max(3, args.steps // 10))},
         "roofline": {"kernel": dom_name, "launches_per_step": dom["launches"],
                      "avg_launch_us": round(dom["ms"] * 1e3 / len(dom["launches"]), 2), "bound": "hbm",
                      "achieved": round(achieved_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
