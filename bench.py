@@ -160,25 +160,38 @@ def streams_on_different_queues(want=4, candidates=12):
         with torch.cuda.stream(st):
             graphs[0].replay()
     torch.cuda.synchronize()
+    for _ in range(3):                   # and so do the clocks' first moments on a box that has just started
+        timed([(graphs[0], pool[0]), (graphs[1], pool[0])])
     alone = timed([(graphs[0], pool[0])])
-    serial = timed([(graphs[0], pool[0]), (graphs[1], pool[0])])    # one stream: one after the other by construction
-    kept, shared = [pool[0]], []
-    for i in range(1, candidates):
-        if len(kept) == want:
+
+    def on_two_queues(a, b, yard):
+        return timed([(graphs[0], a), (graphs[1], b)]) < 0.955 * yard
+
+    # The yardstick is taken before and after the choice, and every chosen pair is checked once more against the
+    # smaller of the two: a yardstick measured while the machine was still speeding up would let a pair that shares a
+    # queue pass (the step is then two chains wide, 0.21 instead of 0.16 ms).  A choice that fails the check is made anew.
+    for attempt in range(1, 4):
+        serial = timed([(graphs[0], pool[0]), (graphs[1], pool[0])])    # one stream: one after the other by construction
+        kept, shared = [pool[0]], []
+        for i in range(1, candidates):
+            if len(kept) == want:
+                break
+            if all(on_two_queues(k, pool[i], serial) for k in kept):
+                kept.append(pool[i])
+            else:
+                shared.append(i)
+        found = len(kept)
+        serial = min(serial, timed([(graphs[0], pool[0]), (graphs[1], pool[0])]))
+        if all(on_two_queues(kept[i], kept[j], serial) for i in range(found) for j in range(i + 1, found)):
             break
-        ok = all(timed([(graphs[0], k), (graphs[1], pool[i])]) < 0.955 * serial for k in kept)
-        if ok:
-            kept.append(pool[i])
-        else:
-            shared.append(i)
-    found = len(kept)
     for st in pool:                      # fewer queues than wanted: fill up in creation order
         if len(kept) == want:
             break
         if st not in kept:
             kept.append(st)
     return kept, {"streams_probed": candidates, "on_different_queues": found, "sharing_a_queue_with_an_earlier_one": shared,
-                  "probe_us_alone": round(alone * 1e6, 1), "probe_us_two_on_one_stream": round(serial * 1e6, 1)}
+                  "probe_us_alone": round(alone * 1e6, 1), "probe_us_two_on_one_stream": round(serial * 1e6, 1),
+                  "choices_made": attempt}
 
 
 def time_layers(mats, steps, warmup):
